@@ -1,0 +1,96 @@
+/*
+ * CPU oracle for the hashed-embedding-table lookup path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, single-threaded statement
+ * of what the path computes, written from the definitions, with double
+ * accumulation.  It shares no code, header, table or constant with the HIP
+ * library and must never be called from a product code path; only the test
+ * suite, the smoke check and the benchmark's CPU-baseline leg use it.
+ *
+ * What the paper fixes (Section 2.2 "Large Embedding Tables"): categorical IDs
+ * are mapped to dense vectors through *hashed lookup tables*, several ID
+ * features per request, collisions allowed; Section 3.1: the rows are
+ * fine-tuned inside the ranking model.  The paper names no hash, pooling mode
+ * or optimizer, so each function states the textbook definition it follows.
+ *
+ * All pointers are host pointers.  Multi-table inputs are table-major: bag
+ * (t, b) is entry t*B + b of `offsets`, which indexes one flat `rows` array.
+ */
+#ifndef EMB_ORACLE_H
+#define EMB_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { ORACLE_POOL_SUM = 0, ORACLE_POOL_MEAN = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+/* status bits, OR-ed into *status (may be NULL) */
+enum { ORACLE_STATUS_BAD_INDEX = 1, ORACLE_STATUS_BAD_OFFSETS = 2 };
+
+/* First output of the SplitMix64 generator (Steele, Lea, Flood 2014) whose
+ * state is x: add the golden-ratio increment, then the two multiply-xorshift
+ * rounds and the final xorshift. */
+uint64_t oracle_splitmix64(uint64_t x);
+
+/* Hashed lookup (Section 2.2): rows[i] = splitmix64(raw[i] XOR salt) mod num_rows. */
+void oracle_hash_ids(const uint64_t *raw, int64_t n, uint64_t salt, int64_t num_rows,
+                     int64_t *rows);
+
+/* CSR bag offsets: offsets[0] = 0, offsets[i+1] = offsets[i] + lengths[i].
+ * A negative length counts as 0 and sets ORACLE_STATUS_BAD_OFFSETS. */
+void oracle_lengths_to_offsets(const int32_t *lengths, int64_t n, int64_t *offsets,
+                               uint32_t *status);
+
+/* Pooled lookup (EmbeddingBag): out[t,b,:] = sum over the bag's lookups of
+ * W_t[rows[j],:]; mean divides by the bag length; an empty bag gives 0.
+ * bf16 rows are widened exactly to fp32 first.  Accumulation in double,
+ * rounded once to fp32.  absum (nullable, [T,B,D] double) receives the sum of
+ * |terms| (divided by the length for mean), the scale of the rounding-error
+ * bound.  A lookup whose row is outside [0, num_rows[t]) is skipped and sets
+ * ORACLE_STATUS_BAD_INDEX; a bag with offsets outside 0 <= s <= e <= nnz is
+ * treated as empty and sets ORACLE_STATUS_BAD_OFFSETS. */
+void oracle_bag_forward(const void *const *tables, int32_t T, const int64_t *num_rows,
+                        int32_t D, int32_t dtype, const int64_t *rows, const int64_t *offsets,
+                        int64_t B, int64_t nnz, int32_t mode, float *out, double *absum,
+                        uint32_t *status);
+
+/* Sparse backward + row-wise Adagrad, one exact step (Section 3.1: fine-tuning
+ * of table rows).  Per lookup j in bag (t,b): g_j = c_b * dout[t,b,:], c_b = 1
+ * (sum) or 1/len_b (mean).  Per distinct (t,row): G = sum of its g_j (in
+ * ascending j), then once per distinct row
+ *     S_new = S_old + (1/D) * sum_d G[d]^2
+ *     W_new[d] = W_old[d] - lr * G[d] / (sqrt(S_new) + eps)
+ * (Duchi et al. 2011 with one accumulator per row).  Untouched rows are not
+ * written.  Outputs: unique_keys[U] ascending (key = sum of num_rows of the
+ * preceding tables + row), unique_counts[U], *num_unique = U; G_out (nullable,
+ * [U, D] double) and Gabs_out (nullable, [U, D] double, sum of |g_j|).
+ * Out-of-range rows are skipped (ORACLE_STATUS_BAD_INDEX).  If any bag
+ * violates 0 <= s <= e <= nnz, or offsets[0] != 0, or offsets[T*B] != nnz,
+ * nothing is updated, U = 0 and ORACLE_STATUS_BAD_OFFSETS is set.
+ * Returns 0, or -1 if memory could not be allocated. */
+int oracle_bag_backward_rowwise_adagrad(void *const *tables, float *const *accum, int32_t T,
+                                        const int64_t *num_rows, int32_t D, int32_t dtype,
+                                        const int64_t *rows, const int64_t *offsets, int64_t B,
+                                        int64_t nnz, int32_t mode, const float *dout, float lr,
+                                        float eps, int64_t *unique_keys, int32_t *unique_counts,
+                                        int64_t *num_unique, double *G_out, double *Gabs_out,
+                                        uint32_t *status);
+
+/* Pooled lookup over a host-resident table fronted by a cache of hot rows
+ * (one-box analogue of the CPU-GPU hybrid serving of Section 3.3).  The cache
+ * is numerically invisible: out is oracle_bag_forward over the single table.
+ * hit_miss[0] = number of in-range lookups whose row is in hot_rows (sorted
+ * ascending, distinct), hit_miss[1] = in-range lookups that are not. */
+void oracle_bag_forward_cached(const void *table, int64_t num_rows, int32_t D, int32_t dtype,
+                               const int64_t *hot_rows, int64_t num_hot, const int64_t *rows,
+                               const int64_t *offsets, int64_t B, int64_t nnz, int32_t mode,
+                               float *out, double *absum, uint64_t *hit_miss, uint32_t *status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMB_ORACLE_H */

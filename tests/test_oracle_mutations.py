@@ -1,0 +1,100 @@
+"""The pins must be able to fail: plant one mistake at a time in a copy of the
+oracle's C source (on the CPU, in a temporary directory), rebuild it, and check
+that at least one pin test rejects the mutant."""
+import importlib.util
+import inspect
+import os
+import shutil
+import subprocess
+
+import pytest
+
+from tests import test_oracle_pins as pins
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ORACLE_DIR = os.path.join(os.path.dirname(HERE), "oracle")
+
+MUTATIONS = [
+    ("hash: golden-ratio increment dropped", "uint64_t z = x + UINT64_C(0x9E3779B97F4A7C15);", "uint64_t z = x;"),
+    ("hash: first shift", "(z >> 30)", "(z >> 31)"),
+    ("hash: second multiplier", "0x94D049BB133111EB", "0x94D049BB133111ED"),
+    ("hash: last shift", "return z ^ (z >> 31);", "return z ^ (z >> 30);"),
+    ("hash: salt added instead of xored", "raw[i] ^ salt", "raw[i] + salt"),
+    ("offsets: 32-bit wrap", "offsets[i + 1] = offsets[i] + len;", "offsets[i + 1] = (int32_t)(offsets[i] + len);"),
+    ("offsets: inclusive instead of exclusive", "offsets[0] = 0;\n    for", "offsets[0] = lengths[0];\n    for"),
+    ("forward: sign", "acc[d] += w;", "acc[d] -= w;"),
+    ("forward: mean not divided", "v /= (double)len;", ";"),
+    ("forward: element order reversed", "((const float *)table)[row * D + d]", "((const float *)table)[row * D + (D - 1 - d)]"),
+    ("forward: wrong bag end", "int64_t s = offsets[bag], e = offsets[bag + 1];\n            for (int32_t d = 0; d < D; ++d) acc",
+     "int64_t s = offsets[bag], e = offsets[bag + 1] - (offsets[bag + 1] > offsets[bag]);\n            for (int32_t d = 0; d < D; ++d) acc"),
+    ("forward: out-of-range row read", "if (r < 0 || r >= num_rows[t]) {\n                    if (status) *status |= ORACLE_STATUS_BAD_INDEX;\n                    continue;\n                }\n                for (int32_t d = 0; d < D; ++d) {\n                    double w",
+     "if (r < 0 || r > num_rows[t]) {\n                    if (status) *status |= ORACLE_STATUS_BAD_INDEX;\n                    continue;\n                }\n                for (int32_t d = 0; d < D; ++d) {\n                    double w"),
+    ("bf16 widen shift", "(uint32_t)b << 16", "(uint32_t)b << 15"),
+    ("bf16 rounding half-up", "u += 0x7FFFu + ((u >> 16) & 1u);", "u += 0x8000u;"),
+    ("bf16 truncation", "u += 0x7FFFu + ((u >> 16) & 1u);", ""),
+    ("backward: mean scale dropped", "if (mode == ORACLE_POOL_MEAN) g /= (double)len;", ""),
+    ("backward: accumulator uses sum not mean over D", "sq / (double)D", "sq"),
+    ("backward: eps inside the root", "sqrt(s_new) + (double)eps", "sqrt(s_new + (double)eps)"),
+    ("backward: old accumulator dropped", "(double)accum[t][r] + sq", "sq"),
+    ("backward: accumulator used before update", "double denom = sqrt(s_new)", "double denom = sqrt((double)accum[t][r])"),
+    ("backward: step sign", "w - (double)lr * G[d] / denom", "w + (double)lr * G[d] / denom"),
+    ("backward: table base missing from key", "lk[n].key = rowbase + r;", "lk[n].key = r;"),
+    ("backward: gradient column", "(double)dout[bag * D + d]", "(double)dout[bag * D]"),
+    ("backward: gradient of wrong bag", "lk[n].bag = bag;", "lk[n].bag = bag > 0 ? bag - 1 : bag;"),
+    ("backward: per-occurrence update", "for (; i < n && lk[i].key == key; ++i) {", "for (int once = 1; once && i < n; ++i, once = 0) {"),
+    ("backward: accumulator not stored", "accum[t][r] = (float)s_new;", ""),
+    ("cached: hits and misses swapped", "hit_miss[hit ? 0 : 1] += 1;", "hit_miss[hit ? 1 : 0] += 1;"),
+]
+
+
+def _pin_calls():
+    calls = []
+    for name, fn in sorted(vars(pins).items()):
+        if not name.startswith("test_") or not callable(fn):
+            continue
+        params = inspect.signature(fn).parameters
+        if "mode" in params:
+            calls += [(name, fn, {"mode": m}) for m in ("sum", "mean")]
+        else:
+            calls.append((name, fn, {}))
+    return calls
+
+
+def _load_variant(lib_path, tag):
+    spec = importlib.util.spec_from_file_location("emb_oracle_mut_" + tag,
+                                                  os.path.join(ORACLE_DIR, "emb_oracle.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    mod.build = lambda force=False: lib_path
+    return mod
+
+
+def _killed_by(mod):
+    for name, fn, kw in _pin_calls():
+        try:
+            fn(mod, **kw)
+        except AssertionError:
+            return name
+    return None
+
+
+def test_unmutated_copy_passes_every_pin(tmp_path):
+    shutil.copy(os.path.join(ORACLE_DIR, "emb_oracle.h"), tmp_path)
+    shutil.copy(os.path.join(ORACLE_DIR, "emb_oracle.c"), tmp_path)
+    lib = str(tmp_path / "lib0.so")
+    subprocess.check_call(["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-o", lib,
+                           str(tmp_path / "emb_oracle.c"), "-lm"])
+    assert _killed_by(_load_variant(lib, "clean")) is None
+
+
+@pytest.mark.parametrize("idx", range(len(MUTATIONS)), ids=[m[0] for m in MUTATIONS])
+def test_every_planted_mistake_is_caught(tmp_path, idx):
+    what, old, new = MUTATIONS[idx]
+    src = open(os.path.join(ORACLE_DIR, "emb_oracle.c")).read()
+    assert src.count(old) >= 1, "mutation site not found: " + what
+    shutil.copy(os.path.join(ORACLE_DIR, "emb_oracle.h"), tmp_path)
+    (tmp_path / "emb_oracle.c").write_text(src.replace(old, new, 1))
+    lib = str(tmp_path / ("lib%d.so" % idx))
+    subprocess.check_call(["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-w", "-o", lib,
+                           str(tmp_path / "emb_oracle.c"), "-lm"])
+    assert _killed_by(_load_variant(lib, str(idx))) is not None, "no pin catches: " + what
