@@ -1,0 +1,202 @@
+/*
+ * emb.h - C ABI of the MI355X (gfx950) library for the hot path behind large
+ * hashed embedding tables: ID hashing, bag offsets, pooled lookup
+ * (EmbeddingBag forward), exact sparse backward with row-wise Adagrad, and a
+ * pooled lookup over a host-resident table fronted by an HBM hot-row cache.
+ *
+ * Source of the problem statement: "Multi-Faceted Large Embedding Tables for
+ * Pinterest Ads Ranking", Section 2.2 (high-cardinality categorical features
+ * are mapped to dense embeddings through hashed lookup tables; collisions are
+ * legal), Section 3.1 (several ID tables of ~1e8-1e9 rows, fine-tuned inside
+ * the ranking model) and Section 3.3 (tables too large for GPU memory are
+ * hosted in CPU memory).  The paper names no hash, pooling mode or optimizer;
+ * each entry point states the definition it implements.
+ *
+ * Conventions
+ *  - "dev" pointers are device pointers (HBM, or host memory mapped into the
+ *    device address space where stated); "host" pointers are ordinary host
+ *    memory read during the call only.
+ *  - The caller owns every buffer.  The library allocates nothing, keeps no
+ *    global state, and never synchronises: a call validates its arguments on
+ *    the host, enqueues kernels on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream) and returns.  Results are valid once the
+ *    caller has synchronised the stream.
+ *  - Return value: EMB_OK or a negative emb_status.  Errors that can be seen
+ *    on the host are reported without launching anything.
+ *  - Errors that live in device data (a row index outside its table, offsets
+ *    that do not describe bags) are reported by OR-ing bits into the 32-bit
+ *    word `status_dev` (nullable; the caller zeroes it).  Memory safety never
+ *    depends on it: an out-of-range lookup is skipped, a malformed bag is
+ *    treated as empty.
+ *  - Multi-table layout ("table-major jagged"): T tables with B bags each; bag
+ *    (t, b) has number t*B + b; one flat `rows[nnz]` array holds the lookups of
+ *    bag 0, bag 1, ...; `offsets[T*B + 1]` (int64, offsets[0] = 0,
+ *    offsets[T*B] = nnz) delimits them.  Pooled outputs and their gradients
+ *    are fp32 `[T, B, D]` contiguous.  Tables are row-major `[num_rows, D]`.
+ *  - D * element_size must be a multiple of 16 bytes (rows are read with
+ *    128-bit loads) and every table base must be 16-byte aligned.
+ */
+#ifndef EMB_H
+#define EMB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    EMB_OK = 0,
+    EMB_ERR_INVALID_ARG = -1, /* null pointer, negative size, bad enum, inconsistent descriptors */
+    EMB_ERR_UNSUPPORTED = -2, /* shape outside what the kernels cover (see each call) */
+    EMB_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or too small */
+    EMB_ERR_HIP = -4          /* a HIP call (kernel launch) failed */
+} emb_status;
+
+typedef enum { EMB_POOL_SUM = 0, EMB_POOL_MEAN = 1 } emb_pool;
+typedef enum { EMB_F32 = 0, EMB_BF16 = 1 } emb_dtype;
+
+/* bits of the device status word */
+#define EMB_STATUS_BAD_INDEX 1u   /* a row index < 0 or >= num_rows of its table */
+#define EMB_STATUS_BAD_OFFSETS 2u /* a negative length, or offsets not 0 <= s <= e <= nnz */
+#define EMB_STATUS_BAD_HOT_SET 4u /* hot rows not strictly ascending / out of range */
+
+/* One embedding table.  The same array of T descriptors is passed twice to
+ * the multi-table calls: in host memory (read for validation) and in device
+ * memory (read by the kernels); the caller keeps the two copies identical. */
+typedef struct emb_table {
+    void *weights;      /* dev: [num_rows, D] fp32 or bf16, 16-byte aligned          */
+    float *accum;       /* dev: [num_rows] fp32 Adagrad accumulators; NULL if unused */
+    int64_t num_rows;   /* > 0                                                       */
+    int64_t row_base;   /* sum of num_rows of the preceding tables (emb_tables_init) */
+    uint64_t salt;      /* XOR-ed into raw IDs before hashing                        */
+    uint64_t mod_magic; /* floor((2^64 - 1) / num_rows)           (emb_tables_init) */
+} emb_table;
+
+/* Human-readable name of a status code (static string). */
+const char *emb_status_string(int status);
+
+/* Fill row_base and mod_magic of T host descriptors from their num_rows.
+ * Host-only helper; call it before copying the array to the device. */
+int emb_tables_init(emb_table *tables_host, int32_t T);
+
+/* Hashed lookup, Section 2.2: rows[i] = splitmix64(raw[i] XOR salt) mod
+ * num_rows, where splitmix64(x) is the first output of the SplitMix64
+ * generator (Steele, Lea, Flood 2014) with state x, and mod is the exact
+ * unsigned 64-bit remainder.  raw_dev: u64[n]; rows_dev: i64[n] (may not
+ * alias raw_dev).  n == 0 is legal.  Requires 0 < num_rows < 2^63. */
+int emb_hash_ids(const uint64_t *raw_dev, int64_t n, uint64_t salt, int64_t num_rows,
+                 int64_t *rows_dev, void *stream);
+
+/* The same for all T tables of a jagged batch in one launch: lookup j belongs
+ * to table t iff offsets[t*B] <= j < offsets[(t+1)*B] and is hashed with that
+ * table's salt and num_rows.  Lookups not covered by any table (malformed
+ * offsets) get row -1 and set EMB_STATUS_BAD_OFFSETS. */
+int emb_hash_ids_tables(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                        const uint64_t *raw_dev, const int64_t *offsets_dev, int64_t B,
+                        int64_t nnz, int64_t *rows_dev, uint32_t *status_dev, void *stream);
+
+/* Bag-offset (CSR) builder: offsets[0] = 0, offsets[i+1] = offsets[i] +
+ * lengths[i] in int64.  lengths_dev: i32[n]; offsets_dev: i64[n+1].  A
+ * negative length counts as 0 and sets EMB_STATUS_BAD_OFFSETS.  n == 0 writes
+ * offsets[0] only. */
+int emb_lengths_to_offsets(const int32_t *lengths_dev, int64_t n, int64_t *offsets_dev,
+                           uint32_t *status_dev, void *stream);
+
+/* Pooled lookup over T tables (Sections 2.2, 3.1):
+ *   out[t,b,:] = sum_{j in [offsets[tB+b], offsets[tB+b+1])} W_t[rows[j], :]
+ * EMB_POOL_MEAN divides by the bag length; an empty bag gives zeros.  bf16
+ * rows are widened exactly and accumulated in fp32; out is fp32 [T,B,D] and
+ * is fully overwritten.  rows_dev: i64[nnz]; offsets_dev: i64[T*B+1].
+ * EMB_ERR_UNSUPPORTED if D*element_size is not a multiple of 16 or exceeds
+ * 16384 bytes, or T > 65535.  B == 0 or T == 0 does nothing. */
+int emb_bag_forward(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                    int32_t D, int32_t dtype, const int64_t *rows_dev,
+                    const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
+                    float *out_dev, uint32_t *status_dev, void *stream);
+
+/* Bytes of device workspace emb_bag_backward_rowwise_adagrad needs for a
+ * batch of T*B bags and nnz lookups over tables with `total_rows` rows in
+ * all.  Returns 0 on invalid arguments. */
+size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t nnz, int64_t total_rows);
+
+/* Exact sparse backward of emb_bag_forward followed by one row-wise Adagrad
+ * step (fine-tuning of table rows, Section 3.1; Adagrad of Duchi, Hazan,
+ * Singer 2011 with one accumulator per row).  With g_j = c_b * dout[t,b,:]
+ * for lookup j of bag (t,b), c_b = 1 (sum) or 1/len_b (mean):
+ *   for every distinct (t, row) in the batch, once:
+ *     G      = sum of g_j over its lookups, in ascending j
+ *     S_new  = S_old + (1/D) * sum_d G[d]^2
+ *     W_new  = W_old - lr * G / (sqrt(S_new) + eps)
+ * Duplicates are summed BEFORE the nonlinear update.  weights and accum of
+ * touched rows are updated in place (fp32 arithmetic; bf16 rows are widened,
+ * updated in fp32 and rounded to nearest-even); other rows are not written.
+ * The result is deterministic (bit-identical from run to run).
+ * Optional outputs (each nullable): unique_keys_out_dev i64[>= nnz] receives
+ * the distinct keys row_base + row in ascending order, unique_counts_out_dev
+ * i32[>= nnz] their lookup counts, num_unique_out_dev i64[1] their number U.
+ * workspace_dev: 256-byte aligned, at least emb_bag_backward_workspace_bytes.
+ * Out-of-range rows are skipped (EMB_STATUS_BAD_INDEX).  If the offsets are
+ * not a partition of [0, nnz) into bags, nothing is updated, U = 0 and
+ * EMB_STATUS_BAD_OFFSETS is set.  EMB_ERR_UNSUPPORTED as for the forward, and
+ * if T*B >= 2^32 - 1, nnz >= 2^31, or accum is NULL for some table. */
+int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, const emb_table *tables_dev,
+                                     int32_t T, int32_t D, int32_t dtype,
+                                     const int64_t *rows_dev, const int64_t *offsets_dev,
+                                     int64_t B, int64_t nnz, int32_t mode, const float *dout_dev,
+                                     float lr, float eps, void *workspace_dev,
+                                     size_t workspace_bytes, int64_t *unique_keys_out_dev,
+                                     int32_t *unique_counts_out_dev, int64_t *num_unique_out_dev,
+                                     uint32_t *status_dev, void *stream);
+
+/* ---- host-resident table with an HBM hot-row cache (Section 3.3) --------- */
+
+/* Bytes of the cache index for a table of num_rows rows (16 bytes per 64
+ * rows: a presence bitmap word and the number of hot rows before it). */
+int emb_cache_index_bytes(int64_t num_rows, size_t *bytes);
+
+/* Build the static cache: copies rows hot_rows[k] of the table into
+ * cache_rows_dev[k] and builds the index.  table_dev: device-visible pointer
+ * to the table (hipHostMalloc'ed mapped memory, or HBM).  hot_rows_dev:
+ * i64[num_hot], strictly ascending, each in [0, num_rows) (violations set
+ * EMB_STATUS_BAD_HOT_SET and leave the cache unusable).  cache_rows_dev:
+ * [num_hot, D] of the table's dtype; cache_index_dev: emb_cache_index_bytes,
+ * 16-byte aligned. */
+int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                    const int64_t *hot_rows_dev, int64_t num_hot, void *cache_rows_dev,
+                    void *cache_index_dev, uint32_t *status_dev, void *stream);
+
+/* emb_bag_forward for one table whose rows are read from the HBM cache when
+ * present and from table_dev (zero-copy over PCIe when it is mapped host
+ * memory) otherwise.  The cache is numerically invisible.  The table must not
+ * have changed since emb_cache_build.  hit_miss_dev (nullable, u64[2], zeroed
+ * by the caller) is incremented by the number of in-range lookups served from
+ * the cache / from the table. */
+int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                           const void *cache_rows_dev, const void *cache_index_dev,
+                           int64_t num_hot, const int64_t *rows_dev, const int64_t *offsets_dev,
+                           int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                           uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream);
+
+/* Device-visible address of page-locked host memory that is mapped into the
+ * device address space (hipHostMalloc / a pinned torch tensor): the pointer to
+ * pass as table_dev above.  EMB_ERR_HIP if the memory is not mapped; nothing is
+ * launched.  host_ptr: host; *dev_ptr_out: receives the device pointer. */
+int emb_host_device_pointer(const void *host_ptr, void **dev_ptr_out);
+
+/* ---- table initialisation ------------------------------------------------ */
+
+/* Fill a table with the procedural pseudo-normal values used by the synthetic
+ * workloads (standard deviation 0.01): element i = row*D + d of the table with
+ * `seed` is 0.01/37837.227524f * (s - 131070), s = the sum of the four 16-bit
+ * fields of fmix64(i + (seed+1)*0xD1B54A32D192ED03), fmix64 = the 64-bit
+ * finalizer of MurmurHash3; bf16 tables store the value rounded to
+ * nearest-even.  weights_dev may be HBM or mapped host memory. */
+int emb_table_fill(void *weights_dev, int64_t num_rows, int32_t D, int32_t dtype, uint64_t seed,
+                   void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMB_H */

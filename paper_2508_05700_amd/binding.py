@@ -1,0 +1,272 @@
+"""ctypes binding of the C ABI in ``include/emb.h``.
+
+Argument marshalling only: every function here has the name of the C entry
+point it calls, checks dtype / device / contiguity of the torch tensors it is
+given, passes their ``data_ptr()`` and the current HIP stream, and raises
+``EmbError`` on a negative status.  No step of the path is computed in Python.
+PyTorch is used for device memory and streams.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+POOL = {"sum": 0, "mean": 1}
+DTYPE = {"f32": 0, "bf16": 1}
+STATUS_BAD_INDEX = 1
+STATUS_BAD_OFFSETS = 2
+STATUS_BAD_HOT_SET = 4
+
+# numpy mirror of ``struct emb_table``
+TABLE_DESC = np.dtype([("weights", "<u8"), ("accum", "<u8"), ("num_rows", "<i8"), ("row_base", "<i8"),
+                       ("salt", "<u8"), ("mod_magic", "<u8")])
+assert TABLE_DESC.itemsize == 48
+
+EXPORTS = [
+    "emb_status_string", "emb_tables_init", "emb_hash_ids", "emb_hash_ids_tables", "emb_lengths_to_offsets",
+    "emb_bag_forward", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
+    "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_host_device_pointer",
+    "emb_table_fill",
+]
+
+
+class EmbError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        self.code = code
+        name = lib().emb_status_string(code).decode()
+        super().__init__(f"{fn} failed: {name} ({code})")
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def lib() -> C.CDLL:
+    """Load ``libemb_hip.so``; build it first only if no built library exists.
+    There is no fallback: without the HIP library nothing in this package works."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build(verbose=False)
+    L = C.CDLL(_build.LIB)
+    vp, i64, i32, u64, f32, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float, C.c_size_t
+    L.emb_status_string.restype = C.c_char_p
+    L.emb_status_string.argtypes = [C.c_int]
+    L.emb_tables_init.restype = C.c_int
+    L.emb_tables_init.argtypes = [vp, i32]
+    L.emb_hash_ids.restype = C.c_int
+    L.emb_hash_ids.argtypes = [vp, i64, u64, i64, vp, vp]
+    L.emb_hash_ids_tables.restype = C.c_int
+    L.emb_hash_ids_tables.argtypes = [vp, vp, i32, vp, vp, i64, i64, vp, vp, vp]
+    L.emb_lengths_to_offsets.restype = C.c_int
+    L.emb_lengths_to_offsets.argtypes = [vp, i64, vp, vp, vp]
+    L.emb_bag_forward.restype = C.c_int
+    L.emb_bag_forward.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp]
+    L.emb_bag_backward_workspace_bytes.restype = sz
+    L.emb_bag_backward_workspace_bytes.argtypes = [i32, i64, i64, i64]
+    L.emb_bag_backward_rowwise_adagrad.restype = C.c_int
+    L.emb_bag_backward_rowwise_adagrad.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, f32, f32,
+                                                   vp, sz, vp, vp, vp, vp, vp]
+    L.emb_cache_index_bytes.restype = C.c_int
+    L.emb_cache_index_bytes.argtypes = [i64, C.POINTER(sz)]
+    L.emb_cache_build.restype = C.c_int
+    L.emb_cache_build.argtypes = [vp, i64, i32, i32, vp, i64, vp, vp, vp, vp]
+    L.emb_bag_forward_cached.restype = C.c_int
+    L.emb_bag_forward_cached.argtypes = [vp, i64, i32, i32, vp, vp, i64, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    L.emb_host_device_pointer.restype = C.c_int
+    L.emb_host_device_pointer.argtypes = [vp, C.POINTER(vp)]
+    L.emb_table_fill.restype = C.c_int
+    L.emb_table_fill.argtypes = [vp, i64, i32, i32, u64, vp]
+    _lib = L
+    return L
+
+
+# ---------------------------------------------------------------------------
+# marshalling helpers
+# ---------------------------------------------------------------------------
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, name: str = "tensor") -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError(f"{name} must be a device tensor")
+    if not t.is_contiguous():
+        raise TypeError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype not in (dtype if isinstance(dtype, tuple) else (dtype,)):
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return int(t.data_ptr())
+
+
+def _check(fn: str, rc: int) -> None:
+    if rc != 0:
+        raise EmbError(fn, rc)
+
+
+_U64 = (torch.int64, torch.uint64)
+_TABLE_TORCH = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+class TableSet:
+    """The ``emb_table`` descriptor array of T tables, on the host and on the device.
+
+    ``weights[t]`` is a device tensor ``[R_t, D]`` (fp32 or bf16) or, for memory
+    that torch does not own (mapped host memory), a tuple ``(ptr, num_rows)``.
+    ``accum[t]`` is a device fp32 tensor ``[R_t]`` or None.
+    """
+
+    def __init__(self, weights: Sequence, D: int, dtype: str, accum: Optional[Sequence] = None,
+                 salts: Optional[Sequence[int]] = None, device: Optional[torch.device] = None):
+        self.T = len(weights)
+        self.D = int(D)
+        self.dtype = dtype
+        self.weights = list(weights)
+        self.accum = list(accum) if accum is not None else [None] * self.T
+        self.host = np.zeros(self.T, dtype=TABLE_DESC)
+        for t, w in enumerate(self.weights):
+            if isinstance(w, tuple):
+                ptr, rows = int(w[0]), int(w[1])
+            else:
+                if w.dim() != 2 or w.shape[1] != self.D:
+                    raise TypeError("weights[%d] must be [num_rows, D]" % t)
+                ptr, rows = _ptr(w, _TABLE_TORCH[dtype], "weights[%d]" % t), int(w.shape[0])
+            self.host["weights"][t] = ptr
+            self.host["num_rows"][t] = rows
+            a = self.accum[t]
+            if a is not None:
+                if a.numel() != rows:
+                    raise TypeError("accum[%d] must have num_rows elements" % t)
+                self.host["accum"][t] = _ptr(a, torch.float32, "accum[%d]" % t)
+            self.host["salt"][t] = (int(salts[t]) if salts is not None else t) % (1 << 64)
+        _check("emb_tables_init", lib().emb_tables_init(self.host.ctypes.data, self.T))
+        self.total_rows = int(self.host["num_rows"].sum()) if self.T else 0
+        if device is None:
+            device = torch.device("cuda", torch.cuda.current_device())
+        raw = torch.from_numpy(self.host.view(np.uint8).reshape(-1).copy())
+        self.dev = raw.to(device) if self.T else torch.empty(0, dtype=torch.uint8, device=device)
+
+    @property
+    def host_ptr(self) -> int:
+        return int(self.host.ctypes.data)
+
+    @property
+    def dev_ptr(self) -> int:
+        return int(self.dev.data_ptr())
+
+
+# ---------------------------------------------------------------------------
+# the entry points
+# ---------------------------------------------------------------------------
+def emb_hash_ids(raw: torch.Tensor, salt: int, num_rows: int, rows: torch.Tensor) -> None:
+    n = raw.numel()
+    if rows.numel() != n:
+        raise TypeError("rows must have as many elements as raw")
+    _check("emb_hash_ids", lib().emb_hash_ids(_ptr(raw, _U64, "raw"), n, C.c_uint64(int(salt) % (1 << 64)),
+                                              int(num_rows), _ptr(rows, torch.int64, "rows"), _stream()))
+
+
+def emb_hash_ids_tables(tables: TableSet, raw: torch.Tensor, offsets: torch.Tensor, B: int, rows: torch.Tensor,
+                        status: Optional[torch.Tensor] = None) -> None:
+    nnz = raw.numel()
+    if rows.numel() != nnz or offsets.numel() != tables.T * B + 1:
+        raise TypeError("shape mismatch")
+    _check("emb_hash_ids_tables", lib().emb_hash_ids_tables(
+        tables.host_ptr, tables.dev_ptr, tables.T, _ptr(raw, _U64, "raw"), _ptr(offsets, torch.int64, "offsets"),
+        int(B), nnz, _ptr(rows, torch.int64, "rows"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_lengths_to_offsets(lengths: torch.Tensor, offsets: torch.Tensor, status: Optional[torch.Tensor] = None) -> None:
+    n = lengths.numel()
+    if offsets.numel() != n + 1:
+        raise TypeError("offsets must have lengths.numel() + 1 elements")
+    _check("emb_lengths_to_offsets", lib().emb_lengths_to_offsets(
+        _ptr(lengths, torch.int32, "lengths") if n else None, n, _ptr(offsets, torch.int64, "offsets"),
+        _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_bag_forward(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
+                    out: torch.Tensor, status: Optional[torch.Tensor] = None) -> None:
+    if offsets.numel() != tables.T * B + 1 or out.numel() != tables.T * B * tables.D:
+        raise TypeError("shape mismatch")
+    _check("emb_bag_forward", lib().emb_bag_forward(
+        tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype],
+        _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), rows.numel(), POOL[mode],
+        _ptr(out, torch.float32, "out"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_bag_backward_workspace_bytes(T: int, B: int, nnz: int, total_rows: int) -> int:
+    return int(lib().emb_bag_backward_workspace_bytes(int(T), int(B), int(nnz), int(total_rows)))
+
+
+def emb_bag_backward_rowwise_adagrad(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
+                                     dout: torch.Tensor, lr: float, eps: float, workspace: torch.Tensor,
+                                     unique_keys: Optional[torch.Tensor] = None,
+                                     unique_counts: Optional[torch.Tensor] = None,
+                                     num_unique: Optional[torch.Tensor] = None,
+                                     status: Optional[torch.Tensor] = None) -> None:
+    nnz = rows.numel()
+    if offsets.numel() != tables.T * B + 1 or dout.numel() != tables.T * B * tables.D:
+        raise TypeError("shape mismatch")
+    for t, name in ((unique_keys, "unique_keys"), (unique_counts, "unique_counts")):
+        if t is not None and t.numel() < nnz:
+            raise TypeError(name + " must hold at least nnz elements")
+    _check("emb_bag_backward_rowwise_adagrad", lib().emb_bag_backward_rowwise_adagrad(
+        tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype],
+        _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode],
+        _ptr(dout, torch.float32, "dout"), C.c_float(lr), C.c_float(eps),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+        _ptr(unique_keys, torch.int64, "unique_keys"), _ptr(unique_counts, torch.int32, "unique_counts"),
+        _ptr(num_unique, torch.int64, "num_unique"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_cache_index_bytes(num_rows: int) -> int:
+    out = C.c_size_t(0)
+    _check("emb_cache_index_bytes", lib().emb_cache_index_bytes(int(num_rows), C.byref(out)))
+    return int(out.value)
+
+
+def emb_cache_build(table_ptr: int, num_rows: int, D: int, dtype: str, hot_rows: torch.Tensor,
+                    cache_rows: torch.Tensor, cache_index: torch.Tensor,
+                    status: Optional[torch.Tensor] = None) -> None:
+    _check("emb_cache_build", lib().emb_cache_build(
+        int(table_ptr), int(num_rows), int(D), DTYPE[dtype], _ptr(hot_rows, torch.int64, "hot_rows"),
+        hot_rows.numel(), _ptr(cache_rows, _TABLE_TORCH[dtype], "cache_rows"),
+        _ptr(cache_index, torch.uint8, "cache_index"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_bag_forward_cached(table_ptr: int, num_rows: int, D: int, dtype: str, cache_rows: torch.Tensor,
+                           cache_index: torch.Tensor, num_hot: int, rows: torch.Tensor, offsets: torch.Tensor,
+                           B: int, mode: str, out: torch.Tensor, hit_miss: Optional[torch.Tensor] = None,
+                           status: Optional[torch.Tensor] = None) -> None:
+    if offsets.numel() != B + 1 or out.numel() != B * D:
+        raise TypeError("shape mismatch")
+    _check("emb_bag_forward_cached", lib().emb_bag_forward_cached(
+        int(table_ptr), int(num_rows), int(D), DTYPE[dtype], _ptr(cache_rows, _TABLE_TORCH[dtype], "cache_rows"),
+        _ptr(cache_index, torch.uint8, "cache_index"), int(num_hot), _ptr(rows, torch.int64, "rows"),
+        _ptr(offsets, torch.int64, "offsets"), int(B), rows.numel(), POOL[mode], _ptr(out, torch.float32, "out"),
+        _ptr(hit_miss, _U64, "hit_miss"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_host_device_pointer(host_ptr: int) -> int:
+    out = C.c_void_p(0)
+    _check("emb_host_device_pointer", lib().emb_host_device_pointer(int(host_ptr), C.byref(out)))
+    return int(out.value)
+
+
+def emb_table_fill(weights, num_rows: int, D: int, dtype: str, seed: int) -> None:
+    """``weights``: a device tensor, or a raw device-visible pointer (int)."""
+    ptr = weights if isinstance(weights, int) else _ptr(weights, _TABLE_TORCH[dtype], "weights")
+    _check("emb_table_fill", lib().emb_table_fill(ptr, int(num_rows), int(D), DTYPE[dtype],
+                                                  C.c_uint64(int(seed) % (1 << 64)), _stream()))

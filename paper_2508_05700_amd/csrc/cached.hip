@@ -1,0 +1,249 @@
+// Pooled lookup over a table that lives in host memory (mapped into the device
+// address space) with a static cache of hot rows in HBM: the one-box analogue
+// of hosting the large tables in CPU memory next to a GPU-resident upper model
+// (paper Section 3.3).
+//
+// Cache index: one 16-byte entry per 64 table rows holding a presence bitmap
+// and the number of hot rows that precede the entry.  Because the cached rows
+// are stored in ascending row order, the slot of a hot row is that count plus
+// the population count of the lower bitmap bits: one 16-byte probe decides
+// hit or miss and yields the slot, with no collisions and no search.
+#include "emb_internal.h"
+#include "gather.h"
+
+namespace {
+
+struct CacheEntry {
+    uint64_t bits;    // bit i set: row 64*e + i is cached
+    uint32_t before;  // number of cached rows with a smaller row number
+    uint32_t pad;
+};
+static_assert(sizeof(CacheEntry) == 16, "cache index entry must be 16 bytes");
+
+constexpr int CB_BLOCK = 256;
+
+__global__ __launch_bounds__(CB_BLOCK) void cache_clear_kernel(uint4 *index, int64_t entries)
+{
+    int64_t i = (int64_t)blockIdx.x * CB_BLOCK + threadIdx.x;
+    if (i < entries) index[i] = make_uint4(0, 0, 0, 0);
+}
+
+// One thread per hot row: validate the ordering, set its bit, and let the
+// first hot row of every entry record how many hot rows precede it.
+__global__ __launch_bounds__(CB_BLOCK) void cache_mark_kernel(const int64_t *__restrict__ hot, int64_t num_hot,
+                                                              int64_t num_rows, CacheEntry *index, uint32_t *status)
+{
+    int64_t k = (int64_t)blockIdx.x * CB_BLOCK + threadIdx.x;
+    if (k >= num_hot) return;
+    const int64_t r = hot[k];
+    const int64_t prev = k > 0 ? hot[k - 1] : -1;
+    if (r < 0 || r >= num_rows || r <= prev) {
+        emb_flag(status, EMB_STATUS_BAD_HOT_SET);
+        return;
+    }
+    CacheEntry *e = index + (r >> 6);
+    atomicOr(reinterpret_cast<unsigned long long *>(&e->bits), 1ull << (r & 63));
+    if (prev < 0 || (prev >> 6) != (r >> 6)) e->before = (uint32_t)k;
+}
+
+// LPR lanes copy one hot row (16-byte chunks) from the table into the cache.
+__global__ __launch_bounds__(CB_BLOCK) void cache_copy_kernel(const char *__restrict__ table,
+                                                              const int64_t *__restrict__ hot, int64_t num_hot,
+                                                              int64_t num_rows, int32_t chunks_per_row,
+                                                              char *__restrict__ cache_rows)
+{
+    const int64_t total = num_hot * chunks_per_row;
+    for (int64_t i = (int64_t)blockIdx.x * CB_BLOCK + threadIdx.x; i < total; i += (int64_t)gridDim.x * CB_BLOCK) {
+        const int64_t k = i / chunks_per_row;
+        const int64_t c = i - k * chunks_per_row;
+        const int64_t r = hot[k];
+        if (r < 0 || r >= num_rows) continue;
+        const uint4 v = *reinterpret_cast<const uint4 *>(table + (r * chunks_per_row + c) * 16);
+        *reinterpret_cast<uint4 *>(cache_rows + i * 16) = v;
+    }
+}
+
+// Rows come from the HBM cache when present, else from the (host) table.
+struct CachedSource {
+    const char *table;
+    const char *cache_rows;
+    const CacheEntry *index;
+    uint64_t num_rows;
+    uint64_t num_hot;
+    int64_t row_bytes;
+    uint32_t *status;
+    uint32_t hits, misses;
+    __device__ __forceinline__ uint64_t resolve(int64_t r)
+    {
+        if ((uint64_t)r >= num_rows) {
+            emb_flag(status, EMB_STATUS_BAD_INDEX);
+            return 0ull;
+        }
+        const uint4 raw = *reinterpret_cast<const uint4 *>(index + (r >> 6));
+        const uint64_t bits = ((uint64_t)raw.y << 32) | raw.x;
+        const int bit = (int)(r & 63);
+        if ((bits >> bit) & 1ull) {
+            const uint64_t slot = (uint64_t)raw.z + (uint64_t)__popcll(bits & ((1ull << bit) - 1ull));
+            if (slot < num_hot) {  // always true for an index built from a valid hot set
+                ++hits;
+                return reinterpret_cast<uint64_t>(cache_rows + (int64_t)slot * row_bytes);
+            }
+        }
+        ++misses;
+        return reinterpret_cast<uint64_t>(table + r * row_bytes);
+    }
+};
+
+constexpr int CF_BLOCK = 256;
+
+template <int LPR, int CPL, int UNROLL, bool BF16>
+__global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_kernel(const char *__restrict__ table,
+                                                                      const char *__restrict__ cache_rows,
+                                                                      const CacheEntry *__restrict__ index,
+                                                                      int64_t num_rows, int64_t num_hot, int64_t B,
+                                                                      int64_t nnz, const int64_t *__restrict__ rows,
+                                                                      const int64_t *__restrict__ offsets,
+                                                                      int32_t chunks_per_row, int32_t mode,
+                                                                      float *__restrict__ out,
+                                                                      unsigned long long *hit_miss, uint32_t *status)
+{
+    constexpr int GROUPS = CF_BLOCK / LPR;
+    const int l = threadIdx.x % LPR;
+    const int64_t b = (int64_t)blockIdx.x * GROUPS + threadIdx.x / LPR;
+    CachedSource src{table,  cache_rows, index, (uint64_t)num_rows, (uint64_t)num_hot, (int64_t)chunks_per_row * 16,
+                     status, 0u,         0u};
+    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, b, l, nnz, rows, offsets, chunks_per_row, mode, out, status);
+    if (hit_miss) {
+        // every lane of the wavefront is still here: reduce, then one atomic per wavefront
+        uint32_t h = src.hits, m = src.misses;
+#pragma unroll
+        for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) {
+            h += __shfl_xor(h, d, EMB_WAVE);
+            m += __shfl_xor(m, d, EMB_WAVE);
+        }
+        if ((threadIdx.x & (EMB_WAVE - 1)) == 0) {
+            if (h) atomicAdd(&hit_miss[0], (unsigned long long)h);
+            if (m) atomicAdd(&hit_miss[1], (unsigned long long)m);
+        }
+    }
+}
+
+template <int LPR, int CPL, int UNROLL>
+int launch_cached(bool bf16, hipStream_t s, const char *table, const char *cache_rows, const CacheEntry *index,
+                  int64_t num_rows, int64_t num_hot, int64_t B, int64_t nnz, const int64_t *rows,
+                  const int64_t *offsets, int32_t chunks, int32_t mode, float *out, unsigned long long *hit_miss, uint32_t *status)
+{
+    constexpr int GROUPS = CF_BLOCK / LPR;
+    dim3 grid((unsigned)((B + GROUPS - 1) / GROUPS));
+    if (bf16)
+        hipLaunchKernelGGL((bag_forward_cached_kernel<LPR, CPL, UNROLL, true>), grid, dim3(CF_BLOCK), 0, s, table,
+                           cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, chunks, mode, out, hit_miss, status);
+    else
+        hipLaunchKernelGGL((bag_forward_cached_kernel<LPR, CPL, UNROLL, false>), grid, dim3(CF_BLOCK), 0, s, table,
+                           cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, chunks, mode, out, hit_miss, status);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    return EMB_OK;
+}
+
+}  // namespace
+
+extern "C" int emb_cache_index_bytes(int64_t num_rows, size_t *bytes)
+{
+    if (num_rows <= 0 || !bytes) return EMB_ERR_INVALID_ARG;
+    *bytes = (size_t)((num_rows + 63) / 64) * sizeof(CacheEntry);
+    return EMB_OK;
+}
+
+extern "C" int emb_host_device_pointer(const void *host_ptr, void **dev_ptr_out)
+{
+    if (!host_ptr || !dev_ptr_out) return EMB_ERR_INVALID_ARG;
+    void *d = nullptr;
+    if (hipHostGetDevicePointer(&d, const_cast<void *>(host_ptr), 0) != hipSuccess || !d) {
+        (void)hipGetLastError();  // clear the sticky error
+        return EMB_ERR_HIP;
+    }
+    *dev_ptr_out = d;
+    return EMB_OK;
+}
+
+extern "C" int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                               const int64_t *hot_rows_dev, int64_t num_hot, void *cache_rows_dev,
+                               void *cache_index_dev, uint32_t *status_dev, void *stream)
+{
+    if (num_rows <= 0 || num_hot < 0 || num_hot > num_rows) return EMB_ERR_INVALID_ARG;
+    int rc = emb_check_row_shape(D, dtype);
+    if (rc != EMB_OK) return rc;
+    if (!table_dev || !cache_index_dev || (num_hot > 0 && (!hot_rows_dev || !cache_rows_dev)))
+        return EMB_ERR_INVALID_ARG;
+    if (!emb_aligned(table_dev, 16) || !emb_aligned(cache_index_dev, 16) || !emb_aligned(cache_rows_dev, 16))
+        return EMB_ERR_INVALID_ARG;
+    if (num_hot > (int64_t)0xFFFFFFFF) return EMB_ERR_UNSUPPORTED;
+    hipStream_t s = emb_stream(stream);
+    const int64_t entries = (num_rows + 63) / 64;
+    const int64_t cblocks = (entries + CB_BLOCK - 1) / CB_BLOCK;
+    if (cblocks > 0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(cache_clear_kernel, dim3((unsigned)cblocks), dim3(CB_BLOCK), 0, s,
+                       reinterpret_cast<uint4 *>(cache_index_dev), entries);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    if (num_hot == 0) return EMB_OK;
+    const int64_t mblocks = (num_hot + CB_BLOCK - 1) / CB_BLOCK;
+    hipLaunchKernelGGL(cache_mark_kernel, dim3((unsigned)mblocks), dim3(CB_BLOCK), 0, s, hot_rows_dev, num_hot,
+                       num_rows, reinterpret_cast<CacheEntry *>(cache_index_dev), status_dev);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    const int chunks = D * emb_elem_size(dtype) / 16;
+    int64_t want = (num_hot * chunks + CB_BLOCK - 1) / CB_BLOCK;
+    unsigned grid = (unsigned)(want > 65536 ? 65536 : want);
+    hipLaunchKernelGGL(cache_copy_kernel, dim3(grid), dim3(CB_BLOCK), 0, s, reinterpret_cast<const char *>(table_dev),
+                       hot_rows_dev, num_hot, num_rows, chunks, reinterpret_cast<char *>(cache_rows_dev));
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    return EMB_OK;
+}
+
+extern "C" int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                                      const void *cache_rows_dev, const void *cache_index_dev, int64_t num_hot,
+                                      const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
+                                      int32_t mode, float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
+                                      void *stream)
+{
+    if (B < 0 || nnz < 0 || num_rows <= 0 || num_hot < 0) return EMB_ERR_INVALID_ARG;
+    if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
+    int rc = emb_check_row_shape(D, dtype);
+    if (rc != EMB_OK) return rc;
+    if (B == 0) return EMB_OK;
+    if (!table_dev || !cache_index_dev || (num_hot > 0 && !cache_rows_dev)) return EMB_ERR_INVALID_ARG;
+    if (!offsets_dev || !out_dev || (nnz > 0 && !rows_dev)) return EMB_ERR_INVALID_ARG;
+    if (!emb_aligned(table_dev, 16) || !emb_aligned(cache_index_dev, 16) || !emb_aligned(cache_rows_dev, 16) ||
+        !emb_aligned(out_dev, 16))
+        return EMB_ERR_INVALID_ARG;
+    if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+
+    const int chunks = D * emb_elem_size(dtype) / 16;
+    int lpr, cpl;
+    emb_row_split(chunks, lpr, cpl);
+    const bool bf16 = dtype == EMB_BF16;
+    hipStream_t s = emb_stream(stream);
+#define EMB_CF(L, C, U)                                                                                         \
+    return launch_cached<L, C, U>(bf16, s, reinterpret_cast<const char *>(table_dev),                           \
+                                  reinterpret_cast<const char *>(cache_rows_dev),                               \
+                                  reinterpret_cast<const CacheEntry *>(cache_index_dev), num_rows, num_hot, B, nnz, \
+                                  rows_dev, offsets_dev, chunks, mode, out_dev,                                  \
+                                  reinterpret_cast<unsigned long long *>(hit_miss_dev), status_dev)
+    if (cpl == 1) {
+        switch (lpr) {
+            case 1: EMB_CF(1, 1, 8);
+            case 2: EMB_CF(2, 1, 8);
+            case 4: EMB_CF(4, 1, 8);
+            case 8: EMB_CF(8, 1, 8);
+            case 16: EMB_CF(16, 1, 8);
+            case 32: EMB_CF(32, 1, 8);
+            default: EMB_CF(64, 1, 8);
+        }
+    }
+    switch (cpl) {
+        case 2: EMB_CF(64, 2, 4);
+        case 4: EMB_CF(64, 4, 2);
+        case 8: EMB_CF(64, 8, 1);
+        default: EMB_CF(64, 16, 1);
+    }
+#undef EMB_CF
+}

@@ -1,0 +1,54 @@
+// Internal helpers shared by the kernels of the library (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "emb.h"
+
+#define EMB_WAVE 64
+
+static inline hipStream_t emb_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+// Launch errors surface through hipGetLastError right after the launch.
+#define EMB_RETURN_IF_LAUNCH_FAILED()                 \
+    do {                                              \
+        if (hipGetLastError() != hipSuccess) return EMB_ERR_HIP; \
+    } while (0)
+
+static inline bool emb_aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Checks shared by the multi-table entry points.  Returns EMB_OK or an error.
+static inline int emb_check_tables(const emb_table *th, const emb_table *td, int32_t T, bool need_accum)
+{
+    if (T < 0) return EMB_ERR_INVALID_ARG;
+    if (T == 0) return EMB_OK;
+    if (!th || !td) return EMB_ERR_INVALID_ARG;
+    int64_t base = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        if (!th[t].weights || th[t].num_rows <= 0) return EMB_ERR_INVALID_ARG;
+        if (!emb_aligned(th[t].weights, 16)) return EMB_ERR_INVALID_ARG;
+        if (th[t].row_base != base) return EMB_ERR_INVALID_ARG;
+        if (th[t].mod_magic != ~UINT64_C(0) / (uint64_t)th[t].num_rows) return EMB_ERR_INVALID_ARG;
+        if (need_accum && !th[t].accum) return EMB_ERR_UNSUPPORTED;
+        if (base > INT64_MAX - th[t].num_rows) return EMB_ERR_INVALID_ARG;
+        base += th[t].num_rows;
+    }
+    return EMB_OK;
+}
+
+static inline int emb_elem_size(int32_t dtype) { return dtype == EMB_F32 ? 4 : (dtype == EMB_BF16 ? 2 : 0); }
+
+// Row shape accepted by the gather kernels: whole 16-byte chunks, at most 1024 of them.
+static inline int emb_check_row_shape(int32_t D, int32_t dtype)
+{
+    int esz = emb_elem_size(dtype);
+    if (esz == 0 || D <= 0) return EMB_ERR_INVALID_ARG;
+    int64_t bytes = (int64_t)D * esz;
+    if (bytes % 16 != 0 || bytes > 16384) return EMB_ERR_UNSUPPORTED;
+    return EMB_OK;
+}
+
+__device__ __forceinline__ void emb_flag(uint32_t *status, uint32_t bit)
+{
+    if (status) atomicOr(status, bit);
+}

@@ -1,0 +1,110 @@
+// Pooled lookup (EmbeddingBag forward) over T hashed embedding tables
+// (paper Sections 2.2 and 3.1): gather the rows a bag selects and sum or
+// average them.
+//
+// One launch covers all tables: blockIdx.y is the table, so the table
+// descriptor is uniform across a workgroup; the gather loop itself lives in
+// gather.h (gather_pool_bag), shared with the cached lookup.
+#include "emb_internal.h"
+#include "gather.h"
+
+namespace {
+
+constexpr int FWD_BLOCK = 256;
+
+// Rows come straight from the table in device memory.
+struct TableSource {
+    const char *weights;
+    uint64_t num_rows;
+    int64_t row_bytes;
+    uint32_t *status;
+    __device__ __forceinline__ uint64_t resolve(int64_t r) const
+    {
+        if ((uint64_t)r >= num_rows) {
+            emb_flag(status, EMB_STATUS_BAD_INDEX);
+            return 0ull;
+        }
+        return reinterpret_cast<uint64_t>(weights + r * row_bytes);
+    }
+};
+
+template <int LPR, int CPL, int UNROLL, bool BF16>
+__global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table *__restrict__ tables, int64_t B,
+                                                                int64_t nnz, const int64_t *__restrict__ rows,
+                                                                const int64_t *__restrict__ offsets,
+                                                                int32_t chunks_per_row, int32_t mode,
+                                                                float *__restrict__ out, uint32_t *status)
+{
+    constexpr int GROUPS = FWD_BLOCK / LPR;
+    const int t = blockIdx.y;
+    const int l = threadIdx.x % LPR;
+    const int64_t b = (int64_t)blockIdx.x * GROUPS + threadIdx.x / LPR;
+    const emb_table tb = tables[t];
+    TableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, (int64_t)chunks_per_row * 16,
+                    status};
+    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, (int64_t)t * B + b, l, nnz, rows, offsets, chunks_per_row,
+                                            mode, out, status);
+}
+
+template <int LPR, int CPL, int UNROLL>
+int launch_forward(bool bf16, dim3 grid, hipStream_t s, const emb_table *tables, int64_t B, int64_t nnz,
+                   const int64_t *rows, const int64_t *offsets, int32_t chunks, int32_t mode, float *out,
+                   uint32_t *status)
+{
+    constexpr int GROUPS = FWD_BLOCK / LPR;
+    grid.x = (unsigned)((B + GROUPS - 1) / GROUPS);
+    if (bf16)
+        hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, true>), grid, dim3(FWD_BLOCK), 0, s, tables, B, nnz,
+                           rows, offsets, chunks, mode, out, status);
+    else
+        hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, false>), grid, dim3(FWD_BLOCK), 0, s, tables, B, nnz,
+                           rows, offsets, chunks, mode, out, status);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    return EMB_OK;
+}
+
+}  // namespace
+
+extern "C" int emb_bag_forward(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
+                               int32_t dtype, const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B,
+                               int64_t nnz, int32_t mode, float *out_dev, uint32_t *status_dev, void *stream)
+{
+    if (B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
+    if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
+    int rc = emb_check_row_shape(D, dtype);
+    if (rc != EMB_OK) return rc;
+    rc = emb_check_tables(tables_host, tables_dev, T, false);
+    if (rc != EMB_OK) return rc;
+    if (T == 0 || B == 0) return EMB_OK;
+    if (T > 65535) return EMB_ERR_UNSUPPORTED;
+    if (!offsets_dev || !out_dev || (nnz > 0 && !rows_dev)) return EMB_ERR_INVALID_ARG;
+    if (!emb_aligned(out_dev, 16)) return EMB_ERR_INVALID_ARG;
+    if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+
+    const int chunks = D * emb_elem_size(dtype) / 16;
+    int lpr, cpl;
+    emb_row_split(chunks, lpr, cpl);
+    const bool bf16 = dtype == EMB_BF16;
+    dim3 grid(1, (unsigned)T, 1);
+    hipStream_t s = emb_stream(stream);
+#define EMB_FWD(L, C, U) \
+    return launch_forward<L, C, U>(bf16, grid, s, tables_dev, B, nnz, rows_dev, offsets_dev, chunks, mode, out_dev, status_dev)
+    if (cpl == 1) {
+        switch (lpr) {
+            case 1: EMB_FWD(1, 1, 8);
+            case 2: EMB_FWD(2, 1, 8);
+            case 4: EMB_FWD(4, 1, 8);
+            case 8: EMB_FWD(8, 1, 8);
+            case 16: EMB_FWD(16, 1, 8);
+            case 32: EMB_FWD(32, 1, 8);
+            default: EMB_FWD(64, 1, 8);
+        }
+    }
+    switch (cpl) {
+        case 2: EMB_FWD(64, 2, 4);
+        case 4: EMB_FWD(64, 4, 2);
+        case 8: EMB_FWD(64, 8, 1);
+        default: EMB_FWD(64, 16, 1);
+    }
+#undef EMB_FWD
+}

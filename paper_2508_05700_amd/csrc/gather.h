@@ -1,0 +1,156 @@
+// Device helpers shared by the gather-pool kernels: 16-byte row chunks of fp32
+// or bf16 rows, accumulated in fp32.
+#pragma once
+#include "emb_internal.h"
+
+// Per-lane accumulator for one 16-byte chunk of a row.
+template <bool BF16>
+struct ChunkAcc;
+
+template <>
+struct ChunkAcc<false> {
+    static constexpr int FLOATS = 4;
+    float a[4];
+    __device__ __forceinline__ void zero() { a[0] = a[1] = a[2] = a[3] = 0.f; }
+    __device__ __forceinline__ void add(const uint4 &v)
+    {
+        a[0] += __uint_as_float(v.x);
+        a[1] += __uint_as_float(v.y);
+        a[2] += __uint_as_float(v.z);
+        a[3] += __uint_as_float(v.w);
+    }
+};
+
+template <>
+struct ChunkAcc<true> {
+    static constexpr int FLOATS = 8;
+    float a[8];
+    __device__ __forceinline__ void zero()
+    {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) a[i] = 0.f;
+    }
+    // a bf16 value is the high half of an fp32: widening is a shift / a mask
+    __device__ __forceinline__ void add(const uint4 &v)
+    {
+        a[0] += __uint_as_float(v.x << 16);
+        a[1] += __uint_as_float(v.x & 0xFFFF0000u);
+        a[2] += __uint_as_float(v.y << 16);
+        a[3] += __uint_as_float(v.y & 0xFFFF0000u);
+        a[4] += __uint_as_float(v.z << 16);
+        a[5] += __uint_as_float(v.z & 0xFFFF0000u);
+        a[6] += __uint_as_float(v.w << 16);
+        a[7] += __uint_as_float(v.w & 0xFFFF0000u);
+    }
+};
+
+__device__ __forceinline__ uint4 load_chunk(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
+
+__device__ __forceinline__ int64_t shfl_i64(int64_t v, int src, int width)
+{
+    int lo = __shfl((int)(uint32_t)(uint64_t)v, src, width);
+    int hi = __shfl((int)(uint32_t)((uint64_t)v >> 32), src, width);
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+// Lanes per row (a power of two <= 64) and chunks per lane for a row of
+// `chunks` 16-byte chunks.
+static inline void emb_row_split(int chunks, int &lpr, int &cpl)
+{
+    lpr = 1;
+    while (lpr < chunks && lpr < 64) lpr <<= 1;
+    int need = (chunks + lpr - 1) / lpr;
+    cpl = 1;
+    while (cpl < need) cpl <<= 1;
+}
+
+// ---------------------------------------------------------------------------
+// The gather-pool loop shared by the plain and the cached pooled lookup.
+//
+// A row of chunks_per_row 16-byte chunks is covered by LPR lanes (CPL chunks
+// per lane when a row is wider than a wavefront).  Each group of LPR lanes owns
+// one bag and walks its lookups UNROLL rows at a time, issuing all UNROLL row
+// loads before the first add, so a wavefront keeps 64/LPR * UNROLL independent
+// row reads in flight.  The group's lanes fetch the bag's row indices with one
+// coalesced load; the lane that fetched an index resolves it to the address of
+// the row (Source::resolve: bounds check, and for the cached table the cache
+// probe) and the address is handed round with lane shuffles, so every index is
+// read and resolved exactly once.  No cross-lane reduction is needed: a lane
+// only ever adds the chunks it owns.
+//
+// Source must provide
+//   __device__ uint64_t resolve(int64_t row)   address of the row, 0 = skip it
+// ---------------------------------------------------------------------------
+template <int LPR, int CPL, int UNROLL, bool BF16, typename Source>
+__device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t bag, int l, int64_t nnz,
+                                                const int64_t *__restrict__ rows,
+                                                const int64_t *__restrict__ offsets, int32_t chunks_per_row,
+                                                int32_t mode, float *__restrict__ out, uint32_t *status)
+{
+    constexpr int IPL = (UNROLL > LPR) ? UNROLL / LPR : 1;  // indices fetched per lane per batch
+    constexpr int IB = IPL * LPR;                           // indices per batch
+    static_assert(IB % UNROLL == 0, "index batch must be whole unroll groups");
+
+    int64_t s = 0, e = 0;
+    if (live) {
+        s = offsets[bag];
+        e = offsets[bag + 1];
+        if (s < 0 || e < s || e > nnz) {
+            if (l == 0) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
+            s = e = 0;
+        }
+    }
+
+    ChunkAcc<BF16> acc[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) acc[c].zero();
+
+    for (int64_t base = s; base < e; base += IB) {
+        uint64_t mine[IPL];
+#pragma unroll
+        for (int m = 0; m < IPL; ++m) {
+            const int64_t j = base + m * LPR + l;
+            mine[m] = (j < e) ? src.resolve(rows[j]) : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < IB / UNROLL; ++u) {
+            if (base + u * UNROLL < e) {
+                uint4 v[UNROLL][CPL];
+#pragma unroll
+                for (int i = 0; i < UNROLL; ++i) {
+                    const int k = u * UNROLL + i;
+                    const uint64_t p = (uint64_t)shfl_i64((int64_t)mine[k / LPR], k % LPR, LPR);
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c) {
+                        v[i][c] = make_uint4(0, 0, 0, 0);
+                        if (p != 0 && l + c * LPR < chunks_per_row)
+                            v[i][c] = load_chunk(reinterpret_cast<const char *>(p) + (int64_t)(l + c * LPR) * 16);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < UNROLL; ++i)
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c) acc[c].add(v[i][c]);
+            }
+        }
+    }
+
+    if (!live) return;
+    const int64_t len = e - s;
+    const bool mean = (mode == EMB_POOL_MEAN) && len > 0;
+    const float flen = (float)len;
+    constexpr int F = ChunkAcc<BF16>::FLOATS;
+    float *obase = out + bag * ((int64_t)chunks_per_row * F);
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const int chunk = l + c * LPR;
+        if (chunk < chunks_per_row) {
+            float r[F];
+#pragma unroll
+            for (int i = 0; i < F; ++i) r[i] = mean ? acc[c].a[i] / flen : acc[c].a[i];
+            float4 *o = reinterpret_cast<float4 *>(obase + (int64_t)chunk * F);
+#pragma unroll
+            for (int i = 0; i < F / 4; ++i) o[i] = make_float4(r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]);
+        }
+    }
+}

@@ -1,0 +1,96 @@
+"""Device-side plumbing for running a workload through the library: allocates
+the tables and per-batch buffers with torch, fills the tables procedurally and
+enqueues the entry points in path order (offsets -> hash -> forward ->
+backward).  It only sequences calls of ``binding``; nothing is computed here.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as emb
+from .workloads import DEFAULT_SEED, Workload
+
+_TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+class DeviceTables:
+    """The T tables of a workload in HBM, filled by ``emb_table_fill``."""
+
+    def __init__(self, w: Workload, seed: int = DEFAULT_SEED, device: str = "cuda:0"):
+        self.w = w
+        self.device = torch.device(device)
+        self.weights: List[torch.Tensor] = []
+        self.accum: Optional[List[torch.Tensor]] = [] if w.backward else None
+        for t in range(w.T):
+            wt = torch.empty((w.R, w.D), dtype=_TORCH_DT[w.dtype], device=self.device)
+            emb.emb_table_fill(wt, w.R, w.D, w.dtype, w.table_seed(t, seed))
+            self.weights.append(wt)
+            if w.backward:
+                self.accum.append(torch.zeros(w.R, dtype=torch.float32, device=self.device))
+        self.set = emb.TableSet(self.weights, w.D, w.dtype, accum=self.accum,
+                                salts=[w.salt(t) for t in range(w.T)], device=self.device)
+
+
+class DeviceBatch:
+    """One batch's inputs, resident on the device."""
+
+    def __init__(self, w: Workload, batch: Dict[str, object], device: torch.device):
+        self.nnz = int(batch["nnz"])
+        self.lengths = torch.from_numpy(batch["lengths"]).to(device)
+        raw = batch["raw"]
+        self.raw = None if raw is None else torch.from_numpy(raw.view(np.int64)).to(device)
+        rows = batch["rows"]
+        self.rows_given = None if rows is None else torch.from_numpy(rows).to(device)
+        dout = batch.get("dout")
+        self.dout = None if dout is None else torch.from_numpy(dout).to(device)
+
+
+class StepBuffers:
+    """Outputs and scratch of one step, sized for at most ``max_nnz`` lookups."""
+
+    def __init__(self, w: Workload, max_nnz: int, total_rows: int, device: torch.device, want_unique: bool = False):
+        n = max(int(max_nnz), 1)
+        self.offsets = torch.empty(w.T * w.B + 1, dtype=torch.int64, device=device)
+        self.rows = torch.empty(n, dtype=torch.int64, device=device)
+        self.out = torch.empty((w.T, w.B, w.D), dtype=torch.float32, device=device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
+        self.workspace = None
+        self.unique_keys = self.unique_counts = self.num_unique = None
+        if w.backward:
+            nbytes = emb.emb_bag_backward_workspace_bytes(w.T, w.B, n, total_rows)
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+            if want_unique:
+                self.unique_keys = torch.empty(n, dtype=torch.int64, device=device)
+                self.unique_counts = torch.empty(n, dtype=torch.int32, device=device)
+                self.num_unique = torch.zeros(1, dtype=torch.int64, device=device)
+
+
+def run_index_stage(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:
+    """Bag offsets, then hashed row numbers.  Returns the view of the row buffer in use."""
+    emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
+    if db.raw is None:
+        return db.rows_given
+    rows = buf.rows[:db.nnz]
+    emb.emb_hash_ids_tables(tables, db.raw, buf.offsets, w.B, rows, buf.status)
+    return rows
+
+
+def run_forward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, buf: StepBuffers) -> None:
+    emb.emb_bag_forward(tables, rows, buf.offsets, w.B, w.pool, buf.out, buf.status)
+
+
+def run_backward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, db: DeviceBatch, buf: StepBuffers) -> None:
+    emb.emb_bag_backward_rowwise_adagrad(tables, rows, buf.offsets, w.B, w.pool, db.dout, w.lr, w.eps, buf.workspace,
+                                         buf.unique_keys, buf.unique_counts, buf.num_unique, buf.status)
+
+
+def run_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:
+    """One pass of the whole path over one batch; returns the row view used."""
+    rows = run_index_stage(w, tables, db, buf)
+    run_forward(w, tables, rows, buf)
+    if w.backward:
+        run_backward(w, tables, rows, db, buf)
+    return rows

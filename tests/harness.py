@@ -1,0 +1,126 @@
+"""Shared helpers of the GPU parity tests: run the oracle on host copies of the
+inputs and compare, element by element, with what the HIP library produced.
+
+Tolerances (fp32 results; ``eps32 = 1e-5`` is the stated relative tolerance):
+  pooled output   |gpu - ref| <= eps32 * max(|ref|, absum)      absum = sum |terms|
+  updated row     |gpu - ref| <= eps32 * max(|ref|, |W_old| + lr)
+  accumulator     |gpu - ref| <= eps32 * S_ref + 2 * eps32 * mean_d(Gabs_d^2)
+(the last from d(G^2) = 2 |G| dG with dG <= eps32 * Gabs).  Where a bf16 value
+is written the same forms are used with 1e-2.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from oracle import emb_oracle as oracle
+from paper_2508_05700_amd import binding as emb
+from paper_2508_05700_amd import workloads as wl
+
+EPS32 = 1e-5
+EPS_BF16 = 1e-2
+DEV = "cuda:0"
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    if a.dtype == np.uint64:
+        a = a.view(np.int64)
+    if a.dtype == np.uint16:      # bf16 bit patterns
+        return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host_table(t: torch.Tensor) -> np.ndarray:
+    """Device table -> numpy in the oracle's storage format."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def assert_pooled_close(gpu: np.ndarray, ref: np.ndarray, absum: np.ndarray, eps: float = EPS32, what: str = ""):
+    gpu = gpu.reshape(ref.shape).astype(np.float64)
+    err = np.abs(gpu - ref.astype(np.float64))
+    bound = eps * np.maximum(np.abs(ref.astype(np.float64)), absum)
+    bad = err > bound
+    assert not bad.any(), "%s: %d of %d pooled values off; worst err/bound %.3g" % (
+        what, int(bad.sum()), bad.size, float((err / np.maximum(bound, 1e-300)).max()))
+    assert np.isfinite(gpu).all()
+
+
+def assert_rows_close(gpu: np.ndarray, ref: np.ndarray, old: np.ndarray, lr: float, eps: float = EPS32,
+                      what: str = ""):
+    gpu, ref, old = (x.astype(np.float64) for x in (gpu, ref, old))
+    err = np.abs(gpu - ref)
+    bound = eps * np.maximum(np.abs(ref), np.abs(old) + lr)
+    bad = err > bound
+    assert not bad.any(), "%s: %d of %d row elements off; worst err/bound %.3g" % (
+        what, int(bad.sum()), bad.size, float((err / bound).max()))
+
+
+def assert_accum_close(gpu: np.ndarray, ref: np.ndarray, gabs: np.ndarray, eps: float = EPS32, what: str = ""):
+    gpu, ref = gpu.astype(np.float64), ref.astype(np.float64)
+    err = np.abs(gpu - ref)
+    bound = eps * ref + 2 * eps * (gabs ** 2).mean(axis=1) + 1e-38
+    bad = err > bound
+    assert not bad.any(), "%s: %d of %d accumulators off; worst err/bound %.3g" % (
+        what, int(bad.sum()), bad.size, float((err / bound).max()))
+
+
+def as_f32(table_np: np.ndarray) -> np.ndarray:
+    return wl.bf16_bits_to_f32(table_np) if table_np.dtype == np.uint16 else table_np
+
+
+def random_case(rng, T: int, B: int, D: int, Rs: Sequence[int], max_len: int, dtype: str = "f32",
+                empty_frac: float = 0.15, scale: float = 1.0, hot_row_frac: float = 0.0):
+    """Random tables, lengths, rows; optionally a fraction of lookups hit row 0."""
+    tables = []
+    for R in Rs:
+        v = (rng.standard_normal((R, D)) * scale).astype(np.float32)
+        tables.append(wl.f32_to_bf16_bits(v).reshape(R, D) if dtype == "bf16" else v)
+    lengths = rng.integers(0, max_len + 1, size=T * B).astype(np.int32)
+    lengths[rng.random(T * B) < empty_frac] = 0
+    off = np.concatenate([[0], np.cumsum(lengths.astype(np.int64))]).astype(np.int64)
+    parts = []
+    for t in range(T):
+        n = int(lengths[t * B:(t + 1) * B].sum())
+        r = rng.integers(0, Rs[t], size=n)
+        if hot_row_frac > 0:
+            r[rng.random(n) < hot_row_frac] = 0
+        parts.append(r)
+    rows = np.concatenate(parts).astype(np.int64) if parts else np.zeros(0, np.int64)
+    return tables, lengths, off, rows
+
+
+def make_tableset(tables_np: List[np.ndarray], dtype: str, with_accum: bool = False, salts=None,
+                  accum_np: Optional[List[np.ndarray]] = None):
+    w = [dev(t) for t in tables_np]
+    if accum_np is not None:
+        acc = [dev(a) for a in accum_np]
+    else:
+        acc = [torch.zeros(t.shape[0], dtype=torch.float32, device=DEV) for t in tables_np] if with_accum else None
+    return emb.TableSet(w, tables_np[0].shape[1], dtype, accum=acc, salts=salts, device=torch.device(DEV)), w, acc
+
+
+def gpu_forward(ts, rows_np, off_np, B, mode):
+    out = torch.full((ts.T, B, ts.D), float("nan"), dtype=torch.float32, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    emb.emb_bag_forward(ts, dev(rows_np), dev(off_np), B, mode, out, status)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), int(status.item())
+
+
+def gpu_backward(ts, rows_np, off_np, B, mode, dout_np, lr, eps):
+    nnz = rows_np.size
+    ws = torch.empty(emb.emb_bag_backward_workspace_bytes(ts.T, B, nnz, ts.total_rows), dtype=torch.uint8, device=DEV)
+    uk = torch.full((max(nnz, 1),), -7, dtype=torch.int64, device=DEV)
+    uc = torch.full((max(nnz, 1),), -7, dtype=torch.int32, device=DEV)
+    nu = torch.full((1,), -7, dtype=torch.int64, device=DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=DEV)
+    emb.emb_bag_backward_rowwise_adagrad(ts, dev(rows_np), dev(off_np), B, mode, dev(dout_np), lr, eps, ws, uk, uc, nu,
+                                         status)
+    torch.cuda.synchronize()
+    U = int(nu.item())
+    return {"unique_keys": uk[:U].cpu().numpy(), "unique_counts": uc[:U].cpu().numpy(), "U": U,
+            "status": int(status.item())}

@@ -1,0 +1,160 @@
+"""The C ABI without a GPU: the library loads, exports what the header
+declares, and every host-checkable error is reported without a launch."""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from paper_2508_05700_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, INVALID, UNSUPPORTED, WORKSPACE = 0, -1, -2, -3
+FAKE = 0x1000  # a non-null, 256-byte aligned address; every call below that uses it has one invalid
+               # argument, so the library returns before any launch and never dereferences it
+
+
+@pytest.fixture(scope="module")
+def L():
+    return b.lib()
+
+
+def _tables(rows=(1000, 7), with_accum=True):
+    d = np.zeros(len(rows), dtype=b.TABLE_DESC)
+    d["num_rows"] = rows
+    d["weights"] = FAKE
+    if with_accum:
+        d["accum"] = FAKE
+    assert b.lib().emb_tables_init(d.ctypes.data, len(rows)) == OK
+    return d
+
+
+def test_library_exports_every_declared_symbol(L):
+    header = open(os.path.join(ROOT, "include", "emb.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(emb_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(b.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_descriptor_layout_matches_header():
+    header = open(os.path.join(ROOT, "include", "emb.h")).read()
+    body = re.search(r"typedef struct emb_table \{(.*?)\} emb_table;", header, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"\b(\w+);", body)
+    assert fields == list(b.TABLE_DESC.names)
+    assert b.TABLE_DESC.itemsize == 48
+
+
+def test_status_strings(L):
+    assert L.emb_status_string(0) == b"EMB_OK"
+    assert L.emb_status_string(-3) == b"EMB_ERR_WORKSPACE"
+    assert L.emb_status_string(-99) == b"EMB_ERR_UNKNOWN"
+
+
+def test_tables_init(L):
+    d = _tables((10_000_000, 7, 1))
+    assert d["row_base"].tolist() == [0, 10_000_000, 10_000_007]
+    assert d["mod_magic"].tolist() == [((1 << 64) - 1) // r for r in (10_000_000, 7, 1)]
+    bad = np.zeros(1, dtype=b.TABLE_DESC)
+    assert L.emb_tables_init(bad.ctypes.data, 1) == INVALID         # num_rows == 0
+    assert L.emb_tables_init(None, 1) == INVALID
+    assert L.emb_tables_init(None, 0) == OK
+
+
+def test_hash_ids_argument_errors(L):
+    assert L.emb_hash_ids(None, 5, 0, 10, None, None) == INVALID
+    assert L.emb_hash_ids(FAKE, -1, 0, 10, FAKE, None) == INVALID
+    assert L.emb_hash_ids(FAKE, 5, 0, 0, FAKE, None) == INVALID
+    assert L.emb_hash_ids(None, 0, 0, 10, None, None) == OK            # empty input: nothing to do
+
+
+def test_offsets_argument_errors(L):
+    assert L.emb_lengths_to_offsets(None, 4, FAKE, None, None) == INVALID
+    assert L.emb_lengths_to_offsets(FAKE, -1, FAKE, None, None) == INVALID
+    assert L.emb_lengths_to_offsets(FAKE, 4, None, None, None) == INVALID
+
+
+def test_forward_argument_errors(L):
+    d = _tables()
+    f = L.emb_bag_forward
+    args = lambda **k: [k.get("th", d.ctypes.data), k.get("td", FAKE), k.get("T", 2), k.get("D", 64),
+                        k.get("dt", 0), k.get("rows", FAKE), k.get("off", FAKE), k.get("B", 4), k.get("nnz", 8),
+                        k.get("mode", 0), k.get("out", FAKE), None, None]
+    assert f(*args(D=0)) == INVALID
+    assert f(*args(D=3)) == UNSUPPORTED            # 12-byte rows cannot be read with 128-bit loads
+    assert f(*args(D=4, dt=1)) == UNSUPPORTED      # 8-byte bf16 rows
+    assert f(*args(D=8192)) == UNSUPPORTED         # 32 KB rows
+    assert f(*args(dt=5)) == INVALID
+    assert f(*args(mode=2)) == INVALID
+    assert f(*args(B=-1)) == INVALID
+    assert f(*args(nnz=-1)) == INVALID
+    assert f(*args(out=None)) == INVALID
+    assert f(*args(off=None)) == INVALID
+    assert f(*args(rows=None)) == INVALID
+    assert f(*args(td=None)) == INVALID
+    assert f(*args(out=FAKE + 4)) == INVALID       # misaligned output
+    assert f(*args(B=0)) == OK                     # no bags: nothing to do
+    d2 = d.copy()
+    d2["row_base"][1] += 1
+    assert f(*args(th=d2.ctypes.data)) == INVALID  # descriptors not initialised consistently
+    d3 = d.copy()
+    d3["weights"][0] = 0
+    assert f(*args(th=d3.ctypes.data)) == INVALID
+
+
+def test_backward_argument_errors(L):
+    d = _tables()
+    need = L.emb_bag_backward_workspace_bytes(2, 4, 8, 1007)
+    assert need > 0 and need % 256 == 0
+    f = L.emb_bag_backward_rowwise_adagrad
+
+    def args(**k):
+        return [k.get("th", d.ctypes.data), FAKE, 2, k.get("D", 64), 0, FAKE, FAKE, 4, k.get("nnz", 8),
+                k.get("mode", 1), k.get("dout", FAKE), C.c_float(0.01), C.c_float(1e-8), k.get("ws", FAKE),
+                k.get("wsb", need), None, None, None, None, None]
+    assert f(*args(ws=None)) == WORKSPACE
+    assert f(*args(wsb=need - 1)) == WORKSPACE
+    assert f(*args(ws=FAKE + 16)) == WORKSPACE          # workspace must be 256-byte aligned
+    assert f(*args(D=3)) == UNSUPPORTED
+    assert f(*args(mode=7)) == INVALID
+    assert f(*args(dout=None)) == INVALID
+    assert f(*args(nnz=1 << 31)) == UNSUPPORTED
+    noacc = _tables(with_accum=False)
+    assert f(*args(th=noacc.ctypes.data)) == UNSUPPORTED
+
+
+def test_workspace_bytes(L):
+    w = L.emb_bag_backward_workspace_bytes
+    assert w(-1, 1, 1, 1) == 0 and w(1, -1, 1, 1) == 0 and w(1, 1, -1, 1) == 0
+    a, c = w(16, 8192, 1_000_000, 160_000_000), w(16, 8192, 2_000_000, 160_000_000)
+    assert 0 < a < c
+    # keys widen to 64 bits once the key range passes 2^32
+    assert w(1, 8, 1_000_000, 1 << 33) > w(1, 8, 1_000_000, 1 << 30) + 7_000_000
+
+
+def test_cache_argument_errors(L):
+    n = C.c_size_t(0)
+    assert L.emb_cache_index_bytes(250_000_000, C.byref(n)) == OK
+    assert n.value == ((250_000_000 + 63) // 64) * 16
+    assert L.emb_cache_index_bytes(0, C.byref(n)) == INVALID
+    assert L.emb_cache_build(FAKE, 100, 64, 0, FAKE, 101, FAKE, FAKE, None, None) == INVALID   # more hot rows than rows
+    assert L.emb_cache_build(FAKE, 100, 3, 0, FAKE, 10, FAKE, FAKE, None, None) == UNSUPPORTED
+    assert L.emb_cache_build(None, 100, 64, 0, FAKE, 10, FAKE, FAKE, None, None) == INVALID
+    assert L.emb_bag_forward_cached(FAKE, 100, 64, 0, FAKE, None, 10, FAKE, FAKE, 4, 8, 0, FAKE, None, None,
+                                    None) == INVALID
+    assert L.emb_bag_forward_cached(FAKE, 100, 64, 0, FAKE, FAKE, 10, FAKE, FAKE, 4, 8, 3, FAKE, None, None,
+                                    None) == INVALID
+    assert L.emb_table_fill(None, 10, 64, 0, 1, None) == INVALID
+    assert L.emb_table_fill(FAKE, 10, 6, 0, 1, None) == UNSUPPORTED
+
+
+def test_exact_remainder_on_the_host(tmp_path):
+    exe = str(tmp_path / "u64mod_check")
+    subprocess.check_call(["g++", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "paper_2508_05700_amd", "csrc"),
+                           os.path.join(ROOT, "tests", "host", "u64mod_check.cpp"), "-o", exe])
+    out = subprocess.run([exe], stdout=subprocess.PIPE, text=True)
+    assert out.returncode == 0 and out.stdout.startswith("OK"), out.stdout

@@ -1,0 +1,391 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, on
+seeded inputs that span several tiles and ragged tails, plus edge cases.
+Everything goes through the C ABI (via the ctypes binding)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from oracle import emb_oracle as oracle  # noqa: E402
+from paper_2508_05700_amd import binding as emb  # noqa: E402
+from paper_2508_05700_amd import workloads as wl  # noqa: E402
+from tests import harness as H  # noqa: E402
+
+M64 = (1 << 64) - 1
+
+
+# ---------------------------------------------------------------------------
+# hashing: bit-exact
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [0, 1, 63, 255, 256, 257, 100_003])
+def test_hash_ids_bit_exact(n):
+    rng = np.random.default_rng(100 + n)
+    raw = rng.integers(0, 1 << 64, size=n, dtype=np.uint64)
+    if n >= 8:
+        raw[:8] = [0, 1, M64, M64 - 1, 1 << 63, (1 << 63) - 1, 1 << 32, (1 << 32) - 1]
+    for R, salt in [(1, 0), (2, 5), (10_000_000, 3), (1_000_000_000, M64), (250_000_000, 1 << 63),
+                    ((1 << 31) - 1, 9), (1 << 32, 11), ((1 << 40) + 17, 13), ((1 << 63) - 1, 17)]:
+        rows = torch.full((n,), -5, dtype=torch.int64, device=H.DEV)
+        emb.emb_hash_ids(H.dev(raw), salt, R, rows)
+        torch.cuda.synchronize()
+        assert np.array_equal(rows.cpu().numpy(), oracle.hash_ids(raw, salt, R)), (n, R, salt)
+
+
+def test_hash_ids_tables_bit_exact():
+    rng = np.random.default_rng(7)
+    T, B = 5, 37
+    Rs = [10_000_000, 3, (1 << 33) + 5, 999_983, 1]
+    salts = [0, 1, M64, 12345, 1 << 40]
+    lengths = rng.integers(0, 50, size=T * B).astype(np.int32)
+    lengths[B:2 * B] = 0                                   # a table with no lookups at all
+    off, _ = oracle.lengths_to_offsets(lengths)
+    nnz = int(off[-1])
+    raw = rng.integers(0, 1 << 64, size=nnz, dtype=np.uint64)
+    tables = [torch.empty((1, 4), dtype=torch.float32, device=H.DEV) for _ in range(T)]
+    ts = emb.TableSet([(int(t.data_ptr()), R) for t, R in zip(tables, Rs)], 4, "f32", salts=salts,
+                      device=torch.device(H.DEV))
+    rows = torch.full((nnz,), -5, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_hash_ids_tables(ts, H.dev(raw), H.dev(off), B, rows, status)
+    torch.cuda.synchronize()
+    ref = np.concatenate([oracle.hash_ids(raw[off[t * B]:off[(t + 1) * B]], salts[t], Rs[t]) for t in range(T)])
+    assert status.item() == 0 and np.array_equal(rows.cpu().numpy(), ref)
+
+
+# ---------------------------------------------------------------------------
+# offsets: bit-exact
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("n", [0, 1, 2, 4095, 4096, 4097, 131_072, 1_000_005, 4096 * 1025 + 3])
+def test_offsets_bit_exact(n):
+    rng = np.random.default_rng(200 + n % 1000)
+    L = rng.integers(0, 101, size=n).astype(np.int32)
+    out = torch.full((n + 1,), -9, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_lengths_to_offsets(H.dev(L) if n else torch.empty(0, dtype=torch.int32, device=H.DEV), out, status)
+    torch.cuda.synchronize()
+    ref, _ = oracle.lengths_to_offsets(L)
+    assert status.item() == 0 and np.array_equal(out.cpu().numpy(), ref)
+
+
+def test_offsets_large_values_and_negative_lengths():
+    L = np.full(10_000, 2_000_000_000, dtype=np.int32)      # sums far beyond 32 bits
+    L[[5, 4096, 9999]] = [-1, -2_000_000_000, -7]
+    out = torch.empty(L.size + 1, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_lengths_to_offsets(H.dev(L), out, status)
+    torch.cuda.synchronize()
+    ref, st = oracle.lengths_to_offsets(L)
+    assert status.item() == st == emb.STATUS_BAD_OFFSETS and np.array_equal(out.cpu().numpy(), ref)
+
+
+# ---------------------------------------------------------------------------
+# forward
+# ---------------------------------------------------------------------------
+FWD_SHAPES = [
+    # D, dtype  -> lanes per row / chunks per lane exercised
+    (4, "f32"), (8, "f32"), (16, "f32"), (32, "f32"), (64, "f32"), (128, "f32"), (256, "f32"),
+    (48, "f32"),      # 12 chunks: not a power of two
+    (320, "f32"),     # 80 chunks: 64 lanes x 2, ragged
+    (1024, "f32"),    # 4 chunks per lane
+    (4096, "f32"),    # 16 chunks per lane (16 KB rows)
+    (8, "bf16"), (32, "bf16"), (64, "bf16"), (128, "bf16"), (520, "bf16"), (8192, "bf16"),
+]
+
+
+@pytest.mark.parametrize("D,dtype", FWD_SHAPES)
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_forward_matches_oracle(D, dtype, mode):
+    rng = np.random.default_rng(D * 7 + (dtype == "bf16") + 2 * (mode == "mean"))
+    T, B = 3, 301 if D <= 256 else 37
+    Rs = [1000, 17, 4099] if D <= 256 else [50, 3, 40]
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, 70 if D <= 256 else 20, dtype, scale=0.01)
+    ts, _, _ = H.make_tableset(tables, dtype)
+    out, st = H.gpu_forward(ts, rows, off, B, mode)
+    ref, absum, rst = oracle.bag_forward(tables, dtype, rows, off, B, mode)
+    assert st == rst == 0
+    H.assert_pooled_close(out, ref, absum, what="forward D=%d %s %s" % (D, dtype, mode))
+    assert np.all(out.reshape(T * B, D)[lengths == 0] == 0.0)         # empty bags give exact zeros
+
+
+def test_forward_integer_valued_tables_are_bit_exact():
+    # small integers make every fp32 summation order exact: GPU == oracle bit for bit
+    rng = np.random.default_rng(31)
+    T, B, D, Rs = 2, 513, 64, [5000, 33]
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, 100)
+    tables = [np.rint(t * 300).astype(np.float32) for t in tables]
+    ts, _, _ = H.make_tableset(tables, "f32")
+    out, st = H.gpu_forward(ts, rows, off, B, "sum")
+    ref, _, _ = oracle.bag_forward(tables, "f32", rows, off, B, "sum")
+    assert st == 0 and np.array_equal(out, ref)
+
+
+def test_forward_long_bags_and_single_bag():
+    rng = np.random.default_rng(32)
+    D, R = 64, 100_000
+    table = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+    lengths = np.array([5000, 0, 1, 64, 65, 127, 128, 129, 3000], dtype=np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    rows = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    ts, _, _ = H.make_tableset([table], "f32")
+    for mode in ("sum", "mean"):
+        out, st = H.gpu_forward(ts, rows, off, lengths.size, mode)
+        ref, absum, _ = oracle.bag_forward([table], "f32", rows, off, lengths.size, mode)
+        assert st == 0
+        H.assert_pooled_close(out, ref, absum, what="long bags " + mode)
+
+
+def test_forward_bad_indices_and_offsets_are_flagged_and_skipped():
+    rng = np.random.default_rng(33)
+    T, B, D, Rs = 2, 40, 32, [100, 50]
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, 12)
+    rows = rows.copy()
+    n0 = int(off[B])
+    rows[[0, 7, n0 - 1]] = [100, -1, 1 << 40]           # out of range for table 0
+    rows[n0 + 3] = 50                                   # == num_rows of table 1
+    ts, _, _ = H.make_tableset(tables, "f32")
+    out, st = H.gpu_forward(ts, rows, off, B, "mean")
+    ref, absum, rst = oracle.bag_forward(tables, "f32", rows, off, B, "mean")
+    assert st == rst == emb.STATUS_BAD_INDEX
+    H.assert_pooled_close(out, ref, absum, what="bad index")
+    bad_off = off.copy()
+    bad_off[5] = bad_off[6] + 3                          # bag 4 too long, bag 5 reversed
+    bad_off[-1] = off[-1] + 10                           # last bag runs past nnz
+    out, st = H.gpu_forward(ts, rows, bad_off, B, "sum")
+    ref, absum, rst = oracle.bag_forward(tables, "f32", rows, bad_off, B, "sum")
+    assert st == rst and (st & emb.STATUS_BAD_OFFSETS)
+    H.assert_pooled_close(out, ref, absum, what="bad offsets")
+
+
+def test_forward_empty_batch_zero_fills():
+    table = np.ones((10, 16), dtype=np.float32)
+    ts, _, _ = H.make_tableset([table], "f32")
+    off = np.zeros(9, dtype=np.int64)
+    out, st = H.gpu_forward(ts, np.zeros(0, np.int64), off, 8, "mean")
+    assert st == 0 and np.all(out == 0)
+
+
+# ---------------------------------------------------------------------------
+# backward + row-wise Adagrad
+# ---------------------------------------------------------------------------
+def _backward_case(rng, T, B, D, Rs, max_len, dtype, mode, hot=0.0, lr=0.01, eps=1e-8, steps=1):
+    """Several training steps; before each one the device state is (re)loaded from the
+    oracle's state, so the two sides start every step from identical tables."""
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, max_len, dtype, scale=0.01, hot_row_frac=hot)
+    ref_tables = [t.copy() for t in tables]
+    ref_acc = [np.zeros(R, dtype=np.float32) for R in Rs]
+    bf = dtype == "bf16"
+    base = np.concatenate([[0], np.cumsum(Rs)])
+    for step in range(steps):
+        dout = rng.standard_normal((T, B, D)).astype(np.float32)
+        old = [H.as_f32(t).copy() for t in ref_tables]
+        old_acc = [a.copy() for a in ref_acc]
+        ts, w_dev, acc_dev = H.make_tableset(ref_tables, dtype, accum_np=ref_acc)
+        g = H.gpu_backward(ts, rows, off, B, mode, dout, lr, eps)
+        r = oracle.bag_backward_rowwise_adagrad(ref_tables, ref_acc, dtype, rows, off, B, mode, dout, lr, eps)
+        assert g["status"] == r["status"] == 0
+        assert np.array_equal(g["unique_keys"], r["unique_keys"])          # bit-exact unique-row set
+        assert np.array_equal(g["unique_counts"], r["unique_counts"])
+        for t in range(T):
+            wg = H.as_f32(H.host_table(w_dev[t]))
+            ag = acc_dev[t].cpu().numpy()
+            sel = (r["unique_keys"] >= base[t]) & (r["unique_keys"] < base[t + 1])
+            touched = r["unique_keys"][sel] - base[t]
+            H.assert_rows_close(wg[touched], H.as_f32(ref_tables[t])[touched], old[t][touched], lr,
+                                H.EPS_BF16 if bf else H.EPS32, what="rows t=%d step=%d" % (t, step))
+            H.assert_accum_close(ag[touched], ref_acc[t][touched], r["Gabs"][sel], what="accum t=%d" % t)
+            assert np.all(ag[touched] >= old_acc[t][touched])              # accumulators are monotone
+            mask = np.ones(Rs[t], dtype=bool)
+            mask[touched] = False
+            assert np.array_equal(wg[mask], old[t][mask])                  # untouched rows bit-identical
+            assert np.array_equal(ag[mask], old_acc[t][mask])
+
+
+BWD_SHAPES = [(4, "f32"), (16, "f32"), (32, "f32"), (64, "f32"), (128, "f32"), (48, "f32"), (320, "f32"),
+              (2048, "f32"), (32, "bf16"), (64, "bf16"), (8, "bf16"), (1040, "bf16")]
+
+
+@pytest.mark.parametrize("D,dtype", BWD_SHAPES)
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_backward_matches_oracle(D, dtype, mode):
+    rng = np.random.default_rng(1000 + D + (dtype == "bf16") + 2 * (mode == "mean"))
+    big = D > 256
+    T, B = 3, (64 if big else 700)
+    Rs = [40, 5, 64] if big else [3000, 11, 20_000]
+    _backward_case(rng, T, B, D, Rs, 10 if big else 30, dtype, mode, steps=2)
+
+
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_backward_hot_rows_take_the_workgroup_path(mode):
+    # 30 % of all lookups hit row 0 of each table: segments of thousands of lookups
+    rng = np.random.default_rng(41)
+    _backward_case(rng, 2, 2000, 64, [50_000, 777], 25, "f32", mode, hot=0.3, steps=2)
+
+
+def test_backward_many_tiles_and_64_bit_keys():
+    # > 4096 * 8 lookups (several sort tiles, ragged tail); second case: key range past 2^32
+    rng = np.random.default_rng(42)
+    _backward_case(rng, 4, 3000, 32, [100_000, 9, 65_536, 1_000_003], 20, "f32", "mean")
+    # 64-bit keys: a fake huge first table that is never looked up shifts row_base past 2^32
+    D, B = 16, 500
+    tables, lengths, off, rows = H.random_case(rng, 1, B, D, [5000], 15, scale=0.01)
+    w = H.dev(tables[0])
+    acc = torch.zeros(5000, dtype=torch.float32, device=H.DEV)
+    dummy = torch.zeros((1, D), dtype=torch.float32, device=H.DEV)
+    dacc = torch.zeros(1, dtype=torch.float32, device=H.DEV)
+    big_rows = (1 << 32) + 12345
+    ts = emb.TableSet([(int(dummy.data_ptr()), big_rows), w], D, "f32", accum=None, device=torch.device(H.DEV))
+    ts.host["accum"][0] = int(dacc.data_ptr())
+    ts.host["accum"][1] = int(acc.data_ptr())
+    ts.dev = torch.from_numpy(ts.host.view(np.uint8).reshape(-1).copy()).to(H.DEV)
+    off2 = np.concatenate([np.zeros(B, dtype=np.int64), off])          # table 0 has B empty bags
+    dout = rng.standard_normal((2, B, D)).astype(np.float32)
+    g = H.gpu_backward(ts, rows, off2, B, "sum", dout, 0.01, 1e-8)
+    ref_t, ref_a = [tables[0].copy()], [np.zeros(5000, dtype=np.float32)]
+    r = oracle.bag_backward_rowwise_adagrad(ref_t, ref_a, "f32", rows, off, B, "sum", dout[1:], 0.01, 1e-8)
+    assert g["status"] == 0
+    assert np.array_equal(g["unique_keys"], r["unique_keys"] + big_rows)
+    assert np.array_equal(g["unique_counts"], r["unique_counts"])
+    touched = r["unique_keys"]
+    H.assert_rows_close(w.cpu().numpy()[touched], ref_t[0][touched], tables[0][touched], 0.01, what="64-bit keys")
+
+
+def test_backward_is_deterministic():
+    rng = np.random.default_rng(43)
+    T, B, D, Rs = 2, 1500, 64, [20_000, 300]
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, 30, scale=0.01, hot_row_frac=0.2)
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    results = []
+    for rep in range(3):
+        ts, w_dev, acc_dev = H.make_tableset(tables, "f32", with_accum=True)
+        H.gpu_backward(ts, rows, off, B, "mean", dout, 0.01, 1e-8)
+        results.append(([w.cpu().numpy() for w in w_dev], [a.cpu().numpy() for a in acc_dev]))
+    for rep in (1, 2):
+        for t in range(T):
+            assert np.array_equal(results[0][0][t], results[rep][0][t])
+            assert np.array_equal(results[0][1][t], results[rep][1][t])
+
+
+def test_backward_bad_indices_skipped_and_bad_offsets_abort():
+    rng = np.random.default_rng(44)
+    T, B, D, Rs = 2, 100, 32, [500, 40]
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, 10, scale=0.01)
+    rows = rows.copy()
+    rows[[1, 5, 9]] = [500, -2, 1 << 50]
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    ts, w_dev, acc_dev = H.make_tableset(tables, "f32", with_accum=True)
+    g = H.gpu_backward(ts, rows, off, B, "sum", dout, 0.01, 1e-8)
+    ref_t, ref_a = [t.copy() for t in tables], [np.zeros(R, np.float32) for R in Rs]
+    r = oracle.bag_backward_rowwise_adagrad(ref_t, ref_a, "f32", rows, off, B, "sum", dout, 0.01, 1e-8)
+    assert g["status"] == r["status"] == emb.STATUS_BAD_INDEX
+    assert np.array_equal(g["unique_keys"], r["unique_keys"]) and np.array_equal(g["unique_counts"], r["unique_counts"])
+    for t in range(T):
+        H.assert_rows_close(w_dev[t].cpu().numpy(), ref_t[t], tables[t], 0.01, what="bad idx rows")
+    # malformed offsets: nothing may change
+    for bad in (lambda o: o.__setitem__(0, 1), lambda o: o.__setitem__(-1, o[-1] - 1),
+                lambda o: o.__setitem__(50, o[51] + 2)):
+        off_b = off.copy()
+        bad(off_b)
+        ts, w_dev, acc_dev = H.make_tableset(tables, "f32", with_accum=True)
+        g = H.gpu_backward(ts, rows, off_b, B, "sum", dout, 0.01, 1e-8)
+        assert g["status"] & emb.STATUS_BAD_OFFSETS and g["U"] == 0
+        for t in range(T):
+            assert np.array_equal(w_dev[t].cpu().numpy(), tables[t])
+            assert np.all(acc_dev[t].cpu().numpy() == 0)
+
+
+def test_backward_empty_batch():
+    tables = [np.ones((10, 16), dtype=np.float32)]
+    ts, w_dev, acc_dev = H.make_tableset(tables, "f32", with_accum=True)
+    g = H.gpu_backward(ts, np.zeros(0, np.int64), np.zeros(5, np.int64), 4, "sum",
+                       np.ones((1, 4, 16), np.float32), 0.01, 1e-8)
+    assert g["U"] == 0 and g["status"] == 0 and np.all(w_dev[0].cpu().numpy() == 1)
+
+
+# ---------------------------------------------------------------------------
+# cached (hybrid) forward
+# ---------------------------------------------------------------------------
+def _cached_case(table_np, dtype, hot, rows, off, B, mode, table_ptr=None, keep=None):
+    R, D = table_np.shape
+    tdev = H.dev(table_np) if table_ptr is None else None
+    ptr = int(tdev.data_ptr()) if table_ptr is None else table_ptr
+    index = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+    cache = torch.empty((max(hot.size, 1), D), dtype=torch.float32 if dtype == "f32" else torch.bfloat16,
+                        device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_cache_build(ptr, R, D, dtype, H.dev(hot) if hot.size else torch.empty(0, dtype=torch.int64, device=H.DEV),
+                        cache, index, status)
+    out = torch.full((1, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    hm = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    emb.emb_bag_forward_cached(ptr, R, D, dtype, cache, index, hot.size, H.dev(rows), H.dev(off), B, mode, out, hm,
+                               status)
+    torch.cuda.synchronize()
+    ref, absum, (hits, misses), rst = oracle.bag_forward_cached(table_np, dtype, hot, rows, off, B, mode)
+    assert int(status.item()) == rst
+    assert hm.cpu().tolist() == [hits, misses]                     # bit-exact hit/miss counts
+    H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="cached forward")
+    if hot.size:                                                   # cached rows are byte copies
+        assert np.array_equal(H.host_table(cache[:hot.size]), table_np[hot])
+    return out.cpu().numpy()
+
+
+@pytest.mark.parametrize("D,dtype", [(64, "f32"), (32, "bf16"), (16, "f32"), (320, "f32")])
+def test_cached_forward_matches_oracle_and_plain_forward(D, dtype):
+    rng = np.random.default_rng(50 + D)
+    R, B = 10_007, 400
+    tables, lengths, off, rows = H.random_case(rng, 1, B, D, [R], 40, dtype, scale=0.01, hot_row_frac=0.1)
+    rows[:3] = [R - 1, 0, 63]
+    ts, _, _ = H.make_tableset(tables, dtype)
+    plain, _ = H.gpu_forward(ts, rows, off, B, "mean")
+    for hot in (np.zeros(0, np.int64), np.arange(R, dtype=np.int64),
+                np.sort(rng.permutation(R)[:R // 20]).astype(np.int64),
+                np.array([0, 63, 64, 127, 128, R - 1], dtype=np.int64)):
+        out = _cached_case(tables[0], dtype, hot, rows, off, B, "mean")
+        assert np.array_equal(out, plain)                          # the cache is numerically invisible
+
+
+def test_cached_forward_bad_hot_set_and_bad_index():
+    rng = np.random.default_rng(60)
+    R, D, B = 1000, 32, 50
+    tables, lengths, off, rows = H.random_case(rng, 1, B, D, [R], 10, scale=0.01)
+    rows = rows.copy()
+    rows[2] = R + 5
+    _cached_case(tables[0], "f32", np.arange(0, R, 3, dtype=np.int64), rows, off, B, "sum")
+    index = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+    cache = torch.empty((3, D), dtype=torch.float32, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    for hot in ([5, 5, 9], [9, 5, 20], [1, 2, R]):
+        status.zero_()
+        emb.emb_cache_build(int(H.dev(tables[0]).data_ptr()), R, D, "f32", H.dev(np.array(hot, np.int64)), cache,
+                            index, status)
+        torch.cuda.synchronize()
+        assert status.item() == emb.STATUS_BAD_HOT_SET
+
+
+def test_cached_forward_reads_misses_from_pinned_host_memory():
+    # the table lives in pinned (device-mapped) host memory; misses are read over PCIe
+    rng = np.random.default_rng(61)
+    R, D, B = 50_000, 64, 600
+    host = torch.empty((R, D), dtype=torch.float32, pin_memory=True)
+    ptr = emb.emb_host_device_pointer(int(host.data_ptr()))           # raises unless the memory is device-mapped
+    emb.emb_table_fill(ptr, R, D, "f32", 99)                          # the GPU writes the host table
+    torch.cuda.synchronize()
+    table_np = host.numpy()
+    assert np.array_equal(table_np[[0, 1, R - 1]], wl.table_values(99, np.array([0, 1, R - 1]), D))
+    lengths = rng.integers(0, 60, size=B).astype(np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    rows = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    hot = np.sort(rng.permutation(R)[:R // 20]).astype(np.int64)
+    _cached_case(table_np, "f32", hot, rows, off, B, "sum", table_ptr=ptr)
+
+
+# ---------------------------------------------------------------------------
+# procedural table fill
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_table_fill_matches_the_host_generator(dtype):
+    R, D = 70_001, 64
+    w = torch.empty((R, D), dtype=torch.float32 if dtype == "f32" else torch.bfloat16, device=H.DEV)
+    emb.emb_table_fill(w, R, D, dtype, 20250805123)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.host_table(w), wl.dense_table(20250805123, R, D, dtype))
