@@ -82,7 +82,7 @@ def main() -> int:
     batches_np = [wl.make_batch(w, i, seed) for i in range(args.batches)]
     dbs = [pipeline.DeviceBatch(w, b, dev) for b in batches_np]
     max_nnz = max(d.nnz for d in dbs)
-    buf = pipeline.StepBuffers(w, max_nnz, tabs.set.total_rows, dev, want_unique=w.backward)
+    buf = pipeline.StepBuffers(w, max_nnz, tabs.set.total_rows, dev)
     torch.cuda.synchronize()
     log("setup: %d tables x %d rows x %d %s, %d batches of ~%d lookups, %.1f s" % (
         w.T, w.R, w.D, w.dtype, len(dbs), max_nnz, time.time() - t_setup))

@@ -1,0 +1,35 @@
+// Constants and the device control block shared by the stages of the backward.
+#pragma once
+#include "emb_internal.h"
+
+struct BwdCtrl {
+    uint32_t abort;        // offsets are not a partition of [0, nnz): do nothing
+    uint32_t long_count;   // entries in the long-segment list
+    uint32_t n_valid;      // records whose key is not the sentinel
+    uint32_t num_unique;   // U
+    uint32_t chunk_count;  // chunk tasks created for long segments
+    uint32_t pad[59];
+};
+static_assert(sizeof(BwdCtrl) == 256, "control block is one 256-byte line");
+
+constexpr int RADIX_BITS = 8;
+constexpr int RADIX = 1 << RADIX_BITS;
+constexpr int MAX_PASSES = 8;
+constexpr int SORT_BLOCK = 256;
+constexpr int SORT_WAVES = SORT_BLOCK / EMB_WAVE;
+constexpr int SORT_ITEMS = 16;
+constexpr int SORT_TILE = SORT_BLOCK * SORT_ITEMS;  // 4096 records per workgroup
+constexpr int TOTAL_SLOTS = 32;                     // digit totals are spread over this many slots per digit
+constexpr int SORT_PAD = 32;                        // records of slack after the key / payload arrays
+
+constexpr int UPD_BLOCK = 256;
+constexpr int UPD_EPG = 32;         // sorted records per lane group in the update
+constexpr int LONG_SEGMENT = 128;   // lookups of one row above which workgroups sum them
+constexpr int LONG_CHUNK = 2048;    // records of a long segment summed by one workgroup
+constexpr int UPD_LDS_TABLES = 512; // table directories up to this size are staged in LDS
+
+struct LongSeg {
+    uint32_t lo, hi;       // records [lo, hi) of the sorted arrays
+    uint32_t chunk_base;   // first partial-sum slot
+    uint32_t n_chunks;
+};

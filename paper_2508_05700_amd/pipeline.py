@@ -60,12 +60,12 @@ class StepBuffers:
         self.workspace = None
         self.unique_keys = self.unique_counts = self.num_unique = None
         if w.backward:
-            nbytes = emb.emb_bag_backward_workspace_bytes(w.T, w.B, n, total_rows)
+            nbytes = emb.emb_bag_backward_workspace_bytes(w.T, w.B, n, total_rows, w.D)
             self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
-            if want_unique:
+            self.num_unique = torch.zeros(1, dtype=torch.int64, device=device)
+            if want_unique:   # the ordered list of distinct rows is optional output
                 self.unique_keys = torch.empty(n, dtype=torch.int64, device=device)
                 self.unique_counts = torch.empty(n, dtype=torch.int32, device=device)
-                self.num_unique = torch.zeros(1, dtype=torch.int64, device=device)
 
 
 def run_index_stage(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:
