@@ -117,10 +117,10 @@ int emb_bag_forward(const emb_table *tables_host, const emb_table *tables_dev, i
                     float *out_dev, uint32_t *status_dev, void *stream);
 
 /* Bytes of device workspace emb_bag_backward_rowwise_adagrad needs for a
- * batch of T*B bags and nnz lookups over tables of dimension D with
- * `total_rows` rows in all.  Returns 0 on invalid arguments. */
+ * batch of T*B bags and nnz lookups over tables of dimension D and storage
+ * type dtype with `total_rows` rows in all.  Returns 0 on invalid arguments. */
 size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t nnz, int64_t total_rows,
-                                        int32_t D);
+                                        int32_t D, int32_t dtype);
 
 /* Exact sparse backward of emb_bag_forward followed by one row-wise Adagrad
  * step (fine-tuning of table rows, Section 3.1; Adagrad of Duchi, Hazan,

@@ -73,7 +73,7 @@ def lib() -> C.CDLL:
     L.emb_bag_forward.restype = C.c_int
     L.emb_bag_forward.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp]
     L.emb_bag_backward_workspace_bytes.restype = sz
-    L.emb_bag_backward_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
+    L.emb_bag_backward_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32]
     L.emb_bag_backward_rowwise_adagrad.restype = C.c_int
     L.emb_bag_backward_rowwise_adagrad.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, f32, f32,
                                                    vp, sz, vp, vp, vp, vp, vp]
@@ -206,8 +206,9 @@ def emb_bag_forward(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor,
         _ptr(out, torch.float32, "out"), _ptr(status, torch.int32, "status"), _stream()))
 
 
-def emb_bag_backward_workspace_bytes(T: int, B: int, nnz: int, total_rows: int, D: int) -> int:
-    return int(lib().emb_bag_backward_workspace_bytes(int(T), int(B), int(nnz), int(total_rows), int(D)))
+def emb_bag_backward_workspace_bytes(T: int, B: int, nnz: int, total_rows: int, D: int, dtype: str) -> int:
+    return int(lib().emb_bag_backward_workspace_bytes(int(T), int(B), int(nnz), int(total_rows), int(D),
+                                                      DTYPE[dtype]))
 
 
 def emb_bag_backward_rowwise_adagrad(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,

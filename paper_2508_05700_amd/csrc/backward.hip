@@ -8,7 +8,7 @@
 //            only as many passes as the key range needs          (radix_sort.h)
 //   update   runs of equal keys are found on the fly; each run's gradients are
 //            summed in ascending record order and Adagrad is applied once to
-//            its row; very long runs are summed by whole workgroups (update.h)
+//            its row; long runs are cut into chunks summed by wavefronts (update.h)
 //   runs     only when the caller asks for the list of distinct rows: head
 //            flags, scan and compaction into unique keys and counts
 // The payload carried through the sort is the bag number: lookups of one row
@@ -27,18 +27,34 @@ namespace {
 // workspace
 // ---------------------------------------------------------------------------
 struct BwdLayout {
-    size_t ctrl, totals, keys_a, keys_b, pay_a, pay_b, bag_scale, hist, tile_heads, seg_start, long_list, segs,
+    size_t ctrl, totals, keys_a, keys_b, pay_a, pay_b, bag_scale, hist, tile_heads, seg_start, queue, wave_heads, segs,
         seg_done, chunk_tasks, partials, total;
     int key_bytes;
     int passes;
+    int lpr, cpl;       // lanes per row and chunks per lane of the update kernels
     int64_t tiles;
-    int64_t long_cap;
+    int64_t slots;      // lane groups (= queue slots) of the short-run kernel
+    int64_t upd_blocks; // its grid
     int64_t chunk_cap;
+    int64_t partial_cap;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_rows, int32_t D)
+// Lanes per row / chunks per lane for the update: as few lanes as keep at least
+// 64 contiguous bytes per row and load instruction, up to 4 chunks per lane.
+inline void upd_row_split(int chunks, int &lpr, int &cpl)
+{
+    int want = (chunks + 3) / 4;
+    if (want < 4) want = chunks < 4 ? chunks : 4;
+    lpr = 1;
+    while (lpr < want && lpr < 64) lpr <<= 1;
+    int need = (chunks + lpr - 1) / lpr;
+    cpl = 1;
+    while (cpl < need) cpl <<= 1;
+}
+
+inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_rows, int32_t D, int32_t dtype)
 {
     BwdLayout L;
     L.key_bytes = ((uint64_t)total_rows < 0xFFFFFFFFull) ? 4 : 8;
@@ -48,8 +64,16 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     if (L.passes < 1) L.passes = 1;
     L.tiles = (nnz + SORT_TILE - 1) / SORT_TILE;
     if (L.tiles < 1) L.tiles = 1;
-    L.long_cap = nnz / LONG_SEGMENT + 1;
-    L.chunk_cap = nnz / LONG_CHUNK + L.long_cap;
+    const int esz = dtype == EMB_BF16 ? 2 : 4;
+    upd_row_split((int)(((int64_t)D * esz + 15) / 16), L.lpr, L.cpl);
+    L.slots = (nnz + UPD_EPG - 1) / UPD_EPG;
+    if (L.slots < 1) L.slots = 1;
+    const int64_t groups = UPD_BLOCK / L.lpr;
+    L.upd_blocks = (L.slots + groups - 1) / groups;
+    // a queued run is longer than UPD_EPG records, so there are at most nnz/UPD_EPG of them
+    L.chunk_cap = nnz / LONG_CHUNK + nnz / UPD_EPG + 2;
+    // chunk sums are stored only for runs longer than LONG_CHUNK: at most 2*len/LONG_CHUNK slots each
+    L.partial_cap = nnz / (LONG_CHUNK / 2) + 2;
     const size_t n = (size_t)(nnz > 0 ? nnz : 1);
     const size_t np = n + SORT_PAD;
     size_t off = 0;
@@ -63,11 +87,12 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     L.hist = off;        off += align256((size_t)L.tiles * RADIX * 4);
     L.tile_heads = off;  off += align256((size_t)L.tiles * 4);
     L.seg_start = off;   off += align256((n + 1) * 4);
-    L.long_list = off;   off += align256((size_t)L.long_cap * 4);
-    L.segs = off;        off += align256((size_t)L.long_cap * sizeof(LongSeg));
-    L.seg_done = off;    off += align256((size_t)L.long_cap * 4);
+    L.queue = off;       off += align256((size_t)L.slots * 4);
+    L.wave_heads = off;  off += align256((size_t)L.upd_blocks * (UPD_BLOCK / EMB_WAVE) * 4);
+    L.segs = off;        off += align256((size_t)L.slots * sizeof(LongSeg));
+    L.seg_done = off;    off += align256((size_t)L.slots * 4);
     L.chunk_tasks = off; off += align256((size_t)L.chunk_cap * sizeof(uint2));
-    L.partials = off;    off += align256((size_t)L.chunk_cap * (size_t)D * 4);
+    L.partials = off;    off += align256((size_t)L.partial_cap * (size_t)D * 4);
     L.total = off;
     return L;
 }
@@ -249,38 +274,42 @@ struct BwdArgs {
     hipStream_t stream;
 };
 
-template <typename KeyT, int LPR, int CPL, int NB, int UNROLL, bool BF16>
+template <typename KeyT, int LPR, int CPL, int EU, bool BF16>
 int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const uint32_t *pay, int chunks)
 {
     BwdCtrl *ctrl = reinterpret_cast<BwdCtrl *>(a.ws + L.ctrl);
     float *bag_scale = reinterpret_cast<float *>(a.ws + L.bag_scale);
-    uint32_t *long_list = reinterpret_cast<uint32_t *>(a.ws + L.long_list);
+    uint32_t *queue = reinterpret_cast<uint32_t *>(a.ws + L.queue);
+    uint32_t *wave_heads = reinterpret_cast<uint32_t *>(a.ws + L.wave_heads);
     LongSeg *segs = reinterpret_cast<LongSeg *>(a.ws + L.segs);
     uint32_t *seg_done = reinterpret_cast<uint32_t *>(a.ws + L.seg_done);
     uint2 *chunk_tasks = reinterpret_cast<uint2 *>(a.ws + L.chunk_tasks);
     float *partials = reinterpret_cast<float *>(a.ws + L.partials);
     const uint32_t n = (uint32_t)a.nnz;
     const KeyT sentinel = (KeyT)a.total_rows;
+    const float inv_D = 1.0f / (float)a.D;
+    BagDiv bdiv;
+    bdiv.B = (uint32_t)a.B;
+    bdiv.magic = 0xFFFFFFFFu / (uint32_t)a.B;
 
-    constexpr int GROUPS = UPD_BLOCK / LPR;
-    const int64_t per_block = (int64_t)GROUPS * UPD_EPG;
-    const unsigned grid = (unsigned)((a.nnz + per_block - 1) / per_block);
-    hipLaunchKernelGGL((update_kernel<KeyT, LPR, CPL, NB, BF16>), dim3(grid), dim3(UPD_BLOCK), 0, a.stream,
-                       a.tables_dev, a.T, keys, pay, n, sentinel, bag_scale, a.dout, chunks, a.D, a.lr, a.eps, ctrl,
-                       long_list, (uint32_t)L.long_cap);
+    hipLaunchKernelGGL((update_kernel<KeyT, LPR, CPL, EU, BF16>), dim3((unsigned)L.upd_blocks), dim3(UPD_BLOCK), 0,
+                       a.stream, a.tables_dev, a.T, keys, pay, n, sentinel, bag_scale, a.dout, chunks, a.D, inv_D, a.lr,
+                       a.eps, bdiv, ctrl, queue, wave_heads);
     EMB_RETURN_IF_LAUNCH_FAILED();
 
-    const unsigned pgrid = (unsigned)((L.long_cap + 255) / 256);
-    hipLaunchKernelGGL(long_prepare_kernel<KeyT>, dim3(pgrid), dim3(256), 0, a.stream, keys, n, ctrl, long_list,
-                       (uint32_t)L.long_cap, segs, seg_done, chunk_tasks, (uint32_t)L.chunk_cap);
+    const int64_t n_wave_heads = L.upd_blocks * (UPD_BLOCK / EMB_WAVE);
+    const int64_t pthreads = L.slots > n_wave_heads ? L.slots : n_wave_heads;
+    hipLaunchKernelGGL(long_prepare_kernel<KeyT>, dim3((unsigned)((pthreads + 255) / 256)), dim3(256), 0, a.stream,
+                       keys, n, ctrl, queue, (uint32_t)L.slots, wave_heads, (uint32_t)n_wave_heads, segs, seg_done,
+                       chunk_tasks, (uint32_t)L.chunk_cap, (uint32_t)L.partial_cap);
     EMB_RETURN_IF_LAUNCH_FAILED();
 
-    // wide rows keep many accumulators per lane: use a smaller workgroup so they stay in registers
-    constexpr int LBLOCK = CPL <= 2 ? 1024 : 256;
-    const unsigned lgrid = (unsigned)(L.chunk_cap < 2048 ? L.chunk_cap : 2048);
-    hipLaunchKernelGGL((long_reduce_kernel<KeyT, LPR, CPL, UNROLL, BF16, LBLOCK>), dim3(lgrid), dim3(LBLOCK), 0,
-                       a.stream, a.tables_dev, a.T, keys, pay, bag_scale, a.dout, chunks, a.D, a.lr, a.eps, ctrl, segs,
-                       seg_done, chunk_tasks, (uint32_t)L.chunk_cap, partials, a.num_unique_out);
+    // one wavefront per task; enough workgroups to fill the chip, tasks beyond that are strided over
+    int64_t want = (L.chunk_cap + (UPD_BLOCK / EMB_WAVE) - 1) / (UPD_BLOCK / EMB_WAVE);
+    const unsigned lgrid = (unsigned)(want < 4096 ? want : 4096);
+    hipLaunchKernelGGL((long_reduce_kernel<KeyT, LPR, CPL, EU, BF16>), dim3(lgrid), dim3(UPD_BLOCK), 0, a.stream,
+                       a.tables_dev, a.T, keys, pay, bag_scale, a.dout, chunks, a.D, inv_D, a.lr, a.eps, bdiv, ctrl,
+                       segs, seg_done, chunk_tasks, (uint32_t)L.chunk_cap, partials, a.num_unique_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -355,38 +384,35 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
     }
 
     const int chunks = a.D * emb_elem_size(a.dtype) / 16;
-    int lpr, cpl;
-    emb_row_split(chunks, lpr, cpl);
     const bool bf16 = a.dtype == EMB_BF16;
-#define EMB_UPD(LL, C, NB, U)                                                                     \
-    return bf16 ? launch_update<KeyT, LL, C, NB, U, true>(a, L, kin, pin, chunks)                 \
-                : launch_update<KeyT, LL, C, NB, U, false>(a, L, kin, pin, chunks)
-    if (cpl == 1) {
-        switch (lpr) {
-            case 1: EMB_UPD(1, 1, 8, 8);
-            case 2: EMB_UPD(2, 1, 8, 8);
-            case 4: EMB_UPD(4, 1, 8, 8);
-            case 8: EMB_UPD(8, 1, 8, 8);
-            case 16: EMB_UPD(16, 1, 8, 8);
-            case 32: EMB_UPD(32, 1, 8, 8);
-            default: EMB_UPD(64, 1, 8, 8);
-        }
-    }
-    switch (cpl) {
-        case 2: EMB_UPD(64, 2, 4, 4);
-        case 4: EMB_UPD(64, 4, 2, 2);
-        case 8: EMB_UPD(64, 8, 1, 1);
-        default: EMB_UPD(64, 16, 1, 1);
+#define EMB_UPD(LL, C, EU)                                                                   \
+    return bf16 ? launch_update<KeyT, LL, C, EU, true>(a, L, kin, pin, chunks)               \
+                : launch_update<KeyT, LL, C, EU, false>(a, L, kin, pin, chunks)
+    switch (L.lpr * 100 + L.cpl) {
+        case 101: EMB_UPD(1, 1, 4);
+        case 201: EMB_UPD(2, 1, 4);
+        case 401: EMB_UPD(4, 1, 4);
+        case 402: EMB_UPD(4, 2, 4);
+        case 404: EMB_UPD(4, 4, 2);
+        case 804: EMB_UPD(8, 4, 2);
+        case 1604: EMB_UPD(16, 4, 2);
+        case 3204: EMB_UPD(32, 4, 2);
+        case 6404: EMB_UPD(64, 4, 2);
+        case 6408: EMB_UPD(64, 8, 1);
+        case 6416: EMB_UPD(64, 16, 1);
+        default: return EMB_ERR_UNSUPPORTED;
     }
 #undef EMB_UPD
 }
 
 }  // namespace
 
-extern "C" size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t nnz, int64_t total_rows, int32_t D)
+extern "C" size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t nnz, int64_t total_rows, int32_t D,
+                                                   int32_t dtype)
 {
-    if (T < 0 || B < 0 || nnz < 0 || total_rows < 0 || D <= 0) return 0;
-    return bwd_layout(T, B, nnz, total_rows, D).total;
+    if (T < 0 || B < 0 || nnz < 0 || total_rows < 0) return 0;
+    if (emb_check_row_shape(D, dtype) != EMB_OK) return 0;
+    return bwd_layout(T, B, nnz, total_rows, D, dtype).total;
 }
 
 extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
@@ -413,7 +439,7 @@ extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, co
 
     int64_t total_rows = 0;
     for (int32_t t = 0; t < T; ++t) total_rows += tables_host[t].num_rows;
-    const BwdLayout L = bwd_layout(T, B, nnz, total_rows, D);
+    const BwdLayout L = bwd_layout(T, B, nnz, total_rows, D, dtype);
     if (!workspace_dev || !emb_aligned(workspace_dev, 256) || workspace_bytes < L.total) return EMB_ERR_WORKSPACE;
     if (L.passes > MAX_PASSES) return EMB_ERR_UNSUPPORTED;
 

@@ -7,8 +7,9 @@ struct BwdCtrl {
     uint32_t long_count;   // entries in the long-segment list
     uint32_t n_valid;      // records whose key is not the sentinel
     uint32_t num_unique;   // U
-    uint32_t chunk_count;  // chunk tasks created for long segments
-    uint32_t pad[59];
+    uint32_t chunk_count;  // chunk tasks created for queued runs
+    uint32_t partial_count;  // chunk-sum slots handed out
+    uint32_t pad[58];
 };
 static_assert(sizeof(BwdCtrl) == 256, "control block is one 256-byte line");
 
@@ -20,16 +21,15 @@ constexpr int SORT_WAVES = SORT_BLOCK / EMB_WAVE;
 constexpr int SORT_ITEMS = 16;
 constexpr int SORT_TILE = SORT_BLOCK * SORT_ITEMS;  // 4096 records per workgroup
 constexpr int TOTAL_SLOTS = 32;                     // digit totals are spread over this many slots per digit
-constexpr int SORT_PAD = 32;                        // records of slack after the key / payload arrays
+constexpr int SORT_PAD = 64;                        // records of slack after the key / payload arrays
 
 constexpr int UPD_BLOCK = 256;
-constexpr int UPD_EPG = 32;         // sorted records per lane group in the update
-constexpr int LONG_SEGMENT = 128;   // lookups of one row above which workgroups sum them
-constexpr int LONG_CHUNK = 2048;    // records of a long segment summed by one workgroup
+constexpr int UPD_EPG = 16;         // sorted records per lane group in the update (and as many of look-ahead)
+constexpr int LONG_CHUNK = 256;     // records of a queued run summed by one wavefront
 constexpr int UPD_LDS_TABLES = 512; // table directories up to this size are staged in LDS
 
 struct LongSeg {
     uint32_t lo, hi;       // records [lo, hi) of the sorted arrays
-    uint32_t chunk_base;   // first partial-sum slot
+    uint32_t chunk_base;   // first chunk-sum slot (runs of several chunks)
     uint32_t n_chunks;
 };

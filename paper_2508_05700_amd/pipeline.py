@@ -60,7 +60,7 @@ class StepBuffers:
         self.workspace = None
         self.unique_keys = self.unique_counts = self.num_unique = None
         if w.backward:
-            nbytes = emb.emb_bag_backward_workspace_bytes(w.T, w.B, n, total_rows, w.D)
+            nbytes = emb.emb_bag_backward_workspace_bytes(w.T, w.B, n, total_rows, w.D, w.dtype)
             self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
             self.num_unique = torch.zeros(1, dtype=torch.int64, device=device)
             if want_unique:   # the ordered list of distinct rows is optional output

@@ -113,7 +113,7 @@ def gpu_forward(ts, rows_np, off_np, B, mode):
 
 def gpu_backward(ts, rows_np, off_np, B, mode, dout_np, lr, eps):
     nnz = rows_np.size
-    ws = torch.empty(emb.emb_bag_backward_workspace_bytes(ts.T, B, nnz, ts.total_rows, ts.D), dtype=torch.uint8, device=DEV)
+    ws = torch.empty(emb.emb_bag_backward_workspace_bytes(ts.T, B, nnz, ts.total_rows, ts.D, ts.dtype), dtype=torch.uint8, device=DEV)
     uk = torch.full((max(nnz, 1),), -7, dtype=torch.int64, device=DEV)
     uc = torch.full((max(nnz, 1),), -7, dtype=torch.int32, device=DEV)
     nu = torch.full((1,), -7, dtype=torch.int64, device=DEV)

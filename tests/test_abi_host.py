@@ -108,7 +108,7 @@ def test_forward_argument_errors(L):
 
 def test_backward_argument_errors(L):
     d = _tables()
-    need = L.emb_bag_backward_workspace_bytes(2, 4, 8, 1007, 64)
+    need = L.emb_bag_backward_workspace_bytes(2, 4, 8, 1007, 64, 0)
     assert need > 0 and need % 256 == 0
     f = L.emb_bag_backward_rowwise_adagrad
 
@@ -129,11 +129,12 @@ def test_backward_argument_errors(L):
 
 def test_workspace_bytes(L):
     w = L.emb_bag_backward_workspace_bytes
-    assert w(-1, 1, 1, 1, 64) == 0 and w(1, -1, 1, 1, 64) == 0 and w(1, 1, -1, 1, 64) == 0 and w(1, 1, 1, 1, 0) == 0
-    a, c = w(16, 8192, 1_000_000, 160_000_000, 64), w(16, 8192, 2_000_000, 160_000_000, 64)
+    assert w(-1, 1, 1, 1, 64, 0) == 0 and w(1, -1, 1, 1, 64, 0) == 0 and w(1, 1, -1, 1, 64, 0) == 0
+    assert w(1, 1, 1, 1, 0, 0) == 0 and w(1, 1, 1, 1, 3, 0) == 0 and w(1, 1, 1, 1, 64, 9) == 0
+    a, c = w(16, 8192, 1_000_000, 160_000_000, 64, 0), w(16, 8192, 2_000_000, 160_000_000, 64, 0)
     assert 0 < a < c
     # keys widen to 64 bits once the key range passes 2^32
-    assert w(1, 8, 1_000_000, 1 << 33, 64) > w(1, 8, 1_000_000, 1 << 30, 64) + 7_000_000
+    assert w(1, 8, 1_000_000, 1 << 33, 64, 0) > w(1, 8, 1_000_000, 1 << 30, 64, 0) + 7_000_000
 
 
 def test_cache_argument_errors(L):
