@@ -28,12 +28,13 @@ namespace {
 // ---------------------------------------------------------------------------
 struct BwdLayout {
     size_t ctrl, totals, keys_a, keys_b, pay_a, pay_b, bag_scale, hist, tile_heads, seg_start, queue, wave_heads, segs,
-        seg_done, chunk_tasks, partials, total;
+        multi_list, chunk_tasks, partials, total;
     int key_bytes;
     int passes;
     int lpr, cpl;       // lanes per row and chunks per lane of the update kernels
     int64_t tiles;
-    int64_t slots;      // lane groups (= queue slots) of the short-run kernel
+    int64_t slots;      // wavefronts of the short-run kernel
+    int64_t qslots;     // queue slots
     int64_t upd_blocks; // its grid
     int64_t chunk_cap;
     int64_t partial_cap;
@@ -66,12 +67,13 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     if (L.tiles < 1) L.tiles = 1;
     const int esz = dtype == EMB_BF16 ? 2 : 4;
     upd_row_split((int)(((int64_t)D * esz + 15) / 16), L.lpr, L.cpl);
-    L.slots = (nnz + UPD_EPG - 1) / UPD_EPG;
+    L.slots = (nnz + UPD_SPAN - 1) / UPD_SPAN;
     if (L.slots < 1) L.slots = 1;
-    const int64_t groups = UPD_BLOCK / L.lpr;
-    L.upd_blocks = (L.slots + groups - 1) / groups;
-    // a queued run is longer than UPD_EPG records, so there are at most nnz/UPD_EPG of them
-    L.chunk_cap = nnz / LONG_CHUNK + nnz / UPD_EPG + 2;
+    const int64_t waves = UPD_BLOCK / EMB_WAVE;
+    L.upd_blocks = (L.slots + waves - 1) / waves;
+    L.qslots = L.slots * UPD_QSLOTS;
+    // every queued run has at least one chunk
+    L.chunk_cap = nnz / LONG_CHUNK + L.qslots + 2;
     // chunk sums are stored only for runs longer than LONG_CHUNK: at most 2*len/LONG_CHUNK slots each
     L.partial_cap = nnz / (LONG_CHUNK / 2) + 2;
     const size_t n = (size_t)(nnz > 0 ? nnz : 1);
@@ -87,10 +89,10 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     L.hist = off;        off += align256((size_t)L.tiles * RADIX * 4);
     L.tile_heads = off;  off += align256((size_t)L.tiles * 4);
     L.seg_start = off;   off += align256((n + 1) * 4);
-    L.queue = off;       off += align256((size_t)L.slots * 4);
+    L.queue = off;       off += align256((size_t)L.qslots * 4);
     L.wave_heads = off;  off += align256((size_t)L.upd_blocks * (UPD_BLOCK / EMB_WAVE) * 4);
-    L.segs = off;        off += align256((size_t)L.slots * sizeof(LongSeg));
-    L.seg_done = off;    off += align256((size_t)L.slots * 4);
+    L.segs = off;        off += align256((size_t)L.qslots * sizeof(LongSeg));
+    L.multi_list = off;  off += align256((size_t)L.qslots * 4);
     L.chunk_tasks = off; off += align256((size_t)L.chunk_cap * sizeof(uint2));
     L.partials = off;    off += align256((size_t)L.partial_cap * (size_t)D * 4);
     L.total = off;
@@ -282,7 +284,7 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     uint32_t *queue = reinterpret_cast<uint32_t *>(a.ws + L.queue);
     uint32_t *wave_heads = reinterpret_cast<uint32_t *>(a.ws + L.wave_heads);
     LongSeg *segs = reinterpret_cast<LongSeg *>(a.ws + L.segs);
-    uint32_t *seg_done = reinterpret_cast<uint32_t *>(a.ws + L.seg_done);
+    uint32_t *multi_list = reinterpret_cast<uint32_t *>(a.ws + L.multi_list);
     uint2 *chunk_tasks = reinterpret_cast<uint2 *>(a.ws + L.chunk_tasks);
     float *partials = reinterpret_cast<float *>(a.ws + L.partials);
     const uint32_t n = (uint32_t)a.nnz;
@@ -298,9 +300,9 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     EMB_RETURN_IF_LAUNCH_FAILED();
 
     const int64_t n_wave_heads = L.upd_blocks * (UPD_BLOCK / EMB_WAVE);
-    const int64_t pthreads = L.slots > n_wave_heads ? L.slots : n_wave_heads;
+    const int64_t pthreads = L.qslots > n_wave_heads ? L.qslots : n_wave_heads;
     hipLaunchKernelGGL(long_prepare_kernel<KeyT>, dim3((unsigned)((pthreads + 255) / 256)), dim3(256), 0, a.stream,
-                       keys, n, ctrl, queue, (uint32_t)L.slots, wave_heads, (uint32_t)n_wave_heads, segs, seg_done,
+                       keys, n, ctrl, queue, (uint32_t)L.qslots, wave_heads, (uint32_t)n_wave_heads, segs, multi_list,
                        chunk_tasks, (uint32_t)L.chunk_cap, (uint32_t)L.partial_cap);
     EMB_RETURN_IF_LAUNCH_FAILED();
 
@@ -309,7 +311,17 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     const unsigned lgrid = (unsigned)(want < 4096 ? want : 4096);
     hipLaunchKernelGGL((long_reduce_kernel<KeyT, LPR, CPL, EU, BF16>), dim3(lgrid), dim3(UPD_BLOCK), 0, a.stream,
                        a.tables_dev, a.T, keys, pay, bag_scale, a.dout, chunks, a.D, inv_D, a.lr, a.eps, bdiv, ctrl,
-                       segs, seg_done, chunk_tasks, (uint32_t)L.chunk_cap, partials, a.num_unique_out);
+                       segs, chunk_tasks, (uint32_t)L.chunk_cap, partials);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+
+    // runs of several chunks: at most nnz / LONG_CHUNK of them
+    const int64_t multi_max = a.nnz / LONG_CHUNK + 1;
+    constexpr int GROUPS = UPD_BLOCK / LPR;
+    int64_t cwant = (multi_max + GROUPS - 1) / GROUPS;
+    const unsigned cgrid = (unsigned)(cwant < 1024 ? cwant : 1024);
+    hipLaunchKernelGGL((long_combine_kernel<KeyT, LPR, CPL, BF16>), dim3(cgrid), dim3(UPD_BLOCK), 0, a.stream,
+                       a.tables_dev, a.T, keys, pay, chunks, inv_D, a.lr, a.eps, bdiv, ctrl, segs, multi_list,
+                       (uint32_t)L.qslots, partials, a.num_unique_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }

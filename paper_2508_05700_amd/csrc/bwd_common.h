@@ -9,7 +9,8 @@ struct BwdCtrl {
     uint32_t num_unique;   // U
     uint32_t chunk_count;  // chunk tasks created for queued runs
     uint32_t partial_count;  // chunk-sum slots handed out
-    uint32_t pad[58];
+    uint32_t multi_count;    // queued runs of several chunks
+    uint32_t pad[57];
 };
 static_assert(sizeof(BwdCtrl) == 256, "control block is one 256-byte line");
 
@@ -21,10 +22,13 @@ constexpr int SORT_WAVES = SORT_BLOCK / EMB_WAVE;
 constexpr int SORT_ITEMS = 16;
 constexpr int SORT_TILE = SORT_BLOCK * SORT_ITEMS;  // 4096 records per workgroup
 constexpr int TOTAL_SLOTS = 32;                     // digit totals are spread over this many slots per digit
-constexpr int SORT_PAD = 64;                        // records of slack after the key / payload arrays
+constexpr int SORT_PAD = 320;                       // records of slack after the key / payload arrays
 
 constexpr int UPD_BLOCK = 256;
-constexpr int UPD_EPG = 16;         // sorted records per lane group in the update (and as many of look-ahead)
+constexpr int UPD_SPAN = 256;        // sorted records per wavefront in the update
+constexpr int UPD_LOOK = 32;         // records of look-ahead after a span
+constexpr int UPD_SHORT_MAX = 32;    // longest run the short-run kernel sums itself
+constexpr int UPD_QSLOTS = UPD_SPAN / (UPD_SHORT_MAX + 1) + 1;  // runs longer than that which can start in one span
 constexpr int LONG_CHUNK = 256;     // records of a queued run summed by one wavefront
 constexpr int UPD_LDS_TABLES = 512; // table directories up to this size are staged in LDS
 

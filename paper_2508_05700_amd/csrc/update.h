@@ -9,26 +9,30 @@
 // 64-wide wavefronts on 16-lane SIMDs that instruction count, not HBM, was the
 // limit of a 16-lanes-per-row mapping.
 //
-// Short runs.  Each lane group takes UPD_EPG consecutive sorted records and
-// owns every run of equal keys that starts in that range.  It stages the keys
-// and bags of its range and of the UPD_EPG records after it in LDS, derives
-// bit masks of run heads, and then handles its runs one after the other: the
-// row, its accumulator and the first gradient rows are requested together,
-// the remaining gradient rows EU at a time, the sum is taken in ascending
-// record order and Adagrad is applied once.  All groups of a wavefront go
-// through the same loop, so the code is convergent.  A run that is not over
-// after the look-ahead is not touched; its first record is written to the
-// group's queue slot (one slot per group: only the last run of a range can
-// overflow), so there are no atomics and no ordering effects.
+// Short runs.  Each wavefront takes UPD_SPAN consecutive sorted records and
+// owns every run of equal keys that starts in that span.  It stages the keys
+// and bags of the span and of UPD_LOOK records after it in LDS, compacts the
+// positions where the key changes into a list of runs, and deals the runs to
+// its lane groups round-robin, so every group has the same number of runs to
+// do.  For a run the row, its accumulator and the first gradient rows are
+// requested together, the remaining gradient rows EU at a
+// time; the sum is taken in ascending record order and Adagrad is applied
+// once.  All groups go through the same loop, so the code is convergent.  A
+// run longer than UPD_SHORT_MAX records, or not over after the look-ahead, is
+// not touched; its first record goes to one of the wavefront's UPD_QSLOTS queue
+// slots (no more such runs can start in one span).  Which slot is a matter of
+// timing, but queued runs are independent of each other, so values are not.
 //
 // Queued runs.  A second kernel finds the end of every queued run (galloping
 // then bisecting in the sorted keys), cuts it into LONG_CHUNK-record chunks and
 // makes one task per chunk.  A third kernel gives each task to one wavefront,
 // whose lane groups take the chunk's records round-robin and are then combined
-// by a fixed butterfly; runs of several chunks store their chunk sums, and the
-// wavefront that completes a run's last chunk adds them in chunk order and
-// applies Adagrad.  All sums are taken in a fixed order: results are
-// bit-identical from run to run.
+// by a fixed butterfly; a run of one chunk is finished there, runs of several
+// chunks store their chunk sums and a last small kernel adds them in chunk
+// order and applies Adagrad.  (The kernel boundary is what makes the chunk sums
+// visible: a device-wide fence inside a kernel writes back the whole L2 of the
+// issuing XCD, dirty table rows included, and was far more expensive.)  All
+// sums are taken in a fixed order: results are bit-identical from run to run.
 #pragma once
 #include "bwd_common.h"
 #include "gather.h"
@@ -232,7 +236,7 @@ __device__ __forceinline__ void load_records(const E *__restrict__ p, E (&out)[N
 }
 
 // ---------------------------------------------------------------------------
-// short runs: one lane group per range of UPD_EPG sorted records
+// short runs: one wavefront per span of UPD_SPAN sorted records
 // ---------------------------------------------------------------------------
 template <typename KeyT, int LPR, int CPL, int EU, bool BF16>
 __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__restrict__ tables, int32_t T,
@@ -245,77 +249,117 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
                                                            uint32_t *__restrict__ wave_heads)
 {
     if (ctrl->abort) return;
-    constexpr int GROUPS = UPD_BLOCK / LPR;
-    constexpr int WIN = 2 * UPD_EPG;                      // records staged per group
-    constexpr int STAGERS = LPR < WIN ? LPR : WIN;        // lanes of a group that stage records
-    constexpr int PER = WIN / STAGERS;                    // records staged per such lane
+    constexpr int WAVES = UPD_BLOCK / EMB_WAVE;
+    constexpr int GPW = EMB_WAVE / LPR;            // lane groups per wavefront
+    constexpr int WIN = UPD_SPAN + UPD_LOOK;       // records staged per wavefront
     constexpr int F = GradAcc<BF16>::F;
     constexpr int V = GradAcc<BF16>::V;
-    static_assert(WIN == 32, "head masks are 32 bits wide");
+    static_assert(UPD_SPAN == 4 * EMB_WAVE && UPD_LOOK == 32, "staging below assumes 4 records per lane + 32");
     EMB_STAGE_TABLE_DIR(dir, tables, T, UPD_BLOCK)
-    __shared__ KeyT lk[GROUPS][WIN + 2];  // [0] = record before the range, [1 + e] = record e, [WIN + 1] = the one after
-    __shared__ uint32_t lp[GROUPS][WIN];
+    // [0] = the record before the span, [1 + e] = record e of the window, [WIN + 1] = the record after it
+    __shared__ KeyT lk[WAVES][WIN + 2];
+    __shared__ uint32_t lp[WAVES][WIN];
+    __shared__ uint16_t lh[WAVES][UPD_SPAN + 2];   // window positions of the run heads, ascending
+    __shared__ uint32_t lq[WAVES];                 // runs queued by this wavefront so far
 
-    const int g = threadIdx.x / LPR;
-    const int l = threadIdx.x % LPR;
-    const uint64_t gid = (uint64_t)blockIdx.x * GROUPS + g;
-    const uint64_t first = gid * UPD_EPG;
+    const int wave = threadIdx.x / EMB_WAVE;
+    const int lane = threadIdx.x & (EMB_WAVE - 1);
+    const int g = lane / LPR;
+    const int l = lane % LPR;
+    const uint64_t wid = (uint64_t)blockIdx.x * WAVES + wave;
+    const uint64_t first = wid * UPD_SPAN;
     const bool in = first < n;
     const uint32_t i0 = (uint32_t)first;
 
-    // ---- stage this group's records (the arrays carry SORT_PAD records of slack)
-    if (in && l < STAGERS) {
-        KeyT k[PER];
-        uint32_t b[PER];
-        load_records<KeyT, PER>(keys + i0 + l * PER, k);
-        load_records<uint32_t, PER>(pay + i0 + l * PER, b);
+    // ---- stage the span and the look-ahead (the arrays carry SORT_PAD records of slack)
+    if (in) {
+        {
+            KeyT k[4];
+            uint32_t b[4];
+            load_records<KeyT, 4>(keys + i0 + lane * 4, k);
+            load_records<uint32_t, 4>(pay + i0 + lane * 4, b);
 #pragma unroll
-        for (int e = 0; e < PER; ++e) {
-            const bool live = i0 + l * PER + e < n;
-            lk[g][1 + l * PER + e] = live ? k[e] : sentinel;
-            lp[g][l * PER + e] = live ? b[e] : 0u;
+            for (int e = 0; e < 4; ++e) {
+                const bool live = i0 + lane * 4 + e < n;
+                lk[wave][1 + lane * 4 + e] = live ? k[e] : sentinel;
+                lp[wave][lane * 4 + e] = live ? b[e] : 0u;
+            }
         }
-        if (l == 0) {
-            lk[g][0] = i0 > 0 ? keys[i0 - 1] : sentinel;
-            lk[g][WIN + 1] = (n - i0 > (uint32_t)WIN) ? keys[i0 + WIN] : sentinel;
+        if (lane < UPD_LOOK / 4) {
+            KeyT k[4];
+            uint32_t b[4];
+            const uint32_t at = i0 + UPD_SPAN + lane * 4;
+            const bool any = at < n;       // a window that starts inside the array may end outside its slack
+            if (any) {
+                load_records<KeyT, 4>(keys + at, k);
+                load_records<uint32_t, 4>(pay + at, b);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool live = any && at + e < n;
+                lk[wave][1 + UPD_SPAN + lane * 4 + e] = live ? k[e] : sentinel;
+                lp[wave][UPD_SPAN + lane * 4 + e] = live ? b[e] : 0u;
+            }
         }
+        if (lane == 0) {
+            lk[wave][0] = i0 > 0 ? keys[i0 - 1] : sentinel;
+            lk[wave][WIN + 1] = (n - i0 > (uint32_t)WIN) ? keys[i0 + WIN] : sentinel;
+            lq[wave] = 0;
+        }
+    }
+    __syncthreads();
+
+    // ---- list the positions where the key changes (the sentinel records count as one last run)
+    uint32_t runs = 0;   // heads inside the span
+    if (in) {
+        uint32_t bits = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bits |= (lk[wave][1 + lane * 4 + e] != lk[wave][lane * 4 + e] ? 1u : 0u) << e;
+        const uint32_t c = __popc(bits);
+        const uint32_t incl = wave_inclusive_scan<uint32_t>(c);
+        runs = (uint32_t)__shfl((int)incl, EMB_WAVE - 1, EMB_WAVE);
+        uint32_t at = incl - c;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if ((bits >> e) & 1u) lh[wave][at++] = (uint16_t)(lane * 4 + e);
+        // the first head of the look-ahead ends the last run of the span
+        uint32_t la = WIN;
+        if (lane < UPD_LOOK / 4) {
+#pragma unroll
+            for (int e = 3; e >= 0; --e) {
+                const int idx = UPD_SPAN + lane * 4 + e;
+                if (lk[wave][1 + idx] != lk[wave][idx]) la = idx;
+            }
+        }
+#pragma unroll
+        for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) {
+            const uint32_t o = (uint32_t)__shfl_xor((int)la, d, EMB_WAVE);
+            la = o < la ? o : la;
+        }
+        if (lane == 0) lh[wave][runs] = (uint16_t)la;
     }
     __syncthreads();
 
     uint32_t heads = 0;
     if (in) {
-        // ---- which records are valid (not the sentinel) and which start a run
-        uint32_t valid = 0, head = 0;
-        if (l < STAGERS) {
-#pragma unroll
-            for (int e = 0; e < PER; ++e) {
-                const int idx = l * PER + e;
-                const KeyT k = lk[g][1 + idx];
-                const bool v = k != sentinel;
-                valid |= (v ? 1u : 0u) << idx;
-                head |= ((v && k != lk[g][idx]) ? 1u : 0u) << idx;   // record 0 of the whole array: lk[0] is the sentinel
-            }
-        }
-        valid = group_or<LPR>(valid);
-        head = group_or<LPR>(head);
-        const uint32_t stop = head | ~valid;                 // a run ends before the next head or invalid record
-        uint32_t todo = head & ((1u << UPD_EPG) - 1u);       // runs that start inside the range are ours
-        uint32_t queued = 0xFFFFFFFFu;
         const int64_t row_bytes = (int64_t)chunks_per_row * 16;
-
-        while (todo) {
-            const int pos = __ffs((int)todo) - 1;
-            todo &= todo - 1;
+        // groups take the runs round-robin: every group gets the same number of runs, give or take one
+        for (uint32_t k = g; k < runs; k += GPW) {
+            const int pos = lh[wave][k];
+            const int end = lh[wave][k + 1];
+            const KeyT key = lk[wave][1 + pos];
+            if (key == sentinel) break;                         // the sentinel run is last and nobody's
             ++heads;
-            const uint32_t later = pos == 31 ? 0u : (stop >> (pos + 1)) << (pos + 1);
-            const int end = later ? __ffs((int)later) - 1 : WIN;
-            const KeyT key = lk[g][1 + pos];
-            if (end == WIN && lk[g][WIN + 1] == key) {        // not over after the look-ahead: someone else's job
-                queued = i0 + (uint32_t)pos;
-                break;
+            // long, or not over after the look-ahead: queue it (at most UPD_QSLOTS such runs start in a span)
+            if (end - pos > UPD_SHORT_MAX || (end == WIN && lk[wave][WIN + 1] == key)) {
+                if (l == 0) {
+                    const uint32_t slot = atomicAdd(&lq[wave], 1u);
+                    if (slot < (uint32_t)UPD_QSLOTS) queue[wid * UPD_QSLOTS + slot] = i0 + (uint32_t)pos;
+                }
+                continue;
             }
             // ---- the row, its accumulator and the first EU gradient rows, all requested together
-            const int t = bdiv.table(lp[g][pos]);
+            const int t = bdiv.table(lp[wave][pos]);
             const int64_t r = (int64_t)key - dir.base(t);
             char *wrow = dir.weights(t) + r * row_bytes;
             float *aptr = dir.accum(t) + r;
@@ -342,7 +386,7 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
 #pragma unroll
                         for (int x = 0; x < V; ++x) gr[u][c][x] = make_float4(0.f, 0.f, 0.f, 0.f);
                     if (e < end) {
-                        const uint32_t bag = lp[g][e];
+                        const uint32_t bag = lp[wave][e];
                         sc[u] = bag_scale[bag];
                         const float *grow = dout + (int64_t)bag * D;
 #pragma unroll
@@ -359,15 +403,16 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
             }
             adagrad_apply<LPR, CPL, BF16>(acc, w, s_old, wrow, aptr, l, chunks_per_row, inv_D, lr, eps);
         }
-        if (l == 0) queue[gid] = queued;
     }
+    // mark the unused queue slots of this wavefront
+    __syncthreads();
+    if (in && lane < UPD_QSLOTS && (uint32_t)lane >= lq[wave]) queue[wid * UPD_QSLOTS + lane] = 0xFFFFFFFFu;
 
     // number of runs started = number of distinct rows; one store per wavefront
     uint32_t h = (l == 0) ? heads : 0u;
 #pragma unroll
     for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) h += __shfl_xor(h, d, EMB_WAVE);
-    if ((threadIdx.x & (EMB_WAVE - 1)) == 0)
-        wave_heads[(uint64_t)blockIdx.x * (UPD_BLOCK / EMB_WAVE) + threadIdx.x / EMB_WAVE] = h;
+    if (lane == 0) wave_heads[wid] = h;
 }
 
 // ---------------------------------------------------------------------------
@@ -380,7 +425,7 @@ __global__ __launch_bounds__(256) void long_prepare_kernel(const KeyT *__restric
                                                            const uint32_t *__restrict__ queue, uint32_t slots,
                                                            const uint32_t *__restrict__ wave_heads,
                                                            uint32_t n_wave_heads, LongSeg *__restrict__ segs,
-                                                           uint32_t *__restrict__ seg_done,
+                                                           uint32_t *__restrict__ multi_list,
                                                            uint2 *__restrict__ chunk_tasks, uint32_t chunk_cap,
                                                            uint32_t partial_cap)
 {
@@ -400,8 +445,8 @@ __global__ __launch_bounds__(256) void long_prepare_kernel(const KeyT *__restric
     uint32_t hi = 0, chunks = 0;
     if (lo != 0xFFFFFFFFu) {
         const KeyT key = keys[lo];
-        // gallop: the run is at least UPD_EPG + 1 records long
-        uint32_t step = UPD_EPG;
+        // gallop: the run is longer than UPD_LOOK records
+        uint32_t step = UPD_LOOK;
         uint32_t a = lo + 1, b = n;                 // the first record whose key differs lies in [a, b]
         for (;;) {
             const uint32_t probe = lo + step;
@@ -423,14 +468,17 @@ __global__ __launch_bounds__(256) void long_prepare_kernel(const KeyT *__restric
         chunks = (hi - lo + LONG_CHUNK - 1) / LONG_CHUNK;
     }
     // task slots: an exclusive scan inside the workgroup, one atomic per workgroup
-    uint32_t total_chunks, total_part;
+    uint32_t total_chunks, total_part, total_multi;
     const uint32_t inc_c = block_inclusive_scan<uint32_t, 256>(chunks, wave_sums, total_chunks);
     const uint32_t part = chunks > 1 ? chunks : 0u;   // chunk sums are stored only for runs of several chunks
     const uint32_t inc_p = block_inclusive_scan<uint32_t, 256>(part, wave_sums, total_part);
-    __shared__ uint32_t s_base_c, s_base_p;
+    const uint32_t multi = chunks > 1 ? 1u : 0u;
+    const uint32_t inc_m = block_inclusive_scan<uint32_t, 256>(multi, wave_sums, total_multi);
+    __shared__ uint32_t s_base_c, s_base_p, s_base_m;
     if (threadIdx.x == 0) {
         s_base_c = total_chunks ? atomicAdd(&ctrl->chunk_count, total_chunks) : 0u;
         s_base_p = total_part ? atomicAdd(&ctrl->partial_count, total_part) : 0u;
+        s_base_m = total_multi ? atomicAdd(&ctrl->multi_count, total_multi) : 0u;
     }
     __syncthreads();
     if (chunks) {
@@ -443,9 +491,31 @@ __global__ __launch_bounds__(256) void long_prepare_kernel(const KeyT *__restric
         // the caps cannot be exceeded (see the workspace layout); the check only guards memory
         sg.n_chunks = (cbase + chunks <= chunk_cap && pbase + part <= partial_cap) ? chunks : 0u;
         segs[s] = sg;
-        seg_done[s] = 0;
         for (uint32_t c = 0; c < sg.n_chunks; ++c) chunk_tasks[cbase + c] = make_uint2(s, c);
+        if (sg.n_chunks > 1) multi_list[s_base_m + inc_m - 1] = s;   // at most one entry per slot
     }
+}
+
+// The row update of a queued run, by the LPR lanes that hold its summed gradient.
+template <typename KeyT, int LPR, int CPL, bool BF16>
+__device__ __forceinline__ void finish_run(const GradAcc<BF16> (&acc)[CPL], const TableDir &dir, const BagDiv &bdiv,
+                                           const KeyT *__restrict__ keys, const uint32_t *__restrict__ pay,
+                                           uint32_t lo, int l, int32_t chunks_per_row, float inv_D, float lr,
+                                           float eps)
+{
+    const int64_t key = (int64_t)keys[lo];
+    const int t = bdiv.table(pay[lo]);
+    const int64_t r = key - dir.base(t);
+    char *wrow = dir.weights(t) + r * ((int64_t)chunks_per_row * 16);
+    float *aptr = dir.accum(t) + r;
+    uint4 w[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const int chunk = l + c * LPR;
+        w[c] = make_uint4(0, 0, 0, 0);
+        if (chunk < chunks_per_row) w[c] = load_chunk(wrow + (int64_t)chunk * 16);
+    }
+    adagrad_apply<LPR, CPL, BF16>(acc, w, *aptr, wrow, aptr, l, chunks_per_row, inv_D, lr, eps);
 }
 
 // One wavefront per chunk task.
@@ -456,15 +526,13 @@ __global__ __launch_bounds__(UPD_BLOCK) void long_reduce_kernel(const emb_table 
                                                                 const float *__restrict__ bag_scale,
                                                                 const float *__restrict__ dout,
                                                                 int32_t chunks_per_row, int32_t D, float inv_D,
-                                                                float lr, float eps, BagDiv bdiv, BwdCtrl *ctrl,
+                                                                float lr, float eps, BagDiv bdiv,
+                                                                const BwdCtrl *ctrl,
                                                                 const LongSeg *__restrict__ segs,
-                                                                uint32_t *__restrict__ seg_done,
                                                                 const uint2 *__restrict__ chunk_tasks,
-                                                                uint32_t chunk_cap, float *__restrict__ partials,
-                                                                int64_t *num_unique_out)
+                                                                uint32_t chunk_cap, float *__restrict__ partials)
 {
     if (ctrl->abort) return;
-    if (blockIdx.x == 0 && threadIdx.x == 0 && num_unique_out) *num_unique_out = (int64_t)ctrl->num_unique;
     EMB_STAGE_TABLE_DIR(dir, tables, T, UPD_BLOCK)
     __syncthreads();
     constexpr int GPW = EMB_WAVE / LPR;  // lane groups per wavefront
@@ -522,60 +590,80 @@ __global__ __launch_bounds__(UPD_BLOCK) void long_reduce_kernel(const emb_table 
 #pragma unroll
                 for (int i = 0; i < F; ++i) acc[c].a[i] += __shfl_xor(acc[c].a[i], d, EMB_WAVE);
 
-        bool finish = sg.n_chunks == 1;
-        if (sg.n_chunks > 1) {
-            // publish this chunk's sum, then find out whether it was the run's last outstanding one
-            if (g == 0) {
+        if (g == 0) {
+            if (sg.n_chunks == 1) {
+                finish_run<KeyT, LPR, CPL, BF16>(acc, dir, bdiv, keys, pay, sg.lo, l, chunks_per_row, inv_D, lr, eps);
+            } else {
                 float *slot = partials + (int64_t)(sg.chunk_base + tk.y) * row_floats;
 #pragma unroll
                 for (int c = 0; c < CPL; ++c) {
                     const int chunk = l + c * LPR;
                     if (chunk < chunks_per_row) {
+                        float4 *o = reinterpret_cast<float4 *>(slot + (int64_t)chunk * F);
 #pragma unroll
-                        for (int i = 0; i < F; ++i)
-                            __hip_atomic_store(slot + (int64_t)chunk * F + i, acc[c].a[i], __ATOMIC_RELAXED,
-                                               __HIP_MEMORY_SCOPE_AGENT);
+                        for (int x = 0; x < V; ++x)
+                            o[x] = make_float4(acc[c].a[4 * x], acc[c].a[4 * x + 1], acc[c].a[4 * x + 2],
+                                               acc[c].a[4 * x + 3]);
                     }
                 }
             }
-            __threadfence();
-            uint32_t ticket = 0;
-            if (lane == 0) ticket = atomicAdd(&seg_done[tk.x], 1u);
-            ticket = (uint32_t)__shfl((int)ticket, 0, EMB_WAVE);
-            finish = ticket == sg.n_chunks - 1;
-            if (finish) {
-                __threadfence();
+        }
+    }
+}
+
+// Runs of several chunks: one lane group per run adds the chunk sums in chunk
+// order and applies Adagrad.  Also publishes the number of distinct rows.
+template <typename KeyT, int LPR, int CPL, bool BF16>
+__global__ __launch_bounds__(UPD_BLOCK) void long_combine_kernel(const emb_table *__restrict__ tables, int32_t T,
+                                                                 const KeyT *__restrict__ keys,
+                                                                 const uint32_t *__restrict__ pay,
+                                                                 int32_t chunks_per_row, float inv_D, float lr,
+                                                                 float eps, BagDiv bdiv, const BwdCtrl *ctrl,
+                                                                 const LongSeg *__restrict__ segs,
+                                                                 const uint32_t *__restrict__ multi_list,
+                                                                 uint32_t multi_cap,
+                                                                 const float *__restrict__ partials,
+                                                                 int64_t *num_unique_out)
+{
+    if (ctrl->abort) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && num_unique_out) *num_unique_out = (int64_t)ctrl->num_unique;
+    EMB_STAGE_TABLE_DIR(dir, tables, T, UPD_BLOCK)
+    __syncthreads();
+    constexpr int GROUPS = UPD_BLOCK / LPR;
+    constexpr int F = GradAcc<BF16>::F;
+    constexpr int V = GradAcc<BF16>::V;
+    constexpr int CU = 4;  // chunk sums requested together
+    const int l = threadIdx.x % LPR;
+    const int64_t row_floats = (int64_t)chunks_per_row * F;
+    uint32_t count = ctrl->multi_count;
+    if (count > multi_cap) count = multi_cap;
+    for (uint32_t m = blockIdx.x * GROUPS + threadIdx.x / LPR; m < count; m += gridDim.x * GROUPS) {
+        const LongSeg sg = segs[multi_list[m]];
+        GradAcc<BF16> acc[CPL];
 #pragma unroll
-                for (int c = 0; c < CPL; ++c) acc[c].zero();
-                for (uint32_t cc = 0; cc < sg.n_chunks; ++cc) {
-                    const float *slot = partials + (int64_t)(sg.chunk_base + cc) * row_floats;
+        for (int c = 0; c < CPL; ++c) acc[c].zero();
+        for (uint32_t c0 = 0; c0 < sg.n_chunks; c0 += CU) {
+            float4 v[CU][CPL][V];
+#pragma unroll
+            for (int u = 0; u < CU; ++u) {
+#pragma unroll
+                for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                    for (int x = 0; x < V; ++x) v[u][c][x] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (c0 + u < sg.n_chunks) {
+                    const float *slot = partials + (int64_t)(sg.chunk_base + c0 + u) * row_floats;
 #pragma unroll
                     for (int c = 0; c < CPL; ++c) {
                         const int chunk = l + c * LPR;
-                        if (chunk < chunks_per_row) {
-#pragma unroll
-                            for (int i = 0; i < F; ++i)
-                                acc[c].a[i] += __hip_atomic_load(slot + (int64_t)chunk * F + i, __ATOMIC_RELAXED,
-                                                                 __HIP_MEMORY_SCOPE_AGENT);
-                        }
+                        if (chunk < chunks_per_row) load_grad<BF16>(slot + (int64_t)chunk * F, v[u][c]);
                     }
                 }
             }
-        }
-        if (finish && g == 0) {
-            const int64_t key = (int64_t)keys[sg.lo];
-            const int t = bdiv.table(pay[sg.lo]);
-            const int64_t r = key - dir.base(t);
-            char *wrow = dir.weights(t) + r * ((int64_t)chunks_per_row * 16);
-            float *aptr = dir.accum(t) + r;
-            uint4 w[CPL];
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) {
-                const int chunk = l + c * LPR;
-                w[c] = make_uint4(0, 0, 0, 0);
-                if (chunk < chunks_per_row) w[c] = load_chunk(wrow + (int64_t)chunk * 16);
-            }
-            adagrad_apply<LPR, CPL, BF16>(acc, w, *aptr, wrow, aptr, l, chunks_per_row, inv_D, lr, eps);
+            for (int u = 0; u < CU; ++u)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) acc[c].fma(1.0f, v[u][c]);
         }
+        finish_run<KeyT, LPR, CPL, BF16>(acc, dir, bdiv, keys, pay, sg.lo, l, chunks_per_row, inv_D, lr, eps);
     }
 }
