@@ -93,8 +93,14 @@ def main() -> int:
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps --------------------------------------
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
-    uniq_counts = []
+    # events on the launch stream: around the index stage and the forward kernel, and (recorded by
+    # the library itself) between the stages of the backward
+    NS = emb.BWD_STAGE_EVENTS
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    bev = [[torch.cuda.Event(enable_timing=True) for _ in range(NS)] for _ in range(K)]
+    for row in bev:
+        for e in row:
+            e.record()          # creates the HIP event behind the torch object
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(K):
@@ -105,40 +111,65 @@ def main() -> int:
         pipeline.run_forward(w, tabs.set, rows, buf)
         ev[k][2].record()
         if w.backward:
-            pipeline.run_backward(w, tabs.set, rows, db, buf)
-        ev[k][3].record()
+            pipeline.run_backward(w, tabs.set, rows, db, buf, stage_events=bev[k])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
     assert int(buf.status.item()) == 0, "device status word set during the timed steps"
 
     lookups = sum(dbs[(W + k) % len(dbs)].nnz for k in range(K))
+    nnz_avg = lookups / K
+    nnz_i = int(nnz_avg)
+    bags = w.T * w.B
     ms_index = sum(e[0].elapsed_time(e[1]) for e in ev) / K
     ms_fwd = sum(e[1].elapsed_time(e[2]) for e in ev) / K
-    ms_bwd = sum(e[2].elapsed_time(e[3]) for e in ev) / K
-    nnz_avg = lookups / K
-    bags = w.T * w.B
-    if w.backward:
-        uniq = int(buf.num_unique.item())      # of the last batch; all batches are alike
-    else:
-        uniq = 0
-    total_rows_bits = max(1, int(tabs.set.total_rows).bit_length())
-    passes = (total_rows_bits + 7) // 8
+    uniq = int(buf.num_unique.item()) if w.backward else 0   # of the last batch; all batches are alike
+    passes = (max(1, int(tabs.set.total_rows).bit_length()) + 7) // 8
+    rowb = w.D * w.esz
 
-    fwd_b = forward_bytes(int(nnz_avg), bags, w.D, w.esz)
-    fwd_gbs = fwd_b / (ms_fwd * 1e-3) / 1e9
-    roofline = {"kernel": "bag_forward_kernel (gather-pool)", "bound": "hbm", "achieved": round(fwd_gbs, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(fwd_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                "avg_ms": round(ms_fwd, 4), "algorithmic_bytes": fwd_b}
-    stages = {"index_ms": round(ms_index, 4), "forward_ms": round(ms_fwd, 4), "backward_ms": round(ms_bwd, 4)}
+    def entry(name, ms, nbytes, what):
+        gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        return {"kernel": name, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "avg_ms": round(ms, 4),
+                "algorithmic_bytes": int(nbytes), "bytes_are": what}
+
+    kernels = [
+        entry("offsets_* + hash_ids_tables_kernel (index stage, 4 launches)", ms_index, nnz_i * 16 + bags * 12,
+              "16 B per lookup (raw ID in, row out) + 12 B per bag (length in, offset out)"),
+        entry("bag_forward_kernel (gather-pool)", ms_fwd, forward_bytes(nnz_i, bags, w.D, w.esz),
+              "row + 8 B index per lookup, fp32 output row + 8 B offset per bag"),
+    ]
+    ms_bwd = 0.0
     if w.backward:
-        bwd_b = backward_bytes(int(nnz_avg), bags, uniq, w.D, w.esz, passes)
-        stages["backward_algorithmic_bytes"] = bwd_b
-        stages["backward_GBps"] = round(bwd_b / (ms_bwd * 1e-3) / 1e9, 1)
-        stages["unique_rows_last_batch"] = uniq
-    step_bytes = fwd_b + (stages.get("backward_algorithmic_bytes", 0)) + int(nnz_avg) * 16 + bags * 12
-    log("step %.3f ms: index %.3f, forward %.3f (%.0f GB/s, %.1f %% of HBM peak), backward %.3f" % (
-        elapsed / K * 1e3, ms_index, ms_fwd, fwd_gbs, 100 * fwd_gbs / HBM_PEAK_GBS, ms_bwd))
+        st = [sum(r[i].elapsed_time(r[i + 1]) for r in bev) / K for i in range(NS - 1)]
+        ms_bwd = sum(bev[k][0].elapsed_time(bev[k][NS - 1]) for k in range(K)) / K
+        kernels += [
+            entry("bwd_init + bwd_keys_kernel (key build)", st[0], nnz_i * 16 + bags * 20,
+                  "8 B row in + 8 B record out per lookup; 16 B offsets in + 4 B scale out per bag"),
+            entry("sort_hist/scan/scatter x %d passes (radix sort)" % passes, st[1], nnz_i * 16 * passes,
+                  "8 B record read + 8 B written per lookup and pass"),
+            entry("update_kernel (segment reduce + row-wise Adagrad, short runs)", st[3] if st[3] > 0 else 1e-9,
+                  uniq * (2 * rowb + 8) + nnz_i * 8 + bags * 4 * w.D,
+                  "row read + row written + 8 B accumulator per distinct row, 8 B record per lookup, "
+                  "gradient row once per bag (all distinct rows counted here; the few queued ones are "
+                  "updated by the next stage)"),
+            entry("long_prepare/reduce/combine (queued long runs)", st[4], 1,
+                  "not priced: its rows are counted under update_kernel"),
+        ]
+    # the roofline object is for the kernel with the largest share of the step
+    roofline = max(kernels, key=lambda e: e["avg_ms"])
+    stages = {"index_ms": round(ms_index, 4), "forward_ms": round(ms_fwd, 4), "backward_ms": round(ms_bwd, 4)}
+    step_bytes = sum(e["algorithmic_bytes"] for e in kernels)
+    if w.backward:
+        stages.update({"bwd_keys_ms": round(st[0], 4), "bwd_sort_ms": round(st[1], 4),
+                       "bwd_unique_list_ms": round(st[2], 4), "bwd_update_ms": round(st[3], 4),
+                       "bwd_long_runs_ms": round(st[4], 4), "unique_rows_last_batch": uniq,
+                       "backward_algorithmic_bytes": backward_bytes(nnz_i, bags, uniq, w.D, w.esz, passes)})
+    log("step %.3f ms: index %.3f, forward %.3f, backward %.3f %s" % (
+        elapsed / K * 1e3, ms_index, ms_fwd, ms_bwd,
+        ("(keys %.3f, sort %.3f, update %.3f, long runs %.3f)" % (st[0], st[1], st[3], st[4])) if w.backward else ""))
+    log("dominant: %s: %.3f ms, %.0f GB/s algorithmic = %.1f %% of HBM peak" % (
+        roofline["kernel"], roofline["avg_ms"], roofline["achieved"], 100 * roofline["frac"]))
 
     # ---- side measurements: the forward kernel alone on workloads 2 and 2u ---
     extra = {}
@@ -239,6 +270,7 @@ def main() -> int:
         "achieved_GBps_whole_step": round(step_bytes / (elapsed / K) / 1e9, 1),
         "stages": stages,
         "roofline": roofline,
+        "kernels": kernels,
         "cpu_baseline": cpu,
     }
     if extra:

@@ -116,6 +116,8 @@ int emb_bag_forward(const emb_table *tables_host, const emb_table *tables_dev, i
                     const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
                     float *out_dev, uint32_t *status_dev, void *stream);
 
+#define EMB_BWD_STAGE_EVENTS 6
+
 /* Bytes of device workspace emb_bag_backward_rowwise_adagrad needs for a
  * batch of T*B bags and nnz lookups over tables of dimension D and storage
  * type dtype with `total_rows` rows in all.  Returns 0 on invalid arguments. */
@@ -141,7 +143,11 @@ size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t nnz, int64
  * Out-of-range rows are skipped (EMB_STATUS_BAD_INDEX).  If the offsets are
  * not a partition of [0, nnz) into bags, nothing is updated, U = 0 and
  * EMB_STATUS_BAD_OFFSETS is set.  EMB_ERR_UNSUPPORTED as for the forward, and
- * if T*B >= 2^32 - 1, nnz >= 2^31, or accum is NULL for some table. */
+ * if T*B >= 2^32 - 1, nnz >= 2^31, or accum is NULL for some table.
+ * stage_events (host, nullable): EMB_BWD_STAGE_EVENTS hipEvent_t handles that
+ * are recorded on `stream` before the first kernel and after the key build,
+ * the sort, the optional list of distinct rows, the short-run update and the
+ * long-run path, for callers that time the stages. */
 int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, const emb_table *tables_dev,
                                      int32_t T, int32_t D, int32_t dtype,
                                      const int64_t *rows_dev, const int64_t *offsets_dev,
@@ -149,7 +155,7 @@ int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, const emb_tab
                                      float lr, float eps, void *workspace_dev,
                                      size_t workspace_bytes, int64_t *unique_keys_out_dev,
                                      int32_t *unique_counts_out_dev, int64_t *num_unique_out_dev,
-                                     uint32_t *status_dev, void *stream);
+                                     uint32_t *status_dev, void *const *stage_events, void *stream);
 
 /* ---- host-resident table with an HBM hot-row cache (Section 3.3) --------- */
 

@@ -22,6 +22,7 @@ DTYPE = {"f32": 0, "bf16": 1}
 STATUS_BAD_INDEX = 1
 STATUS_BAD_OFFSETS = 2
 STATUS_BAD_HOT_SET = 4
+BWD_STAGE_EVENTS = 6
 
 # numpy mirror of ``struct emb_table``
 TABLE_DESC = np.dtype([("weights", "<u8"), ("accum", "<u8"), ("num_rows", "<i8"), ("row_base", "<i8"),
@@ -76,7 +77,7 @@ def lib() -> C.CDLL:
     L.emb_bag_backward_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32]
     L.emb_bag_backward_rowwise_adagrad.restype = C.c_int
     L.emb_bag_backward_rowwise_adagrad.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, f32, f32,
-                                                   vp, sz, vp, vp, vp, vp, vp]
+                                                   vp, sz, vp, vp, vp, vp, vp, vp]
     L.emb_cache_index_bytes.restype = C.c_int
     L.emb_cache_index_bytes.argtypes = [i64, C.POINTER(sz)]
     L.emb_cache_build.restype = C.c_int
@@ -216,20 +217,28 @@ def emb_bag_backward_rowwise_adagrad(tables: TableSet, rows: torch.Tensor, offse
                                      unique_keys: Optional[torch.Tensor] = None,
                                      unique_counts: Optional[torch.Tensor] = None,
                                      num_unique: Optional[torch.Tensor] = None,
-                                     status: Optional[torch.Tensor] = None) -> None:
+                                     status: Optional[torch.Tensor] = None,
+                                     stage_events: Optional[Sequence[torch.cuda.Event]] = None) -> None:
+    """``stage_events``: BWD_STAGE_EVENTS torch events that have been recorded at least once
+    (so that their HIP handles exist); the library records them between its stages."""
     nnz = rows.numel()
     if offsets.numel() != tables.T * B + 1 or dout.numel() != tables.T * B * tables.D:
         raise TypeError("shape mismatch")
     for t, name in ((unique_keys, "unique_keys"), (unique_counts, "unique_counts")):
         if t is not None and t.numel() < nnz:
             raise TypeError(name + " must hold at least nnz elements")
+    ev = None
+    if stage_events is not None:
+        if len(stage_events) != BWD_STAGE_EVENTS:
+            raise TypeError("stage_events must hold %d events" % BWD_STAGE_EVENTS)
+        ev = (C.c_void_p * BWD_STAGE_EVENTS)(*[int(e.cuda_event) for e in stage_events])
     _check("emb_bag_backward_rowwise_adagrad", lib().emb_bag_backward_rowwise_adagrad(
         tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype],
         _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode],
         _ptr(dout, torch.float32, "dout"), C.c_float(lr), C.c_float(eps),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
         _ptr(unique_keys, torch.int64, "unique_keys"), _ptr(unique_counts, torch.int32, "unique_counts"),
-        _ptr(num_unique, torch.int64, "num_unique"), _ptr(status, torch.int32, "status"), _stream()))
+        _ptr(num_unique, torch.int64, "num_unique"), _ptr(status, torch.int32, "status"), ev, _stream()))
 
 
 def emb_cache_index_bytes(num_rows: int) -> int:

@@ -273,8 +273,17 @@ struct BwdArgs {
     int32_t *unique_counts_out;
     int64_t *num_unique_out;
     uint32_t *status;
+    void *const *events;
     hipStream_t stream;
+    // record stage event i, if the caller asked for stage timing
+    int mark(int i) const
+    {
+        if (events && events[i] && hipEventRecord(reinterpret_cast<hipEvent_t>(events[i]), stream) != hipSuccess)
+            return EMB_ERR_HIP;
+        return EMB_OK;
+    }
 };
+#define EMB_MARK(a, i) do { if ((a).mark(i) != EMB_OK) return EMB_ERR_HIP; } while (0)
 
 template <typename KeyT, int LPR, int CPL, int EU, bool BF16>
 int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const uint32_t *pay, int chunks)
@@ -298,6 +307,7 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
                        a.stream, a.tables_dev, a.T, keys, pay, n, sentinel, bag_scale, a.dout, chunks, a.D, inv_D, a.lr,
                        a.eps, bdiv, ctrl, queue, wave_heads);
     EMB_RETURN_IF_LAUNCH_FAILED();
+    EMB_MARK(a, 4);
 
     const int64_t n_wave_heads = L.upd_blocks * (UPD_BLOCK / EMB_WAVE);
     const int64_t pthreads = L.qslots > n_wave_heads ? L.qslots : n_wave_heads;
@@ -323,6 +333,7 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
                        a.tables_dev, a.T, keys, pay, chunks, inv_D, a.lr, a.eps, bdiv, ctrl, segs, multi_list,
                        (uint32_t)L.qslots, partials, a.num_unique_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
+    EMB_MARK(a, 5);
     return EMB_OK;
 }
 
@@ -344,9 +355,13 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
     const uint32_t tiles = (uint32_t)L.tiles;
     hipStream_t s = a.stream;
 
+    EMB_MARK(a, 0);
     hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, s, ctrl, totals, L.passes, n, a.num_unique_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
-    if (a.nnz == 0) return EMB_OK;
+    if (a.nnz == 0) {
+        for (int i = 1; i < EMB_BWD_STAGE_EVENTS; ++i) EMB_MARK(a, i);
+        return EMB_OK;
+    }
 
     {
         constexpr int BAGS = 256 / KEY_LANES;
@@ -355,6 +370,7 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
                            a.offsets, a.mode, sentinel, keys_a, pay_a, bag_scale, ctrl, a.status);
         EMB_RETURN_IF_LAUNCH_FAILED();
     }
+    EMB_MARK(a, 1);
 
     KeyT *kin = keys_a, *kout = keys_b;
     uint32_t *pin = pay_a, *pout = pay_b;
@@ -373,6 +389,7 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
         uint32_t *tp = pin; pin = pout; pout = tp;
     }
     // sorted records are now in (kin, pin)
+    EMB_MARK(a, 2);
 
     if (a.unique_keys_out || a.unique_counts_out) {
         hipLaunchKernelGGL(runs_count_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, n, sentinel, tile_heads,
@@ -395,6 +412,7 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
         EMB_RETURN_IF_LAUNCH_FAILED();
     }
 
+    EMB_MARK(a, 3);
     const int chunks = a.D * emb_elem_size(a.dtype) / 16;
     const bool bf16 = a.dtype == EMB_BF16;
 #define EMB_UPD(LL, C, EU)                                                                   \
@@ -433,7 +451,7 @@ extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, co
                                                 const float *dout_dev, float lr, float eps, void *workspace_dev,
                                                 size_t workspace_bytes, int64_t *unique_keys_out_dev,
                                                 int32_t *unique_counts_out_dev, int64_t *num_unique_out_dev,
-                                                uint32_t *status_dev, void *stream)
+                                                uint32_t *status_dev, void *const *stage_events, void *stream)
 {
     if (B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
@@ -467,6 +485,7 @@ extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, co
     a.unique_counts_out = unique_counts_out_dev;
     a.num_unique_out = num_unique_out_dev;
     a.status = status_dev;
+    a.events = stage_events;
     a.stream = emb_stream(stream);
     return L.key_bytes == 4 ? run_backward<uint32_t>(a, L) : run_backward<uint64_t>(a, L);
 }

@@ -82,9 +82,11 @@ def run_forward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, buf: Step
     emb.emb_bag_forward(tables, rows, buf.offsets, w.B, w.pool, buf.out, buf.status)
 
 
-def run_backward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, db: DeviceBatch, buf: StepBuffers) -> None:
+def run_backward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, db: DeviceBatch, buf: StepBuffers,
+                 stage_events=None) -> None:
     emb.emb_bag_backward_rowwise_adagrad(tables, rows, buf.offsets, w.B, w.pool, db.dout, w.lr, w.eps, buf.workspace,
-                                         buf.unique_keys, buf.unique_counts, buf.num_unique, buf.status)
+                                         buf.unique_keys, buf.unique_counts, buf.num_unique, buf.status,
+                                         stage_events)
 
 
 def run_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:

@@ -115,7 +115,7 @@ def test_backward_argument_errors(L):
     def args(**k):
         return [k.get("th", d.ctypes.data), FAKE, 2, k.get("D", 64), 0, FAKE, FAKE, 4, k.get("nnz", 8),
                 k.get("mode", 1), k.get("dout", FAKE), C.c_float(0.01), C.c_float(1e-8), k.get("ws", FAKE),
-                k.get("wsb", need), None, None, None, None, None]
+                k.get("wsb", need), None, None, None, None, None, None]
     assert f(*args(ws=None)) == WORKSPACE
     assert f(*args(wsb=need - 1)) == WORKSPACE
     assert f(*args(ws=FAKE + 16)) == WORKSPACE          # workspace must be 256-byte aligned
