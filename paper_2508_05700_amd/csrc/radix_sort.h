@@ -4,6 +4,46 @@
 #include "bwd_common.h"
 #include "scan.h"
 
+// Stable rank of every record of a wavefront's share of a tile among the records
+// of the same digit, and the wavefront's digit counts.  A wavefront walks its
+// share 64 records at a time in ascending order; lanes holding the same digit
+// are matched with one ballot per digit bit, the lowest of them bumps the
+// wavefront's private LDS counter, so there are no LDS atomics and no
+// same-address serialisation when many records share a digit (the hot rows of
+// a skewed batch, or the table bits of the key).
+template <typename KeyT, bool WANT_RANK>
+__device__ __forceinline__ void wave_rank_digits(const KeyT (&key)[SORT_ITEMS], uint32_t wbase, uint32_t n, int shift,
+                                                 uint32_t *cnt /*LDS [RADIX], this wavefront's, zeroed*/,
+                                                 uint32_t (&rank)[SORT_ITEMS])
+{
+    const int lane = threadIdx.x & (EMB_WAVE - 1);
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+    for (int k = 0; k < SORT_ITEMS; ++k) {
+        const uint32_t i = wbase + k * EMB_WAVE + lane;
+        const bool live = i < n;
+        const uint32_t digit = (uint32_t)(key[k] >> shift) & (RADIX - 1);
+        uint64_t peers = __ballot(live);  // dead lanes match nobody
+#pragma unroll
+        for (int bit = 0; bit < RADIX_BITS; ++bit) {
+            const bool set = (digit >> bit) & 1u;
+            const uint64_t m = __ballot(set);
+            peers &= set ? m : ~m;
+        }
+        const uint32_t before = __popcll(peers & lt_mask);
+        uint32_t prev = 0;
+        if (live && before == 0) {  // lowest lane of each digit group updates the wavefront's counter
+            prev = cnt[digit];
+            cnt[digit] = prev + (uint32_t)__popcll(peers);
+        }
+        if (WANT_RANK) {
+            const int leader = live ? (__ffsll((unsigned long long)peers) - 1) : lane;
+            prev = __shfl(prev, leader, EMB_WAVE);
+            rank[k] = prev + before;
+        }
+    }
+}
+
 // Digit totals are accumulated into TOTAL_SLOTS slots per digit (tile b adds to
 // slot b % TOTAL_SLOTS) so that hundreds of tiles do not queue on one address.
 template <typename KeyT>
@@ -14,17 +54,25 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__res
                                                                const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
-    __shared__ uint32_t h[RADIX];
-    h[threadIdx.x] = 0;  // SORT_BLOCK == RADIX
+    __shared__ uint32_t cnt[SORT_WAVES][RADIX];
+    const int lane = threadIdx.x & (EMB_WAVE - 1);
+    const int wave = threadIdx.x / EMB_WAVE;
+#pragma unroll
+    for (int w = 0; w < SORT_WAVES; ++w) cnt[w][threadIdx.x] = 0;  // SORT_BLOCK == RADIX
     __syncthreads();
-    const uint32_t base = blockIdx.x * SORT_TILE;
+    const uint32_t wbase = blockIdx.x * SORT_TILE + wave * (SORT_TILE / SORT_WAVES);
+    KeyT key[SORT_ITEMS];
 #pragma unroll
     for (int k = 0; k < SORT_ITEMS; ++k) {
-        uint32_t i = base + k * SORT_BLOCK + threadIdx.x;
-        if (i < n) atomicAdd(&h[(uint32_t)(keys[i] >> shift) & (RADIX - 1)], 1u);
+        const uint32_t i = wbase + k * EMB_WAVE + lane;
+        key[k] = i < n ? keys[i] : (KeyT)0;
     }
+    uint32_t unused[SORT_ITEMS];
+    wave_rank_digits<KeyT, false>(key, wbase, n, shift, cnt[wave], unused);
     __syncthreads();
-    const uint32_t c = h[threadIdx.x];
+    uint32_t c = 0;
+#pragma unroll
+    for (int w = 0; w < SORT_WAVES; ++w) c += cnt[w][threadIdx.x];
     hist[threadIdx.x * tiles + blockIdx.x] = c;
     if (c) atomicAdd(&totals[threadIdx.x * TOTAL_SLOTS + (blockIdx.x % TOTAL_SLOTS)], c);
 }
@@ -54,6 +102,10 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ 
     }
 }
 
+// Stable scatter of one tile.  After ranking, the tile's records are first put in
+// digit order in LDS; the copy-out then walks that order, so the lanes of a store
+// instruction write consecutive addresses within each digit's run (about
+// SORT_TILE / RADIX records long) instead of 64 unrelated ones.
 template <typename KeyT>
 __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__restrict__ keys_in,
                                                                   const uint32_t *__restrict__ pay_in,
@@ -63,56 +115,50 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
                                                                   const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
-    // per-wave digit counters, then per-wave destination bases
-    __shared__ uint32_t cnt[SORT_WAVES][RADIX];
+    __shared__ uint32_t cnt[SORT_WAVES][RADIX];  // per-wavefront digit counts, then offsets inside the tile
+    __shared__ uint32_t delta[RADIX];            // global position minus tile position, per digit
+    __shared__ uint32_t wave_sums[SORT_WAVES];
+    __shared__ KeyT sk[SORT_TILE];
+    __shared__ uint32_t sp[SORT_TILE];
     const int lane = threadIdx.x & (EMB_WAVE - 1);
     const int wave = threadIdx.x / EMB_WAVE;
 #pragma unroll
     for (int w = 0; w < SORT_WAVES; ++w) cnt[w][threadIdx.x] = 0;
     __syncthreads();
 
-    // wave `wave` owns records [base + wave*1024, +1024) and walks them 64 at a
-    // time in ascending order, which makes the ranking stable
-    const uint32_t wbase = blockIdx.x * SORT_TILE + wave * (SORT_TILE / SORT_WAVES);
+    const uint32_t tbase = blockIdx.x * SORT_TILE;
+    const uint32_t wbase = tbase + wave * (SORT_TILE / SORT_WAVES);
     KeyT key[SORT_ITEMS];
+    uint32_t pay[SORT_ITEMS];
     uint32_t rank[SORT_ITEMS];
-    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
 #pragma unroll
     for (int k = 0; k < SORT_ITEMS; ++k) {
         const uint32_t i = wbase + k * EMB_WAVE + lane;
-        const bool live = i < n;
-        key[k] = live ? keys_in[i] : (KeyT)0;
-        const uint32_t digit = (uint32_t)(key[k] >> shift) & (RADIX - 1);
-        // lanes holding the same digit (dead lanes match nobody)
-        uint64_t peers = __ballot(live);
-#pragma unroll
-        for (int bit = 0; bit < RADIX_BITS; ++bit) {
-            const bool set = (digit >> bit) & 1u;
-            const uint64_t m = __ballot(set);
-            peers &= set ? m : ~m;
-        }
-        const uint32_t before = __popcll(peers & lt_mask);
-        uint32_t prev = 0;
-        if (live && before == 0) {  // lowest lane of each digit group updates the wave's counter
-            prev = cnt[wave][digit];
-            cnt[wave][digit] = prev + (uint32_t)__popcll(peers);
-        }
-        const int leader = live ? (__ffsll((unsigned long long)peers) - 1) : lane;
-        prev = __shfl(prev, leader, EMB_WAVE);
-        rank[k] = prev + before;
+        key[k] = i < n ? keys_in[i] : (KeyT)0;
+        pay[k] = i < n ? pay_in[i] : 0u;
     }
+    wave_rank_digits<KeyT, true>(key, wbase, n, shift, cnt[wave], rank);
     __syncthreads();
 
-    // thread d turns the per-wave counts of digit d into destination bases
+    // thread d: digit d's count in the tile, its start inside the tile (exclusive scan over the
+    // digits), the wavefronts' offsets within it, and the shift to global positions
     {
         const uint32_t d = threadIdx.x;
-        uint32_t run = hist[(size_t)d * tiles + blockIdx.x];
+        uint32_t c[SORT_WAVES], total = 0;
 #pragma unroll
         for (int w = 0; w < SORT_WAVES; ++w) {
-            const uint32_t c = cnt[w][d];
-            cnt[w][d] = run;
-            run += c;
+            c[w] = cnt[w][d];
+            total += c[w];
         }
+        uint32_t all;
+        const uint32_t start = block_inclusive_scan<uint32_t, SORT_BLOCK>(total, wave_sums, all) - total;
+        uint32_t run = start;
+#pragma unroll
+        for (int w = 0; w < SORT_WAVES; ++w) {
+            cnt[w][d] = run;
+            run += c[w];
+        }
+        delta[d] = hist[(size_t)d * tiles + blockIdx.x] - start;
     }
     __syncthreads();
 
@@ -121,9 +167,22 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
         const uint32_t i = wbase + k * EMB_WAVE + lane;
         if (i < n) {
             const uint32_t digit = (uint32_t)(key[k] >> shift) & (RADIX - 1);
-            const uint32_t dst = cnt[wave][digit] + rank[k];
-            keys_out[dst] = key[k];
-            pay_out[dst] = pay_in[i];
+            const uint32_t at = cnt[wave][digit] + rank[k];
+            sk[at] = key[k];
+            sp[at] = pay[k];
+        }
+    }
+    __syncthreads();
+
+    const uint32_t count = (n - tbase < (uint32_t)SORT_TILE) ? n - tbase : (uint32_t)SORT_TILE;
+#pragma unroll
+    for (int k = 0; k < SORT_ITEMS; ++k) {
+        const uint32_t at = k * SORT_BLOCK + threadIdx.x;
+        if (at < count) {
+            const KeyT kk = sk[at];
+            const uint32_t dst = delta[(uint32_t)(kk >> shift) & (RADIX - 1)] + at;
+            keys_out[dst] = kk;
+            pay_out[dst] = sp[at];
         }
     }
 }
