@@ -37,7 +37,6 @@ struct BwdLayout {
     int64_t qslots;     // queue slots
     int64_t upd_blocks; // its grid
     int64_t chunk_cap;
-    int64_t partial_cap;
 };
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -74,8 +73,6 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     L.qslots = L.slots * UPD_QSLOTS;
     // every queued run has at least one chunk
     L.chunk_cap = nnz / LONG_CHUNK + L.qslots + 2;
-    // chunk sums are stored only for runs longer than LONG_CHUNK: at most 2*len/LONG_CHUNK slots each
-    L.partial_cap = nnz / (LONG_CHUNK / 2) + 2;
     const size_t n = (size_t)(nnz > 0 ? nnz : 1);
     const size_t np = n + SORT_PAD;
     size_t off = 0;
@@ -94,7 +91,7 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     L.segs = off;        off += align256((size_t)L.qslots * sizeof(LongSeg));
     L.multi_list = off;  off += align256((size_t)L.qslots * 4);
     L.chunk_tasks = off; off += align256((size_t)L.chunk_cap * sizeof(uint2));
-    L.partials = off;    off += align256((size_t)L.partial_cap * (size_t)D * 4);
+    L.partials = off;    off += align256((size_t)L.chunk_cap * (size_t)D * 4);   // one chunk-sum slot per task
     L.total = off;
     return L;
 }
@@ -311,9 +308,9 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
 
     const int64_t n_wave_heads = L.upd_blocks * (UPD_BLOCK / EMB_WAVE);
     const int64_t pthreads = L.qslots > n_wave_heads ? L.qslots : n_wave_heads;
-    hipLaunchKernelGGL(long_prepare_kernel<KeyT>, dim3((unsigned)((pthreads + 255) / 256)), dim3(256), 0, a.stream,
-                       keys, n, ctrl, queue, (uint32_t)L.qslots, wave_heads, (uint32_t)n_wave_heads, segs, multi_list,
-                       chunk_tasks, (uint32_t)L.chunk_cap, (uint32_t)L.partial_cap);
+    hipLaunchKernelGGL(long_prepare_kernel<KeyT>, dim3((unsigned)((pthreads + PREP_BLOCK - 1) / PREP_BLOCK)), dim3(PREP_BLOCK), 0, a.stream,
+                       keys, n, sentinel, ctrl, queue, (uint32_t)L.qslots, wave_heads, (uint32_t)n_wave_heads, segs, multi_list,
+                       chunk_tasks, (uint32_t)L.chunk_cap);
     EMB_RETURN_IF_LAUNCH_FAILED();
 
     // one wavefront per task; enough workgroups to fill the chip, tasks beyond that are strided over
@@ -326,8 +323,8 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
 
     // runs of several chunks: at most nnz / LONG_CHUNK of them
     const int64_t multi_max = a.nnz / LONG_CHUNK + 1;
-    constexpr int GROUPS = UPD_BLOCK / LPR;
-    int64_t cwant = (multi_max + GROUPS - 1) / GROUPS;
+    constexpr int CWAVES = UPD_BLOCK / EMB_WAVE;
+    int64_t cwant = (multi_max + CWAVES - 1) / CWAVES;
     const unsigned cgrid = (unsigned)(cwant < 1024 ? cwant : 1024);
     hipLaunchKernelGGL((long_combine_kernel<KeyT, LPR, CPL, BF16>), dim3(cgrid), dim3(UPD_BLOCK), 0, a.stream,
                        a.tables_dev, a.T, keys, pay, chunks, inv_D, a.lr, a.eps, bdiv, ctrl, segs, multi_list,

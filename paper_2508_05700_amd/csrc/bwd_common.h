@@ -4,13 +4,11 @@
 
 struct BwdCtrl {
     uint32_t abort;        // offsets are not a partition of [0, nnz): do nothing
-    uint32_t long_count;   // entries in the long-segment list
+    uint32_t reserved0;
     uint32_t n_valid;      // records whose key is not the sentinel
     uint32_t num_unique;   // U
-    uint32_t chunk_count;  // chunk tasks created for queued runs
-    uint32_t partial_count;  // chunk-sum slots handed out
-    uint32_t multi_count;    // queued runs of several chunks
-    uint32_t pad[57];
+    unsigned long long task_and_multi_count;  // low half: chunk tasks; high half: queued runs of several chunks
+    uint32_t pad[58];
 };
 static_assert(sizeof(BwdCtrl) == 256, "control block is one 256-byte line");
 
@@ -30,6 +28,7 @@ constexpr int UPD_LOOK = 32;         // records of look-ahead after a span
 constexpr int UPD_SHORT_MAX = 32;    // longest run the short-run kernel sums itself
 constexpr int UPD_QSLOTS = UPD_SPAN / (UPD_SHORT_MAX + 1) + 1;  // runs longer than that which can start in one span
 constexpr int LONG_CHUNK = 256;     // records of a queued run summed by one wavefront
+constexpr int PREP_BLOCK = 1024;     // workgroup of the kernel that turns queued runs into tasks
 constexpr int UPD_LDS_TABLES = 512; // table directories up to this size are staged in LDS
 
 struct LongSeg {

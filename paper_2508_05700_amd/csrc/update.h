@@ -24,12 +24,12 @@
 // timing, but queued runs are independent of each other, so values are not.
 //
 // Queued runs.  A second kernel finds the end of every queued run (galloping
-// then bisecting in the sorted keys), cuts it into LONG_CHUNK-record chunks and
+// then narrowing in the sorted keys, eight probes per round trip), cuts it into LONG_CHUNK-record chunks and
 // makes one task per chunk.  A third kernel gives each task to one wavefront,
 // whose lane groups take the chunk's records round-robin and are then combined
 // by a fixed butterfly; a run of one chunk is finished there, runs of several
-// chunks store their chunk sums and a last small kernel adds them in chunk
-// order and applies Adagrad.  (The kernel boundary is what makes the chunk sums
+// chunks store their chunk sums and a last small kernel, one wavefront per run,
+// adds them in a fixed order and applies Adagrad.  (The kernel boundary is what makes the chunk sums
 // visible: a device-wide fence inside a kernel writes back the whole L2 of the
 // issuing XCD, dirty table rows included, and was far more expensive.)  All
 // sums are taken in a fixed order: results are bit-identical from run to run.
@@ -421,22 +421,22 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
 // One thread per queue slot: find the run's end, cut it into chunks, create the
 // tasks.  Also adds up the per-wavefront run counts of the short-run kernel.
 template <typename KeyT>
-__global__ __launch_bounds__(256) void long_prepare_kernel(const KeyT *__restrict__ keys, uint32_t n, BwdCtrl *ctrl,
+__global__ __launch_bounds__(PREP_BLOCK) void long_prepare_kernel(const KeyT *__restrict__ keys, uint32_t n, KeyT sentinel,
+                                                           BwdCtrl *ctrl,
                                                            const uint32_t *__restrict__ queue, uint32_t slots,
                                                            const uint32_t *__restrict__ wave_heads,
                                                            uint32_t n_wave_heads, LongSeg *__restrict__ segs,
                                                            uint32_t *__restrict__ multi_list,
-                                                           uint2 *__restrict__ chunk_tasks, uint32_t chunk_cap,
-                                                           uint32_t partial_cap)
+                                                           uint2 *__restrict__ chunk_tasks, uint32_t chunk_cap)
 {
     if (ctrl->abort) return;
-    __shared__ uint32_t wave_sums[256 / EMB_WAVE];
-    const uint32_t s = blockIdx.x * 256 + threadIdx.x;
+    __shared__ uint32_t wave_sums[PREP_BLOCK / EMB_WAVE];
+    const uint32_t s = blockIdx.x * PREP_BLOCK + threadIdx.x;
 
     // distinct rows: sum of the run counts
     {
         uint32_t h = s < n_wave_heads ? wave_heads[s] : 0u, total;
-        block_inclusive_scan<uint32_t, 256>(h, wave_sums, total);
+        block_inclusive_scan<uint32_t, PREP_BLOCK>(h, wave_sums, total);
         if (threadIdx.x == 0 && total) atomicAdd(&ctrl->num_unique, total);
     }
 
@@ -445,54 +445,76 @@ __global__ __launch_bounds__(256) void long_prepare_kernel(const KeyT *__restric
     uint32_t hi = 0, chunks = 0;
     if (lo != 0xFFFFFFFFu) {
         const KeyT key = keys[lo];
-        // gallop: the run is longer than UPD_LOOK records
-        uint32_t step = UPD_LOOK;
-        uint32_t a = lo + 1, b = n;                 // the first record whose key differs lies in [a, b]
-        for (;;) {
-            const uint32_t probe = lo + step;
-            if (probe >= n) break;
-            if (keys[probe] == key) {
-                a = probe + 1;
-                if (step >= 0x40000000u) break;
-                step <<= 1;
-            } else {
-                b = probe;
-                break;
+        // The first record whose key differs lies in [a, b] (b == n: none does).  Eight probes are
+        // requested together in every round, so the search takes a few memory round trips.
+        // The run is longer than UPD_LOOK records, so the gallop starts there.
+        uint32_t a = lo + 1, b = n;
+        bool bracketed = false;
+        for (uint32_t j0 = 0; j0 < 27 && !bracketed; j0 += 8) {
+            KeyT pk[8];
+            uint32_t pp[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint64_t at = (uint64_t)lo + ((uint64_t)UPD_LOOK << (j0 + j));
+                pp[j] = at < n ? (uint32_t)at : n;
+                pk[j] = pp[j] < n ? keys[pp[j]] : sentinel;   // the sentinel differs from every run's key
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (bracketed) continue;
+                if (pk[j] == key) a = pp[j] + 1;
+                else { b = pp[j]; bracketed = true; }
             }
         }
         while (a < b) {
-            const uint32_t mid = a + ((b - a) >> 1);
-            if (keys[mid] == key) a = mid + 1; else b = mid;
+            const uint32_t step = (b - a + 8) / 9;                // >= 1
+            KeyT pk[8];
+            uint32_t pp[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint64_t at = (uint64_t)a + (uint64_t)step * (j + 1) - 1;
+                pp[j] = at < b ? (uint32_t)at : b;                 // b itself is known to differ (or is n)
+                pk[j] = pp[j] < b ? keys[pp[j]] : sentinel;
+            }
+            bool cut = false;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (cut) continue;
+                if (pp[j] >= b) { cut = true; continue; }
+                if (pk[j] == key) a = pp[j] + 1;
+                else { b = pp[j]; cut = true; }
+            }
         }
         hi = a;
         chunks = (hi - lo + LONG_CHUNK - 1) / LONG_CHUNK;
     }
-    // task slots: an exclusive scan inside the workgroup, one atomic per workgroup
-    uint32_t total_chunks, total_part, total_multi;
-    const uint32_t inc_c = block_inclusive_scan<uint32_t, 256>(chunks, wave_sums, total_chunks);
-    const uint32_t part = chunks > 1 ? chunks : 0u;   // chunk sums are stored only for runs of several chunks
-    const uint32_t inc_p = block_inclusive_scan<uint32_t, 256>(part, wave_sums, total_part);
+    // task slots: exclusive scans inside the workgroup, then ONE atomic per workgroup on a packed
+    // counter (tasks in the low half, runs of several chunks in the high half): same-address
+    // device atomics are slow, and there are hundreds of workgroups
+    uint32_t total_chunks, total_multi;
+    const uint32_t inc_c = block_inclusive_scan<uint32_t, PREP_BLOCK>(chunks, wave_sums, total_chunks);
     const uint32_t multi = chunks > 1 ? 1u : 0u;
-    const uint32_t inc_m = block_inclusive_scan<uint32_t, 256>(multi, wave_sums, total_multi);
-    __shared__ uint32_t s_base_c, s_base_p, s_base_m;
+    const uint32_t inc_m = block_inclusive_scan<uint32_t, PREP_BLOCK>(multi, wave_sums, total_multi);
+    __shared__ unsigned long long s_base;
     if (threadIdx.x == 0) {
-        s_base_c = total_chunks ? atomicAdd(&ctrl->chunk_count, total_chunks) : 0u;
-        s_base_p = total_part ? atomicAdd(&ctrl->partial_count, total_part) : 0u;
-        s_base_m = total_multi ? atomicAdd(&ctrl->multi_count, total_multi) : 0u;
+        s_base = 0;
+        if (total_chunks)
+            s_base = atomicAdd(&ctrl->task_and_multi_count,
+                               (unsigned long long)total_chunks | ((unsigned long long)total_multi << 32));
     }
     __syncthreads();
     if (chunks) {
-        const uint32_t cbase = s_base_c + inc_c - chunks;
-        const uint32_t pbase = s_base_p + inc_p - part;
+        const uint32_t cbase = (uint32_t)s_base + inc_c - chunks;
+        const uint32_t mbase = (uint32_t)(s_base >> 32) + inc_m - multi;
         LongSeg sg;
         sg.lo = lo;
         sg.hi = hi;
-        sg.chunk_base = pbase;
-        // the caps cannot be exceeded (see the workspace layout); the check only guards memory
-        sg.n_chunks = (cbase + chunks <= chunk_cap && pbase + part <= partial_cap) ? chunks : 0u;
+        sg.chunk_base = cbase;   // the chunk sums of a run use the slots of its tasks
+        // the cap cannot be exceeded (see the workspace layout); the check only guards memory
+        sg.n_chunks = (cbase + chunks <= chunk_cap) ? chunks : 0u;
         segs[s] = sg;
         for (uint32_t c = 0; c < sg.n_chunks; ++c) chunk_tasks[cbase + c] = make_uint2(s, c);
-        if (sg.n_chunks > 1) multi_list[s_base_m + inc_m - 1] = s;   // at most one entry per slot
+        if (sg.n_chunks > 1 && mbase < slots) multi_list[mbase] = s;
     }
 }
 
@@ -542,7 +564,7 @@ __global__ __launch_bounds__(UPD_BLOCK) void long_reduce_kernel(const emb_table 
     const int l = lane % LPR;
     const int g = lane / LPR;
     const int64_t row_floats = (int64_t)chunks_per_row * F;
-    uint32_t tasks = ctrl->chunk_count;
+    uint32_t tasks = (uint32_t)ctrl->task_and_multi_count;
     if (tasks > chunk_cap) tasks = chunk_cap;
     const uint32_t waves = gridDim.x * (UPD_BLOCK / EMB_WAVE);
 
@@ -555,32 +577,45 @@ __global__ __launch_bounds__(UPD_BLOCK) void long_reduce_kernel(const emb_table 
         GradAcc<BF16> acc[CPL];
 #pragma unroll
         for (int c = 0; c < CPL; ++c) acc[c].zero();
-        for (uint32_t i0 = lo + g; i0 < hi; i0 += GPW * EU) {
-            float4 v[EU][CPL][V];
-            float sc[EU];
+        // a group's records are lo + g, lo + g + GPW, ...: their bags are requested PF at a time,
+        // then the gradient rows EU at a time, so a chunk costs few dependent memory round trips
+        constexpr int PF = (LONG_CHUNK / GPW) < 16 ? (LONG_CHUNK / GPW) : 16;
+        static_assert(PF % EU == 0, "prefetch depth must be whole sub-batches");
+        for (uint32_t i0 = lo + g; i0 < hi; i0 += GPW * PF) {
+            uint32_t bags[PF];
 #pragma unroll
-            for (int u = 0; u < EU; ++u) {
+            for (int u = 0; u < PF; ++u) {
                 const uint32_t i = i0 + u * GPW;
-                sc[u] = 0.f;
-#pragma unroll
-                for (int c = 0; c < CPL; ++c)
-#pragma unroll
-                    for (int x = 0; x < V; ++x) v[u][c][x] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (i < hi) {
-                    const uint32_t bag = pay[i];
-                    sc[u] = bag_scale[bag];
-                    const float *grow = dout + (int64_t)bag * D;
-#pragma unroll
-                    for (int c = 0; c < CPL; ++c) {
-                        const int chunk = l + c * LPR;
-                        if (chunk < chunks_per_row) load_grad<BF16>(grow + (int64_t)chunk * F, v[u][c]);
-                    }
-                }
+                bags[u] = i < hi ? pay[i] : 0xFFFFFFFFu;
             }
 #pragma unroll
-            for (int u = 0; u < EU; ++u)
+            for (int u0 = 0; u0 < PF; u0 += EU) {
+                if (bags[u0] == 0xFFFFFFFFu) continue;   // past the end of the chunk
+                float4 v[EU][CPL][V];
+                float sc[EU];
 #pragma unroll
-                for (int c = 0; c < CPL; ++c) acc[c].fma(sc[u], v[u][c]);
+                for (int u = 0; u < EU; ++u) {
+                    const uint32_t bag = bags[u0 + u];
+                    sc[u] = 0.f;
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                        for (int x = 0; x < V; ++x) v[u][c][x] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (bag != 0xFFFFFFFFu) {
+                        sc[u] = bag_scale[bag];
+                        const float *grow = dout + (int64_t)bag * D;
+#pragma unroll
+                        for (int c = 0; c < CPL; ++c) {
+                            const int chunk = l + c * LPR;
+                            if (chunk < chunks_per_row) load_grad<BF16>(grow + (int64_t)chunk * F, v[u][c]);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < EU; ++u)
+#pragma unroll
+                    for (int c = 0; c < CPL; ++c) acc[c].fma(sc[u], v[u][c]);
+            }
         }
         // butterfly over the lane groups of the wavefront: every group ends with the chunk sum
 #pragma unroll
@@ -611,8 +646,9 @@ __global__ __launch_bounds__(UPD_BLOCK) void long_reduce_kernel(const emb_table 
     }
 }
 
-// Runs of several chunks: one lane group per run adds the chunk sums in chunk
-// order and applies Adagrad.  Also publishes the number of distinct rows.
+// Runs of several chunks: one wavefront per run.  Its lane groups take the chunk
+// sums round-robin in chunk order and are combined by the same fixed butterfly,
+// then Adagrad is applied.  Also publishes the number of distinct rows.
 template <typename KeyT, int LPR, int CPL, bool BF16>
 __global__ __launch_bounds__(UPD_BLOCK) void long_combine_kernel(const emb_table *__restrict__ tables, int32_t T,
                                                                  const KeyT *__restrict__ keys,
@@ -629,29 +665,33 @@ __global__ __launch_bounds__(UPD_BLOCK) void long_combine_kernel(const emb_table
     if (blockIdx.x == 0 && threadIdx.x == 0 && num_unique_out) *num_unique_out = (int64_t)ctrl->num_unique;
     EMB_STAGE_TABLE_DIR(dir, tables, T, UPD_BLOCK)
     __syncthreads();
-    constexpr int GROUPS = UPD_BLOCK / LPR;
+    constexpr int GPW = EMB_WAVE / LPR;
     constexpr int F = GradAcc<BF16>::F;
     constexpr int V = GradAcc<BF16>::V;
-    constexpr int CU = 4;  // chunk sums requested together
-    const int l = threadIdx.x % LPR;
+    constexpr int CU = 2;  // chunk sums a group requests together
+    const int lane = threadIdx.x & (EMB_WAVE - 1);
+    const int l = lane % LPR;
+    const int g = lane / LPR;
     const int64_t row_floats = (int64_t)chunks_per_row * F;
-    uint32_t count = ctrl->multi_count;
+    uint32_t count = (uint32_t)(ctrl->task_and_multi_count >> 32);
     if (count > multi_cap) count = multi_cap;
-    for (uint32_t m = blockIdx.x * GROUPS + threadIdx.x / LPR; m < count; m += gridDim.x * GROUPS) {
+    const uint32_t waves = gridDim.x * (UPD_BLOCK / EMB_WAVE);
+    for (uint32_t m = blockIdx.x * (UPD_BLOCK / EMB_WAVE) + threadIdx.x / EMB_WAVE; m < count; m += waves) {
         const LongSeg sg = segs[multi_list[m]];
         GradAcc<BF16> acc[CPL];
 #pragma unroll
         for (int c = 0; c < CPL; ++c) acc[c].zero();
-        for (uint32_t c0 = 0; c0 < sg.n_chunks; c0 += CU) {
+        for (uint32_t c0 = g; c0 < sg.n_chunks; c0 += GPW * CU) {
             float4 v[CU][CPL][V];
 #pragma unroll
             for (int u = 0; u < CU; ++u) {
+                const uint32_t cc = c0 + u * GPW;
 #pragma unroll
                 for (int c = 0; c < CPL; ++c)
 #pragma unroll
                     for (int x = 0; x < V; ++x) v[u][c][x] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (c0 + u < sg.n_chunks) {
-                    const float *slot = partials + (int64_t)(sg.chunk_base + c0 + u) * row_floats;
+                if (cc < sg.n_chunks) {
+                    const float *slot = partials + (int64_t)(sg.chunk_base + cc) * row_floats;
 #pragma unroll
                     for (int c = 0; c < CPL; ++c) {
                         const int chunk = l + c * LPR;
@@ -664,6 +704,13 @@ __global__ __launch_bounds__(UPD_BLOCK) void long_combine_kernel(const emb_table
 #pragma unroll
                 for (int c = 0; c < CPL; ++c) acc[c].fma(1.0f, v[u][c]);
         }
-        finish_run<KeyT, LPR, CPL, BF16>(acc, dir, bdiv, keys, pay, sg.lo, l, chunks_per_row, inv_D, lr, eps);
+#pragma unroll
+        for (int d = LPR; d < EMB_WAVE; d <<= 1)
+#pragma unroll
+            for (int c = 0; c < CPL; ++c)
+#pragma unroll
+                for (int i = 0; i < F; ++i) acc[c].a[i] += __shfl_xor(acc[c].a[i], d, EMB_WAVE);
+        if (g == 0)
+            finish_run<KeyT, LPR, CPL, BF16>(acc, dir, bdiv, keys, pay, sg.lo, l, chunks_per_row, inv_D, lr, eps);
     }
 }
