@@ -41,11 +41,13 @@ struct BwdLayout {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-// Lanes per row / chunks per lane for the update: as few lanes as keep at least
-// 64 contiguous bytes per row and load instruction, up to 4 chunks per lane.
+// Lanes per row / chunks per lane for the update: two 16-byte chunks per lane while
+// that leaves at least 4 lanes (64 contiguous bytes per row and load instruction);
+// measured best on 256-byte rows (8 lanes x 2 chunks: 8 rows per wavefront
+// instruction) against 4 x 4 and 16 x 1.
 inline void upd_row_split(int chunks, int &lpr, int &cpl)
 {
-    int want = (chunks + 3) / 4;
+    int want = (chunks + 1) / 2;
     if (want < 4) want = chunks < 4 ? chunks : 4;
     lpr = 1;
     while (lpr < want && lpr < 64) lpr <<= 1;
@@ -420,10 +422,10 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
         case 201: EMB_UPD(2, 1, 4);
         case 401: EMB_UPD(4, 1, 4);
         case 402: EMB_UPD(4, 2, 4);
-        case 404: EMB_UPD(4, 4, 2);
-        case 804: EMB_UPD(8, 4, 2);
-        case 1604: EMB_UPD(16, 4, 2);
-        case 3204: EMB_UPD(32, 4, 2);
+        case 802: EMB_UPD(8, 2, 4);
+        case 1602: EMB_UPD(16, 2, 4);
+        case 3202: EMB_UPD(32, 2, 4);
+        case 6402: EMB_UPD(64, 2, 4);
         case 6404: EMB_UPD(64, 4, 2);
         case 6408: EMB_UPD(64, 8, 1);
         case 6416: EMB_UPD(64, 16, 1);

@@ -22,7 +22,7 @@ constexpr int SORT_TILE = SORT_BLOCK * SORT_ITEMS;  // 4096 records per workgrou
 constexpr int TOTAL_SLOTS = 32;                     // digit totals are spread over this many slots per digit
 constexpr int SORT_PAD = 320;                       // records of slack after the key / payload arrays
 
-constexpr int UPD_BLOCK = 256;
+constexpr int UPD_BLOCK = 128;       // two wavefronts: measured better than four for the update kernels
 constexpr int UPD_SPAN = 256;        // sorted records per wavefront in the update
 constexpr int UPD_LOOK = 32;         // records of look-ahead after a span
 constexpr int UPD_SHORT_MAX = 32;    // longest run the short-run kernel sums itself

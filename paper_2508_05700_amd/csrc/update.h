@@ -2,12 +2,13 @@
 // update, working directly on the sorted (key, bag) records.
 //
 // Mapping.  A table row of `chunks` 16-byte chunks is covered by a group of LPR
-// lanes holding CPL chunks each, with CPL as large as 4: a 256-byte row takes 4
-// lanes, so a wavefront works on 16 rows at a time.  The work per row that is
-// not per element (finding the run, addresses, the Adagrad scalars) is then
-// paid once per 16 rows of a wavefront instruction instead of once per 4; with
-// 64-wide wavefronts on 16-lane SIMDs that instruction count, not HBM, was the
-// limit of a 16-lanes-per-row mapping.
+// lanes holding CPL chunks each, normally CPL = 2: a 256-byte row takes 8 lanes,
+// so a wavefront works on 8 rows at a time.  The work per row that is not per
+// element (finding the run, addresses, the Adagrad scalars) is then paid once
+// per 8 rows of a wavefront instruction; with 64-wide wavefronts on 16-lane
+// SIMDs that instruction count, not HBM, was the limit of a 16-lanes-per-row
+// mapping with per-lane-group control flow.  (4 lanes x 4 chunks halves the
+// instruction count again but costs registers and occupancy; measured slower.)
 //
 // Short runs.  Each wavefront takes UPD_SPAN consecutive sorted records and
 // owns every run of equal keys that starts in that span.  It stages the keys
