@@ -43,12 +43,174 @@ def backward_bytes(nnz: int, bags: int, uniq: int, D: int, esz: int, passes: int
     return nnz * (8 + 16 * passes) + bags * 4 * D + uniq * (2 * D * esz + 8)
 
 
+def cpu_baseline(w, batches_np, seed, min_seconds=10.0, max_batches=8):
+    """The oracle, untuned, single thread, on whole batches of the same workload until about
+    ``min_seconds`` of oracle time have been spent.  Host tables are full-size virtual arrays in
+    which only the rows a batch touches are materialised (building them is not timed); the
+    oracle's gathers then hit the same scattered addresses a fully materialised table would."""
+    import numpy as np
+
+    from oracle import emb_oracle as oracle
+    from paper_2508_05700_amd import workloads as wl
+
+    t_index = t_f = t_b = 0.0
+    lookups = 0
+    used = 0
+    for b in batches_np[:max_batches]:
+        t0 = time.perf_counter()
+        off, _ = oracle.lengths_to_offsets(b["lengths"])
+        if b["raw"] is not None:
+            rows_np = np.concatenate([oracle.hash_ids(b["raw"][off[t * w.B]:off[(t + 1) * w.B]], w.salt(t), w.R)
+                                      for t in range(w.T)])
+        else:
+            rows_np = b["rows"]
+        t_index += time.perf_counter() - t0
+        tables = [wl.sparse_host_table(w.table_seed(t, seed), w.R, w.D, w.dtype,
+                                       rows_np[off[t * w.B]:off[(t + 1) * w.B]]) for t in range(w.T)]
+        t0 = time.perf_counter()
+        oracle.bag_forward(tables, w.dtype, rows_np, off, w.B, w.pool, want_absum=False)
+        t_f += time.perf_counter() - t0
+        if w.backward:
+            acc = [np.zeros(w.R, dtype=np.float32) for _ in range(w.T)]
+            t0 = time.perf_counter()
+            oracle.bag_backward_rowwise_adagrad(tables, acc, w.dtype, rows_np, off, w.B, w.pool, b["dout"], w.lr,
+                                                w.eps, want_G=False)
+            t_b += time.perf_counter() - t0
+        lookups += int(b["nnz"])
+        used += 1
+        del tables
+        if t_index + t_f + t_b >= min_seconds:
+            break
+    t_all = t_index + t_f + t_b
+    log("cpu oracle: %d batches, %.2f s -> %.3g lookups/s on 1 core" % (used, t_all, lookups / t_all))
+    return {"value": round(lookups / t_all, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
+            "sample": "%d full batches of the same workload (%d lookups, all %d tables): offsets+hash %.2f s, "
+                      "forward %.2f s, backward %.2f s of oracle time; single thread; host tables hold only "
+                      "the touched rows" % (used, lookups, w.T, t_index, t_f, t_b)}
+
+
+def bench_hybrid(args) -> int:
+    """Workload 5: pooled lookup over a table in pinned host memory fronted by an HBM cache of the
+    hottest 5 % of rows.  A step is offsets + hashing + the cached forward; misses cross PCIe."""
+    import numpy as np
+    import psutil
+    import torch
+
+    from paper_2508_05700_amd import binding as emb
+    from paper_2508_05700_amd import pipeline, workloads as wl
+
+    seed = wl.DEFAULT_SEED if args.seed is None else args.seed
+    w = wl.WORKLOADS["5"]
+    if args.scale_rows:
+        w = w.scaled(rows=args.scale_rows)
+    elif psutil.virtual_memory().available < 90 * 2 ** 30:
+        w = w.scaled(rows=w.R // 4)
+        log("workload 5 scaled to %d rows: not enough host memory to pin 64 GB" % w.R)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, W = args.steps, args.warmup
+    t_setup = time.time()
+    host = torch.empty((w.R, w.D), dtype=torch.float32, pin_memory=True)
+    ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+    emb.emb_table_fill(ptr, w.R, w.D, "f32", w.table_seed(0, seed))
+    n_hot = int(round(w.hot_fraction * w.R))
+    n_ranks = int(n_hot * 1.06) + 1000
+    hot_raw = torch.from_numpy(wl.hot_raw_ids(w, 0, n_ranks, seed).view(np.int64)).to(dev)
+    hot_rows = torch.empty(n_ranks, dtype=torch.int64, device=dev)
+    emb.emb_hash_ids(hot_raw, w.salt(0), w.R, hot_rows)
+    hot = torch.from_numpy(wl.first_k_distinct_sorted(hot_rows.cpu().numpy(), n_hot)).to(dev)
+    n_hot = hot.numel()
+    del hot_raw, hot_rows
+    index = torch.empty(emb.emb_cache_index_bytes(w.R), dtype=torch.uint8, device=dev)
+    cache = torch.empty((n_hot, w.D), dtype=torch.float32, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    emb.emb_cache_build(ptr, w.R, w.D, "f32", hot, cache, index, status)
+    dbs = [pipeline.DeviceBatch(w, wl.make_batch(w, i, seed), dev) for i in range(args.batches)]
+    max_nnz = max(d.nnz for d in dbs)
+    offsets = torch.empty(w.B + 1, dtype=torch.int64, device=dev)
+    rows = torch.empty(max_nnz, dtype=torch.int64, device=dev)
+    out = torch.empty((1, w.B, w.D), dtype=torch.float32, device=dev)
+    hm = torch.zeros(2, dtype=torch.int64, device=dev)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    log("setup: host table %d x %d f32 (%.1f GB pinned), cache %d rows (%.2f GB), %.1f s" % (
+        w.R, w.D, w.R * w.D * 4 / 1e9, n_hot, n_hot * w.D * 4 / 1e9, time.time() - t_setup))
+
+    def step(db, e=None):
+        if e:
+            e[0].record()
+        emb.emb_lengths_to_offsets(db.lengths, offsets, status)
+        r = rows[:db.nnz]
+        emb.emb_hash_ids(db.raw, w.salt(0), w.R, r)
+        if e:
+            e[1].record()
+        emb.emb_bag_forward_cached(ptr, w.R, w.D, "f32", cache, index, n_hot, r, offsets, w.B, w.pool, out, hm, status)
+        if e:
+            e[2].record()
+
+    for i in range(W):
+        step(dbs[i % len(dbs)])
+    torch.cuda.synchronize()
+    hm.zero_()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(K):
+        step(dbs[(W + k) % len(dbs)], ev[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert int(status.item()) == 0
+    lookups = sum(dbs[(W + k) % len(dbs)].nnz for k in range(K))
+    hits, misses = [int(x) for x in hm.cpu().tolist()]
+    ms_index = sum(e[0].elapsed_time(e[1]) for e in ev) / K
+    ms_fwd = sum(e[1].elapsed_time(e[2]) for e in ev) / K
+    rowb = w.D * 4
+    pcie_gbs = misses / K * rowb / (ms_fwd * 1e-3) / 1e9
+    hbm_gbs = (hits / K * rowb + lookups / K * 24 + w.B * (4 * w.D + 8)) / (ms_fwd * 1e-3) / 1e9
+
+    # what the link delivers to a plain DMA copy from the same pinned buffer (context for the PCIe rate)
+    n_copy = min(w.R, (1 << 30) // rowb)
+    staging = torch.empty((n_copy, w.D), dtype=torch.float32, device=dev)
+    staging.copy_(host[:n_copy], non_blocking=True)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(3):
+        staging.copy_(host[:n_copy], non_blocking=True)
+    c1.record()
+    torch.cuda.synchronize()
+    dma_gbs = 3 * n_copy * rowb / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    log("step %.3f ms: index %.3f, cached forward %.3f; hit rate %.2f %%; misses %.1f GB/s over PCIe "
+        "(DMA copy from the same buffer: %.1f GB/s); HBM side %.0f GB/s" % (
+            elapsed / K * 1e3, ms_index, ms_fwd, 100.0 * hits / max(1, hits + misses), pcie_gbs, dma_gbs, hbm_gbs))
+    PCIE_PEAK = 64.0   # PCIe Gen5 x16, nominal, one direction
+    out_json = {
+        "metric": METRIC, "value": round(lookups / elapsed, 1), "unit": "lookups/s", "n_gpus": 1, "steps": K,
+        "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "5: host-resident table %d rows x dim %d f32 (pinned) + HBM cache of %d hot rows, "
+                               "%d bags, poisson bag lengths (mean %g), zipf IDs alpha=%g over %.0e keys, %s pooling, "
+                               "forward only" % (w.R, w.D, n_hot, w.B, w.mean_len, w.alpha, w.n_keys, w.pool),
+                   "lookups_per_step": round(lookups / K, 1), "resident_batches": len(dbs), "seed": seed},
+        "stages": {"index_ms": round(ms_index, 4), "forward_cached_ms": round(ms_fwd, 4),
+                   "hit_rate": round(hits / max(1, hits + misses), 5), "misses_per_step": round(misses / K, 1)},
+        "roofline": {"kernel": "bag_forward_cached_kernel", "bound": "pcie", "achieved": round(pcie_gbs, 2),
+                     "peak": PCIE_PEAK, "unit": "GB/s", "frac": round(pcie_gbs / PCIE_PEAK, 4), "traffic": None,
+                     "avg_ms": round(ms_fwd, 4), "algorithmic_bytes": int(misses / K * rowb),
+                     "bytes_are": "one table row per miss, read zero-copy from pinned host memory",
+                     "dma_copy_same_buffer_GBps": round(dma_gbs, 1), "hbm_side_GBps": round(hbm_gbs, 1)},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out_json), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="3", help="3 (fwd+bwd, default), 2 or 2u (forward only), 4")
+    ap.add_argument("--workload", default="3", help="3 (fwd+bwd, default), 1, 2, 2u or 4 (forward only), 5 (host table + HBM cache)")
     ap.add_argument("--batches", type=int, default=8, help="distinct resident batches cycled through")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--scale-rows", type=int, default=None, help="rows per table (debug: smaller tables)")
@@ -70,6 +232,8 @@ def main() -> int:
         log("bench.py: no GPU visible")
         return 2
     emb.lib()
+    if args.workload == "5":
+        return bench_hybrid(args)
     seed = wl.DEFAULT_SEED if args.seed is None else args.seed
     w = wl.WORKLOADS[args.workload]
     if args.scale_rows:
@@ -212,36 +376,7 @@ def main() -> int:
     # ---- CPU baseline: the oracle, as it stands, on this host ----------------
     cpu = None
     if not args.no_cpu_baseline:
-        from oracle import emb_oracle as oracle
-        b = batches_np[0]
-        t_cpu = time.perf_counter()
-        off, _ = oracle.lengths_to_offsets(b["lengths"])
-        if b["raw"] is not None:
-            rows_np = np.concatenate([oracle.hash_ids(b["raw"][off[t * w.B]:off[(t + 1) * w.B]], w.salt(t), w.R)
-                                      for t in range(w.T)])
-        else:
-            rows_np = b["rows"]
-        t_hash = time.perf_counter() - t_cpu
-        # host tables: full-size virtual arrays in which only the rows this batch touches are
-        # materialised (untimed); the oracle's gathers then hit the same scattered addresses
-        tables = [wl.sparse_host_table(w.table_seed(t, seed), w.R, w.D, w.dtype,
-                                       rows_np[off[t * w.B]:off[(t + 1) * w.B]]) for t in range(w.T)]
-        t_cpu = time.perf_counter()
-        oracle.bag_forward(tables, w.dtype, rows_np, off, w.B, w.pool, want_absum=False)
-        t_f = time.perf_counter() - t_cpu
-        t_b = 0.0
-        if w.backward:
-            acc = [np.zeros(w.R, dtype=np.float32) for _ in range(w.T)]
-            t_cpu = time.perf_counter()
-            oracle.bag_backward_rowwise_adagrad(tables, acc, w.dtype, rows_np, off, w.B, w.pool, b["dout"], w.lr,
-                                                w.eps, want_G=False)
-            t_b = time.perf_counter() - t_cpu
-        t_all = t_hash + t_f + t_b
-        cpu = {"value": round(int(b["nnz"]) / t_all, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
-               "sample": "one full batch of the same workload (%d lookups, all %d tables): offsets+hash %.2f s, "
-                         "forward %.2f s, backward %.2f s; single thread; host tables hold only the touched rows"
-                         % (int(b["nnz"]), w.T, t_hash, t_f, t_b)}
-        log("cpu oracle: %.2f s per step -> %.3g lookups/s on 1 core" % (t_all, cpu["value"]))
+        cpu = cpu_baseline(w, batches_np, seed)
 
     value = lookups / elapsed
     out = {
