@@ -46,6 +46,23 @@ struct ChunkAcc<true> {
 
 __device__ __forceinline__ uint4 load_chunk(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
 
+// Streaming variants for data that is touched once (the rows and accumulators the update
+// rewrites): they are marked non-temporal so that they do not push reusable lines (hot
+// rows, gradient rows) out of L2 and the memory-side cache.
+typedef uint32_t emb_u4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_chunk_nt(const char *p)
+{
+    const emb_u4 v = __builtin_nontemporal_load(reinterpret_cast<const emb_u4 *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_chunk_nt(char *p, const uint4 &x)
+{
+    emb_u4 v;
+    v.x = x.x; v.y = x.y; v.z = x.z; v.w = x.w;
+    __builtin_nontemporal_store(v, reinterpret_cast<emb_u4 *>(p));
+}
+
+
 __device__ __forceinline__ int64_t shfl_i64(int64_t v, int src, int width)
 {
     int lo = __shfl((int)(uint32_t)(uint64_t)v, src, width);

@@ -211,10 +211,10 @@ __device__ __forceinline__ void adagrad_apply(const GradAcc<BF16> (&acc)[CPL], u
                 x.z = __float_as_uint(__uint_as_float(x.z) - step * acc[c].a[2]);
                 x.w = __float_as_uint(__uint_as_float(x.w) - step * acc[c].a[3]);
             }
-            *reinterpret_cast<uint4 *>(wrow + (int64_t)chunk * 16) = x;
+            store_chunk_nt(wrow + (int64_t)chunk * 16, x);
         }
     }
-    if (l == 0) *aptr = s_new;
+    if (l == 0) __builtin_nontemporal_store(s_new, aptr);
 }
 
 // NB consecutive records starting at an address aligned to their total size.
@@ -369,9 +369,9 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
             for (int c = 0; c < CPL; ++c) {
                 const int chunk = l + c * LPR;
                 w[c] = make_uint4(0, 0, 0, 0);
-                if (chunk < chunks_per_row) w[c] = load_chunk(wrow + (int64_t)chunk * 16);
+                if (chunk < chunks_per_row) w[c] = load_chunk_nt(wrow + (int64_t)chunk * 16);
             }
-            const float s_old = *aptr;
+            const float s_old = __builtin_nontemporal_load(aptr);
             GradAcc<BF16> acc[CPL];
 #pragma unroll
             for (int c = 0; c < CPL; ++c) acc[c].zero();
