@@ -219,8 +219,9 @@ def emb_bag_backward_rowwise_adagrad(tables: TableSet, rows: torch.Tensor, offse
                                      num_unique: Optional[torch.Tensor] = None,
                                      status: Optional[torch.Tensor] = None,
                                      stage_events: Optional[Sequence[torch.cuda.Event]] = None) -> None:
-    """``stage_events``: BWD_STAGE_EVENTS torch events that have been recorded at least once
-    (so that their HIP handles exist); the library records them between its stages."""
+    """``stage_events``: BWD_STAGE_EVENTS entries, each None or a torch event that has been
+    recorded at least once (so that its HIP handle exists); the library records the given ones
+    between its stages."""
     nnz = rows.numel()
     if offsets.numel() != tables.T * B + 1 or dout.numel() != tables.T * B * tables.D:
         raise TypeError("shape mismatch")
@@ -231,7 +232,7 @@ def emb_bag_backward_rowwise_adagrad(tables: TableSet, rows: torch.Tensor, offse
     if stage_events is not None:
         if len(stage_events) != BWD_STAGE_EVENTS:
             raise TypeError("stage_events must hold %d events" % BWD_STAGE_EVENTS)
-        ev = (C.c_void_p * BWD_STAGE_EVENTS)(*[int(e.cuda_event) for e in stage_events])
+        ev = (C.c_void_p * BWD_STAGE_EVENTS)(*[None if e is None else int(e.cuda_event) for e in stage_events])
     _check("emb_bag_backward_rowwise_adagrad", lib().emb_bag_backward_rowwise_adagrad(
         tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype],
         _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode],
