@@ -27,7 +27,7 @@ namespace {
 // workspace
 // ---------------------------------------------------------------------------
 struct BwdLayout {
-    size_t ctrl, totals, keys_a, keys_b, pay_a, pay_b, bag_scale, hist, tile_heads, seg_start, queue, wave_heads, segs,
+    size_t ctrl, keys_a, keys_b, pay_a, pay_b, bag_scale, hist, tile_heads, seg_start, queue, wave_heads, segs,
         multi_list, chunk_tasks, partials, total;
     int key_bytes;
     int passes;
@@ -71,7 +71,7 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     L.slots = (nnz + UPD_SPAN - 1) / UPD_SPAN;
     if (L.slots < 1) L.slots = 1;
     const int64_t waves = UPD_BLOCK / EMB_WAVE;
-    L.upd_blocks = (L.slots + waves - 1) / waves;
+    L.upd_blocks = emb_round_up_xcds((L.slots + waves - 1) / waves);
     L.qslots = L.slots * UPD_QSLOTS;
     // every queued run has at least one chunk
     L.chunk_cap = nnz / LONG_CHUNK + L.qslots + 2;
@@ -79,13 +79,12 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     const size_t np = n + SORT_PAD;
     size_t off = 0;
     L.ctrl = off;        off += align256(sizeof(BwdCtrl));
-    L.totals = off;      off += align256(sizeof(uint32_t) * RADIX * TOTAL_SLOTS * MAX_PASSES);
     L.keys_a = off;      off += align256(np * L.key_bytes);
     L.keys_b = off;      off += align256(np * L.key_bytes);
     L.pay_a = off;       off += align256(np * 4);
     L.pay_b = off;       off += align256(np * 4);
     L.bag_scale = off;   off += align256((size_t)T * (size_t)B * 4 + 4);
-    L.hist = off;        off += align256((size_t)L.tiles * RADIX * 4);
+    L.hist = off;        off += align256((size_t)(L.tiles + 1) * RADIX * 4);
     L.tile_heads = off;  off += align256((size_t)L.tiles * 4);
     L.seg_start = off;   off += align256((n + 1) * 4);
     L.queue = off;       off += align256((size_t)L.qslots * 4);
@@ -101,12 +100,10 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
 // ---------------------------------------------------------------------------
 // init + key build
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void bwd_init_kernel(BwdCtrl *ctrl, uint32_t *totals, int passes, uint32_t nnz,
-                                                         int64_t *num_unique_out)
+__global__ __launch_bounds__(64) void bwd_init_kernel(BwdCtrl *ctrl, uint32_t nnz, int64_t *num_unique_out)
 {
     const int i = threadIdx.x;
     if (i < 64) reinterpret_cast<uint32_t *>(ctrl)[i] = (i == 2) ? nnz : 0u;  // n_valid defaults to nnz
-    for (int k = i; k < RADIX * TOTAL_SLOTS * passes; k += 1024) totals[k] = 0;
     if (i == 0 && num_unique_out) *num_unique_out = 0;
 }
 
@@ -317,7 +314,7 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
 
     // one wavefront per task; enough workgroups to fill the chip, tasks beyond that are strided over
     int64_t want = (L.chunk_cap + (UPD_BLOCK / EMB_WAVE) - 1) / (UPD_BLOCK / EMB_WAVE);
-    const unsigned lgrid = (unsigned)(want < 4096 ? want : 4096);
+    const unsigned lgrid = (unsigned)emb_round_up_xcds(want < 4096 ? want : 4096);
     hipLaunchKernelGGL((long_reduce_kernel<KeyT, LPR, CPL, EU, BF16>), dim3(lgrid), dim3(UPD_BLOCK), 0, a.stream,
                        a.tables_dev, a.T, keys, pay, bag_scale, a.dout, chunks, a.D, inv_D, a.lr, a.eps, bdiv, ctrl,
                        segs, chunk_tasks, (uint32_t)L.chunk_cap, partials);
@@ -340,7 +337,6 @@ template <typename KeyT>
 int run_backward(const BwdArgs &a, const BwdLayout &L)
 {
     BwdCtrl *ctrl = reinterpret_cast<BwdCtrl *>(a.ws + L.ctrl);
-    uint32_t *totals = reinterpret_cast<uint32_t *>(a.ws + L.totals);
     KeyT *keys_a = reinterpret_cast<KeyT *>(a.ws + L.keys_a);
     KeyT *keys_b = reinterpret_cast<KeyT *>(a.ws + L.keys_b);
     uint32_t *pay_a = reinterpret_cast<uint32_t *>(a.ws + L.pay_a);
@@ -355,7 +351,7 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
     hipStream_t s = a.stream;
 
     EMB_MARK(a, 0);
-    hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, s, ctrl, totals, L.passes, n, a.num_unique_out);
+    hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(64), 0, s, ctrl, n, a.num_unique_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
     if (a.nnz == 0) {
         for (int i = 1; i < EMB_BWD_STAGE_EVENTS; ++i) EMB_MARK(a, i);
@@ -375,11 +371,10 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
     uint32_t *pin = pay_a, *pout = pay_b;
     for (int p = 0; p < L.passes; ++p) {
         const int shift = p * RADIX_BITS;
-        uint32_t *tot = totals + (size_t)p * RADIX * TOTAL_SLOTS;
-        hipLaunchKernelGGL(sort_hist_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, n, shift, hist, tiles, tot,
+        hipLaunchKernelGGL(sort_hist_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, n, shift, hist, tiles,
                            ctrl);
         EMB_RETURN_IF_LAUNCH_FAILED();
-        hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX), dim3(1024), 0, s, hist, tiles, tot, ctrl);
+        hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX), dim3(1024), 0, s, hist, tiles, ctrl);
         EMB_RETURN_IF_LAUNCH_FAILED();
         hipLaunchKernelGGL(sort_scatter_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, pin, kout, pout, n,
                            shift, hist, tiles, ctrl);

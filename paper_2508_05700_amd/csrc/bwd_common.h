@@ -19,7 +19,6 @@ constexpr int SORT_BLOCK = 256;
 constexpr int SORT_WAVES = SORT_BLOCK / EMB_WAVE;
 constexpr int SORT_ITEMS = 16;
 constexpr int SORT_TILE = SORT_BLOCK * SORT_ITEMS;  // 4096 records per workgroup
-constexpr int TOTAL_SLOTS = 32;                     // digit totals are spread over this many slots per digit
 constexpr int SORT_PAD = 320;                       // records of slack after the key / payload arrays
 
 constexpr int UPD_BLOCK = 128;       // two wavefronts: measured better than four for the update kernels

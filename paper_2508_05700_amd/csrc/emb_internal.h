@@ -48,6 +48,20 @@ static inline int emb_check_row_shape(int32_t D, int32_t dtype)
     return EMB_OK;
 }
 
+// The chip is 8 accelerator dies (XCDs), each with an L2 of its own, and the
+// workgroups of a launch are dealt to them round-robin by linear id.  With the
+// grid a multiple of 8, this renumbering hands every die one contiguous eighth
+// of the work, so data that neighbouring workgroups share (one table's hot
+// rows, one table's slice of the output gradient) is fetched into one L2, not
+// all eight.  The mapping is a bijection on [0, gridDim.x) whatever the
+// hardware's dealing order is: only locality depends on it, never results.
+constexpr uint32_t EMB_XCDS = 8;
+static inline int64_t emb_round_up_xcds(int64_t blocks) { return (blocks + EMB_XCDS - 1) / EMB_XCDS * EMB_XCDS; }
+__device__ __forceinline__ uint32_t emb_xcd_block(uint32_t linear_block, uint32_t grid_blocks)
+{
+    return (linear_block % EMB_XCDS) * (grid_blocks / EMB_XCDS) + linear_block / EMB_XCDS;
+}
+
 __device__ __forceinline__ void emb_flag(uint32_t *status, uint32_t bit)
 {
     if (status) atomicOr(status, bit);

@@ -2,9 +2,11 @@
 // (paper Sections 2.2 and 3.1): gather the rows a bag selects and sum or
 // average them.
 //
-// One launch covers all tables: blockIdx.y is the table, so the table
-// descriptor is uniform across a workgroup; the gather loop itself lives in
-// gather.h (gather_pool_bag), shared with the cached lookup.
+// One launch covers all tables.  A workgroup serves bags of one table, so the
+// table descriptor is uniform across it, and the workgroups of one table run
+// on one die (emb_xcd_block), whose L2 then holds that table's hot rows once.
+// The gather loop itself lives in gather.h (gather_pool_bag), shared with the
+// cached lookup.
 #include "emb_internal.h"
 #include "gather.h"
 
@@ -29,16 +31,20 @@ struct TableSource {
 };
 
 template <int LPR, int CPL, int UNROLL, bool BF16>
-__global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table *__restrict__ tables, int64_t B,
-                                                                int64_t nnz, const int64_t *__restrict__ rows,
+__global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table *__restrict__ tables, int32_t T, int64_t B,
+                                                                uint32_t blocks_per_table, int64_t nnz,
+                                                                const int64_t *__restrict__ rows,
                                                                 const int64_t *__restrict__ offsets,
                                                                 int32_t chunks_per_row, int32_t mode,
                                                                 float *__restrict__ out, uint32_t *status)
 {
     constexpr int GROUPS = FWD_BLOCK / LPR;
-    const int t = blockIdx.y;
+    const uint32_t lb = emb_xcd_block(blockIdx.x, gridDim.x);
+    const uint32_t t_raw = lb / blocks_per_table;
+    const bool tail = t_raw >= (uint32_t)T;          // the grid is rounded up to whole dies
+    const int t = tail ? T - 1 : (int)t_raw;
     const int l = threadIdx.x % LPR;
-    const int64_t b = (int64_t)blockIdx.x * GROUPS + threadIdx.x / LPR;
+    const int64_t b = tail ? B : (int64_t)(lb % blocks_per_table) * GROUPS + threadIdx.x / LPR;
     const emb_table tb = tables[t];
     TableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, (int64_t)chunks_per_row * 16,
                     status};
@@ -47,18 +53,21 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table 
 }
 
 template <int LPR, int CPL, int UNROLL>
-int launch_forward(bool bf16, dim3 grid, hipStream_t s, const emb_table *tables, int64_t B, int64_t nnz,
+int launch_forward(bool bf16, int32_t T, hipStream_t s, const emb_table *tables, int64_t B, int64_t nnz,
                    const int64_t *rows, const int64_t *offsets, int32_t chunks, int32_t mode, float *out,
                    uint32_t *status)
 {
     constexpr int GROUPS = FWD_BLOCK / LPR;
-    grid.x = (unsigned)((B + GROUPS - 1) / GROUPS);
+    const int64_t per_table = (B + GROUPS - 1) / GROUPS;
+    const int64_t blocks = emb_round_up_xcds(per_table * T);
+    if (blocks > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)blocks);
     if (bf16)
-        hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, true>), grid, dim3(FWD_BLOCK), 0, s, tables, B, nnz,
-                           rows, offsets, chunks, mode, out, status);
+        hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, true>), grid, dim3(FWD_BLOCK), 0, s, tables, T, B,
+                           (uint32_t)per_table, nnz, rows, offsets, chunks, mode, out, status);
     else
-        hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, false>), grid, dim3(FWD_BLOCK), 0, s, tables, B, nnz,
-                           rows, offsets, chunks, mode, out, status);
+        hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, false>), grid, dim3(FWD_BLOCK), 0, s, tables, T, B,
+                           (uint32_t)per_table, nnz, rows, offsets, chunks, mode, out, status);
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -85,10 +94,9 @@ extern "C" int emb_bag_forward(const emb_table *tables_host, const emb_table *ta
     int lpr, cpl;
     emb_row_split(chunks, lpr, cpl);
     const bool bf16 = dtype == EMB_BF16;
-    dim3 grid(1, (unsigned)T, 1);
     hipStream_t s = emb_stream(stream);
 #define EMB_FWD(L, C, U) \
-    return launch_forward<L, C, U>(bf16, grid, s, tables_dev, B, nnz, rows_dev, offsets_dev, chunks, mode, out_dev, status_dev)
+    return launch_forward<L, C, U>(bf16, T, s, tables_dev, B, nnz, rows_dev, offsets_dev, chunks, mode, out_dev, status_dev)
     if (cpl == 1) {
         switch (lpr) {
             case 1: EMB_FWD(1, 1, 8);

@@ -44,13 +44,11 @@ __device__ __forceinline__ void wave_rank_digits(const KeyT (&key)[SORT_ITEMS], 
     }
 }
 
-// Digit totals are accumulated into TOTAL_SLOTS slots per digit (tile b adds to
-// slot b % TOTAL_SLOTS) so that hundreds of tiles do not queue on one address.
+// hist is [RADIX][tiles + 1]: row d holds digit d's count in every tile and, in
+// its last column (written by the scan), the digit's count over all tiles.
 template <typename KeyT>
 __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__restrict__ keys, uint32_t n, int shift,
-                                                               uint32_t *__restrict__ hist /*[RADIX][tiles]*/,
-                                                               uint32_t tiles,
-                                                               uint32_t *__restrict__ totals /*[RADIX][TOTAL_SLOTS]*/,
+                                                               uint32_t *__restrict__ hist, uint32_t tiles,
                                                                const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
@@ -73,25 +71,19 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__res
     uint32_t c = 0;
 #pragma unroll
     for (int w = 0; w < SORT_WAVES; ++w) c += cnt[w][threadIdx.x];
-    hist[threadIdx.x * tiles + blockIdx.x] = c;
-    if (c) atomicAdd(&totals[threadIdx.x * TOTAL_SLOTS + (blockIdx.x % TOTAL_SLOTS)], c);
+    hist[(size_t)threadIdx.x * (tiles + 1) + blockIdx.x] = c;
 }
 static_assert(SORT_BLOCK == RADIX, "histogram kernels map one thread to one digit");
 
-// One workgroup per digit: exclusive scan of that digit's per-tile counts,
-// offset by the number of records with a smaller digit.
+// One workgroup per digit: exclusive scan of that digit's per-tile counts in
+// place; the digit's total goes to the row's last column.
 __global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ hist, uint32_t tiles,
-                                                          const uint32_t *__restrict__ totals,
                                                           const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
     __shared__ uint32_t wave_sums[1024 / EMB_WAVE];
-    const uint32_t d = blockIdx.x;
-    uint32_t below = 0;
-    for (uint32_t i = threadIdx.x; i < d * TOTAL_SLOTS; i += 1024) below += totals[i];
-    uint32_t carry;
-    block_inclusive_scan<uint32_t, 1024>(below, wave_sums, carry);
-    uint32_t *row = hist + (size_t)d * tiles;
+    uint32_t *row = hist + (size_t)blockIdx.x * (tiles + 1);
+    uint32_t carry = 0;
     for (uint32_t b0 = 0; b0 < tiles; b0 += 1024) {
         const uint32_t b = b0 + threadIdx.x;
         const uint32_t v = b < tiles ? row[b] : 0u;
@@ -100,6 +92,7 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ 
         if (b < tiles) row[b] = carry + inc - v;
         carry += total;
     }
+    if (threadIdx.x == 0) row[tiles] = carry;
 }
 
 // Stable scatter of one tile.  After ranking, the tile's records are first put in
@@ -111,13 +104,13 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
                                                                   const uint32_t *__restrict__ pay_in,
                                                                   KeyT *__restrict__ keys_out,
                                                                   uint32_t *__restrict__ pay_out, uint32_t n, int shift,
-                                                                  const uint32_t *__restrict__ hist, uint32_t tiles,
-                                                                  const BwdCtrl *ctrl)
+                                                                  const uint32_t *__restrict__ hist /*scanned*/,
+                                                                  uint32_t tiles, const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
     __shared__ uint32_t cnt[SORT_WAVES][RADIX];  // per-wavefront digit counts, then offsets inside the tile
     __shared__ uint32_t delta[RADIX];            // global position minus tile position, per digit
-    __shared__ uint32_t wave_sums[SORT_WAVES];
+    __shared__ unsigned long long wave_sums[SORT_WAVES];
     __shared__ KeyT sk[SORT_TILE];
     __shared__ uint32_t sp[SORT_TILE];
     const int lane = threadIdx.x & (EMB_WAVE - 1);
@@ -140,25 +133,33 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
     wave_rank_digits<KeyT, true>(key, wbase, n, shift, cnt[wave], rank);
     __syncthreads();
 
-    // thread d: digit d's count in the tile, its start inside the tile (exclusive scan over the
-    // digits), the wavefronts' offsets within it, and the shift to global positions
+    // thread d: digit d's count in the tile, its start inside the tile and the number of records
+    // with a smaller digit anywhere (one scan over the digits of both, packed: the tile counts
+    // add up to at most SORT_TILE, so the low half never carries), the wavefronts' offsets within
+    // it, and the shift to global positions
     {
         const uint32_t d = threadIdx.x;
+        const uint32_t *row = hist + (size_t)d * (tiles + 1);
+        const uint32_t digit_total = row[tiles];
+        const uint32_t before_in_digit = row[blockIdx.x];
         uint32_t c[SORT_WAVES], total = 0;
 #pragma unroll
         for (int w = 0; w < SORT_WAVES; ++w) {
             c[w] = cnt[w][d];
             total += c[w];
         }
-        uint32_t all;
-        const uint32_t start = block_inclusive_scan<uint32_t, SORT_BLOCK>(total, wave_sums, all) - total;
+        unsigned long long all;
+        const unsigned long long inc = block_inclusive_scan<unsigned long long, SORT_BLOCK>(
+            ((unsigned long long)digit_total << 32) | total, wave_sums, all);
+        const uint32_t start = (uint32_t)inc - total;
+        const uint32_t below = (uint32_t)(inc >> 32) - digit_total;
         uint32_t run = start;
 #pragma unroll
         for (int w = 0; w < SORT_WAVES; ++w) {
             cnt[w][d] = run;
             run += c[w];
         }
-        delta[d] = hist[(size_t)d * tiles + blockIdx.x] - start;
+        delta[d] = below + before_in_digit - start;
     }
     __syncthreads();
 

@@ -267,7 +267,8 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
     const int lane = threadIdx.x & (EMB_WAVE - 1);
     const int g = lane / LPR;
     const int l = lane % LPR;
-    const uint64_t wid = (uint64_t)blockIdx.x * WAVES + wave;
+    // sorted records are table-major: one die works on one stretch of tables (emb_xcd_block)
+    const uint64_t wid = (uint64_t)emb_xcd_block(blockIdx.x, gridDim.x) * WAVES + wave;
     const uint64_t first = wid * UPD_SPAN;
     const bool in = first < n;
     const uint32_t i0 = (uint32_t)first;
@@ -567,9 +568,16 @@ __global__ __launch_bounds__(UPD_BLOCK) void long_reduce_kernel(const emb_table 
     const int64_t row_floats = (int64_t)chunks_per_row * F;
     uint32_t tasks = (uint32_t)ctrl->task_and_multi_count;
     if (tasks > chunk_cap) tasks = chunk_cap;
-    const uint32_t waves = gridDim.x * (UPD_BLOCK / EMB_WAVE);
+    // Tasks were created roughly in record order, so neighbours mostly share a table: every die
+    // (the grid is a multiple of EMB_XCDS) takes one contiguous eighth of them, strided over by
+    // its wavefronts, and reads mostly one stretch of the output gradient.
+    const uint32_t per_die = (tasks + EMB_XCDS - 1) / EMB_XCDS;
+    const uint32_t die = blockIdx.x % EMB_XCDS;
+    const uint32_t die_end = (die + 1) * per_die < tasks ? (die + 1) * per_die : tasks;
+    const uint32_t waves = (gridDim.x / EMB_XCDS) * (UPD_BLOCK / EMB_WAVE);
 
-    for (uint32_t task = blockIdx.x * (UPD_BLOCK / EMB_WAVE) + threadIdx.x / EMB_WAVE; task < tasks; task += waves) {
+    for (uint32_t task = die * per_die + (blockIdx.x / EMB_XCDS) * (UPD_BLOCK / EMB_WAVE) + threadIdx.x / EMB_WAVE;
+         task < die_end; task += waves) {
         const uint2 tk = chunk_tasks[task];
         const LongSeg sg = segs[tk.x];
         const uint32_t lo = sg.lo + tk.y * LONG_CHUNK;
