@@ -2,10 +2,12 @@
 // (fine-tuning of table rows, paper Section 3.1).
 //
 // Stages, all on the caller's stream, all in caller-provided workspace:
-//   keys     one (key, bag) record per lookup; key = row_base + row, or the
-//            sentinel total_rows for an out-of-range row; offsets are validated
+//   keys     one (key, bag) record per lookup; key = the row inside its table,
+//            or a marker for an out-of-range row; offsets are validated
 //   sort     stable LSD radix sort of the records by key, 8 bits per pass,
-//            only as many passes as the key range needs          (radix_sort.h)
+//            table by table (the records of a table are contiguous), only as
+//            many passes as the largest table needs; leaves keys row_base + row,
+//            the marker as the sentinel total_rows               (radix_sort.h)
 //   update   runs of equal keys are found on the fly; each run's gradients are
 //            summed in ascending record order and Adagrad is applied once to
 //            its row; long runs are cut into chunks summed by wavefronts (update.h)
@@ -27,12 +29,12 @@ namespace {
 // workspace
 // ---------------------------------------------------------------------------
 struct BwdLayout {
-    size_t ctrl, keys_a, keys_b, pay_a, pay_b, bag_scale, hist, tile_heads, seg_start, queue, wave_heads, segs,
-        multi_list, chunk_tasks, partials, total;
+    size_t ctrl, keys_a, keys_b, pay_a, pay_b, bag_scale, first_tile, tile_desc, hist, tile_heads, seg_start, seg_real,
+        queue, wave_heads, segs, multi_list, chunk_tasks, partials, total;
     int key_bytes;
-    int passes;
     int lpr, cpl;       // lanes per row and chunks per lane of the update kernels
-    int64_t tiles;
+    int64_t tiles;      // tiles of the sort: none straddles two tables
+    int64_t flat_tiles; // tiles of the run-length kernels, which cut [0, nnz) evenly
     int64_t slots;      // wavefronts of the short-run kernel
     int64_t qslots;     // queue slots
     int64_t upd_blocks; // its grid
@@ -60,12 +62,9 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
 {
     BwdLayout L;
     L.key_bytes = ((uint64_t)total_rows < 0xFFFFFFFFull) ? 4 : 8;
-    int bits = 0;
-    for (uint64_t v = (uint64_t)total_rows; v; v >>= 1) ++bits;  // the sentinel total_rows must sort last
-    L.passes = (bits + RADIX_BITS - 1) / RADIX_BITS;
-    if (L.passes < 1) L.passes = 1;
-    L.tiles = (nnz + SORT_TILE - 1) / SORT_TILE;
-    if (L.tiles < 1) L.tiles = 1;
+    L.flat_tiles = (nnz + SORT_TILE - 1) / SORT_TILE;
+    if (L.flat_tiles < 1) L.flat_tiles = 1;
+    L.tiles = nnz / SORT_TILE + (T > 0 ? T : 1);   // sum over tables of ceil(n_t / SORT_TILE) is at most this
     const int esz = dtype == EMB_BF16 ? 2 : 4;
     upd_row_split((int)(((int64_t)D * esz + 15) / 16), L.lpr, L.cpl);
     L.slots = (nnz + UPD_SPAN - 1) / UPD_SPAN;
@@ -84,9 +83,12 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     L.pay_a = off;       off += align256(np * 4);
     L.pay_b = off;       off += align256(np * 4);
     L.bag_scale = off;   off += align256((size_t)T * (size_t)B * 4 + 4);
+    L.first_tile = off;  off += align256(((size_t)T + 1) * 4);
+    L.tile_desc = off;   off += align256((size_t)L.tiles * sizeof(SortTile));
     L.hist = off;        off += align256((size_t)(L.tiles + 1) * RADIX * 4);
-    L.tile_heads = off;  off += align256((size_t)L.tiles * 4);
+    L.tile_heads = off;  off += align256((size_t)L.flat_tiles * 8);
     L.seg_start = off;   off += align256((n + 1) * 4);
+    L.seg_real = off;    off += align256(n * 4);
     L.queue = off;       off += align256((size_t)L.qslots * 4);
     L.wave_heads = off;  off += align256((size_t)L.upd_blocks * (UPD_BLOCK / EMB_WAVE) * 4);
     L.segs = off;        off += align256((size_t)L.qslots * sizeof(LongSeg));
@@ -100,11 +102,73 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
 // ---------------------------------------------------------------------------
 // init + key build
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void bwd_init_kernel(BwdCtrl *ctrl, uint32_t nnz, int64_t *num_unique_out)
+// One workgroup: clears the control block, checks that the tables' record ranges
+// [offsets[t*B], offsets[(t+1)*B]) partition [0, nnz) in order and numbers the
+// tiles of the sort (first_tile[t] = tiles of the tables before t; T + 1 entries).
+// T == 0 is passed when there are no records and the offsets are not to be read.
+__global__ __launch_bounds__(1024) void bwd_init_kernel(BwdCtrl *ctrl, const int64_t *__restrict__ offsets, int32_t T,
+                                                         int64_t B, int64_t nnz, uint32_t *__restrict__ first_tile,
+                                                         int64_t *num_unique_out, uint32_t *status)
 {
+    __shared__ uint32_t wave_sums[1024 / EMB_WAVE];
+    __shared__ uint32_t bad;
     const int i = threadIdx.x;
-    if (i < 64) reinterpret_cast<uint32_t *>(ctrl)[i] = (i == 2) ? nnz : 0u;  // n_valid defaults to nnz
-    if (i == 0 && num_unique_out) *num_unique_out = 0;
+    if (i == 0) bad = 0;
+    __syncthreads();
+    uint32_t carry = 0;
+    for (int32_t t0 = 0; t0 < T; t0 += 1024) {
+        const int32_t t = t0 + i;
+        uint32_t c = 0;
+        if (t < T) {
+            const int64_t s = offsets[(int64_t)t * B], e = offsets[(int64_t)(t + 1) * B];
+            const bool ok = s >= 0 && s <= e && e <= nnz && (t > 0 || s == 0) && (t < T - 1 || e == nnz);
+            if (ok) c = (uint32_t)((e - s + SORT_TILE - 1) / SORT_TILE);
+            else bad = 1;
+        }
+        uint32_t total;
+        const uint32_t inc = block_inclusive_scan<uint32_t, 1024>(c, wave_sums, total);
+        if (t < T) first_tile[t] = carry + inc - c;
+        carry += total;
+    }
+    __syncthreads();
+    if (i < 64) reinterpret_cast<uint32_t *>(ctrl)[i] = (i == 0) ? bad : 0u;   // word 0 is `abort`
+    if (i == 0) {
+        first_tile[T] = carry;
+        if (bad) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
+        if (num_unique_out) *num_unique_out = 0;
+    }
+}
+static_assert(offsetof(BwdCtrl, abort) == 0, "bwd_init_kernel writes abort as word 0");
+
+// One thread per tile of the sort: which table it belongs to and which records it holds.
+__global__ __launch_bounds__(256) void sort_tiles_kernel(const int64_t *__restrict__ offsets, int32_t T, int64_t B,
+                                                         const uint32_t *__restrict__ first_tile,
+                                                         SortTile *__restrict__ desc, uint32_t tiles,
+                                                         const BwdCtrl *ctrl)
+{
+    if (ctrl->abort) return;   // the record ranges are not to be trusted
+    const uint32_t b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= tiles) return;
+    SortTile d = {0, 0, 0, 0, 0, 0, {0, 0}};
+    if (b < first_tile[T]) {
+        // the table with first_tile[t] <= b < first_tile[t + 1]; tables without records own no tile
+        int32_t lo = 0, hi = T;
+        while (hi - lo > 1) {
+            const int32_t mid = lo + (hi - lo) / 2;
+            if (first_tile[mid] <= b) lo = mid;
+            else hi = mid;
+        }
+        const int64_t s = offsets[(int64_t)lo * B], e = offsets[(int64_t)(lo + 1) * B];
+        const int64_t start = s + (int64_t)(b - first_tile[lo]) * SORT_TILE;
+        const int64_t left = e - start;
+        d.start = (uint32_t)start;
+        d.count = (uint32_t)(left < SORT_TILE ? left : SORT_TILE);
+        d.first = first_tile[lo];
+        d.next = first_tile[lo + 1];
+        d.seg_start = (uint32_t)s;
+        d.table = (uint32_t)lo;
+    }
+    desc[b] = d;
 }
 
 constexpr int KEY_LANES = 16;  // lanes that share one bag in the key build
@@ -113,19 +177,13 @@ template <typename KeyT>
 __global__ __launch_bounds__(256) void bwd_keys_kernel(const emb_table *__restrict__ tables, int32_t T, int64_t B,
                                                        int64_t nnz, const int64_t *__restrict__ rows,
                                                        const int64_t *__restrict__ offsets, int32_t mode,
-                                                       KeyT sentinel, KeyT *__restrict__ keys,
+                                                       KeyT local_sentinel, KeyT *__restrict__ keys,
                                                        uint32_t *__restrict__ pay, float *__restrict__ bag_scale,
                                                        BwdCtrl *ctrl, uint32_t *status)
 {
     const int t = blockIdx.y;
     const int g = threadIdx.x / KEY_LANES;
     const int l = threadIdx.x % KEY_LANES;
-    if (blockIdx.x == 0 && t == 0 && threadIdx.x == 0) {
-        if (offsets[0] != 0 || offsets[(int64_t)T * B] != nnz) {
-            atomicOr(&ctrl->abort, 1u);
-            emb_flag(status, EMB_STATUS_BAD_OFFSETS);
-        }
-    }
     const int64_t b = (int64_t)blockIdx.x * (256 / KEY_LANES) + g;
     if (b >= B) return;
     const emb_table tb = tables[t];
@@ -143,9 +201,9 @@ __global__ __launch_bounds__(256) void bwd_keys_kernel(const emb_table *__restri
         const int64_t r = rows[j];
         KeyT k;
         if ((uint64_t)r < (uint64_t)tb.num_rows) {
-            k = (KeyT)(tb.row_base + r);
+            k = (KeyT)r;
         } else {
-            k = sentinel;
+            k = local_sentinel;   // sorts after every row of the table
             emb_flag(status, EMB_STATUS_BAD_INDEX);
         }
         keys[j] = k;
@@ -156,97 +214,107 @@ __global__ __launch_bounds__(256) void bwd_keys_kernel(const emb_table *__restri
 // ---------------------------------------------------------------------------
 // run-length boundaries of the sorted keys
 // ---------------------------------------------------------------------------
+// Invalid rows leave sentinel records at the end of their table's range, i.e.
+// between the runs of two tables.  Every change of key starts a run; runs of the
+// sentinel are numbered with the others (their start ends the run before them)
+// but are not rows: seg_real maps a run to its place in the list of distinct rows.
 template <typename KeyT>
-__device__ __forceinline__ bool is_head(const KeyT *keys, uint32_t i, uint32_t n, KeyT sentinel)
+__device__ __forceinline__ unsigned long long head_flags(const KeyT *keys, uint32_t i, uint32_t n, KeyT sentinel)
 {
-    if (i >= n) return false;
+    if (i >= n) return 0ull;
     const KeyT k = keys[i];
-    if (k == sentinel) return false;
-    return i == 0 || keys[i - 1] != k;
+    if (i != 0 && keys[i - 1] == k) return 0ull;
+    return (1ull << 32) | (k != sentinel ? 1ull : 0ull);   // high half: runs, low half: rows
 }
 
 template <typename KeyT>
 __global__ __launch_bounds__(SORT_BLOCK) void runs_count_kernel(const KeyT *__restrict__ keys, uint32_t n, KeyT sentinel,
-                                                                uint32_t *__restrict__ tile_heads, BwdCtrl *ctrl)
+                                                                unsigned long long *__restrict__ tile_heads,
+                                                                const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
-    __shared__ uint32_t wave_sums[SORT_WAVES];
+    __shared__ unsigned long long wave_sums[SORT_WAVES];
     const uint32_t base = blockIdx.x * SORT_TILE + threadIdx.x * SORT_ITEMS;
-    uint32_t c = 0;
+    unsigned long long c = 0;
 #pragma unroll
-    for (int k = 0; k < SORT_ITEMS; ++k) {
-        const uint32_t i = base + k;
-        c += is_head(keys, i, n, sentinel) ? 1u : 0u;
-        // the first sentinel record marks the end of the valid records
-        if (i < n && keys[i] == sentinel && (i == 0 || keys[i - 1] != sentinel)) ctrl->n_valid = i;
-    }
-    uint32_t total;
-    block_inclusive_scan<uint32_t, SORT_BLOCK>(c, wave_sums, total);
+    for (int k = 0; k < SORT_ITEMS; ++k) c += head_flags(keys, base + k, n, sentinel);
+    unsigned long long total;
+    block_inclusive_scan<unsigned long long, SORT_BLOCK>(c, wave_sums, total);
     if (threadIdx.x == 0) tile_heads[blockIdx.x] = total;
 }
 
-__global__ __launch_bounds__(1024) void runs_scan_kernel(uint32_t *__restrict__ tile_heads, uint32_t tiles,
-                                                          uint32_t *__restrict__ seg_start, BwdCtrl *ctrl,
+__global__ __launch_bounds__(1024) void runs_scan_kernel(unsigned long long *__restrict__ tile_heads, uint32_t tiles,
+                                                          uint32_t n, uint32_t *__restrict__ seg_start, BwdCtrl *ctrl,
                                                           int64_t *num_unique_out)
 {
     if (ctrl->abort) return;
-    __shared__ uint32_t wave_sums[1024 / EMB_WAVE];
-    uint32_t carry = 0;
+    __shared__ unsigned long long wave_sums[1024 / EMB_WAVE];
+    unsigned long long carry = 0;
     for (uint32_t b0 = 0; b0 < tiles; b0 += 1024) {
         const uint32_t b = b0 + threadIdx.x;
-        const uint32_t v = b < tiles ? tile_heads[b] : 0u;
-        uint32_t total;
-        const uint32_t inc = block_inclusive_scan<uint32_t, 1024>(v, wave_sums, total);
+        const unsigned long long v = b < tiles ? tile_heads[b] : 0ull;
+        unsigned long long total;
+        const unsigned long long inc = block_inclusive_scan<unsigned long long, 1024>(v, wave_sums, total);
         if (b < tiles) tile_heads[b] = carry + inc - v;
         carry += total;
     }
     if (threadIdx.x == 0) {
-        ctrl->num_unique = carry;
-        seg_start[carry] = ctrl->n_valid;
-        if (num_unique_out) *num_unique_out = (int64_t)carry;
+        const uint32_t runs = (uint32_t)(carry >> 32), rows = (uint32_t)carry;
+        ctrl->num_runs = runs;
+        ctrl->num_unique = rows;
+        seg_start[runs] = n;   // the last run ends with the records
+        if (num_unique_out) *num_unique_out = (int64_t)rows;
     }
 }
 
 template <typename KeyT>
 __global__ __launch_bounds__(SORT_BLOCK) void runs_compact_kernel(const KeyT *__restrict__ keys, uint32_t n,
                                                                   KeyT sentinel,
-                                                                  const uint32_t *__restrict__ tile_heads,
+                                                                  const unsigned long long *__restrict__ tile_heads,
                                                                   uint32_t *__restrict__ seg_start,
+                                                                  uint32_t *__restrict__ seg_real,
                                                                   int64_t *__restrict__ unique_keys_out,
                                                                   const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
-    __shared__ uint32_t wave_sums[SORT_WAVES];
+    __shared__ unsigned long long wave_sums[SORT_WAVES];
     const uint32_t base = blockIdx.x * SORT_TILE + threadIdx.x * SORT_ITEMS;
-    bool head[SORT_ITEMS];
-    uint32_t c = 0;
+    unsigned long long f[SORT_ITEMS], c = 0;
 #pragma unroll
     for (int k = 0; k < SORT_ITEMS; ++k) {
-        head[k] = is_head(keys, base + k, n, sentinel);
-        c += head[k] ? 1u : 0u;
+        f[k] = head_flags(keys, base + k, n, sentinel);
+        c += f[k];
     }
-    uint32_t total;
-    const uint32_t inc = block_inclusive_scan<uint32_t, SORT_BLOCK>(c, wave_sums, total);
-    uint32_t u = tile_heads[blockIdx.x] + inc - c;
+    unsigned long long total;
+    const unsigned long long inc = block_inclusive_scan<unsigned long long, SORT_BLOCK>(c, wave_sums, total);
+    const unsigned long long before = tile_heads[blockIdx.x] + inc - c;
+    uint32_t v = (uint32_t)(before >> 32), u = (uint32_t)before;
 #pragma unroll
     for (int k = 0; k < SORT_ITEMS; ++k) {
-        if (head[k]) {
-            seg_start[u] = base + k;
-            if (unique_keys_out) unique_keys_out[u] = (int64_t)keys[base + k];
-            ++u;
+        if (f[k]) {
+            const bool real = (f[k] & 1ull) != 0;
+            seg_start[v] = base + k;
+            seg_real[v] = real ? u : 0xFFFFFFFFu;
+            if (real) {
+                if (unique_keys_out) unique_keys_out[u] = (int64_t)keys[base + k];
+                ++u;
+            }
+            ++v;
         }
     }
 }
 
-template <typename KeyT>
 __global__ __launch_bounds__(256) void runs_counts_kernel(const uint32_t *__restrict__ seg_start,
+                                                          const uint32_t *__restrict__ seg_real,
                                                           int32_t *__restrict__ unique_counts_out,
                                                           const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
-    const uint32_t U = ctrl->num_unique;
-    for (uint32_t u = blockIdx.x * 256 + threadIdx.x; u < U; u += gridDim.x * 256)
-        unique_counts_out[u] = (int32_t)(seg_start[u + 1] - seg_start[u]);
+    const uint32_t runs = ctrl->num_runs;
+    for (uint32_t v = blockIdx.x * 256 + threadIdx.x; v < runs; v += gridDim.x * 256) {
+        const uint32_t u = seg_real[v];
+        if (u != 0xFFFFFFFFu) unique_counts_out[u] = (int32_t)(seg_start[v + 1] - seg_start[v]);
+    }
 }
 
 __global__ void runs_reset_kernel(BwdCtrl *ctrl)
@@ -261,7 +329,8 @@ struct BwdArgs {
     const emb_table *tables_dev;
     int32_t T, D, dtype, mode;
     const int64_t *rows, *offsets;
-    int64_t B, nnz, total_rows;
+    int64_t B, nnz, total_rows, max_rows;
+    int passes;   // of the sort: enough for the bits of max_rows, the value that marks an invalid row
     const float *dout;
     float lr, eps;
     char *ws;
@@ -342,16 +411,22 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
     uint32_t *pay_a = reinterpret_cast<uint32_t *>(a.ws + L.pay_a);
     uint32_t *pay_b = reinterpret_cast<uint32_t *>(a.ws + L.pay_b);
     float *bag_scale = reinterpret_cast<float *>(a.ws + L.bag_scale);
+    uint32_t *first_tile = reinterpret_cast<uint32_t *>(a.ws + L.first_tile);
+    SortTile *tile_desc = reinterpret_cast<SortTile *>(a.ws + L.tile_desc);
     uint32_t *hist = reinterpret_cast<uint32_t *>(a.ws + L.hist);
-    uint32_t *tile_heads = reinterpret_cast<uint32_t *>(a.ws + L.tile_heads);
+    unsigned long long *tile_heads = reinterpret_cast<unsigned long long *>(a.ws + L.tile_heads);
     uint32_t *seg_start = reinterpret_cast<uint32_t *>(a.ws + L.seg_start);
-    const KeyT sentinel = (KeyT)a.total_rows;
+    uint32_t *seg_real = reinterpret_cast<uint32_t *>(a.ws + L.seg_real);
+    const KeyT sentinel = (KeyT)a.total_rows;       // after the sort
+    const KeyT local_sentinel = (KeyT)a.max_rows;   // during it
     const uint32_t n = (uint32_t)a.nnz;
     const uint32_t tiles = (uint32_t)L.tiles;
+    const uint32_t flat_tiles = (uint32_t)L.flat_tiles;
     hipStream_t s = a.stream;
 
     EMB_MARK(a, 0);
-    hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(64), 0, s, ctrl, n, a.num_unique_out);
+    hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, s, ctrl, a.offsets, a.nnz > 0 ? a.T : 0, a.B, a.nnz,
+                       first_tile, a.num_unique_out, a.status);
     EMB_RETURN_IF_LAUNCH_FAILED();
     if (a.nnz == 0) {
         for (int i = 1; i < EMB_BWD_STAGE_EVENTS; ++i) EMB_MARK(a, i);
@@ -362,22 +437,29 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
         constexpr int BAGS = 256 / KEY_LANES;
         dim3 grid((unsigned)((a.B + BAGS - 1) / BAGS), (unsigned)a.T);
         hipLaunchKernelGGL(bwd_keys_kernel<KeyT>, grid, dim3(256), 0, s, a.tables_dev, a.T, a.B, a.nnz, a.rows,
-                           a.offsets, a.mode, sentinel, keys_a, pay_a, bag_scale, ctrl, a.status);
+                           a.offsets, a.mode, local_sentinel, keys_a, pay_a, bag_scale, ctrl, a.status);
         EMB_RETURN_IF_LAUNCH_FAILED();
     }
     EMB_MARK(a, 1);
 
+    hipLaunchKernelGGL(sort_tiles_kernel, dim3((tiles + 255) / 256), dim3(256), 0, s, a.offsets, a.T, a.B, first_tile,
+                       tile_desc, tiles, ctrl);
+    EMB_RETURN_IF_LAUNCH_FAILED();
     KeyT *kin = keys_a, *kout = keys_b;
     uint32_t *pin = pay_a, *pout = pay_b;
-    for (int p = 0; p < L.passes; ++p) {
+    for (int p = 0; p < a.passes; ++p) {
         const int shift = p * RADIX_BITS;
-        hipLaunchKernelGGL(sort_hist_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, n, shift, hist, tiles,
-                           ctrl);
+        hipLaunchKernelGGL(sort_hist_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, tile_desc, shift, hist,
+                           tiles, ctrl);
         EMB_RETURN_IF_LAUNCH_FAILED();
         hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX), dim3(1024), 0, s, hist, tiles, ctrl);
         EMB_RETURN_IF_LAUNCH_FAILED();
-        hipLaunchKernelGGL(sort_scatter_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, pin, kout, pout, n,
-                           shift, hist, tiles, ctrl);
+        if (p == a.passes - 1)
+            hipLaunchKernelGGL((sort_scatter_kernel<KeyT, true>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, pin, kout,
+                               pout, tile_desc, shift, hist, tiles, a.tables_dev, local_sentinel, sentinel, ctrl);
+        else
+            hipLaunchKernelGGL((sort_scatter_kernel<KeyT, false>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, pin, kout,
+                               pout, tile_desc, shift, hist, tiles, a.tables_dev, local_sentinel, sentinel, ctrl);
         EMB_RETURN_IF_LAUNCH_FAILED();
         KeyT *tk = kin; kin = kout; kout = tk;
         uint32_t *tp = pin; pin = pout; pout = tp;
@@ -386,18 +468,18 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
     EMB_MARK(a, 2);
 
     if (a.unique_keys_out || a.unique_counts_out) {
-        hipLaunchKernelGGL(runs_count_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, n, sentinel, tile_heads,
-                           ctrl);
+        hipLaunchKernelGGL(runs_count_kernel<KeyT>, dim3(flat_tiles), dim3(SORT_BLOCK), 0, s, kin, n, sentinel,
+                           tile_heads, ctrl);
         EMB_RETURN_IF_LAUNCH_FAILED();
-        hipLaunchKernelGGL(runs_scan_kernel, dim3(1), dim3(1024), 0, s, tile_heads, tiles, seg_start, ctrl,
+        hipLaunchKernelGGL(runs_scan_kernel, dim3(1), dim3(1024), 0, s, tile_heads, flat_tiles, n, seg_start, ctrl,
                            a.num_unique_out);
         EMB_RETURN_IF_LAUNCH_FAILED();
-        hipLaunchKernelGGL(runs_compact_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, n, sentinel,
-                           tile_heads, seg_start, a.unique_keys_out, ctrl);
+        hipLaunchKernelGGL(runs_compact_kernel<KeyT>, dim3(flat_tiles), dim3(SORT_BLOCK), 0, s, kin, n, sentinel,
+                           tile_heads, seg_start, seg_real, a.unique_keys_out, ctrl);
         EMB_RETURN_IF_LAUNCH_FAILED();
         if (a.unique_counts_out) {
-            const unsigned cgrid = (unsigned)(tiles < 1024 ? tiles : 1024);
-            hipLaunchKernelGGL(runs_counts_kernel<KeyT>, dim3(cgrid), dim3(256), 0, s, seg_start,
+            const unsigned cgrid = (unsigned)(flat_tiles < 1024 ? flat_tiles : 1024);
+            hipLaunchKernelGGL(runs_counts_kernel, dim3(cgrid), dim3(256), 0, s, seg_start, seg_real,
                                a.unique_counts_out, ctrl);
             EMB_RETURN_IF_LAUNCH_FAILED();
         }
@@ -461,17 +543,24 @@ extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, co
     if (nnz > 0 && (!rows_dev || !offsets_dev || !dout_dev)) return EMB_ERR_INVALID_ARG;
     if (nnz > 0 && !emb_aligned(dout_dev, 16)) return EMB_ERR_INVALID_ARG;
 
-    int64_t total_rows = 0;
-    for (int32_t t = 0; t < T; ++t) total_rows += tables_host[t].num_rows;
+    int64_t total_rows = 0, max_rows = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        total_rows += tables_host[t].num_rows;
+        if (tables_host[t].num_rows > max_rows) max_rows = tables_host[t].num_rows;
+    }
     const BwdLayout L = bwd_layout(T, B, nnz, total_rows, D, dtype);
     if (!workspace_dev || !emb_aligned(workspace_dev, 256) || workspace_bytes < L.total) return EMB_ERR_WORKSPACE;
-    if (L.passes > MAX_PASSES) return EMB_ERR_UNSUPPORTED;
+    int bits = 0;
+    for (uint64_t v = (uint64_t)max_rows; v; v >>= 1) ++bits;
+    int passes = (bits + RADIX_BITS - 1) / RADIX_BITS;
+    if (passes < 1) passes = 1;
 
     BwdArgs a;
     a.tables_dev = tables_dev;
     a.T = T; a.D = D; a.dtype = dtype; a.mode = mode;
     a.rows = rows_dev; a.offsets = offsets_dev;
-    a.B = B; a.nnz = nnz; a.total_rows = total_rows;
+    a.B = B; a.nnz = nnz; a.total_rows = total_rows; a.max_rows = max_rows;
+    a.passes = passes;
     a.dout = dout_dev;
     a.lr = lr; a.eps = eps;
     a.ws = reinterpret_cast<char *>(workspace_dev);

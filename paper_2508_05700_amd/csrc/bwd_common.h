@@ -4,8 +4,8 @@
 
 struct BwdCtrl {
     uint32_t abort;        // offsets are not a partition of [0, nnz): do nothing
+    uint32_t num_runs;     // runs of equal keys, those of the sentinel included (distinct-row list only)
     uint32_t reserved0;
-    uint32_t n_valid;      // records whose key is not the sentinel
     uint32_t num_unique;   // U
     unsigned long long task_and_multi_count;  // low half: chunk tasks; high half: queued runs of several chunks
     uint32_t pad[58];
@@ -14,7 +14,6 @@ static_assert(sizeof(BwdCtrl) == 256, "control block is one 256-byte line");
 
 constexpr int RADIX_BITS = 8;
 constexpr int RADIX = 1 << RADIX_BITS;
-constexpr int MAX_PASSES = 8;
 constexpr int SORT_BLOCK = 256;
 constexpr int SORT_WAVES = SORT_BLOCK / EMB_WAVE;
 constexpr int SORT_ITEMS = 16;

@@ -1,8 +1,24 @@
 // Stable LSD radix sort of (key, payload) records, 8 bits per pass, as three
 // launches per pass: per-tile digit histogram, scan, stable scatter.
+//
+// The sort is segmented: the records of one table are contiguous before the sort
+// (bags are table-major) and stay in the table's range, so the keys sorted are
+// row numbers inside the table and the passes cover the bits of the largest
+// table, not of the sum of all tables.  A tile holds records of one table only
+// (SortTile); the last pass turns the keys into positions in the concatenation
+// of the tables, which is what the stages after the sort work on.
 #pragma once
 #include "bwd_common.h"
 #include "scan.h"
+
+struct SortTile {
+    uint32_t start, count;  // records [start, start + count); count == 0: tile not in use
+    uint32_t first, next;   // first tile of this tile's table, first tile of the next table
+    uint32_t seg_start;     // first record of the table
+    uint32_t table;
+    uint32_t pad[2];
+};
+static_assert(sizeof(SortTile) == 32, "tile descriptors are read as two 16-byte loads");
 
 // Stable rank of every record of a wavefront's share of a tile among the records
 // of the same digit, and the wavefront's digit counts.  A wavefront walks its
@@ -47,31 +63,39 @@ __device__ __forceinline__ void wave_rank_digits(const KeyT (&key)[SORT_ITEMS], 
 // hist is [RADIX][tiles + 1]: row d holds digit d's count in every tile and, in
 // its last column (written by the scan), the digit's count over all tiles.
 template <typename KeyT>
-__global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__restrict__ keys, uint32_t n, int shift,
+__global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__restrict__ keys,
+                                                               const SortTile *__restrict__ desc, int shift,
                                                                uint32_t *__restrict__ hist, uint32_t tiles,
                                                                const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
     __shared__ uint32_t cnt[SORT_WAVES][RADIX];
+    const SortTile tile = desc[blockIdx.x];
+    uint32_t *slot = hist + (size_t)threadIdx.x * (tiles + 1) + blockIdx.x;
+    if (tile.count == 0) {   // uniform over the workgroup
+        *slot = 0;
+        return;
+    }
     const int lane = threadIdx.x & (EMB_WAVE - 1);
     const int wave = threadIdx.x / EMB_WAVE;
 #pragma unroll
     for (int w = 0; w < SORT_WAVES; ++w) cnt[w][threadIdx.x] = 0;  // SORT_BLOCK == RADIX
     __syncthreads();
-    const uint32_t wbase = blockIdx.x * SORT_TILE + wave * (SORT_TILE / SORT_WAVES);
+    const uint32_t end = tile.start + tile.count;
+    const uint32_t wbase = tile.start + wave * (SORT_TILE / SORT_WAVES);
     KeyT key[SORT_ITEMS];
 #pragma unroll
     for (int k = 0; k < SORT_ITEMS; ++k) {
         const uint32_t i = wbase + k * EMB_WAVE + lane;
-        key[k] = i < n ? keys[i] : (KeyT)0;
+        key[k] = i < end ? keys[i] : (KeyT)0;
     }
     uint32_t unused[SORT_ITEMS];
-    wave_rank_digits<KeyT, false>(key, wbase, n, shift, cnt[wave], unused);
+    wave_rank_digits<KeyT, false>(key, wbase, end, shift, cnt[wave], unused);
     __syncthreads();
     uint32_t c = 0;
 #pragma unroll
     for (int w = 0; w < SORT_WAVES; ++w) c += cnt[w][threadIdx.x];
-    hist[(size_t)threadIdx.x * (tiles + 1) + blockIdx.x] = c;
+    *slot = c;
 }
 static_assert(SORT_BLOCK == RADIX, "histogram kernels map one thread to one digit");
 
@@ -99,13 +123,26 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ 
 // digit order in LDS; the copy-out then walks that order, so the lanes of a store
 // instruction write consecutive addresses within each digit's run (about
 // SORT_TILE / RADIX records long) instead of 64 unrelated ones.
-template <typename KeyT>
+//
+// A record's destination is: start of its table's range + records of the table
+// with a smaller digit + records of the table with the same digit in earlier
+// tiles + its rank among the tile's records of that digit.  The scanned
+// histogram P (exclusive over all tiles, total in the last column) gives the two
+// middle terms as differences against the column of the table's first tile.
+//
+// LAST: the final pass writes the key's position in the concatenation of the
+// tables (row + row_base), and the marker of an invalid row (`local_sentinel`,
+// which sorts last inside its table) as `global_sentinel`.
+template <typename KeyT, bool LAST>
 __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__restrict__ keys_in,
                                                                   const uint32_t *__restrict__ pay_in,
                                                                   KeyT *__restrict__ keys_out,
-                                                                  uint32_t *__restrict__ pay_out, uint32_t n, int shift,
+                                                                  uint32_t *__restrict__ pay_out,
+                                                                  const SortTile *__restrict__ desc, int shift,
                                                                   const uint32_t *__restrict__ hist /*scanned*/,
-                                                                  uint32_t tiles, const BwdCtrl *ctrl)
+                                                                  uint32_t tiles, const emb_table *__restrict__ tables,
+                                                                  KeyT local_sentinel, KeyT global_sentinel,
+                                                                  const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
     __shared__ uint32_t cnt[SORT_WAVES][RADIX];  // per-wavefront digit counts, then offsets inside the tile
@@ -113,35 +150,38 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
     __shared__ unsigned long long wave_sums[SORT_WAVES];
     __shared__ KeyT sk[SORT_TILE];
     __shared__ uint32_t sp[SORT_TILE];
+    const SortTile tile = desc[blockIdx.x];
+    if (tile.count == 0) return;   // uniform over the workgroup
     const int lane = threadIdx.x & (EMB_WAVE - 1);
     const int wave = threadIdx.x / EMB_WAVE;
 #pragma unroll
     for (int w = 0; w < SORT_WAVES; ++w) cnt[w][threadIdx.x] = 0;
     __syncthreads();
 
-    const uint32_t tbase = blockIdx.x * SORT_TILE;
-    const uint32_t wbase = tbase + wave * (SORT_TILE / SORT_WAVES);
+    const uint32_t end = tile.start + tile.count;
+    const uint32_t wbase = tile.start + wave * (SORT_TILE / SORT_WAVES);
     KeyT key[SORT_ITEMS];
     uint32_t pay[SORT_ITEMS];
     uint32_t rank[SORT_ITEMS];
 #pragma unroll
     for (int k = 0; k < SORT_ITEMS; ++k) {
         const uint32_t i = wbase + k * EMB_WAVE + lane;
-        key[k] = i < n ? keys_in[i] : (KeyT)0;
-        pay[k] = i < n ? pay_in[i] : 0u;
+        key[k] = i < end ? keys_in[i] : (KeyT)0;
+        pay[k] = i < end ? pay_in[i] : 0u;
     }
-    wave_rank_digits<KeyT, true>(key, wbase, n, shift, cnt[wave], rank);
+    wave_rank_digits<KeyT, true>(key, wbase, end, shift, cnt[wave], rank);
     __syncthreads();
 
-    // thread d: digit d's count in the tile, its start inside the tile and the number of records
-    // with a smaller digit anywhere (one scan over the digits of both, packed: the tile counts
-    // add up to at most SORT_TILE, so the low half never carries), the wavefronts' offsets within
-    // it, and the shift to global positions
+    // thread d: digit d's count in the tile, its start inside the tile and the number of the
+    // table's records with a smaller digit (one scan over the digits of both, packed: the tile
+    // counts add up to at most SORT_TILE, so the low half never carries), the wavefronts'
+    // offsets within it, and the shift to global positions
     {
         const uint32_t d = threadIdx.x;
         const uint32_t *row = hist + (size_t)d * (tiles + 1);
-        const uint32_t digit_total = row[tiles];
-        const uint32_t before_in_digit = row[blockIdx.x];
+        const uint32_t p_first = row[tile.first];
+        const uint32_t digit_total = row[tile.next] - p_first;        // in this table
+        const uint32_t before_in_digit = row[blockIdx.x] - p_first;   // in this table's earlier tiles
         uint32_t c[SORT_WAVES], total = 0;
 #pragma unroll
         for (int w = 0; w < SORT_WAVES; ++w) {
@@ -159,14 +199,14 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
             cnt[w][d] = run;
             run += c[w];
         }
-        delta[d] = below + before_in_digit - start;
+        delta[d] = tile.seg_start + below + before_in_digit - start;
     }
     __syncthreads();
 
 #pragma unroll
     for (int k = 0; k < SORT_ITEMS; ++k) {
         const uint32_t i = wbase + k * EMB_WAVE + lane;
-        if (i < n) {
+        if (i < end) {
             const uint32_t digit = (uint32_t)(key[k] >> shift) & (RADIX - 1);
             const uint32_t at = cnt[wave][digit] + rank[k];
             sk[at] = key[k];
@@ -175,14 +215,15 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
     }
     __syncthreads();
 
-    const uint32_t count = (n - tbase < (uint32_t)SORT_TILE) ? n - tbase : (uint32_t)SORT_TILE;
+    KeyT row_base = 0;
+    if (LAST) row_base = (KeyT)tables[tile.table].row_base;
 #pragma unroll
     for (int k = 0; k < SORT_ITEMS; ++k) {
         const uint32_t at = k * SORT_BLOCK + threadIdx.x;
-        if (at < count) {
+        if (at < tile.count) {
             const KeyT kk = sk[at];
             const uint32_t dst = delta[(uint32_t)(kk >> shift) & (RADIX - 1)] + at;
-            keys_out[dst] = kk;
+            keys_out[dst] = LAST ? (kk == local_sentinel ? global_sentinel : (KeyT)(kk + row_base)) : kk;
             pay_out[dst] = sp[at];
         }
     }

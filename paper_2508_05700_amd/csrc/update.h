@@ -311,7 +311,7 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
     }
     __syncthreads();
 
-    // ---- list the positions where the key changes (the sentinel records count as one last run)
+    // ---- list the positions where the key changes (sentinel records form runs that nobody sums)
     uint32_t runs = 0;   // heads inside the span
     if (in) {
         uint32_t bits = 0;
@@ -350,7 +350,7 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
             const int pos = lh[wave][k];
             const int end = lh[wave][k + 1];
             const KeyT key = lk[wave][1 + pos];
-            if (key == sentinel) break;                         // the sentinel run is last and nobody's
+            if (key == sentinel) continue;
             ++heads;
             // long, or not over after the look-ahead: queue it (at most UPD_QSLOTS such runs start in a span)
             if (end - pos > UPD_SHORT_MAX || (end == WIN && lk[wave][WIN + 1] == key)) {
