@@ -250,6 +250,57 @@ def test_backward_many_tiles_and_64_bit_keys():
     H.assert_rows_close(w.cpu().numpy()[touched], ref_t[0][touched], tables[0][touched], 0.01, what="64-bit keys")
 
 
+def test_backward_sort_segments_small_empty_and_large_tables():
+    # The sort works table by table.  Mix: tables without lookups (first, middle, last), a one-row
+    # table, neighbours that touch the same row number, a table with several sort tiles of
+    # lookups, and out-of-range rows in several tables (they sort to the end of their table's
+    # records, i.e. between the runs of two tables).
+    rng = np.random.default_rng(4242)
+    D, B = 16, 7
+    Rs = [9, 1, 5000, 5000, 3, 70_000, 12, 12, 400, 2, 33, 8]
+    T = len(Rs)
+    per_bag_max = [0, 4, 1, 1, 0, 4000, 30, 0, 0, 900, 5, 0]
+    tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
+    lengths = np.concatenate([rng.integers(0, m + 1, size=B) for m in per_bag_max]).astype(np.int64)
+    lengths[2 * B:4 * B] = 1                                   # tables 2 and 3: one lookup per bag, all of row 4999
+    off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    parts = []
+    for t in range(T):
+        n = int(lengths[t * B:(t + 1) * B].sum())
+        r = rng.integers(0, Rs[t], size=n).astype(np.int64)
+        if t in (2, 3):
+            r[:] = 4999
+        if t in (1, 5, 10) and n:
+            r[rng.integers(0, n, size=max(1, n // 50))] = Rs[t] + rng.integers(0, 3)
+        parts.append(r)
+    rows = np.concatenate(parts)
+    assert off[6 * B] - off[5 * B] > 2 * 4096                  # table 5 spans several tiles
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    base = np.concatenate([[0], np.cumsum(Rs)])
+    ts, w_dev, acc_dev = H.make_tableset(tables, "f32", with_accum=True)
+    g = H.gpu_backward(ts, rows, off, B, "mean", dout, 0.01, 1e-8)
+    ref_t, ref_a = [t.copy() for t in tables], [np.zeros(R, np.float32) for R in Rs]
+    r = oracle.bag_backward_rowwise_adagrad(ref_t, ref_a, "f32", rows, off, B, "mean", dout, 0.01, 1e-8)
+    assert g["status"] == r["status"] == emb.STATUS_BAD_INDEX
+    assert np.array_equal(g["unique_keys"], r["unique_keys"])
+    assert np.array_equal(g["unique_counts"], r["unique_counts"])
+    for t in range(T):
+        wg, ag = w_dev[t].cpu().numpy(), acc_dev[t].cpu().numpy()
+        sel = (r["unique_keys"] >= base[t]) & (r["unique_keys"] < base[t + 1])
+        touched = r["unique_keys"][sel] - base[t]
+        H.assert_rows_close(wg[touched], ref_t[t][touched], tables[t][touched], 0.01, what="segments t=%d" % t)
+        H.assert_accum_close(ag[touched], ref_a[t][touched], r["Gabs"][sel], what="segments accum t=%d" % t)
+        mask = np.ones(Rs[t], dtype=bool)
+        mask[touched] = False
+        assert np.array_equal(wg[mask], tables[t][mask]) and np.all(ag[mask] == 0)
+    # the same batch without the list of distinct rows: the update counts them itself
+    ts, w_dev2, acc_dev2 = H.make_tableset(tables, "f32", with_accum=True)
+    g2 = H.gpu_backward(ts, rows, off, B, "mean", dout, 0.01, 1e-8, want_unique=False)
+    assert g2["U"] == len(r["unique_keys"])
+    for t in range(T):
+        assert np.array_equal(w_dev2[t].cpu().numpy(), w_dev[t].cpu().numpy())
+
+
 def test_backward_is_deterministic():
     rng = np.random.default_rng(43)
     T, B, D, Rs = 2, 1500, 64, [20_000, 300]
