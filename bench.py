@@ -30,6 +30,42 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+# HBM traffic per launch, from rocprofv3 --pmc (FETCH_SIZE in one run, WRITE_SIZE in another; KiB per
+# dispatch, averaged over the dispatches of a run of this script), for the kernel sources whose digest
+# is recorded with them: once a source file under csrc/ changes, `traffic` is reported as null until
+# the counters are taken again.  The scale factors come from kernels of known traffic in the same
+# runs: the 512 MiB device copy of --pmc-calibration reads 524288 KiB and FETCH_SIZE shows 262172
+# (factor 2.0: the counter prices this part's 128-byte read requests as 64 bytes); the copy's and the
+# table fill's writes (524288 and 2500000 KiB) are counted exactly (factor 1.0).
+PMC_TRAFFIC = {
+    "sources": "936d475ea7d43524",
+    "fetch_scale": 2.0,
+    "write_scale": 1.0,
+    "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
+        "3": {"bag_forward_kernel": (178038.7, 32768.0), "update_kernel": (240473.6, 324626.9)},
+        "2u": {"bag_forward_kernel": (346119.4, 32768.0)},
+    },
+}
+
+
+def kernel_sources_digest() -> str:
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2508_05700_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(os.path.basename(f).encode() + b"\0" + fh.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel` on `workload` (see PMC_TRAFFIC), or None."""
+    kib = PMC_TRAFFIC["kib_per_launch"].get(workload, {}).get(kernel)
+    if kib is None or PMC_TRAFFIC["sources"] != kernel_sources_digest():
+        return None
+    return int(round((kib[0] * PMC_TRAFFIC["fetch_scale"] + kib[1] * PMC_TRAFFIC["write_scale"]) * 1024))
+
+
 def forward_bytes(nnz: int, bags: int, D: int, esz: int) -> int:
     """Algorithmic bytes of one gather-pool launch: per lookup one table row and
     one 8-byte index; per bag one fp32 output row and one 8-byte offset."""
@@ -162,8 +198,8 @@ def bench_hybrid(args) -> int:
     assert int(status.item()) == 0
     lookups = sum(dbs[(W + k) % len(dbs)].nnz for k in range(K))
     hits, misses = [int(x) for x in hm.cpu().tolist()]
-    ms_index = sum(e[0].elapsed_time(e[1]) for e in ev) / KI
-    ms_fwd = sum(e[1].elapsed_time(e[2]) for e in ev) / KI
+    ms_index = sum(e[0].elapsed_time(e[1]) for e in ev) / K
+    ms_fwd = sum(e[1].elapsed_time(e[2]) for e in ev) / K
     rowb = w.D * 4
     pcie_gbs = misses / K * rowb / (ms_fwd * 1e-3) / 1e9
     hbm_gbs = (hits / K * rowb + lookups / K * 24 + w.B * (4 * w.D + 8)) / (ms_fwd * 1e-3) / 1e9
@@ -323,13 +359,14 @@ def main() -> int:
     ms_index = sum(e[0].elapsed_time(e[1]) for e in ev) / KI
     ms_fwd = sum(e[1].elapsed_time(e[2]) for e in ev) / KI
     uniq = int(buf.num_unique.item()) if w.backward else 0   # of the last batch; all batches are alike
-    passes = (max(1, int(tabs.set.total_rows).bit_length()) + 7) // 8
+    passes = (max(1, int(w.R).bit_length()) + 7) // 8     # the sort works table by table on row numbers
     rowb = w.D * w.esz
 
-    def entry(name, ms, nbytes, what):
+    def entry(name, ms, nbytes, what, pmc_kernel=None):
         gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
+        traffic = measured_traffic(args.workload, pmc_kernel) if pmc_kernel and not args.scale_rows else None
         return {"kernel": name, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "avg_ms": round(ms, 4),
+                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "avg_ms": round(ms, 4),
                 "algorithmic_bytes": int(nbytes), "bytes_are": what}
 
     kernels = [
@@ -337,7 +374,7 @@ def main() -> int:
               "16 B per lookup (raw ID in, row out) + 12 B per bag (length in, offset out)"),
         entry("bag_forward_kernel (gather-pool)", ms_fwd if w.backward else ms_dom,
               forward_bytes(nnz_i, bags, w.D, w.esz),
-              "row + 8 B index per lookup, fp32 output row + 8 B offset per bag"),
+              "row + 8 B index per lookup, fp32 output row + 8 B offset per bag", "bag_forward_kernel"),
     ]
     ms_bwd = 0.0
     if w.backward:
@@ -353,7 +390,7 @@ def main() -> int:
                   uniq * (2 * rowb + 8) + nnz_i * 8 + bags * 4 * w.D,
                   "row read + row written + 8 B accumulator per distinct row, 8 B record per lookup, "
                   "gradient row once per bag (all distinct rows counted here; the few queued ones are "
-                  "updated by the next stage)"),
+                  "updated by the next stage)", "update_kernel"),
             entry("long_prepare/reduce/combine (queued long runs)", st[4], 1,
                   "not priced: its rows are counted under update_kernel"),
         ]
@@ -405,7 +442,8 @@ def main() -> int:
             gbs = nb / (ms * 1e-3) / 1e9
             extra["forward_only_" + name] = {
                 "avg_ms": round(ms, 4), "lookups_per_s": round(tot / n_it / (ms * 1e-3), 1),
-                "algorithmic_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+                "algorithmic_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                "algorithmic_bytes": int(nb), "traffic": measured_traffic(name, "bag_forward_kernel")}
             log("forward only, workload %s: %.3f ms, %.0f GB/s (%.1f %% of HBM peak)" % (
                 name, ms, gbs, 100 * gbs / HBM_PEAK_GBS))
             del fb, fbuf, rows_v
