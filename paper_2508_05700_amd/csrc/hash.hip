@@ -24,9 +24,12 @@ __global__ __launch_bounds__(HASH_BLOCK) void hash_ids_kernel(const uint64_t *__
     if (i < n) rows[i] = (int64_t)emb_fast_mod(splitmix64(raw[i] ^ salt), R, magic);
 }
 
-// One launch for all tables: the table of lookup j is found by a binary search
-// over the T+1 table boundaries offsets[t*B], staged in LDS when they fit.
+// One launch for all tables.  A thread hashes HASH_ITEMS lookups, HASH_BLOCK apart
+// (ascending), so the table of its first lookup is found once by a binary search
+// over the T+1 table boundaries offsets[t*B] (staged in LDS when they fit) and
+// then only advanced; the table's parameters are reloaded when it changes.
 constexpr int HASH_LDS_BOUNDS = 1024;
+constexpr int HASH_ITEMS = 8;
 
 __global__ __launch_bounds__(HASH_BLOCK) void hash_ids_tables_kernel(const emb_table *__restrict__ tables, int32_t T,
                                                                      const uint64_t *__restrict__ raw,
@@ -40,23 +43,44 @@ __global__ __launch_bounds__(HASH_BLOCK) void hash_ids_tables_kernel(const emb_t
         for (int t = threadIdx.x; t <= T; t += HASH_BLOCK) bounds[t] = offsets[(int64_t)t * B];
         __syncthreads();
     }
-    int64_t j = (int64_t)blockIdx.x * HASH_BLOCK + threadIdx.x;
-    if (j >= nnz) return;
-    // largest t in [0, T) with bound(t) <= j; requires bound(t+1) > j to be a valid owner
-    int lo = 0, hi = T;                      // invariant: answer in [lo, hi)
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        int64_t bm = staged ? bounds[mid] : offsets[(int64_t)mid * B];
-        if (bm <= j) lo = mid; else hi = mid;
+    auto bound = [&](int t) -> int64_t { return staged ? bounds[t] : offsets[(int64_t)t * B]; };
+    const int64_t j0 = (int64_t)blockIdx.x * (HASH_BLOCK * HASH_ITEMS) + threadIdx.x;
+    if (j0 >= nnz) return;
+    uint64_t v[HASH_ITEMS];
+#pragma unroll
+    for (int k = 0; k < HASH_ITEMS; ++k) {
+        const int64_t j = j0 + (int64_t)k * HASH_BLOCK;
+        v[k] = j < nnz ? raw[j] : 0ull;
     }
-    int64_t b0 = staged ? bounds[lo] : offsets[(int64_t)lo * B];
-    int64_t b1 = staged ? bounds[lo + 1] : offsets[(int64_t)(lo + 1) * B];
-    if (b0 <= j && j < b1) {
-        const emb_table tb = tables[lo];
-        rows[j] = (int64_t)emb_fast_mod(splitmix64(raw[j] ^ tb.salt), (uint64_t)tb.num_rows, tb.mod_magic);
-    } else {
-        rows[j] = -1;
-        emb_flag(status, EMB_STATUS_BAD_OFFSETS);
+    // largest t in [0, T) with bound(t) <= j0; it owns j0 only if bound(t + 1) > j0 as well
+    int t = 0;
+    {
+        int hi = T;                          // invariant: answer in [t, hi)
+        while (hi - t > 1) {
+            const int mid = (t + hi) >> 1;
+            if (bound(mid) <= j0) t = mid; else hi = mid;
+        }
+    }
+    int64_t b0 = bound(t), b1 = bound(t + 1);
+    emb_table tb = tables[t];
+#pragma unroll
+    for (int k = 0; k < HASH_ITEMS; ++k) {
+        const int64_t j = j0 + (int64_t)k * HASH_BLOCK;
+        if (j >= nnz) break;
+        if (j >= b1 && t + 1 < T) {          // next table(s): tables without lookups are stepped over
+            do {
+                ++t;
+                b1 = bound(t + 1);
+            } while (j >= b1 && t + 1 < T);
+            b0 = bound(t);
+            tb = tables[t];
+        }
+        if (b0 <= j && j < b1) {
+            rows[j] = (int64_t)emb_fast_mod(splitmix64(v[k] ^ tb.salt), (uint64_t)tb.num_rows, tb.mod_magic);
+        } else {                             // the boundaries do not partition [0, nnz)
+            rows[j] = -1;
+            emb_flag(status, EMB_STATUS_BAD_OFFSETS);
+        }
     }
 }
 
@@ -111,7 +135,7 @@ extern "C" int emb_hash_ids_tables(const emb_table *tables_host, const emb_table
     if (rc != EMB_OK) return rc;
     if (nnz == 0) return EMB_OK;
     if (T == 0 || !raw_dev || !offsets_dev || !rows_dev) return EMB_ERR_INVALID_ARG;
-    int64_t blocks = (nnz + HASH_BLOCK - 1) / HASH_BLOCK;
+    int64_t blocks = (nnz + HASH_BLOCK * HASH_ITEMS - 1) / (HASH_BLOCK * HASH_ITEMS);
     if (blocks > 0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(hash_ids_tables_kernel, dim3((unsigned)blocks), dim3(HASH_BLOCK), 0, emb_stream(stream),
                        tables_dev, T, raw_dev, offsets_dev, B, nnz, rows_dev, status_dev);
