@@ -252,6 +252,8 @@ def main() -> int:
     ap.add_argument("--scale-rows", type=int, default=None, help="rows per table (debug: smaller tables)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the forward-only side measurements")
+    ap.add_argument("--no-side-stream", action="store_true",
+                    help="run the backward's long-run path after the short-run update instead of beside it")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 512 MB device copy (a kernel of known traffic, to scale "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters by)")
@@ -285,7 +287,7 @@ def main() -> int:
     batches_np = [wl.make_batch(w, i, seed) for i in range(args.batches)]
     dbs = [pipeline.DeviceBatch(w, b, dev) for b in batches_np]
     max_nnz = max(d.nnz for d in dbs)
-    buf = pipeline.StepBuffers(w, max_nnz, tabs.set.total_rows, dev)
+    buf = pipeline.StepBuffers(w, max_nnz, tabs.set.total_rows, dev, side_stream=not args.no_side_stream)
     torch.cuda.synchronize()
     log("setup: %d tables x %d rows x %d %s, %d batches of ~%d lookups, %.1f s" % (
         w.T, w.R, w.D, w.dtype, len(dbs), max_nnz, time.time() - t_setup))

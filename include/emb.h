@@ -124,6 +124,20 @@ int emb_bag_forward(const emb_table *tables_host, const emb_table *tables_dev, i
 size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t nnz, int64_t total_rows,
                                         int32_t D, int32_t dtype);
 
+/* A second stream the backward may use to run its two update paths (rows
+ * with few lookups; rows with many) beside each other.  All three handles are
+ * created and owned by the caller: stream is a hipStream_t other than the
+ * call's `stream`, of default priority; fork_event and join_event are
+ * hipEvent_t (timing may be disabled) that no other work uses while the call
+ * is in flight.  The call's work is complete, in stream order, on `stream`
+ * when it returns; nothing is left pending on the side stream that `stream`
+ * does not wait for. */
+typedef struct emb_side_stream {
+    void *stream;
+    void *fork_event;
+    void *join_event;
+} emb_side_stream;
+
 /* Exact sparse backward of emb_bag_forward followed by one row-wise Adagrad
  * step (fine-tuning of table rows, Section 3.1; Adagrad of Duchi, Hazan,
  * Singer 2011 with one accumulator per row).  With g_j = c_b * dout[t,b,:]
@@ -144,10 +158,12 @@ size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t nnz, int64
  * not a partition of [0, nnz) into bags, nothing is updated, U = 0 and
  * EMB_STATUS_BAD_OFFSETS is set.  EMB_ERR_UNSUPPORTED as for the forward, and
  * if T*B >= 2^32 - 1, nnz >= 2^31, or accum is NULL for some table.
- * stage_events (host, nullable): EMB_BWD_STAGE_EVENTS hipEvent_t handles that
- * are recorded on `stream` before the first kernel and after the key build,
- * the sort, the optional list of distinct rows, the short-run update and the
- * long-run path, for callers that time the stages. */
+ * stage_events (host, nullable): EMB_BWD_STAGE_EVENTS hipEvent_t handles, each
+ * nullable, that are recorded on `stream` before the first kernel and after
+ * the key build, the sort, the optional list of distinct rows, the short-run
+ * update and the long-run path, for callers that time the stages.
+ * side (host, nullable): see emb_side_stream; NULL runs everything on
+ * `stream`.  Results do not depend on it. */
 int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, const emb_table *tables_dev,
                                      int32_t T, int32_t D, int32_t dtype,
                                      const int64_t *rows_dev, const int64_t *offsets_dev,
@@ -155,7 +171,8 @@ int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, const emb_tab
                                      float lr, float eps, void *workspace_dev,
                                      size_t workspace_bytes, int64_t *unique_keys_out_dev,
                                      int32_t *unique_counts_out_dev, int64_t *num_unique_out_dev,
-                                     uint32_t *status_dev, void *const *stage_events, void *stream);
+                                     uint32_t *status_dev, void *const *stage_events,
+                                     const emb_side_stream *side, void *stream);
 
 /* ---- host-resident table with an HBM hot-row cache (Section 3.3) --------- */
 

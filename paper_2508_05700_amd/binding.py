@@ -77,7 +77,7 @@ def lib() -> C.CDLL:
     L.emb_bag_backward_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32]
     L.emb_bag_backward_rowwise_adagrad.restype = C.c_int
     L.emb_bag_backward_rowwise_adagrad.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, f32, f32,
-                                                   vp, sz, vp, vp, vp, vp, vp, vp]
+                                                   vp, sz, vp, vp, vp, vp, vp, vp, vp]
     L.emb_cache_index_bytes.restype = C.c_int
     L.emb_cache_index_bytes.argtypes = [i64, C.POINTER(sz)]
     L.emb_cache_build.restype = C.c_int
@@ -212,16 +212,35 @@ def emb_bag_backward_workspace_bytes(T: int, B: int, nnz: int, total_rows: int, 
                                                       DTYPE[dtype]))
 
 
+class _SideStreamC(C.Structure):
+    _fields_ = [("stream", C.c_void_p), ("fork_event", C.c_void_p), ("join_event", C.c_void_p)]
+
+
+class SideStream:
+    """The ``emb_side_stream`` argument: a second torch stream (default priority) and two events,
+    kept alive by this object."""
+
+    def __init__(self, device: torch.device):
+        self.stream = torch.cuda.Stream(device=device)
+        self.events = [torch.cuda.Event(), torch.cuda.Event()]
+        for e in self.events:
+            e.record(self.stream)       # creates the HIP event behind the torch object
+        self.c = _SideStreamC(int(self.stream.cuda_stream), int(self.events[0].cuda_event),
+                              int(self.events[1].cuda_event))
+
+
 def emb_bag_backward_rowwise_adagrad(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
                                      dout: torch.Tensor, lr: float, eps: float, workspace: torch.Tensor,
                                      unique_keys: Optional[torch.Tensor] = None,
                                      unique_counts: Optional[torch.Tensor] = None,
                                      num_unique: Optional[torch.Tensor] = None,
                                      status: Optional[torch.Tensor] = None,
-                                     stage_events: Optional[Sequence[torch.cuda.Event]] = None) -> None:
+                                     stage_events: Optional[Sequence[torch.cuda.Event]] = None,
+                                     side: Optional["SideStream"] = None) -> None:
     """``stage_events``: BWD_STAGE_EVENTS entries, each None or a torch event that has been
     recorded at least once (so that its HIP handle exists); the library records the given ones
-    between its stages."""
+    between its stages.  ``side``: a SideStream on which the long-run path runs beside the
+    short-run update."""
     nnz = rows.numel()
     if offsets.numel() != tables.T * B + 1 or dout.numel() != tables.T * B * tables.D:
         raise TypeError("shape mismatch")
@@ -239,7 +258,8 @@ def emb_bag_backward_rowwise_adagrad(tables: TableSet, rows: torch.Tensor, offse
         _ptr(dout, torch.float32, "dout"), C.c_float(lr), C.c_float(eps),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
         _ptr(unique_keys, torch.int64, "unique_keys"), _ptr(unique_counts, torch.int32, "unique_counts"),
-        _ptr(num_unique, torch.int64, "num_unique"), _ptr(status, torch.int32, "status"), ev, _stream()))
+        _ptr(num_unique, torch.int64, "num_unique"), _ptr(status, torch.int32, "status"), ev,
+        None if side is None else C.addressof(side.c), _stream()))
 
 
 def emb_cache_index_bytes(num_rows: int) -> int:

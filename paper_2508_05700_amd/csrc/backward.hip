@@ -339,6 +339,7 @@ struct BwdArgs {
     int64_t *num_unique_out;
     uint32_t *status;
     void *const *events;
+    const emb_side_stream *side;   // NULL: everything on `stream`
     hipStream_t stream;
     // record stage event i, if the caller asked for stage timing
     int mark(int i) const
@@ -368,23 +369,38 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     bdiv.B = (uint32_t)a.B;
     bdiv.magic = 0xFFFFFFFFu / (uint32_t)a.B;
 
+    // Runs of up to UPD_SHORT_MAX records are updated by update_kernel, the longer ones by
+    // detect -> prepare -> reduce -> combine.  The two paths touch different rows and only read the
+    // sorted records, so with a side stream they run beside each other (fork after the sort, join
+    // at the end); without one they run one after the other on the caller's stream.
+    hipStream_t ls = a.stream;
+    if (a.side) {
+        ls = reinterpret_cast<hipStream_t>(a.side->stream);
+        hipEvent_t fork = reinterpret_cast<hipEvent_t>(a.side->fork_event);
+        if (hipEventRecord(fork, a.stream) != hipSuccess || hipStreamWaitEvent(ls, fork, 0) != hipSuccess)
+            return EMB_ERR_HIP;
+    }
+    constexpr int DWAVES = 256 / EMB_WAVE;
+    hipLaunchKernelGGL(long_detect_kernel<KeyT>, dim3((unsigned)((L.slots + DWAVES - 1) / DWAVES)), dim3(256), 0, ls,
+                       keys, n, sentinel, ctrl, queue, wave_heads, (uint32_t)L.slots);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+
     hipLaunchKernelGGL((update_kernel<KeyT, LPR, CPL, EU, BF16>), dim3((unsigned)L.upd_blocks), dim3(UPD_BLOCK), 0,
                        a.stream, a.tables_dev, a.T, keys, pay, n, sentinel, bag_scale, a.dout, chunks, a.D, inv_D, a.lr,
-                       a.eps, bdiv, ctrl, queue, wave_heads);
+                       a.eps, bdiv, ctrl);
     EMB_RETURN_IF_LAUNCH_FAILED();
     EMB_MARK(a, 4);
 
-    const int64_t n_wave_heads = L.upd_blocks * (UPD_BLOCK / EMB_WAVE);
-    const int64_t pthreads = L.qslots > n_wave_heads ? L.qslots : n_wave_heads;
-    hipLaunchKernelGGL(long_prepare_kernel<KeyT>, dim3((unsigned)((pthreads + PREP_BLOCK - 1) / PREP_BLOCK)), dim3(PREP_BLOCK), 0, a.stream,
-                       keys, n, sentinel, ctrl, queue, (uint32_t)L.qslots, wave_heads, (uint32_t)n_wave_heads, segs, multi_list,
-                       chunk_tasks, (uint32_t)L.chunk_cap);
+    const int64_t pthreads = L.qslots > L.slots ? L.qslots : L.slots;
+    hipLaunchKernelGGL(long_prepare_kernel<KeyT>, dim3((unsigned)((pthreads + PREP_BLOCK - 1) / PREP_BLOCK)),
+                       dim3(PREP_BLOCK), 0, ls, keys, n, sentinel, ctrl, queue, (uint32_t)L.qslots, wave_heads,
+                       (uint32_t)L.slots, segs, multi_list, chunk_tasks, (uint32_t)L.chunk_cap);
     EMB_RETURN_IF_LAUNCH_FAILED();
 
     // one wavefront per task; enough workgroups to fill the chip, tasks beyond that are strided over
     int64_t want = (L.chunk_cap + (UPD_BLOCK / EMB_WAVE) - 1) / (UPD_BLOCK / EMB_WAVE);
     const unsigned lgrid = (unsigned)emb_round_up_xcds(want < 4096 ? want : 4096);
-    hipLaunchKernelGGL((long_reduce_kernel<KeyT, LPR, CPL, EU, BF16>), dim3(lgrid), dim3(UPD_BLOCK), 0, a.stream,
+    hipLaunchKernelGGL((long_reduce_kernel<KeyT, LPR, CPL, EU, BF16>), dim3(lgrid), dim3(UPD_BLOCK), 0, ls,
                        a.tables_dev, a.T, keys, pay, bag_scale, a.dout, chunks, a.D, inv_D, a.lr, a.eps, bdiv, ctrl,
                        segs, chunk_tasks, (uint32_t)L.chunk_cap, partials);
     EMB_RETURN_IF_LAUNCH_FAILED();
@@ -394,10 +410,15 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     constexpr int CWAVES = UPD_BLOCK / EMB_WAVE;
     int64_t cwant = (multi_max + CWAVES - 1) / CWAVES;
     const unsigned cgrid = (unsigned)(cwant < 1024 ? cwant : 1024);
-    hipLaunchKernelGGL((long_combine_kernel<KeyT, LPR, CPL, BF16>), dim3(cgrid), dim3(UPD_BLOCK), 0, a.stream,
+    hipLaunchKernelGGL((long_combine_kernel<KeyT, LPR, CPL, BF16>), dim3(cgrid), dim3(UPD_BLOCK), 0, ls,
                        a.tables_dev, a.T, keys, pay, chunks, inv_D, a.lr, a.eps, bdiv, ctrl, segs, multi_list,
                        (uint32_t)L.qslots, partials, a.num_unique_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
+    if (a.side) {
+        hipEvent_t join = reinterpret_cast<hipEvent_t>(a.side->join_event);
+        if (hipEventRecord(join, ls) != hipSuccess || hipStreamWaitEvent(a.stream, join, 0) != hipSuccess)
+            return EMB_ERR_HIP;
+    }
     EMB_MARK(a, 5);
     return EMB_OK;
 }
@@ -527,7 +548,8 @@ extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, co
                                                 const float *dout_dev, float lr, float eps, void *workspace_dev,
                                                 size_t workspace_bytes, int64_t *unique_keys_out_dev,
                                                 int32_t *unique_counts_out_dev, int64_t *num_unique_out_dev,
-                                                uint32_t *status_dev, void *const *stage_events, void *stream)
+                                                uint32_t *status_dev, void *const *stage_events,
+                                                const emb_side_stream *side, void *stream)
 {
     if (B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
@@ -542,6 +564,8 @@ extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, co
     if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
     if (nnz > 0 && (!rows_dev || !offsets_dev || !dout_dev)) return EMB_ERR_INVALID_ARG;
     if (nnz > 0 && !emb_aligned(dout_dev, 16)) return EMB_ERR_INVALID_ARG;
+    if (side && (!side->stream || !side->fork_event || !side->join_event || side->stream == stream))
+        return EMB_ERR_INVALID_ARG;
 
     int64_t total_rows = 0, max_rows = 0;
     for (int32_t t = 0; t < T; ++t) {
@@ -569,6 +593,7 @@ extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, co
     a.num_unique_out = num_unique_out_dev;
     a.status = status_dev;
     a.events = stage_events;
+    a.side = side;
     a.stream = emb_stream(stream);
     return L.key_bytes == 4 ? run_backward<uint32_t>(a, L) : run_backward<uint64_t>(a, L);
 }

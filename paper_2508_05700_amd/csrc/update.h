@@ -246,8 +246,7 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
                                                            KeyT sentinel, const float *__restrict__ bag_scale,
                                                            const float *__restrict__ dout, int32_t chunks_per_row,
                                                            int32_t D, float inv_D, float lr, float eps, BagDiv bdiv,
-                                                           const BwdCtrl *ctrl, uint32_t *__restrict__ queue,
-                                                           uint32_t *__restrict__ wave_heads)
+                                                           const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
     constexpr int WAVES = UPD_BLOCK / EMB_WAVE;
@@ -261,7 +260,6 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
     __shared__ KeyT lk[WAVES][WIN + 2];
     __shared__ uint32_t lp[WAVES][WIN];
     __shared__ uint16_t lh[WAVES][UPD_SPAN + 2];   // window positions of the run heads, ascending
-    __shared__ uint32_t lq[WAVES];                 // runs queued by this wavefront so far
 
     const int wave = threadIdx.x / EMB_WAVE;
     const int lane = threadIdx.x & (EMB_WAVE - 1);
@@ -306,7 +304,6 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
         if (lane == 0) {
             lk[wave][0] = i0 > 0 ? keys[i0 - 1] : sentinel;
             lk[wave][WIN + 1] = (n - i0 > (uint32_t)WIN) ? keys[i0 + WIN] : sentinel;
-            lq[wave] = 0;
         }
     }
     __syncthreads();
@@ -342,7 +339,6 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
     }
     __syncthreads();
 
-    uint32_t heads = 0;
     if (in) {
         const int64_t row_bytes = (int64_t)chunks_per_row * 16;
         // groups take the runs round-robin: every group gets the same number of runs, give or take one
@@ -351,15 +347,9 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
             const int end = lh[wave][k + 1];
             const KeyT key = lk[wave][1 + pos];
             if (key == sentinel) continue;
-            ++heads;
-            // long, or not over after the look-ahead: queue it (at most UPD_QSLOTS such runs start in a span)
-            if (end - pos > UPD_SHORT_MAX || (end == WIN && lk[wave][WIN + 1] == key)) {
-                if (l == 0) {
-                    const uint32_t slot = atomicAdd(&lq[wave], 1u);
-                    if (slot < (uint32_t)UPD_QSLOTS) queue[wid * UPD_QSLOTS + slot] = i0 + (uint32_t)pos;
-                }
-                continue;
-            }
+            // longer than UPD_SHORT_MAX records (a run that is not over after the look-ahead is): not
+            // this kernel's; long_detect_kernel has queued it for the chunked path
+            if (end - pos > UPD_SHORT_MAX || (end == WIN && lk[wave][WIN + 1] == key)) continue;
             // ---- the row, its accumulator and the first EU gradient rows, all requested together
             const int t = bdiv.table(lp[wave][pos]);
             const int64_t r = (int64_t)key - dir.base(t);
@@ -406,22 +396,62 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
             adagrad_apply<LPR, CPL, BF16>(acc, w, s_old, wrow, aptr, l, chunks_per_row, inv_D, lr, eps);
         }
     }
-    // mark the unused queue slots of this wavefront
-    __syncthreads();
-    if (in && lane < UPD_QSLOTS && (uint32_t)lane >= lq[wave]) queue[wid * UPD_QSLOTS + lane] = 0xFFFFFFFFu;
-
-    // number of runs started = number of distinct rows; one store per wavefront
-    uint32_t h = (l == 0) ? heads : 0u;
-#pragma unroll
-    for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) h += __shfl_xor(h, d, EMB_WAVE);
-    if (lane == 0) wave_heads[wid] = h;
 }
 
 // ---------------------------------------------------------------------------
 // queued runs
 // ---------------------------------------------------------------------------
+// Runs longer than UPD_SHORT_MAX records are not summed by update_kernel but cut into
+// chunks for whole wavefronts.  This kernel finds them: one wavefront per span of
+// UPD_SPAN sorted records (the spans of update_kernel), four records per lane.
+// Record i starts such a run iff it starts a run and record i + UPD_SHORT_MAX has the
+// same key (keys are sorted).  Two such starts are more than UPD_SHORT_MAX records
+// apart, so a span has at most UPD_QSLOTS of them: they go to the span's queue slots
+// in ascending order, unused slots are marked.  The kernel only reads the keys, so
+// it and the kernels it feeds can run beside update_kernel on another stream.
+// It also counts the runs (= distinct rows) of the span.
+template <typename KeyT>
+__global__ __launch_bounds__(256) void long_detect_kernel(const KeyT *__restrict__ keys, uint32_t n, KeyT sentinel,
+                                                          const BwdCtrl *ctrl, uint32_t *__restrict__ queue,
+                                                          uint32_t *__restrict__ wave_heads, uint32_t slots)
+{
+    if (ctrl->abort) return;
+    static_assert(UPD_SPAN == 4 * EMB_WAVE, "four records per lane");
+    static_assert(UPD_SHORT_MAX % 4 == 0 && UPD_SHORT_MAX + 4 <= SORT_PAD, "far records are read four at a time");
+    const int lane = threadIdx.x & (EMB_WAVE - 1);
+    const uint32_t wid = blockIdx.x * (256 / EMB_WAVE) + threadIdx.x / EMB_WAVE;
+    if (wid >= slots) return;                       // whole wavefronts leave together
+    const uint32_t i = wid * UPD_SPAN + lane * 4;   // < n + UPD_SPAN: inside the slack of the array
+    KeyT k[4], far[4];
+    KeyT prev = sentinel;
+    if (i < n) {
+        load_records<KeyT, 4>(keys + i, k);
+        load_records<KeyT, 4>(keys + i + UPD_SHORT_MAX, far);
+        if (i > 0) prev = keys[i - 1];
+    }
+    uint32_t heads = 0, start = 0xFFFFFFFFu;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (i + e < n) {
+            const bool head = k[e] != sentinel && (i + e == 0 || k[e] != prev);
+            heads += head ? 1u : 0u;
+            if (head && i + e + UPD_SHORT_MAX < n && far[e] == k[e]) start = i + e;   // at most one per lane
+            prev = k[e];
+        }
+    }
+    const uint64_t m = __ballot(start != 0xFFFFFFFFu);
+    const uint32_t rank = (uint32_t)__popcll(m & ((lane == 0) ? 0ull : (~0ull >> (64 - lane))));
+    const uint32_t count = (uint32_t)__popcll(m);
+    uint32_t *q = queue + (size_t)wid * UPD_QSLOTS;
+    if (start != 0xFFFFFFFFu && rank < (uint32_t)UPD_QSLOTS) q[rank] = start;
+    if (lane < UPD_QSLOTS && (uint32_t)lane >= count) q[lane] = 0xFFFFFFFFu;
+#pragma unroll
+    for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) heads += __shfl_xor(heads, d, EMB_WAVE);
+    if (lane == 0) wave_heads[wid] = heads;
+}
+
 // One thread per queue slot: find the run's end, cut it into chunks, create the
-// tasks.  Also adds up the per-wavefront run counts of the short-run kernel.
+// tasks.  Also adds up the per-span run counts.
 template <typename KeyT>
 __global__ __launch_bounds__(PREP_BLOCK) void long_prepare_kernel(const KeyT *__restrict__ keys, uint32_t n, KeyT sentinel,
                                                            BwdCtrl *ctrl,

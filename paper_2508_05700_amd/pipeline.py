@@ -51,18 +51,22 @@ class DeviceBatch:
 class StepBuffers:
     """Outputs and scratch of one step, sized for at most ``max_nnz`` lookups."""
 
-    def __init__(self, w: Workload, max_nnz: int, total_rows: int, device: torch.device, want_unique: bool = False):
+    def __init__(self, w: Workload, max_nnz: int, total_rows: int, device: torch.device, want_unique: bool = False,
+                 side_stream: bool = True):
         n = max(int(max_nnz), 1)
         self.offsets = torch.empty(w.T * w.B + 1, dtype=torch.int64, device=device)
         self.rows = torch.empty(n, dtype=torch.int64, device=device)
         self.out = torch.empty((w.T, w.B, w.D), dtype=torch.float32, device=device)
         self.status = torch.zeros(1, dtype=torch.int32, device=device)
         self.workspace = None
+        self.side = None
         self.unique_keys = self.unique_counts = self.num_unique = None
         if w.backward:
             nbytes = emb.emb_bag_backward_workspace_bytes(w.T, w.B, n, total_rows, w.D, w.dtype)
             self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
             self.num_unique = torch.zeros(1, dtype=torch.int64, device=device)
+            if side_stream:   # the backward's two update paths run side by side
+                self.side = emb.SideStream(device)
             if want_unique:   # the ordered list of distinct rows is optional output
                 self.unique_keys = torch.empty(n, dtype=torch.int64, device=device)
                 self.unique_counts = torch.empty(n, dtype=torch.int32, device=device)
@@ -86,7 +90,7 @@ def run_backward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, db: Devi
                  stage_events=None) -> None:
     emb.emb_bag_backward_rowwise_adagrad(tables, rows, buf.offsets, w.B, w.pool, db.dout, w.lr, w.eps, buf.workspace,
                                          buf.unique_keys, buf.unique_counts, buf.num_unique, buf.status,
-                                         stage_events)
+                                         stage_events, buf.side)
 
 
 def run_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:

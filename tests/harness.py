@@ -111,7 +111,19 @@ def gpu_forward(ts, rows_np, off_np, B, mode):
     return out.cpu().numpy(), int(status.item())
 
 
-def gpu_backward(ts, rows_np, off_np, B, mode, dout_np, lr, eps, want_unique=True):
+_side = None
+
+
+def side_stream():
+    """One emb_side_stream for the whole test session."""
+    global _side
+    if _side is None:
+        _side = emb.SideStream(torch.device(DEV))
+    return _side
+
+
+def gpu_backward(ts, rows_np, off_np, B, mode, dout_np, lr, eps, want_unique=True, side=True):
+    """side=True: the long-run path runs on a second stream beside the short-run update."""
     nnz = rows_np.size
     ws = torch.empty(emb.emb_bag_backward_workspace_bytes(ts.T, B, nnz, ts.total_rows, ts.D, ts.dtype), dtype=torch.uint8, device=DEV)
     uk = torch.full((max(nnz, 1),), -7, dtype=torch.int64, device=DEV)
@@ -119,7 +131,8 @@ def gpu_backward(ts, rows_np, off_np, B, mode, dout_np, lr, eps, want_unique=Tru
     nu = torch.full((1,), -7, dtype=torch.int64, device=DEV)
     status = torch.zeros(1, dtype=torch.int32, device=DEV)
     emb.emb_bag_backward_rowwise_adagrad(ts, dev(rows_np), dev(off_np), B, mode, dev(dout_np), lr, eps, ws,
-                                         uk if want_unique else None, uc if want_unique else None, nu, status)
+                                         uk if want_unique else None, uc if want_unique else None, nu, status,
+                                         None, side_stream() if side else None)
     torch.cuda.synchronize()
     U = int(nu.item())
     return {"unique_keys": uk[:U].cpu().numpy(), "unique_counts": uc[:U].cpu().numpy(), "U": U,

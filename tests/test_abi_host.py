@@ -115,7 +115,7 @@ def test_backward_argument_errors(L):
     def args(**k):
         return [k.get("th", d.ctypes.data), FAKE, 2, k.get("D", 64), 0, FAKE, FAKE, 4, k.get("nnz", 8),
                 k.get("mode", 1), k.get("dout", FAKE), C.c_float(0.01), C.c_float(1e-8), k.get("ws", FAKE),
-                k.get("wsb", need), None, None, None, None, None, None]
+                k.get("wsb", need), None, None, None, None, None, k.get("side", None), None]
     assert f(*args(ws=None)) == WORKSPACE
     assert f(*args(wsb=need - 1)) == WORKSPACE
     assert f(*args(ws=FAKE + 16)) == WORKSPACE          # workspace must be 256-byte aligned
@@ -125,6 +125,11 @@ def test_backward_argument_errors(L):
     assert f(*args(nnz=1 << 31)) == UNSUPPORTED
     noacc = _tables(with_accum=False)
     assert f(*args(th=noacc.ctypes.data)) == UNSUPPORTED
+    # a side stream needs a stream of its own and both events
+    side = (C.c_void_p * 3)(FAKE, FAKE, None)
+    assert f(*args(side=C.addressof(side))) == INVALID
+    side = (C.c_void_p * 3)(None, FAKE, FAKE)           # NULL is the call's own (default) stream here
+    assert f(*args(side=C.addressof(side))) == INVALID
 
 
 def test_workspace_bytes(L):

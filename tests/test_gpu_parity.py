@@ -181,7 +181,7 @@ def _backward_case(rng, T, B, D, Rs, max_len, dtype, mode, hot=0.0, lr=0.01, eps
         old = [H.as_f32(t).copy() for t in ref_tables]
         old_acc = [a.copy() for a in ref_acc]
         ts, w_dev, acc_dev = H.make_tableset(ref_tables, dtype, accum_np=ref_acc)
-        g = H.gpu_backward(ts, rows, off, B, mode, dout, lr, eps)
+        g = H.gpu_backward(ts, rows, off, B, mode, dout, lr, eps, side=(step % 2 == 0))   # both ways
         r = oracle.bag_backward_rowwise_adagrad(ref_tables, ref_acc, dtype, rows, off, B, mode, dout, lr, eps)
         assert g["status"] == r["status"] == 0
         assert np.array_equal(g["unique_keys"], r["unique_keys"])          # bit-exact unique-row set
@@ -307,9 +307,9 @@ def test_backward_is_deterministic():
     tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, 30, scale=0.01, hot_row_frac=0.2)
     dout = rng.standard_normal((T, B, D)).astype(np.float32)
     results = []
-    for rep in range(3):
+    for rep in range(3):                      # the last repetition without the side stream
         ts, w_dev, acc_dev = H.make_tableset(tables, "f32", with_accum=True)
-        H.gpu_backward(ts, rows, off, B, "mean", dout, 0.01, 1e-8)
+        H.gpu_backward(ts, rows, off, B, "mean", dout, 0.01, 1e-8, side=(rep < 2))
         results.append(([w.cpu().numpy() for w in w_dev], [a.cpu().numpy() for a in acc_dev]))
     for rep in (1, 2):
         for t in range(T):
