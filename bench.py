@@ -252,6 +252,9 @@ def main() -> int:
     ap.add_argument("--scale-rows", type=int, default=None, help="rows per table (debug: smaller tables)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the forward-only side measurements")
+    ap.add_argument("--overlap-sort", action="store_true",
+                    help="enqueue the backward's sort on a second stream beside the forward (measured: no gain "
+                         "here, the forward saturates HBM and the sort's small kernels only get slower)")
     ap.add_argument("--no-side-stream", action="store_true",
                     help="run the backward's long-run path after the short-run update instead of beside it")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -300,8 +303,9 @@ def main() -> int:
         del cal
 
     K, W = args.steps, args.warmup
+    step_fn = pipeline.run_step_overlapped if args.overlap_sort else pipeline.run_step
     for i in range(W):
-        pipeline.run_step(w, tabs.set, dbs[i % len(dbs)], buf)
+        step_fn(w, tabs.set, dbs[i % len(dbs)], buf)
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps --------------------------------------
@@ -323,12 +327,16 @@ def main() -> int:
     t0 = time.perf_counter()
     for k in range(K):
         db = dbs[(W + k) % len(dbs)]
-        rows = pipeline.run_index_stage(w, tabs.set, db, buf)
         if w.backward:
-            pipeline.run_forward(w, tabs.set, rows, buf)
-            pipeline.run_backward(w, tabs.set, rows, db, buf,
-                                  stage_events=[None, None, None, dom[k][0], dom[k][1], None])
+            sev = [None, None, None, dom[k][0], dom[k][1], None]
+            if args.overlap_sort:
+                pipeline.run_step_overlapped(w, tabs.set, db, buf, stage_events=sev)
+            else:
+                rows = pipeline.run_index_stage(w, tabs.set, db, buf)
+                pipeline.run_forward(w, tabs.set, rows, buf)
+                pipeline.run_backward(w, tabs.set, rows, db, buf, stage_events=sev)
         else:
+            rows = pipeline.run_index_stage(w, tabs.set, db, buf)
             dom[k][0].record()
             pipeline.run_forward(w, tabs.set, rows, buf)
             dom[k][1].record()

@@ -174,6 +174,37 @@ int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, const emb_tab
                                      uint32_t *status_dev, void *const *stage_events,
                                      const emb_side_stream *side, void *stream);
 
+/* The same backward in two calls, for callers that overlap its first half
+ * with other work: the sort needs only the indices, not the gradient, so it
+ * can be enqueued (on any stream) as soon as rows and offsets exist and run
+ * beside the forward pass and the dense part of the model (Section 3.1: the
+ * tables are trained inside the ranking model).
+ *   emb_bag_backward_sort    validates the offsets, builds and sorts the
+ *                            (row, bag) records and, if asked, writes the list
+ *                            of distinct rows; reads no table memory, writes
+ *                            only the workspace and the optional outputs;
+ *   emb_bag_backward_update  sums the gradients per distinct row and applies
+ *                            the Adagrad step, from the records the first call
+ *                            left in the workspace.
+ * Both take the arguments of emb_bag_backward_rowwise_adagrad with the same
+ * meaning; T, D, dtype, B, nnz, the tables and the workspace must be the same
+ * in both calls, and the update must be ordered after the sort (same stream,
+ * or an event).  The sort records stage events 0..3, the update 3..5.
+ * emb_bag_backward_rowwise_adagrad is exactly the two calls in a row. */
+int emb_bag_backward_sort(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                          int32_t D, int32_t dtype, const int64_t *rows_dev,
+                          const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
+                          void *workspace_dev, size_t workspace_bytes,
+                          int64_t *unique_keys_out_dev, int32_t *unique_counts_out_dev,
+                          int64_t *num_unique_out_dev, uint32_t *status_dev,
+                          void *const *stage_events, void *stream);
+int emb_bag_backward_update(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                            int32_t D, int32_t dtype, int64_t B, int64_t nnz,
+                            const float *dout_dev, float lr, float eps, void *workspace_dev,
+                            size_t workspace_bytes, int64_t *num_unique_out_dev,
+                            void *const *stage_events, const emb_side_stream *side,
+                            void *stream);
+
 /* ---- host-resident table with an HBM hot-row cache (Section 3.3) --------- */
 
 /* Bytes of the cache index for a table of num_rows rows (16 bytes per 64

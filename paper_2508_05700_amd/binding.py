@@ -32,6 +32,7 @@ assert TABLE_DESC.itemsize == 48
 EXPORTS = [
     "emb_status_string", "emb_tables_init", "emb_hash_ids", "emb_hash_ids_tables", "emb_lengths_to_offsets",
     "emb_bag_forward", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
+    "emb_bag_backward_sort", "emb_bag_backward_update",
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_host_device_pointer",
     "emb_table_fill",
 ]
@@ -78,6 +79,10 @@ def lib() -> C.CDLL:
     L.emb_bag_backward_rowwise_adagrad.restype = C.c_int
     L.emb_bag_backward_rowwise_adagrad.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, f32, f32,
                                                    vp, sz, vp, vp, vp, vp, vp, vp, vp]
+    L.emb_bag_backward_sort.restype = C.c_int
+    L.emb_bag_backward_sort.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, sz, vp, vp, vp, vp, vp, vp]
+    L.emb_bag_backward_update.restype = C.c_int
+    L.emb_bag_backward_update.argtypes = [vp, vp, i32, i32, i32, i64, i64, vp, f32, f32, vp, sz, vp, vp, vp, vp]
     L.emb_cache_index_bytes.restype = C.c_int
     L.emb_cache_index_bytes.argtypes = [i64, C.POINTER(sz)]
     L.emb_cache_build.restype = C.c_int
@@ -229,6 +234,49 @@ class SideStream:
                               int(self.events[1].cuda_event))
 
 
+def _stage_events(stage_events):
+    if stage_events is None:
+        return None
+    if len(stage_events) != BWD_STAGE_EVENTS:
+        raise TypeError("stage_events must hold %d events" % BWD_STAGE_EVENTS)
+    return (C.c_void_p * BWD_STAGE_EVENTS)(*[None if e is None else int(e.cuda_event) for e in stage_events])
+
+
+def emb_bag_backward_sort(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
+                          workspace: torch.Tensor, unique_keys: Optional[torch.Tensor] = None,
+                          unique_counts: Optional[torch.Tensor] = None, num_unique: Optional[torch.Tensor] = None,
+                          status: Optional[torch.Tensor] = None,
+                          stage_events: Optional[Sequence[torch.cuda.Event]] = None) -> None:
+    """First half of the backward (indices only); see emb_bag_backward_rowwise_adagrad."""
+    nnz = rows.numel()
+    if offsets.numel() != tables.T * B + 1:
+        raise TypeError("shape mismatch")
+    for t, name in ((unique_keys, "unique_keys"), (unique_counts, "unique_counts")):
+        if t is not None and t.numel() < nnz:
+            raise TypeError(name + " must hold at least nnz elements")
+    _check("emb_bag_backward_sort", lib().emb_bag_backward_sort(
+        tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype],
+        _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode],
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+        _ptr(unique_keys, torch.int64, "unique_keys"), _ptr(unique_counts, torch.int32, "unique_counts"),
+        _ptr(num_unique, torch.int64, "num_unique"), _ptr(status, torch.int32, "status"),
+        _stage_events(stage_events), _stream()))
+
+
+def emb_bag_backward_update(tables: TableSet, B: int, nnz: int, dout: torch.Tensor, lr: float, eps: float,
+                            workspace: torch.Tensor, num_unique: Optional[torch.Tensor] = None,
+                            stage_events: Optional[Sequence[torch.cuda.Event]] = None,
+                            side: Optional["SideStream"] = None) -> None:
+    """Second half of the backward, from the records emb_bag_backward_sort left in ``workspace``."""
+    if dout.numel() != tables.T * B * tables.D:
+        raise TypeError("shape mismatch")
+    _check("emb_bag_backward_update", lib().emb_bag_backward_update(
+        tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype], int(B), int(nnz),
+        _ptr(dout, torch.float32, "dout"), C.c_float(lr), C.c_float(eps),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _ptr(num_unique, torch.int64, "num_unique"),
+        _stage_events(stage_events), None if side is None else C.addressof(side.c), _stream()))
+
+
 def emb_bag_backward_rowwise_adagrad(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
                                      dout: torch.Tensor, lr: float, eps: float, workspace: torch.Tensor,
                                      unique_keys: Optional[torch.Tensor] = None,
@@ -247,19 +295,14 @@ def emb_bag_backward_rowwise_adagrad(tables: TableSet, rows: torch.Tensor, offse
     for t, name in ((unique_keys, "unique_keys"), (unique_counts, "unique_counts")):
         if t is not None and t.numel() < nnz:
             raise TypeError(name + " must hold at least nnz elements")
-    ev = None
-    if stage_events is not None:
-        if len(stage_events) != BWD_STAGE_EVENTS:
-            raise TypeError("stage_events must hold %d events" % BWD_STAGE_EVENTS)
-        ev = (C.c_void_p * BWD_STAGE_EVENTS)(*[None if e is None else int(e.cuda_event) for e in stage_events])
     _check("emb_bag_backward_rowwise_adagrad", lib().emb_bag_backward_rowwise_adagrad(
         tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype],
         _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode],
         _ptr(dout, torch.float32, "dout"), C.c_float(lr), C.c_float(eps),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
         _ptr(unique_keys, torch.int64, "unique_keys"), _ptr(unique_counts, torch.int32, "unique_counts"),
-        _ptr(num_unique, torch.int64, "num_unique"), _ptr(status, torch.int32, "status"), ev,
-        None if side is None else C.addressof(side.c), _stream()))
+        _ptr(num_unique, torch.int64, "num_unique"), _ptr(status, torch.int32, "status"),
+        _stage_events(stage_events), None if side is None else C.addressof(side.c), _stream()))
 
 
 def emb_cache_index_bytes(num_rows: int) -> int:

@@ -326,21 +326,21 @@ __global__ void runs_reset_kernel(BwdCtrl *ctrl)
 // host side
 // ---------------------------------------------------------------------------
 struct BwdArgs {
-    const emb_table *tables_dev;
-    int32_t T, D, dtype, mode;
-    const int64_t *rows, *offsets;
-    int64_t B, nnz, total_rows, max_rows;
-    int passes;   // of the sort: enough for the bits of max_rows, the value that marks an invalid row
-    const float *dout;
-    float lr, eps;
-    char *ws;
-    int64_t *unique_keys_out;
-    int32_t *unique_counts_out;
-    int64_t *num_unique_out;
-    uint32_t *status;
-    void *const *events;
-    const emb_side_stream *side;   // NULL: everything on `stream`
-    hipStream_t stream;
+    const emb_table *tables_dev = nullptr;
+    int32_t T = 0, D = 0, dtype = 0, mode = 0;
+    const int64_t *rows = nullptr, *offsets = nullptr;
+    int64_t B = 0, nnz = 0, total_rows = 0, max_rows = 0;
+    int passes = 1;   // of the sort: enough for the bits of max_rows, the value that marks an invalid row
+    const float *dout = nullptr;
+    float lr = 0.f, eps = 0.f;
+    char *ws = nullptr;
+    int64_t *unique_keys_out = nullptr;
+    int32_t *unique_counts_out = nullptr;
+    int64_t *num_unique_out = nullptr;
+    uint32_t *status = nullptr;
+    void *const *events = nullptr;
+    const emb_side_stream *side = nullptr;   // NULL: everything on `stream`
+    hipStream_t stream = nullptr;
     // record stage event i, if the caller asked for stage timing
     int mark(int i) const
     {
@@ -423,8 +423,9 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     return EMB_OK;
 }
 
+// Keys, sort and the optional list of distinct rows: everything that needs the indices only.
 template <typename KeyT>
-int run_backward(const BwdArgs &a, const BwdLayout &L)
+int run_sort(const BwdArgs &a, const BwdLayout &L)
 {
     BwdCtrl *ctrl = reinterpret_cast<BwdCtrl *>(a.ws + L.ctrl);
     KeyT *keys_a = reinterpret_cast<KeyT *>(a.ws + L.keys_a);
@@ -450,7 +451,7 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
                        first_tile, a.num_unique_out, a.status);
     EMB_RETURN_IF_LAUNCH_FAILED();
     if (a.nnz == 0) {
-        for (int i = 1; i < EMB_BWD_STAGE_EVENTS; ++i) EMB_MARK(a, i);
+        for (int i = 1; i <= 3; ++i) EMB_MARK(a, i);
         return EMB_OK;
     }
 
@@ -510,6 +511,23 @@ int run_backward(const BwdArgs &a, const BwdLayout &L)
     }
 
     EMB_MARK(a, 3);
+    return EMB_OK;
+}
+
+// Segment reduce + Adagrad over the records run_sort left in the workspace.
+template <typename KeyT>
+int run_update(const BwdArgs &a, const BwdLayout &L)
+{
+    // an odd number of passes leaves the sorted records in the second pair of arrays
+    const bool in_b = (a.passes & 1) != 0;
+    const KeyT *kin = reinterpret_cast<const KeyT *>(a.ws + (in_b ? L.keys_b : L.keys_a));
+    const uint32_t *pin = reinterpret_cast<const uint32_t *>(a.ws + (in_b ? L.pay_b : L.pay_a));
+    EMB_MARK(a, 3);
+    if (a.nnz == 0) {
+        EMB_MARK(a, 4);
+        EMB_MARK(a, 5);
+        return EMB_OK;
+    }
     const int chunks = a.D * emb_elem_size(a.dtype) / 16;
     const bool bf16 = a.dtype == EMB_BF16;
 #define EMB_UPD(LL, C, EU)                                                                   \
@@ -542,17 +560,13 @@ extern "C" size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t
     return bwd_layout(T, B, nnz, total_rows, D, dtype).total;
 }
 
-extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
-                                                int32_t D, int32_t dtype, const int64_t *rows_dev,
-                                                const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
-                                                const float *dout_dev, float lr, float eps, void *workspace_dev,
-                                                size_t workspace_bytes, int64_t *unique_keys_out_dev,
-                                                int32_t *unique_counts_out_dev, int64_t *num_unique_out_dev,
-                                                uint32_t *status_dev, void *const *stage_events,
-                                                const emb_side_stream *side, void *stream)
+namespace {
+
+// Host-side checks and the workspace layout shared by the three backward entry points.
+int bwd_plan(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, int64_t B,
+             int64_t nnz, void *workspace_dev, size_t workspace_bytes, void *stream, BwdArgs &a, BwdLayout &L)
 {
     if (B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
-    if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
     int rc = emb_check_row_shape(D, dtype);
     if (rc != EMB_OK) return rc;
     rc = emb_check_tables(tables_host, tables_dev, T, true);
@@ -562,38 +576,92 @@ extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, co
     if (nnz >= ((int64_t)1 << 31)) return EMB_ERR_UNSUPPORTED;
     if (B > 0 && (int64_t)T > ((int64_t)0xFFFFFFFE) / B) return EMB_ERR_UNSUPPORTED;
     if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
-    if (nnz > 0 && (!rows_dev || !offsets_dev || !dout_dev)) return EMB_ERR_INVALID_ARG;
-    if (nnz > 0 && !emb_aligned(dout_dev, 16)) return EMB_ERR_INVALID_ARG;
-    if (side && (!side->stream || !side->fork_event || !side->join_event || side->stream == stream))
-        return EMB_ERR_INVALID_ARG;
 
     int64_t total_rows = 0, max_rows = 0;
     for (int32_t t = 0; t < T; ++t) {
         total_rows += tables_host[t].num_rows;
         if (tables_host[t].num_rows > max_rows) max_rows = tables_host[t].num_rows;
     }
-    const BwdLayout L = bwd_layout(T, B, nnz, total_rows, D, dtype);
+    L = bwd_layout(T, B, nnz, total_rows, D, dtype);
     if (!workspace_dev || !emb_aligned(workspace_dev, 256) || workspace_bytes < L.total) return EMB_ERR_WORKSPACE;
     int bits = 0;
     for (uint64_t v = (uint64_t)max_rows; v; v >>= 1) ++bits;
     int passes = (bits + RADIX_BITS - 1) / RADIX_BITS;
     if (passes < 1) passes = 1;
 
-    BwdArgs a;
+    a = BwdArgs();
     a.tables_dev = tables_dev;
-    a.T = T; a.D = D; a.dtype = dtype; a.mode = mode;
-    a.rows = rows_dev; a.offsets = offsets_dev;
+    a.T = T; a.D = D; a.dtype = dtype;
     a.B = B; a.nnz = nnz; a.total_rows = total_rows; a.max_rows = max_rows;
     a.passes = passes;
-    a.dout = dout_dev;
-    a.lr = lr; a.eps = eps;
     a.ws = reinterpret_cast<char *>(workspace_dev);
+    a.stream = emb_stream(stream);
+    return EMB_OK;
+}
+
+}  // namespace
+
+extern "C" int emb_bag_backward_sort(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
+                                     int32_t dtype, const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B,
+                                     int64_t nnz, int32_t mode, void *workspace_dev, size_t workspace_bytes,
+                                     int64_t *unique_keys_out_dev, int32_t *unique_counts_out_dev,
+                                     int64_t *num_unique_out_dev, uint32_t *status_dev, void *const *stage_events,
+                                     void *stream)
+{
+    if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
+    BwdArgs a;
+    BwdLayout L;
+    const int rc = bwd_plan(tables_host, tables_dev, T, D, dtype, B, nnz, workspace_dev, workspace_bytes, stream, a, L);
+    if (rc != EMB_OK) return rc;
+    if (nnz > 0 && (!rows_dev || !offsets_dev)) return EMB_ERR_INVALID_ARG;
+    a.mode = mode;
+    a.rows = rows_dev; a.offsets = offsets_dev;
     a.unique_keys_out = unique_keys_out_dev;
     a.unique_counts_out = unique_counts_out_dev;
     a.num_unique_out = num_unique_out_dev;
     a.status = status_dev;
     a.events = stage_events;
+    return L.key_bytes == 4 ? run_sort<uint32_t>(a, L) : run_sort<uint64_t>(a, L);
+}
+
+extern "C" int emb_bag_backward_update(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
+                                       int32_t dtype, int64_t B, int64_t nnz, const float *dout_dev, float lr,
+                                       float eps, void *workspace_dev, size_t workspace_bytes,
+                                       int64_t *num_unique_out_dev, void *const *stage_events,
+                                       const emb_side_stream *side, void *stream)
+{
+    BwdArgs a;
+    BwdLayout L;
+    const int rc = bwd_plan(tables_host, tables_dev, T, D, dtype, B, nnz, workspace_dev, workspace_bytes, stream, a, L);
+    if (rc != EMB_OK) return rc;
+    if (nnz > 0 && (!dout_dev || !emb_aligned(dout_dev, 16))) return EMB_ERR_INVALID_ARG;
+    if (side && (!side->stream || !side->fork_event || !side->join_event || side->stream == stream))
+        return EMB_ERR_INVALID_ARG;
+    a.dout = dout_dev;
+    a.lr = lr; a.eps = eps;
+    a.num_unique_out = num_unique_out_dev;
+    a.events = stage_events;
     a.side = side;
-    a.stream = emb_stream(stream);
-    return L.key_bytes == 4 ? run_backward<uint32_t>(a, L) : run_backward<uint64_t>(a, L);
+    return L.key_bytes == 4 ? run_update<uint32_t>(a, L) : run_update<uint64_t>(a, L);
+}
+
+extern "C" int emb_bag_backward_rowwise_adagrad(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                                                int32_t D, int32_t dtype, const int64_t *rows_dev,
+                                                const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
+                                                const float *dout_dev, float lr, float eps, void *workspace_dev,
+                                                size_t workspace_bytes, int64_t *unique_keys_out_dev,
+                                                int32_t *unique_counts_out_dev, int64_t *num_unique_out_dev,
+                                                uint32_t *status_dev, void *const *stage_events,
+                                                const emb_side_stream *side, void *stream)
+{
+    // every argument of the second half is checked before the first half is enqueued
+    if (nnz > 0 && (!dout_dev || !emb_aligned(dout_dev, 16))) return EMB_ERR_INVALID_ARG;
+    if (side && (!side->stream || !side->fork_event || !side->join_event || side->stream == stream))
+        return EMB_ERR_INVALID_ARG;
+    const int rc = emb_bag_backward_sort(tables_host, tables_dev, T, D, dtype, rows_dev, offsets_dev, B, nnz, mode,
+                                         workspace_dev, workspace_bytes, unique_keys_out_dev, unique_counts_out_dev,
+                                         num_unique_out_dev, status_dev, stage_events, stream);
+    if (rc != EMB_OK) return rc;
+    return emb_bag_backward_update(tables_host, tables_dev, T, D, dtype, B, nnz, dout_dev, lr, eps, workspace_dev,
+                                   workspace_bytes, num_unique_out_dev, stage_events, side, stream);
 }

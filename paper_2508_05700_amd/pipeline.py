@@ -67,6 +67,9 @@ class StepBuffers:
             self.num_unique = torch.zeros(1, dtype=torch.int64, device=device)
             if side_stream:   # the backward's two update paths run side by side
                 self.side = emb.SideStream(device)
+            # for run_step_overlapped: the backward's sort runs beside the forward
+            self.sort_stream = torch.cuda.Stream(device=device)
+            self.sort_events = [torch.cuda.Event(), torch.cuda.Event()]
             if want_unique:   # the ordered list of distinct rows is optional output
                 self.unique_keys = torch.empty(n, dtype=torch.int64, device=device)
                 self.unique_counts = torch.empty(n, dtype=torch.int32, device=device)
@@ -91,6 +94,30 @@ def run_backward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, db: Devi
     emb.emb_bag_backward_rowwise_adagrad(tables, rows, buf.offsets, w.B, w.pool, db.dout, w.lr, w.eps, buf.workspace,
                                          buf.unique_keys, buf.unique_counts, buf.num_unique, buf.status,
                                          stage_events, buf.side)
+
+
+def run_step_overlapped(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers,
+                        stage_events=None) -> torch.Tensor:
+    """One pass of the whole path with the backward's sort enqueued on a second stream as soon as
+    the indices exist, beside the forward (it needs neither the tables nor the gradient); the
+    update follows on the calling stream once both are done.  ``stage_events`` go to the update only
+    (entries 3 to 5)."""
+    rows = run_index_stage(w, tables, db, buf)
+    if not w.backward:
+        run_forward(w, tables, rows, buf)
+        return rows
+    main = torch.cuda.current_stream()
+    buf.sort_events[0].record(main)
+    with torch.cuda.stream(buf.sort_stream):
+        buf.sort_stream.wait_event(buf.sort_events[0])
+        emb.emb_bag_backward_sort(tables, rows, buf.offsets, w.B, w.pool, buf.workspace, buf.unique_keys,
+                                  buf.unique_counts, buf.num_unique, buf.status)
+        buf.sort_events[1].record(buf.sort_stream)
+    run_forward(w, tables, rows, buf)
+    main.wait_event(buf.sort_events[1])
+    emb.emb_bag_backward_update(tables, w.B, rows.numel(), db.dout, w.lr, w.eps, buf.workspace, buf.num_unique,
+                                stage_events, buf.side)
+    return rows
 
 
 def run_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:

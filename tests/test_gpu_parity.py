@@ -301,6 +301,50 @@ def test_backward_sort_segments_small_empty_and_large_tables():
         assert np.array_equal(w_dev2[t].cpu().numpy(), w_dev[t].cpu().numpy())
 
 
+def test_backward_split_calls_on_two_streams_equal_the_single_call():
+    # emb_bag_backward_sort on a second stream (while other work runs on the first), then
+    # emb_bag_backward_update: bit-identical tables, accumulators and row lists.
+    rng = np.random.default_rng(4343)
+    T, B, D, Rs = 3, 1800, 64, [30_000, 500, 70_000]
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, 30, scale=0.01, hot_row_frac=0.1)
+    rows = rows.copy()
+    rows[[3, 40_000]] = [1 << 40, -1]                        # invalid rows travel through the split too
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    nnz = rows.size
+    ts1, w1, a1 = H.make_tableset(tables, "f32", with_accum=True)
+    g1 = H.gpu_backward(ts1, rows, off, B, "mean", dout, 0.01, 1e-8, side=False)
+    ts2, w2, a2 = H.make_tableset(tables, "f32", with_accum=True)
+    ws = torch.empty(emb.emb_bag_backward_workspace_bytes(T, B, nnz, ts2.total_rows, D, "f32"), dtype=torch.uint8,
+                     device=H.DEV)
+    uk = torch.full((nnz,), -7, dtype=torch.int64, device=H.DEV)
+    uc = torch.full((nnz,), -7, dtype=torch.int32, device=H.DEV)
+    nu = torch.full((1,), -7, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    rows_d, off_d, dout_d = H.dev(rows), H.dev(off), H.dev(dout)
+    out = torch.empty((T, B, D), dtype=torch.float32, device=H.DEV)
+    second = torch.cuda.Stream()
+    ready, done = torch.cuda.Event(), torch.cuda.Event()
+    torch.cuda.synchronize()
+    main = torch.cuda.current_stream()
+    ready.record(main)
+    with torch.cuda.stream(second):
+        second.wait_event(ready)
+        emb.emb_bag_backward_sort(ts2, rows_d, off_d, B, "mean", ws, uk, uc, nu, status)
+        done.record(second)
+    emb.emb_bag_forward(ts2, rows_d, off_d, B, "mean", out, status)      # runs beside the sort
+    main.wait_event(done)
+    emb.emb_bag_backward_update(ts2, B, nnz, dout_d, 0.01, 1e-8, ws, nu, None, H.side_stream())
+    torch.cuda.synchronize()
+    U = int(nu.item())
+    assert int(status.item()) == g1["status"] == emb.STATUS_BAD_INDEX
+    assert U == g1["U"]
+    assert np.array_equal(uk[:U].cpu().numpy(), g1["unique_keys"])
+    assert np.array_equal(uc[:U].cpu().numpy(), g1["unique_counts"])
+    for t in range(T):
+        assert np.array_equal(w1[t].cpu().numpy(), w2[t].cpu().numpy())
+        assert np.array_equal(a1[t].cpu().numpy(), a2[t].cpu().numpy())
+
+
 def test_backward_is_deterministic():
     rng = np.random.default_rng(43)
     T, B, D, Rs = 2, 1500, 64, [20_000, 300]
