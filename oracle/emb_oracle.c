@@ -62,8 +62,59 @@ static uint16_t round_bf16(float f)
     return (uint16_t)(u >> 16);
 }
 
+/* ---- row-quantised storage (Section 4.1.2: INT4 tables) ------------------ */
+
+int64_t oracle_quant_row_bytes(int32_t D, int32_t dtype)
+{
+    if (D <= 0) return 0;
+    int64_t code_bytes;
+    if (dtype == ORACLE_INT8) code_bytes = D;
+    else if (dtype == ORACLE_INT4 && D % 2 == 0) code_bytes = D / 2;
+    else return 0;
+    return (8 + code_bytes + 15) / 16 * 16;
+}
+
+void oracle_quantize_rows(const float *src, int64_t R, int32_t D, int32_t dtype, uint8_t *dst)
+{
+    const int64_t rb = oracle_quant_row_bytes(D, dtype);
+    const float qmax = dtype == ORACLE_INT8 ? 255.0f : 15.0f;
+    for (int64_t r = 0; r < R; ++r) {
+        const float *x = src + r * D;
+        uint8_t *row = dst + r * rb;
+        memset(row, 0, (size_t)rb);
+        float lo = x[0], hi = x[0];
+        for (int32_t d = 1; d < D; ++d) {
+            if (x[d] < lo) lo = x[d];
+            if (x[d] > hi) hi = x[d];
+        }
+        float scale = hi == lo ? 1.0f : (hi - lo) / qmax;
+        float bias = lo;
+        memcpy(row, &scale, 4);
+        memcpy(row + 4, &bias, 4);
+        for (int32_t d = 0; d < D; ++d) {
+            float q = rintf((x[d] - bias) / scale); /* ties to even in the default rounding mode */
+            if (q < 0.0f) q = 0.0f;
+            if (q > qmax) q = qmax;
+            uint8_t code = (uint8_t)q;
+            if (dtype == ORACLE_INT8) row[8 + d] = code;
+            else row[8 + d / 2] |= (uint8_t)(code << (4 * (d % 2)));
+        }
+    }
+}
+
+static double load_quant(const void *table, int32_t dtype, int64_t row, int32_t D, int32_t d)
+{
+    const uint8_t *p = (const uint8_t *)table + row * oracle_quant_row_bytes(D, dtype);
+    float scale, bias;
+    memcpy(&scale, p, 4);
+    memcpy(&bias, p + 4, 4);
+    unsigned code = dtype == ORACLE_INT8 ? p[8 + d] : (p[8 + d / 2] >> (4 * (d % 2))) & 15u;
+    return (double)scale * (double)code + (double)bias;
+}
+
 static double load_elem(const void *table, int32_t dtype, int64_t row, int32_t D, int32_t d)
 {
+    if (dtype == ORACLE_INT8 || dtype == ORACLE_INT4) return load_quant(table, dtype, row, D, d);
     if (dtype == ORACLE_BF16)
         return (double)widen_bf16(((const uint16_t *)table)[row * D + d]);
     return (double)((const float *)table)[row * D + d];

@@ -27,7 +27,7 @@ extern "C" {
 #endif
 
 enum { ORACLE_POOL_SUM = 0, ORACLE_POOL_MEAN = 1 };
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_INT8 = 2, ORACLE_INT4 = 3 };
 /* status bits, OR-ed into *status (may be NULL) */
 enum { ORACLE_STATUS_BAD_INDEX = 1, ORACLE_STATUS_BAD_OFFSETS = 2 };
 
@@ -45,9 +45,32 @@ void oracle_hash_ids(const uint64_t *raw, int64_t n, uint64_t salt, int64_t num_
 void oracle_lengths_to_offsets(const int32_t *lengths, int64_t n, int64_t *offsets,
                                uint32_t *status);
 
+/* Row-quantised table storage (Section 3.3 / 4.1.2: the CPU-hosted tables are
+ * stored as INT4 after post-training quantisation, about 40 % of their fp16
+ * size; the paper gives no scheme, this is the usual row-wise one).  A row of
+ * D elements with b = 8 or 4 bits per code occupies
+ *     bytes 0..3  scale (fp32)      bytes 4..7  bias (fp32)
+ *     bytes 8..   codes: INT8 one byte per element; INT4 element 2k in the low
+ *                 nibble of byte k, element 2k+1 in the high nibble
+ * zero-padded to a multiple of 16 bytes (D = 64, INT4: 48 bytes = 37.5 % of
+ * the 128 bytes of an fp16 row).  Element d of the row has the value
+ * scale * code_d + bias.  Returns the row size, or 0 if dtype is not
+ * ORACLE_INT8 / ORACLE_INT4 or D is not positive (INT4: and even). */
+int64_t oracle_quant_row_bytes(int32_t D, int32_t dtype);
+
+/* Row-wise asymmetric min/max quantisation of an fp32 table [R, D] into the
+ * storage above.  Per row, all in fp32 with round-to-nearest-even:
+ *     lo = min_d x_d, hi = max_d x_d, bias = lo,
+ *     scale = (hi - lo) / (2^b - 1), or 1 if hi == lo,
+ *     code_d = min(max(rint((x_d - bias) / scale), 0), 2^b - 1).
+ * dst: R * oracle_quant_row_bytes bytes. */
+void oracle_quantize_rows(const float *src, int64_t R, int32_t D, int32_t dtype, uint8_t *dst);
+
 /* Pooled lookup (EmbeddingBag): out[t,b,:] = sum over the bag's lookups of
  * W_t[rows[j],:]; mean divides by the bag length; an empty bag gives 0.
- * bf16 rows are widened exactly to fp32 first.  Accumulation in double,
+ * bf16 rows are widened exactly to fp32 first; rows of a quantised table
+ * (ORACLE_INT8 / ORACLE_INT4, layout above) contribute scale * code + bias.
+ * Accumulation in double,
  * rounded once to fp32.  absum (nullable, [T,B,D] double) receives the sum of
  * |terms| (divided by the length for mean), the scale of the rounding-error
  * bound.  A lookup whose row is outside [0, num_rows[t]) is skipped and sets

@@ -18,7 +18,7 @@ _SRC = os.path.join(_HERE, "emb_oracle.c")
 _LIB = os.path.join(_HERE, "libemb_oracle.so")
 
 POOL = {"sum": 0, "mean": 1}
-DTYPE = {"f32": 0, "bf16": 1}
+DTYPE = {"f32": 0, "bf16": 1, "int8": 2, "int4": 3}
 STATUS_BAD_INDEX = 1
 STATUS_BAD_OFFSETS = 2
 
@@ -47,6 +47,10 @@ def lib() -> C.CDLL:
         L.oracle_hash_ids.argtypes = [vp, i64, u64, i64, vp]
         L.oracle_lengths_to_offsets.restype = None
         L.oracle_lengths_to_offsets.argtypes = [vp, i64, vp, vp]
+        L.oracle_quant_row_bytes.restype = i64
+        L.oracle_quant_row_bytes.argtypes = [i32, i32]
+        L.oracle_quantize_rows.restype = None
+        L.oracle_quantize_rows.argtypes = [vp, i64, i32, i32, vp]
         L.oracle_bag_forward.restype = None
         L.oracle_bag_forward.argtypes = [vp, i32, vp, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp]
         L.oracle_bag_backward_rowwise_adagrad.restype = C.c_int
@@ -74,7 +78,22 @@ def _ptr_array(arrs: Sequence[np.ndarray]):
 
 
 def _table_np_dtype(dtype: str):
-    return np.float32 if dtype == "f32" else np.uint16
+    return {"f32": np.float32, "bf16": np.uint16, "int8": np.uint8, "int4": np.uint8}[dtype]
+
+
+def quant_row_bytes(D: int, dtype: str) -> int:
+    return int(lib().oracle_quant_row_bytes(int(D), DTYPE[dtype]))
+
+
+def quantize_rows(table: np.ndarray, dtype: str) -> np.ndarray:
+    """fp32 [R, D] -> row-quantised storage, uint8 [R, quant_row_bytes(D, dtype)]."""
+    table = _chk(np.ascontiguousarray(table), np.float32)
+    R, D = table.shape
+    rb = quant_row_bytes(D, dtype)
+    assert rb > 0
+    out = np.empty((R, rb), dtype=np.uint8)
+    lib().oracle_quantize_rows(_p(table), R, D, DTYPE[dtype], _p(out))
+    return out
 
 
 def splitmix64(x: int) -> int:
@@ -97,13 +116,17 @@ def lengths_to_offsets(lengths: np.ndarray) -> Tuple[np.ndarray, int]:
 
 
 def bag_forward(tables: Sequence[np.ndarray], dtype: str, rows: np.ndarray, offsets: np.ndarray,
-                B: int, mode: str, want_absum: bool = True):
-    """Returns (out fp32 [T,B,D], absum fp64 [T,B,D] or None, status)."""
+                B: int, mode: str, want_absum: bool = True, D: Optional[int] = None):
+    """Returns (out fp32 [T,B,D], absum fp64 [T,B,D] or None, status).  Row-quantised tables
+    (``int8`` / ``int4``) are uint8 [R, quant_row_bytes] and need ``D``."""
     T = len(tables)
-    D = int(tables[0].shape[1])
+    quant = dtype in ("int8", "int4")
+    assert quant == (D is not None)
+    width = quant_row_bytes(D, dtype) if quant else int(tables[0].shape[1])
+    D = int(D) if quant else width
     for t in tables:
         _chk(t, _table_np_dtype(dtype))
-        assert t.shape[1] == D
+        assert t.shape[1] == width
     rows = _chk(np.ascontiguousarray(rows), np.int64)
     offsets = _chk(np.ascontiguousarray(offsets), np.int64)
     assert offsets.size == T * B + 1

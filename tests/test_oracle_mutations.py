@@ -43,20 +43,41 @@ MUTATIONS = [
     ("backward: gradient of wrong bag", "lk[n].bag = bag;", "lk[n].bag = bag > 0 ? bag - 1 : bag;"),
     ("backward: per-occurrence update", "for (; i < n && lk[i].key == key; ++i) {", "for (int once = 1; once && i < n; ++i, once = 0) {"),
     ("backward: accumulator not stored", "accum[t][r] = (float)s_new;", ""),
+    ("quant: 16 levels for INT4", "dtype == ORACLE_INT8 ? 255.0f : 15.0f", "dtype == ORACLE_INT8 ? 255.0f : 16.0f"),
+    ("quant: truncation instead of rounding", "rintf((x[d] - bias) / scale)", "floorf((x[d] - bias) / scale)"),
+    ("quant: rounding half up", "rintf((x[d] - bias) / scale)", "floorf((x[d] - bias) / scale + 0.5f)"),
+    ("quant: nibble order on store", "(code << (4 * (d % 2)))", "(code << (4 * (1 - d % 2)))"),
+    ("quant: nibble order on load", ">> (4 * (d % 2))) & 15u", ">> (4 * (1 - d % 2))) & 15u"),
+    ("quant: bias not subtracted", "(x[d] - bias) / scale", "x[d] / scale"),
+    ("quant: bias is the maximum", "float bias = lo;", "float bias = hi;"),
+    ("quant: scale and bias swapped on load", "memcpy(&scale, p, 4);\n    memcpy(&bias, p + 4, 4);",
+     "memcpy(&bias, p, 4);\n    memcpy(&scale, p + 4, 4);"),
+    ("quant: bias dropped on load", "(double)scale * (double)code + (double)bias", "(double)scale * (double)code"),
+    ("quant: row stride unpadded", "return (8 + code_bytes + 15) / 16 * 16;", "return 8 + code_bytes;"),
+    ("quant: INT8 codes read as nibbles", "dtype == ORACLE_INT8 ? p[8 + d] :", "dtype != ORACLE_INT8 ? p[8 + d] :"),
     ("cached: hits and misses swapped", "hit_miss[hit ? 0 : 1] += 1;", "hit_miss[hit ? 1 : 0] += 1;"),
 ]
 
 
 def _pin_calls():
+    """Every pin test with every combination of its parametrize marks, as (name, fn, kwargs)."""
+    import itertools
     calls = []
     for name, fn in sorted(vars(pins).items()):
         if not name.startswith("test_") or not callable(fn):
             continue
-        params = inspect.signature(fn).parameters
-        if "mode" in params:
-            calls += [(name, fn, {"mode": m}) for m in ("sum", "mean")]
-        else:
-            calls.append((name, fn, {}))
+        axes = []
+        for mark in getattr(fn, "pytestmark", []):
+            if mark.name != "parametrize":
+                continue
+            names = [n.strip() for n in mark.args[0].split(",")]
+            values = [v if isinstance(v, (tuple, list)) and len(names) > 1 else (v,) for v in mark.args[1]]
+            axes.append([dict(zip(names, v)) for v in values])
+        for combo in itertools.product(*axes):
+            kw = {}
+            for part in combo:
+                kw.update(part)
+            calls.append((name, fn, kw))
     return calls
 
 

@@ -444,3 +444,133 @@ def test_backward_bf16_tie_rounds_to_even(oracle):
     assert np.all(bits[0] == 0x3F80)
     assert np.all(bits[1] == 0x3F7F)
     np.testing.assert_array_equal(S, [9.0, 9.0])
+
+
+# ---------------------------------------------------------------------------
+# row-quantised tables (INT8 / INT4 storage, Section 4.1.2)
+# ---------------------------------------------------------------------------
+def _unpack(q, D, dtype):
+    """scale, bias, codes of packed rows, taken apart by hand from the stated layout."""
+    scale = q[:, 0:4].copy().view(np.float32)[:, 0]
+    bias = q[:, 4:8].copy().view(np.float32)[:, 0]
+    if dtype == "int8":
+        codes = q[:, 8:8 + D].astype(np.int64)
+    else:
+        b = q[:, 8:8 + D // 2].astype(np.int64)
+        codes = np.empty((q.shape[0], D), dtype=np.int64)
+        codes[:, 0::2] = b & 15
+        codes[:, 1::2] = b >> 4
+    return scale, bias, codes
+
+
+def test_quantized_row_size_matches_the_papers_ratio(oracle):
+    # Section 4.1.2: the INT4 tables take about 40 % of their fp16 size.  An fp16 row of D = 64 is 128 bytes.
+    assert oracle.quant_row_bytes(64, "int4") == 48            # 37.5 %
+    assert oracle.quant_row_bytes(32, "int4") == 32 and oracle.quant_row_bytes(128, "int4") == 80
+    assert oracle.quant_row_bytes(64, "int8") == 80 and oracle.quant_row_bytes(8, "int8") == 16
+    assert oracle.quant_row_bytes(63, "int4") == 0 and oracle.quant_row_bytes(0, "int8") == 0
+    assert oracle.quant_row_bytes(64, "f32") == 0
+
+
+@pytest.mark.parametrize("dtype,qmax", [("int8", 255), ("int4", 15)])
+def test_quantizer_invariants(oracle, dtype, qmax):
+    rng = np.random.default_rng(77)
+    D = 64
+    x = (rng.standard_normal((300, D)) * rng.uniform(1e-3, 10, size=(300, 1))).astype(np.float32)
+    x[7] = 0.25                                                   # a constant row
+    q = oracle.quantize_rows(x, dtype)
+    assert q.shape == (300, oracle.quant_row_bytes(D, dtype))
+    scale, bias, codes = _unpack(q, D, dtype)
+    assert np.array_equal(bias, x.min(axis=1))                    # bias is the row minimum, exactly
+    lo, hi = x.min(axis=1).astype(np.float64), x.max(axis=1).astype(np.float64)
+    var = hi > lo
+    assert np.allclose(scale[var], (hi[var] - lo[var]) / qmax, rtol=2e-7, atol=0)
+    assert scale[7] == 1.0 and np.all(codes[7] == 0)
+    assert codes.min() >= 0 and codes.max() <= qmax
+    rows = np.arange(300)
+    assert np.all(codes[rows, x.argmin(axis=1)] == 0)             # the extremes get the end codes
+    assert np.all(codes[rows[var], x[var].argmax(axis=1)] == qmax)
+    deq = scale[:, None].astype(np.float64) * codes + bias[:, None].astype(np.float64)
+    err = np.abs(deq - x.astype(np.float64))
+    assert np.all(err <= 0.5 * scale[:, None] * (1 + 1e-5) + 1e-12)   # nearest code
+    order = np.argsort(x, axis=1, kind="stable")
+    assert np.all(np.diff(np.take_along_axis(codes, order, axis=1), axis=1) >= 0)   # monotone in x
+    pad = q[:, 8 + (D if dtype == "int8" else D // 2):]
+    assert pad.size > 0 and not pad.any()                         # padding is zero
+
+
+@pytest.mark.parametrize("dtype,qmax", [("int8", 255), ("int4", 15)])
+def test_quantizer_is_exact_on_grid_rows(oracle, dtype, qmax):
+    # rows whose elements are bias + k * 2^-e with both end codes present come back unchanged
+    rng = np.random.default_rng(78)
+    D = 32
+    k = rng.integers(0, qmax + 1, size=(50, D))
+    k[:, 3], k[:, 17] = 0, qmax
+    step = 2.0 ** -rng.integers(2, 9, size=(50, 1))
+    base = rng.integers(-40, 40, size=(50, 1)) * step
+    x = (base + k * step).astype(np.float32)
+    scale, bias, codes = _unpack(oracle.quantize_rows(x, dtype), D, dtype)
+    assert np.array_equal(codes, k)
+    assert np.array_equal(scale, step[:, 0].astype(np.float32)) and np.array_equal(bias, base[:, 0].astype(np.float32))
+
+
+@pytest.mark.parametrize("dtype,qmax", [("int8", 255), ("int4", 15)])
+def test_quantizer_rounds_ties_to_even(oracle, dtype, qmax):
+    # a row spanning [0, qmax] has scale exactly 1: x = k + 0.5 is an exact tie
+    D = 16
+    x = np.zeros((1, D), dtype=np.float32)
+    x[0, :8] = [0.0, qmax, 0.5, 1.5, 2.5, 3.5, 4.5, qmax - 0.5]
+    scale, bias, codes = _unpack(oracle.quantize_rows(x, dtype), D, dtype)
+    assert scale[0] == 1.0 and bias[0] == 0.0
+    assert list(codes[0, :8]) == [0, qmax, 0, 2, 2, 4, 4, qmax - 1]
+
+
+@pytest.mark.parametrize("dtype,tdtype,qmax", [("int8", torch.quint8, 255), ("int4", torch.quint4x2, 15)])
+def test_quantizer_agrees_with_torch_per_channel_float_qparams(oracle, dtype, tdtype, qmax):
+    # torch's row-wise quantiser with float scale / zero point (its embedding-table scheme) rounds
+    # x / scale + zero_point instead of (x - bias) / scale: codes may differ by one at near-ties only
+    rng = np.random.default_rng(79)
+    D = 64
+    x = torch.from_numpy((rng.standard_normal((400, D)) * 0.01).astype(np.float32))
+    lo, hi = x.min(1).values, x.max(1).values
+    tscale = (hi - lo) / qmax
+    tq = torch.quantize_per_channel(x, tscale, -lo / tscale, 0, tdtype)
+    tdeq = tq.dequantize().numpy().astype(np.float64)
+    tcodes = np.rint((tdeq - lo.numpy()[:, None].astype(np.float64)) / tscale.numpy()[:, None].astype(np.float64))
+    scale, bias, codes = _unpack(oracle.quantize_rows(x.numpy(), dtype), D, dtype)
+    diff = np.abs(codes - tcodes)
+    assert diff.max() <= 1 and (diff != 0).mean() < 2e-3
+    assert np.array_equal(scale, tscale.numpy())
+    if dtype == "int4":   # same nibble order as torch's packed storage
+        packed = tq.int_repr().numpy().reshape(400, D // 2)
+        mine = oracle.quantize_rows(x.numpy(), dtype)[:, 8:8 + D // 2]
+        assert (packed != mine).mean() < 4e-3
+
+
+@pytest.mark.parametrize("dtype,qmax", [("int8", 255), ("int4", 15)])
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_quantized_forward_equals_fp32_forward_of_the_dequantized_table(oracle, dtype, qmax, mode):
+    rng = np.random.default_rng(80)
+    T, B, D, R = 2, 9, 16, 40
+    # grid-valued tables: quantisation is lossless (pinned above), so both paths sum identical numbers
+    tabs = []
+    for t in range(T):
+        k = rng.integers(0, qmax + 1, size=(R, D))
+        k[:, 0], k[:, 5] = 0, qmax
+        step = 2.0 ** -rng.integers(2, 7, size=(R, 1))
+        tabs.append((rng.integers(-9, 9, size=(R, 1)) * step + k * step).astype(np.float32))
+    lengths = rng.integers(0, 6, size=T * B).astype(np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    rows = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    qt = [oracle.quantize_rows(x, dtype) for x in tabs]
+    out_q, absum_q, st = oracle.bag_forward(qt, dtype, rows, off, B, mode, D=D)
+    out_f, absum_f, _ = oracle.bag_forward(tabs, "f32", rows, off, B, mode)
+    assert st == 0 and np.array_equal(out_q, out_f) and np.array_equal(absum_q, absum_f)
+    # and torch's embedding_bag over its own dequantised copy of a generic (lossy) table
+    x = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+    scale, bias, codes = _unpack(oracle.quantize_rows(x, dtype), D, dtype)
+    deq = torch.from_numpy(scale[:, None].astype(np.float64) * codes + bias[:, None].astype(np.float64))
+    o1, _, _ = oracle.bag_forward([oracle.quantize_rows(x, dtype)], dtype, rows[:off[B]], off[:B + 1], B, mode, D=D)
+    ref = torch.nn.functional.embedding_bag(torch.from_numpy(rows[:off[B]]), deq, torch.from_numpy(off[:B]),
+                                            mode=mode, include_last_offset=False)
+    assert np.allclose(o1[0], ref.numpy(), rtol=1e-6, atol=1e-9)
