@@ -55,7 +55,9 @@ typedef enum {
 } emb_status;
 
 typedef enum { EMB_POOL_SUM = 0, EMB_POOL_MEAN = 1 } emb_pool;
-typedef enum { EMB_F32 = 0, EMB_BF16 = 1 } emb_dtype;
+/* Storage type of table rows.  EMB_INT8 / EMB_INT4 are row-quantised tables
+ * (see emb_quantize_rows); only the forward lookup reads those. */
+typedef enum { EMB_F32 = 0, EMB_BF16 = 1, EMB_INT8 = 2, EMB_INT4 = 3 } emb_dtype;
 
 /* bits of the device status word */
 #define EMB_STATUS_BAD_INDEX 1u   /* a row index < 0 or >= num_rows of its table */
@@ -66,7 +68,7 @@ typedef enum { EMB_F32 = 0, EMB_BF16 = 1 } emb_dtype;
  * the multi-table calls: in host memory (read for validation) and in device
  * memory (read by the kernels); the caller keeps the two copies identical. */
 typedef struct emb_table {
-    void *weights;      /* dev: [num_rows, D] fp32 or bf16, 16-byte aligned          */
+    void *weights;      /* dev: num_rows rows of emb_row_bytes each, 16-byte aligned */
     float *accum;       /* dev: [num_rows] fp32 Adagrad accumulators; NULL if unused */
     int64_t num_rows;   /* > 0                                                       */
     int64_t row_base;   /* sum of num_rows of the preceding tables (emb_tables_init) */
@@ -107,10 +109,13 @@ int emb_lengths_to_offsets(const int32_t *lengths_dev, int64_t n, int64_t *offse
 /* Pooled lookup over T tables (Sections 2.2, 3.1):
  *   out[t,b,:] = sum_{j in [offsets[tB+b], offsets[tB+b+1])} W_t[rows[j], :]
  * EMB_POOL_MEAN divides by the bag length; an empty bag gives zeros.  bf16
- * rows are widened exactly and accumulated in fp32; out is fp32 [T,B,D] and
- * is fully overwritten.  rows_dev: i64[nnz]; offsets_dev: i64[T*B+1].
+ * rows are widened exactly and accumulated in fp32; rows of a quantised table
+ * (EMB_INT8, EMB_INT4) contribute scale * code + bias, dequantised in fp32
+ * while they are gathered; out is fp32 [T,B,D] and is fully overwritten.
+ * rows_dev: i64[nnz]; offsets_dev: i64[T*B+1].
  * EMB_ERR_UNSUPPORTED if D*element_size is not a multiple of 16 or exceeds
- * 16384 bytes, or T > 65535.  B == 0 or T == 0 does nothing. */
+ * 16384 bytes (quantised: D not a multiple of 16 or above 1024), or T > 65535.
+ * B == 0 or T == 0 does nothing. */
 int emb_bag_forward(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
                     int32_t D, int32_t dtype, const int64_t *rows_dev,
                     const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
@@ -204,6 +209,26 @@ int emb_bag_backward_update(const emb_table *tables_host, const emb_table *table
                             size_t workspace_bytes, int64_t *num_unique_out_dev,
                             void *const *stage_events, const emb_side_stream *side,
                             void *stream);
+
+/* ---- row-quantised tables (Section 4.1.2: INT4 tables for serving) ------- */
+
+/* Bytes of one table row: D*4 (EMB_F32), D*2 (EMB_BF16), or for the quantised
+ * types 8 + D (EMB_INT8) / 8 + D/2 (EMB_INT4) rounded up to a multiple of 16:
+ *   bytes 0..3 scale (fp32), bytes 4..7 bias (fp32), then the codes: one byte
+ *   per element (INT8), or element 2k in the low and 2k+1 in the high nibble
+ *   of byte k (INT4); zero padding.  Element value = scale * code + bias.
+ * D = 64: 48 bytes for INT4, 37.5 % of an fp16 row.  0 on invalid arguments. */
+int64_t emb_row_bytes(int32_t D, int32_t dtype);
+
+/* Post-training quantisation of an fp32 table [num_rows, D] (src_dev) into
+ * the row storage above (dst_dev, num_rows * emb_row_bytes bytes), row by row,
+ * asymmetric min/max, all in fp32 with IEEE division and round-half-even:
+ *   bias = min_d x_d, scale = (max_d x_d - bias) / (2^b - 1), or 1 if the row
+ *   is constant, code_d = clamp(rint((x_d - bias) / scale), 0, 2^b - 1).
+ * dtype: EMB_INT8 or EMB_INT4.  Both pointers 16-byte aligned.
+ * EMB_ERR_UNSUPPORTED if D is not a multiple of 16 or above 1024. */
+int emb_quantize_rows(const float *src_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                      void *dst_dev, void *stream);
 
 /* ---- host-resident table with an HBM hot-row cache (Section 3.3) --------- */
 

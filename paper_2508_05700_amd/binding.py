@@ -18,7 +18,7 @@ import torch
 from . import build as _build
 
 POOL = {"sum": 0, "mean": 1}
-DTYPE = {"f32": 0, "bf16": 1}
+DTYPE = {"f32": 0, "bf16": 1, "int8": 2, "int4": 3}
 STATUS_BAD_INDEX = 1
 STATUS_BAD_OFFSETS = 2
 STATUS_BAD_HOT_SET = 4
@@ -32,7 +32,7 @@ assert TABLE_DESC.itemsize == 48
 EXPORTS = [
     "emb_status_string", "emb_tables_init", "emb_hash_ids", "emb_hash_ids_tables", "emb_lengths_to_offsets",
     "emb_bag_forward", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
-    "emb_bag_backward_sort", "emb_bag_backward_update",
+    "emb_bag_backward_sort", "emb_bag_backward_update", "emb_row_bytes", "emb_quantize_rows",
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_host_device_pointer",
     "emb_table_fill",
 ]
@@ -83,6 +83,10 @@ def lib() -> C.CDLL:
     L.emb_bag_backward_sort.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, sz, vp, vp, vp, vp, vp, vp]
     L.emb_bag_backward_update.restype = C.c_int
     L.emb_bag_backward_update.argtypes = [vp, vp, i32, i32, i32, i64, i64, vp, f32, f32, vp, sz, vp, vp, vp, vp]
+    L.emb_row_bytes.restype = i64
+    L.emb_row_bytes.argtypes = [i32, i32]
+    L.emb_quantize_rows.restype = C.c_int
+    L.emb_quantize_rows.argtypes = [vp, i64, i32, i32, vp, vp]
     L.emb_cache_index_bytes.restype = C.c_int
     L.emb_cache_index_bytes.argtypes = [i64, C.POINTER(sz)]
     L.emb_cache_build.restype = C.c_int
@@ -122,14 +126,15 @@ def _check(fn: str, rc: int) -> None:
 
 
 _U64 = (torch.int64, torch.uint64)
-_TABLE_TORCH = {"f32": torch.float32, "bf16": torch.bfloat16}
+_TABLE_TORCH = {"f32": torch.float32, "bf16": torch.bfloat16, "int8": torch.uint8, "int4": torch.uint8}
 
 
 class TableSet:
     """The ``emb_table`` descriptor array of T tables, on the host and on the device.
 
-    ``weights[t]`` is a device tensor ``[R_t, D]`` (fp32 or bf16) or, for memory
-    that torch does not own (mapped host memory), a tuple ``(ptr, num_rows)``.
+    ``weights[t]`` is a device tensor ``[R_t, D]`` (fp32 or bf16; uint8
+    ``[R_t, emb_row_bytes]`` for the quantised types) or, for memory that torch
+    does not own (mapped host memory), a tuple ``(ptr, num_rows)``.
     ``accum[t]`` is a device fp32 tensor ``[R_t]`` or None.
     """
 
@@ -145,8 +150,9 @@ class TableSet:
             if isinstance(w, tuple):
                 ptr, rows = int(w[0]), int(w[1])
             else:
-                if w.dim() != 2 or w.shape[1] != self.D:
-                    raise TypeError("weights[%d] must be [num_rows, D]" % t)
+                width = emb_row_bytes(self.D, dtype) if dtype in ("int8", "int4") else self.D
+                if w.dim() != 2 or w.shape[1] != width:
+                    raise TypeError("weights[%d] must be [num_rows, %d]" % (t, width))
                 ptr, rows = _ptr(w, _TABLE_TORCH[dtype], "weights[%d]" % t), int(w.shape[0])
             self.host["weights"][t] = ptr
             self.host["num_rows"][t] = rows
@@ -210,6 +216,19 @@ def emb_bag_forward(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor,
         tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype],
         _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), rows.numel(), POOL[mode],
         _ptr(out, torch.float32, "out"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_row_bytes(D: int, dtype: str) -> int:
+    return int(lib().emb_row_bytes(int(D), DTYPE[dtype]))
+
+
+def emb_quantize_rows(src: torch.Tensor, dtype: str, dst: torch.Tensor) -> None:
+    """fp32 ``src`` [R, D] -> row-quantised ``dst`` uint8 [R, emb_row_bytes(D, dtype)]."""
+    R, D = int(src.shape[0]), int(src.shape[1])
+    if dst.numel() != R * emb_row_bytes(D, dtype):
+        raise TypeError("dst must hold R * emb_row_bytes bytes")
+    _check("emb_quantize_rows", lib().emb_quantize_rows(_ptr(src, torch.float32, "src"), R, D, DTYPE[dtype],
+                                                        _ptr(dst, torch.uint8, "dst"), _stream()))
 
 
 def emb_bag_backward_workspace_bytes(T: int, B: int, nnz: int, total_rows: int, D: int, dtype: str) -> int:

@@ -38,9 +38,17 @@ static inline int emb_check_tables(const emb_table *th, const emb_table *td, int
 
 static inline int emb_elem_size(int32_t dtype) { return dtype == EMB_F32 ? 4 : (dtype == EMB_BF16 ? 2 : 0); }
 
+// Quantised tables (quant.hip): shape check, and the pooled lookup emb_bag_forward hands over to.
+int emb_check_quant_shape(int32_t D, int32_t dtype);
+int emb_forward_quant(const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, const int64_t *rows_dev,
+                      const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                      uint32_t *status_dev, hipStream_t s);
+
 // Row shape accepted by the gather kernels: whole 16-byte chunks, at most 1024 of them.
+// Quantised rows are read by the forward lookup only.
 static inline int emb_check_row_shape(int32_t D, int32_t dtype)
 {
+    if (dtype == EMB_INT8 || dtype == EMB_INT4) return EMB_ERR_UNSUPPORTED;
     int esz = emb_elem_size(dtype);
     if (esz == 0 || D <= 0) return EMB_ERR_INVALID_ARG;
     int64_t bytes = (int64_t)D * esz;

@@ -80,7 +80,8 @@ extern "C" int emb_bag_forward(const emb_table *tables_host, const emb_table *ta
 {
     if (B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
-    int rc = emb_check_row_shape(D, dtype);
+    const bool quant = dtype == EMB_INT8 || dtype == EMB_INT4;
+    int rc = quant ? emb_check_quant_shape(D, dtype) : emb_check_row_shape(D, dtype);
     if (rc != EMB_OK) return rc;
     rc = emb_check_tables(tables_host, tables_dev, T, false);
     if (rc != EMB_OK) return rc;
@@ -90,6 +91,9 @@ extern "C" int emb_bag_forward(const emb_table *tables_host, const emb_table *ta
     if (!emb_aligned(out_dev, 16)) return EMB_ERR_INVALID_ARG;
     if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
 
+    if (quant)
+        return emb_forward_quant(tables_dev, T, D, dtype, rows_dev, offsets_dev, B, nnz, mode, out_dev, status_dev,
+                                 emb_stream(stream));
     const int chunks = D * emb_elem_size(dtype) / 16;
     int lpr, cpl;
     emb_row_split(chunks, lpr, cpl);

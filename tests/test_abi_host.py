@@ -132,6 +132,27 @@ def test_backward_argument_errors(L):
     assert f(*args(side=C.addressof(side))) == INVALID
 
 
+def test_quantized_row_size_and_argument_errors(L):
+    L.emb_row_bytes.restype = C.c_int64
+    rb = L.emb_row_bytes
+    assert rb(64, 0) == 256 and rb(64, 1) == 128 and rb(64, 2) == 80 and rb(64, 3) == 48
+    assert rb(32, 3) == 32 and rb(16, 3) == 16 and rb(0, 3) == 0 and rb(63, 3) == 0 and rb(64, 9) == 0
+    q = L.emb_quantize_rows
+    assert q(FAKE, 10, 24, 3, FAKE, None) == UNSUPPORTED        # D must be a multiple of 16
+    assert q(FAKE, 10, 2048, 2, FAKE, None) == UNSUPPORTED
+    assert q(FAKE, 10, 64, 0, FAKE, None) == INVALID            # not a quantised type
+    assert q(None, 10, 64, 3, FAKE, None) == INVALID
+    assert q(FAKE, 10, 64, 3, FAKE + 8, None) == INVALID        # 16-byte alignment
+    assert q(FAKE, -1, 64, 3, FAKE, None) == INVALID
+    assert q(FAKE, 0, 64, 3, FAKE, None) == OK                  # nothing to do
+    # quantised tables are read by the forward only
+    assert L.emb_bag_backward_workspace_bytes(2, 4, 8, 1007, 64, 3) == 0
+    d = _tables()
+    f = L.emb_bag_forward
+    assert f(d.ctypes.data, FAKE, 2, 24, 3, FAKE, FAKE, 4, 8, 0, FAKE, None, None) == UNSUPPORTED
+    assert f(d.ctypes.data, FAKE, 2, 64, 3, FAKE, FAKE, 4, 8, 0, None, None, None) == INVALID
+
+
 def test_workspace_bytes(L):
     w = L.emb_bag_backward_workspace_bytes
     assert w(-1, 1, 1, 1, 64, 0) == 0 and w(1, -1, 1, 1, 64, 0) == 0 and w(1, 1, -1, 1, 64, 0) == 0

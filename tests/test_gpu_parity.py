@@ -166,6 +166,75 @@ def test_forward_empty_batch_zero_fills():
 
 
 # ---------------------------------------------------------------------------
+# row-quantised tables: quantiser bit-exact, dequantise-on-gather forward within tolerance
+# ---------------------------------------------------------------------------
+def _quant_source(rng, R, D):
+    x = (rng.standard_normal((R, D)) * rng.uniform(1e-3, 5.0, size=(R, 1))).astype(np.float32)
+    x[1] = -0.75                                              # constant row
+    x[2, :] = 0.0
+    x[2, :8] = [0.0, 15.0, 0.5, 1.5, 2.5, 3.5, 4.5, 14.5]     # exact ties for INT4 (scale 1)
+    x[3, :] = 0.0
+    x[3, :8] = [0.0, 255.0, 0.5, 1.5, 2.5, 3.5, 254.5, 100.5]  # exact ties for INT8
+    x[4] = np.float32(1e-30) * rng.standard_normal(D).astype(np.float32)   # tiny scale
+    return x
+
+
+@pytest.mark.parametrize("D", [16, 32, 48, 64, 128, 208, 1024])
+@pytest.mark.parametrize("dtype", ["int8", "int4"])
+def test_quantize_rows_bit_exact(D, dtype):
+    rng = np.random.default_rng(900 + D)
+    R = 1000 + 3
+    x = _quant_source(rng, R, D)
+    dst = torch.full((R, emb.emb_row_bytes(D, dtype)), 0xAB, dtype=torch.uint8, device=H.DEV)
+    emb.emb_quantize_rows(H.dev(x), dtype, dst)
+    torch.cuda.synchronize()
+    assert emb.emb_row_bytes(D, dtype) == oracle.quant_row_bytes(D, dtype)
+    assert np.array_equal(dst.cpu().numpy(), oracle.quantize_rows(x, dtype))
+
+
+@pytest.mark.parametrize("D", [16, 64, 48, 256, 1024])
+@pytest.mark.parametrize("dtype", ["int8", "int4"])
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_forward_quantized_matches_oracle(D, dtype, mode):
+    rng = np.random.default_rng(950 + D + 7 * (dtype == "int4") + (mode == "mean"))
+    T, B = 3, (40 if D >= 256 else 600)
+    Rs = [5000, 7, 20_000]
+    src = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
+    qt = [oracle.quantize_rows(x, dtype) for x in src]         # the oracle's quantiser makes the inputs
+    lengths = rng.integers(0, 40, size=T * B).astype(np.int32)
+    lengths[rng.random(T * B) < 0.15] = 0
+    lengths[5] = 333                                           # one long bag
+    off, _ = oracle.lengths_to_offsets(lengths)
+    rows = np.concatenate([rng.integers(0, Rs[t], size=int(off[(t + 1) * B] - off[t * B])) for t in range(T)])
+    rows = rows.astype(np.int64)
+    rows[[2, 17]] = [-1, 1 << 40]                              # skipped and flagged on both sides
+    ts = emb.TableSet([H.dev(q) for q in qt], D, dtype, device=torch.device(H.DEV))
+    out, st = H.gpu_forward(ts, rows, off, B, mode)
+    ref, absum, rst = oracle.bag_forward(qt, dtype, rows, off, B, mode, D=D)
+    assert st == rst == emb.STATUS_BAD_INDEX
+    H.assert_pooled_close(out, ref, absum, what="quantised forward %s D=%d" % (dtype, D))
+
+
+def test_forward_quantized_grid_tables_are_bit_exact_and_empty_batch():
+    # integer codes with scale 1 and integer bias: every partial sum is exact in fp32
+    rng = np.random.default_rng(960)
+    D, B, R = 64, 50, 300
+    x = rng.integers(0, 16, size=(R, D)).astype(np.float32)
+    x[:, 0], x[:, 1] = 0, 15
+    x += rng.integers(-20, 20, size=(R, 1)).astype(np.float32)
+    q = oracle.quantize_rows(x, "int4")
+    lengths = rng.integers(0, 30, size=B).astype(np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    rows = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    ts = emb.TableSet([H.dev(q)], D, "int4", device=torch.device(H.DEV))
+    out, st = H.gpu_forward(ts, rows, off, B, "sum")
+    ref, _, _ = oracle.bag_forward([q], "int4", rows, off, B, "sum", D=D)
+    assert st == 0 and np.array_equal(out.reshape(ref.shape), ref)
+    out, st = H.gpu_forward(ts, np.zeros(0, np.int64), np.zeros(B + 1, np.int64), B, "mean")
+    assert st == 0 and np.all(out == 0)
+
+
+# ---------------------------------------------------------------------------
 # backward + row-wise Adagrad
 # ---------------------------------------------------------------------------
 def _backward_case(rng, T, B, D, Rs, max_len, dtype, mode, hot=0.0, lr=0.01, eps=1e-8, steps=1):
