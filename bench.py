@@ -66,10 +66,10 @@ def measured_traffic(workload: str, kernel: str):
     return int(round((kib[0] * PMC_TRAFFIC["fetch_scale"] + kib[1] * PMC_TRAFFIC["write_scale"]) * 1024))
 
 
-def forward_bytes(nnz: int, bags: int, D: int, esz: int) -> int:
+def forward_bytes(nnz: int, bags: int, D: int, row_bytes: int) -> int:
     """Algorithmic bytes of one gather-pool launch: per lookup one table row and
     one 8-byte index; per bag one fp32 output row and one 8-byte offset."""
-    return nnz * (D * esz + 8) + bags * (4 * D + 8) + 8
+    return nnz * (row_bytes + 8) + bags * (4 * D + 8) + 8
 
 
 def backward_bytes(nnz: int, bags: int, uniq: int, D: int, esz: int, passes: int) -> int:
@@ -101,6 +101,24 @@ def cpu_baseline(w, batches_np, seed, min_seconds=10.0, max_batches=8):
         else:
             rows_np = b["rows"]
         t_index += time.perf_counter() - t0
+        if w.quant:
+            # compact quantised tables holding the touched rows only (the oracle's own quantiser, not
+            # timed), lookups renumbered to match: denser than a full table, which flatters the CPU
+            tables, parts = [], []
+            for t in range(w.T):
+                seg = rows_np[off[t * w.B]:off[(t + 1) * w.B]]
+                touched = np.unique(seg)
+                tables.append(oracle.quantize_rows(wl.table_values(w.table_seed(t, seed), touched, w.D), w.quant))
+                parts.append(np.searchsorted(touched, seg))
+            rows_q = np.concatenate(parts).astype(np.int64)
+            t0 = time.perf_counter()
+            oracle.bag_forward(tables, w.quant, rows_q, off, w.B, w.pool, want_absum=False, D=w.D)
+            t_f += time.perf_counter() - t0
+            lookups += int(b["nnz"])
+            used += 1
+            if t_index + t_f + t_b >= min_seconds:
+                break
+            continue
         tables = [wl.sparse_host_table(w.table_seed(t, seed), w.R, w.D, w.dtype,
                                        rows_np[off[t * w.B]:off[(t + 1) * w.B]]) for t in range(w.T)]
         t0 = time.perf_counter()
@@ -246,7 +264,9 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="3", help="3 (fwd+bwd, default), 1, 2, 2u or 4 (forward only), 5 (host table + HBM cache)")
+    ap.add_argument("--workload", default="3",
+                    help="3 (fwd+bwd, default), 1, 2, 2u or 4 (forward only), 2q4 / 2q8 / 2uq4 (forward over INT4 / "
+                         "INT8 row-quantised tables), 5 (host table + HBM cache)")
     ap.add_argument("--batches", type=int, default=8, help="distinct resident batches cycled through")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--scale-rows", type=int, default=None, help="rows per table (debug: smaller tables)")
@@ -296,10 +316,11 @@ def main() -> int:
         w.T, w.R, w.D, w.dtype, len(dbs), max_nnz, time.time() - t_setup))
 
     if args.pmc_calibration:
-        n_cal = min(w.R, (512 << 20) // (w.D * w.esz))
+        cal_rowb = tabs.weights[0].shape[1] * tabs.weights[0].element_size()
+        n_cal = min(w.R, (512 << 20) // cal_rowb)
         cal = tabs.weights[0][:n_cal].clone()      # plain copy kernel: reads and writes n_cal rows
         torch.cuda.synchronize()
-        log("calibration copy: %d bytes read, %d bytes written" % (cal.numel() * w.esz, cal.numel() * w.esz))
+        log("calibration copy: %d bytes read, %d bytes written" % (n_cal * cal_rowb, n_cal * cal_rowb))
         del cal
 
     K, W = args.steps, args.warmup
@@ -370,7 +391,7 @@ def main() -> int:
     ms_fwd = sum(e[1].elapsed_time(e[2]) for e in ev) / KI
     uniq = int(buf.num_unique.item()) if w.backward else 0   # of the last batch; all batches are alike
     passes = (max(1, int(w.R).bit_length()) + 7) // 8     # the sort works table by table on row numbers
-    rowb = w.D * w.esz
+    rowb = emb.emb_row_bytes(w.D, w.storage)
 
     def entry(name, ms, nbytes, what, pmc_kernel=None):
         gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
@@ -382,9 +403,11 @@ def main() -> int:
     kernels = [
         entry("offsets_* + hash_ids_tables_kernel (index stage, 4 launches)", ms_index, nnz_i * 16 + bags * 12,
               "16 B per lookup (raw ID in, row out) + 12 B per bag (length in, offset out)"),
-        entry("bag_forward_kernel (gather-pool)", ms_fwd if w.backward else ms_dom,
-              forward_bytes(nnz_i, bags, w.D, w.esz),
-              "row + 8 B index per lookup, fp32 output row + 8 B offset per bag", "bag_forward_kernel"),
+        entry("bag_forward_quant_kernel (gather-dequantise-pool, %s rows of %d B)" % (w.quant, rowb) if w.quant
+              else "bag_forward_kernel (gather-pool)", ms_fwd if w.backward else ms_dom,
+              forward_bytes(nnz_i, bags, w.D, rowb),
+              "row + 8 B index per lookup, fp32 output row + 8 B offset per bag",
+              "bag_forward_quant_kernel" if w.quant else "bag_forward_kernel"),
     ]
     ms_bwd = 0.0
     if w.backward:
@@ -419,21 +442,28 @@ def main() -> int:
     log("dominant: %s: %.3f ms, %.0f GB/s algorithmic = %.1f %% of HBM peak" % (
         roofline["kernel"], roofline["avg_ms"], roofline["achieved"], 100 * roofline["frac"]))
 
-    # ---- side measurements: the forward kernel alone on workloads 2 and 2u ---
+    # ---- side measurements: the forward kernel alone on workloads 2 and 2u, and over INT4 copies
+    # of the same tables (2q4, 2uq4)
     extra = {}
     if not args.no_extra and args.workload == "3" and not args.scale_rows:
-        for name in ("2", "2u"):
+        qkeep, qset = None, None
+        for name in ("2", "2u", "2q4", "2uq4"):
             wf = wl.WORKLOADS[name]
+            tset = tabs.set
+            if wf.quant:
+                if qset is None:
+                    qkeep, qset = pipeline.quantized_tableset(tabs, wf.quant)
+                tset = qset
             fb = [pipeline.DeviceBatch(wf, wl.make_batch(wf, i, seed), dev) for i in range(args.batches)]
             fbuf = pipeline.StepBuffers(wf, max(d.nnz for d in fb), tabs.set.total_rows, dev)
             rows_v = []
             for d in fb:                      # index stage once per batch, rows kept resident
-                r = pipeline.run_index_stage(wf, tabs.set, d, fbuf).clone()
+                r = pipeline.run_index_stage(wf, tset, d, fbuf).clone()
                 rows_v.append((r, fbuf.offsets.clone()))
             torch.cuda.synchronize()
             for i in range(3):
                 fbuf.offsets.copy_(rows_v[i % len(fb)][1])
-                pipeline.run_forward(wf, tabs.set, rows_v[i % len(fb)][0], fbuf)
+                pipeline.run_forward(wf, tset, rows_v[i % len(fb)][0], fbuf)
             torch.cuda.synchronize()
             n_it = 40
             e0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_it)]
@@ -443,20 +473,23 @@ def main() -> int:
                 r, o = rows_v[i % len(fb)]
                 fbuf.offsets.copy_(o)
                 e0[i].record()
-                pipeline.run_forward(wf, tabs.set, r, fbuf)
+                pipeline.run_forward(wf, tset, r, fbuf)
                 e1[i].record()
                 tot += r.numel()
             torch.cuda.synchronize()
             ms = sum(a.elapsed_time(b) for a, b in zip(e0, e1)) / n_it
-            nb = forward_bytes(tot // n_it, wf.T * wf.B, wf.D, wf.esz)
+            nb = forward_bytes(tot // n_it, wf.T * wf.B, wf.D, emb.emb_row_bytes(wf.D, wf.storage))
             gbs = nb / (ms * 1e-3) / 1e9
+            kern = "bag_forward_quant_kernel" if wf.quant else "bag_forward_kernel"
             extra["forward_only_" + name] = {
+                "kernel": kern, "row_bytes": emb.emb_row_bytes(wf.D, wf.storage),
                 "avg_ms": round(ms, 4), "lookups_per_s": round(tot / n_it / (ms * 1e-3), 1),
                 "algorithmic_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                "algorithmic_bytes": int(nb), "traffic": measured_traffic(name, "bag_forward_kernel")}
-            log("forward only, workload %s: %.3f ms, %.0f GB/s (%.1f %% of HBM peak)" % (
-                name, ms, gbs, 100 * gbs / HBM_PEAK_GBS))
+                "algorithmic_bytes": int(nb), "traffic": measured_traffic(name, kern)}
+            log("forward only, workload %s: %.3f ms, %.3g lookups/s, %.0f GB/s (%.1f %% of HBM peak)" % (
+                name, ms, tot / n_it / (ms * 1e-3), gbs, 100 * gbs / HBM_PEAK_GBS))
             del fb, fbuf, rows_v
+        del qkeep, qset
 
     # ---- CPU baseline: the oracle, as it stands, on this host ----------------
     cpu = None
@@ -480,7 +513,9 @@ def main() -> int:
         "config": {
             "workload": ("%s: %d tables x %d rows x dim %d %s, %d bags/table, %s bag lengths (mean %g), %s IDs%s, "
                          "%s pooling, %s" % (
-                             w.name, w.T, w.R, w.D, w.dtype, w.B, w.length, w.mean_len, w.ids,
+                             w.name, w.T, w.R, w.D,
+                             w.dtype if not w.quant else "(fp32 quantised row-wise to %s, %d B per row)" % (w.quant, rowb),
+                             w.B, w.length, w.mean_len, w.ids,
                              (" alpha=%g over %.0e keys" % (w.alpha, w.n_keys)) if w.ids == "zipf" else "", w.pool,
                              "forward + sparse row-wise Adagrad backward" if w.backward else "forward only")),
             "lookups_per_step": round(nnz_avg, 1),

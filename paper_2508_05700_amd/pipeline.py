@@ -17,7 +17,8 @@ _TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
 
 
 class DeviceTables:
-    """The T tables of a workload in HBM, filled by ``emb_table_fill``."""
+    """The T tables of a workload in HBM, filled by ``emb_table_fill``; for a workload with
+    ``quant`` set, each filled fp32 table is quantised by ``emb_quantize_rows`` and dropped."""
 
     def __init__(self, w: Workload, seed: int = DEFAULT_SEED, device: str = "cuda:0"):
         self.w = w
@@ -27,11 +28,30 @@ class DeviceTables:
         for t in range(w.T):
             wt = torch.empty((w.R, w.D), dtype=_TORCH_DT[w.dtype], device=self.device)
             emb.emb_table_fill(wt, w.R, w.D, w.dtype, w.table_seed(t, seed))
-            self.weights.append(wt)
+            if w.quant:
+                self.weights.append(quantize_table(wt, w.quant))
+                del wt
+            else:
+                self.weights.append(wt)
             if w.backward:
                 self.accum.append(torch.zeros(w.R, dtype=torch.float32, device=self.device))
-        self.set = emb.TableSet(self.weights, w.D, w.dtype, accum=self.accum,
+        self.set = emb.TableSet(self.weights, w.D, w.storage, accum=self.accum,
                                 salts=[w.salt(t) for t in range(w.T)], device=self.device)
+
+
+def quantize_table(table: torch.Tensor, quant: str) -> torch.Tensor:
+    """fp32 device table -> its row-quantised storage (a new uint8 tensor)."""
+    R, D = table.shape
+    q = torch.empty((R, emb.emb_row_bytes(D, quant)), dtype=torch.uint8, device=table.device)
+    emb.emb_quantize_rows(table, quant, q)
+    return q
+
+
+def quantized_tableset(tabs: DeviceTables, quant: str):
+    """Row-quantised copies of fp32 DeviceTables: (list of uint8 tensors, TableSet)."""
+    w = tabs.w
+    qs = [quantize_table(t, quant) for t in tabs.weights]
+    return qs, emb.TableSet(qs, w.D, quant, salts=[w.salt(t) for t in range(w.T)], device=tabs.device)
 
 
 class DeviceBatch:

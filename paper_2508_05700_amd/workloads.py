@@ -204,6 +204,7 @@ class Workload:
     hot_fraction: float = 0.0
     lr: float = 0.01
     eps: float = 1e-8
+    quant: Optional[str] = None   # "int8" | "int4": the fp32 tables are stored row-quantised (forward only)
 
     def scaled(self, rows: Optional[int] = None, bags: Optional[int] = None,
                tables: Optional[int] = None, n_keys: Optional[int] = None) -> "Workload":
@@ -220,6 +221,11 @@ class Workload:
     @property
     def esz(self) -> int:
         return 4 if self.dtype == "f32" else 2
+
+    @property
+    def storage(self) -> str:
+        """Storage type of the table rows the lookups read."""
+        return self.quant or self.dtype
 
     def table_seed(self, t: int, seed: int = DEFAULT_SEED) -> int:
         return int(seed) * 1000 + int(t)
@@ -244,6 +250,13 @@ WORKLOADS: Dict[str, Workload] = {
     # 4: one 1e9-row bf16 table, Zipf(1.2) over 1e12 keys, sum pooling
     "4": Workload("4", T=1, R=1_000_000_000, D=32, dtype="bf16", B=65536, length="poisson", mean_len=50,
                   max_len=None, ids="zipf", alpha=1.2, n_keys=10 ** 12, pool="sum"),
+    # 2q4 / 2q8 / 2uq4: config 2 (and its uniform-ID variant) over post-training-quantised tables
+    "2q4": Workload("2q4", T=16, R=10_000_000, D=64, dtype="f32", B=8192, length="poisson", mean_len=20,
+                    max_len=100, ids="zipf", alpha=1.05, n_keys=10 ** 9, pool="mean", quant="int4"),
+    "2q8": Workload("2q8", T=16, R=10_000_000, D=64, dtype="f32", B=8192, length="poisson", mean_len=20,
+                    max_len=100, ids="zipf", alpha=1.05, n_keys=10 ** 9, pool="mean", quant="int8"),
+    "2uq4": Workload("2uq4", T=16, R=10_000_000, D=64, dtype="f32", B=8192, length="poisson", mean_len=20,
+                     max_len=100, ids="raw_uniform", pool="mean", quant="int4"),
     # 5: host-resident table plus an HBM cache of the hottest 5 % of rows
     "5": Workload("5", T=1, R=250_000_000, D=64, dtype="f32", B=16384, length="poisson", mean_len=30,
                   max_len=None, ids="zipf", alpha=1.1, n_keys=10 ** 9, pool="sum", hybrid=True,

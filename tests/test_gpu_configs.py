@@ -96,6 +96,41 @@ def test_workload_2u_uniform_forward(tables16):
     assert np.unique(batch["raw"]).size > 0.999 * batch["raw"].size
 
 
+@pytest.mark.parametrize("name", ["2q4", "2q8"])
+def test_workload_2_over_quantized_tables(tables16, name):
+    # Runs before the backward test below changes the tables.  The fp32 tables are quantised on the
+    # device; the oracle quantises the generator's values of the rows the batch touches and pools
+    # them (lookups renumbered into that compact table: plumbing, the values are the same).
+    w = wl.WORKLOADS[name]
+    tabs = tables16
+    say("workload %s: quantising 16 tables on the device" % name)
+    qkeep, qset = pipeline.quantized_tableset(tabs, w.quant)
+    batch = wl.make_batch(w, 0)
+    db = pipeline.DeviceBatch(w, batch, tabs.device)
+    buf = pipeline.StepBuffers(w, db.nnz, tabs.set.total_rows, tabs.device)
+    rows_dev = pipeline.run_index_stage(w, qset, db, buf)
+    pipeline.run_forward(w, qset, rows_dev, buf)
+    torch.cuda.synchronize()
+    assert int(buf.status.item()) == 0
+    off, rows = _oracle_index(w, batch)
+    assert np.array_equal(rows_dev.cpu().numpy(), rows)
+    say("workload %s: oracle quantiser and forward" % name)
+    qt, parts = [], []
+    for t in range(w.T):
+        seg = rows[off[t * w.B]:off[(t + 1) * w.B]]
+        touched = np.unique(seg)
+        packed = oracle.quantize_rows(wl.table_values(w.table_seed(t), touched, w.D), w.quant)
+        got = qkeep[t][torch.from_numpy(touched).to(H.DEV)].cpu().numpy()
+        assert np.array_equal(got, packed), "quantised rows of table %d differ" % t       # bit-exact codes
+        qt.append(packed)
+        parts.append(np.searchsorted(touched, seg))
+    ref, absum, st = oracle.bag_forward(qt, w.quant, np.concatenate(parts).astype(np.int64), off, w.B, w.pool, D=w.D)
+    assert st == 0
+    H.assert_pooled_close(buf.out.cpu().numpy(), ref, absum, what="workload " + name)
+    del qkeep, qset
+    torch.cuda.empty_cache()
+
+
 def test_workload_3_forward_and_backward(tables16):
     w = wl.WORKLOADS["3"]
     tabs = tables16
