@@ -206,7 +206,7 @@ def bench_hybrid(args) -> int:
         step(dbs[i % len(dbs)])
     torch.cuda.synchronize()
     hm.zero_()
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    ev = [[emb.Event(timing=True) for _ in range(3)] for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(K):
@@ -338,10 +338,9 @@ def main() -> int:
     NS = emb.BWD_STAGE_EVENTS
 
     def new_events(n):
-        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
-        for e in evs:
-            e.record()          # creates the HIP event behind the torch object
-        return evs
+        # HIP events that release to device scope: a record does not write caches back to system
+        # memory (a default event's record costs the stream several microseconds)
+        return [emb.Event(timing=True) for _ in range(n)]
 
     dom = [new_events(2) for _ in range(K)]
     torch.cuda.synchronize()
@@ -466,8 +465,8 @@ def main() -> int:
                 pipeline.run_forward(wf, tset, rows_v[i % len(fb)][0], fbuf)
             torch.cuda.synchronize()
             n_it = 40
-            e0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_it)]
-            e1 = [torch.cuda.Event(enable_timing=True) for _ in range(n_it)]
+            e0 = [emb.Event(timing=True) for _ in range(n_it)]
+            e1 = [emb.Event(timing=True) for _ in range(n_it)]
             tot = 0
             for i in range(n_it):
                 r, o = rows_v[i % len(fb)]

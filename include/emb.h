@@ -143,6 +143,24 @@ typedef struct emb_side_stream {
     void *join_event;
 } emb_side_stream;
 
+/* Helpers for callers without a HIP binding of their own.  Events made here
+ * release to device scope only (recording one does not write caches back to
+ * system memory): enough to order or time work on the streams of one device,
+ * and cheaper than a default event by microseconds per record.
+ * emb_side_stream_create fills `side` with a new non-blocking stream of default
+ * priority and two such events; the caller destroys them with
+ * emb_side_stream_destroy once no call that uses them is in flight.
+ * emb_event_create makes one event (timing != 0: it can be timed),
+ * emb_event_record records it on `stream`, emb_event_elapsed_ms gives the time
+ * between two recorded, completed timing events.  All: host calls, EMB_ERR_HIP
+ * if the runtime refuses. */
+int emb_side_stream_create(emb_side_stream *side);
+int emb_side_stream_destroy(emb_side_stream *side);
+int emb_event_create(void **event_out, int32_t timing);
+int emb_event_destroy(void *event);
+int emb_event_record(void *event, void *stream);
+int emb_event_elapsed_ms(void *start, void *stop, float *ms_out);
+
 /* Exact sparse backward of emb_bag_forward followed by one row-wise Adagrad
  * step (fine-tuning of table rows, Section 3.1; Adagrad of Duchi, Hazan,
  * Singer 2011 with one accumulator per row).  With g_j = c_b * dout[t,b,:]

@@ -33,6 +33,8 @@ EXPORTS = [
     "emb_status_string", "emb_tables_init", "emb_hash_ids", "emb_hash_ids_tables", "emb_lengths_to_offsets",
     "emb_bag_forward", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
     "emb_bag_backward_sort", "emb_bag_backward_update", "emb_row_bytes", "emb_quantize_rows",
+    "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
+    "emb_event_elapsed_ms",
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_host_device_pointer",
     "emb_table_fill",
 ]
@@ -83,6 +85,18 @@ def lib() -> C.CDLL:
     L.emb_bag_backward_sort.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, sz, vp, vp, vp, vp, vp, vp]
     L.emb_bag_backward_update.restype = C.c_int
     L.emb_bag_backward_update.argtypes = [vp, vp, i32, i32, i32, i64, i64, vp, f32, f32, vp, sz, vp, vp, vp, vp]
+    L.emb_side_stream_create.restype = C.c_int
+    L.emb_side_stream_create.argtypes = [vp]
+    L.emb_side_stream_destroy.restype = C.c_int
+    L.emb_side_stream_destroy.argtypes = [vp]
+    L.emb_event_create.restype = C.c_int
+    L.emb_event_create.argtypes = [C.POINTER(vp), i32]
+    L.emb_event_destroy.restype = C.c_int
+    L.emb_event_destroy.argtypes = [vp]
+    L.emb_event_record.restype = C.c_int
+    L.emb_event_record.argtypes = [vp, vp]
+    L.emb_event_elapsed_ms.restype = C.c_int
+    L.emb_event_elapsed_ms.argtypes = [vp, vp, C.POINTER(f32)]
     L.emb_row_bytes.restype = i64
     L.emb_row_bytes.argtypes = [i32, i32]
     L.emb_quantize_rows.restype = C.c_int
@@ -241,16 +255,45 @@ class _SideStreamC(C.Structure):
 
 
 class SideStream:
-    """The ``emb_side_stream`` argument: a second torch stream (default priority) and two events,
-    kept alive by this object."""
+    """The ``emb_side_stream`` argument, made by ``emb_side_stream_create`` (a stream of default
+    priority and two events that release to device scope) on the current device and destroyed with
+    this object."""
 
-    def __init__(self, device: torch.device):
-        self.stream = torch.cuda.Stream(device=device)
-        self.events = [torch.cuda.Event(), torch.cuda.Event()]
-        for e in self.events:
-            e.record(self.stream)       # creates the HIP event behind the torch object
-        self.c = _SideStreamC(int(self.stream.cuda_stream), int(self.events[0].cuda_event),
-                              int(self.events[1].cuda_event))
+    def __init__(self, device: Optional[torch.device] = None):
+        self.c = _SideStreamC()
+        with torch.cuda.device(device if device is not None else torch.cuda.current_device()):
+            _check("emb_side_stream_create", lib().emb_side_stream_create(C.addressof(self.c)))
+
+    def __del__(self):
+        try:
+            lib().emb_side_stream_destroy(C.addressof(self.c))
+        except Exception:
+            pass
+
+
+class Event:
+    """A HIP event with device-scope release (``emb_event_create``); ``cuda_event`` is its handle,
+    so it can be passed where a torch event is accepted by this module."""
+
+    def __init__(self, timing: bool = True):
+        h = C.c_void_p()
+        _check("emb_event_create", lib().emb_event_create(C.byref(h), 1 if timing else 0))
+        self.cuda_event = int(h.value)
+
+    def record(self, stream: Optional[torch.cuda.Stream] = None) -> None:
+        s = _stream() if stream is None else int(stream.cuda_stream)
+        _check("emb_event_record", lib().emb_event_record(self.cuda_event, s))
+
+    def elapsed_time(self, end: "Event") -> float:
+        ms = C.c_float()
+        _check("emb_event_elapsed_ms", lib().emb_event_elapsed_ms(self.cuda_event, end.cuda_event, C.byref(ms)))
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            lib().emb_event_destroy(self.cuda_event)
+        except Exception:
+            pass
 
 
 def _stage_events(stage_events):

@@ -89,8 +89,25 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__res
         const uint32_t i = wbase + k * EMB_WAVE + lane;
         key[k] = i < end ? keys[i] : (KeyT)0;
     }
-    uint32_t unused[SORT_ITEMS];
-    wave_rank_digits<KeyT, false>(key, wbase, end, shift, cnt[wave], unused);
+    // Counting needs no ranks: one LDS add per record into the wavefront's own counters.  Lanes
+    // that share a digit are serialised by the LDS, which is cheaper than matching them by ballots
+    // unless all 64 hold the same digit (the records of one hot row, once an earlier pass has made
+    // them adjacent): that case is one add by one lane.
+#pragma unroll
+    for (int k = 0; k < SORT_ITEMS; ++k) {
+        const uint32_t i = wbase + k * EMB_WAVE + lane;
+        const bool live = i < end;
+        const uint32_t digit = (uint32_t)(key[k] >> shift) & (RADIX - 1);
+        const uint64_t lv = __ballot(live);
+        if (lv == 0) continue;                                     // uniform
+        const int first = __ffsll((unsigned long long)lv) - 1;
+        const uint32_t d0 = (uint32_t)__shfl((int)digit, first, EMB_WAVE);
+        if (__ballot(live && digit == d0) == lv) {                 // uniform
+            if (lane == first) cnt[wave][d0] += (uint32_t)__popcll(lv);
+        } else if (live) {
+            atomicAdd(&cnt[wave][digit], 1u);
+        }
+    }
     __syncthreads();
     uint32_t c = 0;
 #pragma unroll
