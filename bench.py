@@ -36,14 +36,17 @@ def log(*a):
 # the counters are taken again.  The scale factors come from kernels of known traffic in the same
 # runs: the 512 MiB device copy of --pmc-calibration reads 524288 KiB and FETCH_SIZE shows 262172
 # (factor 2.0: the counter prices this part's 128-byte read requests as 64 bytes); the copy's and the
-# table fill's writes (524288 and 2500000 KiB) are counted exactly (factor 1.0).
+# table fill's writes (524288 and 2500000 KiB) are counted exactly (factor 1.0).  Read requests of 64
+# bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
+# 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "936d475ea7d43524",
+    "sources": "508b4bb58791d0a2",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_kernel": (178038.7, 32768.0), "update_kernel": (240473.6, 324626.9)},
-        "2u": {"bag_forward_kernel": (346119.4, 32768.0)},
+        "3": {"bag_forward_kernel": (178017.7, 32768.0), "update_kernel": (240621.6, 323999.4)},
+        "2u": {"bag_forward_kernel": (346115.2, 32768.0)},
+        "2uq4": {"bag_forward_quant_kernel": (233551.6, 32883.4)},
     },
 }
 

@@ -153,6 +153,37 @@ def test_quantized_row_size_and_argument_errors(L):
     assert f(d.ctypes.data, FAKE, 2, 64, 3, FAKE, FAKE, 4, 8, 0, None, None, None) == INVALID
 
 
+def test_split_backward_and_helper_argument_errors(L):
+    d = _tables()
+    need = L.emb_bag_backward_workspace_bytes(2, 4, 8, 1007, 64, 0)
+    srt, upd = L.emb_bag_backward_sort, L.emb_bag_backward_update
+
+    def sort_args(**k):
+        return [k.get("th", d.ctypes.data), FAKE, 2, k.get("D", 64), 0, k.get("rows", FAKE), FAKE, 4, k.get("nnz", 8),
+                k.get("mode", 1), k.get("ws", FAKE), k.get("wsb", need), None, None, None, None, None, None]
+
+    def upd_args(**k):
+        return [d.ctypes.data, FAKE, 2, k.get("D", 64), 0, 4, k.get("nnz", 8), k.get("dout", FAKE), C.c_float(0.01),
+                C.c_float(1e-8), k.get("ws", FAKE), k.get("wsb", need), None, None, k.get("side", None), None]
+    assert srt(*sort_args(mode=5)) == INVALID
+    assert srt(*sort_args(rows=None)) == INVALID
+    assert srt(*sort_args(wsb=need - 1)) == WORKSPACE
+    assert srt(*sort_args(D=3)) == UNSUPPORTED
+    assert srt(*sort_args(nnz=-1)) == INVALID
+    assert upd(*upd_args(dout=None)) == INVALID
+    assert upd(*upd_args(dout=FAKE + 4)) == INVALID           # gradient rows are read 16 bytes at a time
+    assert upd(*upd_args(ws=None)) == WORKSPACE
+    assert upd(*upd_args(nnz=1 << 31)) == UNSUPPORTED
+    side = (C.c_void_p * 3)(FAKE, None, FAKE)
+    assert upd(*upd_args(side=C.addressof(side))) == INVALID
+    # helpers: null arguments are refused before the runtime is touched
+    assert L.emb_event_create(None, 1) == INVALID
+    assert L.emb_event_record(None, None) == INVALID
+    assert L.emb_event_elapsed_ms(None, None, None) == INVALID
+    assert L.emb_event_destroy(None) == OK
+    assert L.emb_side_stream_create(None) == INVALID and L.emb_side_stream_destroy(None) == INVALID
+
+
 def test_workspace_bytes(L):
     w = L.emb_bag_backward_workspace_bytes
     assert w(-1, 1, 1, 1, 64, 0) == 0 and w(1, -1, 1, 1, 64, 0) == 0 and w(1, 1, -1, 1, 64, 0) == 0
