@@ -243,7 +243,8 @@ int64_t emb_row_bytes(int32_t D, int32_t dtype);
  * asymmetric min/max, all in fp32 with IEEE division and round-half-even:
  *   bias = min_d x_d, scale = (max_d x_d - bias) / (2^b - 1), or 1 if the row
  *   is constant, code_d = clamp(rint((x_d - bias) / scale), 0, 2^b - 1).
- * dtype: EMB_INT8 or EMB_INT4.  Both pointers 16-byte aligned.
+ * dtype: EMB_INT8 or EMB_INT4.  Both pointers 16-byte aligned; dst_dev may be
+ * mapped host memory (the rows are then written over the link).
  * EMB_ERR_UNSUPPORTED if D is not a multiple of 16 or above 1024. */
 int emb_quantize_rows(const float *src_dev, int64_t num_rows, int32_t D, int32_t dtype,
                       void *dst_dev, void *stream);
@@ -259,15 +260,18 @@ int emb_cache_index_bytes(int64_t num_rows, size_t *bytes);
  * to the table (hipHostMalloc'ed mapped memory, or HBM).  hot_rows_dev:
  * i64[num_hot], strictly ascending, each in [0, num_rows) (violations set
  * EMB_STATUS_BAD_HOT_SET and leave the cache unusable).  cache_rows_dev:
- * [num_hot, D] of the table's dtype; cache_index_dev: emb_cache_index_bytes,
- * 16-byte aligned. */
+ * num_hot rows of emb_row_bytes(D, dtype) each, in the table's storage type
+ * (a quantised table is cached as it is, packed); cache_index_dev:
+ * emb_cache_index_bytes, 16-byte aligned. */
 int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
                     const int64_t *hot_rows_dev, int64_t num_hot, void *cache_rows_dev,
                     void *cache_index_dev, uint32_t *status_dev, void *stream);
 
 /* emb_bag_forward for one table whose rows are read from the HBM cache when
  * present and from table_dev (zero-copy over PCIe when it is mapped host
- * memory) otherwise.  The cache is numerically invisible.  The table must not
+ * memory) otherwise.  The cache is numerically invisible.  dtype may be any
+ * storage type of emb_bag_forward; with EMB_INT8 / EMB_INT4 a miss moves the
+ * packed row (48 bytes at D = 64, INT4) over the link.  The table must not
  * have changed since emb_cache_build.  hit_miss_dev (nullable, u64[2], zeroed
  * by the caller) is incremented by the number of in-range lookups served from
  * the cache / from the table. */

@@ -181,10 +181,15 @@ def bag_backward_rowwise_adagrad(tables: Sequence[np.ndarray], accum: Sequence[n
 
 
 def bag_forward_cached(table: np.ndarray, dtype: str, hot_rows: np.ndarray, rows: np.ndarray,
-                       offsets: np.ndarray, B: int, mode: str):
-    """Returns (out fp32 [1,B,D], absum, (hits, misses), status)."""
+                       offsets: np.ndarray, B: int, mode: str, D: Optional[int] = None):
+    """Returns (out fp32 [1,B,D], absum, (hits, misses), status).  A row-quantised table
+    (``int8`` / ``int4``: uint8 [R, quant_row_bytes]) needs ``D``."""
     _chk(table, _table_np_dtype(dtype))
-    D = int(table.shape[1])
+    quant = dtype in ("int8", "int4")
+    assert quant == (D is not None)
+    if quant:
+        assert table.shape[1] == quant_row_bytes(D, dtype)
+    D = int(D) if quant else int(table.shape[1])
     hot_rows = _chk(np.ascontiguousarray(hot_rows), np.int64)
     rows = _chk(np.ascontiguousarray(rows), np.int64)
     offsets = _chk(np.ascontiguousarray(offsets), np.int64)

@@ -236,13 +236,18 @@ def emb_row_bytes(D: int, dtype: str) -> int:
     return int(lib().emb_row_bytes(int(D), DTYPE[dtype]))
 
 
-def emb_quantize_rows(src: torch.Tensor, dtype: str, dst: torch.Tensor) -> None:
-    """fp32 ``src`` [R, D] -> row-quantised ``dst`` uint8 [R, emb_row_bytes(D, dtype)]."""
+def emb_quantize_rows(src: torch.Tensor, dtype: str, dst) -> None:
+    """fp32 ``src`` [R, D] -> row-quantised ``dst``: a device tensor uint8 [R, emb_row_bytes(D, dtype)],
+    or a raw device-visible pointer (int) to that many bytes, e.g. mapped host memory."""
     R, D = int(src.shape[0]), int(src.shape[1])
-    if dst.numel() != R * emb_row_bytes(D, dtype):
-        raise TypeError("dst must hold R * emb_row_bytes bytes")
-    _check("emb_quantize_rows", lib().emb_quantize_rows(_ptr(src, torch.float32, "src"), R, D, DTYPE[dtype],
-                                                        _ptr(dst, torch.uint8, "dst"), _stream()))
+    if isinstance(dst, int):
+        dptr = dst
+    else:
+        if dst.numel() != R * emb_row_bytes(D, dtype):
+            raise TypeError("dst must hold R * emb_row_bytes bytes")
+        dptr = _ptr(dst, torch.uint8, "dst")
+    _check("emb_quantize_rows", lib().emb_quantize_rows(_ptr(src, torch.float32, "src"), R, D, DTYPE[dtype], dptr,
+                                                        _stream()))
 
 
 def emb_bag_backward_workspace_bytes(T: int, B: int, nnz: int, total_rows: int, D: int, dtype: str) -> int:

@@ -8,8 +8,14 @@
 // are stored in ascending row order, the slot of a hot row is that count plus
 // the population count of the lower bitmap bits: one 16-byte probe decides
 // hit or miss and yields the slot, with no collisions and no search.
+//
+// The table may be row-quantised (EMB_INT8 / EMB_INT4, Section 4.1.2: the
+// hosted tables are the ones the paper quantises): cache and table then hold
+// the same packed rows, a miss moves 48 instead of 256 bytes over the link
+// (D = 64, INT4), and rows are dequantised while they are gathered.
 #include "emb_internal.h"
 #include "gather.h"
+#include "gather_quant.h"
 
 namespace {
 
@@ -145,6 +151,71 @@ int launch_cached(bool bf16, hipStream_t s, const char *table, const char *cache
     return EMB_OK;
 }
 
+template <int LPR, int BITS, int UNROLL>
+__global__ __launch_bounds__(Q_BLOCK) void bag_forward_cached_quant_kernel(const char *__restrict__ table,
+                                                                           const char *__restrict__ cache_rows,
+                                                                           const CacheEntry *__restrict__ index,
+                                                                           int64_t num_rows, int64_t num_hot, int64_t B,
+                                                                           int64_t nnz, const int64_t *__restrict__ rows,
+                                                                           const int64_t *__restrict__ offsets,
+                                                                           int32_t D, int64_t row_bytes, int32_t mode,
+                                                                           float *__restrict__ out,
+                                                                           unsigned long long *hit_miss, uint32_t *status)
+{
+    constexpr int GROUPS = Q_BLOCK / LPR;
+    const int l = threadIdx.x % LPR;
+    const int64_t b = (int64_t)blockIdx.x * GROUPS + threadIdx.x / LPR;
+    CachedSource src{table, cache_rows, index, (uint64_t)num_rows, (uint64_t)num_hot, row_bytes, status, 0u, 0u};
+    gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, b, l, nnz, rows, offsets, D, mode, out, status);
+    if (hit_miss) {
+        // every lane of the wavefront is still here: reduce, then one atomic per wavefront
+        uint32_t h = src.hits, m = src.misses;
+#pragma unroll
+        for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) {
+            h += __shfl_xor(h, d, EMB_WAVE);
+            m += __shfl_xor(m, d, EMB_WAVE);
+        }
+        if ((threadIdx.x & (EMB_WAVE - 1)) == 0) {
+            if (h) atomicAdd(&hit_miss[0], (unsigned long long)h);
+            if (m) atomicAdd(&hit_miss[1], (unsigned long long)m);
+        }
+    }
+}
+
+template <int BITS>
+int dispatch_cached_quant(int lpr, hipStream_t s, const char *table, const char *cache_rows, const CacheEntry *index,
+                          int64_t num_rows, int64_t num_hot, int64_t B, int64_t nnz, const int64_t *rows,
+                          const int64_t *offsets, int32_t D, int64_t row_bytes, int32_t mode, float *out,
+                          unsigned long long *hit_miss, uint32_t *status)
+{
+#define EMB_CQ(L)                                                                                                   \
+    do {                                                                                                            \
+        constexpr int GROUPS = Q_BLOCK / L;                                                                         \
+        hipLaunchKernelGGL((bag_forward_cached_quant_kernel<L, BITS, 8>), dim3((unsigned)((B + GROUPS - 1) / GROUPS)), \
+                           dim3(Q_BLOCK), 0, s, table, cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, D, \
+                           row_bytes, mode, out, hit_miss, status);                                                 \
+        EMB_RETURN_IF_LAUNCH_FAILED();                                                                              \
+        return EMB_OK;                                                                                              \
+    } while (0)
+    switch (lpr) {
+        case 1: EMB_CQ(1);
+        case 2: EMB_CQ(2);
+        case 4: EMB_CQ(4);
+        case 8: EMB_CQ(8);
+        case 16: EMB_CQ(16);
+        case 32: EMB_CQ(32);
+        default: EMB_CQ(64);
+    }
+#undef EMB_CQ
+}
+
+// Row shapes the cached lookup accepts: those of the plain lookup, quantised ones included.
+int cached_row_shape(int32_t D, int32_t dtype)
+{
+    if (dtype == EMB_INT8 || dtype == EMB_INT4) return emb_check_quant_shape(D, dtype);
+    return emb_check_row_shape(D, dtype);
+}
+
 }  // namespace
 
 extern "C" int emb_cache_index_bytes(int64_t num_rows, size_t *bytes)
@@ -171,7 +242,7 @@ extern "C" int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t 
                                void *cache_index_dev, uint32_t *status_dev, void *stream)
 {
     if (num_rows <= 0 || num_hot < 0 || num_hot > num_rows) return EMB_ERR_INVALID_ARG;
-    int rc = emb_check_row_shape(D, dtype);
+    int rc = cached_row_shape(D, dtype);
     if (rc != EMB_OK) return rc;
     if (!table_dev || !cache_index_dev || (num_hot > 0 && (!hot_rows_dev || !cache_rows_dev)))
         return EMB_ERR_INVALID_ARG;
@@ -190,7 +261,7 @@ extern "C" int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t 
     hipLaunchKernelGGL(cache_mark_kernel, dim3((unsigned)mblocks), dim3(CB_BLOCK), 0, s, hot_rows_dev, num_hot,
                        num_rows, reinterpret_cast<CacheEntry *>(cache_index_dev), status_dev);
     EMB_RETURN_IF_LAUNCH_FAILED();
-    const int chunks = D * emb_elem_size(dtype) / 16;
+    const int chunks = (int)(emb_row_bytes(D, dtype) / 16);   // rows of every storage type are whole 16-byte chunks
     int64_t want = (num_hot * chunks + CB_BLOCK - 1) / CB_BLOCK;
     unsigned grid = (unsigned)(want > 65536 ? 65536 : want);
     hipLaunchKernelGGL(cache_copy_kernel, dim3(grid), dim3(CB_BLOCK), 0, s, reinterpret_cast<const char *>(table_dev),
@@ -207,7 +278,7 @@ extern "C" int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, i
 {
     if (B < 0 || nnz < 0 || num_rows <= 0 || num_hot < 0) return EMB_ERR_INVALID_ARG;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
-    int rc = emb_check_row_shape(D, dtype);
+    int rc = cached_row_shape(D, dtype);
     if (rc != EMB_OK) return rc;
     if (B == 0) return EMB_OK;
     if (!table_dev || !cache_index_dev || (num_hot > 0 && !cache_rows_dev)) return EMB_ERR_INVALID_ARG;
@@ -217,11 +288,23 @@ extern "C" int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, i
         return EMB_ERR_INVALID_ARG;
     if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
 
+    hipStream_t s = emb_stream(stream);
+    if (dtype == EMB_INT8 || dtype == EMB_INT4) {
+        const int64_t rb = emb_row_bytes(D, dtype);
+        const int ql = emb_quant_lanes(D);
+        const char *tp = reinterpret_cast<const char *>(table_dev), *cp = reinterpret_cast<const char *>(cache_rows_dev);
+        const CacheEntry *ip = reinterpret_cast<const CacheEntry *>(cache_index_dev);
+        unsigned long long *hm = reinterpret_cast<unsigned long long *>(hit_miss_dev);
+        if (dtype == EMB_INT8)
+            return dispatch_cached_quant<8>(ql, s, tp, cp, ip, num_rows, num_hot, B, nnz, rows_dev, offsets_dev, D, rb,
+                                            mode, out_dev, hm, status_dev);
+        return dispatch_cached_quant<4>(ql, s, tp, cp, ip, num_rows, num_hot, B, nnz, rows_dev, offsets_dev, D, rb, mode,
+                                        out_dev, hm, status_dev);
+    }
     const int chunks = D * emb_elem_size(dtype) / 16;
     int lpr, cpl;
     emb_row_split(chunks, lpr, cpl);
     const bool bf16 = dtype == EMB_BF16;
-    hipStream_t s = emb_stream(stream);
 #define EMB_CF(L, C, U)                                                                                         \
     return launch_cached<L, C, U>(bf16, s, reinterpret_cast<const char *>(table_dev),                           \
                                   reinterpret_cast<const char *>(cache_rows_dev),                               \

@@ -12,14 +12,9 @@
 // 16 (INT8) code bytes, so a row of D elements takes LPR = D/16 lanes rounded up
 // to a power of two; D must be a multiple of 16 and at most 1024.
 #include "emb_internal.h"
-#include "gather.h"
+#include "gather_quant.h"
 
 namespace {
-
-constexpr int Q_ELEMS = 16;   // elements per lane
-constexpr int Q_BLOCK = 256;
-
-__device__ __forceinline__ uint2 load_u2(const char *p) { return *reinterpret_cast<const uint2 *>(p); }
 
 // ---------------------------------------------------------------------------
 // quantiser
@@ -99,36 +94,24 @@ __global__ __launch_bounds__(Q_BLOCK) void quantize_rows_kernel(const float *__r
 }
 
 // ---------------------------------------------------------------------------
-// pooled lookup with dequantisation
+// pooled lookup with dequantisation (the loop is in gather_quant.h)
 // ---------------------------------------------------------------------------
-// 16 codes of a lane -> fp32.  INT4: masking every other nibble leaves one code per
-// byte, which converts with the byte-to-float instructions.
-template <int BITS>
-__device__ __forceinline__ void codes_to_float(const uint32_t (&w)[BITS == 8 ? 4 : 2], float (&f)[Q_ELEMS])
-{
-    if (BITS == 8) {
-#pragma unroll
-        for (int i = 0; i < Q_ELEMS; ++i) f[i] = (float)((w[i / 4] >> (8 * (i % 4))) & 0xFFu);
-    } else {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t even = w[h] & 0x0F0F0F0Fu, odd = (w[h] >> 4) & 0x0F0F0F0Fu;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                f[8 * h + 2 * i] = (float)((even >> (8 * i)) & 0xFFu);
-                f[8 * h + 2 * i + 1] = (float)((odd >> (8 * i)) & 0xFFu);
-            }
+// Rows come straight from the table in device memory.
+struct QuantTableSource {
+    const char *weights;
+    uint64_t num_rows;
+    int64_t row_bytes;
+    uint32_t *status;
+    __device__ __forceinline__ uint64_t resolve(int64_t r) const
+    {
+        if ((uint64_t)r >= num_rows) {
+            emb_flag(status, EMB_STATUS_BAD_INDEX);
+            return 0ull;
         }
+        return reinterpret_cast<uint64_t>(weights + r * row_bytes);
     }
-}
+};
 
-// The loop has the shape of gather_pool_bag (gather.h): a group of LPR lanes owns a
-// bag, fetches its indices with one coalesced load, the fetching lane resolves an
-// index to the row's address, addresses go round by shuffles, UNROLL rows are
-// requested before the first add.  A row costs every lane the 8-byte header (one
-// request for the group) and its own 8 or 16 code bytes.  Each element is
-// dequantised (one fused multiply-add) and then added, so the rounding behaviour
-// is that of summing fp32 rows.
 template <int LPR, int BITS, int UNROLL>
 __global__ __launch_bounds__(Q_BLOCK) void bag_forward_quant_kernel(const emb_table *__restrict__ tables, int32_t T,
                                                                     int64_t B, uint32_t blocks_per_table, int64_t nnz,
@@ -138,105 +121,16 @@ __global__ __launch_bounds__(Q_BLOCK) void bag_forward_quant_kernel(const emb_ta
                                                                     float *__restrict__ out, uint32_t *status)
 {
     constexpr int GROUPS = Q_BLOCK / LPR;
-    constexpr int IPL = (UNROLL > LPR) ? UNROLL / LPR : 1;  // indices fetched per lane per batch
-    constexpr int IB = IPL * LPR;                           // indices per batch
-    constexpr int CW = BITS == 8 ? 4 : 2;                   // code words per lane and row
-    static_assert(IB % UNROLL == 0, "index batch must be whole unroll groups");
-
     const uint32_t lb = emb_xcd_block(blockIdx.x, gridDim.x);
     const uint32_t t_raw = lb / blocks_per_table;
     const bool tail = t_raw >= (uint32_t)T;          // the grid is rounded up to whole dies
     const int t = tail ? T - 1 : (int)t_raw;
     const int l = threadIdx.x % LPR;
     const int64_t b = tail ? B : (int64_t)(lb % blocks_per_table) * GROUPS + threadIdx.x / LPR;
-    const bool live = b < B;
-    const int64_t bag = (int64_t)t * B + b;
     const emb_table tb = tables[t];
-    const char *weights = reinterpret_cast<const char *>(tb.weights);
-    const uint64_t num_rows = (uint64_t)tb.num_rows;
-    const bool mine_elems = l * Q_ELEMS < D;         // lanes past the row (D/16 not a power of two) idle
-    const int code_off = 8 + l * (BITS == 8 ? 16 : 8);
-
-    int64_t s = 0, e = 0;
-    if (live) {
-        s = offsets[bag];
-        e = offsets[bag + 1];
-        if (s < 0 || e < s || e > nnz) {
-            if (l == 0) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
-            s = e = 0;
-        }
-    }
-    float acc[Q_ELEMS];
-#pragma unroll
-    for (int i = 0; i < Q_ELEMS; ++i) acc[i] = 0.f;
-
-    for (int64_t base = s; base < e; base += IB) {
-        uint64_t mine[IPL];
-#pragma unroll
-        for (int m = 0; m < IPL; ++m) {
-            const int64_t j = base + m * LPR + l;
-            mine[m] = 0ull;
-            if (j < e) {
-                const int64_t r = rows[j];
-                if ((uint64_t)r < num_rows) mine[m] = reinterpret_cast<uint64_t>(weights + r * row_bytes);
-                else emb_flag(status, EMB_STATUS_BAD_INDEX);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < IB / UNROLL; ++u) {
-            if (base + u * UNROLL < e) {
-                uint2 hdr[UNROLL];
-                uint32_t w[UNROLL][CW];
-#pragma unroll
-                for (int i = 0; i < UNROLL; ++i) {
-                    const int k = u * UNROLL + i;
-                    const uint64_t p = (uint64_t)shfl_i64((int64_t)mine[k / LPR], k % LPR, LPR);
-                    hdr[i] = make_uint2(0u, 0u);     // a skipped row counts as scale 0, bias 0
-#pragma unroll
-                    for (int c = 0; c < CW; ++c) w[i][c] = 0u;
-                    if (p != 0 && mine_elems) {
-                        const char *row = reinterpret_cast<const char *>(p);
-                        hdr[i] = load_u2(row);
-                        const uint2 c0 = load_u2(row + code_off);
-                        w[i][0] = c0.x;
-                        w[i][1] = c0.y;
-                        if (BITS == 8) {
-                            const uint2 c1 = load_u2(row + code_off + 8);
-                            w[i][CW - 2] = c1.x;
-                            w[i][CW - 1] = c1.y;
-                        }
-                    }
-                }
-#pragma unroll
-                for (int i = 0; i < UNROLL; ++i) {
-                    const float scale = __uint_as_float(hdr[i].x), bias = __uint_as_float(hdr[i].y);
-                    float f[Q_ELEMS];
-                    codes_to_float<BITS>(w[i], f);
-#pragma unroll
-                    for (int x = 0; x < Q_ELEMS; ++x) acc[x] += __builtin_fmaf(scale, f[x], bias);
-                }
-            }
-        }
-    }
-
-    if (!live || !mine_elems) return;
-    const int64_t len = e - s;
-    const bool mean = (mode == EMB_POOL_MEAN) && len > 0;
-    const float flen = (float)len;
-    float4 *o = reinterpret_cast<float4 *>(out + bag * (int64_t)D + l * Q_ELEMS);
-#pragma unroll
-    for (int i = 0; i < Q_ELEMS / 4; ++i) {
-        float4 v = make_float4(acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]);
-        if (mean) v = make_float4(v.x / flen, v.y / flen, v.z / flen, v.w / flen);
-        o[i] = v;
-    }
-}
-
-int quant_lanes(int32_t D)
-{
-    int lpr = 1;
-    while (lpr * Q_ELEMS < D) lpr <<= 1;
-    return lpr;
+    QuantTableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, row_bytes, status};
+    gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, (int64_t)t * B + b, l, nnz, rows, offsets, D, mode, out,
+                                               status);
 }
 
 template <int LPR, int BITS>
@@ -329,8 +223,8 @@ extern "C" int emb_quantize_rows(const float *src_dev, int64_t num_rows, int32_t
     if (num_rows > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
     const int64_t rb = emb_row_bytes(D, dtype);
     hipStream_t s = emb_stream(stream);
-    if (dtype == EMB_INT8) dispatch_quantize<8>(quant_lanes(D), s, src_dev, num_rows, D, rb, static_cast<char *>(dst_dev));
-    else dispatch_quantize<4>(quant_lanes(D), s, src_dev, num_rows, D, rb, static_cast<char *>(dst_dev));
+    if (dtype == EMB_INT8) dispatch_quantize<8>(emb_quant_lanes(D), s, src_dev, num_rows, D, rb, static_cast<char *>(dst_dev));
+    else dispatch_quantize<4>(emb_quant_lanes(D), s, src_dev, num_rows, D, rb, static_cast<char *>(dst_dev));
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -341,7 +235,7 @@ int emb_forward_quant(const emb_table *tables_dev, int32_t T, int32_t D, int32_t
                       uint32_t *status_dev, hipStream_t s)
 {
     const int64_t rb = emb_row_bytes(D, dtype);
-    const int lpr = quant_lanes(D);
+    const int lpr = emb_quant_lanes(D);
     if (dtype == EMB_INT8)
         return dispatch_quant_forward<8>(lpr, s, tables_dev, T, B, nnz, rows_dev, offsets_dev, D, rb, mode, out_dev,
                                          status_dev);

@@ -526,6 +526,46 @@ def test_cached_forward_bad_hot_set_and_bad_index():
         assert status.item() == emb.STATUS_BAD_HOT_SET
 
 
+@pytest.mark.parametrize("dtype", ["int4", "int8"])
+@pytest.mark.parametrize("D", [64, 48])
+def test_cached_forward_over_quantized_table(dtype, D):
+    # the table is quantised into pinned host memory by the device; cache and table hold packed rows
+    rng = np.random.default_rng(1300 + D)
+    R, B, K = 30_000, 900, 2000
+    x = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+    packed = oracle.quantize_rows(x, dtype)
+    rb = emb.emb_row_bytes(D, dtype)
+    host = torch.empty((R, rb), dtype=torch.uint8, pin_memory=True)
+    ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+    emb.emb_quantize_rows(H.dev(x), dtype, ptr)
+    torch.cuda.synchronize()
+    assert np.array_equal(host.numpy(), packed)                       # written over the link, bit-exact
+    hot = np.sort(rng.choice(R, size=K, replace=False)).astype(np.int64)
+    lengths = rng.integers(0, 40, size=B).astype(np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    rows = np.where(rng.random(int(off[-1])) < 0.8, rng.choice(hot, size=int(off[-1])),
+                    rng.integers(0, R, size=int(off[-1]))).astype(np.int64)
+    rows[[4, 9]] = [R, -3]
+    index = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+    cache = torch.full((K, rb), 0xEE, dtype=torch.uint8, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_cache_build(ptr, R, D, dtype, H.dev(hot), cache, index, status)
+    torch.cuda.synchronize()
+    assert status.item() == 0 and np.array_equal(cache.cpu().numpy(), packed[hot])
+    out = torch.full((1, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    hm = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    emb.emb_bag_forward_cached(ptr, R, D, dtype, cache, index, K, H.dev(rows), H.dev(off), B, "sum", out, hm, status)
+    torch.cuda.synchronize()
+    ref, absum, (hits, misses), st = oracle.bag_forward_cached(packed, dtype, hot, rows, off, B, "sum", D=D)
+    assert int(status.item()) == st == emb.STATUS_BAD_INDEX
+    assert hm.cpu().tolist() == [hits, misses] and hits > 0 and misses > 0
+    H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="cached quantised forward")
+    # the cache is numerically invisible: the plain lookup over the same packed table gives the same bits
+    ts = emb.TableSet([H.dev(packed)], D, dtype, device=torch.device(H.DEV))
+    plain, _ = H.gpu_forward(ts, rows, off, B, "sum")
+    assert np.array_equal(plain.reshape(1, B, D), out.cpu().numpy())
+
+
 def test_cached_forward_reads_misses_from_pinned_host_memory():
     # the table lives in pinned (device-mapped) host memory; misses are read over PCIe
     rng = np.random.default_rng(61)
