@@ -157,19 +157,33 @@ def bench_hybrid(args) -> int:
     from paper_2508_05700_amd import pipeline, workloads as wl
 
     seed = wl.DEFAULT_SEED if args.seed is None else args.seed
-    w = wl.WORKLOADS["5"]
+    w = wl.WORKLOADS[args.workload]
+    store = w.storage
+    rowb = emb.emb_row_bytes(w.D, store)
+    need = w.R * rowb + (26 << 30)
     if args.scale_rows:
         w = w.scaled(rows=args.scale_rows)
-    elif psutil.virtual_memory().available < 90 * 2 ** 30:
+    elif psutil.virtual_memory().available < need:
         w = w.scaled(rows=w.R // 4)
-        log("workload 5 scaled to %d rows: not enough host memory to pin 64 GB" % w.R)
+        log("workload %s scaled to %d rows: not enough host memory to pin %.0f GB" % (args.workload, w.R, need / 2 ** 30))
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     K, W = args.steps, args.warmup
     t_setup = time.time()
-    host = torch.empty((w.R, w.D), dtype=torch.float32, pin_memory=True)
-    ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
-    emb.emb_table_fill(ptr, w.R, w.D, "f32", w.table_seed(0, seed))
+    if w.quant:
+        # the fp32 table is filled in HBM, quantised row by row into the pinned host table, and dropped
+        host = torch.empty((w.R, rowb), dtype=torch.uint8, pin_memory=True)
+        ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+        src = torch.empty((w.R, w.D), dtype=torch.float32, device=dev)
+        emb.emb_table_fill(src, w.R, w.D, "f32", w.table_seed(0, seed))
+        emb.emb_quantize_rows(src, store, ptr)
+        torch.cuda.synchronize()
+        del src
+        torch.cuda.empty_cache()
+    else:
+        host = torch.empty((w.R, w.D), dtype=torch.float32, pin_memory=True)
+        ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+        emb.emb_table_fill(ptr, w.R, w.D, "f32", w.table_seed(0, seed))
     n_hot = int(round(w.hot_fraction * w.R))
     n_ranks = int(n_hot * 1.06) + 1000
     hot_raw = torch.from_numpy(wl.hot_raw_ids(w, 0, n_ranks, seed).view(np.int64)).to(dev)
@@ -179,9 +193,10 @@ def bench_hybrid(args) -> int:
     n_hot = hot.numel()
     del hot_raw, hot_rows
     index = torch.empty(emb.emb_cache_index_bytes(w.R), dtype=torch.uint8, device=dev)
-    cache = torch.empty((n_hot, w.D), dtype=torch.float32, device=dev)
+    cache = (torch.empty((n_hot, rowb), dtype=torch.uint8, device=dev) if w.quant
+             else torch.empty((n_hot, w.D), dtype=torch.float32, device=dev))
     status = torch.zeros(1, dtype=torch.int32, device=dev)
-    emb.emb_cache_build(ptr, w.R, w.D, "f32", hot, cache, index, status)
+    emb.emb_cache_build(ptr, w.R, w.D, store, hot, cache, index, status)
     dbs = [pipeline.DeviceBatch(w, wl.make_batch(w, i, seed), dev) for i in range(args.batches)]
     max_nnz = max(d.nnz for d in dbs)
     offsets = torch.empty(w.B + 1, dtype=torch.int64, device=dev)
@@ -190,8 +205,8 @@ def bench_hybrid(args) -> int:
     hm = torch.zeros(2, dtype=torch.int64, device=dev)
     torch.cuda.synchronize()
     assert int(status.item()) == 0
-    log("setup: host table %d x %d f32 (%.1f GB pinned), cache %d rows (%.2f GB), %.1f s" % (
-        w.R, w.D, w.R * w.D * 4 / 1e9, n_hot, n_hot * w.D * 4 / 1e9, time.time() - t_setup))
+    log("setup: host table %d x %d %s (%.1f GB pinned), cache %d rows (%.2f GB), %.1f s" % (
+        w.R, w.D, store, w.R * rowb / 1e9, n_hot, n_hot * rowb / 1e9, time.time() - t_setup))
 
     def step(db, e=None):
         if e:
@@ -201,7 +216,7 @@ def bench_hybrid(args) -> int:
         emb.emb_hash_ids(db.raw, w.salt(0), w.R, r)
         if e:
             e[1].record()
-        emb.emb_bag_forward_cached(ptr, w.R, w.D, "f32", cache, index, n_hot, r, offsets, w.B, w.pool, out, hm, status)
+        emb.emb_bag_forward_cached(ptr, w.R, w.D, store, cache, index, n_hot, r, offsets, w.B, w.pool, out, hm, status)
         if e:
             e[2].record()
 
@@ -221,13 +236,12 @@ def bench_hybrid(args) -> int:
     hits, misses = [int(x) for x in hm.cpu().tolist()]
     ms_index = sum(e[0].elapsed_time(e[1]) for e in ev) / K
     ms_fwd = sum(e[1].elapsed_time(e[2]) for e in ev) / K
-    rowb = w.D * 4
     pcie_gbs = misses / K * rowb / (ms_fwd * 1e-3) / 1e9
     hbm_gbs = (hits / K * rowb + lookups / K * 24 + w.B * (4 * w.D + 8)) / (ms_fwd * 1e-3) / 1e9
 
     # what the link delivers to a plain DMA copy from the same pinned buffer (context for the PCIe rate)
     n_copy = min(w.R, (1 << 30) // rowb)
-    staging = torch.empty((n_copy, w.D), dtype=torch.float32, device=dev)
+    staging = torch.empty((n_copy, host.shape[1]), dtype=host.dtype, device=dev)
     staging.copy_(host[:n_copy], non_blocking=True)
     torch.cuda.synchronize()
     c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -245,13 +259,15 @@ def bench_hybrid(args) -> int:
         "metric": METRIC, "value": round(lookups / elapsed, 1), "unit": "lookups/s", "n_gpus": 1, "steps": K,
         "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "5: host-resident table %d rows x dim %d f32 (pinned) + HBM cache of %d hot rows, "
-                               "%d bags, poisson bag lengths (mean %g), zipf IDs alpha=%g over %.0e keys, %s pooling, "
-                               "forward only" % (w.R, w.D, n_hot, w.B, w.mean_len, w.alpha, w.n_keys, w.pool),
+        "config": {"workload": "%s: host-resident table %d rows x dim %d %s (%d B per row, pinned) + HBM cache of %d "
+                               "hot rows, %d bags, poisson bag lengths (mean %g), zipf IDs alpha=%g over %.0e keys, "
+                               "%s pooling, forward only" % (w.name, w.R, w.D, store, rowb, n_hot, w.B, w.mean_len,
+                                                             w.alpha, w.n_keys, w.pool),
                    "lookups_per_step": round(lookups / K, 1), "resident_batches": len(dbs), "seed": seed},
         "stages": {"index_ms": round(ms_index, 4), "forward_cached_ms": round(ms_fwd, 4),
                    "hit_rate": round(hits / max(1, hits + misses), 5), "misses_per_step": round(misses / K, 1)},
-        "roofline": {"kernel": "bag_forward_cached_kernel", "bound": "pcie", "achieved": round(pcie_gbs, 2),
+        "roofline": {"kernel": "bag_forward_cached_quant_kernel" if w.quant else "bag_forward_cached_kernel",
+                     "bound": "pcie", "achieved": round(pcie_gbs, 2),
                      "peak": PCIE_PEAK, "unit": "GB/s", "frac": round(pcie_gbs / PCIE_PEAK, 4), "traffic": None,
                      "avg_ms": round(ms_fwd, 4), "algorithmic_bytes": int(misses / K * rowb),
                      "bytes_are": "one table row per miss, read zero-copy from pinned host memory",
@@ -299,7 +315,7 @@ def main() -> int:
         log("bench.py: no GPU visible")
         return 2
     emb.lib()
-    if args.workload == "5":
+    if wl.WORKLOADS[args.workload].hybrid:
         return bench_hybrid(args)
     seed = wl.DEFAULT_SEED if args.seed is None else args.seed
     w = wl.WORKLOADS[args.workload]

@@ -261,6 +261,10 @@ WORKLOADS: Dict[str, Workload] = {
     "5": Workload("5", T=1, R=250_000_000, D=64, dtype="f32", B=16384, length="poisson", mean_len=30,
                   max_len=None, ids="zipf", alpha=1.1, n_keys=10 ** 9, pool="sum", hybrid=True,
                   hot_fraction=0.05),
+    # 5q4: the same with the host table (and the cache) stored as INT4 rows
+    "5q4": Workload("5q4", T=1, R=250_000_000, D=64, dtype="f32", B=16384, length="poisson", mean_len=30,
+                    max_len=None, ids="zipf", alpha=1.1, n_keys=10 ** 9, pool="sum", hybrid=True,
+                    hot_fraction=0.05, quant="int4"),
 }
 
 

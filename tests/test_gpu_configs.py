@@ -257,3 +257,69 @@ def test_workload_5_host_table_with_hbm_cache():
         say("workload 5 scaled to %d rows: only %.0f GB of host memory available" % (w.R, avail / 2 ** 30))
     rate = _hybrid_parity(w, "workload " + w.name)
     assert 0.85 < rate < 0.97            # Zipf(1.1) over 1e9 keys: the top 5 % of rows carry ~92 % of lookups
+
+
+def test_workload_5q4_int4_host_table_with_hbm_cache():
+    # Workload 5 with the hosted table stored as INT4 rows (the paper quantises exactly these tables).
+    # The fp32 table is filled in HBM and quantised into pinned host memory by the device; the oracle
+    # quantises the generator's values of the rows the batch and the checks touch.
+    w = wl.WORKLOADS["5q4"]
+    import psutil
+    rb = emb.emb_row_bytes(w.D, w.quant)
+    if psutil.virtual_memory().available < w.R * rb + (26 << 30):
+        w = w.scaled(rows=w.R // 4)
+        say("workload 5q4 scaled to %d rows" % w.R)
+    rng = np.random.default_rng(6)
+    K = int(round(w.hot_fraction * w.R))
+    say("5q4: filling %.0f GB of fp32 rows in HBM, quantising into %.1f GB of pinned host memory" % (
+        w.R * w.D * 4 / 2 ** 30, w.R * rb / 2 ** 30))
+    host = torch.empty((w.R, rb), dtype=torch.uint8, pin_memory=True)
+    ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+    src = torch.empty((w.R, w.D), dtype=torch.float32, device=H.DEV)
+    emb.emb_table_fill(src, w.R, w.D, "f32", w.table_seed(0))
+    emb.emb_quantize_rows(src, w.quant, ptr)
+    torch.cuda.synchronize()
+    del src
+    torch.cuda.empty_cache()
+    probe = np.sort(rng.integers(0, w.R, size=20_000))
+    assert np.array_equal(host.numpy()[probe],
+                          oracle.quantize_rows(wl.table_values(w.table_seed(0), probe, w.D), w.quant))
+
+    n_ranks = int(K * 1.06) + 1000
+    hot = wl.first_k_distinct_sorted(oracle.hash_ids(wl.hot_raw_ids(w, 0, n_ranks), w.salt(0), w.R), K)
+    assert hot.size == K
+    index = torch.empty(emb.emb_cache_index_bytes(w.R), dtype=torch.uint8, device=H.DEV)
+    cache = torch.empty((K, rb), dtype=torch.uint8, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_cache_build(ptr, w.R, w.D, w.quant, H.dev(hot), cache, index, status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    sample = np.sort(rng.integers(0, K, size=20_000))
+    assert np.array_equal(cache[torch.from_numpy(sample).to(H.DEV)].cpu().numpy(),
+                          oracle.quantize_rows(wl.table_values(w.table_seed(0), hot[sample], w.D), w.quant))
+
+    batch = wl.make_batch(w, 0)
+    db = pipeline.DeviceBatch(w, batch, torch.device(H.DEV))
+    off_dev = torch.empty(w.B + 1, dtype=torch.int64, device=H.DEV)
+    rows_dev = torch.empty(db.nnz, dtype=torch.int64, device=H.DEV)
+    out = torch.empty((1, w.B, w.D), dtype=torch.float32, device=H.DEV)
+    hm = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    emb.emb_lengths_to_offsets(db.lengths, off_dev, status)
+    emb.emb_hash_ids(db.raw, w.salt(0), w.R, rows_dev)
+    emb.emb_bag_forward_cached(ptr, w.R, w.D, w.quant, cache, index, K, rows_dev, off_dev, w.B, w.pool, out, hm, status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    off, rows = _oracle_index(w, batch)
+    assert np.array_equal(rows_dev.cpu().numpy(), rows)
+    say("5q4: oracle quantiser and forward over %d lookups" % rows.size)
+    # compact table of the touched rows; lookups and hot rows renumbered into it (plumbing only)
+    touched = np.unique(rows)
+    packed = oracle.quantize_rows(wl.table_values(w.table_seed(0), touched, w.D), w.quant)
+    hot_compact = np.flatnonzero(np.isin(touched, hot, assume_unique=True)).astype(np.int64)
+    ref, absum, (hits, misses), st = oracle.bag_forward_cached(packed, w.quant, hot_compact,
+                                                               np.searchsorted(touched, rows).astype(np.int64), off,
+                                                               w.B, w.pool, D=w.D)
+    assert st == 0
+    assert hm.cpu().tolist() == [hits, misses]
+    H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="workload 5q4")
+    assert 0.85 < hits / max(1, hits + misses) < 0.97
