@@ -291,6 +291,8 @@ def main() -> int:
     ap.add_argument("--scale-rows", type=int, default=None, help="rows per table (debug: smaller tables)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the forward-only side measurements")
+    ap.add_argument("--no-fused-forward", action="store_true",
+                    help="hash the IDs in a kernel of their own instead of inside the forward lookup")
     ap.add_argument("--overlap-sort", action="store_true",
                     help="enqueue the backward's sort on a second stream beside the forward (measured: no gain "
                          "here, the forward saturates HBM and the sort's small kernels only get slower)")
@@ -343,7 +345,35 @@ def main() -> int:
         del cal
 
     K, W = args.steps, args.warmup
-    step_fn = pipeline.run_step_overlapped if args.overlap_sort else pipeline.run_step
+    fused = not args.no_fused_forward and not args.overlap_sort and not w.quant and dbs[0].raw is not None
+
+    def do_index(db):
+        """Bag offsets, and the hashing unless it is fused into the forward.  Returns the rows (or None)."""
+        if fused:
+            emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
+            return None
+        return pipeline.run_index_stage(w, tabs.set, db, buf)
+
+    def do_forward(db, rows):
+        if fused:
+            rows = buf.rows[:db.nnz]
+            emb.emb_bag_forward_hashed(tabs.set, db.raw, buf.offsets, w.B, w.pool, buf.out,
+                                       rows if w.backward else None, buf.status)
+            return rows
+        pipeline.run_forward(w, tabs.set, rows, buf)
+        return rows
+
+    def index_and_forward(db):
+        return do_forward(db, do_index(db))
+
+    def step_fn(w_, tset, db, buf_):
+        if args.overlap_sort:
+            return pipeline.run_step_overlapped(w_, tset, db, buf_)
+        rows = index_and_forward(db)
+        if w_.backward:
+            pipeline.run_backward(w_, tset, rows, db, buf_)
+        return rows
+
     for i in range(W):
         step_fn(w, tabs.set, dbs[i % len(dbs)], buf)
     torch.cuda.synchronize()
@@ -371,13 +401,12 @@ def main() -> int:
             if args.overlap_sort:
                 pipeline.run_step_overlapped(w, tabs.set, db, buf, stage_events=sev)
             else:
-                rows = pipeline.run_index_stage(w, tabs.set, db, buf)
-                pipeline.run_forward(w, tabs.set, rows, buf)
+                rows = index_and_forward(db)
                 pipeline.run_backward(w, tabs.set, rows, db, buf, stage_events=sev)
         else:
-            rows = pipeline.run_index_stage(w, tabs.set, db, buf)
+            rows = do_index(db)
             dom[k][0].record()
-            pipeline.run_forward(w, tabs.set, rows, buf)
+            do_forward(db, rows)
             dom[k][1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -393,9 +422,9 @@ def main() -> int:
     for k in range(KI):
         db = dbs[(W + k) % len(dbs)]
         ev[k][0].record()
-        rows = pipeline.run_index_stage(w, tabs.set, db, buf)
+        rows = do_index(db)
         ev[k][1].record()
-        pipeline.run_forward(w, tabs.set, rows, buf)
+        rows = do_forward(db, rows)
         ev[k][2].record()
         if w.backward:
             pipeline.run_backward(w, tabs.set, rows, db, buf, stage_events=bev[k])
@@ -418,14 +447,24 @@ def main() -> int:
                 "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "avg_ms": round(ms, 4),
                 "algorithmic_bytes": int(nbytes), "bytes_are": what}
 
+    if fused:
+        fwd_name, fwd_pmc = "bag_forward_hashed_kernel (hash + gather-pool)", "bag_forward_hashed_kernel"
+        fwd_extra = nnz_i * 8 if w.backward else 0        # the row numbers written for the backward
+        index_entry = entry("offsets_* (index stage, 3 launches; hashing is done inside the forward)", ms_index,
+                            bags * 12, "12 B per bag (length in, offset out)")
+    else:
+        fwd_name = ("bag_forward_quant_kernel (gather-dequantise-pool, %s rows of %d B)" % (w.quant, rowb) if w.quant
+                    else "bag_forward_kernel (gather-pool)")
+        fwd_pmc = "bag_forward_quant_kernel" if w.quant else "bag_forward_kernel"
+        fwd_extra = 0
+        index_entry = entry("offsets_* + hash_ids_tables_kernel (index stage, 4 launches)", ms_index,
+                            nnz_i * 16 + bags * 12,
+                            "16 B per lookup (raw ID in, row out) + 12 B per bag (length in, offset out)")
     kernels = [
-        entry("offsets_* + hash_ids_tables_kernel (index stage, 4 launches)", ms_index, nnz_i * 16 + bags * 12,
-              "16 B per lookup (raw ID in, row out) + 12 B per bag (length in, offset out)"),
-        entry("bag_forward_quant_kernel (gather-dequantise-pool, %s rows of %d B)" % (w.quant, rowb) if w.quant
-              else "bag_forward_kernel (gather-pool)", ms_fwd if w.backward else ms_dom,
-              forward_bytes(nnz_i, bags, w.D, rowb),
-              "row + 8 B index per lookup, fp32 output row + 8 B offset per bag",
-              "bag_forward_quant_kernel" if w.quant else "bag_forward_kernel"),
+        index_entry,
+        entry(fwd_name, ms_fwd if w.backward else ms_dom, forward_bytes(nnz_i, bags, w.D, rowb) + fwd_extra,
+              "row + 8 B index per lookup (+ 8 B row number out when a backward follows), fp32 output row + 8 B "
+              "offset per bag", fwd_pmc),
     ]
     ms_bwd = 0.0
     if w.backward:

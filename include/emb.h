@@ -228,6 +228,20 @@ int emb_bag_backward_update(const emb_table *tables_host, const emb_table *table
                             void *const *stage_events, const emb_side_stream *side,
                             void *stream);
 
+/* emb_hash_ids_tables and emb_bag_forward in one pass (Sections 2.2, 3.1): the
+ * entries of raw_dev (u64[nnz], table-major like rows_dev) are raw IDs; the
+ * lookup hashes each with its table's salt and num_rows as it fetches it, so
+ * hashing costs neither a launch nor a pass over the indices.  out_dev is
+ * bit-identical to emb_bag_forward over the hashed rows.  rows_out_dev
+ * (nullable, i64[nnz]) receives the row numbers, for the backward; entries of
+ * lookups that lie in no valid bag (EMB_STATUS_BAD_OFFSETS) are not written.
+ * dtype: EMB_F32 or EMB_BF16 (EMB_ERR_UNSUPPORTED for quantised tables). */
+int emb_bag_forward_hashed(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                           int32_t D, int32_t dtype, const uint64_t *raw_dev,
+                           const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
+                           float *out_dev, int64_t *rows_out_dev, uint32_t *status_dev,
+                           void *stream);
+
 /* ---- row-quantised tables (Section 4.1.2: INT4 tables for serving) ------- */
 
 /* Bytes of one table row: D*4 (EMB_F32), D*2 (EMB_BF16), or for the quantised

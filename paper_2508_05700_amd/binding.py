@@ -31,7 +31,7 @@ assert TABLE_DESC.itemsize == 48
 
 EXPORTS = [
     "emb_status_string", "emb_tables_init", "emb_hash_ids", "emb_hash_ids_tables", "emb_lengths_to_offsets",
-    "emb_bag_forward", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
+    "emb_bag_forward", "emb_bag_forward_hashed", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
     "emb_bag_backward_sort", "emb_bag_backward_update", "emb_row_bytes", "emb_quantize_rows",
     "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
@@ -76,6 +76,8 @@ def lib() -> C.CDLL:
     L.emb_lengths_to_offsets.argtypes = [vp, i64, vp, vp, vp]
     L.emb_bag_forward.restype = C.c_int
     L.emb_bag_forward.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp]
+    L.emb_bag_forward_hashed.restype = C.c_int
+    L.emb_bag_forward_hashed.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     L.emb_bag_backward_workspace_bytes.restype = sz
     L.emb_bag_backward_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32]
     L.emb_bag_backward_rowwise_adagrad.restype = C.c_int
@@ -230,6 +232,21 @@ def emb_bag_forward(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor,
         tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype],
         _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), rows.numel(), POOL[mode],
         _ptr(out, torch.float32, "out"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_bag_forward_hashed(tables: TableSet, raw: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
+                           out: torch.Tensor, rows_out: Optional[torch.Tensor] = None,
+                           status: Optional[torch.Tensor] = None) -> None:
+    """Hashing and pooled lookup in one pass; ``rows_out`` (int64 [nnz]) receives the row numbers."""
+    nnz = raw.numel()
+    if offsets.numel() != tables.T * B + 1 or out.numel() != tables.T * B * tables.D:
+        raise TypeError("shape mismatch")
+    if rows_out is not None and rows_out.numel() != nnz:
+        raise TypeError("rows_out must have as many elements as raw")
+    _check("emb_bag_forward_hashed", lib().emb_bag_forward_hashed(
+        tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype], _ptr(raw, _U64, "raw"),
+        _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode], _ptr(out, torch.float32, "out"),
+        _ptr(rows_out, torch.int64, "rows_out"), _ptr(status, torch.int32, "status"), _stream()))
 
 
 def emb_row_bytes(D: int, dtype: str) -> int:

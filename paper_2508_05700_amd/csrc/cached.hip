@@ -79,7 +79,7 @@ struct CachedSource {
     int64_t row_bytes;
     uint32_t *status;
     uint32_t hits, misses;
-    __device__ __forceinline__ uint64_t resolve(int64_t r)
+    __device__ __forceinline__ uint64_t resolve(int64_t r, int64_t)
     {
         if ((uint64_t)r >= num_rows) {
             emb_flag(status, EMB_STATUS_BAD_INDEX);

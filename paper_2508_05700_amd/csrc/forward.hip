@@ -9,6 +9,7 @@
 // cached lookup.
 #include "emb_internal.h"
 #include "gather.h"
+#include "u64mod.h"
 
 namespace {
 
@@ -20,7 +21,7 @@ struct TableSource {
     uint64_t num_rows;
     int64_t row_bytes;
     uint32_t *status;
-    __device__ __forceinline__ uint64_t resolve(int64_t r) const
+    __device__ __forceinline__ uint64_t resolve(int64_t r, int64_t) const
     {
         if ((uint64_t)r >= num_rows) {
             emb_flag(status, EMB_STATUS_BAD_INDEX);
@@ -29,6 +30,45 @@ struct TableSource {
         return reinterpret_cast<uint64_t>(weights + r * row_bytes);
     }
 };
+
+// The entries are raw IDs: the row is splitmix64(raw XOR salt) mod num_rows (Section 2.2), computed
+// by the lane that fetched the ID, so hashing costs no pass of its own.  The row numbers can be
+// written out for the backward.
+struct HashedTableSource {
+    const char *weights;
+    uint64_t num_rows, salt, magic;
+    int64_t row_bytes;
+    int64_t *rows_out;   // nullable
+    __device__ __forceinline__ uint64_t resolve(int64_t raw, int64_t j) const
+    {
+        const uint64_t r = emb_fast_mod(emb_splitmix64((uint64_t)raw ^ salt), num_rows, magic);
+        if (rows_out) rows_out[j] = (int64_t)r;
+        return reinterpret_cast<uint64_t>(weights + (int64_t)r * row_bytes);
+    }
+};
+
+template <int LPR, int CPL, int UNROLL, bool BF16>
+__global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb_table *__restrict__ tables, int32_t T,
+                                                                       int64_t B, uint32_t blocks_per_table,
+                                                                       int64_t nnz, const int64_t *__restrict__ raw,
+                                                                       const int64_t *__restrict__ offsets,
+                                                                       int32_t chunks_per_row, int32_t mode,
+                                                                       float *__restrict__ out,
+                                                                       int64_t *__restrict__ rows_out, uint32_t *status)
+{
+    constexpr int GROUPS = FWD_BLOCK / LPR;
+    const uint32_t lb = emb_xcd_block(blockIdx.x, gridDim.x);
+    const uint32_t t_raw = lb / blocks_per_table;
+    const bool tail = t_raw >= (uint32_t)T;          // the grid is rounded up to whole dies
+    const int t = tail ? T - 1 : (int)t_raw;
+    const int l = threadIdx.x % LPR;
+    const int64_t b = tail ? B : (int64_t)(lb % blocks_per_table) * GROUPS + threadIdx.x / LPR;
+    const emb_table tb = tables[t];
+    HashedTableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, tb.salt, tb.mod_magic,
+                          (int64_t)chunks_per_row * 16, rows_out};
+    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, (int64_t)t * B + b, l, nnz, raw, offsets, chunks_per_row,
+                                            mode, out, status);
+}
 
 template <int LPR, int CPL, int UNROLL, bool BF16>
 __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table *__restrict__ tables, int32_t T, int64_t B,
@@ -52,16 +92,27 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table 
                                             mode, out, status);
 }
 
+// rows_out != NULL or hashed: `rows` holds raw IDs and the hashing kernel is launched.
 template <int LPR, int CPL, int UNROLL>
 int launch_forward(bool bf16, int32_t T, hipStream_t s, const emb_table *tables, int64_t B, int64_t nnz,
                    const int64_t *rows, const int64_t *offsets, int32_t chunks, int32_t mode, float *out,
-                   uint32_t *status)
+                   uint32_t *status, bool hashed = false, int64_t *rows_out = nullptr)
 {
     constexpr int GROUPS = FWD_BLOCK / LPR;
     const int64_t per_table = (B + GROUPS - 1) / GROUPS;
     const int64_t blocks = emb_round_up_xcds(per_table * T);
     if (blocks > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)blocks);
+    if (hashed) {
+        if (bf16)
+            hipLaunchKernelGGL((bag_forward_hashed_kernel<LPR, CPL, UNROLL, true>), grid, dim3(FWD_BLOCK), 0, s, tables,
+                               T, B, (uint32_t)per_table, nnz, rows, offsets, chunks, mode, out, rows_out, status);
+        else
+            hipLaunchKernelGGL((bag_forward_hashed_kernel<LPR, CPL, UNROLL, false>), grid, dim3(FWD_BLOCK), 0, s, tables,
+                               T, B, (uint32_t)per_table, nnz, rows, offsets, chunks, mode, out, rows_out, status);
+        EMB_RETURN_IF_LAUNCH_FAILED();
+        return EMB_OK;
+    }
     if (bf16)
         hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, true>), grid, dim3(FWD_BLOCK), 0, s, tables, T, B,
                            (uint32_t)per_table, nnz, rows, offsets, chunks, mode, out, status);
@@ -74,9 +125,10 @@ int launch_forward(bool bf16, int32_t T, hipStream_t s, const emb_table *tables,
 
 }  // namespace
 
-extern "C" int emb_bag_forward(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
-                               int32_t dtype, const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B,
-                               int64_t nnz, int32_t mode, float *out_dev, uint32_t *status_dev, void *stream)
+static int forward_entry(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
+                         int32_t dtype, const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
+                         int32_t mode, float *out_dev, uint32_t *status_dev, void *stream, bool hashed,
+                         int64_t *rows_out_dev)
 {
     if (B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
@@ -91,16 +143,19 @@ extern "C" int emb_bag_forward(const emb_table *tables_host, const emb_table *ta
     if (!emb_aligned(out_dev, 16)) return EMB_ERR_INVALID_ARG;
     if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
 
-    if (quant)
+    if (quant) {
+        if (hashed) return EMB_ERR_UNSUPPORTED;   // quantised tables take row numbers
         return emb_forward_quant(tables_dev, T, D, dtype, rows_dev, offsets_dev, B, nnz, mode, out_dev, status_dev,
                                  emb_stream(stream));
+    }
     const int chunks = D * emb_elem_size(dtype) / 16;
     int lpr, cpl;
     emb_row_split(chunks, lpr, cpl);
     const bool bf16 = dtype == EMB_BF16;
     hipStream_t s = emb_stream(stream);
 #define EMB_FWD(L, C, U) \
-    return launch_forward<L, C, U>(bf16, T, s, tables_dev, B, nnz, rows_dev, offsets_dev, chunks, mode, out_dev, status_dev)
+    return launch_forward<L, C, U>(bf16, T, s, tables_dev, B, nnz, rows_dev, offsets_dev, chunks, mode, out_dev, \
+                                   status_dev, hashed, rows_out_dev)
     if (cpl == 1) {
         switch (lpr) {
             case 1: EMB_FWD(1, 1, 8);
@@ -119,4 +174,21 @@ extern "C" int emb_bag_forward(const emb_table *tables_host, const emb_table *ta
         default: EMB_FWD(64, 16, 1);
     }
 #undef EMB_FWD
+}
+
+extern "C" int emb_bag_forward(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
+                               int32_t dtype, const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B,
+                               int64_t nnz, int32_t mode, float *out_dev, uint32_t *status_dev, void *stream)
+{
+    return forward_entry(tables_host, tables_dev, T, D, dtype, rows_dev, offsets_dev, B, nnz, mode, out_dev,
+                         status_dev, stream, false, nullptr);
+}
+
+extern "C" int emb_bag_forward_hashed(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
+                                      int32_t dtype, const uint64_t *raw_dev, const int64_t *offsets_dev, int64_t B,
+                                      int64_t nnz, int32_t mode, float *out_dev, int64_t *rows_out_dev,
+                                      uint32_t *status_dev, void *stream)
+{
+    return forward_entry(tables_host, tables_dev, T, D, dtype, reinterpret_cast<const int64_t *>(raw_dev), offsets_dev,
+                         B, nnz, mode, out_dev, status_dev, stream, true, rows_out_dev);
 }

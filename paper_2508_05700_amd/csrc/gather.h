@@ -96,7 +96,8 @@ static inline void emb_row_split(int chunks, int &lpr, int &cpl)
 // only ever adds the chunks it owns.
 //
 // Source must provide
-//   __device__ uint64_t resolve(int64_t row)   address of the row, 0 = skip it
+//   __device__ uint64_t resolve(int64_t v, int64_t j)   address of the row that entry j of
+//                                                       `rows` (value v) selects, 0 = skip it
 // ---------------------------------------------------------------------------
 template <int LPR, int CPL, int UNROLL, bool BF16, typename Source>
 __device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t bag, int l, int64_t nnz,
@@ -127,7 +128,7 @@ __device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t 
 #pragma unroll
         for (int m = 0; m < IPL; ++m) {
             const int64_t j = base + m * LPR + l;
-            mine[m] = (j < e) ? src.resolve(rows[j]) : 0ull;
+            mine[m] = (j < e) ? src.resolve(rows[j], j) : 0ull;
         }
 #pragma unroll
         for (int u = 0; u < IB / UNROLL; ++u) {

@@ -68,7 +68,7 @@ __device__ __forceinline__ void gather_dequant_pool_bag(Source &src, bool live, 
 #pragma unroll
         for (int m = 0; m < IPL; ++m) {
             const int64_t j = base + m * LPR + l;
-            mine[m] = (j < e) ? src.resolve(rows[j]) : 0ull;
+            mine[m] = (j < e) ? src.resolve(rows[j], j) : 0ull;
         }
 #pragma unroll
         for (int u = 0; u < IB / UNROLL; ++u) {

@@ -5,15 +5,6 @@
 
 namespace {
 
-// First output of a SplitMix64 generator with state x (Steele, Lea, Flood 2014).
-__device__ __forceinline__ uint64_t splitmix64(uint64_t x)
-{
-    uint64_t z = x + 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
 constexpr int HASH_BLOCK = 256;
 
 __global__ __launch_bounds__(HASH_BLOCK) void hash_ids_kernel(const uint64_t *__restrict__ raw, int64_t n,
@@ -21,7 +12,7 @@ __global__ __launch_bounds__(HASH_BLOCK) void hash_ids_kernel(const uint64_t *__
                                                               int64_t *__restrict__ rows)
 {
     int64_t i = (int64_t)blockIdx.x * HASH_BLOCK + threadIdx.x;
-    if (i < n) rows[i] = (int64_t)emb_fast_mod(splitmix64(raw[i] ^ salt), R, magic);
+    if (i < n) rows[i] = (int64_t)emb_fast_mod(emb_splitmix64(raw[i] ^ salt), R, magic);
 }
 
 // One launch for all tables.  A thread hashes HASH_ITEMS lookups, HASH_BLOCK apart
@@ -76,7 +67,7 @@ __global__ __launch_bounds__(HASH_BLOCK) void hash_ids_tables_kernel(const emb_t
             tb = tables[t];
         }
         if (b0 <= j && j < b1) {
-            rows[j] = (int64_t)emb_fast_mod(splitmix64(v[k] ^ tb.salt), (uint64_t)tb.num_rows, tb.mod_magic);
+            rows[j] = (int64_t)emb_fast_mod(emb_splitmix64(v[k] ^ tb.salt), (uint64_t)tb.num_rows, tb.mod_magic);
         } else {                             // the boundaries do not partition [0, nnz)
             rows[j] = -1;
             emb_flag(status, EMB_STATUS_BAD_OFFSETS);

@@ -102,7 +102,7 @@ struct QuantTableSource {
     uint64_t num_rows;
     int64_t row_bytes;
     uint32_t *status;
-    __device__ __forceinline__ uint64_t resolve(int64_t r) const
+    __device__ __forceinline__ uint64_t resolve(int64_t r, int64_t) const
     {
         if ((uint64_t)r >= num_rows) {
             emb_flag(status, EMB_STATUS_BAD_INDEX);

@@ -32,3 +32,12 @@ EMB_HD static inline uint64_t emb_fast_mod(uint64_t x, uint64_t R, uint64_t magi
     uint64_t r = x - q * R;
     return r >= R ? r - R : r;
 }
+
+// First output of a SplitMix64 generator with state x (Steele, Lea, Flood 2014).
+EMB_HD static inline uint64_t emb_splitmix64(uint64_t x)
+{
+    uint64_t z = x + UINT64_C(0x9E3779B97F4A7C15);
+    z = (z ^ (z >> 30)) * UINT64_C(0xBF58476D1CE4E5B9);
+    z = (z ^ (z >> 27)) * UINT64_C(0x94D049BB133111EB);
+    return z ^ (z >> 31);
+}

@@ -105,6 +105,21 @@ def run_index_stage(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: Ste
     return rows
 
 
+def run_index_and_forward_fused(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:
+    """Bag offsets, then hashing and pooled lookup in one kernel.  Returns the view of the row
+    buffer the kernel filled (for the backward).  Workloads whose IDs are row numbers already, or
+    whose tables are quantised, take the two-kernel route."""
+    if db.raw is None or w.quant:
+        rows = run_index_stage(w, tables, db, buf)
+        run_forward(w, tables, rows, buf)
+        return rows
+    emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
+    rows = buf.rows[:db.nnz]
+    emb.emb_bag_forward_hashed(tables, db.raw, buf.offsets, w.B, w.pool, buf.out, rows if w.backward else None,
+                               buf.status)
+    return rows
+
+
 def run_forward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, buf: StepBuffers) -> None:
     emb.emb_bag_forward(tables, rows, buf.offsets, w.B, w.pool, buf.out, buf.status)
 

@@ -145,6 +145,12 @@ def test_quantized_row_size_and_argument_errors(L):
     assert q(FAKE, 10, 64, 3, FAKE + 8, None) == INVALID        # 16-byte alignment
     assert q(FAKE, -1, 64, 3, FAKE, None) == INVALID
     assert q(FAKE, 0, 64, 3, FAKE, None) == OK                  # nothing to do
+    # hashing fused into the forward: fp32 / bf16 tables only
+    d0 = _tables()
+    fh = L.emb_bag_forward_hashed
+    assert fh(d0.ctypes.data, FAKE, 2, 64, 3, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == UNSUPPORTED
+    assert fh(d0.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, None, None, None, None) == INVALID
+    assert fh(d0.ctypes.data, FAKE, 2, 64, 0, None, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID
     # quantised tables are read by the forward only
     assert L.emb_bag_backward_workspace_bytes(2, 4, 8, 1007, 64, 3) == 0
     d = _tables()

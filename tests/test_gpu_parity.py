@@ -157,6 +157,35 @@ def test_forward_bad_indices_and_offsets_are_flagged_and_skipped():
     H.assert_pooled_close(out, ref, absum, what="bad offsets")
 
 
+@pytest.mark.parametrize("D,dtype", [(64, "f32"), (32, "bf16"), (320, "f32")])
+def test_forward_hashed_equals_hash_then_forward(D, dtype):
+    rng = np.random.default_rng(1500 + D)
+    T, B = 4, 500
+    Rs = [100_003, 7, 1 << 20, 5000]
+    salts = [0, 11, M64, 1 << 33]
+    tables, lengths, off, _ = H.random_case(rng, T, B, D, Rs, 25, dtype)
+    nnz = int(off[-1])
+    raw = rng.integers(0, 1 << 64, size=nnz, dtype=np.uint64)
+    w = [H.dev(t) for t in tables]
+    ts = emb.TableSet(w, D, dtype, salts=salts, device=torch.device(H.DEV))
+    out = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    rows_out = torch.full((nnz,), -9, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_hashed(ts, H.dev(raw), H.dev(off), B, "mean", out, rows_out, status)
+    torch.cuda.synchronize()
+    rows = np.concatenate([oracle.hash_ids(raw[off[t * B]:off[(t + 1) * B]], salts[t], Rs[t]) for t in range(T)])
+    assert status.item() == 0 and np.array_equal(rows_out.cpu().numpy(), rows)       # bit-exact rows
+    ref, absum, _ = oracle.bag_forward(tables, dtype, rows, off, B, "mean")
+    H.assert_pooled_close(out.cpu().numpy(), ref, absum, eps=H.EPS32, what="hashed forward")
+    two_step, _ = H.gpu_forward(ts, rows, off, B, "mean")
+    assert np.array_equal(two_step.reshape(T, B, D), out.cpu().numpy())              # same bits as the two calls
+    # without the row output
+    out2 = torch.empty_like(out)
+    emb.emb_bag_forward_hashed(ts, H.dev(raw), H.dev(off), B, "mean", out2, None, status)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+
+
 def test_forward_empty_batch_zero_fills():
     table = np.ones((10, 16), dtype=np.float32)
     ts, _, _ = H.make_tableset([table], "f32")
