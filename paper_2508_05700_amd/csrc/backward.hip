@@ -103,11 +103,13 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
 // init + key build
 // ---------------------------------------------------------------------------
 // One workgroup: clears the control block, checks that the tables' record ranges
-// [offsets[t*B], offsets[(t+1)*B]) partition [0, nnz) in order and numbers the
-// tiles of the sort (first_tile[t] = tiles of the tables before t; T + 1 entries).
+// [offsets[t*B], offsets[(t+1)*B]) partition [0, nnz) in order, numbers the
+// tiles of the sort (first_tile[t] = tiles of the tables before t; T + 1 entries)
+// and writes their descriptors.
 // T == 0 is passed when there are no records and the offsets are not to be read.
 __global__ __launch_bounds__(1024) void bwd_init_kernel(BwdCtrl *ctrl, const int64_t *__restrict__ offsets, int32_t T,
                                                          int64_t B, int64_t nnz, uint32_t *__restrict__ first_tile,
+                                                         SortTile *__restrict__ desc, uint32_t tiles,
                                                          int64_t *num_unique_out, uint32_t *status)
 {
     __shared__ uint32_t wave_sums[1024 / EMB_WAVE];
@@ -137,39 +139,34 @@ __global__ __launch_bounds__(1024) void bwd_init_kernel(BwdCtrl *ctrl, const int
         if (bad) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
         if (num_unique_out) *num_unique_out = 0;
     }
+    if (bad) return;          // uniform; the record ranges are not to be trusted and nothing will read the tiles
+    __syncthreads();          // first_tile[] was written by this workgroup: visible to all of it now
+
+    // which table every tile of the sort belongs to and which records it holds
+    for (uint32_t b = (uint32_t)i; b < tiles; b += 1024) {
+        SortTile d = {0, 0, 0, 0, 0, 0, {0, 0}};
+        if (b < carry) {
+            // the table with first_tile[t] <= b < first_tile[t + 1]; tables without records own no tile
+            int32_t lo = 0, hi = T;
+            while (hi - lo > 1) {
+                const int32_t mid = lo + (hi - lo) / 2;
+                if (first_tile[mid] <= b) lo = mid;
+                else hi = mid;
+            }
+            const int64_t s = offsets[(int64_t)lo * B], e = offsets[(int64_t)(lo + 1) * B];
+            const int64_t start = s + (int64_t)(b - first_tile[lo]) * SORT_TILE;
+            const int64_t left = e - start;
+            d.start = (uint32_t)start;
+            d.count = (uint32_t)(left < SORT_TILE ? left : SORT_TILE);
+            d.first = first_tile[lo];
+            d.next = first_tile[lo + 1];
+            d.seg_start = (uint32_t)s;
+            d.table = (uint32_t)lo;
+        }
+        desc[b] = d;
+    }
 }
 static_assert(offsetof(BwdCtrl, abort) == 0, "bwd_init_kernel writes abort as word 0");
-
-// One thread per tile of the sort: which table it belongs to and which records it holds.
-__global__ __launch_bounds__(256) void sort_tiles_kernel(const int64_t *__restrict__ offsets, int32_t T, int64_t B,
-                                                         const uint32_t *__restrict__ first_tile,
-                                                         SortTile *__restrict__ desc, uint32_t tiles,
-                                                         const BwdCtrl *ctrl)
-{
-    if (ctrl->abort) return;   // the record ranges are not to be trusted
-    const uint32_t b = blockIdx.x * 256 + threadIdx.x;
-    if (b >= tiles) return;
-    SortTile d = {0, 0, 0, 0, 0, 0, {0, 0}};
-    if (b < first_tile[T]) {
-        // the table with first_tile[t] <= b < first_tile[t + 1]; tables without records own no tile
-        int32_t lo = 0, hi = T;
-        while (hi - lo > 1) {
-            const int32_t mid = lo + (hi - lo) / 2;
-            if (first_tile[mid] <= b) lo = mid;
-            else hi = mid;
-        }
-        const int64_t s = offsets[(int64_t)lo * B], e = offsets[(int64_t)(lo + 1) * B];
-        const int64_t start = s + (int64_t)(b - first_tile[lo]) * SORT_TILE;
-        const int64_t left = e - start;
-        d.start = (uint32_t)start;
-        d.count = (uint32_t)(left < SORT_TILE ? left : SORT_TILE);
-        d.first = first_tile[lo];
-        d.next = first_tile[lo + 1];
-        d.seg_start = (uint32_t)s;
-        d.table = (uint32_t)lo;
-    }
-    desc[b] = d;
-}
 
 constexpr int KEY_LANES = 16;  // lanes that share one bag in the key build
 
@@ -448,7 +445,7 @@ int run_sort(const BwdArgs &a, const BwdLayout &L)
 
     EMB_MARK(a, 0);
     hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, s, ctrl, a.offsets, a.nnz > 0 ? a.T : 0, a.B, a.nnz,
-                       first_tile, a.num_unique_out, a.status);
+                       first_tile, tile_desc, a.nnz > 0 ? tiles : 0u, a.num_unique_out, a.status);
     EMB_RETURN_IF_LAUNCH_FAILED();
     if (a.nnz == 0) {
         for (int i = 1; i <= 3; ++i) EMB_MARK(a, i);
@@ -464,9 +461,6 @@ int run_sort(const BwdArgs &a, const BwdLayout &L)
     }
     EMB_MARK(a, 1);
 
-    hipLaunchKernelGGL(sort_tiles_kernel, dim3((tiles + 255) / 256), dim3(256), 0, s, a.offsets, a.T, a.B, first_tile,
-                       tile_desc, tiles, ctrl);
-    EMB_RETURN_IF_LAUNCH_FAILED();
     KeyT *kin = keys_a, *kout = keys_b;
     uint32_t *pin = pay_a, *pout = pay_b;
     for (int p = 0; p < a.passes; ++p) {
