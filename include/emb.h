@@ -242,6 +242,36 @@ int emb_bag_forward_hashed(const emb_table *tables_host, const emb_table *tables
                            float *out_dev, int64_t *rows_out_dev, uint32_t *status_dev,
                            void *stream);
 
+/* Shape of one table for emb_bag_forward_mixed.  The caller fills D, dtype,
+ * out_offset and out_stride; emb_table_shapes_init derives the rest for a batch
+ * of B bags per table; like emb_table, the array is passed in host and in
+ * device memory. */
+typedef struct emb_table_shape {
+    int32_t D;           /* elements per row; D * element size a multiple of 16, at most 1024 bytes */
+    int32_t dtype;       /* EMB_F32 or EMB_BF16                                                    */
+    int64_t out_offset;  /* pooled row b of this table starts at out[out_offset + b * out_stride]  */
+    int64_t out_stride;  /* both in floats, multiples of 4; out_stride >= D                        */
+    uint32_t first_block; /* derived */
+    int32_t lanes;        /* derived */
+} emb_table_shape;
+int emb_table_shapes_init(emb_table_shape *shapes_host, int32_t T, int64_t B);
+
+/* emb_bag_forward for tables whose width and storage type differ (Section 3.1:
+ * several ID features with their own tables), in one launch.  Bags, rows_dev
+ * and offsets_dev are laid out as for emb_bag_forward; table t's pooled row b
+ * is written to out_dev[out_offset_t + b * out_stride_t + 0 .. D_t), which
+ * allows one [B, D_t] block per table as well as one concatenated vector per
+ * sample (out_stride = sum of D, out_offset = the table's column).  Output
+ * floats that no table covers are not written.  out_floats: size of out_dev;
+ * EMB_ERR_INVALID_ARG if a row would fall outside it or the shapes were not
+ * initialised for this B.  EMB_ERR_UNSUPPORTED for rows above 1024 bytes or
+ * quantised tables. */
+int emb_bag_forward_mixed(const emb_table *tables_host, const emb_table *tables_dev,
+                          const emb_table_shape *shapes_host, const emb_table_shape *shapes_dev,
+                          int32_t T, const int64_t *rows_dev, const int64_t *offsets_dev,
+                          int64_t B, int64_t nnz, int32_t mode, float *out_dev, int64_t out_floats,
+                          uint32_t *status_dev, void *stream);
+
 /* ---- row-quantised tables (Section 4.1.2: INT4 tables for serving) ------- */
 
 /* Bytes of one table row: D*4 (EMB_F32), D*2 (EMB_BF16), or for the quantised

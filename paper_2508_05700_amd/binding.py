@@ -29,9 +29,14 @@ TABLE_DESC = np.dtype([("weights", "<u8"), ("accum", "<u8"), ("num_rows", "<i8")
                        ("salt", "<u8"), ("mod_magic", "<u8")])
 assert TABLE_DESC.itemsize == 48
 
+# numpy mirror of ``struct emb_table_shape``
+SHAPE_DESC = np.dtype([("D", "<i4"), ("dtype", "<i4"), ("out_offset", "<i8"), ("out_stride", "<i8"),
+                       ("first_block", "<u4"), ("lanes", "<i4")])
+assert SHAPE_DESC.itemsize == 32
+
 EXPORTS = [
     "emb_status_string", "emb_tables_init", "emb_hash_ids", "emb_hash_ids_tables", "emb_lengths_to_offsets",
-    "emb_bag_forward", "emb_bag_forward_hashed", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
+    "emb_bag_forward", "emb_bag_forward_hashed", "emb_table_shapes_init", "emb_bag_forward_mixed", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
     "emb_bag_backward_sort", "emb_bag_backward_update", "emb_row_bytes", "emb_quantize_rows",
     "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
@@ -78,6 +83,10 @@ def lib() -> C.CDLL:
     L.emb_bag_forward.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp]
     L.emb_bag_forward_hashed.restype = C.c_int
     L.emb_bag_forward_hashed.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    L.emb_table_shapes_init.restype = C.c_int
+    L.emb_table_shapes_init.argtypes = [vp, i32, i64]
+    L.emb_bag_forward_mixed.restype = C.c_int
+    L.emb_bag_forward_mixed.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, i64, i32, vp, i64, vp, vp]
     L.emb_bag_backward_workspace_bytes.restype = sz
     L.emb_bag_backward_workspace_bytes.argtypes = [i32, i64, i64, i64, i32, i32]
     L.emb_bag_backward_rowwise_adagrad.restype = C.c_int
@@ -247,6 +256,54 @@ def emb_bag_forward_hashed(tables: TableSet, raw: torch.Tensor, offsets: torch.T
         tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype], _ptr(raw, _U64, "raw"),
         _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode], _ptr(out, torch.float32, "out"),
         _ptr(rows_out, torch.int64, "rows_out"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+class MixedTables:
+    """Tables of different width / storage type for ``emb_bag_forward_mixed``.
+
+    ``weights[t]`` is a device tensor ``[R_t, D_t]`` (fp32 or bf16).  ``layout``: "table_major" puts
+    table t's pooled rows in a ``[B, D_t]`` block of their own, one block after the other;
+    "concat" gives one row of ``sum(D_t)`` floats per sample with the tables side by side.
+    """
+
+    def __init__(self, weights: Sequence[torch.Tensor], B: int, layout: str = "concat",
+                 salts: Optional[Sequence[int]] = None, device: Optional[torch.device] = None):
+        self.T = len(weights)
+        self.B = int(B)
+        self.weights = list(weights)
+        names = {torch.float32: "f32", torch.bfloat16: "bf16"}
+        self.Ds = [int(w.shape[1]) for w in weights]
+        self.dtypes = [names[w.dtype] for w in weights]
+        self.tables = TableSet([(_ptr(w, None, "weights"), int(w.shape[0])) for w in weights], 0, "f32", salts=salts,
+                               device=device)
+        self.host = np.zeros(self.T, dtype=SHAPE_DESC)
+        total = sum(self.Ds)
+        col = 0
+        for t in range(self.T):
+            self.host["D"][t] = self.Ds[t]
+            self.host["dtype"][t] = DTYPE[self.dtypes[t]]
+            if layout == "concat":
+                self.host["out_offset"][t], self.host["out_stride"][t] = col, total
+            elif layout == "table_major":
+                self.host["out_offset"][t], self.host["out_stride"][t] = col * self.B, self.Ds[t]
+            else:
+                raise ValueError(layout)
+            col += self.Ds[t]
+        self.layout = layout
+        self.out_floats = total * self.B
+        _check("emb_table_shapes_init", lib().emb_table_shapes_init(self.host.ctypes.data, self.T, self.B))
+        dev = self.tables.dev.device
+        self.dev = torch.from_numpy(self.host.view(np.uint8).reshape(-1).copy()).to(dev)
+
+
+def emb_bag_forward_mixed(mt: MixedTables, rows: torch.Tensor, offsets: torch.Tensor, mode: str, out: torch.Tensor,
+                          status: Optional[torch.Tensor] = None) -> None:
+    if offsets.numel() != mt.T * mt.B + 1 or out.numel() < mt.out_floats:
+        raise TypeError("shape mismatch")
+    _check("emb_bag_forward_mixed", lib().emb_bag_forward_mixed(
+        mt.tables.host_ptr, mt.tables.dev_ptr, int(mt.host.ctypes.data), int(mt.dev.data_ptr()), mt.T,
+        _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), mt.B, rows.numel(), POOL[mode],
+        _ptr(out, torch.float32, "out"), out.numel(), _ptr(status, torch.int32, "status"), _stream()))
 
 
 def emb_row_bytes(D: int, dtype: str) -> int:

@@ -118,7 +118,9 @@ __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_kernel(const char
     const int64_t b = (int64_t)blockIdx.x * GROUPS + threadIdx.x / LPR;
     CachedSource src{table,  cache_rows, index, (uint64_t)num_rows, (uint64_t)num_hot, (int64_t)chunks_per_row * 16,
                      status, 0u,         0u};
-    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, b, l, nnz, rows, offsets, chunks_per_row, mode, out, status);
+    constexpr int F = ChunkAcc<BF16>::FLOATS;
+    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, b, l, nnz, rows, offsets, chunks_per_row, mode,
+                                            out + b * ((int64_t)chunks_per_row * F), status);
     if (hit_miss) {
         // every lane of the wavefront is still here: reduce, then one atomic per wavefront
         uint32_t h = src.hits, m = src.misses;

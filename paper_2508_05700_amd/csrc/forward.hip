@@ -66,8 +66,10 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb
     const emb_table tb = tables[t];
     HashedTableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, tb.salt, tb.mod_magic,
                           (int64_t)chunks_per_row * 16, rows_out};
-    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, (int64_t)t * B + b, l, nnz, raw, offsets, chunks_per_row,
-                                            mode, out, status);
+    constexpr int F = ChunkAcc<BF16>::FLOATS;
+    const int64_t bag = (int64_t)t * B + b;
+    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, bag, l, nnz, raw, offsets, chunks_per_row, mode,
+                                            out + bag * ((int64_t)chunks_per_row * F), status);
 }
 
 template <int LPR, int CPL, int UNROLL, bool BF16>
@@ -88,8 +90,10 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table 
     const emb_table tb = tables[t];
     TableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, (int64_t)chunks_per_row * 16,
                     status};
-    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, (int64_t)t * B + b, l, nnz, rows, offsets, chunks_per_row,
-                                            mode, out, status);
+    constexpr int F = ChunkAcc<BF16>::FLOATS;
+    const int64_t bag = (int64_t)t * B + b;
+    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, bag, l, nnz, rows, offsets, chunks_per_row, mode,
+                                            out + bag * ((int64_t)chunks_per_row * F), status);
 }
 
 // rows_out != NULL or hashed: `rows` holds raw IDs and the hashing kernel is launched.

@@ -103,8 +103,9 @@ template <int LPR, int CPL, int UNROLL, bool BF16, typename Source>
 __device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t bag, int l, int64_t nnz,
                                                 const int64_t *__restrict__ rows,
                                                 const int64_t *__restrict__ offsets, int32_t chunks_per_row,
-                                                int32_t mode, float *__restrict__ out, uint32_t *status)
+                                                int32_t mode, float *__restrict__ out_row, uint32_t *status)
 {
+    // `bag` indexes offsets; out_row is where the bag's pooled row goes (not touched unless live)
     constexpr int IPL = (UNROLL > LPR) ? UNROLL / LPR : 1;  // indices fetched per lane per batch
     constexpr int IB = IPL * LPR;                           // indices per batch
     static_assert(IB % UNROLL == 0, "index batch must be whole unroll groups");
@@ -158,7 +159,7 @@ __device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t 
     const bool mean = (mode == EMB_POOL_MEAN) && len > 0;
     const float flen = (float)len;
     constexpr int F = ChunkAcc<BF16>::FLOATS;
-    float *obase = out + bag * ((int64_t)chunks_per_row * F);
+    float *obase = out_row;
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
         const int chunk = l + c * LPR;

@@ -190,6 +190,37 @@ def test_split_backward_and_helper_argument_errors(L):
     assert L.emb_side_stream_create(None) == INVALID and L.emb_side_stream_destroy(None) == INVALID
 
 
+def test_mixed_forward_shapes_and_argument_errors(L):
+    import numpy as np
+    SH = np.dtype([("D", "<i4"), ("dtype", "<i4"), ("out_offset", "<i8"), ("out_stride", "<i8"),
+                   ("first_block", "<u4"), ("lanes", "<i4")])
+    sh = np.zeros(2, dtype=SH)
+    sh["D"], sh["dtype"] = [64, 8], [0, 1]
+    sh["out_offset"], sh["out_stride"] = [0, 64], [72, 72]
+    init = L.emb_table_shapes_init
+    assert init(sh.ctypes.data, 2, 100) == OK
+    assert list(sh["lanes"]) == [16, 1] and list(sh["first_block"]) == [0, 7]     # 100 bags / 16 groups = 7 blocks
+    bad = sh.copy(); bad["D"][1] = 6
+    assert init(bad.ctypes.data, 2, 100) == UNSUPPORTED                              # 12-byte rows
+    bad = sh.copy(); bad["dtype"][0] = 3
+    assert init(bad.ctypes.data, 2, 100) == INVALID                                  # quantised tables: not here
+    bad = sh.copy(); bad["out_stride"][0] = 60
+    assert init(bad.ctypes.data, 2, 100) == INVALID
+    bad = sh.copy(); bad["out_offset"][1] = 66
+    assert init(bad.ctypes.data, 2, 100) == INVALID
+    d = _tables()
+    f = L.emb_bag_forward_mixed
+
+    def args(**k):
+        return [d.ctypes.data, FAKE, k.get("sh", sh.ctypes.data), FAKE, 2, FAKE, FAKE, k.get("B", 100), 8,
+                k.get("mode", 0), k.get("out", FAKE), k.get("floats", 7200), None, None]
+    assert f(*args(floats=7199)) == INVALID                # the last output row would not fit
+    assert f(*args(B=101)) == INVALID                      # shapes were derived for another B
+    assert f(*args(mode=2)) == INVALID
+    assert f(*args(out=None)) == INVALID
+    assert f(*args(B=0)) == OK
+
+
 def test_workspace_bytes(L):
     w = L.emb_bag_backward_workspace_bytes
     assert w(-1, 1, 1, 1, 64, 0) == 0 and w(1, -1, 1, 1, 64, 0) == 0 and w(1, 1, -1, 1, 64, 0) == 0

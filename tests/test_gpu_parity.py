@@ -186,6 +186,47 @@ def test_forward_hashed_equals_hash_then_forward(D, dtype):
     assert torch.equal(out, out2)
 
 
+@pytest.mark.parametrize("layout", ["concat", "table_major"])
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_forward_mixed_widths_and_types_matches_oracle(layout, mode):
+    # eight tables, widths 4 .. 256, fp32 and bf16, in one launch; the oracle pools them one by one
+    rng = np.random.default_rng(1600 + (layout == "concat") + 2 * (mode == "mean"))
+    spec = [(4, "f32", 300), (16, "f32", 5000), (8, "bf16", 77), (64, "f32", 20_000), (256, "f32", 900),
+            (32, "bf16", 3000), (512, "bf16", 64), (48, "f32", 1)]
+    T, B = len(spec), 333
+    tables = []
+    for D, dt, R in spec:
+        v = rng.standard_normal((R, D)).astype(np.float32)
+        tables.append(wl.f32_to_bf16_bits(v).reshape(R, D) if dt == "bf16" else v)
+    lengths = rng.integers(0, 30, size=T * B).astype(np.int32)
+    lengths[rng.random(T * B) < 0.2] = 0
+    off, _ = oracle.lengths_to_offsets(lengths)
+    rows = np.concatenate([rng.integers(0, spec[t][2], size=int(off[(t + 1) * B] - off[t * B])) for t in range(T)])
+    rows = rows.astype(np.int64)
+    rows[[1, 50]] = [-4, 1 << 35]
+    mt = emb.MixedTables([H.dev(t) for t in tables], B, layout, device=torch.device(H.DEV))
+    out = torch.full((mt.out_floats,), float("nan"), dtype=torch.float32, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_mixed(mt, H.dev(rows), H.dev(off), mode, out, status)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()                              # the layout covers every float
+    total = sum(D for D, _, _ in spec)
+    col = 0
+    st_ref = 0
+    for t, (D, dt, R) in enumerate(spec):
+        seg = slice(off[t * B], off[(t + 1) * B])
+        ref, absum, st = oracle.bag_forward([tables[t]], dt, rows[seg], off[t * B:(t + 1) * B + 1] - off[t * B], B, mode)
+        st_ref |= st
+        if layout == "concat":
+            mine = got.reshape(B, total)[:, col:col + D]
+        else:
+            mine = got[col * B:(col + D) * B].reshape(B, D)
+        H.assert_pooled_close(mine, ref[0], absum[0], eps=H.EPS32, what="mixed table %d" % t)
+        col += D
+    assert int(status.item()) == st_ref == emb.STATUS_BAD_INDEX
+
+
 def test_forward_empty_batch_zero_fills():
     table = np.ones((10, 16), dtype=np.float32)
     ts, _, _ = H.make_tableset([table], "f32")
