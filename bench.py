@@ -278,6 +278,81 @@ def bench_hybrid(args) -> int:
     return 0
 
 
+def bench_mixed(args) -> int:
+    """Workload "mix": offsets + hashing + ONE pooled-lookup launch over 24 tables of four widths and
+    two storage types, output concatenated per sample."""
+    import numpy as np
+    import torch
+
+    from paper_2508_05700_amd import binding as emb
+    from paper_2508_05700_amd import pipeline, workloads as wl
+
+    seed = wl.DEFAULT_SEED if args.seed is None else args.seed
+    w = wl.WORKLOADS["mix"]
+    spec = wl.MIX_SPEC
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, W = args.steps, args.warmup
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}
+    weights = []
+    for t, (D, dt, R) in enumerate(spec):
+        wt = torch.empty((R, D), dtype=tdt[dt], device=dev)
+        emb.emb_table_fill(wt, R, D, dt, w.table_seed(t, seed))
+        weights.append(wt)
+    mt = emb.MixedTables(weights, w.B, "concat", salts=[w.salt(t) for t in range(w.T)], device=dev)
+    dbs = [pipeline.DeviceBatch(w, wl.make_batch(w, i, seed), dev) for i in range(args.batches)]
+    max_nnz = max(d.nnz for d in dbs)
+    offsets = torch.empty(w.T * w.B + 1, dtype=torch.int64, device=dev)
+    rows = torch.empty(max_nnz, dtype=torch.int64, device=dev)
+    out = torch.empty(mt.out_floats, dtype=torch.float32, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    torch.cuda.synchronize()
+
+    def step(db, e=None):
+        emb.emb_lengths_to_offsets(db.lengths, offsets, status)
+        r = rows[:db.nnz]
+        emb.emb_hash_ids_tables(mt.tables, db.raw, offsets, w.B, r, status)
+        if e:
+            e[0].record()
+        emb.emb_bag_forward_mixed(mt, r, offsets, w.pool, out, status)
+        if e:
+            e[1].record()
+
+    for i in range(W):
+        step(dbs[i % len(dbs)])
+    torch.cuda.synchronize()
+    ev = [[emb.Event(timing=True) for _ in range(2)] for _ in range(K)]
+    t0 = time.perf_counter()
+    for k in range(K):
+        step(dbs[(W + k) % len(dbs)], ev[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert int(status.item()) == 0
+    lookups = sum(dbs[(W + k) % len(dbs)].nnz for k in range(K))
+    ms_fwd = sum(e[0].elapsed_time(e[1]) for e in ev) / K
+    # algorithmic bytes of the lookup: per lookup its table's row + 8 B index; per bag its output row + 8 B offset
+    per_table = np.mean([b_["nnz_per_table"] for b_ in [wl.make_batch(w, i, seed) for i in range(1)]], axis=0)
+    nbytes = sum(per_table[t] * (emb.emb_row_bytes(D, dt) + 8) + w.B * (4 * D + 8) for t, (D, dt, R) in enumerate(spec))
+    gbs = nbytes / (ms_fwd * 1e-3) / 1e9
+    log("step %.3f ms: mixed forward %.3f ms, %.0f GB/s algorithmic (%.1f %% of HBM peak)" % (
+        elapsed / K * 1e3, ms_fwd, gbs, 100 * gbs / HBM_PEAK_GBS))
+    print(json.dumps({
+        "metric": METRIC, "value": round(lookups / elapsed, 1), "unit": "lookups/s", "n_gpus": 1, "steps": K,
+        "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "mix: 24 tables (6 x dim 16 fp32 x 2e6 rows, 6 x dim 32 bf16 x 5e6, 8 x dim 64 fp32 x 1e7, "
+                               "4 x dim 128 fp32 x 2e6), %d bags/table, poisson bag lengths (mean %g), zipf IDs "
+                               "alpha=%g, %s pooling, one launch, output concatenated per sample, forward only" % (
+                                   w.B, w.mean_len, w.alpha, w.pool),
+                   "lookups_per_step": round(lookups / K, 1), "resident_batches": len(dbs), "seed": seed},
+        "roofline": {"kernel": "bag_forward_mixed_kernel", "bound": "hbm", "achieved": round(gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_ms": round(ms_fwd, 4), "algorithmic_bytes": int(nbytes),
+                     "bytes_are": "row + 8 B index per lookup, fp32 output row + 8 B offset per bag"},
+        "cpu_baseline": None}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -319,6 +394,8 @@ def main() -> int:
     emb.lib()
     if wl.WORKLOADS[args.workload].hybrid:
         return bench_hybrid(args)
+    if args.workload == "mix":
+        return bench_mixed(args)
     seed = wl.DEFAULT_SEED if args.seed is None else args.seed
     w = wl.WORKLOADS[args.workload]
     if args.scale_rows:

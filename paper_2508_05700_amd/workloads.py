@@ -268,6 +268,13 @@ WORKLOADS: Dict[str, Workload] = {
 }
 
 
+# "mix": config 2's batch recipe over 24 tables of different width and storage type (D, dtype, rows):
+# the kind of table set a ranking model with several ID features has.
+MIX_SPEC = ([(16, "f32", 2_000_000)] * 6 + [(32, "bf16", 5_000_000)] * 6 + [(64, "f32", 10_000_000)] * 8 +
+            [(128, "f32", 2_000_000)] * 4)
+WORKLOADS["mix"] = dataclasses.replace(WORKLOADS["2"], name="mix", T=len(MIX_SPEC), D=0, R=0)
+
+
 def _rng(seed: int, *key: int) -> np.random.Generator:
     return np.random.Generator(np.random.PCG64(np.random.SeedSequence([int(seed), *[int(k) for k in key]])))
 
