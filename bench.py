@@ -40,13 +40,13 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "508b4bb58791d0a2",
+    "sources": "d0b10cf0bd6c197f",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_kernel": (178017.7, 32768.0), "update_kernel": (240621.6, 323999.4)},
-        "2u": {"bag_forward_kernel": (346115.2, 32768.0)},
-        "2uq4": {"bag_forward_quant_kernel": (233551.6, 32883.4)},
+        "3": {"bag_forward_hashed_kernel": (178841.3, 61245.8), "update_kernel": (240603.8, 324001.0)},
+        "2u": {"bag_forward_kernel": (346116.7, 32768.0)},
+        "2uq4": {"bag_forward_quant_kernel": (233567.1, 32886.9)},
     },
 }
 
