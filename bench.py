@@ -435,7 +435,7 @@ def main() -> int:
         if fused:
             rows = buf.rows[:db.nnz]
             emb.emb_bag_forward_hashed(tabs.set, db.raw, buf.offsets, w.B, w.pool, buf.out,
-                                       rows if w.backward else None, buf.status)
+                                       rows if w.backward else None, buf.status, streaming=w.streaming)
             return rows
         pipeline.run_forward(w, tabs.set, rows, buf)
         return rows
@@ -581,7 +581,7 @@ def main() -> int:
     extra = {}
     if not args.no_extra and args.workload == "3" and not args.scale_rows:
         qkeep, qset = None, None
-        for name in ("2", "2u", "2q4", "2uq4"):
+        for name in ("2", "2un", "2u", "2q4", "2uq4"):
             wf = wl.WORKLOADS[name]
             tset = tabs.set
             if wf.quant:
@@ -651,7 +651,8 @@ def main() -> int:
                              w.dtype if not w.quant else "(fp32 quantised row-wise to %s, %d B per row)" % (w.quant, rowb),
                              w.B, w.length, w.mean_len, w.ids,
                              (" alpha=%g over %.0e keys" % (w.alpha, w.n_keys)) if w.ids == "zipf" else "", w.pool,
-                             "forward + sparse row-wise Adagrad backward" if w.backward else "forward only")),
+                             ("forward + sparse row-wise Adagrad backward" if w.backward else "forward only") +
+                             (", rows read with the streaming hint" if w.streaming else ""))),
             "lookups_per_step": round(nnz_avg, 1),
             "resident_batches": len(dbs),
             "seed": seed,

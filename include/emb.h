@@ -55,6 +55,14 @@ typedef enum {
 } emb_status;
 
 typedef enum { EMB_POOL_SUM = 0, EMB_POOL_MEAN = 1 } emb_pool;
+/* May be OR-ed into the `mode` of emb_bag_forward and emb_bag_forward_hashed:
+ * a hint that the rows of this batch are unlikely to be looked up again soon
+ * (IDs without popular heads).  Rows are then read with streaming loads that
+ * do not displace other data in the caches: measured +10 % on uniformly
+ * distributed IDs, -19 % on Zipf(1.05) IDs, whose popular rows are otherwise
+ * served from cache.  Results are bit-identical with and without it; quantised
+ * tables ignore it. */
+#define EMB_ROWS_STREAMING 0x100
 /* Storage type of table rows.  EMB_INT8 / EMB_INT4 are row-quantised tables
  * (see emb_quantize_rows); only the forward lookup reads those. */
 typedef enum { EMB_F32 = 0, EMB_BF16 = 1, EMB_INT8 = 2, EMB_INT4 = 3 } emb_dtype;

@@ -19,6 +19,7 @@ from . import build as _build
 
 POOL = {"sum": 0, "mean": 1}
 DTYPE = {"f32": 0, "bf16": 1, "int8": 2, "int4": 3}
+ROWS_STREAMING = 0x100   # hint bit for the forward lookups (EMB_ROWS_STREAMING)
 STATUS_BAD_INDEX = 1
 STATUS_BAD_OFFSETS = 2
 STATUS_BAD_HOT_SET = 4
@@ -234,18 +235,20 @@ def emb_lengths_to_offsets(lengths: torch.Tensor, offsets: torch.Tensor, status:
 
 
 def emb_bag_forward(tables: TableSet, rows: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
-                    out: torch.Tensor, status: Optional[torch.Tensor] = None) -> None:
+                    out: torch.Tensor, status: Optional[torch.Tensor] = None, streaming: bool = False) -> None:
+    """``streaming``: the EMB_ROWS_STREAMING hint (rows of this batch are unlikely to be reused)."""
     if offsets.numel() != tables.T * B + 1 or out.numel() != tables.T * B * tables.D:
         raise TypeError("shape mismatch")
     _check("emb_bag_forward", lib().emb_bag_forward(
         tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype],
-        _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), rows.numel(), POOL[mode],
+        _ptr(rows, torch.int64, "rows"), _ptr(offsets, torch.int64, "offsets"), int(B), rows.numel(),
+        POOL[mode] | (ROWS_STREAMING if streaming else 0),
         _ptr(out, torch.float32, "out"), _ptr(status, torch.int32, "status"), _stream()))
 
 
 def emb_bag_forward_hashed(tables: TableSet, raw: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
                            out: torch.Tensor, rows_out: Optional[torch.Tensor] = None,
-                           status: Optional[torch.Tensor] = None) -> None:
+                           status: Optional[torch.Tensor] = None, streaming: bool = False) -> None:
     """Hashing and pooled lookup in one pass; ``rows_out`` (int64 [nnz]) receives the row numbers."""
     nnz = raw.numel()
     if offsets.numel() != tables.T * B + 1 or out.numel() != tables.T * B * tables.D:
@@ -254,8 +257,9 @@ def emb_bag_forward_hashed(tables: TableSet, raw: torch.Tensor, offsets: torch.T
         raise TypeError("rows_out must have as many elements as raw")
     _check("emb_bag_forward_hashed", lib().emb_bag_forward_hashed(
         tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype], _ptr(raw, _U64, "raw"),
-        _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode], _ptr(out, torch.float32, "out"),
-        _ptr(rows_out, torch.int64, "rows_out"), _ptr(status, torch.int32, "status"), _stream()))
+        _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode] | (ROWS_STREAMING if streaming else 0),
+        _ptr(out, torch.float32, "out"), _ptr(rows_out, torch.int64, "rows_out"), _ptr(status, torch.int32, "status"),
+        _stream()))
 
 
 class MixedTables:

@@ -47,7 +47,7 @@ struct HashedTableSource {
     }
 };
 
-template <int LPR, int CPL, int UNROLL, bool BF16>
+template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM>
 __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb_table *__restrict__ tables, int32_t T,
                                                                        int64_t B, uint32_t blocks_per_table,
                                                                        int64_t nnz, const int64_t *__restrict__ raw,
@@ -68,11 +68,11 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb
                           (int64_t)chunks_per_row * 16, rows_out};
     constexpr int F = ChunkAcc<BF16>::FLOATS;
     const int64_t bag = (int64_t)t * B + b;
-    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, bag, l, nnz, raw, offsets, chunks_per_row, mode,
+    gather_pool_bag<LPR, CPL, UNROLL, BF16, STREAM>(src, b < B, bag, l, nnz, raw, offsets, chunks_per_row, mode,
                                             out + bag * ((int64_t)chunks_per_row * F), status);
 }
 
-template <int LPR, int CPL, int UNROLL, bool BF16>
+template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM>
 __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table *__restrict__ tables, int32_t T, int64_t B,
                                                                 uint32_t blocks_per_table, int64_t nnz,
                                                                 const int64_t *__restrict__ rows,
@@ -92,37 +92,43 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table 
                     status};
     constexpr int F = ChunkAcc<BF16>::FLOATS;
     const int64_t bag = (int64_t)t * B + b;
-    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, bag, l, nnz, rows, offsets, chunks_per_row, mode,
+    gather_pool_bag<LPR, CPL, UNROLL, BF16, STREAM>(src, b < B, bag, l, nnz, rows, offsets, chunks_per_row, mode,
                                             out + bag * ((int64_t)chunks_per_row * F), status);
 }
 
-// rows_out != NULL or hashed: `rows` holds raw IDs and the hashing kernel is launched.
+template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM>
+void launch_forward_variant(dim3 grid, hipStream_t s, const emb_table *tables, int32_t T, int64_t B, uint32_t per_table,
+                            int64_t nnz, const int64_t *rows, const int64_t *offsets, int32_t chunks, int32_t mode,
+                            float *out, uint32_t *status, bool hashed, int64_t *rows_out)
+{
+    if (hashed)
+        hipLaunchKernelGGL((bag_forward_hashed_kernel<LPR, CPL, UNROLL, BF16, STREAM>), grid, dim3(FWD_BLOCK), 0, s,
+                           tables, T, B, per_table, nnz, rows, offsets, chunks, mode, out, rows_out, status);
+    else
+        hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, BF16, STREAM>), grid, dim3(FWD_BLOCK), 0, s, tables, T,
+                           B, per_table, nnz, rows, offsets, chunks, mode, out, status);
+}
+
+// hashed: `rows` holds raw IDs and the hashing kernel is launched; stream: non-temporal row reads.
 template <int LPR, int CPL, int UNROLL>
 int launch_forward(bool bf16, int32_t T, hipStream_t s, const emb_table *tables, int64_t B, int64_t nnz,
                    const int64_t *rows, const int64_t *offsets, int32_t chunks, int32_t mode, float *out,
-                   uint32_t *status, bool hashed = false, int64_t *rows_out = nullptr)
+                   uint32_t *status, bool hashed, int64_t *rows_out, bool stream)
 {
     constexpr int GROUPS = FWD_BLOCK / LPR;
     const int64_t per_table = (B + GROUPS - 1) / GROUPS;
     const int64_t blocks = emb_round_up_xcds(per_table * T);
     if (blocks > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
     const dim3 grid((unsigned)blocks);
-    if (hashed) {
-        if (bf16)
-            hipLaunchKernelGGL((bag_forward_hashed_kernel<LPR, CPL, UNROLL, true>), grid, dim3(FWD_BLOCK), 0, s, tables,
-                               T, B, (uint32_t)per_table, nnz, rows, offsets, chunks, mode, out, rows_out, status);
-        else
-            hipLaunchKernelGGL((bag_forward_hashed_kernel<LPR, CPL, UNROLL, false>), grid, dim3(FWD_BLOCK), 0, s, tables,
-                               T, B, (uint32_t)per_table, nnz, rows, offsets, chunks, mode, out, rows_out, status);
-        EMB_RETURN_IF_LAUNCH_FAILED();
-        return EMB_OK;
+#define EMB_FV(BF, ST)                                                                                              \
+    launch_forward_variant<LPR, CPL, UNROLL, BF, ST>(grid, s, tables, T, B, (uint32_t)per_table, nnz, rows, offsets, \
+                                                     chunks, mode, out, status, hashed, rows_out)
+    if (bf16) {
+        if (stream) EMB_FV(true, true); else EMB_FV(true, false);
+    } else {
+        if (stream) EMB_FV(false, true); else EMB_FV(false, false);
     }
-    if (bf16)
-        hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, true>), grid, dim3(FWD_BLOCK), 0, s, tables, T, B,
-                           (uint32_t)per_table, nnz, rows, offsets, chunks, mode, out, status);
-    else
-        hipLaunchKernelGGL((bag_forward_kernel<LPR, CPL, UNROLL, false>), grid, dim3(FWD_BLOCK), 0, s, tables, T, B,
-                           (uint32_t)per_table, nnz, rows, offsets, chunks, mode, out, status);
+#undef EMB_FV
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -135,6 +141,8 @@ static int forward_entry(const emb_table *tables_host, const emb_table *tables_d
                          int64_t *rows_out_dev)
 {
     if (B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
+    const bool streaming = (mode & EMB_ROWS_STREAMING) != 0;
+    mode &= ~EMB_ROWS_STREAMING;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
     const bool quant = dtype == EMB_INT8 || dtype == EMB_INT4;
     int rc = quant ? emb_check_quant_shape(D, dtype) : emb_check_row_shape(D, dtype);
@@ -159,7 +167,7 @@ static int forward_entry(const emb_table *tables_host, const emb_table *tables_d
     hipStream_t s = emb_stream(stream);
 #define EMB_FWD(L, C, U) \
     return launch_forward<L, C, U>(bf16, T, s, tables_dev, B, nnz, rows_dev, offsets_dev, chunks, mode, out_dev, \
-                                   status_dev, hashed, rows_out_dev)
+                                   status_dev, hashed, rows_out_dev, streaming)
     if (cpl == 1) {
         switch (lpr) {
             case 1: EMB_FWD(1, 1, 8);

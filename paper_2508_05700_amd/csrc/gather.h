@@ -99,7 +99,8 @@ static inline void emb_row_split(int chunks, int &lpr, int &cpl)
 //   __device__ uint64_t resolve(int64_t v, int64_t j)   address of the row that entry j of
 //                                                       `rows` (value v) selects, 0 = skip it
 // ---------------------------------------------------------------------------
-template <int LPR, int CPL, int UNROLL, bool BF16, typename Source>
+// STREAM: the rows are read with non-temporal loads (see EMB_ROWS_STREAMING in the header).
+template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM = false, typename Source>
 __device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t bag, int l, int64_t nnz,
                                                 const int64_t *__restrict__ rows,
                                                 const int64_t *__restrict__ offsets, int32_t chunks_per_row,
@@ -143,7 +144,8 @@ __device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t 
                     for (int c = 0; c < CPL; ++c) {
                         v[i][c] = make_uint4(0, 0, 0, 0);
                         if (p != 0 && l + c * LPR < chunks_per_row)
-                            v[i][c] = load_chunk(reinterpret_cast<const char *>(p) + (int64_t)(l + c * LPR) * 16);
+                            v[i][c] = STREAM ? load_chunk_nt(reinterpret_cast<const char *>(p) + (int64_t)(l + c * LPR) * 16)
+                                             : load_chunk(reinterpret_cast<const char *>(p) + (int64_t)(l + c * LPR) * 16);
                     }
                 }
 #pragma unroll

@@ -116,12 +116,12 @@ def run_index_and_forward_fused(w: Workload, tables: emb.TableSet, db: DeviceBat
     emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
     rows = buf.rows[:db.nnz]
     emb.emb_bag_forward_hashed(tables, db.raw, buf.offsets, w.B, w.pool, buf.out, rows if w.backward else None,
-                               buf.status)
+                               buf.status, streaming=w.streaming)
     return rows
 
 
 def run_forward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, buf: StepBuffers) -> None:
-    emb.emb_bag_forward(tables, rows, buf.offsets, w.B, w.pool, buf.out, buf.status)
+    emb.emb_bag_forward(tables, rows, buf.offsets, w.B, w.pool, buf.out, buf.status, streaming=w.streaming)
 
 
 def run_backward(w: Workload, tables: emb.TableSet, rows: torch.Tensor, db: DeviceBatch, buf: StepBuffers,

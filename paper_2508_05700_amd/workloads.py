@@ -205,6 +205,7 @@ class Workload:
     lr: float = 0.01
     eps: float = 1e-8
     quant: Optional[str] = None   # "int8" | "int4": the fp32 tables are stored row-quantised (forward only)
+    streaming: bool = False       # the lookups pass the "rows are not reused" hint (IDs without popular heads)
 
     def scaled(self, rows: Optional[int] = None, bags: Optional[int] = None,
                tables: Optional[int] = None, n_keys: Optional[int] = None) -> "Workload":
@@ -243,7 +244,10 @@ WORKLOADS: Dict[str, Workload] = {
                   max_len=100, ids="zipf", alpha=1.05, n_keys=10 ** 9, pool="mean"),
     # 2u: config 2's shapes with uniformly distributed raw IDs (no reuse: every row read is an HBM read)
     "2u": Workload("2u", T=16, R=10_000_000, D=64, dtype="f32", B=8192, length="poisson", mean_len=20,
-                   max_len=100, ids="raw_uniform", pool="mean"),
+                   max_len=100, ids="raw_uniform", pool="mean", streaming=True),
+    # 2un: the same without the hint (rows read with ordinary cached loads)
+    "2un": Workload("2un", T=16, R=10_000_000, D=64, dtype="f32", B=8192, length="poisson", mean_len=20,
+                    max_len=100, ids="raw_uniform", pool="mean"),
     # 3: config 2 plus the sparse row-wise Adagrad backward
     "3": Workload("3", T=16, R=10_000_000, D=64, dtype="f32", B=8192, length="poisson", mean_len=20,
                   max_len=100, ids="zipf", alpha=1.05, n_keys=10 ** 9, pool="mean", backward=True),

@@ -145,6 +145,11 @@ def test_quantized_row_size_and_argument_errors(L):
     assert q(FAKE, 10, 64, 3, FAKE + 8, None) == INVALID        # 16-byte alignment
     assert q(FAKE, -1, 64, 3, FAKE, None) == INVALID
     assert q(FAKE, 0, 64, 3, FAKE, None) == OK                  # nothing to do
+    # the streaming hint is the only extra bit a mode may carry
+    dm = _tables()
+    assert L.emb_bag_forward(dm.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0x200, FAKE, None, None) == INVALID
+    assert L.emb_bag_forward(dm.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 0, 8, 0x100 | 1, FAKE, None, None) == OK
+    # (no bags: the mode with the hint bit passes validation and nothing is launched)
     # hashing fused into the forward: fp32 / bf16 tables only
     d0 = _tables()
     fh = L.emb_bag_forward_hashed

@@ -227,6 +227,29 @@ def test_forward_mixed_widths_and_types_matches_oracle(layout, mode):
     assert int(status.item()) == st_ref == emb.STATUS_BAD_INDEX
 
 
+@pytest.mark.parametrize("D,dtype", [(64, "f32"), (16, "bf16"), (1024, "f32")])
+def test_forward_streaming_hint_changes_no_bit(D, dtype):
+    rng = np.random.default_rng(1700 + D)
+    T, B = 2, 300
+    Rs = [4000, 90]
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, 20, dtype)
+    ts = emb.TableSet([H.dev(t) for t in tables], D, dtype, device=torch.device(H.DEV))
+    plain, st = H.gpu_forward(ts, rows, off, B, "mean")
+    out = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward(ts, H.dev(rows), H.dev(off), B, "mean", out, status, streaming=True)
+    raw = rng.integers(0, 1 << 64, size=rows.size, dtype=np.uint64)
+    h1 = torch.empty_like(out)
+    h2 = torch.empty_like(out)
+    emb.emb_bag_forward_hashed(ts, H.dev(raw), H.dev(off), B, "sum", h1, None, status)
+    emb.emb_bag_forward_hashed(ts, H.dev(raw), H.dev(off), B, "sum", h2, None, status, streaming=True)
+    torch.cuda.synchronize()
+    assert st == 0 and status.item() == 0
+    assert np.array_equal(out.cpu().numpy().reshape(plain.shape), plain) and torch.equal(h1, h2)
+    ref, absum, _ = oracle.bag_forward(tables, dtype, rows, off, B, "mean")
+    H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="streaming forward")
+
+
 def test_forward_empty_batch_zero_fills():
     table = np.ones((10, 16), dtype=np.float32)
     ts, _, _ = H.make_tableset([table], "f32")
