@@ -40,13 +40,14 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "d0b10cf0bd6c197f",
+    "sources": "145d6d35cb3d77e2",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_hashed_kernel": (178841.3, 61245.8), "update_kernel": (240603.8, 324001.0)},
-        "2u": {"bag_forward_kernel": (346116.7, 32768.0)},
-        "2uq4": {"bag_forward_quant_kernel": (233567.1, 32886.9)},
+        "3": {"bag_forward_hashed_kernel": (178839.5, 61283.4), "update_kernel": (240555.0, 324000.1)},
+        "2u": {"bag_forward_kernel": (338142.3, 32768.0)},
+        "2un": {"bag_forward_kernel": (346113.0, 32768.0)},
+        "2uq4": {"bag_forward_quant_kernel": (233521.8, 32889.2)},
     },
 }
 
