@@ -213,11 +213,17 @@ def bench_hybrid(args) -> int:
         if e:
             e[0].record()
         emb.emb_lengths_to_offsets(db.lengths, offsets, status)
-        r = rows[:db.nnz]
-        emb.emb_hash_ids(db.raw, w.salt(0), w.R, r)
+        if args.no_fused_forward:
+            r = rows[:db.nnz]
+            emb.emb_hash_ids(db.raw, w.salt(0), w.R, r)
         if e:
             e[1].record()
-        emb.emb_bag_forward_cached(ptr, w.R, w.D, store, cache, index, n_hot, r, offsets, w.B, w.pool, out, hm, status)
+        if args.no_fused_forward:
+            emb.emb_bag_forward_cached(ptr, w.R, w.D, store, cache, index, n_hot, r, offsets, w.B, w.pool, out, hm,
+                                       status)
+        else:    # hashing inside the lookup
+            emb.emb_bag_forward_cached_hashed(ptr, w.R, w.D, store, cache, index, n_hot, w.salt(0), db.raw, offsets,
+                                              w.B, w.pool, out, hm, status)
         if e:
             e[2].record()
 

@@ -333,6 +333,16 @@ int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, int32_t D, i
                            int64_t B, int64_t nnz, int32_t mode, float *out_dev,
                            uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream);
 
+/* emb_hash_ids and emb_bag_forward_cached in one pass: raw_dev (u64[nnz]) holds
+ * raw IDs, hashed with `salt` and num_rows as they are fetched (Section 2.2).
+ * Output and hit/miss counts equal those of the two calls in a row. */
+int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                                  const void *cache_rows_dev, const void *cache_index_dev,
+                                  int64_t num_hot, uint64_t salt, const uint64_t *raw_dev,
+                                  const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
+                                  float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
+                                  void *stream);
+
 /* Device-visible address of page-locked host memory that is mapped into the
  * device address space (hipHostMalloc / a pinned torch tensor): the pointer to
  * pass as table_dev above.  EMB_ERR_HIP if the memory is not mapped; nothing is

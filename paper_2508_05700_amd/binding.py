@@ -41,7 +41,7 @@ EXPORTS = [
     "emb_bag_backward_sort", "emb_bag_backward_update", "emb_row_bytes", "emb_quantize_rows",
     "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
-    "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_host_device_pointer",
+    "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_host_device_pointer",
     "emb_table_fill",
 ]
 
@@ -119,6 +119,9 @@ def lib() -> C.CDLL:
     L.emb_cache_build.argtypes = [vp, i64, i32, i32, vp, i64, vp, vp, vp, vp]
     L.emb_bag_forward_cached.restype = C.c_int
     L.emb_bag_forward_cached.argtypes = [vp, i64, i32, i32, vp, vp, i64, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    L.emb_bag_forward_cached_hashed.restype = C.c_int
+    L.emb_bag_forward_cached_hashed.argtypes = [vp, i64, i32, i32, vp, vp, i64, u64, vp, vp, i64, i64, i32, vp, vp, vp,
+                                                vp]
     L.emb_host_device_pointer.restype = C.c_int
     L.emb_host_device_pointer.argtypes = [vp, C.POINTER(vp)]
     L.emb_table_fill.restype = C.c_int
@@ -476,6 +479,21 @@ def emb_bag_forward_cached(table_ptr: int, num_rows: int, D: int, dtype: str, ca
         _ptr(cache_index, torch.uint8, "cache_index"), int(num_hot), _ptr(rows, torch.int64, "rows"),
         _ptr(offsets, torch.int64, "offsets"), int(B), rows.numel(), POOL[mode], _ptr(out, torch.float32, "out"),
         _ptr(hit_miss, _U64, "hit_miss"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_bag_forward_cached_hashed(table_ptr: int, num_rows: int, D: int, dtype: str, cache_rows: torch.Tensor,
+                                  cache_index: torch.Tensor, num_hot: int, salt: int, raw: torch.Tensor,
+                                  offsets: torch.Tensor, B: int, mode: str, out: torch.Tensor,
+                                  hit_miss: Optional[torch.Tensor] = None,
+                                  status: Optional[torch.Tensor] = None) -> None:
+    if offsets.numel() != B + 1 or out.numel() != B * D:
+        raise TypeError("shape mismatch")
+    _check("emb_bag_forward_cached_hashed", lib().emb_bag_forward_cached_hashed(
+        int(table_ptr), int(num_rows), int(D), DTYPE[dtype], _ptr(cache_rows, _TABLE_TORCH[dtype], "cache_rows"),
+        _ptr(cache_index, torch.uint8, "cache_index"), int(num_hot), C.c_uint64(int(salt) % (1 << 64)),
+        _ptr(raw, _U64, "raw"), _ptr(offsets, torch.int64, "offsets"), int(B), raw.numel(), POOL[mode],
+        _ptr(out, torch.float32, "out"), _ptr(hit_miss, _U64, "hit_miss"), _ptr(status, torch.int32, "status"),
+        _stream()))
 
 
 def emb_host_device_pointer(host_ptr: int) -> int:

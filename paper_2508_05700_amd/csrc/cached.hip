@@ -16,6 +16,7 @@
 #include "emb_internal.h"
 #include "gather.h"
 #include "gather_quant.h"
+#include "u64mod.h"
 
 namespace {
 
@@ -79,8 +80,12 @@ struct CachedSource {
     int64_t row_bytes;
     uint32_t *status;
     uint32_t hits, misses;
+    // hashed: the entries are raw IDs, the row is splitmix64(raw XOR salt) mod num_rows (Section 2.2)
+    bool hashed;
+    uint64_t salt, magic;
     __device__ __forceinline__ uint64_t resolve(int64_t r, int64_t)
     {
+        if (hashed) r = (int64_t)emb_fast_mod(emb_splitmix64((uint64_t)r ^ salt), num_rows, magic);
         if ((uint64_t)r >= num_rows) {
             emb_flag(status, EMB_STATUS_BAD_INDEX);
             return 0ull;
@@ -111,13 +116,14 @@ __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_kernel(const char
                                                                       const int64_t *__restrict__ offsets,
                                                                       int32_t chunks_per_row, int32_t mode,
                                                                       float *__restrict__ out,
-                                                                      unsigned long long *hit_miss, uint32_t *status)
+                                                                      unsigned long long *hit_miss, uint32_t *status,
+                                                                      bool hashed, uint64_t salt, uint64_t magic)
 {
     constexpr int GROUPS = CF_BLOCK / LPR;
     const int l = threadIdx.x % LPR;
     const int64_t b = (int64_t)blockIdx.x * GROUPS + threadIdx.x / LPR;
     CachedSource src{table,  cache_rows, index, (uint64_t)num_rows, (uint64_t)num_hot, (int64_t)chunks_per_row * 16,
-                     status, 0u,         0u};
+                     status, 0u,         0u,    hashed,             salt,              magic};
     constexpr int F = ChunkAcc<BF16>::FLOATS;
     gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, b, l, nnz, rows, offsets, chunks_per_row, mode,
                                             out + b * ((int64_t)chunks_per_row * F), status);
@@ -139,16 +145,19 @@ __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_kernel(const char
 template <int LPR, int CPL, int UNROLL>
 int launch_cached(bool bf16, hipStream_t s, const char *table, const char *cache_rows, const CacheEntry *index,
                   int64_t num_rows, int64_t num_hot, int64_t B, int64_t nnz, const int64_t *rows,
-                  const int64_t *offsets, int32_t chunks, int32_t mode, float *out, unsigned long long *hit_miss, uint32_t *status)
+                  const int64_t *offsets, int32_t chunks, int32_t mode, float *out, unsigned long long *hit_miss,
+                  uint32_t *status, bool hashed, uint64_t salt, uint64_t magic)
 {
     constexpr int GROUPS = CF_BLOCK / LPR;
     dim3 grid((unsigned)((B + GROUPS - 1) / GROUPS));
     if (bf16)
         hipLaunchKernelGGL((bag_forward_cached_kernel<LPR, CPL, UNROLL, true>), grid, dim3(CF_BLOCK), 0, s, table,
-                           cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, chunks, mode, out, hit_miss, status);
+                           cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, chunks, mode, out, hit_miss, status,
+                           hashed, salt, magic);
     else
         hipLaunchKernelGGL((bag_forward_cached_kernel<LPR, CPL, UNROLL, false>), grid, dim3(CF_BLOCK), 0, s, table,
-                           cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, chunks, mode, out, hit_miss, status);
+                           cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, chunks, mode, out, hit_miss, status,
+                           hashed, salt, magic);
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -162,12 +171,14 @@ __global__ __launch_bounds__(Q_BLOCK) void bag_forward_cached_quant_kernel(const
                                                                            const int64_t *__restrict__ offsets,
                                                                            int32_t D, int64_t row_bytes, int32_t mode,
                                                                            float *__restrict__ out,
-                                                                           unsigned long long *hit_miss, uint32_t *status)
+                                                                           unsigned long long *hit_miss, uint32_t *status,
+                                                                           bool hashed, uint64_t salt, uint64_t magic)
 {
     constexpr int GROUPS = Q_BLOCK / LPR;
     const int l = threadIdx.x % LPR;
     const int64_t b = (int64_t)blockIdx.x * GROUPS + threadIdx.x / LPR;
-    CachedSource src{table, cache_rows, index, (uint64_t)num_rows, (uint64_t)num_hot, row_bytes, status, 0u, 0u};
+    CachedSource src{table, cache_rows, index, (uint64_t)num_rows, (uint64_t)num_hot, row_bytes, status, 0u, 0u,
+                     hashed, salt, magic};
     gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, b, l, nnz, rows, offsets, D, mode, out, status);
     if (hit_miss) {
         // every lane of the wavefront is still here: reduce, then one atomic per wavefront
@@ -188,14 +199,14 @@ template <int BITS>
 int dispatch_cached_quant(int lpr, hipStream_t s, const char *table, const char *cache_rows, const CacheEntry *index,
                           int64_t num_rows, int64_t num_hot, int64_t B, int64_t nnz, const int64_t *rows,
                           const int64_t *offsets, int32_t D, int64_t row_bytes, int32_t mode, float *out,
-                          unsigned long long *hit_miss, uint32_t *status)
+                          unsigned long long *hit_miss, uint32_t *status, bool hashed, uint64_t salt, uint64_t magic)
 {
 #define EMB_CQ(L)                                                                                                   \
     do {                                                                                                            \
         constexpr int GROUPS = Q_BLOCK / L;                                                                         \
         hipLaunchKernelGGL((bag_forward_cached_quant_kernel<L, BITS, 8>), dim3((unsigned)((B + GROUPS - 1) / GROUPS)), \
                            dim3(Q_BLOCK), 0, s, table, cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, D, \
-                           row_bytes, mode, out, hit_miss, status);                                                 \
+                           row_bytes, mode, out, hit_miss, status, hashed, salt, magic);                            \
         EMB_RETURN_IF_LAUNCH_FAILED();                                                                              \
         return EMB_OK;                                                                                              \
     } while (0)
@@ -272,12 +283,12 @@ extern "C" int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t 
     return EMB_OK;
 }
 
-extern "C" int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
-                                      const void *cache_rows_dev, const void *cache_index_dev, int64_t num_hot,
-                                      const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
-                                      int32_t mode, float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
-                                      void *stream)
+static int cached_entry(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype, const void *cache_rows_dev,
+                        const void *cache_index_dev, int64_t num_hot, const int64_t *rows_dev,
+                        const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                        uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream, bool hashed, uint64_t salt)
 {
+    const uint64_t magic = num_rows > 0 ? emb_mod_magic((uint64_t)num_rows) : 0;
     if (B < 0 || nnz < 0 || num_rows <= 0 || num_hot < 0) return EMB_ERR_INVALID_ARG;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
     int rc = cached_row_shape(D, dtype);
@@ -299,9 +310,9 @@ extern "C" int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, i
         unsigned long long *hm = reinterpret_cast<unsigned long long *>(hit_miss_dev);
         if (dtype == EMB_INT8)
             return dispatch_cached_quant<8>(ql, s, tp, cp, ip, num_rows, num_hot, B, nnz, rows_dev, offsets_dev, D, rb,
-                                            mode, out_dev, hm, status_dev);
+                                            mode, out_dev, hm, status_dev, hashed, salt, magic);
         return dispatch_cached_quant<4>(ql, s, tp, cp, ip, num_rows, num_hot, B, nnz, rows_dev, offsets_dev, D, rb, mode,
-                                        out_dev, hm, status_dev);
+                                        out_dev, hm, status_dev, hashed, salt, magic);
     }
     const int chunks = D * emb_elem_size(dtype) / 16;
     int lpr, cpl;
@@ -312,7 +323,7 @@ extern "C" int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, i
                                   reinterpret_cast<const char *>(cache_rows_dev),                               \
                                   reinterpret_cast<const CacheEntry *>(cache_index_dev), num_rows, num_hot, B, nnz, \
                                   rows_dev, offsets_dev, chunks, mode, out_dev,                                  \
-                                  reinterpret_cast<unsigned long long *>(hit_miss_dev), status_dev)
+                                  reinterpret_cast<unsigned long long *>(hit_miss_dev), status_dev, hashed, salt, magic)
     if (cpl == 1) {
         switch (lpr) {
             case 1: EMB_CF(1, 1, 8);
@@ -331,4 +342,25 @@ extern "C" int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, i
         default: EMB_CF(64, 16, 1);
     }
 #undef EMB_CF
+}
+
+extern "C" int emb_bag_forward_cached(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                                      const void *cache_rows_dev, const void *cache_index_dev, int64_t num_hot,
+                                      const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
+                                      int32_t mode, float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
+                                      void *stream)
+{
+    return cached_entry(table_dev, num_rows, D, dtype, cache_rows_dev, cache_index_dev, num_hot, rows_dev, offsets_dev,
+                        B, nnz, mode, out_dev, hit_miss_dev, status_dev, stream, false, 0);
+}
+
+extern "C" int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                                             const void *cache_rows_dev, const void *cache_index_dev, int64_t num_hot,
+                                             uint64_t salt, const uint64_t *raw_dev, const int64_t *offsets_dev,
+                                             int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                                             uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream)
+{
+    return cached_entry(table_dev, num_rows, D, dtype, cache_rows_dev, cache_index_dev, num_hot,
+                        reinterpret_cast<const int64_t *>(raw_dev), offsets_dev, B, nnz, mode, out_dev, hit_miss_dev,
+                        status_dev, stream, true, salt);
 }

@@ -653,6 +653,19 @@ def test_cached_forward_over_quantized_table(dtype, D):
     assert int(status.item()) == st == emb.STATUS_BAD_INDEX
     assert hm.cpu().tolist() == [hits, misses] and hits > 0 and misses > 0
     H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="cached quantised forward")
+    # hashing inside the cached lookup: same bits and counts as hashing first
+    raw = rng.integers(0, 1 << 64, size=rows.size, dtype=np.uint64)
+    hrows = oracle.hash_ids(raw, 77, R)
+    o1 = torch.empty_like(out)
+    o2 = torch.empty_like(out)
+    hm1 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    hm2 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    st2 = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_cached(ptr, R, D, dtype, cache, index, K, H.dev(hrows), H.dev(off), B, "mean", o1, hm1, st2)
+    emb.emb_bag_forward_cached_hashed(ptr, R, D, dtype, cache, index, K, 77, H.dev(raw), H.dev(off), B, "mean", o2, hm2,
+                                      st2)
+    torch.cuda.synchronize()
+    assert st2.item() == 0 and torch.equal(o1, o2) and torch.equal(hm1, hm2) and int(hm1.sum()) == rows.size
     # the cache is numerically invisible: the plain lookup over the same packed table gives the same bits
     ts = emb.TableSet([H.dev(packed)], D, dtype, device=torch.device(H.DEV))
     plain, _ = H.gpu_forward(ts, rows, off, B, "sum")
