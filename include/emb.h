@@ -1,23 +1,28 @@
 /*
  * emb.h - C ABI of the MI355X (gfx950) library for the hot path behind large
  * hashed embedding tables: ID hashing, bag offsets, pooled lookup
- * (EmbeddingBag forward), exact sparse backward with row-wise Adagrad, and a
- * pooled lookup over a host-resident table fronted by an HBM hot-row cache.
+ * (EmbeddingBag forward; also over row-quantised INT8 / INT4 tables and over
+ * tables of different width), exact sparse backward with row-wise Adagrad, and
+ * a pooled lookup over a host-resident table fronted by an HBM hot-row cache.
  *
  * Source of the problem statement: "Multi-Faceted Large Embedding Tables for
  * Pinterest Ads Ranking", Section 2.2 (high-cardinality categorical features
  * are mapped to dense embeddings through hashed lookup tables; collisions are
  * legal), Section 3.1 (several ID tables of ~1e8-1e9 rows, fine-tuned inside
  * the ranking model) and Section 3.3 (tables too large for GPU memory are
- * hosted in CPU memory).  The paper names no hash, pooling mode or optimizer;
- * each entry point states the definition it implements.
+ * hosted in CPU memory) and Section 4.1.2 (those tables are stored as INT4
+ * after post-training quantisation).  The paper names no hash, pooling mode,
+ * optimizer or quantisation scheme; each entry point states the definition
+ * it implements.
  *
  * Conventions
  *  - "dev" pointers are device pointers (HBM, or host memory mapped into the
  *    device address space where stated); "host" pointers are ordinary host
  *    memory read during the call only.
- *  - The caller owns every buffer.  The library allocates nothing, keeps no
- *    global state, and never synchronises: a call validates its arguments on
+ *  - The caller owns every buffer.  The library allocates no memory, keeps no
+ *    global state, and never synchronises (the only objects it creates are the
+ *    stream and events a caller asks for with emb_side_stream_create /
+ *    emb_event_create, which the caller destroys): a call validates its arguments on
  *    the host, enqueues kernels on `stream` (a hipStream_t passed as void*,
  *    NULL = the default stream) and returns.  Results are valid once the
  *    caller has synchronised the stream.
