@@ -438,7 +438,13 @@ def main() -> int:
             return None
         return pipeline.run_index_stage(w, tabs.set, db, buf)
 
+    train_route = fused and w.backward     # the lookup also writes the backward's records
+
     def do_forward(db, rows):
+        if train_route:
+            emb.emb_bag_forward_train(tabs.set, db.raw, buf.offsets, w.B, w.pool, buf.out, buf.workspace, None,
+                                      buf.num_unique, buf.status)
+            return None
         if fused:
             rows = buf.rows[:db.nnz]
             emb.emb_bag_forward_hashed(tabs.set, db.raw, buf.offsets, w.B, w.pool, buf.out,
@@ -455,8 +461,17 @@ def main() -> int:
             return pipeline.run_step_overlapped(w_, tset, db, buf_)
         rows = index_and_forward(db)
         if w_.backward:
-            pipeline.run_backward(w_, tset, rows, db, buf_)
+            do_backward(db, rows, None)
         return rows
+
+    def do_backward(db, rows, sev):
+        if train_route:
+            emb.emb_bag_backward_sort_prepared(tabs.set, w.B, db.nnz, buf.workspace, buf.unique_keys,
+                                               buf.unique_counts, buf.num_unique, buf.status, sev)
+            emb.emb_bag_backward_update(tabs.set, w.B, db.nnz, db.dout, w.lr, w.eps, buf.workspace, buf.num_unique,
+                                        sev, buf.side)
+        else:
+            pipeline.run_backward(w, tabs.set, rows, db, buf, stage_events=sev)
 
     for i in range(W):
         step_fn(w, tabs.set, dbs[i % len(dbs)], buf)
@@ -486,7 +501,7 @@ def main() -> int:
                 pipeline.run_step_overlapped(w, tabs.set, db, buf, stage_events=sev)
             else:
                 rows = index_and_forward(db)
-                pipeline.run_backward(w, tabs.set, rows, db, buf, stage_events=sev)
+                do_backward(db, rows, sev)
         else:
             rows = do_index(db)
             dom[k][0].record()
@@ -511,7 +526,7 @@ def main() -> int:
         rows = do_forward(db, rows)
         ev[k][2].record()
         if w.backward:
-            pipeline.run_backward(w, tabs.set, rows, db, buf, stage_events=bev[k])
+            do_backward(db, rows, bev[k])
     torch.cuda.synchronize()
 
     lookups = sum(dbs[(W + k) % len(dbs)].nnz for k in range(K))
@@ -533,7 +548,11 @@ def main() -> int:
 
     if fused:
         fwd_name, fwd_pmc = "bag_forward_hashed_kernel (hash + gather-pool)", "bag_forward_hashed_kernel"
-        fwd_extra = nnz_i * 8 if w.backward else 0        # the row numbers written for the backward
+        fwd_extra = 0
+        if train_route:
+            fwd_name = "bwd_init + bag_forward_train_kernel (hash + gather-pool + the backward's records)"
+            fwd_pmc = "bag_forward_train_kernel"
+            fwd_extra = nnz_i * 8 + bags * 4          # one 8-byte record per lookup, one scale per bag
         index_entry = entry("offsets_* (index stage, 3 launches; hashing is done inside the forward)", ms_index,
                             bags * 12, "12 B per bag (length in, offset out)")
     else:
@@ -547,7 +566,7 @@ def main() -> int:
     kernels = [
         index_entry,
         entry(fwd_name, ms_fwd if w.backward else ms_dom, forward_bytes(nnz_i, bags, w.D, rowb) + fwd_extra,
-              "row + 8 B index per lookup (+ 8 B row number out when a backward follows), fp32 output row + 8 B "
+              "row + 8 B index per lookup (+ 8 B record out when a backward follows), fp32 output row + 8 B "
               "offset per bag", fwd_pmc),
     ]
     ms_bwd = 0.0
@@ -556,7 +575,8 @@ def main() -> int:
         st[3] = ms_dom      # the dominant kernel's time is the one measured inside the timed region
         ms_bwd = sum(r[0].elapsed_time(r[NS - 1]) for r in bev) / KI
         kernels += [
-            entry("bwd_init + bwd_keys_kernel (key build)", st[0], nnz_i * 16 + bags * 20,
+            entry("bwd_init + bwd_keys_kernel (key build)" if not train_route
+                  else "(key build: done by the training lookup)", st[0], (nnz_i * 16 + bags * 20) if not train_route else 1,
                   "8 B row in + 8 B record out per lookup; 16 B offsets in + 4 B scale out per bag"),
             entry("sort_hist/scan/scatter x %d passes (radix sort)" % passes, st[1], nnz_i * 16 * passes,
                   "8 B record read + 8 B written per lookup and pass"),

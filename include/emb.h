@@ -306,6 +306,36 @@ int64_t emb_row_bytes(int32_t D, int32_t dtype);
 int emb_quantize_rows(const float *src_dev, int64_t num_rows, int32_t D, int32_t dtype,
                       void *dst_dev, void *stream);
 
+/* The lookup of a training step (Section 3.1: the tables are fine-tuned inside
+ * the ranking model, so every lookup is followed by its backward):
+ * emb_bag_forward_hashed that also begins the backward of the same batch.
+ * While it has the row number and the bag of every lookup in hand it validates
+ * the offsets and writes the backward's (row, bag) records and per-bag
+ * gradient scales into workspace_dev, so that the backward needs no pass over
+ * the indices:
+ *     emb_bag_forward_train            (this call; reads the tables)
+ *     ... the model computes dout ...
+ *     emb_bag_backward_sort_prepared   (emb_bag_backward_sort without rows_dev)
+ *     emb_bag_backward_update
+ * Pooled output, row numbers, updated tables and row lists are bit-identical
+ * to emb_bag_forward_hashed followed by emb_bag_backward_rowwise_adagrad.
+ * The tables need accumulators (accum != NULL), the workspace is that of
+ * emb_bag_backward_workspace_bytes and must stay untouched until the update
+ * has run; T, D, dtype, B, nnz, tables and workspace are the same in the three
+ * calls.  rows_out_dev is nullable.  dtype: EMB_F32 or EMB_BF16. */
+int emb_bag_forward_train(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                          int32_t D, int32_t dtype, const uint64_t *raw_dev,
+                          const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
+                          float *out_dev, int64_t *rows_out_dev, void *workspace_dev,
+                          size_t workspace_bytes, int64_t *num_unique_out_dev,
+                          uint32_t *status_dev, void *stream);
+int emb_bag_backward_sort_prepared(const emb_table *tables_host, const emb_table *tables_dev,
+                                   int32_t T, int32_t D, int32_t dtype, int64_t B, int64_t nnz,
+                                   void *workspace_dev, size_t workspace_bytes,
+                                   int64_t *unique_keys_out_dev, int32_t *unique_counts_out_dev,
+                                   int64_t *num_unique_out_dev, uint32_t *status_dev,
+                                   void *const *stage_events, void *stream);
+
 /* ---- host-resident table with an HBM hot-row cache (Section 3.3) --------- */
 
 /* Bytes of the cache index for a table of num_rows rows (16 bytes per 64

@@ -22,6 +22,7 @@
 #include "radix_sort.h"
 #include "scan.h"
 #include "update.h"
+#include "u64mod.h"
 
 namespace {
 
@@ -421,8 +422,10 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
 }
 
 // Keys, sort and the optional list of distinct rows: everything that needs the indices only.
+// prepared: the control block, the tile descriptors and the records are in the workspace already
+// (emb_bag_forward_train put them there), so only the passes and the optional list run.
 template <typename KeyT>
-int run_sort(const BwdArgs &a, const BwdLayout &L)
+int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
 {
     BwdCtrl *ctrl = reinterpret_cast<BwdCtrl *>(a.ws + L.ctrl);
     KeyT *keys_a = reinterpret_cast<KeyT *>(a.ws + L.keys_a);
@@ -444,15 +447,17 @@ int run_sort(const BwdArgs &a, const BwdLayout &L)
     hipStream_t s = a.stream;
 
     EMB_MARK(a, 0);
-    hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, s, ctrl, a.offsets, a.nnz > 0 ? a.T : 0, a.B, a.nnz,
-                       first_tile, tile_desc, a.nnz > 0 ? tiles : 0u, a.num_unique_out, a.status);
-    EMB_RETURN_IF_LAUNCH_FAILED();
+    if (!prepared) {
+        hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, s, ctrl, a.offsets, a.nnz > 0 ? a.T : 0, a.B, a.nnz,
+                           first_tile, tile_desc, a.nnz > 0 ? tiles : 0u, a.num_unique_out, a.status);
+        EMB_RETURN_IF_LAUNCH_FAILED();
+    }
     if (a.nnz == 0) {
         for (int i = 1; i <= 3; ++i) EMB_MARK(a, i);
         return EMB_OK;
     }
 
-    {
+    if (!prepared) {
         constexpr int BAGS = 256 / KEY_LANES;
         dim3 grid((unsigned)((a.B + BAGS - 1) / BAGS), (unsigned)a.T);
         hipLaunchKernelGGL(bwd_keys_kernel<KeyT>, grid, dim3(256), 0, s, a.tables_dev, a.T, a.B, a.nnz, a.rows,
@@ -556,7 +561,123 @@ extern "C" size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t
 
 namespace {
 
-// Host-side checks and the workspace layout shared by the three backward entry points.
+// ---------------------------------------------------------------------------
+// training forward: the pooled lookup of a batch that will be followed by its backward
+// ---------------------------------------------------------------------------
+// The lookup hashes the raw IDs itself (as emb_bag_forward_hashed) and, having the row number
+// and the bag of every lookup in hand, writes the backward's (row, bag) record and the bag's
+// gradient scale while it is there: the backward then needs no pass over the indices.
+template <typename KeyT>
+struct TrainSource {
+    const char *weights;
+    uint64_t num_rows, salt, magic;
+    int64_t row_bytes;
+    int64_t *rows_out;   // nullable
+    KeyT *keys;
+    uint32_t *pay;
+    uint32_t bag;
+    __device__ __forceinline__ uint64_t resolve(int64_t raw, int64_t j) const
+    {
+        const uint64_t r = emb_fast_mod(emb_splitmix64((uint64_t)raw ^ salt), num_rows, magic);
+        if (rows_out) rows_out[j] = (int64_t)r;
+        keys[j] = (KeyT)r;
+        pay[j] = bag;
+        return reinterpret_cast<uint64_t>(weights + (int64_t)r * row_bytes);
+    }
+};
+
+constexpr int TRAIN_BLOCK = 256;
+
+template <int LPR, int CPL, int UNROLL, bool BF16, typename KeyT>
+__global__ __launch_bounds__(TRAIN_BLOCK) void bag_forward_train_kernel(
+    const emb_table *__restrict__ tables, int32_t T, int64_t B, uint32_t blocks_per_table, int64_t nnz,
+    const int64_t *__restrict__ raw, const int64_t *__restrict__ offsets, int32_t chunks_per_row, int32_t mode,
+    float *__restrict__ out, int64_t *__restrict__ rows_out, KeyT *__restrict__ keys, uint32_t *__restrict__ pay,
+    float *__restrict__ bag_scale, BwdCtrl *ctrl, uint32_t *status)
+{
+    constexpr int GROUPS = TRAIN_BLOCK / LPR;
+    constexpr int F = ChunkAcc<BF16>::FLOATS;
+    const uint32_t lb = emb_xcd_block(blockIdx.x, gridDim.x);
+    const uint32_t t_raw = lb / blocks_per_table;
+    const bool tail = t_raw >= (uint32_t)T;          // the grid is rounded up to whole dies
+    const int t = tail ? T - 1 : (int)t_raw;
+    const int l = threadIdx.x % LPR;
+    const int64_t b = tail ? B : (int64_t)(lb % blocks_per_table) * GROUPS + threadIdx.x / LPR;
+    const bool live = b < B;
+    const int64_t bag = (int64_t)t * B + b;
+    const emb_table tb = tables[t];
+    if (live && l == 0) {
+        // what bwd_keys_kernel does per bag: the scale of its gradient, or the abort of the backward
+        const int64_t s = offsets[bag], e = offsets[bag + 1];
+        if (s < 0 || e < s || e > nnz) atomicOr(&ctrl->abort, 1u);   // the lookup below flags the status word
+        else bag_scale[bag] = (mode == EMB_POOL_MEAN && e > s) ? 1.0f / (float)(e - s) : 1.0f;
+    }
+    TrainSource<KeyT> src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, tb.salt, tb.mod_magic,
+                          (int64_t)chunks_per_row * 16, rows_out, keys, pay, (uint32_t)bag};
+    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, live, bag, l, nnz, raw, offsets, chunks_per_row, mode,
+                                            out + bag * ((int64_t)chunks_per_row * F), status);
+}
+
+template <typename KeyT, int LPR, int CPL, int UNROLL>
+int launch_train(bool bf16, const BwdArgs &a, const BwdLayout &L, const int64_t *raw, float *out, int64_t *rows_out,
+                 int chunks)
+{
+    constexpr int GROUPS = TRAIN_BLOCK / LPR;
+    const int64_t per_table = (a.B + GROUPS - 1) / GROUPS;
+    const int64_t blocks = emb_round_up_xcds(per_table * a.T);
+    if (blocks > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+    BwdCtrl *ctrl = reinterpret_cast<BwdCtrl *>(a.ws + L.ctrl);
+    KeyT *keys = reinterpret_cast<KeyT *>(a.ws + L.keys_a);
+    uint32_t *pay = reinterpret_cast<uint32_t *>(a.ws + L.pay_a);
+    float *bag_scale = reinterpret_cast<float *>(a.ws + L.bag_scale);
+    if (bf16)
+        hipLaunchKernelGGL((bag_forward_train_kernel<LPR, CPL, UNROLL, true, KeyT>), dim3((unsigned)blocks),
+                           dim3(TRAIN_BLOCK), 0, a.stream, a.tables_dev, a.T, a.B, (uint32_t)per_table, a.nnz, raw,
+                           a.offsets, chunks, a.mode, out, rows_out, keys, pay, bag_scale, ctrl, a.status);
+    else
+        hipLaunchKernelGGL((bag_forward_train_kernel<LPR, CPL, UNROLL, false, KeyT>), dim3((unsigned)blocks),
+                           dim3(TRAIN_BLOCK), 0, a.stream, a.tables_dev, a.T, a.B, (uint32_t)per_table, a.nnz, raw,
+                           a.offsets, chunks, a.mode, out, rows_out, keys, pay, bag_scale, ctrl, a.status);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    return EMB_OK;
+}
+
+template <typename KeyT>
+int run_train_forward(const BwdArgs &a, const BwdLayout &L, const int64_t *raw, float *out, int64_t *rows_out)
+{
+    BwdCtrl *ctrl = reinterpret_cast<BwdCtrl *>(a.ws + L.ctrl);
+    uint32_t *first_tile = reinterpret_cast<uint32_t *>(a.ws + L.first_tile);
+    SortTile *tile_desc = reinterpret_cast<SortTile *>(a.ws + L.tile_desc);
+    hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, a.stream, ctrl, a.offsets, a.nnz > 0 ? a.T : 0, a.B,
+                       a.nnz, first_tile, tile_desc, a.nnz > 0 ? (uint32_t)L.tiles : 0u, a.num_unique_out, a.status);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    if (a.T == 0 || a.B == 0) return EMB_OK;
+    const int chunks = a.D * emb_elem_size(a.dtype) / 16;
+    int lpr, cpl;
+    emb_row_split(chunks, lpr, cpl);
+    const bool bf16 = a.dtype == EMB_BF16;
+#define EMB_TR(LL, C, U) return launch_train<KeyT, LL, C, U>(bf16, a, L, raw, out, rows_out, chunks)
+    if (cpl == 1) {
+        switch (lpr) {
+            case 1: EMB_TR(1, 1, 8);
+            case 2: EMB_TR(2, 1, 8);
+            case 4: EMB_TR(4, 1, 8);
+            case 8: EMB_TR(8, 1, 8);
+            case 16: EMB_TR(16, 1, 8);
+            case 32: EMB_TR(32, 1, 8);
+            default: EMB_TR(64, 1, 8);
+        }
+    }
+    switch (cpl) {
+        case 2: EMB_TR(64, 2, 4);
+        case 4: EMB_TR(64, 4, 2);
+        case 8: EMB_TR(64, 8, 1);
+        default: EMB_TR(64, 16, 1);
+    }
+#undef EMB_TR
+}
+
+// Host-side checks and the workspace layout shared by the backward entry points.
 int bwd_plan(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, int64_t B,
              int64_t nnz, void *workspace_dev, size_t workspace_bytes, void *stream, BwdArgs &a, BwdLayout &L)
 {
@@ -616,6 +737,48 @@ extern "C" int emb_bag_backward_sort(const emb_table *tables_host, const emb_tab
     a.status = status_dev;
     a.events = stage_events;
     return L.key_bytes == 4 ? run_sort<uint32_t>(a, L) : run_sort<uint64_t>(a, L);
+}
+
+extern "C" int emb_bag_forward_train(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
+                                     int32_t dtype, const uint64_t *raw_dev, const int64_t *offsets_dev, int64_t B,
+                                     int64_t nnz, int32_t mode, float *out_dev, int64_t *rows_out_dev,
+                                     void *workspace_dev, size_t workspace_bytes, int64_t *num_unique_out_dev,
+                                     uint32_t *status_dev, void *stream)
+{
+    if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
+    BwdArgs a;
+    BwdLayout L;
+    const int rc = bwd_plan(tables_host, tables_dev, T, D, dtype, B, nnz, workspace_dev, workspace_bytes, stream, a, L);
+    if (rc != EMB_OK) return rc;
+    if (T > 0 && B > 0) {
+        if (!offsets_dev || !out_dev || (nnz > 0 && !raw_dev)) return EMB_ERR_INVALID_ARG;
+        if (!emb_aligned(out_dev, 16)) return EMB_ERR_INVALID_ARG;
+    }
+    a.mode = mode;
+    a.offsets = offsets_dev;
+    a.num_unique_out = num_unique_out_dev;
+    a.status = status_dev;
+    const int64_t *raw = reinterpret_cast<const int64_t *>(raw_dev);
+    return L.key_bytes == 4 ? run_train_forward<uint32_t>(a, L, raw, out_dev, rows_out_dev)
+                            : run_train_forward<uint64_t>(a, L, raw, out_dev, rows_out_dev);
+}
+
+extern "C" int emb_bag_backward_sort_prepared(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                                              int32_t D, int32_t dtype, int64_t B, int64_t nnz, void *workspace_dev,
+                                              size_t workspace_bytes, int64_t *unique_keys_out_dev,
+                                              int32_t *unique_counts_out_dev, int64_t *num_unique_out_dev,
+                                              uint32_t *status_dev, void *const *stage_events, void *stream)
+{
+    BwdArgs a;
+    BwdLayout L;
+    const int rc = bwd_plan(tables_host, tables_dev, T, D, dtype, B, nnz, workspace_dev, workspace_bytes, stream, a, L);
+    if (rc != EMB_OK) return rc;
+    a.unique_keys_out = unique_keys_out_dev;
+    a.unique_counts_out = unique_counts_out_dev;
+    a.num_unique_out = num_unique_out_dev;
+    a.status = status_dev;
+    a.events = stage_events;
+    return L.key_bytes == 4 ? run_sort<uint32_t>(a, L, true) : run_sort<uint64_t>(a, L, true);
 }
 
 extern "C" int emb_bag_backward_update(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,

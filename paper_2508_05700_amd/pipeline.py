@@ -155,10 +155,26 @@ def run_step_overlapped(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf:
     return rows
 
 
-def run_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:
-    """One pass of the whole path over one batch; returns the row view used."""
-    rows = run_index_stage(w, tables, db, buf)
-    run_forward(w, tables, rows, buf)
+def run_train_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers, stage_events=None) -> None:
+    """One pass of the whole path for a workload with a backward and raw IDs: bag offsets, the training
+    lookup (hashing, pooling and the backward's records in one kernel), sort, update."""
+    emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
+    emb.emb_bag_forward_train(tables, db.raw, buf.offsets, w.B, w.pool, buf.out, buf.workspace, None, buf.num_unique,
+                              buf.status)
+    emb.emb_bag_backward_sort_prepared(tables, w.B, db.nnz, buf.workspace, buf.unique_keys, buf.unique_counts,
+                                       buf.num_unique, buf.status, stage_events)
+    emb.emb_bag_backward_update(tables, w.B, db.nnz, db.dout, w.lr, w.eps, buf.workspace, buf.num_unique,
+                                stage_events, buf.side)
+
+
+def run_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> Optional[torch.Tensor]:
+    """One pass of the whole path over one batch, by the shortest route the workload allows: the
+    training lookup when there is a backward and the IDs are raw, hashing inside the lookup when
+    the IDs are raw, separate kernels otherwise.  Returns the row view where one was produced."""
+    if w.backward and db.raw is not None and not w.quant:
+        run_train_step(w, tables, db, buf)
+        return None
+    rows = run_index_and_forward_fused(w, tables, db, buf)
     if w.backward:
         run_backward(w, tables, rows, db, buf)
     return rows

@@ -187,6 +187,21 @@ def test_split_backward_and_helper_argument_errors(L):
     assert upd(*upd_args(nnz=1 << 31)) == UNSUPPORTED
     side = (C.c_void_p * 3)(FAKE, None, FAKE)
     assert upd(*upd_args(side=C.addressof(side))) == INVALID
+    # the training lookup and the sort that follows it
+    tr, sp = L.emb_bag_forward_train, L.emb_bag_backward_sort_prepared
+
+    def tr_args(**k):
+        return [k.get("th", d.ctypes.data), FAKE, 2, k.get("D", 64), k.get("dtype", 0), k.get("raw", FAKE), FAKE, 4, 8,
+                k.get("mode", 1), k.get("out", FAKE), None, k.get("ws", FAKE), k.get("wsb", need), None, None, None]
+    assert tr(*tr_args(mode=9)) == INVALID
+    assert tr(*tr_args(out=None)) == INVALID
+    assert tr(*tr_args(raw=None)) == INVALID
+    assert tr(*tr_args(wsb=need - 256)) == WORKSPACE
+    assert tr(*tr_args(dtype=3)) == UNSUPPORTED                       # quantised tables are not trained
+    noacc = _tables(with_accum=False)
+    assert tr(*tr_args(th=noacc.ctypes.data)) == UNSUPPORTED          # training needs accumulators
+    assert sp(d.ctypes.data, FAKE, 2, 64, 0, 4, 8, None, need, None, None, None, None, None, None) == WORKSPACE
+    assert sp(d.ctypes.data, FAKE, 2, 3, 0, 4, 8, FAKE, need, None, None, None, None, None, None) == UNSUPPORTED
     # helpers: null arguments are refused before the runtime is touched
     assert L.emb_event_create(None, 1) == INVALID
     assert L.emb_event_record(None, None) == INVALID

@@ -507,6 +507,83 @@ def test_backward_split_calls_on_two_streams_equal_the_single_call():
         assert np.array_equal(a1[t].cpu().numpy(), a2[t].cpu().numpy())
 
 
+@pytest.mark.parametrize("D,dtype", [(64, "f32"), (32, "bf16"), (320, "f32")])
+def test_training_forward_equals_hashed_forward_plus_backward(D, dtype):
+    # emb_bag_forward_train + sort_prepared + update against emb_bag_forward_hashed + the one-call
+    # backward: pooled output, row numbers, tables, accumulators and row lists bit for bit; and
+    # against the oracle within tolerance.
+    rng = np.random.default_rng(4400 + D)
+    T, B = 3, 900
+    Rs = [20_000, 13, 70_001]
+    salts = [5, 0, M64]
+    tables, lengths, off, _ = H.random_case(rng, T, B, D, Rs, 25, dtype, scale=0.01)
+    nnz = int(off[-1])
+    raw = rng.integers(0, 1 << 64, size=nnz, dtype=np.uint64)
+    raw[: nnz // 3] = raw[0]                                   # a hot ID: long runs in table 0
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    rows = np.concatenate([oracle.hash_ids(raw[off[t * B]:off[(t + 1) * B]], salts[t], Rs[t]) for t in range(T)])
+
+    def fresh():
+        w = [H.dev(t) for t in tables]
+        acc = [torch.zeros(R, dtype=torch.float32, device=H.DEV) for R in Rs]
+        return emb.TableSet(w, D, dtype, accum=acc, salts=salts, device=torch.device(H.DEV)), w, acc
+
+    raw_d, off_d, dout_d = H.dev(raw), H.dev(off), H.dev(dout)
+    # reference route on the device
+    ts1, w1, a1 = fresh()
+    out1 = torch.empty((T, B, D), dtype=torch.float32, device=H.DEV)
+    rows1 = torch.empty(nnz, dtype=torch.int64, device=H.DEV)
+    st1 = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_hashed(ts1, raw_d, off_d, B, "mean", out1, rows1, st1)
+    g1 = H.gpu_backward(ts1, rows, off, B, "mean", dout, 0.01, 1e-8, side=False)
+    # training route
+    ts2, w2, a2 = fresh()
+    ws = torch.empty(emb.emb_bag_backward_workspace_bytes(T, B, nnz, ts2.total_rows, D, dtype), dtype=torch.uint8,
+                     device=H.DEV)
+    out2 = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    rows2 = torch.full((nnz,), -1, dtype=torch.int64, device=H.DEV)
+    uk = torch.full((nnz,), -7, dtype=torch.int64, device=H.DEV)
+    uc = torch.full((nnz,), -7, dtype=torch.int32, device=H.DEV)
+    nu = torch.full((1,), -7, dtype=torch.int64, device=H.DEV)
+    st2 = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_train(ts2, raw_d, off_d, B, "mean", out2, ws, rows2, nu, st2)
+    emb.emb_bag_backward_sort_prepared(ts2, B, nnz, ws, uk, uc, nu, st2)
+    emb.emb_bag_backward_update(ts2, B, nnz, dout_d, 0.01, 1e-8, ws, nu, None, H.side_stream())
+    torch.cuda.synchronize()
+    assert st1.item() == 0 and st2.item() == 0 and g1["status"] == 0
+    assert torch.equal(out1, out2) and torch.equal(rows1, rows2) and np.array_equal(rows2.cpu().numpy(), rows)
+    U = int(nu.item())
+    assert U == g1["U"] and np.array_equal(uk[:U].cpu().numpy(), g1["unique_keys"])
+    assert np.array_equal(uc[:U].cpu().numpy(), g1["unique_counts"])
+    for t in range(T):
+        assert torch.equal(w1[t], w2[t]) and torch.equal(a1[t], a2[t])
+    # and the oracle
+    ref, absum, _ = oracle.bag_forward(tables, dtype, rows, off, B, "mean")
+    H.assert_pooled_close(out2.cpu().numpy(), ref, absum, what="training forward")
+    ref_t, ref_a = [t.copy() for t in tables], [np.zeros(R, np.float32) for R in Rs]
+    r = oracle.bag_backward_rowwise_adagrad(ref_t, ref_a, dtype, rows, off, B, "mean", dout, 0.01, 1e-8)
+    assert np.array_equal(uk[:U].cpu().numpy(), r["unique_keys"])
+    base = np.concatenate([[0], np.cumsum(Rs)])
+    for t in range(T):
+        sel = (r["unique_keys"] >= base[t]) & (r["unique_keys"] < base[t + 1])
+        touched = r["unique_keys"][sel] - base[t]
+        H.assert_rows_close(H.as_f32(H.host_table(w2[t]))[touched], H.as_f32(ref_t[t])[touched],
+                            H.as_f32(tables[t])[touched], 0.01, H.EPS_BF16 if dtype == "bf16" else H.EPS32,
+                            what="training route rows t=%d" % t)
+    # malformed offsets: the lookup flags them and the backward does nothing
+    bad = off.copy()
+    bad[7] = bad[8] + 1
+    ts3, w3, a3 = fresh()
+    st3 = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_train(ts3, raw_d, H.dev(bad), B, "mean", out2, ws, None, nu, st3)
+    emb.emb_bag_backward_sort_prepared(ts3, B, nnz, ws, uk, uc, nu, st3)
+    emb.emb_bag_backward_update(ts3, B, nnz, dout_d, 0.01, 1e-8, ws, nu, None, None)
+    torch.cuda.synchronize()
+    assert st3.item() & emb.STATUS_BAD_OFFSETS and int(nu.item()) == 0
+    for t in range(T):
+        assert np.array_equal(H.host_table(w3[t]), tables[t]) and float(a3[t].abs().sum()) == 0.0
+
+
 def test_backward_is_deterministic():
     rng = np.random.default_rng(43)
     T, B, D, Rs = 2, 1500, 64, [20_000, 300]
