@@ -40,14 +40,14 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "24280fc3a610b79e",
+    "sources": "95337eb65a24ed87",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_hashed_kernel": (178838.7, 61191.5), "update_kernel": (240580.3, 324001.0)},
-        "2u": {"bag_forward_kernel": (338143.5, 32768.0)},
-        "2un": {"bag_forward_kernel": (346108.5, 32768.0)},
-        "2uq4": {"bag_forward_quant_kernel": (233564.0, 32887.3)},
+        "3": {"bag_forward_train_kernel": (178070.8, 67610.0), "update_kernel": (240599.7, 323999.7)},
+        "2u": {"bag_forward_kernel": (338145.6, 32768.0)},
+        "2un": {"bag_forward_kernel": (346118.3, 32768.0)},
+        "2uq4": {"bag_forward_quant_kernel": (233575.3, 32886.2)},
     },
 }
 
