@@ -364,7 +364,7 @@ def _backward_case(rng, T, B, D, Rs, max_len, dtype, mode, hot=0.0, lr=0.01, eps
 
 
 BWD_SHAPES = [(4, "f32"), (16, "f32"), (32, "f32"), (64, "f32"), (128, "f32"), (48, "f32"), (320, "f32"),
-              (2048, "f32"), (32, "bf16"), (64, "bf16"), (8, "bf16"), (1040, "bf16")]
+              (2048, "f32"), (4096, "f32"), (32, "bf16"), (64, "bf16"), (8, "bf16"), (1040, "bf16"), (8192, "bf16")]
 
 
 @pytest.mark.parametrize("D,dtype", BWD_SHAPES)
