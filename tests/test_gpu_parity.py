@@ -584,6 +584,42 @@ def test_training_forward_equals_hashed_forward_plus_backward(D, dtype):
         assert np.array_equal(H.host_table(w3[t]), tables[t]) and float(a3[t].abs().sum()) == 0.0
 
 
+def test_many_tables_take_the_paths_without_lds_staging():
+    # more tables than the kernels stage in LDS (table boundaries in the hashing kernel, the table
+    # directory in the update kernels): 1100 small tables, 3 bags each
+    rng = np.random.default_rng(4500)
+    T, B, D = 1100, 3, 16
+    Rs = [int(r) for r in rng.integers(1, 60, size=T)]
+    tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
+    lengths = rng.integers(0, 12, size=T * B).astype(np.int32)
+    lengths[3 * B:9 * B] = 0                                         # a stretch of tables without lookups
+    off, _ = oracle.lengths_to_offsets(lengths)
+    nnz = int(off[-1])
+    raw = rng.integers(0, 1 << 64, size=nnz, dtype=np.uint64)
+    salts = list(range(7, 7 + T))
+    w = [H.dev(t) for t in tables]
+    acc = [torch.zeros(R, dtype=torch.float32, device=H.DEV) for R in Rs]
+    ts = emb.TableSet(w, D, "f32", accum=acc, salts=salts, device=torch.device(H.DEV))
+    rows_dev = torch.full((nnz,), -5, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_hash_ids_tables(ts, H.dev(raw), H.dev(off), B, rows_dev, status)
+    torch.cuda.synchronize()
+    rows = np.concatenate([oracle.hash_ids(raw[off[t * B]:off[(t + 1) * B]], salts[t], Rs[t]) for t in range(T)])
+    assert status.item() == 0 and np.array_equal(rows_dev.cpu().numpy(), rows)
+    out, st = H.gpu_forward(ts, rows, off, B, "sum")
+    ref, absum, _ = oracle.bag_forward(tables, "f32", rows, off, B, "sum")
+    assert st == 0
+    H.assert_pooled_close(out, ref, absum, what="many tables forward")
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    g = H.gpu_backward(ts, rows, off, B, "sum", dout, 0.01, 1e-8)
+    ref_t, ref_a = [t.copy() for t in tables], [np.zeros(R, np.float32) for R in Rs]
+    r = oracle.bag_backward_rowwise_adagrad(ref_t, ref_a, "f32", rows, off, B, "sum", dout, 0.01, 1e-8)
+    assert g["status"] == 0 and np.array_equal(g["unique_keys"], r["unique_keys"])
+    assert np.array_equal(g["unique_counts"], r["unique_counts"])
+    for t in range(T):
+        H.assert_rows_close(w[t].cpu().numpy(), ref_t[t], tables[t], 0.01, what="many tables rows t=%d" % t)
+
+
 def test_backward_is_deterministic():
     rng = np.random.default_rng(43)
     T, B, D, Rs = 2, 1500, 64, [20_000, 300]
