@@ -325,3 +325,45 @@ void oracle_bag_forward_cached(const void *table, int64_t num_rows, int32_t D, i
         }
     }
 }
+
+/* ---- frequency-based cache policy --------------------------------------- */
+
+int64_t oracle_cache_observe(uint32_t *freq, int64_t num_rows, const int64_t *rows, int64_t nnz)
+{
+    int64_t bad = 0;
+    for (int64_t j = 0; j < nnz; ++j) {
+        int64_t r = rows[j];
+        if (r < 0 || r >= num_rows) {
+            ++bad;
+            continue;
+        }
+        freq[r] += 1u; /* unsigned: wraps at 2^32 */
+    }
+    return bad;
+}
+
+static const uint32_t *g_select_freq; /* qsort has no context argument */
+
+/* order of preference: larger counter first, then smaller row number */
+static int cmp_preference(const void *a, const void *b)
+{
+    int64_t ra = *(const int64_t *)a, rb = *(const int64_t *)b;
+    uint32_t fa = g_select_freq[ra], fb = g_select_freq[rb];
+    if (fa != fb) return fa > fb ? -1 : 1;
+    return (ra > rb) - (ra < rb);
+}
+
+int oracle_cache_select(uint32_t *freq, int64_t num_rows, int64_t num_hot, int32_t decay_shift,
+                        int64_t *hot_rows_out)
+{
+    int64_t *order = (int64_t *)malloc((size_t)(num_rows > 0 ? num_rows : 1) * sizeof(int64_t));
+    if (!order) return -1;
+    for (int64_t r = 0; r < num_rows; ++r) order[r] = r;
+    g_select_freq = freq;
+    qsort(order, (size_t)num_rows, sizeof(int64_t), cmp_preference);
+    for (int64_t k = 0; k < num_hot; ++k) hot_rows_out[k] = order[k];
+    qsort(hot_rows_out, (size_t)num_hot, sizeof(int64_t), cmp_i64);
+    free(order);
+    for (int64_t r = 0; r < num_rows; ++r) freq[r] >>= decay_shift;
+    return 0;
+}

@@ -113,6 +113,19 @@ void oracle_bag_forward_cached(const void *table, int64_t num_rows, int32_t D, i
                                const int64_t *offsets, int64_t B, int64_t nnz, int32_t mode,
                                float *out, double *absum, uint64_t *hit_miss, uint32_t *status);
 
+/* Frequency-based cache policy for the hot-row cache ("caching strategies",
+ * Section 5; the paper names no policy, this is the reading built here).
+ * Access counters: freq[r] += 1 (u32, wrapping) for every entry of rows that is
+ * in [0, num_rows); returns the number of entries that are not. */
+int64_t oracle_cache_observe(uint32_t *freq, int64_t num_rows, const int64_t *rows, int64_t nnz);
+
+/* The hot set of a refresh: the num_hot rows with the largest counters, a tie
+ * going to the smaller row number, written in ascending row order to
+ * hot_rows_out; afterwards every counter is aged, freq[r] >>= decay_shift
+ * (0..31).  Returns 0, or -1 if memory could not be allocated. */
+int oracle_cache_select(uint32_t *freq, int64_t num_rows, int64_t num_hot, int32_t decay_shift,
+                        int64_t *hot_rows_out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -56,6 +56,10 @@ def lib() -> C.CDLL:
         L.oracle_bag_backward_rowwise_adagrad.restype = C.c_int
         L.oracle_bag_backward_rowwise_adagrad.argtypes = [
             vp, vp, i32, vp, i32, i32, vp, vp, i64, i64, i32, vp, f32, f32, vp, vp, vp, vp, vp, vp]
+        L.oracle_cache_observe.restype = i64
+        L.oracle_cache_observe.argtypes = [vp, i64, vp, i64]
+        L.oracle_cache_select.restype = C.c_int
+        L.oracle_cache_select.argtypes = [vp, i64, i64, i32, vp]
         L.oracle_bag_forward_cached.restype = None
         L.oracle_bag_forward_cached.argtypes = [vp, i64, i32, i32, vp, i64, vp, vp, i64, i64, i32,
                                                 vp, vp, vp, vp]
@@ -202,3 +206,20 @@ def bag_forward_cached(table: np.ndarray, dtype: str, hot_rows: np.ndarray, rows
                                     hot_rows.size, _p(rows), _p(offsets), B, rows.size, POOL[mode],
                                     _p(out), _p(absum), _p(hm), _p(status))
     return out, absum, (int(hm[0]), int(hm[1])), int(status[0])
+
+
+def cache_observe(freq: np.ndarray, rows: np.ndarray) -> int:
+    """freq (uint32 [R], updated in place) += 1 per in-range entry of rows; returns the number out of range."""
+    _chk(freq, np.uint32)
+    rows = _chk(np.ascontiguousarray(rows), np.int64)
+    return int(lib().oracle_cache_observe(_p(freq), freq.size, _p(rows), rows.size))
+
+
+def cache_select(freq: np.ndarray, num_hot: int, decay_shift: int = 0) -> np.ndarray:
+    """The num_hot rows with the largest counters (ties to the smaller row), ascending; freq is aged in place."""
+    _chk(freq, np.uint32)
+    assert 0 <= num_hot <= freq.size and 0 <= decay_shift <= 31
+    hot = np.empty(num_hot, dtype=np.int64)
+    rc = lib().oracle_cache_select(_p(freq), freq.size, num_hot, decay_shift, _p(hot))
+    assert rc == 0
+    return hot

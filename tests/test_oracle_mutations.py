@@ -56,6 +56,16 @@ MUTATIONS = [
     ("quant: row stride unpadded", "return (8 + code_bytes + 15) / 16 * 16;", "return 8 + code_bytes;"),
     ("quant: INT8 codes read as nibbles", "dtype == ORACLE_INT8 ? p[8 + d] :", "dtype != ORACLE_INT8 ? p[8 + d] :"),
     ("cached: hits and misses swapped", "hit_miss[hit ? 0 : 1] += 1;", "hit_miss[hit ? 1 : 0] += 1;"),
+    ("policy: counter incremented by two", "freq[r] += 1u;", "freq[r] += 2u;"),
+    ("policy: out-of-range entries not counted", "++bad;\n            continue;", "continue;"),
+    ("policy: smaller counters preferred", "if (fa != fb) return fa > fb ? -1 : 1;", "if (fa != fb) return fa > fb ? 1 : -1;"),
+    ("policy: ties go to the larger row", "return (ra > rb) - (ra < rb);", "return (ra < rb) - (ra > rb);"),
+    ("policy: ties broken arbitrarily", "return (ra > rb) - (ra < rb);", "return ((ra ^ 5) > (rb ^ 5)) - ((ra ^ 5) < (rb ^ 5));"),
+    ("policy: hot set left in preference order", "qsort(hot_rows_out, (size_t)num_hot, sizeof(int64_t), cmp_i64);", ""),
+    ("policy: aging dropped", "freq[r] >>= decay_shift;", ""),
+    ("policy: counters aged before the selection", "qsort(order, (size_t)num_rows, sizeof(int64_t), cmp_preference);",
+     "for (int64_t r = 0; r < num_rows; ++r) freq[r] >>= decay_shift;\n    qsort(order, (size_t)num_rows, sizeof(int64_t), cmp_preference);"),
+    ("policy: counters saturate at 2^31", "freq[r] += 1u;", "if (freq[r] < 0x80000000u) freq[r] += 1u;"),
 ]
 
 

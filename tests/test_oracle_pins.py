@@ -574,3 +574,88 @@ def test_quantized_forward_equals_fp32_forward_of_the_dequantized_table(oracle, 
     ref = torch.nn.functional.embedding_bag(torch.from_numpy(rows[:off[B]]), deq, torch.from_numpy(off[:B]),
                                             mode=mode, include_last_offset=False)
     assert np.allclose(o1[0], ref.numpy(), rtol=1e-6, atol=1e-9)
+
+
+# ---------------------------------------------------------------------------
+# frequency-based cache policy (which rows the hot-row cache of Section 3.3 holds; "caching strategies", Section 5)
+# ---------------------------------------------------------------------------
+
+def test_cache_observe_is_a_histogram_of_the_in_range_rows(oracle):
+    rng = np.random.default_rng(90)
+    R = 257
+    freq = rng.integers(0, 50, size=R).astype(np.uint32)
+    before = freq.copy()
+    rows = rng.integers(-40, R + 40, size=20000).astype(np.int64)
+    rows[:3000] = 7                                                  # one very hot row
+    bad = oracle.cache_observe(freq, rows)
+    ok = rows[(rows >= 0) & (rows < R)]
+    assert bad == rows.size - ok.size
+    assert np.array_equal(freq.astype(np.int64), before.astype(np.int64) + np.bincount(ok, minlength=R))
+    # counters are u32 and wrap
+    freq = np.array([0xFFFFFFFE, 5], dtype=np.uint32)
+    assert oracle.cache_observe(freq, np.array([0, 0, 0, 1], dtype=np.int64)) == 0
+    assert freq.tolist() == [1, 6]
+    # nothing observed, nothing changes
+    assert oracle.cache_observe(freq, np.zeros(0, np.int64)) == 0 and freq.tolist() == [1, 6]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_cache_select_equals_brute_force_on_small_inputs_with_many_ties(oracle, seed):
+    rng = np.random.default_rng(100 + seed)
+    R = int(rng.integers(1, 40))
+    freq = rng.integers(0, 4, size=R).astype(np.uint32)              # few distinct values: ties everywhere
+    if seed == 0:
+        freq[:] = 0xFFFFFFFF                                         # the largest counter value, all equal
+    for num_hot in sorted({0, 1, R // 3, R - 1 if R > 1 else 0, R}):
+        f = freq.copy()
+        hot = oracle.cache_select(f, num_hot, 0)
+        # plain statement of the rule: walk the rows by (larger counter, then smaller row) and keep num_hot
+        pref = sorted(range(R), key=lambda r: (-int(freq[r]), r))
+        assert hot.tolist() == sorted(pref[:num_hot])
+        assert np.array_equal(f, freq)                               # shift 0 leaves the counters alone
+
+
+def test_cache_select_invariants_and_aging(oracle):
+    rng = np.random.default_rng(110)
+    R, H = 5000, 600
+    freq = np.minimum(rng.zipf(1.3, size=R), 1 << 20).astype(np.uint32)
+    f = freq.copy()
+    hot = oracle.cache_select(f, H, 3)
+    assert hot.size == H and (np.diff(hot) > 0).all() and hot[0] >= 0 and hot[-1] < R
+    assert np.array_equal(f, freq >> 3)                              # every counter aged, selected or not
+    sel = np.zeros(R, bool)
+    sel[hot] = True
+    thr = freq[sel].min()
+    assert freq[~sel].max() <= thr                                   # nothing left out beats anything kept
+    tied = np.flatnonzero(freq == thr)                               # the tie at the threshold goes to small rows
+    kept = sel[tied]
+    assert not (~kept[:-1] & kept[1:]).any()
+    # distinct counters: the rule is a plain top-k (torch.topk as the library routine)
+    distinct = rng.permutation(R).astype(np.uint32) + 5
+    hot = oracle.cache_select(distinct.copy(), H, 0)
+    top = torch.topk(torch.from_numpy(distinct.astype(np.int64)), H).indices.numpy()
+    assert np.array_equal(hot, np.sort(top))
+    # all counters equal: the first rows
+    assert oracle.cache_select(np.full(R, 9, np.uint32), H, 0).tolist() == list(range(H))
+
+
+def test_cache_policy_keeps_the_set_with_the_most_hits_on_the_observed_stream(oracle):
+    # Observing a stream and selecting H rows must give the H-row set with the most hits on that same
+    # stream (no other set of that size can have more: its hits are a sum of H counters), as counted by
+    # the cached lookup's own hit accounting.
+    rng = np.random.default_rng(120)
+    R, D, B, H = 300, 4, 50, 25
+    table = rng.standard_normal((R, D)).astype(np.float32)
+    lengths = rng.integers(0, 30, size=B).astype(np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    rows = np.minimum(rng.zipf(1.2, size=int(off[-1])) - 1, R - 1).astype(np.int64)
+    freq = np.zeros(R, np.uint32)
+    assert oracle.cache_observe(freq, rows) == 0
+    counts = freq.copy()
+    hot = oracle.cache_select(freq, H, 0)
+    _, _, (hits, misses), st = oracle.bag_forward_cached(table, "f32", hot, rows, off, B, "sum")
+    assert st == 0 and hits + misses == rows.size
+    assert hits == int(np.sort(counts.astype(np.int64))[-H:].sum())
+    other = np.sort(rng.permutation(R)[:H]).astype(np.int64)
+    _, _, (hits2, _), _ = oracle.bag_forward_cached(table, "f32", other, rows, off, B, "sum")
+    assert hits2 <= hits
