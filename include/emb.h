@@ -378,6 +378,59 @@ int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_rows, int32
                                   float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
                                   void *stream);
 
+/* ---- which rows the cache holds: frequency-based policy -------------------
+ * Section 5 lists better caching strategies as open work and the paper names
+ * no policy; the one built here is frequency-based admission with batched
+ * refresh.  freq_dev is a u32 counter per table row (u32[num_rows], 16-byte
+ * aligned, owned and zeroed by the caller).  A refresh is emb_cache_select,
+ * then emb_cache_rebuild into a second pair of cache buffers, after which the
+ * caller passes the new pair to the lookups. */
+
+/* Count lookups: freq_dev[r] += 1 for every entry r of rows_dev (i64[nnz]) in
+ * [0, num_rows); other entries set EMB_STATUS_BAD_INDEX and count nowhere.
+ * Counters wrap at 2^32: age them (emb_cache_select's decay_shift) before any
+ * row has been looked up that often.  The _hashed form takes raw IDs and
+ * counts row splitmix64(raw XOR salt) mod num_rows (Section 2.2), as
+ * emb_bag_forward_cached_hashed resolves them. */
+int emb_cache_observe(int64_t num_rows, const int64_t *rows_dev, int64_t nnz, uint32_t *freq_dev,
+                      uint32_t *status_dev, void *stream);
+int emb_cache_observe_hashed(int64_t num_rows, uint64_t salt, const uint64_t *raw_dev, int64_t nnz,
+                             uint32_t *freq_dev, uint32_t *status_dev, void *stream);
+
+/* Device workspace emb_cache_select needs for a table of num_rows rows (about
+ * 6 bytes per 1024 rows). */
+int emb_cache_select_workspace_bytes(int64_t num_rows, size_t *bytes);
+
+/* Choose the hot set: the num_hot rows (0 <= num_hot <= num_rows) with the
+ * largest counters, a tie going to the smaller row number, written to
+ * hot_rows_out_dev (i64[num_hot]) in ascending row order, the form
+ * emb_cache_build takes.  Afterwards every counter is aged:
+ * freq_dev[r] >>= decay_shift (0..31; 0 leaves them).  Exact and
+ * deterministic.  workspace_dev: 256-byte aligned, at least
+ * emb_cache_select_workspace_bytes, contents irrelevant (EMB_ERR_WORKSPACE
+ * otherwise).  info_out_dev (nullable, u64[2], only written when num_hot > 0):
+ * [0] = the smallest counter value in the hot set, [1] = how many rows with
+ * exactly that value it holds.  Reads the counters six times and writes them
+ * once: 1 GB of counters (2.5e8 rows) takes a few milliseconds. */
+int emb_cache_select(uint32_t *freq_dev, int64_t num_rows, int64_t num_hot, int32_t decay_shift,
+                     void *workspace_dev, size_t workspace_bytes, int64_t *hot_rows_out_dev,
+                     uint64_t *info_out_dev, void *stream);
+
+/* emb_cache_build for a refresh: builds the cache for hot_rows_dev in
+ * cache_rows_dev / cache_index_dev, copying a row from the older cache
+ * (old_cache_rows_dev, old_cache_index_dev, old_num_hot: a cache of the same
+ * table, built earlier and still valid) when it is there, in HBM, and reading
+ * only the other rows from table_dev, over the link when the table is host
+ * memory.  The new buffers must not be the old ones (EMB_ERR_INVALID_ARG).
+ * moved_dev (nullable, u64[2], zeroed by the caller): [0] += rows taken from
+ * the older cache, [1] += rows read from the table.  Everything else as
+ * emb_cache_build. */
+int emb_cache_rebuild(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                      const void *old_cache_rows_dev, const void *old_cache_index_dev,
+                      int64_t old_num_hot, const int64_t *hot_rows_dev, int64_t num_hot,
+                      void *cache_rows_dev, void *cache_index_dev, uint64_t *moved_dev,
+                      uint32_t *status_dev, void *stream);
+
 /* Device-visible address of page-locked host memory that is mapped into the
  * device address space (hipHostMalloc / a pinned torch tensor): the pointer to
  * pass as table_dev above.  EMB_ERR_HIP if the memory is not mapped; nothing is

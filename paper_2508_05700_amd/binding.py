@@ -42,6 +42,7 @@ EXPORTS = [
     "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_host_device_pointer",
+    "emb_cache_observe", "emb_cache_observe_hashed", "emb_cache_select_workspace_bytes", "emb_cache_select", "emb_cache_rebuild",
     "emb_table_fill",
 ]
 
@@ -126,6 +127,16 @@ def lib() -> C.CDLL:
     L.emb_bag_forward_cached_hashed.restype = C.c_int
     L.emb_bag_forward_cached_hashed.argtypes = [vp, i64, i32, i32, vp, vp, i64, u64, vp, vp, i64, i64, i32, vp, vp, vp,
                                                 vp]
+    L.emb_cache_observe.restype = C.c_int
+    L.emb_cache_observe.argtypes = [i64, vp, i64, vp, vp, vp]
+    L.emb_cache_observe_hashed.restype = C.c_int
+    L.emb_cache_observe_hashed.argtypes = [i64, u64, vp, i64, vp, vp, vp]
+    L.emb_cache_select_workspace_bytes.restype = C.c_int
+    L.emb_cache_select_workspace_bytes.argtypes = [i64, C.POINTER(sz)]
+    L.emb_cache_select.restype = C.c_int
+    L.emb_cache_select.argtypes = [vp, i64, i64, i32, vp, sz, vp, vp, vp]
+    L.emb_cache_rebuild.restype = C.c_int
+    L.emb_cache_rebuild.argtypes = [vp, i64, i32, i32, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp]
     L.emb_host_device_pointer.restype = C.c_int
     L.emb_host_device_pointer.argtypes = [vp, C.POINTER(vp)]
     L.emb_table_fill.restype = C.c_int
@@ -530,6 +541,54 @@ def emb_bag_forward_cached_hashed(table_ptr: int, num_rows: int, D: int, dtype: 
         _ptr(cache_index, torch.uint8, "cache_index"), int(num_hot), C.c_uint64(int(salt) % (1 << 64)),
         _ptr(raw, _U64, "raw"), _ptr(offsets, torch.int64, "offsets"), int(B), raw.numel(), POOL[mode],
         _ptr(out, torch.float32, "out"), _ptr(hit_miss, _U64, "hit_miss"), _ptr(status, torch.int32, "status"),
+        _stream()))
+
+
+_U32 = (torch.int32, torch.uint32)
+
+
+def emb_cache_observe(num_rows: int, rows: torch.Tensor, freq: torch.Tensor,
+                      status: Optional[torch.Tensor] = None) -> None:
+    if freq.numel() != num_rows:
+        raise TypeError("freq must hold one counter per table row")
+    _check("emb_cache_observe", lib().emb_cache_observe(
+        int(num_rows), _ptr(rows, torch.int64, "rows"), rows.numel(), _ptr(freq, _U32, "freq"),
+        _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_cache_observe_hashed(num_rows: int, salt: int, raw: torch.Tensor, freq: torch.Tensor,
+                             status: Optional[torch.Tensor] = None) -> None:
+    if freq.numel() != num_rows:
+        raise TypeError("freq must hold one counter per table row")
+    _check("emb_cache_observe_hashed", lib().emb_cache_observe_hashed(
+        int(num_rows), C.c_uint64(int(salt) % (1 << 64)), _ptr(raw, _U64, "raw"), raw.numel(),
+        _ptr(freq, _U32, "freq"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_cache_select_workspace_bytes(num_rows: int) -> int:
+    out = C.c_size_t(0)
+    _check("emb_cache_select_workspace_bytes", lib().emb_cache_select_workspace_bytes(int(num_rows), C.byref(out)))
+    return int(out.value)
+
+
+def emb_cache_select(freq: torch.Tensor, num_hot: int, decay_shift: int, workspace: torch.Tensor,
+                     hot_rows_out: torch.Tensor, info_out: Optional[torch.Tensor] = None) -> None:
+    if hot_rows_out.numel() < num_hot:
+        raise TypeError("hot_rows_out too small")
+    _check("emb_cache_select", lib().emb_cache_select(
+        _ptr(freq, _U32, "freq"), freq.numel(), int(num_hot), int(decay_shift), _ptr(workspace, torch.uint8, "workspace"),
+        workspace.numel(), _ptr(hot_rows_out, torch.int64, "hot_rows_out"), _ptr(info_out, _U64, "info_out"), _stream()))
+
+
+def emb_cache_rebuild(table_ptr: int, num_rows: int, D: int, dtype: str, old_cache_rows: Optional[torch.Tensor],
+                      old_cache_index: torch.Tensor, old_num_hot: int, hot_rows: torch.Tensor,
+                      cache_rows: torch.Tensor, cache_index: torch.Tensor, moved: Optional[torch.Tensor] = None,
+                      status: Optional[torch.Tensor] = None) -> None:
+    _check("emb_cache_rebuild", lib().emb_cache_rebuild(
+        int(table_ptr), int(num_rows), int(D), DTYPE[dtype], _ptr(old_cache_rows, _TABLE_TORCH[dtype], "old_cache_rows"),
+        _ptr(old_cache_index, torch.uint8, "old_cache_index"), int(old_num_hot),
+        _ptr(hot_rows, torch.int64, "hot_rows"), hot_rows.numel(), _ptr(cache_rows, _TABLE_TORCH[dtype], "cache_rows"),
+        _ptr(cache_index, torch.uint8, "cache_index"), _ptr(moved, _U64, "moved"), _ptr(status, torch.int32, "status"),
         _stream()))
 
 

@@ -53,20 +53,56 @@ __global__ __launch_bounds__(CB_BLOCK) void cache_mark_kernel(const int64_t *__r
     if (prev < 0 || (prev >> 6) != (r >> 6)) e->before = (uint32_t)k;
 }
 
-// LPR lanes copy one hot row (16-byte chunks) from the table into the cache.
+// One thread per 16-byte chunk copies the hot rows into the cache.  With an
+// older cache at hand (a refresh), a row that it holds is taken from there, in
+// HBM, and only newly admitted rows are read from the table.  moved (nullable):
+// [0] += rows taken from the older cache, [1] += rows read from the table.
 __global__ __launch_bounds__(CB_BLOCK) void cache_copy_kernel(const char *__restrict__ table,
-                                                              const int64_t *__restrict__ hot, int64_t num_hot,
-                                                              int64_t num_rows, int32_t chunks_per_row,
-                                                              char *__restrict__ cache_rows)
+                                                              const char *__restrict__ old_rows,
+                                                              const CacheEntry *__restrict__ old_index,
+                                                              int64_t old_num_hot, const int64_t *__restrict__ hot,
+                                                              int64_t num_hot, int64_t num_rows, int32_t chunks_per_row,
+                                                              char *__restrict__ cache_rows, unsigned long long *moved)
 {
     const int64_t total = num_hot * chunks_per_row;
+    uint32_t kept = 0u, fetched = 0u;
     for (int64_t i = (int64_t)blockIdx.x * CB_BLOCK + threadIdx.x; i < total; i += (int64_t)gridDim.x * CB_BLOCK) {
         const int64_t k = i / chunks_per_row;
         const int64_t c = i - k * chunks_per_row;
         const int64_t r = hot[k];
         if (r < 0 || r >= num_rows) continue;
-        const uint4 v = *reinterpret_cast<const uint4 *>(table + (r * chunks_per_row + c) * 16);
+        const char *src = table + r * chunks_per_row * 16;
+        bool in_old = false;
+        if (old_index) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(old_index + (r >> 6));
+            const uint64_t bits = ((uint64_t)raw.y << 32) | raw.x;
+            const int bit = (int)(r & 63);
+            if ((bits >> bit) & 1ull) {
+                const int64_t slot = (int64_t)raw.z + __popcll(bits & ((1ull << bit) - 1ull));
+                if (slot < old_num_hot) {
+                    src = old_rows + slot * chunks_per_row * 16;
+                    in_old = true;
+                }
+            }
+        }
+        const uint4 v = *reinterpret_cast<const uint4 *>(src + c * 16);
         *reinterpret_cast<uint4 *>(cache_rows + i * 16) = v;
+        if (c == 0) {
+            kept += in_old ? 1u : 0u;
+            fetched += in_old ? 0u : 1u;
+        }
+    }
+    if (moved) {
+        // the loop has ended for every lane of the wavefront: reduce, then one atomic per wavefront
+#pragma unroll
+        for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) {
+            kept += __shfl_xor(kept, d, EMB_WAVE);
+            fetched += __shfl_xor(fetched, d, EMB_WAVE);
+        }
+        if ((threadIdx.x & (EMB_WAVE - 1)) == 0) {
+            if (kept) atomicAdd(&moved[0], (unsigned long long)kept);
+            if (fetched) atomicAdd(&moved[1], (unsigned long long)fetched);
+        }
     }
 }
 
@@ -250,9 +286,10 @@ extern "C" int emb_host_device_pointer(const void *host_ptr, void **dev_ptr_out)
     return EMB_OK;
 }
 
-extern "C" int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
-                               const int64_t *hot_rows_dev, int64_t num_hot, void *cache_rows_dev,
-                               void *cache_index_dev, uint32_t *status_dev, void *stream)
+static int cache_build_entry(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                             const void *old_rows_dev, const void *old_index_dev, int64_t old_num_hot,
+                             const int64_t *hot_rows_dev, int64_t num_hot, void *cache_rows_dev, void *cache_index_dev,
+                             uint64_t *moved_dev, uint32_t *status_dev, void *stream)
 {
     if (num_rows <= 0 || num_hot < 0 || num_hot > num_rows) return EMB_ERR_INVALID_ARG;
     int rc = cached_row_shape(D, dtype);
@@ -262,6 +299,13 @@ extern "C" int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t 
     if (!emb_aligned(table_dev, 16) || !emb_aligned(cache_index_dev, 16) || !emb_aligned(cache_rows_dev, 16))
         return EMB_ERR_INVALID_ARG;
     if (num_hot > (int64_t)0xFFFFFFFF) return EMB_ERR_UNSUPPORTED;
+    if (old_index_dev) {
+        // the older cache is read while the new one is written: they must be different buffers
+        if (old_num_hot < 0 || old_num_hot > num_rows || (old_num_hot > 0 && !old_rows_dev)) return EMB_ERR_INVALID_ARG;
+        if (!emb_aligned(old_index_dev, 16) || !emb_aligned(old_rows_dev, 16)) return EMB_ERR_INVALID_ARG;
+        if (old_index_dev == cache_index_dev || (old_rows_dev && old_rows_dev == cache_rows_dev))
+            return EMB_ERR_INVALID_ARG;
+    }
     hipStream_t s = emb_stream(stream);
     const int64_t entries = (num_rows + 63) / 64;
     const int64_t cblocks = (entries + CB_BLOCK - 1) / CB_BLOCK;
@@ -278,9 +322,29 @@ extern "C" int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t 
     int64_t want = (num_hot * chunks + CB_BLOCK - 1) / CB_BLOCK;
     unsigned grid = (unsigned)(want > 65536 ? 65536 : want);
     hipLaunchKernelGGL(cache_copy_kernel, dim3(grid), dim3(CB_BLOCK), 0, s, reinterpret_cast<const char *>(table_dev),
-                       hot_rows_dev, num_hot, num_rows, chunks, reinterpret_cast<char *>(cache_rows_dev));
+                       reinterpret_cast<const char *>(old_rows_dev), reinterpret_cast<const CacheEntry *>(old_index_dev),
+                       old_num_hot, hot_rows_dev, num_hot, num_rows, chunks, reinterpret_cast<char *>(cache_rows_dev),
+                       reinterpret_cast<unsigned long long *>(moved_dev));
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
+}
+
+extern "C" int emb_cache_build(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                               const int64_t *hot_rows_dev, int64_t num_hot, void *cache_rows_dev,
+                               void *cache_index_dev, uint32_t *status_dev, void *stream)
+{
+    return cache_build_entry(table_dev, num_rows, D, dtype, nullptr, nullptr, 0, hot_rows_dev, num_hot, cache_rows_dev,
+                             cache_index_dev, nullptr, status_dev, stream);
+}
+
+extern "C" int emb_cache_rebuild(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                                 const void *old_cache_rows_dev, const void *old_cache_index_dev, int64_t old_num_hot,
+                                 const int64_t *hot_rows_dev, int64_t num_hot, void *cache_rows_dev,
+                                 void *cache_index_dev, uint64_t *moved_dev, uint32_t *status_dev, void *stream)
+{
+    if (!old_cache_index_dev) return EMB_ERR_INVALID_ARG;
+    return cache_build_entry(table_dev, num_rows, D, dtype, old_cache_rows_dev, old_cache_index_dev, old_num_hot,
+                             hot_rows_dev, num_hot, cache_rows_dev, cache_index_dev, moved_dev, status_dev, stream);
 }
 
 static int cached_entry(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype, const void *cache_rows_dev,

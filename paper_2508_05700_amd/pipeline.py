@@ -178,3 +178,54 @@ def run_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffer
     if w.backward:
         run_backward(w, tables, rows, db, buf)
     return rows
+
+
+class HotRowCache:
+    """The HBM hot-row cache of one host-resident table together with the frequency-based policy that
+    decides what it holds: two cache buffers (the lookups read one while a refresh fills the other),
+    one access counter per table row, and the selection workspace.  Call sequencing only."""
+
+    def __init__(self, table_ptr: int, num_rows: int, D: int, dtype: str, num_hot: int, salt: int,
+                 device: torch.device, decay_shift: int = 1):
+        self.table_ptr, self.R, self.D, self.dtype, self.salt = int(table_ptr), int(num_rows), int(D), dtype, int(salt)
+        self.capacity, self.decay_shift = int(num_hot), int(decay_shift)
+        rowb = emb.emb_row_bytes(D, dtype)
+        shape = (self.capacity, rowb) if dtype in ("int8", "int4") else (self.capacity, D)
+        tdt = torch.uint8 if dtype in ("int8", "int4") else (torch.float32 if dtype == "f32" else torch.bfloat16)
+        self.rows = [torch.empty(shape, dtype=tdt, device=device) for _ in range(2)]
+        self.index = [torch.empty(emb.emb_cache_index_bytes(num_rows), dtype=torch.uint8, device=device)
+                      for _ in range(2)]
+        self.hot = torch.empty(max(self.capacity, 1), dtype=torch.int64, device=device)
+        self.freq = torch.zeros(num_rows, dtype=torch.int32, device=device)
+        self.workspace = torch.empty(emb.emb_cache_select_workspace_bytes(num_rows), dtype=torch.uint8, device=device)
+        self.info = torch.zeros(2, dtype=torch.int64, device=device)
+        self.moved = torch.zeros(2, dtype=torch.int64, device=device)
+        self.hit_miss = torch.zeros(2, dtype=torch.int64, device=device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
+        self.active = 0
+        self.num_hot = 0                                             # starts empty: every lookup is a miss
+        emb.emb_cache_build(self.table_ptr, self.R, D, dtype, self.hot[:0], self.rows[0], self.index[0], self.status)
+
+    def set_static(self, hot_rows: torch.Tensor) -> None:
+        """Load a given hot set (ascending rows) into the active buffers."""
+        self.num_hot = hot_rows.numel()
+        emb.emb_cache_build(self.table_ptr, self.R, self.D, self.dtype, hot_rows, self.rows[self.active],
+                            self.index[self.active], self.status)
+
+    def observe(self, raw: torch.Tensor) -> None:
+        emb.emb_cache_observe_hashed(self.R, self.salt, raw, self.freq, self.status)
+
+    def refresh(self) -> None:
+        """Select the most frequently looked-up rows and fill the idle buffers with them, taking the rows the
+        active cache already holds from HBM; then swap.  In stream order with the lookups."""
+        emb.emb_cache_select(self.freq, self.capacity, self.decay_shift, self.workspace, self.hot, self.info)
+        new = 1 - self.active
+        emb.emb_cache_rebuild(self.table_ptr, self.R, self.D, self.dtype, self.rows[self.active],
+                              self.index[self.active], self.num_hot, self.hot[:self.capacity], self.rows[new],
+                              self.index[new], self.moved, self.status)
+        self.active, self.num_hot = new, self.capacity
+
+    def forward_hashed(self, raw: torch.Tensor, offsets: torch.Tensor, B: int, mode: str, out: torch.Tensor) -> None:
+        emb.emb_bag_forward_cached_hashed(self.table_ptr, self.R, self.D, self.dtype, self.rows[self.active],
+                                          self.index[self.active], self.num_hot, self.salt, raw, offsets, B, mode, out,
+                                          self.hit_miss, self.status)

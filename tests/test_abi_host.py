@@ -267,6 +267,38 @@ def test_cache_argument_errors(L):
     assert L.emb_table_fill(FAKE, 10, 6, 0, 1, None) == UNSUPPORTED
 
 
+def test_cache_policy_argument_errors(L):
+    n = C.c_size_t(0)
+    assert L.emb_cache_select_workspace_bytes(250_000_000, C.byref(n)) == OK
+    assert 1 << 20 < n.value < 2 << 20 and n.value % 256 == 0       # a few bytes per thousand rows
+    small = C.c_size_t(0)
+    assert L.emb_cache_select_workspace_bytes(1, C.byref(small)) == OK and 0 < small.value < n.value
+    assert L.emb_cache_select_workspace_bytes(0, C.byref(n)) == INVALID
+    assert L.emb_cache_select_workspace_bytes(10, None) == INVALID
+    # nothing to count is not an error and launches nothing; bad sizes and null pointers are
+    assert L.emb_cache_observe(100, None, 0, None, None, None) == OK
+    assert L.emb_cache_observe(0, FAKE, 5, FAKE, None, None) == INVALID
+    assert L.emb_cache_observe(100, FAKE, -1, FAKE, None, None) == INVALID
+    assert L.emb_cache_observe(100, None, 5, FAKE, None, None) == INVALID
+    assert L.emb_cache_observe_hashed(100, 7, FAKE, 5, None, None, None) == INVALID
+    ws = small.value
+    assert L.emb_cache_select(FAKE, 100, 101, 0, FAKE, ws, FAKE, None, None) == INVALID     # more hot rows than rows
+    assert L.emb_cache_select(FAKE, 100, 10, 32, FAKE, ws, FAKE, None, None) == INVALID     # shift out of range
+    assert L.emb_cache_select(FAKE + 4, 100, 10, 0, FAKE, ws, FAKE, None, None) == INVALID  # counters misaligned
+    assert L.emb_cache_select(FAKE, 100, 10, 0, FAKE, ws, None, None, None) == INVALID
+    assert L.emb_cache_select(FAKE, 100, 10, 0, None, ws, FAKE, None, None) == WORKSPACE
+    assert L.emb_cache_select(FAKE, 100, 10, 0, FAKE, ws - 1, FAKE, None, None) == WORKSPACE
+    assert L.emb_cache_select(FAKE, 100, 10, 0, FAKE + 16, ws, FAKE, None, None) == WORKSPACE
+    # a refresh needs an older cache, in buffers other than the new ones
+    OLD = FAKE + 4096
+    assert L.emb_cache_rebuild(FAKE, 100, 64, 0, OLD, None, 5, FAKE, 10, FAKE, FAKE, None, None, None) == INVALID
+    assert L.emb_cache_rebuild(FAKE, 100, 64, 0, OLD, FAKE, 5, FAKE, 10, FAKE, FAKE, None, None, None) == INVALID
+    assert L.emb_cache_rebuild(FAKE, 100, 64, 0, FAKE, OLD, 5, FAKE, 10, FAKE, FAKE, None, None, None) == INVALID
+    assert L.emb_cache_rebuild(FAKE, 100, 64, 0, None, OLD, 5, FAKE, 10, FAKE, FAKE, None, None, None) == INVALID
+    assert L.emb_cache_rebuild(FAKE, 100, 64, 0, OLD, OLD, 101, FAKE, 10, FAKE, FAKE, None, None, None) == INVALID
+    assert L.emb_cache_rebuild(FAKE, 100, 6, 0, OLD, OLD, 5, FAKE, 10, FAKE, FAKE, None, None, None) == UNSUPPORTED
+
+
 def test_exact_remainder_on_the_host(tmp_path):
     exe = str(tmp_path / "u64mod_check")
     subprocess.check_call(["g++", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "paper_2508_05700_amd", "csrc"),

@@ -812,3 +812,199 @@ def test_table_fill_matches_the_host_generator(dtype):
     emb.emb_table_fill(w, R, D, dtype, 20250805123)
     torch.cuda.synchronize()
     assert np.array_equal(H.host_table(w), wl.dense_table(20250805123, R, D, dtype))
+
+
+# ---------------------------------------------------------------------------
+# frequency-based cache policy: counters, exact top-k selection, refresh
+# ---------------------------------------------------------------------------
+
+def _freq_dev(freq_np):
+    return torch.from_numpy(freq_np.view(np.int32).copy()).to(H.DEV)
+
+
+def _freq_host(freq_dev):
+    return freq_dev.cpu().numpy().view(np.uint32)
+
+
+def test_cache_observe_counts_like_the_oracle():
+    rng = np.random.default_rng(5000)
+    R = 70_001
+    freq = rng.integers(0, 9, size=R).astype(np.uint32)
+    freq[11] = 0xFFFFFFFE                                             # wraps
+    rows = np.minimum(rng.zipf(1.2, size=300_000) - 1, R - 1).astype(np.int64)
+    rows[:2000] = 11
+    rows[[5, 77]] = [-1, R]
+    fd = _freq_dev(freq)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_cache_observe(R, H.dev(rows), fd, status)
+    torch.cuda.synchronize()
+    ref = freq.copy()
+    assert oracle.cache_observe(ref, rows) == 2
+    assert status.item() == emb.STATUS_BAD_INDEX and np.array_equal(_freq_host(fd), ref)
+    # raw IDs: the row counted is the hashed one
+    raw = rng.integers(0, 1 << 64, size=50_000, dtype=np.uint64)
+    raw[:5000] = raw[0]
+    status.zero_()
+    emb.emb_cache_observe_hashed(R, 991, H.dev(raw), fd, status)
+    emb.emb_cache_observe(R, H.dev(rows[:0]), fd, status)             # nothing to count
+    torch.cuda.synchronize()
+    assert oracle.cache_observe(ref, oracle.hash_ids(raw, 991, R)) == 0
+    assert status.item() == 0 and np.array_equal(_freq_host(fd), ref)
+
+
+def _select_case(freq, num_hot, shift):
+    R = freq.size
+    fd = _freq_dev(freq)
+    ws = torch.empty(emb.emb_cache_select_workspace_bytes(R), dtype=torch.uint8, device=H.DEV)
+    ws.fill_(0xA5)                                                    # contents must not matter
+    hot = torch.full((max(num_hot, 1),), -9, dtype=torch.int64, device=H.DEV)
+    info = torch.full((2,), -9, dtype=torch.int64, device=H.DEV)
+    emb.emb_cache_select(fd, num_hot, shift, ws, hot, info)
+    torch.cuda.synchronize()
+    ref_f = freq.copy()
+    ref_hot = oracle.cache_select(ref_f, num_hot, shift)
+    what = "R=%d num_hot=%d shift=%d" % (R, num_hot, shift)
+    assert np.array_equal(hot.cpu().numpy()[:num_hot], ref_hot), what
+    assert np.array_equal(_freq_host(fd), ref_f), what
+    if num_hot > 0:
+        thr = int(freq[ref_hot].min())
+        assert info.cpu().tolist() == [thr, int((freq[ref_hot] == thr).sum())], what
+    else:
+        assert info.cpu().tolist() == [-9, -9] and hot.cpu().tolist() == [-9]
+
+
+@pytest.mark.parametrize("R", [1, 5, 4095, 4096, 4097, 100_003, 1_300_007])
+def test_cache_select_is_the_exact_top_k(R):
+    rng = np.random.default_rng(5100 + R % 97)
+    dists = {
+        "zeros": np.zeros(R, np.uint32),
+        "all max": np.full(R, 0xFFFFFFFF, np.uint32),
+        "few values": rng.integers(0, 3, size=R).astype(np.uint32),
+        "zipf": np.minimum(rng.zipf(1.1, size=R), 0xFFFFFFFF).astype(np.uint32),
+        "full range": rng.integers(0, 1 << 32, size=R, dtype=np.uint64).astype(np.uint32),
+        "high digits only": (rng.integers(0, 4, size=R).astype(np.uint32) << 24),
+    }
+    shifts = iter([0, 1, 31, 3, 0, 8, 0, 2])
+    for name, freq in dists.items():
+        for num_hot in sorted({0, 1, R // 20, R // 2, R - 1 if R > 1 else 0, R}):
+            if R > 200_000 and num_hot not in (R // 20, R):
+                continue                                              # the oracle sorts every row: keep it short
+            try:
+                shift = next(shifts)
+            except StopIteration:
+                shifts = iter([0, 1, 31, 3, 0, 8, 0, 2])
+                shift = next(shifts)
+            _select_case(freq, num_hot, shift)
+
+
+def test_cache_select_rejects_bad_arguments():
+    R = 1000
+    fd = torch.zeros(R, dtype=torch.int32, device=H.DEV)
+    ws = torch.empty(emb.emb_cache_select_workspace_bytes(R), dtype=torch.uint8, device=H.DEV)
+    hot = torch.empty(R + 1, dtype=torch.int64, device=H.DEV)
+    for args in ((R + 1, 0), (-1, 0), (5, 32), (5, -1)):
+        with pytest.raises(emb.EmbError) as e:
+            emb.emb_cache_select(fd, args[0], args[1], ws, hot)
+        assert e.value.code == -1
+    with pytest.raises(emb.EmbError) as e:
+        emb.emb_cache_select(fd, 5, 0, ws[:ws.numel() - 256], hot)
+    assert e.value.code == -3
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "int4"])
+def test_cache_rebuild_takes_kept_rows_from_the_old_cache(dtype):
+    rng = np.random.default_rng(5200)
+    R, D, B = 20_011, 64, 300
+    x = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+    table = x if dtype == "f32" else oracle.quantize_rows(x, dtype)
+    rb = emb.emb_row_bytes(D, dtype)
+    tdev = H.dev(table)
+    ptr = int(tdev.data_ptr())
+    hot_a = np.sort(rng.choice(R, size=1500, replace=False)).astype(np.int64)
+    hot_b = np.sort(np.concatenate([rng.choice(hot_a, size=900, replace=False),
+                                    rng.choice(np.setdiff1d(np.arange(R), hot_a), size=800, replace=False)])).astype(np.int64)
+    mk = (lambda n: torch.full((n, D), 7.0, dtype=torch.float32, device=H.DEV)) if dtype == "f32" else \
+         (lambda n: torch.full((n, rb), 0xEE, dtype=torch.uint8, device=H.DEV))
+    cache_a, cache_b = mk(hot_a.size), mk(hot_b.size)
+    idx_a = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+    idx_b = torch.empty_like(idx_a)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    moved = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    emb.emb_cache_build(ptr, R, D, dtype, H.dev(hot_a), cache_a, idx_a, status)
+    torch.cuda.synchronize()
+    # mark the old cache's copies (test only: a real table and its cache agree), so that where a row of the
+    # new cache came from shows in its bytes
+    marked = cache_a.clone()
+    if dtype == "f32":
+        marked += 1.0
+    else:
+        marked ^= 0xFF
+    emb.emb_cache_rebuild(ptr, R, D, dtype, marked, idx_a, hot_a.size, H.dev(hot_b), cache_b, idx_b, moved, status)
+    torch.cuda.synchronize()
+    kept = np.isin(hot_b, hot_a)
+    assert status.item() == 0 and moved.cpu().tolist() == [int(kept.sum()), int((~kept).sum())]
+    got = cache_b.cpu().numpy()
+    want = table[hot_b].copy()
+    slot_in_a = np.searchsorted(hot_a, hot_b[kept])
+    want[kept] = marked.cpu().numpy()[slot_in_a]
+    assert np.array_equal(got, want)
+    # a refresh without marking gives exactly what a build from the table gives, index included
+    emb.emb_cache_rebuild(ptr, R, D, dtype, cache_a, idx_a, hot_a.size, H.dev(hot_b), cache_b, idx_b, None, status)
+    cache_c, idx_c = mk(hot_b.size), torch.empty_like(idx_a)
+    emb.emb_cache_build(ptr, R, D, dtype, H.dev(hot_b), cache_c, idx_c, status)
+    torch.cuda.synchronize()
+    assert torch.equal(cache_b, cache_c) and torch.equal(idx_b, idx_c) and status.item() == 0
+    # an empty old cache: everything comes from the table; old and new buffers must differ
+    moved.zero_()
+    emb.emb_cache_build(ptr, R, D, dtype, H.dev(hot_a[:0]), cache_a, idx_a, status)
+    emb.emb_cache_rebuild(ptr, R, D, dtype, None, idx_a, 0, H.dev(hot_b), cache_b, idx_b, moved, status)
+    torch.cuda.synchronize()
+    assert moved.cpu().tolist() == [0, hot_b.size] and torch.equal(cache_b, cache_c)
+    with pytest.raises(emb.EmbError):
+        emb.emb_cache_rebuild(ptr, R, D, dtype, cache_b, idx_b, hot_b.size, H.dev(hot_b), cache_b, idx_c, None, status)
+    with pytest.raises(emb.EmbError):
+        emb.emb_cache_rebuild(ptr, R, D, dtype, cache_a, idx_b, hot_b.size, H.dev(hot_b), cache_b, idx_b, None, status)
+
+
+def test_cache_policy_loop_matches_the_oracle_step_by_step():
+    # a drifting Zipf stream of raw IDs: observe each batch, refresh every few batches; the hot set, the
+    # counters, hits and misses and the pooled output follow the oracle's at every step
+    from paper_2508_05700_amd import pipeline
+    rng = np.random.default_rng(5300)
+    R, D, B, Hn, salt = 40_009, 32, 200, 2000, 4242
+    table = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+    tdev = H.dev(table)
+    cache = pipeline.HotRowCache(int(tdev.data_ptr()), R, D, "f32", Hn, salt, torch.device(H.DEV), decay_shift=1)
+    freq = np.zeros(R, np.uint32)
+    hot = np.zeros(0, np.int64)
+    out = torch.empty((1, B, D), dtype=torch.float32, device=H.DEV)
+    perm = rng.permutation(1 << 20).astype(np.uint64)
+    for step in range(12):
+        if step == 6:
+            perm = rng.permutation(1 << 20).astype(np.uint64)       # popularity moves to other IDs
+        lengths = rng.integers(0, 60, size=B).astype(np.int32)
+        off, _ = oracle.lengths_to_offsets(lengths)
+        ranks = np.minimum(rng.zipf(1.15, size=int(off[-1])), (1 << 20) - 1)
+        raw = perm[ranks] * np.uint64(0x9E3779B97F4A7C15)
+        rows = oracle.hash_ids(raw, salt, R)
+        cache.hit_miss.zero_()
+        cache.forward_hashed(H.dev(raw), H.dev(off), B, "sum", out)
+        cache.observe(H.dev(raw))
+        ref, absum, (hits, misses), st = oracle.bag_forward_cached(table, "f32", hot, rows, off, B, "sum")
+        assert oracle.cache_observe(freq, rows) == 0
+        torch.cuda.synchronize()
+        assert cache.hit_miss.cpu().tolist() == [hits, misses], step
+        H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="policy loop step %d" % step)
+        if step % 3 == 2:
+            old = hot
+            cache.moved.zero_()
+            cache.refresh()
+            hot = oracle.cache_select(freq, Hn, 1)
+            torch.cuda.synchronize()
+            assert np.array_equal(cache.hot.cpu().numpy(), hot), step
+            assert np.array_equal(_freq_host(cache.freq), freq), step
+            kept = int(np.isin(hot, old).sum())
+            assert cache.moved.cpu().tolist() == [kept, Hn - kept], step
+            assert np.array_equal(cache.rows[cache.active].cpu().numpy(), table[hot])
+    assert cache.status.item() == 0 and hits > misses                # the learnt set serves most lookups
