@@ -261,6 +261,8 @@ def bench_hybrid(args) -> int:
     log("step %.3f ms: index %.3f, cached forward %.3f; hit rate %.2f %%; misses %.1f GB/s over PCIe "
         "(DMA copy from the same buffer: %.1f GB/s); HBM side %.0f GB/s" % (
             elapsed / K * 1e3, ms_index, ms_fwd, 100.0 * hits / max(1, hits + misses), pcie_gbs, dma_gbs, hbm_gbs))
+    policy = cache_policy_study(args, w, seed, ptr, store, n_hot, hot, dbs, offsets, out, W, K) \
+        if args.cache_policy == "dynamic" else None
     PCIE_PEAK = 64.0   # PCIe Gen5 x16, nominal, one direction
     out_json = {
         "metric": METRIC, "value": round(lookups / elapsed, 1), "unit": "lookups/s", "n_gpus": 1, "steps": K,
@@ -281,8 +283,124 @@ def bench_hybrid(args) -> int:
                      "dma_copy_same_buffer_GBps": round(dma_gbs, 1), "hbm_side_GBps": round(hbm_gbs, 1)},
         "cpu_baseline": None,
     }
+    if policy is not None:
+        out_json["cache_policy"] = policy
     print(json.dumps(out_json), flush=True)
     return 0
+
+
+def cache_policy_study(args, w, seed, ptr, store, n_hot, static_hot, dbs, offsets, out, W, K):
+    """The frequency-based policy against the static hot set of the benchmark, on the same batches: the
+    cache starts empty, watches a growing amount of traffic (lookups drawn like the batches'), and is
+    refreshed after each stage; then the popularity moves to other IDs and it has to follow.  Reports hit
+    rates, step times and what a refresh costs.  Not part of ``value``."""
+    import torch
+
+    from paper_2508_05700_amd import binding as emb
+    from paper_2508_05700_amd import pipeline, workloads as wl
+
+    dev = torch.device("cuda:0")
+    cache = pipeline.HotRowCache(ptr, w.R, w.D, store, n_hot, w.salt(0), dev, decay_shift=1)
+    status = cache.status
+    chunk = 10_000_000
+    next_chunk = [0]
+
+    def watch(n, s):
+        done = 0
+        while done < n:
+            m = min(chunk, n - done)
+            raw = torch.from_numpy(wl.traffic_raw_ids(w, 0, m, next_chunk[0], s).view("int64")).to(dev)
+            cache.observe(raw)
+            next_chunk[0] += 1
+            done += m
+        torch.cuda.synchronize()
+
+    def refresh():
+        ev = [emb.Event(timing=True) for _ in range(3)]
+        cache.moved.zero_()
+        ev[0].record()
+        emb.emb_cache_select(cache.freq, cache.capacity, cache.decay_shift, cache.workspace, cache.hot, cache.info)
+        ev[1].record()
+        new = 1 - cache.active
+        emb.emb_cache_rebuild(ptr, w.R, w.D, store, cache.rows[cache.active], cache.index[cache.active], cache.num_hot,
+                              cache.hot[:cache.capacity], cache.rows[new], cache.index[new], cache.moved, status)
+        ev[2].record()
+        cache.active, cache.num_hot = new, cache.capacity
+        torch.cuda.synchronize()
+        kept, fetched = [int(x) for x in cache.moved.cpu().tolist()]
+        thr, tied = [int(x) for x in cache.info.cpu().tolist()]
+        return {"select_ms": round(ev[0].elapsed_time(ev[1]), 3), "rebuild_ms": round(ev[1].elapsed_time(ev[2]), 3),
+                "rows_kept_in_hbm": kept, "rows_fetched_from_table": fetched, "threshold_count": thr,
+                "rows_at_threshold": tied}
+
+    def measure(batches, fwd):
+        """Hit rate and time per step of offsets + cached lookup over ``batches``."""
+        for i in range(W):
+            fwd(batches[i % len(batches)])
+        torch.cuda.synchronize()
+        cache.hit_miss.zero_()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(K):
+            fwd(batches[(W + k) % len(batches)])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        h, m = [int(x) for x in cache.hit_miss.cpu().tolist()]
+        return round(h / max(1, h + m), 5), round(dt / K * 1e3, 4)
+
+    def fwd_dynamic(db):
+        emb.emb_lengths_to_offsets(db.lengths, offsets, status)
+        cache.forward_hashed(db.raw, offsets, w.B, w.pool, out)
+
+    static_index = torch.empty_like(cache.index[0])
+    static_rows = torch.empty_like(cache.rows[0][:static_hot.numel()])
+    emb.emb_cache_build(ptr, w.R, w.D, store, static_hot, static_rows, static_index, status)
+
+    def fwd_static(db):
+        emb.emb_lengths_to_offsets(db.lengths, offsets, status)
+        emb.emb_bag_forward_cached_hashed(ptr, w.R, w.D, store, static_rows, static_index, static_hot.numel(), w.salt(0),
+                                          db.raw, offsets, w.B, w.pool, out, cache.hit_miss, status)
+
+    result = {"policy": "per-row u32 access counters; at a refresh the %d rows with the largest counters are kept "
+                        "(ties to the smaller row), counters halved" % n_hot, "stages": []}
+    hr, ms = measure(dbs, fwd_static)
+    result["static"] = {"hit_rate": hr, "ms_per_step": ms}
+    hr, ms = measure(dbs, fwd_dynamic)
+    result["stages"].append({"watched_lookups": 0, "hit_rate": hr, "ms_per_step": ms})
+    log("cache policy: static set %.2f %% hits (%.3f ms); empty cache %.2f %% (%.3f ms)" % (
+        100 * result["static"]["hit_rate"], result["static"]["ms_per_step"], 100 * hr, ms))
+    watched = 0
+    for target in [int(float(x)) for x in args.watch_lookups.split(",")]:
+        t0 = time.time()
+        watch(target - watched, seed)
+        watched = target
+        st = {"watched_lookups": watched}
+        st.update(refresh())
+        st["hit_rate"], st["ms_per_step"] = measure(dbs, fwd_dynamic)
+        result["stages"].append(st)
+        log("cache policy: %.0e lookups watched (%.0f s): %.2f %% hits, step %.3f ms; refresh = select %.2f ms + "
+            "rebuild %.2f ms (%d rows kept in HBM, %d fetched)" % (
+                watched, time.time() - t0, 100 * st["hit_rate"], st["ms_per_step"], st["select_ms"], st["rebuild_ms"],
+                st["rows_kept_in_hbm"], st["rows_fetched_from_table"]))
+    # popularity moves: the same law over other IDs (another seed gives another rank -> ID map)
+    seed2 = seed + 1
+    moved_batches = [pipeline.DeviceBatch(w, wl.make_batch(w, i, seed2), dev) for i in range(len(dbs))]
+    drift = {"static": dict(zip(("hit_rate", "ms_per_step"), measure(moved_batches, fwd_static))),
+             "before_refresh": dict(zip(("hit_rate", "ms_per_step"), measure(moved_batches, fwd_dynamic))), "stages": []}
+    watched = 0
+    for target in [int(float(x)) for x in args.watch_lookups.split(",")][:2]:
+        watch(target - watched, seed2)
+        watched = target
+        st = {"watched_lookups": watched}
+        st.update(refresh())
+        st["hit_rate"], st["ms_per_step"] = measure(moved_batches, fwd_dynamic)
+        drift["stages"].append(st)
+    result["after_popularity_moved"] = drift
+    log("cache policy, popularity moved: static set %.2f %% hits, dynamic before refresh %.2f %%, after %s" % (
+        100 * drift["static"]["hit_rate"], 100 * drift["before_refresh"]["hit_rate"],
+        ", ".join("%.0e lookups: %.2f %%" % (s["watched_lookups"], 100 * s["hit_rate"]) for s in drift["stages"])))
+    assert int(status.item()) == 0
+    return result
 
 
 def bench_mixed(args) -> int:
@@ -372,6 +490,10 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--scale-rows", type=int, default=None, help="rows per table (debug: smaller tables)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cache-policy", choices=["static", "dynamic"], default="static",
+                    help="workloads 5/5q4: 'dynamic' adds the study of the frequency-based cache policy")
+    ap.add_argument("--watch-lookups", default="1e6,1e7,1e8",
+                    help="cumulative lookups the dynamic policy has watched at each refresh")
     ap.add_argument("--no-extra", action="store_true", help="skip the forward-only side measurements")
     ap.add_argument("--no-fused-forward", action="store_true",
                     help="hash the IDs in a kernel of their own instead of inside the forward lookup")

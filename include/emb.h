@@ -76,6 +76,7 @@ typedef enum { EMB_F32 = 0, EMB_BF16 = 1, EMB_INT8 = 2, EMB_INT4 = 3 } emb_dtype
 #define EMB_STATUS_BAD_INDEX 1u   /* a row index < 0 or >= num_rows of its table */
 #define EMB_STATUS_BAD_OFFSETS 2u /* a negative length, or offsets not 0 <= s <= e <= nnz */
 #define EMB_STATUS_BAD_HOT_SET 4u /* hot rows not strictly ascending / out of range */
+#define EMB_STATUS_NO_VERSION 8u  /* a lookup latched a handle with no (matching) version published */
 
 /* One embedding table.  The same array of T descriptors is passed twice to
  * the multi-table calls: in host memory (read for validation) and in device
@@ -430,6 +431,59 @@ int emb_cache_rebuild(const void *table_dev, int64_t num_rows, int32_t D, int32_
                       int64_t old_num_hot, const int64_t *hot_rows_dev, int64_t num_hot,
                       void *cache_rows_dev, void *cache_index_dev, uint64_t *moved_dev,
                       uint32_t *status_dev, void *stream);
+
+/* ---- version-tagged table sets (Section 3.3, Algorithms 1 and 2) ----------
+ * A request must be served by tables and an upper model of one version, and a
+ * new version is brought up beside the old one before traffic moves to it.
+ * The data-plane part: a lookup returns (E, V), with E computed wholly from the
+ * tables of version V.
+ *   record  device memory (emb_version_record_bytes, 16-byte aligned, caller's):
+ *           version number + the T descriptors of that version's tables;
+ *           immutable once published;
+ *   handle  one u64 in device memory (8-byte aligned, caller's, zero = nothing
+ *           published) holding the address of the current record;
+ *   latch   device memory owned by one lookup (emb_version_latch_bytes, 16-byte
+ *           aligned): starts with u64 version, u64 T; receives a copy of the
+ *           record that was current when the lookup's latch ran.
+ * A record and its tables must stay as they are until every lookup that
+ * latched them has finished; retiring a version (Algorithm 1, last phase) is
+ * the caller's step after synchronising with those lookups. */
+int emb_version_record_bytes(int32_t T, size_t *bytes);
+int emb_version_latch_bytes(int32_t T, size_t *bytes);
+
+/* Fill a record: validates the descriptors as emb_bag_forward does
+ * (tables_host), copies tables_dev and the version (non-zero) into record_dev,
+ * in stream order. */
+int emb_version_record_write(void *record_dev, const emb_table *tables_host,
+                             const emb_table *tables_dev, int32_t T, uint64_t version,
+                             void *stream);
+
+/* Make record_dev the current version: one atomic 64-bit store to *handle_dev,
+ * in stream order (after the record's write when both are on one stream;
+ * otherwise the caller orders them).  Lookups that latched earlier keep the
+ * version they latched. */
+int emb_version_publish(uint64_t *handle_dev, const void *record_dev, void *stream);
+
+/* Copy the current record into latch_dev: one atomic load of the handle, then
+ * the copy, by one workgroup.  If nothing is published, or the record is for
+ * another T, EMB_STATUS_NO_VERSION is set, the latched version is 0 and the
+ * latched descriptors are T one-row tables of zeros, so that a lookup over them
+ * is harmless and returns zeros. */
+int emb_version_latch(const uint64_t *handle_dev, int32_t T, void *latch_dev,
+                      uint32_t *status_dev, void *stream);
+
+/* emb_bag_forward / emb_bag_forward_hashed over the tables latched in
+ * latch_dev; the version the result belongs to is the u64 at latch_dev.  D and
+ * dtype are the same for every version of a table set; the number of rows may
+ * differ between versions.  Errors as for those calls. */
+int emb_bag_forward_latched(const void *latch_dev, int32_t T, int32_t D, int32_t dtype,
+                            const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B,
+                            int64_t nnz, int32_t mode, float *out_dev, uint32_t *status_dev,
+                            void *stream);
+int emb_bag_forward_latched_hashed(const void *latch_dev, int32_t T, int32_t D, int32_t dtype,
+                                   const uint64_t *raw_dev, const int64_t *offsets_dev, int64_t B,
+                                   int64_t nnz, int32_t mode, float *out_dev,
+                                   uint32_t *status_dev, void *stream);
 
 /* Device-visible address of page-locked host memory that is mapped into the
  * device address space (hipHostMalloc / a pinned torch tensor): the pointer to

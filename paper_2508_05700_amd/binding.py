@@ -23,6 +23,7 @@ ROWS_STREAMING = 0x100   # hint bit for the forward lookups (EMB_ROWS_STREAMING)
 STATUS_BAD_INDEX = 1
 STATUS_BAD_OFFSETS = 2
 STATUS_BAD_HOT_SET = 4
+STATUS_NO_VERSION = 8
 BWD_STAGE_EVENTS = 6
 
 # numpy mirror of ``struct emb_table``
@@ -42,6 +43,8 @@ EXPORTS = [
     "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_host_device_pointer",
+    "emb_version_record_bytes", "emb_version_latch_bytes", "emb_version_record_write", "emb_version_publish",
+    "emb_version_latch", "emb_bag_forward_latched", "emb_bag_forward_latched_hashed",
     "emb_cache_observe", "emb_cache_observe_hashed", "emb_cache_select_workspace_bytes", "emb_cache_select", "emb_cache_rebuild",
     "emb_table_fill",
 ]
@@ -137,6 +140,20 @@ def lib() -> C.CDLL:
     L.emb_cache_select.argtypes = [vp, i64, i64, i32, vp, sz, vp, vp, vp]
     L.emb_cache_rebuild.restype = C.c_int
     L.emb_cache_rebuild.argtypes = [vp, i64, i32, i32, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp]
+    L.emb_version_record_bytes.restype = C.c_int
+    L.emb_version_record_bytes.argtypes = [i32, C.POINTER(sz)]
+    L.emb_version_latch_bytes.restype = C.c_int
+    L.emb_version_latch_bytes.argtypes = [i32, C.POINTER(sz)]
+    L.emb_version_record_write.restype = C.c_int
+    L.emb_version_record_write.argtypes = [vp, vp, vp, i32, u64, vp]
+    L.emb_version_publish.restype = C.c_int
+    L.emb_version_publish.argtypes = [vp, vp, vp]
+    L.emb_version_latch.restype = C.c_int
+    L.emb_version_latch.argtypes = [vp, i32, vp, vp, vp]
+    L.emb_bag_forward_latched.restype = C.c_int
+    L.emb_bag_forward_latched.argtypes = [vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp]
+    L.emb_bag_forward_latched_hashed.restype = C.c_int
+    L.emb_bag_forward_latched_hashed.argtypes = [vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp]
     L.emb_host_device_pointer.restype = C.c_int
     L.emb_host_device_pointer.argtypes = [vp, C.POINTER(vp)]
     L.emb_table_fill.restype = C.c_int
@@ -590,6 +607,70 @@ def emb_cache_rebuild(table_ptr: int, num_rows: int, D: int, dtype: str, old_cac
         _ptr(hot_rows, torch.int64, "hot_rows"), hot_rows.numel(), _ptr(cache_rows, _TABLE_TORCH[dtype], "cache_rows"),
         _ptr(cache_index, torch.uint8, "cache_index"), _ptr(moved, _U64, "moved"), _ptr(status, torch.int32, "status"),
         _stream()))
+
+
+def emb_version_record_bytes(T: int) -> int:
+    out = C.c_size_t(0)
+    _check("emb_version_record_bytes", lib().emb_version_record_bytes(int(T), C.byref(out)))
+    return int(out.value)
+
+
+def emb_version_latch_bytes(T: int) -> int:
+    out = C.c_size_t(0)
+    _check("emb_version_latch_bytes", lib().emb_version_latch_bytes(int(T), C.byref(out)))
+    return int(out.value)
+
+
+def emb_version_record_write(record: torch.Tensor, tables: "TableSet", version: int) -> None:
+    if record.numel() < emb_version_record_bytes(tables.T):
+        raise TypeError("record too small")
+    _check("emb_version_record_write", lib().emb_version_record_write(
+        _ptr(record, torch.uint8, "record"), tables.host_ptr, tables.dev_ptr, tables.T,
+        C.c_uint64(int(version)), _stream()))
+
+
+def emb_version_publish(handle: torch.Tensor, record: torch.Tensor) -> None:
+    _check("emb_version_publish", lib().emb_version_publish(
+        _ptr(handle, _U64, "handle"), _ptr(record, torch.uint8, "record"), _stream()))
+
+
+def emb_version_latch(handle: torch.Tensor, T: int, latch: torch.Tensor,
+                      status: Optional[torch.Tensor] = None) -> None:
+    if latch.numel() < emb_version_latch_bytes(T):
+        raise TypeError("latch too small")
+    _check("emb_version_latch", lib().emb_version_latch(
+        _ptr(handle, _U64, "handle"), int(T), _ptr(latch, torch.uint8, "latch"), _ptr(status, torch.int32, "status"),
+        _stream()))
+
+
+def latched_version(latch: torch.Tensor) -> torch.Tensor:
+    """The u64 version number at the start of a latch, as a one-element int64 view (device tensor)."""
+    return latch[:8].view(torch.int64)
+
+
+def _forward_latched(fn: str, latch, T, D, dtype, ids, id_dtype, offsets, B, mode, out, status, streaming):
+    if latch.numel() < emb_version_latch_bytes(T):
+        raise TypeError("latch too small")
+    if offsets.numel() != T * B + 1 or out.numel() != T * B * D:
+        raise TypeError("shape mismatch")
+    _check(fn, getattr(lib(), fn)(
+        _ptr(latch, torch.uint8, "latch"), int(T), int(D), DTYPE[dtype], _ptr(ids, id_dtype, "ids"),
+        _ptr(offsets, torch.int64, "offsets"), int(B), ids.numel(), POOL[mode] | (ROWS_STREAMING if streaming else 0),
+        _ptr(out, torch.float32, "out"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_bag_forward_latched(latch: torch.Tensor, T: int, D: int, dtype: str, rows: torch.Tensor, offsets: torch.Tensor,
+                            B: int, mode: str, out: torch.Tensor, status: Optional[torch.Tensor] = None,
+                            streaming: bool = False) -> None:
+    _forward_latched("emb_bag_forward_latched", latch, T, D, dtype, rows, torch.int64, offsets, B, mode, out, status,
+                     streaming)
+
+
+def emb_bag_forward_latched_hashed(latch: torch.Tensor, T: int, D: int, dtype: str, raw: torch.Tensor,
+                                   offsets: torch.Tensor, B: int, mode: str, out: torch.Tensor,
+                                   status: Optional[torch.Tensor] = None, streaming: bool = False) -> None:
+    _forward_latched("emb_bag_forward_latched_hashed", latch, T, D, dtype, raw, _U64, offsets, B, mode, out, status,
+                     streaming)
 
 
 def emb_host_device_pointer(host_ptr: int) -> int:

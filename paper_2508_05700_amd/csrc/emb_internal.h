@@ -44,6 +44,12 @@ int emb_forward_quant(const emb_table *tables_dev, int32_t T, int32_t D, int32_t
                       const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
                       uint32_t *status_dev, hipStream_t s);
 
+// emb_bag_forward / emb_bag_forward_hashed over descriptors that exist in device memory only and were
+// validated earlier (the latched copy of a version record; versioned.hip).
+int emb_forward_unchecked_tables(const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, const int64_t *ids_dev,
+                                 const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                                 uint32_t *status_dev, void *stream, bool hashed);
+
 // Row shape accepted by the gather kernels: whole 16-byte chunks, at most 1024 of them.
 // Quantised rows are read by the forward lookup only.
 static inline int emb_check_row_shape(int32_t D, int32_t dtype)

@@ -135,10 +135,11 @@ int launch_forward(bool bf16, int32_t T, hipStream_t s, const emb_table *tables,
 
 }  // namespace
 
+// check_tables = false: the descriptors were validated when their version record was written.
 static int forward_entry(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
                          int32_t dtype, const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
                          int32_t mode, float *out_dev, uint32_t *status_dev, void *stream, bool hashed,
-                         int64_t *rows_out_dev)
+                         int64_t *rows_out_dev, bool check_tables = true)
 {
     if (B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
     const bool streaming = (mode & EMB_ROWS_STREAMING) != 0;
@@ -147,8 +148,12 @@ static int forward_entry(const emb_table *tables_host, const emb_table *tables_d
     const bool quant = dtype == EMB_INT8 || dtype == EMB_INT4;
     int rc = quant ? emb_check_quant_shape(D, dtype) : emb_check_row_shape(D, dtype);
     if (rc != EMB_OK) return rc;
-    rc = emb_check_tables(tables_host, tables_dev, T, false);
-    if (rc != EMB_OK) return rc;
+    if (check_tables) {
+        rc = emb_check_tables(tables_host, tables_dev, T, false);
+        if (rc != EMB_OK) return rc;
+    } else if (T < 0 || (T > 0 && !tables_dev)) {
+        return EMB_ERR_INVALID_ARG;
+    }
     if (T == 0 || B == 0) return EMB_OK;
     if (T > 65535) return EMB_ERR_UNSUPPORTED;
     if (!offsets_dev || !out_dev || (nnz > 0 && !rows_dev)) return EMB_ERR_INVALID_ARG;
@@ -203,4 +208,12 @@ extern "C" int emb_bag_forward_hashed(const emb_table *tables_host, const emb_ta
 {
     return forward_entry(tables_host, tables_dev, T, D, dtype, reinterpret_cast<const int64_t *>(raw_dev), offsets_dev,
                          B, nnz, mode, out_dev, status_dev, stream, true, rows_out_dev);
+}
+
+int emb_forward_unchecked_tables(const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, const int64_t *ids_dev,
+                                 const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                                 uint32_t *status_dev, void *stream, bool hashed)
+{
+    return forward_entry(nullptr, tables_dev, T, D, dtype, ids_dev, offsets_dev, B, nnz, mode, out_dev, status_dev,
+                         stream, hashed, nullptr, false);
 }

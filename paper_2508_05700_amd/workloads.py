@@ -346,6 +346,14 @@ def make_batch(w: Workload, batch_index: int = 0, seed: int = DEFAULT_SEED) -> D
     return batch
 
 
+def traffic_raw_ids(w: Workload, t: int, n: int, chunk_index: int, seed: int = DEFAULT_SEED) -> np.ndarray:
+    """``n`` raw IDs of table ``t`` drawn like the lookups of a batch (same Zipf law, same rank -> ID map), as
+    one flat stream: the traffic a cache policy watches between refreshes."""
+    assert w.ids == "zipf"
+    ranks = zipf_for(w).sample(_rng(seed, 3, t, chunk_index), n)
+    return ranks_to_raw_ids(ranks, _stream_key(seed, t))
+
+
 def hot_raw_ids(w: Workload, t: int, n_ranks: int, seed: int = DEFAULT_SEED) -> np.ndarray:
     """Raw IDs of Zipf ranks 1..n_ranks of table ``t`` (most popular first)."""
     ranks = np.arange(1, n_ranks + 1, dtype=np.int64)

@@ -299,6 +299,35 @@ def test_cache_policy_argument_errors(L):
     assert L.emb_cache_rebuild(FAKE, 100, 6, 0, OLD, OLD, 5, FAKE, 10, FAKE, FAKE, None, None, None) == UNSUPPORTED
 
 
+def test_versioned_tables_argument_errors(L):
+    n, m = C.c_size_t(0), C.c_size_t(0)
+    assert L.emb_version_record_bytes(16, C.byref(n)) == OK and n.value == 16 + 16 * b.TABLE_DESC.itemsize
+    assert L.emb_version_latch_bytes(16, C.byref(m)) == OK and m.value == n.value + 16384
+    assert L.emb_version_record_bytes(0, C.byref(n)) == INVALID and L.emb_version_latch_bytes(3, None) == INVALID
+    tabs = _tables()
+    th = tabs.ctypes.data
+    assert L.emb_version_record_write(None, th, FAKE, 2, 7, None) == INVALID
+    assert L.emb_version_record_write(FAKE, th, FAKE, 2, 0, None) == INVALID          # version 0 means "none"
+    assert L.emb_version_record_write(FAKE + 8, th, FAKE, 2, 7, None) == INVALID      # misaligned record
+    assert L.emb_version_record_write(FAKE, None, FAKE, 2, 7, None) == INVALID        # descriptors are validated here
+    bad = tabs.copy()
+    bad["mod_magic"][1] += 1
+    assert L.emb_version_record_write(FAKE, bad.ctypes.data, FAKE, 2, 7, None) == INVALID
+    assert L.emb_version_publish(None, FAKE, None) == INVALID and L.emb_version_publish(FAKE, None, None) == INVALID
+    assert L.emb_version_publish(FAKE + 4, FAKE, None) == INVALID
+    assert L.emb_version_latch(None, 2, FAKE, None, None) == INVALID
+    assert L.emb_version_latch(FAKE, 0, FAKE, None, None) == INVALID
+    assert L.emb_version_latch(FAKE, 2, None, None, None) == INVALID
+    for fn in (L.emb_bag_forward_latched, L.emb_bag_forward_latched_hashed):
+        assert fn(None, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None) == INVALID
+        assert fn(FAKE, 0, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None) == INVALID
+        assert fn(FAKE, 2, 6, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None) == UNSUPPORTED
+        assert fn(FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 7, FAKE, None, None) == INVALID   # pooling mode
+        assert fn(FAKE, 2, 64, 0, FAKE, None, 4, 8, 0, FAKE, None, None) == INVALID
+        assert fn(FAKE, 2, 64, 0, FAKE, FAKE, 0, 0, 0, FAKE, None, None) == OK        # no bags: nothing launched
+    assert L.emb_bag_forward_latched_hashed(FAKE, 2, 64, 3, FAKE, FAKE, 4, 8, 0, FAKE, None, None) == UNSUPPORTED
+
+
 def test_exact_remainder_on_the_host(tmp_path):
     exe = str(tmp_path / "u64mod_check")
     subprocess.check_call(["g++", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "paper_2508_05700_amd", "csrc"),

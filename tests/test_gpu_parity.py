@@ -1008,3 +1008,113 @@ def test_cache_policy_loop_matches_the_oracle_step_by_step():
             assert cache.moved.cpu().tolist() == [kept, Hn - kept], step
             assert np.array_equal(cache.rows[cache.active].cpu().numpy(), table[hot])
     assert cache.status.item() == 0 and hits > misses                # the learnt set serves most lookups
+
+
+# ---------------------------------------------------------------------------
+# version-tagged table sets: a lookup returns (E, V), E wholly from version V
+# ---------------------------------------------------------------------------
+
+def _version_case(rng, T, B, D, dtype="f32"):
+    Rs = {1: [900, 3000, 77], 2: [1200, 500, 4000]}                   # row counts differ between versions
+    out = {}
+    for v, rs in Rs.items():
+        tabs = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in rs[:T]]
+        if dtype in ("int8", "int4"):
+            tabs = [oracle.quantize_rows(x, dtype) for x in tabs]
+        w = [H.dev(t) for t in tabs]
+        ts = emb.TableSet(w, D, dtype, salts=[11 * v + t for t in range(T)], device=torch.device(H.DEV))
+        rec = torch.empty(emb.emb_version_record_bytes(T), dtype=torch.uint8, device=H.DEV)
+        emb.emb_version_record_write(rec, ts, 100 + v)
+        out[v] = {"np": tabs, "ts": ts, "rec": rec, "Rs": rs[:T], "salts": [11 * v + t for t in range(T)], "keep": w}
+    return out
+
+
+def _oracle_hashed(ver, D, raw, off, B, T, mode):
+    rows = np.concatenate([oracle.hash_ids(raw[off[t * B]:off[(t + 1) * B]], ver["salts"][t], ver["Rs"][t])
+                           for t in range(T)])
+    return oracle.bag_forward(ver["np"], "f32", rows, off, B, mode)
+
+
+def test_versioned_lookup_returns_the_latched_version_whatever_is_published_meanwhile():
+    rng = np.random.default_rng(6000)
+    T, B, D = 3, 120, 32
+    vers = _version_case(rng, T, B, D)
+    lengths = rng.integers(0, 30, size=T * B).astype(np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    raw = rng.integers(0, 1 << 64, size=int(off[-1]), dtype=np.uint64)
+    raw_d, off_d = H.dev(raw), H.dev(off)
+    handle = torch.zeros(1, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    latch = torch.empty(emb.emb_version_latch_bytes(T), dtype=torch.uint8, device=H.DEV)
+    out = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+
+    def lookup():
+        emb.emb_version_latch(handle, T, latch, status)
+        emb.emb_bag_forward_latched_hashed(latch, T, D, "f32", raw_d, off_d, B, "mean", out, status)
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), int(emb.latched_version(latch).item())
+
+    # nothing published: version 0, zeros, a status bit, no fault
+    E, V = lookup()
+    assert V == 0 and status.item() == emb.STATUS_NO_VERSION and not E.any()
+    status.zero_()
+    for v in (1, 2, 1):                                               # and back: a rollback is a publish too
+        emb.emb_version_publish(handle, vers[v]["rec"])
+        E, V = lookup()
+        ref, absum, st = _oracle_hashed(vers[v], D, raw, off, B, T, "mean")
+        assert V == 100 + v and status.item() == 0 == st
+        H.assert_pooled_close(E, ref, absum, what="version %d" % v)
+    # a latch taken under version 1 keeps serving version 1 after version 2 is published, on another stream,
+    # before the lookup's own kernel runs
+    other = torch.cuda.Stream(device=H.DEV)
+    emb.emb_version_latch(handle, T, latch, status)
+    latched = torch.cuda.Event()
+    latched.record()
+    with torch.cuda.stream(other):
+        other.wait_event(latched)
+        emb.emb_version_publish(handle, vers[2]["rec"])
+        published = torch.cuda.Event()
+        published.record()
+    torch.cuda.current_stream().wait_event(published)
+    emb.emb_bag_forward_latched_hashed(latch, T, D, "f32", raw_d, off_d, B, "mean", out, status)
+    torch.cuda.synchronize()
+    ref1, absum1, _ = _oracle_hashed(vers[1], D, raw, off, B, T, "mean")
+    assert int(emb.latched_version(latch).item()) == 101
+    H.assert_pooled_close(out.cpu().numpy(), ref1, absum1, what="latched before the publish")
+    E, V = lookup()                                                   # the next lookup sees version 2
+    ref2, absum2, _ = _oracle_hashed(vers[2], D, raw, off, B, T, "mean")
+    assert V == 102
+    H.assert_pooled_close(E, ref2, absum2, what="after the publish")
+    # a record for another number of tables is refused by the latch, harmlessly
+    rec1 = torch.empty(emb.emb_version_record_bytes(1), dtype=torch.uint8, device=H.DEV)
+    ts1 = emb.TableSet([vers[1]["keep"][0]], D, "f32", salts=[5], device=torch.device(H.DEV))
+    emb.emb_version_record_write(rec1, ts1, 55)
+    emb.emb_version_publish(handle, rec1)
+    E, V = lookup()
+    assert V == 0 and status.item() == emb.STATUS_NO_VERSION and not E.any()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "int4"])
+def test_versioned_lookup_by_row_number(dtype):
+    rng = np.random.default_rng(6100)
+    T, B, D = 2, 90, 64
+    vers = _version_case(rng, T, B, D, dtype)
+    lengths = rng.integers(0, 25, size=T * B).astype(np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    handle = torch.zeros(1, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    latch = torch.empty(emb.emb_version_latch_bytes(T), dtype=torch.uint8, device=H.DEV)
+    out = torch.empty((T, B, D), dtype=torch.float32, device=H.DEV)
+    for v in (2, 1):
+        Rs = vers[v]["Rs"]
+        rows = np.concatenate([rng.integers(0, Rs[t], size=int(off[(t + 1) * B] - off[t * B])) for t in range(T)]).astype(np.int64)
+        emb.emb_version_publish(handle, vers[v]["rec"])
+        emb.emb_version_latch(handle, T, latch, status)
+        emb.emb_bag_forward_latched(latch, T, D, dtype, H.dev(rows), H.dev(off), B, "sum", out, status)
+        torch.cuda.synchronize()
+        ref, absum, st = oracle.bag_forward(vers[v]["np"], dtype, rows, off, B, "sum", D=D if dtype != "f32" else None)
+        assert int(emb.latched_version(latch).item()) == 100 + v and status.item() == 0 == st
+        H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="rows, version %d" % v)
+        # same bits as the plain lookup over that version's descriptors
+        plain, _ = H.gpu_forward(vers[v]["ts"], rows, off, B, "sum")
+        assert np.array_equal(out.cpu().numpy(), plain)
