@@ -40,14 +40,14 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "95337eb65a24ed87",
+    "sources": "f8bc94c7bea74ed0",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (178070.8, 67610.0), "update_kernel": (240599.7, 323999.7)},
-        "2u": {"bag_forward_kernel": (338145.6, 32768.0)},
-        "2un": {"bag_forward_kernel": (346118.3, 32768.0)},
-        "2uq4": {"bag_forward_quant_kernel": (233575.3, 32886.2)},
+        "3": {"bag_forward_train_kernel": (178059.5, 67598.4), "update_kernel": (240600.6, 323999.4)},
+        "2u": {"bag_forward_kernel": (338146.4, 32768.0)},
+        "2un": {"bag_forward_kernel": (346113.8, 32768.0)},
+        "2uq4": {"bag_forward_quant_kernel": (233561.2, 32887.0)},
     },
 }
 
@@ -490,6 +490,8 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--scale-rows", type=int, default=None, help="rows per table (debug: smaller tables)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--versioned", action="store_true",
+                    help="forward-only workloads: look up through a version handle (latch + lookup), returning (E, V)")
     ap.add_argument("--cache-policy", choices=["static", "dynamic"], default="static",
                     help="workloads 5/5q4: 'dynamic' adds the study of the frequency-based cache policy")
     ap.add_argument("--watch-lookups", default="1e6,1e7,1e8",
@@ -561,11 +563,27 @@ def main() -> int:
         return pipeline.run_index_stage(w, tabs.set, db, buf)
 
     train_route = fused and w.backward     # the lookup also writes the backward's records
+    versioned = args.versioned
+    if versioned:
+        if w.backward or not fused:
+            log("--versioned applies to the forward-only workloads with hashing inside the lookup")
+            return 2
+        ver_record = torch.empty(emb.emb_version_record_bytes(w.T), dtype=torch.uint8, device=dev)
+        ver_latch = torch.empty(emb.emb_version_latch_bytes(w.T), dtype=torch.uint8, device=dev)
+        ver_handle = torch.zeros(1, dtype=torch.int64, device=dev)
+        emb.emb_version_record_write(ver_record, tabs.set, 1)
+        emb.emb_version_publish(ver_handle, ver_record)
 
     def do_forward(db, rows):
         if train_route:
             emb.emb_bag_forward_train(tabs.set, db.raw, buf.offsets, w.B, w.pool, buf.out, buf.workspace, None,
                                       buf.num_unique, buf.status)
+            return None
+        if versioned:
+            # the lookup latches the current version record and reads only the latched copy: (E, V)
+            emb.emb_version_latch(ver_handle, w.T, ver_latch, buf.status)
+            emb.emb_bag_forward_latched_hashed(ver_latch, w.T, w.D, w.dtype, db.raw, buf.offsets, w.B, w.pool, buf.out,
+                                               buf.status, streaming=w.streaming)
             return None
         if fused:
             rows = buf.rows[:db.nnz]
@@ -801,7 +819,8 @@ def main() -> int:
                              w.B, w.length, w.mean_len, w.ids,
                              (" alpha=%g over %.0e keys" % (w.alpha, w.n_keys)) if w.ids == "zipf" else "", w.pool,
                              ("forward + sparse row-wise Adagrad backward" if w.backward else "forward only") +
-                             (", rows read with the streaming hint" if w.streaming else ""))),
+                             (", rows read with the streaming hint" if w.streaming else "") +
+                             (", through a version handle (latch + lookup)" if versioned else ""))),
             "lookups_per_step": round(nnz_avg, 1),
             "resident_batches": len(dbs),
             "seed": seed,

@@ -57,20 +57,58 @@ SelLayout sel_layout(int64_t num_rows)
     return L;
 }
 
+// Popular rows repeat: under a Zipf law the most popular row alone takes a tenth of all lookups, and
+// atomics on one address are served one at a time by the L2.  A workgroup therefore first merges its
+// OBS_TILE lookups in a small LDS hash table (row -> count, open addressing) and then adds each distinct
+// row's count to its counter once.  A lookup that finds no slot within a few probes goes to its counter
+// directly, so the result is the exact count either way.
+constexpr int OBS_ITEMS = 8;                       // lookups per thread
+constexpr int OBS_TILE = CP_BLOCK * OBS_ITEMS;     // lookups per workgroup
+constexpr int OBS_SLOTS = 2 * OBS_TILE;            // load factor at most one half
+constexpr int OBS_PROBES = 8;
+constexpr unsigned long long OBS_EMPTY = ~0ull;    // not a row number: rows are below 2^63
+
 template <bool HASHED>
 __global__ __launch_bounds__(CP_BLOCK) void cache_observe_kernel(const int64_t *__restrict__ ids, int64_t nnz,
                                                                  uint64_t num_rows, uint64_t salt, uint64_t magic,
                                                                  uint32_t *freq, uint32_t *status)
 {
-    const int64_t j = (int64_t)blockIdx.x * CP_BLOCK + threadIdx.x;
-    if (j >= nnz) return;
-    uint64_t r = (uint64_t)ids[j];
-    if (HASHED) r = emb_fast_mod(emb_splitmix64(r ^ salt), num_rows, magic);
-    if (r >= num_rows) {  // negative row numbers are huge as unsigned
-        emb_flag(status, EMB_STATUS_BAD_INDEX);
-        return;
+    __shared__ unsigned long long keys[OBS_SLOTS];
+    __shared__ uint32_t counts[OBS_SLOTS];
+    for (int i = threadIdx.x; i < OBS_SLOTS; i += CP_BLOCK) {
+        keys[i] = OBS_EMPTY;
+        counts[i] = 0u;
     }
-    atomicAdd(freq + r, 1u);
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * OBS_TILE;
+#pragma unroll
+    for (int k = 0; k < OBS_ITEMS; ++k) {
+        const int64_t j = base + (int64_t)k * CP_BLOCK + threadIdx.x;
+        if (j >= nnz) continue;
+        uint64_t r = (uint64_t)ids[j];
+        if (HASHED) r = emb_fast_mod(emb_splitmix64(r ^ salt), num_rows, magic);
+        if (r >= num_rows) {  // negative row numbers are huge as unsigned
+            emb_flag(status, EMB_STATUS_BAD_INDEX);
+            continue;
+        }
+        uint32_t slot = (uint32_t)((r * UINT64_C(0x9E3779B97F4A7C15)) >> 32) & (OBS_SLOTS - 1);
+        bool placed = false;
+        for (int p = 0; p < OBS_PROBES && !placed; ++p) {
+            const unsigned long long prev = atomicCAS(&keys[slot], OBS_EMPTY, (unsigned long long)r);
+            if (prev == OBS_EMPTY || prev == (unsigned long long)r) {
+                atomicAdd(&counts[slot], 1u);
+                placed = true;
+            } else {
+                slot = (slot + 1) & (OBS_SLOTS - 1);
+            }
+        }
+        if (!placed) atomicAdd(freq + r, 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < OBS_SLOTS; i += CP_BLOCK) {
+        const uint32_t c = counts[i];
+        if (c) atomicAdd(freq + keys[i], c);
+    }
 }
 
 __global__ __launch_bounds__(CP_BLOCK) void sel_init_kernel(SelCtrl *ctrl, unsigned long long *hist, int64_t num_hot)
@@ -323,7 +361,7 @@ int observe_entry(int64_t num_rows, const int64_t *ids, int64_t nnz, uint32_t *f
     if (num_rows <= 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
     if (nnz == 0) return EMB_OK;
     if (!ids || !freq_dev) return EMB_ERR_INVALID_ARG;
-    const int64_t blocks = (nnz + CP_BLOCK - 1) / CP_BLOCK;
+    const int64_t blocks = (nnz + OBS_TILE - 1) / OBS_TILE;
     if (blocks > 0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
     const uint64_t magic = emb_mod_magic((uint64_t)num_rows);
     hipStream_t s = emb_stream(stream);
