@@ -3,17 +3,20 @@
  * hashed embedding tables: ID hashing, bag offsets, pooled lookup
  * (EmbeddingBag forward; also over row-quantised INT8 / INT4 tables and over
  * tables of different width), exact sparse backward with row-wise Adagrad, and
- * a pooled lookup over a host-resident table fronted by an HBM hot-row cache.
+ * a pooled lookup over a host-resident table fronted by an HBM hot-row cache,
+ * with a frequency-based policy for what the cache holds, and version-tagged
+ * table sets whose lookups return the version they were computed from.
  *
  * Source of the problem statement: "Multi-Faceted Large Embedding Tables for
  * Pinterest Ads Ranking", Section 2.2 (high-cardinality categorical features
  * are mapped to dense embeddings through hashed lookup tables; collisions are
  * legal), Section 3.1 (several ID tables of ~1e8-1e9 rows, fine-tuned inside
  * the ranking model) and Section 3.3 (tables too large for GPU memory are
- * hosted in CPU memory) and Section 4.1.2 (those tables are stored as INT4
- * after post-training quantisation).  The paper names no hash, pooling mode,
- * optimizer or quantisation scheme; each entry point states the definition
- * it implements.
+ * hosted in CPU memory, and a request is served by tables and upper model of
+ * one version) and Section 4.1.2 (those tables are stored as INT4 after
+ * post-training quantisation).  The paper names no hash, pooling mode,
+ * optimizer, quantisation scheme or cache policy; each entry point states the
+ * definition it implements.
  *
  * Conventions
  *  - "dev" pointers are device pointers (HBM, or host memory mapped into the
@@ -343,7 +346,7 @@ int emb_bag_backward_sort_prepared(const emb_table *tables_host, const emb_table
  * rows: a presence bitmap word and the number of hot rows before it). */
 int emb_cache_index_bytes(int64_t num_rows, size_t *bytes);
 
-/* Build the static cache: copies rows hot_rows[k] of the table into
+/* Build the cache for a given hot set: copies rows hot_rows[k] of the table into
  * cache_rows_dev[k] and builds the index.  table_dev: device-visible pointer
  * to the table (hipHostMalloc'ed mapped memory, or HBM).  hot_rows_dev:
  * i64[num_hot], strictly ascending, each in [0, num_rows) (violations set

@@ -1,5 +1,6 @@
 // Pooled lookup over a table that lives in host memory (mapped into the device
-// address space) with a static cache of hot rows in HBM: the one-box analogue
+// address space) with a cache of hot rows in HBM (built for a hot set the
+// caller gives; cache_policy.hip chooses one from lookup counts): the one-box analogue
 // of hosting the large tables in CPU memory next to a GPU-resident upper model
 // (paper Section 3.3).
 //

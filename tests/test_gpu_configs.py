@@ -350,3 +350,88 @@ def test_workload_5q4_int4_host_table_with_hbm_cache():
     assert hm.cpu().tolist() == [hits, misses]
     H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="workload 5q4")
     assert 0.85 < hits / max(1, hits + misses) < 0.97
+
+
+def test_workload_5q4_cache_policy_at_full_size():
+    # The frequency-based policy on the full-size hosted INT4 table: counters against the oracle's over the
+    # whole table; the selected hot set against the properties that define it uniquely (checked with numpy
+    # over all 2.5e8 counters: the oracle sorts every row, which takes minutes at this size); the refreshed
+    # cache's rows and the lookup through it against the oracle.
+    w = wl.WORKLOADS["5q4"]
+    import psutil
+    rb = emb.emb_row_bytes(w.D, w.quant)
+    if psutil.virtual_memory().available < w.R * rb + (30 << 30):
+        w = w.scaled(rows=w.R // 4)
+        say("cache policy: scaled to %d rows" % w.R)
+    _release_pinned_cache()
+    rng = np.random.default_rng(7)
+    K = int(round(w.hot_fraction * w.R))
+    host = torch.empty((w.R, rb), dtype=torch.uint8, pin_memory=True)
+    ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+    src = torch.empty((w.R, w.D), dtype=torch.float32, device=H.DEV)
+    emb.emb_table_fill(src, w.R, w.D, "f32", w.table_seed(0))
+    emb.emb_quantize_rows(src, w.quant, ptr)
+    torch.cuda.synchronize()
+    del src
+    torch.cuda.empty_cache()
+    cache = pipeline.HotRowCache(ptr, w.R, w.D, w.quant, K, w.salt(0), torch.device(H.DEV), decay_shift=1)
+    ref_freq = np.zeros(w.R, np.uint32)
+
+    def watch(chunks):
+        for c in chunks:
+            raw = wl.traffic_raw_ids(w, 0, 5_000_000, c)
+            cache.observe(H.dev(raw))
+            assert oracle.cache_observe(ref_freq, oracle.hash_ids(raw, w.salt(0), w.R)) == 0
+        torch.cuda.synchronize()
+        say("cache policy: %d lookups watched" % (5_000_000 * len(chunks)))
+
+    def check_refresh(old_hot):
+        counts = ref_freq.copy()
+        assert np.array_equal(cache.freq.cpu().numpy().view(np.uint32), counts)      # every counter, exactly
+        cache.moved.zero_()
+        cache.refresh()
+        torch.cuda.synchronize()
+        hot = cache.hot[:K].cpu().numpy()
+        thr, tied_taken = [int(x) for x in cache.info.cpu().tolist()]
+        # the set the rule defines is the only one with these properties
+        assert hot.size == K and (np.diff(hot) > 0).all() and hot[0] >= 0 and hot[-1] < w.R
+        sel = np.zeros(w.R, bool)
+        sel[hot] = True
+        assert int(counts[sel].min()) == thr and int(counts[~sel].max()) <= thr
+        tied = np.flatnonzero(counts == thr)
+        kept = sel[tied]
+        assert int(kept.sum()) == tied_taken and kept[:tied_taken].all()              # ties: the smallest rows
+        assert int((counts > thr).sum()) + tied_taken == K
+        ref_freq[:] = counts >> 1                                                     # aging
+        assert np.array_equal(cache.freq.cpu().numpy().view(np.uint32), ref_freq)
+        n_kept = int(np.isin(hot, old_hot, assume_unique=True).sum())
+        assert cache.moved.cpu().tolist() == [n_kept, K - n_kept]
+        sample = np.sort(rng.integers(0, K, size=20_000))
+        got = cache.rows[cache.active][torch.from_numpy(sample).to(H.DEV)].cpu().numpy()
+        assert np.array_equal(got, oracle.quantize_rows(wl.table_values(w.table_seed(0), hot[sample], w.D), w.quant))
+        say("cache policy: refresh ok (threshold count %d, %d rows kept in HBM, %d fetched)" % (thr, n_kept, K - n_kept))
+        return hot
+
+    watch([0, 1])
+    hot = check_refresh(np.zeros(0, np.int64))
+    watch([2])
+    hot = check_refresh(hot)
+
+    batch = wl.make_batch(w, 0)
+    db = pipeline.DeviceBatch(w, batch, torch.device(H.DEV))
+    off_dev = torch.empty(w.B + 1, dtype=torch.int64, device=H.DEV)
+    out = torch.empty((1, w.B, w.D), dtype=torch.float32, device=H.DEV)
+    emb.emb_lengths_to_offsets(db.lengths, off_dev, cache.status)
+    cache.forward_hashed(db.raw, off_dev, w.B, w.pool, out)
+    torch.cuda.synchronize()
+    assert cache.status.item() == 0
+    off, rows = _oracle_index(w, batch)
+    touched = np.unique(rows)
+    packed = oracle.quantize_rows(wl.table_values(w.table_seed(0), touched, w.D), w.quant)
+    hot_compact = np.flatnonzero(np.isin(touched, hot, assume_unique=True)).astype(np.int64)
+    ref, absum, (hits, misses), st = oracle.bag_forward_cached(packed, w.quant, hot_compact,
+                                                               np.searchsorted(touched, rows).astype(np.int64), off,
+                                                               w.B, w.pool, D=w.D)
+    assert st == 0 and cache.hit_miss.cpu().tolist() == [hits, misses]
+    H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="workload 5q4 through the learnt cache")
+    assert hits / max(1, hits + misses) > 0.75             # 1.5e7 watched lookups: what the law allows is ~0.85
