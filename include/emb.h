@@ -382,6 +382,44 @@ int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_rows, int32
                                   float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
                                   void *stream);
 
+/* One hosted table with its cache, for the multi-table cached lookup: the
+ * arguments of emb_bag_forward_cached as a descriptor.  Like emb_table, the
+ * array of T descriptors is passed in host memory (validation) and in device
+ * memory (read by the kernel); the caller keeps the two copies identical. */
+typedef struct emb_cached_table {
+    const void *table;       /* dev-visible: the table (mapped host memory, or HBM)  */
+    const void *cache_rows;  /* dev: num_hot rows, as emb_cache_build wrote them     */
+    const void *cache_index; /* dev: the index emb_cache_build wrote                 */
+    int64_t num_rows;        /* > 0                                                  */
+    int64_t num_hot;         /* rows in the cache                                    */
+    uint64_t salt;           /* XOR-ed into raw IDs before hashing (hashed form)     */
+    uint64_t mod_magic;      /* floor((2^64 - 1) / num_rows)  (emb_cached_tables_init) */
+    uint64_t reserved;       /* keeps the descriptor at 64 bytes                     */
+} emb_cached_table;
+
+/* Fill mod_magic of T host descriptors from their num_rows (host-only). */
+int emb_cached_tables_init(emb_cached_table *tables_host, int32_t T);
+
+/* emb_bag_forward_cached over T hosted tables in one launch (Section 3.3: the
+ * hosted model holds several large tables).  Bags, ids and offsets are laid
+ * out as for emb_bag_forward (table-major, one offsets array of T*B+1 entries);
+ * all tables share D and dtype (any storage type of the cached lookup);
+ * out_dev: f32[T, B, D].  hit_miss_dev (nullable, u64[2], zeroed by the
+ * caller): totals over all tables.  Results equal T single-table calls; one
+ * launch keeps the misses of all tables in flight together.  The _hashed form
+ * takes raw IDs and resolves them with each table's salt and num_rows. */
+int emb_bag_forward_cached_tables(const emb_cached_table *tables_host,
+                                  const emb_cached_table *tables_dev, int32_t T, int32_t D,
+                                  int32_t dtype, const int64_t *rows_dev, const int64_t *offsets_dev,
+                                  int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                                  uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream);
+int emb_bag_forward_cached_tables_hashed(const emb_cached_table *tables_host,
+                                         const emb_cached_table *tables_dev, int32_t T, int32_t D,
+                                         int32_t dtype, const uint64_t *raw_dev,
+                                         const int64_t *offsets_dev, int64_t B, int64_t nnz,
+                                         int32_t mode, float *out_dev, uint64_t *hit_miss_dev,
+                                         uint32_t *status_dev, void *stream);
+
 /* ---- which rows the cache holds: frequency-based policy -------------------
  * Section 5 lists better caching strategies as open work and the paper names
  * no policy; the one built here is frequency-based admission with batched

@@ -31,6 +31,11 @@ TABLE_DESC = np.dtype([("weights", "<u8"), ("accum", "<u8"), ("num_rows", "<i8")
                        ("salt", "<u8"), ("mod_magic", "<u8")])
 assert TABLE_DESC.itemsize == 48
 
+# numpy mirror of ``struct emb_cached_table``
+CACHED_DESC = np.dtype([("table", "<u8"), ("cache_rows", "<u8"), ("cache_index", "<u8"), ("num_rows", "<i8"),
+                        ("num_hot", "<i8"), ("salt", "<u8"), ("mod_magic", "<u8"), ("reserved", "<u8")])
+assert CACHED_DESC.itemsize == 64
+
 # numpy mirror of ``struct emb_table_shape``
 SHAPE_DESC = np.dtype([("D", "<i4"), ("dtype", "<i4"), ("out_offset", "<i8"), ("out_stride", "<i8"),
                        ("first_block", "<u4"), ("lanes", "<i4")])
@@ -45,6 +50,7 @@ EXPORTS = [
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_host_device_pointer",
     "emb_version_record_bytes", "emb_version_latch_bytes", "emb_version_record_write", "emb_version_publish",
     "emb_version_latch", "emb_bag_forward_latched", "emb_bag_forward_latched_hashed",
+    "emb_cached_tables_init", "emb_bag_forward_cached_tables", "emb_bag_forward_cached_tables_hashed",
     "emb_cache_observe", "emb_cache_observe_hashed", "emb_cache_select_workspace_bytes", "emb_cache_select", "emb_cache_rebuild",
     "emb_table_fill",
 ]
@@ -154,6 +160,12 @@ def lib() -> C.CDLL:
     L.emb_bag_forward_latched.argtypes = [vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp]
     L.emb_bag_forward_latched_hashed.restype = C.c_int
     L.emb_bag_forward_latched_hashed.argtypes = [vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp]
+    L.emb_cached_tables_init.restype = C.c_int
+    L.emb_cached_tables_init.argtypes = [vp, i32]
+    L.emb_bag_forward_cached_tables.restype = C.c_int
+    L.emb_bag_forward_cached_tables.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    L.emb_bag_forward_cached_tables_hashed.restype = C.c_int
+    L.emb_bag_forward_cached_tables_hashed.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     L.emb_host_device_pointer.restype = C.c_int
     L.emb_host_device_pointer.argtypes = [vp, C.POINTER(vp)]
     L.emb_table_fill.restype = C.c_int
@@ -671,6 +683,50 @@ def emb_bag_forward_latched_hashed(latch: torch.Tensor, T: int, D: int, dtype: s
                                    status: Optional[torch.Tensor] = None, streaming: bool = False) -> None:
     _forward_latched("emb_bag_forward_latched_hashed", latch, T, D, dtype, raw, _U64, offsets, B, mode, out, status,
                      streaming)
+
+
+class CachedTables:
+    """The ``emb_cached_table`` descriptor array of T hosted tables with their caches, on the host and on the
+    device.  ``entries[t]`` = (table_ptr, num_rows, cache_rows tensor, cache_index tensor, num_hot, salt)."""
+
+    def __init__(self, entries: Sequence, D: int, dtype: str, device: Optional[torch.device] = None):
+        self.T, self.D, self.dtype = len(entries), int(D), dtype
+        self.keep = list(entries)                       # the cache tensors stay referenced
+        self.host = np.zeros(self.T, dtype=CACHED_DESC)
+        for t, (ptr, rows, cache_rows, cache_index, num_hot, salt) in enumerate(entries):
+            self.host["table"][t] = int(ptr)
+            self.host["num_rows"][t] = int(rows)
+            self.host["cache_rows"][t] = _ptr(cache_rows, _TABLE_TORCH[dtype], "cache_rows[%d]" % t) or 0
+            self.host["cache_index"][t] = _ptr(cache_index, torch.uint8, "cache_index[%d]" % t)
+            self.host["num_hot"][t] = int(num_hot)
+            self.host["salt"][t] = int(salt) % (1 << 64)
+        _check("emb_cached_tables_init", lib().emb_cached_tables_init(self.host.ctypes.data, self.T))
+        if device is None:
+            device = torch.device("cuda", torch.cuda.current_device())
+        self.dev = torch.from_numpy(self.host.view(np.uint8).reshape(-1).copy()).to(device)
+
+
+def _forward_cached_tables(fn: str, ct: CachedTables, ids, id_dtype, offsets, B, mode, out, hit_miss, status):
+    if offsets.numel() != ct.T * B + 1 or out.numel() != ct.T * B * ct.D:
+        raise TypeError("shape mismatch")
+    _check(fn, getattr(lib(), fn)(
+        int(ct.host.ctypes.data), int(ct.dev.data_ptr()), ct.T, ct.D, DTYPE[ct.dtype], _ptr(ids, id_dtype, "ids"),
+        _ptr(offsets, torch.int64, "offsets"), int(B), ids.numel(), POOL[mode], _ptr(out, torch.float32, "out"),
+        _ptr(hit_miss, _U64, "hit_miss"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_bag_forward_cached_tables(ct: CachedTables, rows: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
+                                  out: torch.Tensor, hit_miss: Optional[torch.Tensor] = None,
+                                  status: Optional[torch.Tensor] = None) -> None:
+    _forward_cached_tables("emb_bag_forward_cached_tables", ct, rows, torch.int64, offsets, B, mode, out, hit_miss,
+                           status)
+
+
+def emb_bag_forward_cached_tables_hashed(ct: CachedTables, raw: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
+                                         out: torch.Tensor, hit_miss: Optional[torch.Tensor] = None,
+                                         status: Optional[torch.Tensor] = None) -> None:
+    _forward_cached_tables("emb_bag_forward_cached_tables_hashed", ct, raw, _U64, offsets, B, mode, out, hit_miss,
+                           status)
 
 
 def emb_host_device_pointer(host_ptr: int) -> int:

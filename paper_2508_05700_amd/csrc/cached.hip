@@ -259,6 +259,139 @@ int dispatch_cached_quant(int lpr, hipStream_t s, const char *table, const char 
 #undef EMB_CQ
 }
 
+// ---- several hosted tables in one launch --------------------------------------------------------
+// A workgroup serves bags of one table and takes that table's cache from its descriptor.  Beyond
+// saving launches, one launch keeps the misses of all tables in flight together, and the link's
+// rate for scattered rows grows with the number of requests in flight.
+__device__ __forceinline__ CachedSource cached_source_of(const emb_cached_table &tb, int64_t row_bytes, uint32_t *status,
+                                                         bool hashed)
+{
+    return CachedSource{reinterpret_cast<const char *>(tb.table),
+                        reinterpret_cast<const char *>(tb.cache_rows),
+                        reinterpret_cast<const CacheEntry *>(tb.cache_index),
+                        (uint64_t)tb.num_rows,
+                        (uint64_t)tb.num_hot,
+                        row_bytes,
+                        status,
+                        0u,
+                        0u,
+                        hashed,
+                        tb.salt,
+                        tb.mod_magic};
+}
+
+__device__ __forceinline__ void add_hit_miss(const CachedSource &src, unsigned long long *hit_miss)
+{
+    if (!hit_miss) return;
+    // every lane of the wavefront is still here: reduce, then one atomic per wavefront
+    uint32_t h = src.hits, m = src.misses;
+#pragma unroll
+    for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) {
+        h += __shfl_xor(h, d, EMB_WAVE);
+        m += __shfl_xor(m, d, EMB_WAVE);
+    }
+    if ((threadIdx.x & (EMB_WAVE - 1)) == 0) {
+        if (h) atomicAdd(&hit_miss[0], (unsigned long long)h);
+        if (m) atomicAdd(&hit_miss[1], (unsigned long long)m);
+    }
+}
+
+template <int LPR, int CPL, int UNROLL, bool BF16>
+__global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_tables_kernel(
+    const emb_cached_table *__restrict__ tables, int64_t B, uint32_t blocks_per_table, int64_t nnz,
+    const int64_t *__restrict__ ids, const int64_t *__restrict__ offsets, int32_t chunks_per_row, int32_t mode,
+    float *__restrict__ out, unsigned long long *hit_miss, uint32_t *status, bool hashed)
+{
+    constexpr int GROUPS = CF_BLOCK / LPR;
+    const uint32_t t = blockIdx.x / blocks_per_table;   // the grid is exactly T * blocks_per_table
+    const int l = threadIdx.x % LPR;
+    const int64_t b = (int64_t)(blockIdx.x % blocks_per_table) * GROUPS + threadIdx.x / LPR;
+    const emb_cached_table tb = tables[t];
+    CachedSource src = cached_source_of(tb, (int64_t)chunks_per_row * 16, status, hashed);
+    constexpr int F = ChunkAcc<BF16>::FLOATS;
+    const int64_t bag = (int64_t)t * B + b;
+    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, bag, l, nnz, ids, offsets, chunks_per_row, mode,
+                                            out + bag * ((int64_t)chunks_per_row * F), status);
+    add_hit_miss(src, hit_miss);
+}
+
+template <int LPR, int BITS, int UNROLL>
+__global__ __launch_bounds__(Q_BLOCK) void bag_forward_cached_tables_quant_kernel(
+    const emb_cached_table *__restrict__ tables, int64_t B, uint32_t blocks_per_table, int64_t nnz,
+    const int64_t *__restrict__ ids, const int64_t *__restrict__ offsets, int32_t D, int64_t row_bytes, int32_t mode,
+    float *__restrict__ out, unsigned long long *hit_miss, uint32_t *status, bool hashed)
+{
+    constexpr int GROUPS = Q_BLOCK / LPR;
+    const uint32_t t = blockIdx.x / blocks_per_table;
+    const int l = threadIdx.x % LPR;
+    const int64_t b = (int64_t)(blockIdx.x % blocks_per_table) * GROUPS + threadIdx.x / LPR;
+    const emb_cached_table tb = tables[t];
+    CachedSource src = cached_source_of(tb, row_bytes, status, hashed);
+    gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, (int64_t)t * B + b, l, nnz, ids, offsets, D, mode, out, status);
+    add_hit_miss(src, hit_miss);
+}
+
+struct CachedTablesArgs {
+    const emb_cached_table *tables;
+    int32_t T;
+    int64_t B, nnz;
+    const int64_t *ids, *offsets;
+    int32_t D, mode;
+    int64_t row_bytes;
+    float *out;
+    unsigned long long *hit_miss;
+    uint32_t *status;
+    bool hashed;
+    hipStream_t s;
+};
+
+template <int LPR, int CPL, int UNROLL>
+int launch_cached_tables(const CachedTablesArgs &a, bool bf16)
+{
+    constexpr int GROUPS = CF_BLOCK / LPR;
+    const int64_t per_table = (a.B + GROUPS - 1) / GROUPS;
+    if (per_table * a.T > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+    const dim3 grid((unsigned)(per_table * a.T));
+    const int32_t chunks = (int32_t)(a.row_bytes / 16);
+    if (bf16)
+        hipLaunchKernelGGL((bag_forward_cached_tables_kernel<LPR, CPL, UNROLL, true>), grid, dim3(CF_BLOCK), 0, a.s,
+                           a.tables, a.B, (uint32_t)per_table, a.nnz, a.ids, a.offsets, chunks, a.mode, a.out, a.hit_miss,
+                           a.status, a.hashed);
+    else
+        hipLaunchKernelGGL((bag_forward_cached_tables_kernel<LPR, CPL, UNROLL, false>), grid, dim3(CF_BLOCK), 0, a.s,
+                           a.tables, a.B, (uint32_t)per_table, a.nnz, a.ids, a.offsets, chunks, a.mode, a.out, a.hit_miss,
+                           a.status, a.hashed);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    return EMB_OK;
+}
+
+template <int LPR, int BITS>
+int launch_cached_tables_quant(const CachedTablesArgs &a)
+{
+    constexpr int GROUPS = Q_BLOCK / LPR;
+    const int64_t per_table = (a.B + GROUPS - 1) / GROUPS;
+    if (per_table * a.T > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((bag_forward_cached_tables_quant_kernel<LPR, BITS, 8>), dim3((unsigned)(per_table * a.T)),
+                       dim3(Q_BLOCK), 0, a.s, a.tables, a.B, (uint32_t)per_table, a.nnz, a.ids, a.offsets, a.D,
+                       a.row_bytes, a.mode, a.out, a.hit_miss, a.status, a.hashed);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    return EMB_OK;
+}
+
+template <int BITS>
+int dispatch_cached_tables_quant(int lpr, const CachedTablesArgs &a)
+{
+    switch (lpr) {
+        case 1: return launch_cached_tables_quant<1, BITS>(a);
+        case 2: return launch_cached_tables_quant<2, BITS>(a);
+        case 4: return launch_cached_tables_quant<4, BITS>(a);
+        case 8: return launch_cached_tables_quant<8, BITS>(a);
+        case 16: return launch_cached_tables_quant<16, BITS>(a);
+        case 32: return launch_cached_tables_quant<32, BITS>(a);
+        default: return launch_cached_tables_quant<64, BITS>(a);
+    }
+}
+
 // Row shapes the cached lookup accepts: those of the plain lookup, quantised ones included.
 int cached_row_shape(int32_t D, int32_t dtype)
 {
@@ -428,4 +561,82 @@ extern "C" int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_
     return cached_entry(table_dev, num_rows, D, dtype, cache_rows_dev, cache_index_dev, num_hot,
                         reinterpret_cast<const int64_t *>(raw_dev), offsets_dev, B, nnz, mode, out_dev, hit_miss_dev,
                         status_dev, stream, true, salt);
+}
+
+extern "C" int emb_cached_tables_init(emb_cached_table *tables_host, int32_t T)
+{
+    if (T < 0 || (T > 0 && !tables_host)) return EMB_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < T; ++t) {
+        if (tables_host[t].num_rows <= 0) return EMB_ERR_INVALID_ARG;
+        tables_host[t].mod_magic = emb_mod_magic((uint64_t)tables_host[t].num_rows);
+    }
+    return EMB_OK;
+}
+
+static int cached_tables_entry(const emb_cached_table *th, const emb_cached_table *td, int32_t T, int32_t D,
+                               int32_t dtype, const int64_t *ids_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
+                               int32_t mode, float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream,
+                               bool hashed)
+{
+    if (T < 0 || B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
+    if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
+    int rc = cached_row_shape(D, dtype);
+    if (rc != EMB_OK) return rc;
+    if (T == 0 || B == 0) return EMB_OK;
+    if (!th || !td) return EMB_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < T; ++t) {
+        const emb_cached_table &e = th[t];
+        if (e.num_rows <= 0 || e.num_hot < 0 || e.num_hot > e.num_rows) return EMB_ERR_INVALID_ARG;
+        if (!e.table || !e.cache_index || (e.num_hot > 0 && !e.cache_rows)) return EMB_ERR_INVALID_ARG;
+        if (!emb_aligned(e.table, 16) || !emb_aligned(e.cache_index, 16) || !emb_aligned(e.cache_rows, 16))
+            return EMB_ERR_INVALID_ARG;
+        if (e.mod_magic != emb_mod_magic((uint64_t)e.num_rows)) return EMB_ERR_INVALID_ARG;
+    }
+    if (!offsets_dev || !out_dev || (nnz > 0 && !ids_dev)) return EMB_ERR_INVALID_ARG;
+    if (!emb_aligned(out_dev, 16)) return EMB_ERR_INVALID_ARG;
+    if (B > (int64_t)0x7FFFFFFF || T > 65535) return EMB_ERR_UNSUPPORTED;
+
+    CachedTablesArgs a{td,      T,      B,         nnz,  ids_dev, offsets_dev, D, mode, emb_row_bytes(D, dtype),
+                       out_dev, reinterpret_cast<unsigned long long *>(hit_miss_dev), status_dev, hashed, emb_stream(stream)};
+    if (dtype == EMB_INT8) return dispatch_cached_tables_quant<8>(emb_quant_lanes(D), a);
+    if (dtype == EMB_INT4) return dispatch_cached_tables_quant<4>(emb_quant_lanes(D), a);
+    int lpr, cpl;
+    emb_row_split((int)(a.row_bytes / 16), lpr, cpl);
+    const bool bf16 = dtype == EMB_BF16;
+    if (cpl == 1) {
+        switch (lpr) {
+            case 1: return launch_cached_tables<1, 1, 8>(a, bf16);
+            case 2: return launch_cached_tables<2, 1, 8>(a, bf16);
+            case 4: return launch_cached_tables<4, 1, 8>(a, bf16);
+            case 8: return launch_cached_tables<8, 1, 8>(a, bf16);
+            case 16: return launch_cached_tables<16, 1, 8>(a, bf16);
+            case 32: return launch_cached_tables<32, 1, 8>(a, bf16);
+            default: return launch_cached_tables<64, 1, 8>(a, bf16);
+        }
+    }
+    switch (cpl) {
+        case 2: return launch_cached_tables<64, 2, 4>(a, bf16);
+        case 4: return launch_cached_tables<64, 4, 2>(a, bf16);
+        case 8: return launch_cached_tables<64, 8, 1>(a, bf16);
+        default: return launch_cached_tables<64, 16, 1>(a, bf16);
+    }
+}
+
+extern "C" int emb_bag_forward_cached_tables(const emb_cached_table *tables_host, const emb_cached_table *tables_dev,
+                                             int32_t T, int32_t D, int32_t dtype, const int64_t *rows_dev,
+                                             const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,
+                                             float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream)
+{
+    return cached_tables_entry(tables_host, tables_dev, T, D, dtype, rows_dev, offsets_dev, B, nnz, mode, out_dev,
+                               hit_miss_dev, status_dev, stream, false);
+}
+
+extern "C" int emb_bag_forward_cached_tables_hashed(const emb_cached_table *tables_host,
+                                                    const emb_cached_table *tables_dev, int32_t T, int32_t D,
+                                                    int32_t dtype, const uint64_t *raw_dev, const int64_t *offsets_dev,
+                                                    int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                                                    uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream)
+{
+    return cached_tables_entry(tables_host, tables_dev, T, D, dtype, reinterpret_cast<const int64_t *>(raw_dev),
+                               offsets_dev, B, nnz, mode, out_dev, hit_miss_dev, status_dev, stream, true);
 }

@@ -328,6 +328,34 @@ def test_versioned_tables_argument_errors(L):
     assert L.emb_bag_forward_latched_hashed(FAKE, 2, 64, 3, FAKE, FAKE, 4, 8, 0, FAKE, None, None) == UNSUPPORTED
 
 
+def test_cached_tables_descriptor_and_argument_errors(L):
+    header = open(os.path.join(ROOT, "include", "emb.h")).read()
+    body = re.search(r"typedef struct emb_cached_table \{(.*?)\} emb_cached_table;", header, flags=re.S).group(1)
+    fields = re.findall(r"\b(\w+);", re.sub(r"/\*.*?\*/", "", body, flags=re.S))
+    assert fields == list(b.CACHED_DESC.names)
+    d = np.zeros(2, dtype=b.CACHED_DESC)
+    d["table"], d["cache_rows"], d["cache_index"] = FAKE, FAKE, FAKE
+    d["num_rows"], d["num_hot"] = [1000, 7], [10, 7]
+    assert L.emb_cached_tables_init(d.ctypes.data, 2) == OK
+    assert d["mod_magic"].tolist() == [(2 ** 64 - 1) // 1000, (2 ** 64 - 1) // 7]
+    assert L.emb_cached_tables_init(None, 2) == INVALID
+    bad = d.copy()
+    bad["num_rows"][1] = 0
+    assert L.emb_cached_tables_init(bad.ctypes.data, 2) == INVALID
+    for fn in (L.emb_bag_forward_cached_tables, L.emb_bag_forward_cached_tables_hashed):
+        th = d.ctypes.data
+        assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 0, 0, 0, FAKE, None, None, None) == OK          # no bags
+        assert fn(None, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID
+        assert fn(th, None, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID
+        assert fn(th, FAKE, 2, 6, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == UNSUPPORTED
+        assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 5, FAKE, None, None, None) == INVALID     # pooling mode
+        assert fn(th, FAKE, 2, 64, 0, FAKE, None, 4, 8, 0, FAKE, None, None, None) == INVALID
+        for field, value in (("num_hot", 8), ("cache_index", 0), ("mod_magic", 1), ("table", FAKE + 8)):
+            bad = d.copy()
+            bad[field][1] = value
+            assert fn(bad.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID, field
+
+
 def test_exact_remainder_on_the_host(tmp_path):
     exe = str(tmp_path / "u64mod_check")
     subprocess.check_call(["g++", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "paper_2508_05700_amd", "csrc"),

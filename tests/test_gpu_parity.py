@@ -1118,3 +1118,64 @@ def test_versioned_lookup_by_row_number(dtype):
         # same bits as the plain lookup over that version's descriptors
         plain, _ = H.gpu_forward(vers[v]["ts"], rows, off, B, "sum")
         assert np.array_equal(out.cpu().numpy(), plain)
+
+
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 32), ("int4", 64), ("int8", 48)])
+def test_cached_forward_over_several_tables_in_one_launch(dtype, D):
+    rng = np.random.default_rng(7000 + D)
+    T, B = 5, 333
+    Rs = [4001, 900, 20_000, 64, 7777]
+    quant = dtype in ("int8", "int4")
+    tabs, hots, entries, keep = [], [], [], []
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    for t, R in enumerate(Rs):
+        x = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+        tab = oracle.quantize_rows(x, dtype) if quant else (wl.f32_to_bf16_bits(x).reshape(R, D) if dtype == "bf16" else x)
+        K = [R // 10, 0, R // 3, R, 5][t]                             # an empty and a full cache among them
+        hot = np.sort(rng.choice(R, size=K, replace=False)).astype(np.int64)
+        tdev = H.dev(tab)
+        width = tab.shape[1]
+        cache = torch.zeros((max(K, 1), width), dtype=tdev.dtype, device=H.DEV)
+        index = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+        emb.emb_cache_build(int(tdev.data_ptr()), R, D, dtype, H.dev(hot), cache, index, status)
+        tabs.append(tab)
+        hots.append(hot)
+        keep.append(tdev)
+        entries.append((int(tdev.data_ptr()), R, cache, index, K, 31 + t))
+    ct = emb.CachedTables(entries, D, dtype, device=torch.device(H.DEV))
+    lengths = rng.integers(0, 40, size=T * B).astype(np.int32)
+    lengths[rng.random(T * B) < 0.1] = 0
+    off, _ = oracle.lengths_to_offsets(lengths)
+    seg = [(int(off[t * B]), int(off[(t + 1) * B])) for t in range(T)]
+    rows = np.concatenate([np.where(rng.random(e - s) < 0.6, rng.choice(hots[t], size=e - s) if hots[t].size else 0,
+                                    rng.integers(0, Rs[t], size=e - s)) for t, (s, e) in enumerate(seg)]).astype(np.int64)
+    rows[[3, 11]] = [-1, Rs[0]]                                       # table 0: two bad rows
+    raw = rng.integers(0, 1 << 64, size=rows.size, dtype=np.uint64)
+    for hashed in (False, True):
+        ids = raw if hashed else rows
+        out = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+        hm = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+        status.zero_()
+        if hashed:
+            emb.emb_bag_forward_cached_tables_hashed(ct, H.dev(raw), H.dev(off), B, "mean", out, hm, status)
+        else:
+            emb.emb_bag_forward_cached_tables(ct, H.dev(rows), H.dev(off), B, "mean", out, hm, status)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        hits = misses = 0
+        st_all = 0
+        for t, (s, e) in enumerate(seg):
+            r = oracle.hash_ids(raw[s:e], 31 + t, Rs[t]) if hashed else rows[s:e]
+            o = off[t * B:(t + 1) * B + 1] - off[t * B]
+            ref, absum, (h, m), st = oracle.bag_forward_cached(tabs[t], dtype, hots[t], r, o, B, "mean",
+                                                               D=D if quant else None)
+            H.assert_pooled_close(got[t], ref[0], absum[0], eps=H.EPS32, what="cached tables t=%d hashed=%s" % (t, hashed))
+            hits, misses, st_all = hits + h, misses + m, st_all | st
+            # and the same bits as the single-table call
+            one = torch.empty((1, B, D), dtype=torch.float32, device=H.DEV)
+            ptr, R, cache, index, K, salt = entries[t]
+            emb.emb_bag_forward_cached(ptr, R, D, dtype, cache, index, K, H.dev(r), H.dev(o), B, "mean", one)
+            torch.cuda.synchronize()
+            assert np.array_equal(one.cpu().numpy()[0], got[t])
+        assert hm.cpu().tolist() == [hits, misses] and int(status.item()) == st_all
+        assert st_all == (0 if hashed else emb.STATUS_BAD_INDEX)
