@@ -289,6 +289,133 @@ def bench_hybrid(args) -> int:
     return 0
 
 
+def bench_hybrid_tables(args) -> int:
+    """Workloads 5m / 5mq4: several hosted tables, each with its HBM cache.  A step is offsets + ONE cached
+    lookup over all tables (hashing inside); the same step with one cached lookup per table is timed beside
+    it."""
+    import numpy as np
+    import psutil
+    import torch
+
+    from paper_2508_05700_amd import binding as emb
+    from paper_2508_05700_amd import pipeline, workloads as wl
+
+    seed = wl.DEFAULT_SEED if args.seed is None else args.seed
+    w = wl.WORKLOADS[args.workload]
+    store = w.storage
+    rowb = emb.emb_row_bytes(w.D, store)
+    if args.scale_rows:
+        w = w.scaled(rows=args.scale_rows)
+    elif psutil.virtual_memory().available < w.T * w.R * rowb + (26 << 30):
+        w = w.scaled(rows=w.R // 4)
+        log("workload %s scaled to %d rows per table: not enough host memory to pin the tables" % (args.workload, w.R))
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, W = args.steps, args.warmup
+    t_setup = time.time()
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    n_hot = int(round(w.hot_fraction * w.R))
+    hosts, entries = [], []
+    for t in range(w.T):
+        if w.quant:
+            host = torch.empty((w.R, rowb), dtype=torch.uint8, pin_memory=True)
+            ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+            src = torch.empty((w.R, w.D), dtype=torch.float32, device=dev)
+            emb.emb_table_fill(src, w.R, w.D, "f32", w.table_seed(t, seed))
+            emb.emb_quantize_rows(src, store, ptr)
+            torch.cuda.synchronize()
+            del src
+        else:
+            host = torch.empty((w.R, w.D), dtype=torch.float32, pin_memory=True)
+            ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+            emb.emb_table_fill(ptr, w.R, w.D, "f32", w.table_seed(t, seed))
+        n_ranks = int(n_hot * 1.06) + 1000
+        hot_raw = torch.from_numpy(wl.hot_raw_ids(w, t, n_ranks, seed).view(np.int64)).to(dev)
+        hot_rows = torch.empty(n_ranks, dtype=torch.int64, device=dev)
+        emb.emb_hash_ids(hot_raw, w.salt(t), w.R, hot_rows)
+        hot = torch.from_numpy(wl.first_k_distinct_sorted(hot_rows.cpu().numpy(), n_hot)).to(dev)
+        index = torch.empty(emb.emb_cache_index_bytes(w.R), dtype=torch.uint8, device=dev)
+        cache = (torch.empty((hot.numel(), rowb), dtype=torch.uint8, device=dev) if w.quant
+                 else torch.empty((hot.numel(), w.D), dtype=torch.float32, device=dev))
+        emb.emb_cache_build(ptr, w.R, w.D, store, hot, cache, index, status)
+        hosts.append(host)
+        entries.append((ptr, w.R, cache, index, hot.numel(), w.salt(t)))
+    torch.cuda.empty_cache()
+    ct = emb.CachedTables(entries, w.D, store, device=dev)
+    dbs = [pipeline.DeviceBatch(w, wl.make_batch(w, i, seed), dev) for i in range(args.batches)]
+    offsets = torch.empty(w.T * w.B + 1, dtype=torch.int64, device=dev)
+    out = torch.empty((w.T, w.B, w.D), dtype=torch.float32, device=dev)
+    hm = torch.zeros(2, dtype=torch.int64, device=dev)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0
+    log("setup: %d host tables %d x %d %s (%.1f GB pinned in all), caches of %d rows each, %.1f s" % (
+        w.T, w.R, w.D, store, w.T * w.R * rowb / 1e9, n_hot, time.time() - t_setup))
+
+    def step_one_launch(db, e=None):
+        emb.emb_lengths_to_offsets(db.lengths, offsets, status)
+        if e:
+            e[0].record()
+        emb.emb_bag_forward_cached_tables_hashed(ct, db.raw, offsets, w.B, w.pool, out, hm, status)
+        if e:
+            e[1].record()
+
+    def step_per_table(db, e=None):
+        emb.emb_lengths_to_offsets(db.lengths, offsets, status)
+        if e:
+            e[0].record()
+        for t, (ptr, R, cache, index, nh, salt) in enumerate(entries):
+            # the table's B+1 offsets index the whole ID array
+            emb.emb_bag_forward_cached_hashed(ptr, R, w.D, store, cache, index, nh, salt, db.raw,
+                                              offsets[t * w.B:(t + 1) * w.B + 1], w.B, w.pool, out[t:t + 1], hm, status)
+        if e:
+            e[1].record()
+
+    def run(step):
+        for i in range(W):
+            step(dbs[i % len(dbs)])
+        torch.cuda.synchronize()
+        hm.zero_()
+        ev = [[emb.Event(timing=True) for _ in range(2)] for _ in range(K)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(K):
+            step(dbs[(W + k) % len(dbs)], ev[k])
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        hits, misses = [int(x) for x in hm.cpu().tolist()]
+        return dt, sum(e[0].elapsed_time(e[1]) for e in ev) / K, hits, misses
+
+    dt_pt, ms_pt, _, _ = run(step_per_table)
+    elapsed, ms_fwd, hits, misses = run(step_one_launch)
+    assert int(status.item()) == 0
+    lookups = sum(dbs[(W + k) % len(dbs)].nnz for k in range(K))
+    pcie_gbs = misses / K * rowb / (ms_fwd * 1e-3) / 1e9
+    log("step %.3f ms: one cached lookup over %d tables %.3f ms (one lookup per table: step %.3f ms, lookups %.3f ms); "
+        "hit rate %.2f %%; misses %.1f GB/s over PCIe" % (elapsed / K * 1e3, w.T, ms_fwd, dt_pt / K * 1e3, ms_pt,
+                                                         100.0 * hits / max(1, hits + misses), pcie_gbs))
+    PCIE_PEAK = 64.0
+    print(json.dumps({
+        "metric": METRIC, "value": round(lookups / elapsed, 1), "unit": "lookups/s", "n_gpus": 1, "steps": K,
+        "warmup": W, "ms_per_step": round(elapsed / K * 1e3, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%s: %d host-resident tables of %d rows x dim %d %s (%d B per row, pinned), each with an HBM "
+                               "cache of %d hot rows, %d bags per table, poisson bag lengths (mean %g), zipf IDs alpha=%g "
+                               "over %.0e keys, %s pooling, forward only, one launch for all tables" % (
+                                   w.name, w.T, w.R, w.D, store, rowb, n_hot, w.B, w.mean_len, w.alpha, w.n_keys, w.pool),
+                   "lookups_per_step": round(lookups / K, 1), "resident_batches": len(dbs), "seed": seed},
+        "stages": {"forward_cached_tables_ms": round(ms_fwd, 4), "hit_rate": round(hits / max(1, hits + misses), 5),
+                   "misses_per_step": round(misses / K, 1),
+                   "one_lookup_per_table": {"ms_per_step": round(dt_pt / K * 1e3, 4), "lookups_ms": round(ms_pt, 4)}},
+        "roofline": {"kernel": "bag_forward_cached_tables_quant_kernel" if w.quant else "bag_forward_cached_tables_kernel",
+                     "bound": "pcie", "achieved": round(pcie_gbs, 2), "peak": PCIE_PEAK, "unit": "GB/s",
+                     "frac": round(pcie_gbs / PCIE_PEAK, 4), "traffic": None, "avg_ms": round(ms_fwd, 4),
+                     "algorithmic_bytes": int(misses / K * rowb),
+                     "bytes_are": "one table row per miss, read zero-copy from pinned host memory"},
+        "cpu_baseline": None,
+    }), flush=True)
+    return 0
+
+
 def cache_policy_study(args, w, seed, ptr, store, n_hot, static_hot, dbs, offsets, out, W, K):
     """The frequency-based policy against the static hot set of the benchmark, on the same batches: the
     cache starts empty, watches a growing amount of traffic (lookups drawn like the batches'), and is
@@ -485,7 +612,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="3",
                     help="3 (fwd+bwd, default), 1, 2, 2u or 4 (forward only), 2q4 / 2q8 / 2uq4 (forward over INT4 / "
-                         "INT8 row-quantised tables), 5 (host table + HBM cache)")
+                         "INT8 row-quantised tables), 5 / 5q4 (host table + HBM cache), 5m / 5mq4 (four hosted tables, one "
+                         "launch), mix (tables of different width)")
     ap.add_argument("--batches", type=int, default=8, help="distinct resident batches cycled through")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--scale-rows", type=int, default=None, help="rows per table (debug: smaller tables)")
@@ -524,7 +652,7 @@ def main() -> int:
         return 2
     emb.lib()
     if wl.WORKLOADS[args.workload].hybrid:
-        return bench_hybrid(args)
+        return bench_hybrid_tables(args) if wl.WORKLOADS[args.workload].T > 1 else bench_hybrid(args)
     if args.workload == "mix":
         return bench_mixed(args)
     seed = wl.DEFAULT_SEED if args.seed is None else args.seed

@@ -269,6 +269,13 @@ WORKLOADS: Dict[str, Workload] = {
     "5q4": Workload("5q4", T=1, R=250_000_000, D=64, dtype="f32", B=16384, length="poisson", mean_len=30,
                     max_len=None, ids="zipf", alpha=1.1, n_keys=10 ** 9, pool="sum", hybrid=True,
                     hot_fraction=0.05, quant="int4"),
+    # 5m / 5mq4: workload 5's rows and lookups split over four hosted tables (a hosted model has several)
+    "5m": Workload("5m", T=4, R=62_500_000, D=64, dtype="f32", B=4096, length="poisson", mean_len=30,
+                   max_len=None, ids="zipf", alpha=1.1, n_keys=10 ** 9, pool="sum", hybrid=True,
+                   hot_fraction=0.05),
+    "5mq4": Workload("5mq4", T=4, R=62_500_000, D=64, dtype="f32", B=4096, length="poisson", mean_len=30,
+                     max_len=None, ids="zipf", alpha=1.1, n_keys=10 ** 9, pool="sum", hybrid=True,
+                     hot_fraction=0.05, quant="int4"),
 }
 
 

@@ -435,3 +435,65 @@ def test_workload_5q4_cache_policy_at_full_size():
     assert st == 0 and cache.hit_miss.cpu().tolist() == [hits, misses]
     H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="workload 5q4 through the learnt cache")
     assert hits / max(1, hits + misses) > 0.75             # 1.5e7 watched lookups: what the law allows is ~0.85
+
+
+def test_workload_5mq4_four_hosted_int4_tables_in_one_launch():
+    # The launch bench.py times for workload 5mq4: four hosted INT4 tables with their caches, raw IDs, one
+    # cached lookup for all.  The oracle quantises the generator's values of the rows each table's lookups touch.
+    w = wl.WORKLOADS["5mq4"]
+    import psutil
+    rb = emb.emb_row_bytes(w.D, w.quant)
+    if psutil.virtual_memory().available < w.T * w.R * rb + (30 << 30):
+        w = w.scaled(rows=w.R // 4)
+        say("5mq4: scaled to %d rows per table" % w.R)
+    _release_pinned_cache()
+    K = int(round(w.hot_fraction * w.R))
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    hosts, hots, entries = [], [], []
+    for t in range(w.T):
+        host = torch.empty((w.R, rb), dtype=torch.uint8, pin_memory=True)
+        ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+        src = torch.empty((w.R, w.D), dtype=torch.float32, device=H.DEV)
+        emb.emb_table_fill(src, w.R, w.D, "f32", w.table_seed(t))
+        emb.emb_quantize_rows(src, w.quant, ptr)
+        torch.cuda.synchronize()
+        del src
+        hot = wl.first_k_distinct_sorted(oracle.hash_ids(wl.hot_raw_ids(w, t, int(K * 1.06) + 1000), w.salt(t), w.R), K)
+        assert hot.size == K
+        index = torch.empty(emb.emb_cache_index_bytes(w.R), dtype=torch.uint8, device=H.DEV)
+        cache = torch.empty((K, rb), dtype=torch.uint8, device=H.DEV)
+        emb.emb_cache_build(ptr, w.R, w.D, w.quant, H.dev(hot), cache, index, status)
+        hosts.append(host)
+        hots.append(hot)
+        entries.append((ptr, w.R, cache, index, K, w.salt(t)))
+        say("5mq4: table %d quantised into pinned memory, cache built" % t)
+    torch.cuda.empty_cache()
+    ct = emb.CachedTables(entries, w.D, w.quant, device=torch.device(H.DEV))
+    batch = wl.make_batch(w, 0)
+    db = pipeline.DeviceBatch(w, batch, torch.device(H.DEV))
+    off_dev = torch.empty(w.T * w.B + 1, dtype=torch.int64, device=H.DEV)
+    out = torch.full((w.T, w.B, w.D), float("nan"), dtype=torch.float32, device=H.DEV)
+    hm = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    emb.emb_lengths_to_offsets(db.lengths, off_dev, status)
+    emb.emb_bag_forward_cached_tables_hashed(ct, db.raw, off_dev, w.B, w.pool, out, hm, status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    off, rows = _oracle_index(w, batch)
+    assert np.array_equal(off_dev.cpu().numpy(), off)
+    got = out.cpu().numpy()
+    hits = misses = 0
+    for t in range(w.T):
+        s, e = int(off[t * w.B]), int(off[(t + 1) * w.B])
+        r = rows[s:e]
+        touched = np.unique(r)
+        packed = oracle.quantize_rows(wl.table_values(w.table_seed(t), touched, w.D), w.quant)
+        hot_compact = np.flatnonzero(np.isin(touched, hots[t], assume_unique=True)).astype(np.int64)
+        ref, absum, (h, m), st = oracle.bag_forward_cached(packed, w.quant, hot_compact,
+                                                           np.searchsorted(touched, r).astype(np.int64),
+                                                           off[t * w.B:(t + 1) * w.B + 1] - s, w.B, w.pool, D=w.D)
+        assert st == 0
+        H.assert_pooled_close(got[t], ref[0], absum[0], what="workload 5mq4 table %d" % t)
+        hits, misses = hits + h, misses + m
+    assert hm.cpu().tolist() == [hits, misses]
+    say("5mq4: %d hits, %d misses" % (hits, misses))
+    assert 0.8 < hits / max(1, hits + misses) < 0.97
