@@ -40,14 +40,14 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "f8bc94c7bea74ed0",
+    "sources": "d50f2dd81ad208f6",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (178059.5, 67598.4), "update_kernel": (240600.6, 323999.4)},
-        "2u": {"bag_forward_kernel": (338146.4, 32768.0)},
-        "2un": {"bag_forward_kernel": (346113.8, 32768.0)},
-        "2uq4": {"bag_forward_quant_kernel": (233561.2, 32887.0)},
+        "3": {"bag_forward_train_kernel": (178034.6, 67593.8), "update_kernel": (240614.8, 324000.0)},
+        "2u": {"bag_forward_kernel": (338144.7, 32768.0)},
+        "2un": {"bag_forward_kernel": (346115.4, 32768.0)},
+        "2uq4": {"bag_forward_quant_kernel": (233568.7, 32886.2)},
     },
 }
 
