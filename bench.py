@@ -638,7 +638,7 @@ def main() -> int:
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
+        log("bench.py: this library runs on ONE GPU only (no sharding, no collectives); use --gpus 1")
         return 2
 
     import numpy as np
