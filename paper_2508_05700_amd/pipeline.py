@@ -5,7 +5,7 @@ backward).  It only sequences calls of ``binding``; nothing is computed here.
 """
 from __future__ import annotations
 
-from typing import Dict, List, Optional
+from typing import Dict, List, Optional, Sequence
 
 import numpy as np
 import torch
@@ -229,3 +229,33 @@ class HotRowCache:
         emb.emb_bag_forward_cached_hashed(self.table_ptr, self.R, self.D, self.dtype, self.rows[self.active],
                                           self.index[self.active], self.num_hot, self.salt, raw, offsets, B, mode, out,
                                           self.hit_miss, self.status)
+
+
+class HostedTableSet:
+    """Several host-resident tables, each with a ``HotRowCache``, looked up with one launch.  The descriptor
+    array names each table's active cache buffers, so it is rebuilt (a copy of T x 64 bytes) after a refresh."""
+
+    def __init__(self, caches: List[HotRowCache], device: torch.device):
+        assert len({(c.D, c.dtype) for c in caches}) == 1, "the tables of one launch share D and storage type"
+        self.caches, self.device = list(caches), device
+        self.D, self.dtype = caches[0].D, caches[0].dtype
+        self.hit_miss = torch.zeros(2, dtype=torch.int64, device=device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=device)
+        self._describe()
+
+    def _describe(self) -> None:
+        self.tables = emb.CachedTables([(c.table_ptr, c.R, c.rows[c.active], c.index[c.active], c.num_hot, c.salt)
+                                        for c in self.caches], self.D, self.dtype, device=self.device)
+
+    def observe(self, raw: torch.Tensor, offsets_host: Sequence[int], B: int) -> None:
+        """Count the lookups of a batch: ``offsets_host[t * B]`` bounds table t's slice of ``raw``."""
+        for t, c in enumerate(self.caches):
+            c.observe(raw[int(offsets_host[t * B]):int(offsets_host[(t + 1) * B])])
+
+    def refresh(self) -> None:
+        for c in self.caches:
+            c.refresh()
+        self._describe()
+
+    def forward_hashed(self, raw: torch.Tensor, offsets: torch.Tensor, B: int, mode: str, out: torch.Tensor) -> None:
+        emb.emb_bag_forward_cached_tables_hashed(self.tables, raw, offsets, B, mode, out, self.hit_miss, self.status)

@@ -1179,3 +1179,46 @@ def test_cached_forward_over_several_tables_in_one_launch(dtype, D):
             assert np.array_equal(one.cpu().numpy()[0], got[t])
         assert hm.cpu().tolist() == [hits, misses] and int(status.item()) == st_all
         assert st_all == (0 if hashed else emb.STATUS_BAD_INDEX)
+
+
+def test_hosted_table_set_with_policy_refresh_matches_the_oracle():
+    # two hosted tables, caches chosen by the policy, one launch per lookup; after each refresh the
+    # descriptor array names the new buffers
+    from paper_2508_05700_amd import pipeline
+    rng = np.random.default_rng(7100)
+    T, B, D = 2, 150, 32
+    Rs, Ks, salts = [9001, 30_011], [300, 1500], [5, 6]
+    tabs = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
+    tdev = [H.dev(x) for x in tabs]
+    caches = [pipeline.HotRowCache(int(tdev[t].data_ptr()), Rs[t], D, "f32", Ks[t], salts[t], torch.device(H.DEV))
+              for t in range(T)]
+    hs = pipeline.HostedTableSet(caches, torch.device(H.DEV))
+    freq = [np.zeros(R, np.uint32) for R in Rs]
+    hots = [np.zeros(0, np.int64) for _ in Rs]
+    out = torch.empty((T, B, D), dtype=torch.float32, device=H.DEV)
+    for step in range(6):
+        lengths = rng.integers(0, 50, size=T * B).astype(np.int32)
+        off, _ = oracle.lengths_to_offsets(lengths)
+        raw = (np.minimum(rng.zipf(1.2, size=int(off[-1])), 1 << 20).astype(np.uint64)) * np.uint64(0x9E3779B97F4A7C15)
+        hs.hit_miss.zero_()
+        hs.forward_hashed(H.dev(raw), H.dev(off), B, "sum", out)
+        hs.observe(H.dev(raw), off, B)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        hits = misses = 0
+        for t in range(T):
+            s, e = int(off[t * B]), int(off[(t + 1) * B])
+            rows = oracle.hash_ids(raw[s:e], salts[t], Rs[t])
+            ref, absum, (h, m), st = oracle.bag_forward_cached(tabs[t], "f32", hots[t], rows,
+                                                               off[t * B:(t + 1) * B + 1] - s, B, "sum")
+            H.assert_pooled_close(got[t], ref[0], absum[0], what="hosted set step %d table %d" % (step, t))
+            assert oracle.cache_observe(freq[t], rows) == 0 and st == 0
+            hits, misses = hits + h, misses + m
+        assert hs.hit_miss.cpu().tolist() == [hits, misses], step
+        if step % 2 == 1:
+            hs.refresh()
+            torch.cuda.synchronize()
+            for t in range(T):
+                hots[t] = oracle.cache_select(freq[t], Ks[t], 1)
+                assert np.array_equal(caches[t].hot[:Ks[t]].cpu().numpy(), hots[t])
+    assert hs.status.item() == 0 and hits > misses
