@@ -532,6 +532,17 @@ int emb_bag_forward_latched_hashed(const void *latch_dev, int32_t T, int32_t D, 
  * launched.  host_ptr: host; *dev_ptr_out: receives the device pointer. */
 int emb_host_device_pointer(const void *host_ptr, void **dev_ptr_out);
 
+/* ---- table memory checksum ----------------------------------------------- */
+
+/* *sum_out_dev = sum over the 32-bit little-endian words w_i (i = 0, 1, ...) of
+ * data_dev[0 .. bytes) of w_i * (i + 1), modulo 2^64.  data_dev: HBM or mapped
+ * host memory, 16-byte aligned; bytes a multiple of 16 (EMB_ERR_INVALID_ARG
+ * otherwise); 0 bytes give 0.  Lets a caller check that table rows a step did
+ * not touch are bit-identical without moving the table (the backward updates
+ * tables in place, Section 3.1), and, as a plain streaming read, measures the
+ * read bandwidth a kernel gets on this part. */
+int emb_checksum(const void *data_dev, uint64_t bytes, uint64_t *sum_out_dev, void *stream);
+
 /* ---- table initialisation ------------------------------------------------ */
 
 /* Fill a table with the procedural pseudo-normal values used by the synthetic

@@ -367,3 +367,17 @@ int oracle_cache_select(uint32_t *freq, int64_t num_rows, int64_t num_hot, int32
     for (int64_t r = 0; r < num_rows; ++r) freq[r] >>= decay_shift;
     return 0;
 }
+
+/* ---- checksum ------------------------------------------------------------ */
+
+uint64_t oracle_checksum(const void *data, uint64_t bytes)
+{
+    const unsigned char *p = (const unsigned char *)data;
+    uint64_t sum = 0;
+    for (uint64_t i = 0; i < bytes / 4; ++i) {
+        uint32_t w = (uint32_t)p[4 * i] | ((uint32_t)p[4 * i + 1] << 8) | ((uint32_t)p[4 * i + 2] << 16) |
+                     ((uint32_t)p[4 * i + 3] << 24);
+        sum += (uint64_t)w * (i + 1); /* unsigned: wraps modulo 2^64 */
+    }
+    return sum;
+}

@@ -126,6 +126,10 @@ int64_t oracle_cache_observe(uint32_t *freq, int64_t num_rows, const int64_t *ro
 int oracle_cache_select(uint32_t *freq, int64_t num_rows, int64_t num_hot, int32_t decay_shift,
                         int64_t *hot_rows_out);
 
+/* Position-weighted checksum of a buffer: sum over its 32-bit little-endian
+ * words w_i of w_i * (i + 1), modulo 2^64 (bytes a multiple of 4). */
+uint64_t oracle_checksum(const void *data, uint64_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -60,6 +60,8 @@ def lib() -> C.CDLL:
         L.oracle_cache_observe.argtypes = [vp, i64, vp, i64]
         L.oracle_cache_select.restype = C.c_int
         L.oracle_cache_select.argtypes = [vp, i64, i64, i32, vp]
+        L.oracle_checksum.restype = u64
+        L.oracle_checksum.argtypes = [vp, u64]
         L.oracle_bag_forward_cached.restype = None
         L.oracle_bag_forward_cached.argtypes = [vp, i64, i32, i32, vp, i64, vp, vp, i64, i64, i32,
                                                 vp, vp, vp, vp]
@@ -223,3 +225,9 @@ def cache_select(freq: np.ndarray, num_hot: int, decay_shift: int = 0) -> np.nda
     rc = lib().oracle_cache_select(_p(freq), freq.size, num_hot, decay_shift, _p(hot))
     assert rc == 0
     return hot
+
+
+def checksum(a: np.ndarray) -> int:
+    """Position-weighted checksum of the array's memory (C-contiguous, a multiple of 4 bytes)."""
+    assert a.flags["C_CONTIGUOUS"] and a.nbytes % 4 == 0
+    return int(lib().oracle_checksum(_p(a), a.nbytes))

@@ -52,7 +52,7 @@ EXPORTS = [
     "emb_version_latch", "emb_bag_forward_latched", "emb_bag_forward_latched_hashed",
     "emb_cached_tables_init", "emb_bag_forward_cached_tables", "emb_bag_forward_cached_tables_hashed",
     "emb_cache_observe", "emb_cache_observe_hashed", "emb_cache_select_workspace_bytes", "emb_cache_select", "emb_cache_rebuild",
-    "emb_table_fill",
+    "emb_table_fill", "emb_checksum",
 ]
 
 
@@ -166,6 +166,8 @@ def lib() -> C.CDLL:
     L.emb_bag_forward_cached_tables.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     L.emb_bag_forward_cached_tables_hashed.restype = C.c_int
     L.emb_bag_forward_cached_tables_hashed.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    L.emb_checksum.restype = C.c_int
+    L.emb_checksum.argtypes = [vp, u64, vp, vp]
     L.emb_host_device_pointer.restype = C.c_int
     L.emb_host_device_pointer.argtypes = [vp, C.POINTER(vp)]
     L.emb_table_fill.restype = C.c_int
@@ -727,6 +729,15 @@ def emb_bag_forward_cached_tables_hashed(ct: CachedTables, raw: torch.Tensor, of
                                          status: Optional[torch.Tensor] = None) -> None:
     _forward_cached_tables("emb_bag_forward_cached_tables_hashed", ct, raw, _U64, offsets, B, mode, out, hit_miss,
                            status)
+
+
+def emb_checksum(data, sum_out: torch.Tensor, nbytes: Optional[int] = None) -> None:
+    """``data``: a contiguous device tensor, or a raw device-visible pointer (int) with ``nbytes``."""
+    if isinstance(data, int):
+        ptr, n = data, int(nbytes)
+    else:
+        ptr, n = _ptr(data, None, "data"), data.numel() * data.element_size()
+    _check("emb_checksum", lib().emb_checksum(ptr, C.c_uint64(n), _ptr(sum_out, _U64, "sum_out"), _stream()))
 
 
 def emb_host_device_pointer(host_ptr: int) -> int:

@@ -356,6 +356,14 @@ def test_cached_tables_descriptor_and_argument_errors(L):
             assert fn(bad.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID, field
 
 
+def test_checksum_argument_errors(L):
+    assert L.emb_checksum(FAKE, 64, None, None) == INVALID
+    assert L.emb_checksum(None, 64, FAKE, None) == INVALID
+    assert L.emb_checksum(FAKE, 60, FAKE, None) == INVALID            # not whole 16-byte chunks
+    assert L.emb_checksum(FAKE + 8, 64, FAKE, None) == INVALID        # misaligned data
+    assert L.emb_checksum(FAKE, 64, FAKE + 4, None) == INVALID        # misaligned result
+
+
 def test_exact_remainder_on_the_host(tmp_path):
     exe = str(tmp_path / "u64mod_check")
     subprocess.check_call(["g++", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "paper_2508_05700_amd", "csrc"),

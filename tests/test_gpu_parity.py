@@ -1222,3 +1222,34 @@ def test_hosted_table_set_with_policy_refresh_matches_the_oracle():
                 hots[t] = oracle.cache_select(freq[t], Ks[t], 1)
                 assert np.array_equal(caches[t].hot[:Ks[t]].cpu().numpy(), hots[t])
     assert hs.status.item() == 0 and hits > misses
+
+
+def test_checksum_matches_the_oracle_and_sees_a_single_changed_bit():
+    rng = np.random.default_rng(7200)
+    out = torch.full((1,), -1, dtype=torch.int64, device=H.DEV)
+    for n_words in (0, 4, 1024, 4 * 999_983, 4 * 3_000_001):
+        w = rng.integers(0, 1 << 32, size=n_words, dtype=np.uint64).astype(np.uint32)
+        d = torch.from_numpy(w.view(np.int32).copy()).to(H.DEV)
+        emb.emb_checksum(d, out)
+        torch.cuda.synchronize()
+        assert int(out.item()) % (1 << 64) == oracle.checksum(w), n_words
+    # a table as the backward leaves it: only the touched rows differ, and the checksum of the rest says so
+    T, B, D = 1, 64, 32
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, [5000], 12, scale=0.01)
+    ts, wdev, acc = H.make_tableset(tables, "f32", with_accum=True)
+    before = wdev[0].clone()
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    g = H.gpu_backward(ts, rows, off, B, "sum", dout, 0.01, 1e-8)
+    untouched = np.setdiff1d(np.arange(5000), g["unique_keys"])
+    a = torch.zeros(1, dtype=torch.int64, device=H.DEV)
+    b = torch.zeros(1, dtype=torch.int64, device=H.DEV)
+    idx = torch.from_numpy(untouched).to(H.DEV)
+    emb.emb_checksum(before[idx].contiguous(), a)
+    emb.emb_checksum(wdev[0][idx].contiguous(), b)
+    torch.cuda.synchronize()
+    assert a.item() == b.item() and a.item() % (1 << 64) == oracle.checksum(np.ascontiguousarray(tables[0][untouched]))
+    flipped = wdev[0][idx].contiguous()
+    flipped.view(torch.int32)[1234, 7] ^= 1 << 20
+    emb.emb_checksum(flipped, b)
+    torch.cuda.synchronize()
+    assert a.item() != b.item()

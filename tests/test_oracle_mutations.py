@@ -56,6 +56,11 @@ MUTATIONS = [
     ("quant: row stride unpadded", "return (8 + code_bytes + 15) / 16 * 16;", "return 8 + code_bytes;"),
     ("quant: INT8 codes read as nibbles", "dtype == ORACLE_INT8 ? p[8 + d] :", "dtype != ORACLE_INT8 ? p[8 + d] :"),
     ("cached: hits and misses swapped", "hit_miss[hit ? 0 : 1] += 1;", "hit_miss[hit ? 1 : 0] += 1;"),
+    ("checksum: weights start at zero", "sum += (uint64_t)w * (i + 1);", "sum += (uint64_t)w * i;"),
+    ("checksum: unweighted", "sum += (uint64_t)w * (i + 1);", "sum += (uint64_t)w;"),
+    ("checksum: 32-bit product", "sum += (uint64_t)w * (i + 1);", "sum += (uint64_t)(uint32_t)(w * (uint32_t)(i + 1));"),
+    ("checksum: big-endian words", "(uint32_t)p[4 * i] | ((uint32_t)p[4 * i + 1] << 8) | ((uint32_t)p[4 * i + 2] << 16) |\n                     ((uint32_t)p[4 * i + 3] << 24)",
+     "(uint32_t)p[4 * i + 3] | ((uint32_t)p[4 * i + 2] << 8) | ((uint32_t)p[4 * i + 1] << 16) |\n                     ((uint32_t)p[4 * i] << 24)"),
     ("policy: counter incremented by two", "freq[r] += 1u;", "freq[r] += 2u;"),
     ("policy: out-of-range entries not counted", "++bad;\n            continue;", "continue;"),
     ("policy: smaller counters preferred", "if (fa != fb) return fa > fb ? -1 : 1;", "if (fa != fb) return fa > fb ? 1 : -1;"),

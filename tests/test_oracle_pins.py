@@ -659,3 +659,28 @@ def test_cache_policy_keeps_the_set_with_the_most_hits_on_the_observed_stream(or
     other = np.sort(rng.permutation(R)[:H]).astype(np.int64)
     _, _, (hits2, _), _ = oracle.bag_forward_cached(table, "f32", other, rows, off, B, "sum")
     assert hits2 <= hits
+
+
+# ---------------------------------------------------------------------------
+# checksum of table memory
+# ---------------------------------------------------------------------------
+
+def test_checksum_closed_forms_and_brute_force(oracle):
+    n = 1000
+    assert oracle.checksum(np.ones(n, np.uint32)) == n * (n + 1) // 2                    # sum of the weights
+    i = np.arange(n, dtype=np.uint32)
+    assert oracle.checksum(i) == sum(k * (k + 1) for k in range(n))                      # = (n-1) n (n+1) / 3
+    assert oracle.checksum(i) == (n - 1) * n * (n + 1) // 3
+    assert oracle.checksum(np.zeros(0, np.uint32)) == 0
+    # little-endian words, whatever the element type of the array
+    assert oracle.checksum(np.array([1, 0, 0, 0, 0, 1, 0, 0], np.uint8)) == 1 * 1 + 256 * 2
+    rng = np.random.default_rng(130)
+    w = rng.integers(0, 1 << 32, size=3001, dtype=np.uint64).astype(np.uint32)
+    want = sum(int(x) * (k + 1) for k, x in enumerate(w)) % (1 << 64)                    # big integers, then modulo
+    assert oracle.checksum(w) == want and want != sum(int(x) for x in w)
+    assert oracle.checksum(w.view(np.float32)) == want                                   # the bits, not the values
+    big = np.full(70_000, 0xFFFFFFFF, np.uint32)                                         # wraps past 2^64
+    assert oracle.checksum(big) == (0xFFFFFFFF * (70_000 * 70_001 // 2)) % (1 << 64)
+    sw = w.copy()
+    sw[[5, 900]] = sw[[900, 5]]
+    assert oracle.checksum(sw) != want                                                   # position matters
