@@ -384,6 +384,58 @@ def test_backward_hot_rows_take_the_workgroup_path(mode):
     _backward_case(rng, 2, 2000, 64, [50_000, 777], 25, "f32", mode, hot=0.3, steps=2)
 
 
+@pytest.mark.parametrize("seed,D,dtype", [(0, 64, "f32"), (1, 64, "f32"), (2, 32, "bf16"), (3, 320, "f32")])
+def test_backward_run_lengths_at_every_boundary(seed, D, dtype):
+    # The update works on spans of 256 sorted records, looks 32 records ahead, and hands runs of more than
+    # 32 records to another path that cuts them into 256-record chunks.  Here the multiplicities of the rows
+    # are chosen around those sizes and shuffled, so that runs of every such length start, end and cross at
+    # arbitrary places relative to the spans; lookups are dealt to bags at random, so every record carries a
+    # different gradient.
+    rng = np.random.default_rng(8000 + seed)
+    lengths_pool = [1] * 40 + [2, 3, 5, 30, 31, 32, 33, 34, 35, 63, 64, 65, 96, 223, 224, 225, 255, 256, 257, 258, 288,
+                               289, 511, 512, 513, 544, 1000, 2049]
+    T, B = 2, 300
+    Rs = [4000, 90_000]
+    rows_parts, lens = [], []
+    for t in range(T):
+        runs = rng.choice(lengths_pool, size=260 if t == 0 else 500)
+        ids = np.sort(rng.choice(Rs[t], size=runs.size, replace=False))
+        recs = np.repeat(ids, runs)
+        rng.shuffle(recs)                                             # order in the batch is arbitrary
+        cuts = np.sort(rng.integers(0, recs.size + 1, size=B - 1))    # deal them to B bags, some empty
+        lens.append(np.diff(np.concatenate([[0], cuts, [recs.size]])))
+        rows_parts.append(recs)
+    lengths = np.concatenate(lens).astype(np.int32)
+    rows = np.concatenate(rows_parts).astype(np.int64)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    bf = dtype == "bf16"
+    tables = []
+    for R in Rs:
+        v = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+        tables.append(wl.f32_to_bf16_bits(v).reshape(R, D) if bf else v)
+    base = np.concatenate([[0], np.cumsum(Rs)])
+    for mode, side in (("sum", True), ("mean", False)):
+        ref_tables = [t.copy() for t in tables]
+        ref_acc = [np.full(R, 0.5, dtype=np.float32) for R in Rs]
+        dout = rng.standard_normal((T, B, D)).astype(np.float32)
+        ts, w_dev, acc_dev = H.make_tableset(ref_tables, dtype, accum_np=ref_acc)
+        g = H.gpu_backward(ts, rows, off, B, mode, dout, 0.01, 1e-8, side=side)
+        r = oracle.bag_backward_rowwise_adagrad(ref_tables, ref_acc, dtype, rows, off, B, mode, dout, 0.01, 1e-8)
+        assert g["status"] == r["status"] == 0
+        assert np.array_equal(g["unique_keys"], r["unique_keys"]) and np.array_equal(g["unique_counts"], r["unique_counts"])
+        for t in range(T):
+            wg = H.as_f32(H.host_table(w_dev[t]))
+            ag = acc_dev[t].cpu().numpy()
+            sel = (r["unique_keys"] >= base[t]) & (r["unique_keys"] < base[t + 1])
+            touched = r["unique_keys"][sel] - base[t]
+            H.assert_rows_close(wg[touched], H.as_f32(ref_tables[t])[touched], H.as_f32(tables[t])[touched], 0.01,
+                                H.EPS_BF16 if bf else H.EPS32, what="rows t=%d %s" % (t, mode))
+            H.assert_accum_close(ag[touched], ref_acc[t][touched], r["Gabs"][sel], what="accum t=%d %s" % (t, mode))
+            mask = np.ones(Rs[t], dtype=bool)
+            mask[touched] = False
+            assert np.array_equal(wg[mask], H.as_f32(tables[t])[mask]) and (ag[mask] == 0.5).all()
+
+
 def test_backward_many_tiles_and_64_bit_keys():
     # > 4096 * 8 lookups (several sort tiles, ragged tail); second case: key range past 2^32
     rng = np.random.default_rng(42)
