@@ -364,6 +364,26 @@ def test_checksum_argument_errors(L):
     assert L.emb_checksum(FAKE, 64, FAKE + 4, None) == INVALID        # misaligned result
 
 
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    # The boundary is a C ABI: the header must compile as C11 (and as C++) on its own, and a C program that
+    # takes the address of every declared entry point must link against the built library.
+    header = open(os.path.join(ROOT, "include", "emb.h")).read()
+    names = sorted(set(re.findall(r"\b(emb_[a-z_0-9]+)\s*\(", re.sub(r"/\*.*?\*/", "", header, flags=re.S))))
+    src = tmp_path / "use.c"
+    src.write_text('#include "emb.h"\n#include <stdio.h>\ntypedef void (*fn)(void);\nint main(void) {\n    fn f[] = {%s};\n'
+                   '    printf("%%d %%s\\n", (int)(sizeof f / sizeof f[0]), emb_status_string(EMB_ERR_WORKSPACE));\n'
+                   '    return f[0] == 0;\n}\n' % ", ".join("(fn)%s" % n for n in names))
+    inc = os.path.join(ROOT, "include")
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)])
+    subprocess.check_call(["g++", "-std=c++17", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", "-I", inc, str(src)])
+    exe = tmp_path / "use"
+    libdir = os.path.dirname(b.lib_path())
+    subprocess.check_call(["gcc", "-std=c11", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-lemb_hip",
+                           "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.check_output([str(exe)], env=dict(os.environ, LD_LIBRARY_PATH="/opt/rocm/lib")).decode().split(None, 1)
+    assert int(out[0]) == len(names) == len(b.EXPORTS) and "workspace" in out[1].lower()
+
+
 def test_exact_remainder_on_the_host(tmp_path):
     exe = str(tmp_path / "u64mod_check")
     subprocess.check_call(["g++", "-O2", "-std=c++17", "-I", os.path.join(ROOT, "paper_2508_05700_amd", "csrc"),
