@@ -497,3 +497,46 @@ def test_workload_5mq4_four_hosted_int4_tables_in_one_launch():
     assert hm.cpu().tolist() == [hits, misses]
     say("5mq4: %d hits, %d misses" % (hits, misses))
     assert 0.8 < hits / max(1, hits + misses) < 0.97
+
+
+def test_workload_mix_24_tables_of_four_widths_in_one_launch():
+    # The launch bench.py times for workload "mix": 24 full-size tables (D = 16/32/64/128, fp32 and bf16),
+    # config 2's batch recipe, one mixed-width lookup writing one concatenated vector per sample.
+    w = wl.WORKLOADS["mix"]
+    spec = wl.MIX_SPEC
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}
+    say("mix: filling %d tables (%.1f GB)" % (len(spec), sum(R * D * (4 if dt == "f32" else 2) for D, dt, R in spec) / 2 ** 30))
+    weights = []
+    for t, (D, dt, R) in enumerate(spec):
+        wt = torch.empty((R, D), dtype=tdt[dt], device=H.DEV)
+        emb.emb_table_fill(wt, R, D, dt, w.table_seed(t))
+        weights.append(wt)
+    mt = emb.MixedTables(weights, w.B, "concat", salts=[w.salt(t) for t in range(w.T)], device=torch.device(H.DEV))
+    batch = wl.make_batch(w, 0)
+    db = pipeline.DeviceBatch(w, batch, torch.device(H.DEV))
+    offsets = torch.empty(w.T * w.B + 1, dtype=torch.int64, device=H.DEV)
+    rows_dev = torch.empty(db.nnz, dtype=torch.int64, device=H.DEV)
+    out = torch.full((mt.out_floats,), float("nan"), dtype=torch.float32, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_lengths_to_offsets(db.lengths, offsets, status)
+    emb.emb_hash_ids_tables(mt.tables, db.raw, offsets, w.B, rows_dev, status)
+    emb.emb_bag_forward_mixed(mt, rows_dev, offsets, w.pool, out, status)
+    torch.cuda.synchronize()
+    assert status.item() == 0
+    off, st = oracle.lengths_to_offsets(batch["lengths"])
+    assert st == 0 and np.array_equal(offsets.cpu().numpy(), off)
+    got = out.cpu().numpy().reshape(w.B, sum(D for D, _, _ in spec))
+    rows_got = rows_dev.cpu().numpy()
+    col = 0
+    for t, (D, dt, R) in enumerate(spec):
+        s, e = int(off[t * w.B]), int(off[(t + 1) * w.B])
+        rows = oracle.hash_ids(batch["raw"][s:e], w.salt(t), R)
+        assert np.array_equal(rows_got[s:e], rows)
+        touched = np.unique(rows)
+        table = wl.table_rows(w.table_seed(t), touched, D, dt)
+        ref, absum, st = oracle.bag_forward([table], dt, np.searchsorted(touched, rows).astype(np.int64),
+                                            off[t * w.B:(t + 1) * w.B + 1] - s, w.B, w.pool)
+        assert st == 0
+        H.assert_pooled_close(got[:, col:col + D], ref[0], absum[0], what="mix table %d (D=%d %s)" % (t, D, dt))
+        col += D
+    say("mix: %d lookups over %d tables checked" % (db.nnz, w.T))
