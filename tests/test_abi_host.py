@@ -364,7 +364,7 @@ def test_checksum_argument_errors(L):
     assert L.emb_checksum(FAKE, 64, FAKE + 4, None) == INVALID        # misaligned result
 
 
-def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+def test_header_is_plain_c_and_links_against_the_library(L, tmp_path):
     # The boundary is a C ABI: the header must compile as C11 (and as C++) on its own, and a C program that
     # takes the address of every declared entry point must link against the built library.
     header = open(os.path.join(ROOT, "include", "emb.h")).read()
