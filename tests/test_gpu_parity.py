@@ -1305,3 +1305,96 @@ def test_checksum_matches_the_oracle_and_sees_a_single_changed_bit():
     emb.emb_checksum(flipped, b)
     torch.cuda.synchronize()
     assert a.item() != b.item()
+
+
+# ---------------------------------------------------------------------------
+# the calls only enqueue kernels: a caller can capture them in a HIP graph
+# ---------------------------------------------------------------------------
+
+def _graph_inputs(rng, T, B, max_len, Rs):
+    lengths = rng.integers(0, max_len + 1, size=T * B).astype(np.int32)
+    nnz = int(lengths.sum())
+    raw = rng.integers(0, 1 << 64, size=nnz, dtype=np.uint64)
+    return lengths, raw
+
+
+@pytest.mark.parametrize("side", [False, True])
+def test_a_captured_training_step_replays_like_eager_calls(side):
+    # offsets + training lookup + sort + update captured once into a graph, then replayed on new inputs
+    # written into the same buffers (the number of lookups is part of the captured arguments, so every batch
+    # here has the same total); each replay is compared with the oracle, with eager work and
+    # synchronisations between the replays.
+    rng = np.random.default_rng(9000 + side)
+    T, B, D = 3, 400, 64
+    Rs = [5000, 300, 20_000]
+    tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
+    ref_tables = [t.copy() for t in tables]
+    ref_acc = [np.zeros(R, np.float32) for R in Rs]
+    ts, w_dev, acc_dev = H.make_tableset(ref_tables, "f32", accum_np=ref_acc, salts=[3, 4, 5])
+    nnz = 9000
+
+    def batch():
+        cuts = np.sort(rng.integers(0, nnz + 1, size=T * B - 1))
+        lengths = np.diff(np.concatenate([[0], cuts, [nnz]])).astype(np.int32)
+        raw = np.minimum(rng.zipf(1.3, size=nnz), 1 << 30).astype(np.uint64) * np.uint64(0x9E3779B97F4A7C15)
+        dout = rng.standard_normal((T, B, D)).astype(np.float32)
+        return lengths, raw, dout
+
+    dev = torch.device(H.DEV)
+    lengths_d = torch.zeros(T * B, dtype=torch.int32, device=dev)
+    raw_d = torch.zeros(nnz, dtype=torch.int64, device=dev)
+    dout_d = torch.zeros((T, B, D), dtype=torch.float32, device=dev)
+    offsets_d = torch.zeros(T * B + 1, dtype=torch.int64, device=dev)
+    out_d = torch.zeros((T, B, D), dtype=torch.float32, device=dev)
+    ws = torch.empty(emb.emb_bag_backward_workspace_bytes(T, B, nnz, ts.total_rows, D, "f32"), dtype=torch.uint8, device=dev)
+    nu = torch.zeros(1, dtype=torch.int64, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    sd = H.side_stream() if side else None
+
+    def step():
+        emb.emb_lengths_to_offsets(lengths_d, offsets_d, status)
+        emb.emb_bag_forward_train(ts, raw_d, offsets_d, B, "mean", out_d, ws, None, nu, status)
+        emb.emb_bag_backward_sort_prepared(ts, B, nnz, ws, None, None, nu, status, None)
+        emb.emb_bag_backward_update(ts, B, nnz, dout_d, 0.01, 1e-8, ws, nu, None, sd)
+
+    def load(b):
+        lengths_d.copy_(torch.from_numpy(b[0]))
+        raw_d.copy_(torch.from_numpy(b[1].view(np.int64)))
+        dout_d.copy_(torch.from_numpy(b[2]))
+
+    def check(b, what):
+        off, _ = oracle.lengths_to_offsets(b[0])
+        rows = np.concatenate([oracle.hash_ids(b[1][off[t * B]:off[(t + 1) * B]], 3 + t, Rs[t]) for t in range(T)])
+        old = [t.copy() for t in ref_tables]
+        ref_out, absum, st = oracle.bag_forward(ref_tables, "f32", rows, off, B, "mean")
+        r = oracle.bag_backward_rowwise_adagrad(ref_tables, ref_acc, "f32", rows, off, B, "mean", b[2], 0.01, 1e-8)
+        assert st == 0 and r["status"] == 0 and status.item() == 0
+        H.assert_pooled_close(out_d.cpu().numpy(), ref_out, absum, what=what + " forward")
+        assert int(nu.item()) == r["unique_keys"].size
+        for t in range(T):
+            H.assert_rows_close(w_dev[t].cpu().numpy(), ref_tables[t], old[t], 0.01, what="%s rows t=%d" % (what, t))
+            w_dev[t].copy_(torch.from_numpy(ref_tables[t]))      # both sides go on from identical state
+            acc_dev[t].copy_(torch.from_numpy(ref_acc[t]))
+
+    b0 = batch()
+    load(b0)
+    step()                                                            # eager, also warms everything up
+    torch.cuda.synchronize()
+    check(b0, "eager")
+    cap = torch.cuda.Stream(device=dev)
+    graph = torch.cuda.CUDAGraph()
+    b1 = batch()
+    load(b1)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=cap):
+        step()
+    # capturing does not run anything: tables and outputs are as the eager step left them
+    for i in range(3):
+        bi = b1 if i == 0 else batch()
+        load(bi)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check(bi, "replay %d" % i)
+        junk = torch.randn(1 << 20, device=dev).sum().item()          # eager work between the replays
+        assert np.isfinite(junk)
