@@ -44,10 +44,10 @@ PMC_TRAFFIC = {
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (178029.6, 67600.2), "update_kernel": (240583.3, 323999.8)},
-        "2u": {"bag_forward_kernel": (338143.4, 32768.0)},
-        "2un": {"bag_forward_kernel": (346111.3, 32768.0)},
-        "2uq4": {"bag_forward_quant_kernel": (233571.6, 32885.2)},
+        "3": {"bag_forward_train_kernel": (178057.9, 67593.4), "update_kernel": (240606.3, 323999.7)},
+        "2u": {"bag_forward_kernel": (338146.1, 32768.0)},
+        "2un": {"bag_forward_kernel": (346110.8, 32768.0)},
+        "2uq4": {"bag_forward_quant_kernel": (233561.4, 32882.6)},
     },
 }
 
