@@ -684,3 +684,16 @@ def test_checksum_closed_forms_and_brute_force(oracle):
     sw = w.copy()
     sw[[5, 900]] = sw[[900, 5]]
     assert oracle.checksum(sw) != want                                                   # position matters
+
+
+def test_cache_select_by_partition_agrees_with_the_sorting_definition(oracle):
+    rng = np.random.default_rng(140)
+    for R in (1, 2, 37, 1000, 50_001):
+        for freq in (rng.integers(0, 3, size=R).astype(np.uint32),
+                     np.minimum(rng.zipf(1.2, size=R), 1 << 31).astype(np.uint32),
+                     np.full(R, 0xFFFFFFFF, np.uint32), np.zeros(R, np.uint32)):
+            for num_hot in sorted({0, 1, R // 20, R // 2, R}):
+                a, b = freq.copy(), freq.copy()
+                ha = oracle.cache_select(a, num_hot, 2)
+                hb = oracle.cache_select_large(b, num_hot, 2)
+                assert np.array_equal(ha, hb) and np.array_equal(a, b)
