@@ -8,9 +8,9 @@
  * table sets whose lookups return the version they were computed from.
  *
  * Source of the problem statement: "Multi-Faceted Large Embedding Tables for
- * Pinterest Ads Ranking", Section 2.2 (high-cardinality categorical features
- * are mapped to dense embeddings through hashed lookup tables; collisions are
- * legal), Section 3.1 (several ID tables of ~1e8-1e9 rows, fine-tuned inside
+ * Pinterest Ads Ranking", Section 2.2 (an ID feature with very many distinct
+ * values selects its vector by hashing the ID into a table of fixed size, so two
+ * IDs may share a row), Section 3.1 (several ID tables of ~1e8-1e9 rows, fine-tuned inside
  * the ranking model) and Section 3.3 (tables too large for GPU memory are
  * hosted in CPU memory, and a request is served by tables and upper model of
  * one version) and Section 4.1.2 (those tables are stored as INT4 after
@@ -183,7 +183,12 @@ int emb_event_elapsed_ms(void *start, void *stop, float *ms_out);
  * Singer 2011 with one accumulator per row).  With g_j = c_b * dout[t,b,:]
  * for lookup j of bag (t,b), c_b = 1 (sum) or 1/len_b (mean):
  *   for every distinct (t, row) in the batch, once:
- *     G      = sum of g_j over its lookups, in ascending j
+ *     G      = sum of g_j over its lookups, in a fixed order that does not
+ *              depend on timing: ascending j for a row with at most 32
+ *              lookups in the batch; a row with more has its lookups dealt
+ *              round-robin to lane groups whose partial sums are joined by a
+ *              fixed tree, 256 lookups at a time, the pieces then added in
+ *              ascending order
  *     S_new  = S_old + (1/D) * sum_d G[d]^2
  *     W_new  = W_old - lr * G / (sqrt(S_new) + eps)
  * Duplicates are summed BEFORE the nonlinear update.  weights and accum of
@@ -421,7 +426,7 @@ int emb_bag_forward_cached_tables_hashed(const emb_cached_table *tables_host,
                                          uint32_t *status_dev, void *stream);
 
 /* ---- which rows the cache holds: frequency-based policy -------------------
- * Section 5 lists better caching strategies as open work and the paper names
+ * Section 6 lists better caching strategies as open work and the paper names
  * no policy; the one built here is frequency-based admission with batched
  * refresh.  freq_dev is a u32 counter per table row (u32[num_rows], 16-byte
  * aligned, owned and zeroed by the caller).  A refresh is emb_cache_select,

@@ -114,7 +114,7 @@ void oracle_bag_forward_cached(const void *table, int64_t num_rows, int32_t D, i
                                float *out, double *absum, uint64_t *hit_miss, uint32_t *status);
 
 /* Frequency-based cache policy for the hot-row cache ("caching strategies",
- * Section 5; the paper names no policy, this is the reading built here).
+ * Section 6; the paper names no policy, this is the reading built here).
  * Access counters: freq[r] += 1 (u32, wrapping) for every entry of rows that is
  * in [0, num_rows); returns the number of entries that are not. */
 int64_t oracle_cache_observe(uint32_t *freq, int64_t num_rows, const int64_t *rows, int64_t nnz);

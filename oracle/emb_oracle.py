@@ -231,22 +231,3 @@ def checksum(a: np.ndarray) -> int:
     """Position-weighted checksum of the array's memory (C-contiguous, a multiple of 4 bytes)."""
     assert a.flags["C_CONTIGUOUS"] and a.nbytes % 4 == 0
     return int(lib().oracle_checksum(_p(a), a.nbytes))
-
-
-def cache_select_large(freq: np.ndarray, num_hot: int, decay_shift: int = 0) -> np.ndarray:
-    """The rule of ``cache_select`` evaluated with numpy's selection instead of a full sort, for tables of
-    hundreds of millions of rows where the sorting definition takes minutes: the num_hot-th largest counter is
-    the threshold; every row above it is kept, and of the rows equal to it the smallest row numbers, as many
-    as still fit.  freq is aged in place.  Pinned against ``cache_select`` in the CPU tests."""
-    _chk(freq, np.uint32)
-    R = freq.size
-    assert 0 <= num_hot <= R and 0 <= decay_shift <= 31
-    if num_hot == 0:
-        hot = np.zeros(0, dtype=np.int64)
-    else:
-        thr = np.partition(freq, R - num_hot)[R - num_hot]           # the num_hot-th largest value
-        above = np.flatnonzero(freq > thr)
-        tied = np.flatnonzero(freq == thr)[:num_hot - above.size]      # flatnonzero is ascending
-        hot = np.sort(np.concatenate([above, tied])).astype(np.int64)
-    freq >>= np.uint32(decay_shift)
-    return hot

@@ -71,12 +71,16 @@ def lib_path() -> str:
 
 
 def lib() -> C.CDLL:
-    """Load ``libemb_hip.so``; build it first only if no built library exists.
+    """Load ``libemb_hip.so``; build it first if no built library exists or if a
+    kernel source or header is newer than the built one (where the sources are
+    present and a compiler is at hand: a stale library is never loaded silently).
     There is no fallback: without the HIP library nothing in this package works."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
+    if _build.is_stale():
+        if os.path.exists(_build.LIB) and not os.path.exists(_build.HIPCC):
+            raise RuntimeError("libemb_hip.so is older than its sources and no hipcc is here to rebuild it")
         _build.build(verbose=False)
     L = C.CDLL(_build.LIB)
     vp, i64, i32, u64, f32, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float, C.c_size_t

@@ -9,8 +9,10 @@
 //            many passes as the largest table needs; leaves keys row_base + row,
 //            the marker as the sentinel total_rows               (radix_sort.h)
 //   update   runs of equal keys are found on the fly; each run's gradients are
-//            summed in ascending record order and Adagrad is applied once to
-//            its row; long runs are cut into chunks summed by wavefronts (update.h)
+//            summed in a fixed order (ascending record order for runs of up to
+//            UPD_SHORT_MAX records; longer runs are cut into chunks, each summed
+//            by a wavefront as a fixed tree, and the chunk sums added in chunk
+//            order) and Adagrad is applied once to its row              (update.h)
 //   runs     only when the caller asks for the list of distinct rows: head
 //            flags, scan and compaction into unique keys and counts
 // The payload carried through the sort is the bag number: lookups of one row

@@ -1,5 +1,5 @@
 // Which rows the HBM hot-row cache of a host-resident table holds (paper
-// Section 3.3 for the hosted table; Section 5 names better caching strategies
+// Section 3.3 for the hosted table; Section 6 names better caching strategies
 // as open work and gives no policy, so this one is a stated choice):
 // frequency-based admission with batched refresh.
 //

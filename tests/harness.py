@@ -137,3 +137,23 @@ def gpu_backward(ts, rows_np, off_np, B, mode, dout_np, lr, eps, want_unique=Tru
     U = int(nu.item())
     return {"unique_keys": uk[:U].cpu().numpy(), "unique_counts": uc[:U].cpu().numpy(), "U": U,
             "status": int(status.item())}
+
+
+def cache_select_large(freq: np.ndarray, num_hot: int, decay_shift: int = 0) -> np.ndarray:
+    """The rule of ``cache_select`` evaluated with numpy's selection instead of a full sort, for tables of
+    hundreds of millions of rows where the sorting definition takes minutes: the num_hot-th largest counter is
+    the threshold; every row above it is kept, and of the rows equal to it the smallest row numbers, as many
+    as still fit.  freq is aged in place.  Test-side arithmetic, not part of the oracle: the CPU tests pin it to ``oracle.cache_select`` (the sorting
+    definition) on inputs with many ties and at the extremes of num_hot."""
+    assert freq.dtype == np.uint32 and freq.flags["C_CONTIGUOUS"]
+    R = freq.size
+    assert 0 <= num_hot <= R and 0 <= decay_shift <= 31
+    if num_hot == 0:
+        hot = np.zeros(0, dtype=np.int64)
+    else:
+        thr = np.partition(freq, R - num_hot)[R - num_hot]           # the num_hot-th largest value
+        above = np.flatnonzero(freq > thr)
+        tied = np.flatnonzero(freq == thr)[:num_hot - above.size]      # flatnonzero is ascending
+        hot = np.sort(np.concatenate([above, tied])).astype(np.int64)
+    freq >>= np.uint32(decay_shift)
+    return hot

@@ -207,7 +207,8 @@ def test_workload_4_one_billion_row_bf16_table():
     w = wl.WORKLOADS["4"]
     free, total = torch.cuda.mem_get_info()
     if free < 70 * 2 ** 30:
-        pytest.skip("needs 64 GB of free HBM")
+        pytest.skip("workload 4 at full size needs 70 GB of free HBM; %.0f GB free" % (free / 2 ** 30))
+    assert w.R == 1_000_000_000 and w.D == 32
     say("filling 1e9 x 32 bf16 (64 GB) on the device")
     tabs = pipeline.DeviceTables(w)
     torch.cuda.synchronize()
@@ -215,6 +216,20 @@ def test_workload_4_one_billion_row_bf16_table():
     _forward_parity(w, tabs)
     del tabs
     torch.cuda.empty_cache()
+
+
+def _full_size_or_skip(name, host_bytes):
+    """The workload at exactly its stated size, or a skip that says why: these tests never run on a
+    smaller table under the same name."""
+    import psutil
+    w = wl.WORKLOADS[name]
+    avail = psutil.virtual_memory().available
+    if avail < host_bytes:
+        pytest.skip("workload %s at full size needs %.0f GB of free host memory to pin its table(s); %.0f GB available"
+                    % (name, host_bytes / 2 ** 30, avail / 2 ** 30))
+    say("workload %s at full size: %d table(s) x %d rows (%.0f GB of host memory available)"
+        % (name, w.T, w.R, avail / 2 ** 30))
+    return w
 
 
 def _release_pinned_cache():
@@ -288,13 +303,8 @@ def _hybrid_parity(w, say_name):
 
 
 def test_workload_5_host_table_with_hbm_cache():
-    w = wl.WORKLOADS["5"]
-    import psutil
-    avail = psutil.virtual_memory().available
-    if avail < 90 * 2 ** 30:
-        # not enough host memory to pin 64 GB: run the same recipe on a quarter-size table
-        w = w.scaled(rows=w.R // 4)
-        say("workload 5 scaled to %d rows: only %.0f GB of host memory available" % (w.R, avail / 2 ** 30))
+    w = _full_size_or_skip("5", 90 * 2 ** 30)
+    assert w.R == 250_000_000 and w.D == 64                  # 64 GB of fp32 rows in pinned host memory
     rate = _hybrid_parity(w, "workload " + w.name)
     assert 0.85 < rate < 0.97            # Zipf(1.1) over 1e9 keys: the top 5 % of rows carry ~92 % of lookups
 
@@ -303,12 +313,9 @@ def test_workload_5q4_int4_host_table_with_hbm_cache():
     # Workload 5 with the hosted table stored as INT4 rows (the paper quantises exactly these tables).
     # The fp32 table is filled in HBM and quantised into pinned host memory by the device; the oracle
     # quantises the generator's values of the rows the batch and the checks touch.
-    w = wl.WORKLOADS["5q4"]
-    import psutil
-    rb = emb.emb_row_bytes(w.D, w.quant)
-    if psutil.virtual_memory().available < w.R * rb + (26 << 30):
-        w = w.scaled(rows=w.R // 4)
-        say("workload 5q4 scaled to %d rows" % w.R)
+    rb = emb.emb_row_bytes(wl.WORKLOADS["5q4"].D, wl.WORKLOADS["5q4"].quant)
+    w = _full_size_or_skip("5q4", wl.WORKLOADS["5q4"].R * rb + (26 << 30))
+    assert w.R == 250_000_000
     _release_pinned_cache()
     rng = np.random.default_rng(6)
     K = int(round(w.hot_fraction * w.R))
@@ -371,12 +378,9 @@ def test_workload_5q4_cache_policy_at_full_size():
     # whole table; the selected hot set row for row against the oracle's rule evaluated by selection instead
     # of a full sort (the sorting definition takes minutes over 2.5e8 rows; the two are pinned to each other
     # on the CPU); the refreshed cache's rows and the lookup through it against the oracle.
-    w = wl.WORKLOADS["5q4"]
-    import psutil
-    rb = emb.emb_row_bytes(w.D, w.quant)
-    if psutil.virtual_memory().available < w.R * rb + (30 << 30):
-        w = w.scaled(rows=w.R // 4)
-        say("cache policy: scaled to %d rows" % w.R)
+    rb = emb.emb_row_bytes(wl.WORKLOADS["5q4"].D, wl.WORKLOADS["5q4"].quant)
+    w = _full_size_or_skip("5q4", wl.WORKLOADS["5q4"].R * rb + (30 << 30))
+    assert w.R == 250_000_000
     _release_pinned_cache()
     rng = np.random.default_rng(7)
     K = int(round(w.hot_fraction * w.R))
@@ -406,7 +410,7 @@ def test_workload_5q4_cache_policy_at_full_size():
         cache.refresh()
         torch.cuda.synchronize()
         thr, tied_taken = [int(x) for x in cache.info.cpu().tolist()]
-        hot = oracle.cache_select_large(ref_freq, K, 1)                               # also ages ref_freq
+        hot = H.cache_select_large(ref_freq, K, 1)                               # also ages ref_freq
         assert np.array_equal(cache.hot[:K].cpu().numpy(), hot)                       # the hot set, row for row
         assert thr == int(counts[hot].min()) and tied_taken == int((counts[hot] == thr).sum())
         assert np.array_equal(cache.freq.cpu().numpy().view(np.uint32), ref_freq)
@@ -446,12 +450,10 @@ def test_workload_5q4_cache_policy_at_full_size():
 def test_workload_5mq4_four_hosted_int4_tables_in_one_launch():
     # The launch bench.py times for workload 5mq4: four hosted INT4 tables with their caches, raw IDs, one
     # cached lookup for all.  The oracle quantises the generator's values of the rows each table's lookups touch.
-    w = wl.WORKLOADS["5mq4"]
-    import psutil
-    rb = emb.emb_row_bytes(w.D, w.quant)
-    if psutil.virtual_memory().available < w.T * w.R * rb + (30 << 30):
-        w = w.scaled(rows=w.R // 4)
-        say("5mq4: scaled to %d rows per table" % w.R)
+    w0 = wl.WORKLOADS["5mq4"]
+    rb = emb.emb_row_bytes(w0.D, w0.quant)
+    w = _full_size_or_skip("5mq4", w0.T * w0.R * rb + (30 << 30))
+    assert w.T * w.R == 250_000_000
     _release_pinned_cache()
     K = int(round(w.hot_fraction * w.R))
     status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
