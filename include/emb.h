@@ -463,6 +463,26 @@ int emb_cache_select(uint32_t *freq_dev, int64_t num_rows, int64_t num_hot, int3
                      void *workspace_dev, size_t workspace_bytes, int64_t *hot_rows_out_dev,
                      uint64_t *info_out_dev, void *stream);
 
+/* emb_cache_select for callers that cannot allocate device memory or be handed
+ * a workspace: code under HIP graph capture, tight serving loops that refresh
+ * a cache between requests, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as emb_cache_select, without workspace_dev /
+ * workspace_bytes: the scratch memory is a 4 MiB array inside the library's
+ * device code, one per GPU the library is used on, held until the process
+ * ends.  The call allocates and frees nothing.  num_rows above
+ * EMB_CACHE_SELECT_STATIC_MAX_ROWS is rejected with EMB_ERR_UNSUPPORTED and
+ * nothing is launched.  All calls on one GPU share that GPU's array: calls
+ * whose kernels may overlap on one GPU (different streams) race and must be
+ * ordered by the caller; calls in stream order on one stream are safe, and
+ * nothing is assumed about what an earlier call left in the array.  The first
+ * call on a GPU looks up the array's device address (a host-side query, no
+ * allocation, EMB_ERR_HIP if the runtime refuses); make that first call
+ * outside a stream capture. */
+#define EMB_CACHE_SELECT_STATIC_MAX_ROWS 700000000
+int emb_cache_select_static(uint32_t *freq_dev, int64_t num_rows, int64_t num_hot,
+                            int32_t decay_shift, int64_t *hot_rows_out_dev,
+                            uint64_t *info_out_dev, void *stream);
+
 /* emb_cache_build for a refresh: builds the cache for hot_rows_dev in
  * cache_rows_dev / cache_index_dev, copying a row from the older cache
  * (old_cache_rows_dev, old_cache_index_dev, old_num_hot: a cache of the same

@@ -51,7 +51,8 @@ EXPORTS = [
     "emb_version_record_bytes", "emb_version_latch_bytes", "emb_version_record_write", "emb_version_publish",
     "emb_version_latch", "emb_bag_forward_latched", "emb_bag_forward_latched_hashed",
     "emb_cached_tables_init", "emb_bag_forward_cached_tables", "emb_bag_forward_cached_tables_hashed",
-    "emb_cache_observe", "emb_cache_observe_hashed", "emb_cache_select_workspace_bytes", "emb_cache_select", "emb_cache_rebuild",
+    "emb_cache_observe", "emb_cache_observe_hashed", "emb_cache_select_workspace_bytes", "emb_cache_select", "emb_cache_select_static",
+    "emb_cache_rebuild",
     "emb_table_fill", "emb_checksum",
 ]
 
@@ -148,6 +149,8 @@ def lib() -> C.CDLL:
     L.emb_cache_select_workspace_bytes.argtypes = [i64, C.POINTER(sz)]
     L.emb_cache_select.restype = C.c_int
     L.emb_cache_select.argtypes = [vp, i64, i64, i32, vp, sz, vp, vp, vp]
+    L.emb_cache_select_static.restype = C.c_int
+    L.emb_cache_select_static.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.emb_cache_rebuild.restype = C.c_int
     L.emb_cache_rebuild.argtypes = [vp, i64, i32, i32, vp, vp, i64, vp, i64, vp, vp, vp, vp, vp]
     L.emb_version_record_bytes.restype = C.c_int
@@ -613,6 +616,19 @@ def emb_cache_select(freq: torch.Tensor, num_hot: int, decay_shift: int, workspa
     _check("emb_cache_select", lib().emb_cache_select(
         _ptr(freq, _U32, "freq"), freq.numel(), int(num_hot), int(decay_shift), _ptr(workspace, torch.uint8, "workspace"),
         workspace.numel(), _ptr(hot_rows_out, torch.int64, "hot_rows_out"), _ptr(info_out, _U64, "info_out"), _stream()))
+
+
+CACHE_SELECT_STATIC_MAX_ROWS = 700_000_000   # EMB_CACHE_SELECT_STATIC_MAX_ROWS
+
+
+def emb_cache_select_static(freq: torch.Tensor, num_hot: int, decay_shift: int, hot_rows_out: torch.Tensor,
+                            info_out: Optional[torch.Tensor] = None) -> None:
+    """``emb_cache_select`` with the library's own static scratch array instead of a workspace."""
+    if hot_rows_out.numel() < num_hot:
+        raise TypeError("hot_rows_out too small")
+    _check("emb_cache_select_static", lib().emb_cache_select_static(
+        _ptr(freq, _U32, "freq"), freq.numel(), int(num_hot), int(decay_shift),
+        _ptr(hot_rows_out, torch.int64, "hot_rows_out"), _ptr(info_out, _U64, "info_out"), _stream()))
 
 
 def emb_cache_rebuild(table_ptr: int, num_rows: int, D: int, dtype: str, old_cache_rows: Optional[torch.Tensor],

@@ -14,6 +14,8 @@
 // exactly that value are taken; two more streaming passes then count and
 // compact the selected rows in ascending row order, which is the order the
 // cache index needs.  Everything is integer work: results are exact.
+#include <mutex>
+
 #include "emb_internal.h"
 #include "u64mod.h"
 
@@ -397,18 +399,15 @@ extern "C" int emb_cache_select_workspace_bytes(int64_t num_rows, size_t *bytes)
     return EMB_OK;
 }
 
-extern "C" int emb_cache_select(uint32_t *freq_dev, int64_t num_rows, int64_t num_hot, int32_t decay_shift,
-                                void *workspace_dev, size_t workspace_bytes, int64_t *hot_rows_out_dev,
-                                uint64_t *info_out_dev, void *stream)
+namespace {
+
+// The launches of a selection over counters freq_dev, with the scratch memory at `ws` (laid out by
+// sel_layout, at least that large, 256-byte aligned).  Nothing in `ws` has to be zero on entry:
+// sel_init_kernel clears the control block and the histograms, every other word is written before
+// it is read.
+int select_run(uint32_t *freq_dev, int64_t num_rows, int64_t num_hot, int32_t decay_shift, const SelLayout &L, char *ws,
+               int64_t *hot_rows_out_dev, uint64_t *info_out_dev, hipStream_t s)
 {
-    if (num_rows <= 0 || num_hot < 0 || num_hot > num_rows || decay_shift < 0 || decay_shift > 31)
-        return EMB_ERR_INVALID_ARG;
-    if (!freq_dev || !emb_aligned(freq_dev, 16) || (num_hot > 0 && !hot_rows_out_dev)) return EMB_ERR_INVALID_ARG;
-    const SelLayout L = sel_layout(num_rows);
-    if (L.tiles > 0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
-    if (!workspace_dev || !emb_aligned(workspace_dev, 256) || workspace_bytes < L.total) return EMB_ERR_WORKSPACE;
-    hipStream_t s = emb_stream(stream);
-    char *ws = reinterpret_cast<char *>(workspace_dev);
     SelCtrl *ctrl = reinterpret_cast<SelCtrl *>(ws + L.ctrl);
     unsigned long long *hist = reinterpret_cast<unsigned long long *>(ws + L.hist);
     uint2 *counts = reinterpret_cast<uint2 *>(ws + L.counts);
@@ -433,8 +432,6 @@ extern "C" int emb_cache_select(uint32_t *freq_dev, int64_t num_rows, int64_t nu
         EMB_RETURN_IF_LAUNCH_FAILED();
         hipLaunchKernelGGL(sel_scan_kernel, dim3(1), dim3(SCAN_BLOCK), 0, s, counts, L.tiles, gt_before, eq_before);
         EMB_RETURN_IF_LAUNCH_FAILED();
-    }
-    if (num_hot > 0) {
         hipLaunchKernelGGL(sel_write_kernel, dim3((unsigned)L.tiles), dim3(CP_BLOCK), 0, s, freq_dev, num_rows, ctrl,
                            gt_before, eq_before, num_hot, (int)decay_shift, hot_rows_out_dev);
         EMB_RETURN_IF_LAUNCH_FAILED();
@@ -448,4 +445,78 @@ extern "C" int emb_cache_select(uint32_t *freq_dev, int64_t num_rows, int64_t nu
         EMB_RETURN_IF_LAUNCH_FAILED();
     }
     return EMB_OK;
+}
+
+int select_check(const uint32_t *freq_dev, int64_t num_rows, int64_t num_hot, int32_t decay_shift,
+                 const int64_t *hot_rows_out_dev)
+{
+    if (num_rows <= 0 || num_hot < 0 || num_hot > num_rows || decay_shift < 0 || decay_shift > 31)
+        return EMB_ERR_INVALID_ARG;
+    if (!freq_dev || !emb_aligned(freq_dev, 16) || (num_hot > 0 && !hot_rows_out_dev)) return EMB_ERR_INVALID_ARG;
+    return EMB_OK;
+}
+
+}  // namespace
+
+extern "C" int emb_cache_select(uint32_t *freq_dev, int64_t num_rows, int64_t num_hot, int32_t decay_shift,
+                                void *workspace_dev, size_t workspace_bytes, int64_t *hot_rows_out_dev,
+                                uint64_t *info_out_dev, void *stream)
+{
+    const int rc = select_check(freq_dev, num_rows, num_hot, decay_shift, hot_rows_out_dev);
+    if (rc != EMB_OK) return rc;
+    const SelLayout L = sel_layout(num_rows);
+    if (L.tiles > 0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+    if (!workspace_dev || !emb_aligned(workspace_dev, 256) || workspace_bytes < L.total) return EMB_ERR_WORKSPACE;
+    return select_run(freq_dev, num_rows, num_hot, decay_shift, L, reinterpret_cast<char *>(workspace_dev),
+                      hot_rows_out_dev, info_out_dev, emb_stream(stream));
+}
+
+// ---------------------------------------------------------------------------
+// the selection for callers that cannot allocate
+// ---------------------------------------------------------------------------
+// The scratch memory of emb_cache_select_static: one array per device, part of the
+// loaded code object, held until the process ends.  In host code the name `scratch`
+// is only a handle for hipGetSymbolAddress: the device address it stands for on a
+// given device is looked up once per device (sel_static_address) and that address,
+// never the name, is what the kernels are given.
+constexpr size_t SEL_STATIC_BYTES = (size_t)4 << 20;
+static __device__ __align__(256) unsigned char scratch[SEL_STATIC_BYTES];
+
+namespace {
+
+constexpr int SEL_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+char *g_scratch_ptr[SEL_MAX_DEVICES];   // by device ordinal; null until that device's first call
+
+// Device address of `scratch` on the current device; null if the runtime refuses.
+char *sel_static_address()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= SEL_MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        g_scratch_ptr[dev] = reinterpret_cast<char *>(p);
+    }
+    return g_scratch_ptr[dev];
+}
+
+}  // namespace
+
+static_assert(EMB_CACHE_SELECT_STATIC_MAX_ROWS / SEL_TILE + 1 <= (SEL_STATIC_BYTES - 256 - 8 * SEL_PASSES * SEL_RADIX - 3 * 256) / 24,
+              "the static scratch array holds the selection's tile tables up to the stated maximum");
+
+extern "C" int emb_cache_select_static(uint32_t *freq_dev, int64_t num_rows, int64_t num_hot, int32_t decay_shift,
+                                       int64_t *hot_rows_out_dev, uint64_t *info_out_dev, void *stream)
+{
+    const int rc = select_check(freq_dev, num_rows, num_hot, decay_shift, hot_rows_out_dev);
+    if (rc != EMB_OK) return rc;
+    if (num_rows > EMB_CACHE_SELECT_STATIC_MAX_ROWS) return EMB_ERR_UNSUPPORTED;   // beyond the scratch array
+    const SelLayout L = sel_layout(num_rows);
+    if (L.total > SEL_STATIC_BYTES) return EMB_ERR_UNSUPPORTED;
+    char *ws = sel_static_address();
+    if (!ws) return EMB_ERR_HIP;
+    return select_run(freq_dev, num_rows, num_hot, decay_shift, L, ws, hot_rows_out_dev, info_out_dev,
+                      emb_stream(stream));
 }

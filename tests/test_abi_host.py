@@ -289,6 +289,17 @@ def test_cache_policy_argument_errors(L):
     assert L.emb_cache_select(FAKE, 100, 10, 0, None, ws, FAKE, None, None) == WORKSPACE
     assert L.emb_cache_select(FAKE, 100, 10, 0, FAKE, ws - 1, FAKE, None, None) == WORKSPACE
     assert L.emb_cache_select(FAKE, 100, 10, 0, FAKE + 16, ws, FAKE, None, None) == WORKSPACE
+    # the variant with the library's own scratch array: same checks, and a stated maximum size, all before
+    # anything is launched or the array is looked up
+    assert L.emb_cache_select_static(FAKE, 100, 101, 0, FAKE, None, None) == INVALID
+    assert L.emb_cache_select_static(FAKE, 100, 10, 32, FAKE, None, None) == INVALID
+    assert L.emb_cache_select_static(FAKE + 4, 100, 10, 0, FAKE, None, None) == INVALID
+    assert L.emb_cache_select_static(FAKE, 100, 10, 0, None, None, None) == INVALID
+    assert L.emb_cache_select_static(None, 100, 10, 0, FAKE, None, None) == INVALID
+    assert L.emb_cache_select_static(FAKE, b.CACHE_SELECT_STATIC_MAX_ROWS + 1, 10, 0, FAKE, None, None) == UNSUPPORTED
+    header = open(os.path.join(ROOT, "include", "emb.h")).read()
+    assert int(re.search(r"#define EMB_CACHE_SELECT_STATIC_MAX_ROWS (\d+)", header).group(1)) == b.CACHE_SELECT_STATIC_MAX_ROWS
+    assert L.emb_cache_select_workspace_bytes(b.CACHE_SELECT_STATIC_MAX_ROWS, C.byref(n)) == OK and n.value <= 4 << 20
     # a refresh needs an older cache, in buffers other than the new ones
     OLD = FAKE + 4096
     assert L.emb_cache_rebuild(FAKE, 100, 64, 0, OLD, None, 5, FAKE, 10, FAKE, FAKE, None, None, None) == INVALID
