@@ -33,7 +33,7 @@ namespace {
 // ---------------------------------------------------------------------------
 struct BwdLayout {
     size_t ctrl, keys_a, keys_b, pay_a, pay_b, bag_scale, first_tile, tile_desc, hist, tile_heads, seg_start, seg_real,
-        queue, wave_heads, segs, multi_list, chunk_tasks, partials, total;
+        queue, queue_end, span_head, wave_heads, segs, multi_list, chunk_tasks, partials, total;
     int key_bytes;
     int lpr, cpl;       // lanes per row and chunks per lane of the update kernels
     int64_t tiles;      // tiles of the sort: none straddles two tables
@@ -93,6 +93,8 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     L.seg_start = off;   off += align256((n + 1) * 4);
     L.seg_real = off;    off += align256(n * 4);
     L.queue = off;       off += align256((size_t)L.qslots * 4);
+    L.queue_end = off;   off += align256((size_t)L.qslots * 4);
+    L.span_head = off;   off += align256((size_t)L.slots * 4);
     L.wave_heads = off;  off += align256((size_t)L.upd_blocks * (UPD_BLOCK / EMB_WAVE) * 4);
     L.segs = off;        off += align256((size_t)L.qslots * sizeof(LongSeg));
     L.multi_list = off;  off += align256((size_t)L.qslots * 4);
@@ -357,6 +359,8 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     BwdCtrl *ctrl = reinterpret_cast<BwdCtrl *>(a.ws + L.ctrl);
     float *bag_scale = reinterpret_cast<float *>(a.ws + L.bag_scale);
     uint32_t *queue = reinterpret_cast<uint32_t *>(a.ws + L.queue);
+    uint32_t *queue_end = reinterpret_cast<uint32_t *>(a.ws + L.queue_end);
+    uint32_t *span_head = reinterpret_cast<uint32_t *>(a.ws + L.span_head);
     uint32_t *wave_heads = reinterpret_cast<uint32_t *>(a.ws + L.wave_heads);
     LongSeg *segs = reinterpret_cast<LongSeg *>(a.ws + L.segs);
     uint32_t *multi_list = reinterpret_cast<uint32_t *>(a.ws + L.multi_list);
@@ -382,7 +386,7 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     }
     constexpr int DWAVES = 256 / EMB_WAVE;
     hipLaunchKernelGGL(long_detect_kernel<KeyT>, dim3((unsigned)((L.slots + DWAVES - 1) / DWAVES)), dim3(256), 0, ls,
-                       keys, n, sentinel, ctrl, queue, wave_heads, (uint32_t)L.slots);
+                       keys, n, sentinel, ctrl, queue, queue_end, span_head, wave_heads, (uint32_t)L.slots);
     EMB_RETURN_IF_LAUNCH_FAILED();
 
     hipLaunchKernelGGL((update_kernel<KeyT, LPR, CPL, EU, BF16>), dim3((unsigned)L.upd_blocks), dim3(UPD_BLOCK), 0,
@@ -392,9 +396,9 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     EMB_MARK(a, 4);
 
     const int64_t pthreads = L.qslots > L.slots ? L.qslots : L.slots;
-    hipLaunchKernelGGL(long_prepare_kernel<KeyT>, dim3((unsigned)((pthreads + PREP_BLOCK - 1) / PREP_BLOCK)),
-                       dim3(PREP_BLOCK), 0, ls, keys, n, sentinel, ctrl, queue, (uint32_t)L.qslots, wave_heads,
-                       (uint32_t)L.slots, segs, multi_list, chunk_tasks, (uint32_t)L.chunk_cap);
+    hipLaunchKernelGGL(long_prepare_kernel, dim3((unsigned)((pthreads + PREP_BLOCK - 1) / PREP_BLOCK)), dim3(PREP_BLOCK),
+                       0, ls, n, ctrl, queue, queue_end, (uint32_t)L.qslots, span_head, wave_heads, (uint32_t)L.slots, segs,
+                       multi_list, chunk_tasks, (uint32_t)L.chunk_cap);
     EMB_RETURN_IF_LAUNCH_FAILED();
 
     // one wavefront per task; enough workgroups to fill the chip, tasks beyond that are strided over

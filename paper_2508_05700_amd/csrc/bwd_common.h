@@ -14,9 +14,9 @@ static_assert(sizeof(BwdCtrl) == 256, "control block is one 256-byte line");
 
 constexpr int RADIX_BITS = 8;
 constexpr int RADIX = 1 << RADIX_BITS;
-constexpr int SORT_BLOCK = 256;
+constexpr int SORT_BLOCK = 512;
 constexpr int SORT_WAVES = SORT_BLOCK / EMB_WAVE;
-constexpr int SORT_ITEMS = 16;
+constexpr int SORT_ITEMS = 8;
 constexpr int SORT_TILE = SORT_BLOCK * SORT_ITEMS;  // 4096 records per workgroup
 constexpr int SORT_PAD = 320;                       // records of slack after the key / payload arrays
 

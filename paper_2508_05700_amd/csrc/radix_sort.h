@@ -23,8 +23,9 @@ static_assert(sizeof(SortTile) == 32, "tile descriptors are read as two 16-byte 
 // Stable rank of every record of a wavefront's share of a tile among the records
 // of the same digit, and the wavefront's digit counts.  A wavefront walks its
 // share 64 records at a time in ascending order; lanes holding the same digit
-// are matched with one ballot per digit bit, the lowest of them bumps the
-// wavefront's private LDS counter, so there are no LDS atomics and no
+// are matched with one ballot per digit bit (every lane collects the lanes whose
+// bit differs from its own: what is left are its peers), the lowest of them bumps
+// the wavefront's private LDS counter, so there are no LDS atomics and no
 // same-address serialisation when many records share a digit (the hot rows of
 // a skewed batch, or the table bits of the key).
 template <typename KeyT, bool WANT_RANK>
@@ -38,14 +39,17 @@ __device__ __forceinline__ void wave_rank_digits(const KeyT (&key)[SORT_ITEMS], 
     for (int k = 0; k < SORT_ITEMS; ++k) {
         const uint32_t i = wbase + k * EMB_WAVE + lane;
         const bool live = i < n;
+        rank[k] = 0;
+        const uint64_t lv = __ballot(live);
+        if (lv == 0) continue;            // uniform: the share ends before this step
         const uint32_t digit = (uint32_t)(key[k] >> shift) & (RADIX - 1);
-        uint64_t peers = __ballot(live);  // dead lanes match nobody
+        uint64_t differ = 0;
 #pragma unroll
         for (int bit = 0; bit < RADIX_BITS; ++bit) {
-            const bool set = (digit >> bit) & 1u;
-            const uint64_t m = __ballot(set);
-            peers &= set ? m : ~m;
+            const uint64_t mine = 0ull - (uint64_t)((digit >> bit) & 1u);   // all ones if my bit is set
+            differ |= __ballot(mine != 0) ^ mine;
         }
+        const uint64_t peers = lv & ~differ;   // dead lanes match nobody
         const uint32_t before = __popcll(peers & lt_mask);
         uint32_t prev = 0;
         if (live && before == 0) {  // lowest lane of each digit group updates the wavefront's counter
@@ -71,15 +75,15 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__res
     if (ctrl->abort) return;
     __shared__ uint32_t cnt[SORT_WAVES][RADIX];
     const SortTile tile = desc[blockIdx.x];
-    uint32_t *slot = hist + (size_t)threadIdx.x * (tiles + 1) + blockIdx.x;
+    const bool owner = threadIdx.x < RADIX;   // thread d < RADIX reports digit d
+    uint32_t *slot = hist + (size_t)(owner ? threadIdx.x : 0) * (tiles + 1) + blockIdx.x;
     if (tile.count == 0) {   // uniform over the workgroup
-        *slot = 0;
+        if (owner) *slot = 0;
         return;
     }
     const int lane = threadIdx.x & (EMB_WAVE - 1);
     const int wave = threadIdx.x / EMB_WAVE;
-#pragma unroll
-    for (int w = 0; w < SORT_WAVES; ++w) cnt[w][threadIdx.x] = 0;  // SORT_BLOCK == RADIX
+    for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_BLOCK) (&cnt[0][0])[i] = 0;
     __syncthreads();
     const uint32_t end = tile.start + tile.count;
     const uint32_t wbase = tile.start + wave * (SORT_TILE / SORT_WAVES);
@@ -109,12 +113,14 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__res
         }
     }
     __syncthreads();
-    uint32_t c = 0;
+    if (owner) {
+        uint32_t c = 0;
 #pragma unroll
-    for (int w = 0; w < SORT_WAVES; ++w) c += cnt[w][threadIdx.x];
-    *slot = c;
+        for (int w = 0; w < SORT_WAVES; ++w) c += cnt[w][threadIdx.x];
+        *slot = c;
+    }
 }
-static_assert(SORT_BLOCK == RADIX, "histogram kernels map one thread to one digit");
+static_assert(SORT_BLOCK >= RADIX && SORT_BLOCK % RADIX == 0, "the first RADIX threads of a workgroup own one digit each");
 
 // One workgroup per digit: exclusive scan of that digit's per-tile counts in
 // place; the digit's total goes to the row's last column.
@@ -171,8 +177,12 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
     if (tile.count == 0) return;   // uniform over the workgroup
     const int lane = threadIdx.x & (EMB_WAVE - 1);
     const int wave = threadIdx.x / EMB_WAVE;
-#pragma unroll
-    for (int w = 0; w < SORT_WAVES; ++w) cnt[w][threadIdx.x] = 0;
+    // thread d's three entries of the scanned histogram do not depend on the records: they are
+    // asked for together with them, not after the ranking
+    const bool owner = threadIdx.x < RADIX;   // thread d < RADIX looks after digit d
+    const uint32_t *hrow = hist + (size_t)(owner ? threadIdx.x : 0) * (tiles + 1);
+    const uint32_t p_first = hrow[tile.first], p_next = hrow[tile.next], p_mine = hrow[blockIdx.x];
+    for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_BLOCK) (&cnt[0][0])[i] = 0;
     __syncthreads();
 
     const uint32_t end = tile.start + tile.count;
@@ -194,29 +204,31 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
     // counts add up to at most SORT_TILE, so the low half never carries), the wavefronts'
     // offsets within it, and the shift to global positions
     {
-        const uint32_t d = threadIdx.x;
-        const uint32_t *row = hist + (size_t)d * (tiles + 1);
-        const uint32_t p_first = row[tile.first];
-        const uint32_t digit_total = row[tile.next] - p_first;        // in this table
-        const uint32_t before_in_digit = row[blockIdx.x] - p_first;   // in this table's earlier tiles
+        const uint32_t d = owner ? threadIdx.x : 0;
+        const uint32_t digit_total = owner ? p_next - p_first : 0;   // in this table
+        const uint32_t before_in_digit = p_mine - p_first;           // in this table's earlier tiles
         uint32_t c[SORT_WAVES], total = 0;
+        if (owner) {
 #pragma unroll
-        for (int w = 0; w < SORT_WAVES; ++w) {
-            c[w] = cnt[w][d];
-            total += c[w];
+            for (int w = 0; w < SORT_WAVES; ++w) {
+                c[w] = cnt[w][d];
+                total += c[w];
+            }
         }
         unsigned long long all;
         const unsigned long long inc = block_inclusive_scan<unsigned long long, SORT_BLOCK>(
             ((unsigned long long)digit_total << 32) | total, wave_sums, all);
-        const uint32_t start = (uint32_t)inc - total;
-        const uint32_t below = (uint32_t)(inc >> 32) - digit_total;
-        uint32_t run = start;
+        if (owner) {
+            const uint32_t start = (uint32_t)inc - total;
+            const uint32_t below = (uint32_t)(inc >> 32) - digit_total;
+            uint32_t run = start;
 #pragma unroll
-        for (int w = 0; w < SORT_WAVES; ++w) {
-            cnt[w][d] = run;
-            run += c[w];
+            for (int w = 0; w < SORT_WAVES; ++w) {
+                cnt[w][d] = run;
+                run += c[w];
+            }
+            delta[d] = tile.seg_start + below + before_in_digit - start;
         }
-        delta[d] = tile.seg_start + below + before_in_digit - start;
     }
     __syncthreads();
 

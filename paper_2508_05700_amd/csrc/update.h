@@ -24,9 +24,10 @@
 // slots (no more such runs can start in one span).  Which slot is a matter of
 // timing, but queued runs are independent of each other, so values are not.
 //
-// Queued runs.  A second kernel finds the end of every queued run (galloping
-// then narrowing in the sorted keys, eight probes per round trip), cuts it into LONG_CHUNK-record chunks and
-// makes one task per chunk.  A third kernel gives each task to one wavefront,
+// Queued runs.  The kernel that queues them also notes where runs start; a second
+// kernel takes the end of every queued run from those notes (the next run start in
+// its span, else the first run start of the spans after it), cuts it into
+// LONG_CHUNK-record chunks and makes one task per chunk.  A third kernel gives each task to one wavefront,
 // whose lane groups take the chunk's records round-robin and are then combined
 // by a fixed butterfly; a run of one chunk is finished there, runs of several
 // chunks store their chunk sums and a last small kernel, one wavefront per run,
@@ -409,10 +410,18 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
 // apart, so a span has at most UPD_QSLOTS of them: they go to the span's queue slots
 // in ascending order, unused slots are marked.  The kernel only reads the keys, so
 // it and the kernels it feeds can run beside update_kernel on another stream.
-// It also counts the runs (= distinct rows) of the span.
+// It also counts the runs (= distinct rows) of the span, and records where runs
+// start, which is where the run before them ends: for every queued run the next
+// run start inside the span (queue_end, NO_RECORD if there is none), and the
+// span's first run start (span_head), so that the end of a run that leaves its span
+// is found by looking at the spans after it and not by searching the keys.
+constexpr uint32_t NO_RECORD = 0xFFFFFFFFu;
+
 template <typename KeyT>
 __global__ __launch_bounds__(256) void long_detect_kernel(const KeyT *__restrict__ keys, uint32_t n, KeyT sentinel,
                                                           const BwdCtrl *ctrl, uint32_t *__restrict__ queue,
+                                                          uint32_t *__restrict__ queue_end,
+                                                          uint32_t *__restrict__ span_head,
                                                           uint32_t *__restrict__ wave_heads, uint32_t slots)
 {
     if (ctrl->abort) return;
@@ -429,97 +438,100 @@ __global__ __launch_bounds__(256) void long_detect_kernel(const KeyT *__restrict
         load_records<KeyT, 4>(keys + i + UPD_SHORT_MAX, far);
         if (i > 0) prev = keys[i - 1];
     }
-    uint32_t heads = 0, start = 0xFFFFFFFFu;
+    uint32_t heads = 0, start = NO_RECORD;
+    uint32_t change = 0;   // bit e: record i + e starts a run (of a row, or of the marker of invalid rows)
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         if (i + e < n) {
-            const bool head = k[e] != sentinel && (i + e == 0 || k[e] != prev);
+            const bool first = i + e == 0 || k[e] != prev;
+            const bool head = first && k[e] != sentinel;
+            change |= (first ? 1u : 0u) << e;
             heads += head ? 1u : 0u;
             if (head && i + e + UPD_SHORT_MAX < n && far[e] == k[e]) start = i + e;   // at most one per lane
             prev = k[e];
         }
     }
-    const uint64_t m = __ballot(start != 0xFFFFFFFFu);
+    // the run starts of the span as four masks over the lanes (position in the span = 4 * lane + e)
+    uint64_t cm[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) cm[e] = __ballot(((change >> e) & 1u) != 0);
+    const uint64_t above = (lane == EMB_WAVE - 1) ? 0ull : (~0ull << (lane + 1));   // the lanes after mine
+    uint32_t next = NO_RECORD;   // first run start after my queued run, inside the span
+    uint32_t head0 = NO_RECORD;  // first run start of the span
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (cm[e]) head0 = min(head0, (uint32_t)(__ffsll((unsigned long long)cm[e]) - 1) * 4 + e);
+        if (start != NO_RECORD) {
+            const uint64_t later = cm[e] & ((uint32_t)e > start - i ? (above | (1ull << lane)) : above);
+            if (later) next = min(next, (uint32_t)(__ffsll((unsigned long long)later) - 1) * 4 + e);
+        }
+    }
+    const uint64_t m = __ballot(start != NO_RECORD);
     const uint32_t rank = (uint32_t)__popcll(m & ((lane == 0) ? 0ull : (~0ull >> (64 - lane))));
     const uint32_t count = (uint32_t)__popcll(m);
     uint32_t *q = queue + (size_t)wid * UPD_QSLOTS;
-    if (start != 0xFFFFFFFFu && rank < (uint32_t)UPD_QSLOTS) q[rank] = start;
-    if (lane < UPD_QSLOTS && (uint32_t)lane >= count) q[lane] = 0xFFFFFFFFu;
+    if (start != NO_RECORD && rank < (uint32_t)UPD_QSLOTS) {
+        q[rank] = start;
+        queue_end[(size_t)wid * UPD_QSLOTS + rank] = next == NO_RECORD ? NO_RECORD : wid * UPD_SPAN + next;
+    }
+    if (lane < UPD_QSLOTS && (uint32_t)lane >= count) q[lane] = NO_RECORD;
 #pragma unroll
     for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) heads += __shfl_xor(heads, d, EMB_WAVE);
-    if (lane == 0) wave_heads[wid] = heads;
+    if (lane == 0) {
+        wave_heads[wid] = heads;
+        span_head[wid] = head0 == NO_RECORD ? NO_RECORD : wid * UPD_SPAN + head0;
+    }
 }
 
-// One thread per queue slot: find the run's end, cut it into chunks, create the
-// tasks.  Also adds up the per-span run counts.
-template <typename KeyT>
-__global__ __launch_bounds__(PREP_BLOCK) void long_prepare_kernel(const KeyT *__restrict__ keys, uint32_t n, KeyT sentinel,
-                                                           BwdCtrl *ctrl,
-                                                           const uint32_t *__restrict__ queue, uint32_t slots,
+// One thread per queue slot: the run's end, its chunks, the tasks.  Also adds up the
+// per-span run counts.  A run ends where the next run starts: inside its own span
+// (queue_end), else at the first run start of the spans after it, which the
+// wavefront looks up together, 64 spans per round trip.
+__global__ __launch_bounds__(PREP_BLOCK) void long_prepare_kernel(uint32_t n, BwdCtrl *ctrl,
+                                                           const uint32_t *__restrict__ queue,
+                                                           const uint32_t *__restrict__ queue_end, uint32_t slots,
+                                                           const uint32_t *__restrict__ span_head,
                                                            const uint32_t *__restrict__ wave_heads,
-                                                           uint32_t n_wave_heads, LongSeg *__restrict__ segs,
+                                                           uint32_t n_spans, LongSeg *__restrict__ segs,
                                                            uint32_t *__restrict__ multi_list,
                                                            uint2 *__restrict__ chunk_tasks, uint32_t chunk_cap)
 {
     if (ctrl->abort) return;
     __shared__ uint32_t wave_sums[PREP_BLOCK / EMB_WAVE];
     const uint32_t s = blockIdx.x * PREP_BLOCK + threadIdx.x;
+    const int lane = threadIdx.x & (EMB_WAVE - 1);
 
     // distinct rows: sum of the run counts
     {
-        uint32_t h = s < n_wave_heads ? wave_heads[s] : 0u, total;
+        uint32_t h = s < n_spans ? wave_heads[s] : 0u, total;
         block_inclusive_scan<uint32_t, PREP_BLOCK>(h, wave_sums, total);
         if (threadIdx.x == 0 && total) atomicAdd(&ctrl->num_unique, total);
     }
 
-    uint32_t lo = 0xFFFFFFFFu;
-    if (s < slots) lo = queue[s];
-    uint32_t hi = 0, chunks = 0;
-    if (lo != 0xFFFFFFFFu) {
-        const KeyT key = keys[lo];
-        // The first record whose key differs lies in [a, b] (b == n: none does).  Eight probes are
-        // requested together in every round, so the search takes a few memory round trips.
-        // The run is longer than UPD_LOOK records, so the gallop starts there.
-        uint32_t a = lo + 1, b = n;
-        bool bracketed = false;
-        for (uint32_t j0 = 0; j0 < 27 && !bracketed; j0 += 8) {
-            KeyT pk[8];
-            uint32_t pp[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint64_t at = (uint64_t)lo + ((uint64_t)UPD_LOOK << (j0 + j));
-                pp[j] = at < n ? (uint32_t)at : n;
-                pk[j] = pp[j] < n ? keys[pp[j]] : sentinel;   // the sentinel differs from every run's key
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (bracketed) continue;
-                if (pk[j] == key) a = pp[j] + 1;
-                else { b = pp[j]; bracketed = true; }
-            }
-        }
-        while (a < b) {
-            const uint32_t step = (b - a + 8) / 9;                // >= 1
-            KeyT pk[8];
-            uint32_t pp[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint64_t at = (uint64_t)a + (uint64_t)step * (j + 1) - 1;
-                pp[j] = at < b ? (uint32_t)at : b;                 // b itself is known to differ (or is n)
-                pk[j] = pp[j] < b ? keys[pp[j]] : sentinel;
-            }
-            bool cut = false;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (cut) continue;
-                if (pp[j] >= b) { cut = true; continue; }
-                if (pk[j] == key) a = pp[j] + 1;
-                else { b = pp[j]; cut = true; }
-            }
-        }
-        hi = a;
-        chunks = (hi - lo + LONG_CHUNK - 1) / LONG_CHUNK;
+    uint32_t lo = NO_RECORD, hi = 0, chunks = 0;
+    if (s < slots) {   // both asked for together; queue_end of an unused slot is never looked at
+        lo = queue[s];
+        hi = queue_end[s];
     }
+    // runs that leave their span: one at a time, the whole wavefront looks at the following spans
+    uint64_t open = __ballot(lo != NO_RECORD && hi == NO_RECORD);
+    while (open) {   // uniform
+        const int l = __ffsll((unsigned long long)open) - 1;
+        open &= open - 1;
+        uint32_t w = (uint32_t)__shfl((int)lo, l, EMB_WAVE) / UPD_SPAN + 1;
+        uint32_t found = n;                                 // no later run start: the run ends with the records
+        while (w < n_spans) {   // uniform
+            const uint32_t v = w + lane < n_spans ? span_head[w + lane] : NO_RECORD;
+            const uint64_t hit = __ballot(v != NO_RECORD);
+            if (hit) {
+                found = (uint32_t)__shfl((int)v, __ffsll((unsigned long long)hit) - 1, EMB_WAVE);
+                break;
+            }
+            w += EMB_WAVE;
+        }
+        if (lane == l) hi = found;
+    }
+    if (lo != NO_RECORD) chunks = (hi - lo + LONG_CHUNK - 1) / LONG_CHUNK;
     // task slots: exclusive scans inside the workgroup, then ONE atomic per workgroup on a packed
     // counter (tasks in the low half, runs of several chunks in the high half): same-address
     // device atomics are slow, and there are hundreds of workgroups

@@ -515,6 +515,79 @@ def test_backward_sort_segments_small_empty_and_large_tables():
         assert np.array_equal(w_dev2[t].cpu().numpy(), w_dev[t].cpu().numpy())
 
 
+def _check_backward_against_oracle(tables, Rs, rows, off, B, D, mode, dout, what, expect_status=0):
+    T = len(Rs)
+    base = np.concatenate([[0], np.cumsum(Rs)])
+    ts, w_dev, acc_dev = H.make_tableset(tables, "f32", with_accum=True)
+    g = H.gpu_backward(ts, rows, off, B, mode, dout, 0.01, 1e-8)
+    ref_t, ref_a = [t.copy() for t in tables], [np.zeros(R, np.float32) for R in Rs]
+    r = oracle.bag_backward_rowwise_adagrad(ref_t, ref_a, "f32", rows, off, B, mode, dout, 0.01, 1e-8)
+    assert g["status"] == r["status"] == expect_status
+    assert np.array_equal(g["unique_keys"], r["unique_keys"]), what
+    assert np.array_equal(g["unique_counts"], r["unique_counts"]), what
+    for t in range(T):
+        sel = (r["unique_keys"] >= base[t]) & (r["unique_keys"] < base[t + 1])
+        touched = r["unique_keys"][sel] - base[t]
+        idx = torch.from_numpy(touched).to(H.DEV)
+        H.assert_rows_close(w_dev[t][idx].cpu().numpy(), ref_t[t][touched], tables[t][touched], 0.01,
+                            what="%s rows t=%d" % (what, t))
+        H.assert_accum_close(acc_dev[t][idx].cpu().numpy(), ref_a[t][touched], r["Gabs"][sel],
+                             what="%s accum t=%d" % (what, t))
+        assert int((acc_dev[t] != 0).sum().item()) == int((ref_a[t] != 0).sum())      # nothing else was touched
+
+
+def test_backward_sort_tables_of_very_different_key_widths():
+    # Tables whose keys need different numbers of sort passes in one batch (the passes cover the widest):
+    # table 0 (22-bit keys): one row with 30 000 lookups and one with 9 000 (runs that leave their span by
+    #   dozens of spans; their ends are found from the noted run starts), the rest spread out;
+    # table 1 (200 rows, one pass would do): one row with 10 000 lookups, and out-of-range rows (their marker
+    #   sorts last inside the table);
+    # table 2 (27-bit keys, four passes): rows spread over the whole table, a hot row, and the last row;
+    # table 3: no lookups; table 4: a single lookup.
+    rng = np.random.default_rng(777)
+    D, B = 4, 64
+    Rs = [3_000_000, 200, 70_000_000, 50, 1000]
+    T = len(Rs)
+    parts = []
+    r0 = rng.integers(0, Rs[0], size=40_000)
+    r0[rng.choice(40_000, size=9_000, replace=False)] = 1_234_567
+    parts.append(np.concatenate([r0, np.full(30_000, 2_999_999)]))
+    r1 = rng.integers(0, Rs[1], size=3_000)
+    r1[:40] = [200, 201, -1, 1 << 33] * 10
+    parts.append(np.concatenate([np.full(10_000, 77), r1]))
+    r2 = rng.integers(0, Rs[2], size=50_000)
+    r2[rng.choice(50_000, size=12_000, replace=False)] = 33_554_431
+    r2[:5] = Rs[2] - 1
+    parts.append(r2)
+    parts.append(np.zeros(0, np.int64))
+    parts.append(np.array([999]))
+    lens = []
+    for p in parts:
+        rng.shuffle(p)
+        cuts = np.sort(rng.integers(0, p.size + 1, size=B - 1))
+        lens.append(np.diff(np.concatenate([[0], cuts, [p.size]])))
+    lengths = np.concatenate(lens).astype(np.int64)
+    off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    rows = np.concatenate(parts).astype(np.int64)
+    tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    _check_backward_against_oracle(tables, Rs, rows, off, B, D, "sum", dout, "buckets", emb.STATUS_BAD_INDEX)
+
+
+def test_backward_sort_one_table_of_many_tiles():
+    # 1.2 M lookups of one table: a sort segment of 293 tiles (the scan over a table's tiles runs over more
+    # than one workgroup's worth of them), with a row repeated 20 000 times among them.
+    rng = np.random.default_rng(778)
+    D, B, R = 4, 3000, 1_000_003
+    lengths = np.full(B, 400, dtype=np.int64)
+    off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    rows = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    rows[rng.choice(rows.size, size=20_000, replace=False)] = 500_000
+    tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32)]
+    dout = rng.standard_normal((1, B, D)).astype(np.float32)
+    _check_backward_against_oracle(tables, [R], rows, off, B, D, "mean", dout, "one table")
+
+
 def test_backward_split_calls_on_two_streams_equal_the_single_call():
     # emb_bag_backward_sort on a second stream (while other work runs on the first), then
     # emb_bag_backward_update: bit-identical tables, accumulators and row lists.
