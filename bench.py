@@ -70,6 +70,17 @@ def measured_traffic(workload: str, kernel: str):
     return int(round((kib[0] * PMC_TRAFFIC["fetch_scale"] + kib[1] * PMC_TRAFFIC["write_scale"]) * 1024))
 
 
+def traffic_source(traffic):
+    """Where a `traffic` figure comes from (it is never measured by the run that prints it)."""
+    if traffic is None:
+        return ("none: no counter run exists for this kernel and workload with the kernel sources as they are "
+                "(digest %s)" % kernel_sources_digest())
+    return ("carried from earlier rocprofv3 --pmc runs of this command (FETCH_SIZE x %.1f + WRITE_SIZE x %.1f, KiB per "
+            "dispatch; profiles/hbm_traffic_pmc.md), taken with kernel sources of digest %s, which are the ones built "
+            "now; not re-measured in this run" % (PMC_TRAFFIC["fetch_scale"], PMC_TRAFFIC["write_scale"],
+                                                   PMC_TRAFFIC["sources"]))
+
+
 def forward_bytes(nnz: int, bags: int, D: int, row_bytes: int) -> int:
     """Algorithmic bytes of one gather-pool launch: per lookup one table row and
     one 8-byte index; per bag one fp32 output row and one 8-byte offset."""
@@ -83,50 +94,74 @@ def backward_bytes(nnz: int, bags: int, uniq: int, D: int, esz: int, passes: int
     return nnz * (8 + 16 * passes) + bags * 4 * D + uniq * (2 * D * esz + 8)
 
 
-def cpu_baseline(w, batches_np, seed, min_seconds=10.0, max_batches=8):
-    """The oracle, untuned, single thread, on whole batches of the same workload until about
-    ``min_seconds`` of oracle time have been spent.  Host tables are full-size virtual arrays in
-    which only the rows a batch touches are materialised (building them is not timed); the
-    oracle's gathers then hit the same scattered addresses a fully materialised table would."""
+def _oracle_batch_inputs(w, b, seed):
+    """Index stage of one batch by the oracle (timed by the caller) is separate; this builds what
+    the pooled lookup and the backward read: hashed rows, offsets and the host tables (untimed)."""
     import numpy as np
 
     from oracle import emb_oracle as oracle
     from paper_2508_05700_amd import workloads as wl
 
+    t0 = time.perf_counter()
+    off, _ = oracle.lengths_to_offsets(b["lengths"])
+    if b["raw"] is not None:
+        rows_np = np.concatenate([oracle.hash_ids(b["raw"][off[t * w.B]:off[(t + 1) * w.B]], w.salt(t), w.R)
+                                  for t in range(w.T)])
+    else:
+        rows_np = b["rows"]
+    t_index = time.perf_counter() - t0
+    if w.quant:
+        # compact quantised tables holding the touched rows only (the oracle's own quantiser, not
+        # timed), lookups renumbered to match: denser than a full table, which flatters the CPU
+        tables, parts = [], []
+        for t in range(w.T):
+            seg = rows_np[off[t * w.B]:off[(t + 1) * w.B]]
+            touched = np.unique(seg)
+            tables.append(oracle.quantize_rows(wl.table_values(w.table_seed(t, seed), touched, w.D), w.quant))
+            parts.append(np.searchsorted(touched, seg))
+        rows_np = np.concatenate(parts).astype(np.int64)
+    else:
+        tables = [wl.sparse_host_table(w.table_seed(t, seed), w.R, w.D, w.dtype,
+                                       rows_np[off[t * w.B]:off[(t + 1) * w.B]]) for t in range(w.T)]
+    return off, rows_np, tables, t_index
+
+
+def _oracle_one_table(w, t, off, rows_np, tables, acc, dout):
+    """The oracle's forward (and backward) over table t alone: the tables of a batch are independent."""
+    from oracle import emb_oracle as oracle
+
+    s, e = int(off[t * w.B]), int(off[(t + 1) * w.B])
+    off_t = off[t * w.B:(t + 1) * w.B + 1] - s
+    store = w.quant if w.quant else w.dtype
+    kw = {"D": w.D} if w.quant else {}
+    oracle.bag_forward([tables[t]], store, rows_np[s:e], off_t, w.B, w.pool, want_absum=False, **kw)
+    if w.backward:
+        oracle.bag_backward_rowwise_adagrad([tables[t]], [acc[t]], w.dtype, rows_np[s:e], off_t, w.B, w.pool,
+                                            dout[t:t + 1], w.lr, w.eps, want_G=False)
+
+
+def cpu_baseline(w, batches_np, seed, min_seconds=10.0, max_batches=8):
+    """The oracle, untuned, on whole batches of the same workload until about ``min_seconds`` of
+    oracle time have been spent: first on one thread (the figure reported as ``value``), then the
+    same oracle functions on all host cores, one table per call and one call per thread (the tables
+    of a batch are independent; nothing in the oracle changes).  Host tables are full-size virtual
+    arrays in which only the rows a batch touches are materialised (building them is not timed); the
+    oracle's gathers then hit the same scattered addresses a fully materialised table would."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+
+    from oracle import emb_oracle as oracle
+
     t_index = t_f = t_b = 0.0
     lookups = 0
     used = 0
     for b in batches_np[:max_batches]:
+        off, rows_np, tables, ti = _oracle_batch_inputs(w, b, seed)
+        t_index += ti
+        store = w.quant if w.quant else w.dtype
+        kw = {"D": w.D} if w.quant else {}
         t0 = time.perf_counter()
-        off, _ = oracle.lengths_to_offsets(b["lengths"])
-        if b["raw"] is not None:
-            rows_np = np.concatenate([oracle.hash_ids(b["raw"][off[t * w.B]:off[(t + 1) * w.B]], w.salt(t), w.R)
-                                      for t in range(w.T)])
-        else:
-            rows_np = b["rows"]
-        t_index += time.perf_counter() - t0
-        if w.quant:
-            # compact quantised tables holding the touched rows only (the oracle's own quantiser, not
-            # timed), lookups renumbered to match: denser than a full table, which flatters the CPU
-            tables, parts = [], []
-            for t in range(w.T):
-                seg = rows_np[off[t * w.B]:off[(t + 1) * w.B]]
-                touched = np.unique(seg)
-                tables.append(oracle.quantize_rows(wl.table_values(w.table_seed(t, seed), touched, w.D), w.quant))
-                parts.append(np.searchsorted(touched, seg))
-            rows_q = np.concatenate(parts).astype(np.int64)
-            t0 = time.perf_counter()
-            oracle.bag_forward(tables, w.quant, rows_q, off, w.B, w.pool, want_absum=False, D=w.D)
-            t_f += time.perf_counter() - t0
-            lookups += int(b["nnz"])
-            used += 1
-            if t_index + t_f + t_b >= min_seconds:
-                break
-            continue
-        tables = [wl.sparse_host_table(w.table_seed(t, seed), w.R, w.D, w.dtype,
-                                       rows_np[off[t * w.B]:off[(t + 1) * w.B]]) for t in range(w.T)]
-        t0 = time.perf_counter()
-        oracle.bag_forward(tables, w.dtype, rows_np, off, w.B, w.pool, want_absum=False)
+        oracle.bag_forward(tables, store, rows_np, off, w.B, w.pool, want_absum=False, **kw)
         t_f += time.perf_counter() - t0
         if w.backward:
             acc = [np.zeros(w.R, dtype=np.float32) for _ in range(w.T)]
@@ -141,10 +176,33 @@ def cpu_baseline(w, batches_np, seed, min_seconds=10.0, max_batches=8):
             break
     t_all = t_index + t_f + t_b
     log("cpu oracle: %d batches, %.2f s -> %.3g lookups/s on 1 core" % (used, t_all, lookups / t_all))
-    return {"value": round(lookups / t_all, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
-            "sample": "%d full batches of the same workload (%d lookups, all %d tables): offsets+hash %.2f s, "
-                      "forward %.2f s, backward %.2f s of oracle time; single thread; host tables hold only "
-                      "the touched rows" % (used, lookups, w.T, t_index, t_f, t_b)}
+    result = {"value": round(lookups / t_all, 1), "unit": "lookups/s", "cores": 1, "kind": "oracle",
+              "sample": "%d full batches of the same workload (%d lookups, all %d tables): offsets+hash %.2f s, "
+                        "forward %.2f s, backward %.2f s of oracle time; single thread; host tables hold only "
+                        "the touched rows" % (used, lookups, w.T, t_index, t_f, t_b)}
+
+    # ---- the same oracle on all host cores: one table per call, one call per thread
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    threads = max(1, min(cores, w.T, 16))     # a one-GPU machine's share of the host is 16 cores
+    if threads > 1:
+        t_par = 0.0
+        lookups_par = 0
+        with ThreadPoolExecutor(max_workers=threads) as pool:
+            for b in batches_np[:used]:
+                off, rows_np, tables, ti = _oracle_batch_inputs(w, b, seed)
+                acc = [np.zeros(w.R, dtype=np.float32) for _ in range(w.T)] if w.backward else None
+                t0 = time.perf_counter()
+                list(pool.map(lambda t: _oracle_one_table(w, t, off, rows_np, tables, acc, b.get("dout")), range(w.T)))
+                t_par += ti + time.perf_counter() - t0      # the index stage stays on one thread
+                lookups_par += int(b["nnz"])
+                del tables
+        log("cpu oracle: the same %d batches with %d threads (one table per call; %d cores visible) -> %.3g lookups/s" % (
+            used, threads, cores, lookups_par / t_par))
+        result["all_cores"] = {"value": round(lookups_par / t_par, 1), "unit": "lookups/s", "cores": threads,
+                               "cores_visible": cores, "kind": "oracle",
+                               "how": "the same oracle functions called once per table from %d threads (the tables of a "
+                                      "batch are independent); offsets and hashing stay on one thread" % threads}
+    return result
 
 
 def stream_read_rate(data, nbytes=None, reps=5):
@@ -846,12 +904,22 @@ def main() -> int:
     passes = (max(1, int(w.R).bit_length()) + 7) // 8     # the sort works table by table on row numbers
     rowb = emb.emb_row_bytes(w.D, w.storage)
 
-    def entry(name, ms, nbytes, what, pmc_kernel=None):
+    def entry(name, ms, nbytes, what, pmc_kernel=None, cache_fed=False):
         gbs = nbytes / (ms * 1e-3) / 1e9 if ms > 0 else 0.0
         traffic = measured_traffic(args.workload, pmc_kernel) if pmc_kernel and not args.scale_rows else None
-        return {"kernel": name, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "avg_ms": round(ms, 4),
-                "algorithmic_bytes": int(nbytes), "bytes_are": what}
+        e = {"kernel": name, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+             "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source(traffic),
+             "avg_ms": round(ms, 4), "algorithmic_bytes": int(nbytes), "bytes_are": what}
+        if traffic is not None and ms > 0:
+            e["measured_traffic_GBps"] = round(traffic / (ms * 1e-3) / 1e9, 1)
+            e["frac_measured_traffic"] = round(traffic / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        if cache_fed:
+            # popular rows repeat within a batch and are served from L2 / the memory-side cache: the
+            # algorithmic bytes are not HBM bytes and `frac` is not a fraction of an HBM roofline
+            e["cache_fed"] = True
+            e["frac_is"] = ("algorithmic GB/s over the HBM peak; rows that repeat come from cache, so this can "
+                            "exceed 1; frac_measured_traffic (when present) is the HBM-side figure")
+        return e
 
     if fused:
         fwd_name, fwd_pmc = "bag_forward_hashed_kernel (hash + gather-pool)", "bag_forward_hashed_kernel"
@@ -874,7 +942,7 @@ def main() -> int:
         index_entry,
         entry(fwd_name, ms_fwd if w.backward else ms_dom, forward_bytes(nnz_i, bags, w.D, rowb) + fwd_extra,
               "row + 8 B index per lookup (+ 8 B record out when a backward follows), fp32 output row + 8 B "
-              "offset per bag", fwd_pmc),
+              "offset per bag", fwd_pmc, cache_fed=(w.ids == "zipf")),
     ]
     ms_bwd = 0.0
     if w.backward:
@@ -959,13 +1027,26 @@ def main() -> int:
             nb = forward_bytes(tot // n_it, wf.T * wf.B, wf.D, emb.emb_row_bytes(wf.D, wf.storage))
             gbs = nb / (ms * 1e-3) / 1e9
             kern = "bag_forward_quant_kernel" if wf.quant else "bag_forward_kernel"
-            extra["forward_only_" + name] = {
-                "kernel": kern, "row_bytes": emb.emb_row_bytes(wf.D, wf.storage),
-                "avg_ms": round(ms, 4), "lookups_per_s": round(tot / n_it / (ms * 1e-3), 1),
-                "algorithmic_GBps": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-                "algorithmic_bytes": int(nb), "traffic": measured_traffic(name, kern)}
-            log("forward only, workload %s: %.3f ms, %.3g lookups/s, %.0f GB/s (%.1f %% of HBM peak)" % (
-                name, ms, tot / n_it / (ms * 1e-3), gbs, 100 * gbs / HBM_PEAK_GBS))
+            tr = measured_traffic(name, kern)
+            ex = {"kernel": kern, "row_bytes": emb.emb_row_bytes(wf.D, wf.storage),
+                  "avg_ms": round(ms, 4), "lookups_per_s": round(tot / n_it / (ms * 1e-3), 1),
+                  "algorithmic_GBps": round(gbs, 1), "algorithmic_bytes": int(nb), "traffic": tr,
+                  "traffic_source": traffic_source(tr)}
+            if tr is not None:
+                ex["measured_traffic_GBps"] = round(tr / (ms * 1e-3) / 1e9, 1)
+                ex["frac_of_hbm_peak_measured_traffic"] = round(tr / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            if wf.ids == "zipf":
+                # rows repeat and come from cache: algorithmic GB/s is not an HBM rate, no roofline fraction from it
+                ex["cache_fed"] = True
+                log("forward only, workload %s: %.3f ms, %.3g lookups/s, %.0f GB/s algorithmic (cache-fed: popular rows "
+                    "repeat)%s" % (name, ms, tot / n_it / (ms * 1e-3), gbs,
+                                   "" if tr is None else "; %.0f GB/s of measured HBM traffic = %.1f %% of peak" % (
+                                       ex["measured_traffic_GBps"], 100 * ex["frac_of_hbm_peak_measured_traffic"])))
+            else:
+                ex["frac_of_hbm_peak"] = round(gbs / HBM_PEAK_GBS, 4)
+                log("forward only, workload %s: %.3f ms, %.3g lookups/s, %.0f GB/s (%.1f %% of HBM peak)" % (
+                    name, ms, tot / n_it / (ms * 1e-3), gbs, 100 * gbs / HBM_PEAK_GBS))
+            extra["forward_only_" + name] = ex
             del fb, fbuf, rows_v
         del qkeep, qset
 
