@@ -225,6 +225,26 @@ def stream_read_rate(data, nbytes=None, reps=5):
     return reps * n / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
 
 
+def stream_copy_rate(nbytes=1 << 30, reps=5):
+    """GB/s (bytes read + bytes written) of a plain device-to-device copy of ``nbytes``: what this
+    part delivers to a kernel whose traffic is half reads, half writes."""
+    import torch
+
+    from paper_2508_05700_amd import binding as emb
+
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda:0").fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev = [emb.Event(timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(reps):
+        dst.copy_(src)
+    ev[1].record()
+    torch.cuda.synchronize()
+    return reps * 2 * nbytes / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+
+
 def bench_hybrid(args) -> int:
     """Workload 5: pooled lookup over a table in pinned host memory fronted by an HBM cache of the
     hottest 5 % of rows.  A step is offsets + hashing + the cached forward; misses cross PCIe."""
@@ -695,7 +715,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="3",
-                    help="3 (fwd+bwd, default), 1, 2, 2u or 4 (forward only), 2q4 / 2q8 / 2uq4 (forward over INT4 / "
+                    help="3 (fwd+bwd, default), 3b (the same over bf16 tables), 1, 2, 2u or 4 (forward only), 2q4 / 2q8 / 2uq4 (forward over INT4 / "
                          "INT8 row-quantised tables), 5 / 5q4 (host table + HBM cache), 5m / 5mq4 (four hosted tables, one "
                          "launch), mix (tables of different width)")
     ap.add_argument("--batches", type=int, default=8, help="distinct resident batches cycled through")
@@ -979,6 +999,13 @@ def main() -> int:
     stream_gbs = stream_read_rate(tabs.weights[0])
     roofline = dict(roofline, stream_read_GBps=round(stream_gbs, 1),
                     frac_of_stream_read=round(roofline["achieved"] / stream_gbs, 4))
+    if w.backward:
+        # the update kernel writes as much as it reads: a plain copy is the nearer yardstick
+        copy_gbs = stream_copy_rate()
+        roofline["stream_copy_GBps"] = round(copy_gbs, 1)
+        if roofline.get("measured_traffic_GBps"):
+            roofline["measured_traffic_frac_of_stream_copy"] = round(roofline["measured_traffic_GBps"] / copy_gbs, 4)
+        log("a plain device copy moves %.0f GB/s (read + written)" % copy_gbs)
     if abs(roofline["avg_ms"] - round(ms_dom, 4)) < 1e-9:
         # the kernel bracketed by events inside the timed region: its spread over the K steps
         roofline.update(median_ms=round(dom_ms[len(dom_ms) // 2], 4), min_ms=round(dom_ms[0], 4),

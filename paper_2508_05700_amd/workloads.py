@@ -251,6 +251,9 @@ WORKLOADS: Dict[str, Workload] = {
     # 3: config 2 plus the sparse row-wise Adagrad backward
     "3": Workload("3", T=16, R=10_000_000, D=64, dtype="f32", B=8192, length="poisson", mean_len=20,
                   max_len=100, ids="zipf", alpha=1.05, n_keys=10 ** 9, pool="mean", backward=True),
+    # 3b: workload 3 with the tables stored as bf16 (rows halve; accumulators, gradients and outputs stay fp32)
+    "3b": Workload("3b", T=16, R=10_000_000, D=64, dtype="bf16", B=8192, length="poisson", mean_len=20,
+                   max_len=100, ids="zipf", alpha=1.05, n_keys=10 ** 9, pool="mean", backward=True),
     # 4: one 1e9-row bf16 table, Zipf(1.2) over 1e12 keys, sum pooling
     "4": Workload("4", T=1, R=1_000_000_000, D=32, dtype="bf16", B=65536, length="poisson", mean_len=50,
                   max_len=None, ids="zipf", alpha=1.2, n_keys=10 ** 12, pool="sum"),

@@ -203,6 +203,47 @@ def test_workload_3_forward_and_backward(tables16):
         assert int((tabs.accum[t] != 0).sum().item()) == int((acc[t] != 0).sum())
 
 
+def test_workload_3b_bf16_tables_forward_and_backward():
+    # Workload 3 with bf16 rows at full size, by the route the benchmark times.  Pooled values see no bf16
+    # rounding (rows are widened exactly, sums are fp32): 1e-5.  Updated rows are written as bf16: 1e-2.
+    w = wl.WORKLOADS["3b"]
+    say("filling 16 tables x 1e7 x 64 bf16 (20 GB) on the device")
+    tabs = pipeline.DeviceTables(w)
+    torch.cuda.synchronize()
+    _check_fill_sample(w, tabs, np.random.default_rng(12))
+    batch, db, buf, rows_dev, off, rows, tables = _forward_parity(w, tabs)
+    pooled = buf.out.clone()
+    buf.out.fill_(float("nan"))
+    pipeline.run_train_step(w, tabs.set, db, buf)
+    torch.cuda.synchronize()
+    assert int(buf.status.item()) == 0
+    assert torch.equal(buf.out, pooled)
+    say("workload 3b: oracle backward")
+    acc = [np.zeros(w.R, dtype=np.float32) for _ in range(w.T)]
+    base = np.arange(w.T + 1, dtype=np.int64) * w.R
+    touched = [np.unique(rows[off[t * w.B]:off[(t + 1) * w.B]]) for t in range(w.T)]
+    old = [H.as_f32(tables[t][touched[t]]) for t in range(w.T)]
+    r = oracle.bag_backward_rowwise_adagrad(tables, acc, w.dtype, rows, off, w.B, w.pool, batch["dout"], w.lr, w.eps)
+    assert r["status"] == 0
+    U = int(buf.num_unique.item())
+    assert np.array_equal(buf.unique_keys[:U].cpu().numpy(), r["unique_keys"])
+    assert np.array_equal(buf.unique_counts[:U].cpu().numpy(), r["unique_counts"])
+    rng = np.random.default_rng(13)
+    for t in range(w.T):
+        idx = torch.from_numpy(touched[t]).to(H.DEV)
+        got = H.as_f32(H.host_table(tabs.weights[t][idx]))
+        H.assert_rows_close(got, H.as_f32(tables[t][touched[t]]), old[t], w.lr, H.EPS_BF16, what="workload 3b rows t=%d" % t)
+        sel = (r["unique_keys"] >= base[t]) & (r["unique_keys"] < base[t + 1])
+        H.assert_accum_close(tabs.accum[t][idx].cpu().numpy(), acc[t][touched[t]], r["Gabs"][sel],
+                             what="workload 3b accum t=%d" % t)
+        probe = np.setdiff1d(rng.integers(0, w.R, size=100_000), touched[t])
+        pidx = torch.from_numpy(probe).to(H.DEV)
+        assert np.array_equal(H.host_table(tabs.weights[t][pidx]), wl.table_rows(w.table_seed(t), probe, w.D, w.dtype))
+        assert int((tabs.accum[t] != 0).sum().item()) == int((acc[t] != 0).sum())
+    del tabs
+    torch.cuda.empty_cache()
+
+
 def test_workload_4_one_billion_row_bf16_table():
     w = wl.WORKLOADS["4"]
     free, total = torch.cuda.mem_get_info()
