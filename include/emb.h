@@ -387,6 +387,53 @@ int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_rows, int32
                                   float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
                                   void *stream);
 
+/* The rows a hosted table's lookups miss in the cache, fetched ahead of the
+ * lookups (Section 3.4: the fetch from CPU memory is started as early as
+ * possible and runs beside the rest of the request; Section 3.3 for the hosted
+ * table).  rows_dev (i64[nnz]) holds the lookups of one batch or of SEVERAL
+ * batches one after the other: one launch then has the misses of all of them
+ * in flight over the link together.  Every lookup is resolved (bounds check,
+ * cache probe against cache_index_dev / num_hot as emb_cache_build left them);
+ * every missed row is copied from table_dev into the staging buffer
+ * stage_rows_dev (room for stage_capacity rows of emb_row_bytes(D, dtype),
+ * 16-byte aligned, in HBM), one copy per missed lookup, and loc_dev (i64[nnz])
+ * receives where each lookup's row is to be found, in a form only
+ * emb_bag_forward_staged reads.  *stage_count_dev (u64, zeroed by the caller
+ * before the call) is incremented by the number of missed lookups; if that
+ * exceeds stage_capacity the lookups that found no room are not staged and
+ * emb_bag_forward_staged reads their rows from the table itself.  Out-of-range
+ * rows set EMB_STATUS_BAD_INDEX and are skipped by the lookup.  Which staging
+ * row a miss gets depends on timing; results do not.  dtype: any storage type
+ * of emb_bag_forward_cached.  EMB_ERR_UNSUPPORTED if num_rows or
+ * stage_capacity is 2^61 or more.  The _hashed form takes raw IDs and resolves
+ * them with `salt` and num_rows (Section 2.2). */
+int emb_cache_stage_misses(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                           const void *cache_index_dev, int64_t num_hot, const int64_t *rows_dev,
+                           int64_t nnz, void *stage_rows_dev, int64_t stage_capacity,
+                           int64_t *loc_dev, uint64_t *stage_count_dev, uint32_t *status_dev,
+                           void *stream);
+int emb_cache_stage_misses_hashed(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                                  const void *cache_index_dev, int64_t num_hot, uint64_t salt,
+                                  const uint64_t *raw_dev, int64_t nnz, void *stage_rows_dev,
+                                  int64_t stage_capacity, int64_t *loc_dev,
+                                  uint64_t *stage_count_dev, uint32_t *status_dev, void *stream);
+
+/* emb_bag_forward_cached for one batch whose lookups emb_cache_stage_misses has
+ * resolved: loc_dev (i64[nnz]) is that batch's stretch of the locations, offsets_dev
+ * (i64[B+1]) delimits its bags within that stretch.  Rows are read from the
+ * cache (cache_rows_dev), from the staging buffer, or, for lookups that found
+ * no room there, from table_dev; the cache, the staging buffer and the table
+ * must be as they were when the lookups were staged.  out_dev: f32[1, B, D], equal
+ * to emb_bag_forward_cached over the same lookups (same order of summation);
+ * hit_miss_dev (nullable, u64[2], zeroed by the caller): += lookups served
+ * from the cache / otherwise.  A location that names no row of the cache, the
+ * staging buffer or the table sets EMB_STATUS_BAD_INDEX and is skipped. */
+int emb_bag_forward_staged(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                           const void *cache_rows_dev, int64_t num_hot, const void *stage_rows_dev,
+                           int64_t stage_capacity, const int64_t *loc_dev, const int64_t *offsets_dev,
+                           int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                           uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream);
+
 /* One hosted table with its cache, for the multi-table cached lookup: the
  * arguments of emb_bag_forward_cached as a descriptor.  Like emb_table, the
  * array of T descriptors is passed in host memory (validation) and in device

@@ -48,6 +48,7 @@ EXPORTS = [
     "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_host_device_pointer",
+    "emb_cache_stage_misses", "emb_cache_stage_misses_hashed", "emb_bag_forward_staged",
     "emb_version_record_bytes", "emb_version_latch_bytes", "emb_version_record_write", "emb_version_publish",
     "emb_version_latch", "emb_bag_forward_latched", "emb_bag_forward_latched_hashed",
     "emb_cached_tables_init", "emb_bag_forward_cached_tables", "emb_bag_forward_cached_tables_hashed",
@@ -149,6 +150,12 @@ def lib() -> C.CDLL:
     L.emb_cache_select_workspace_bytes.argtypes = [i64, C.POINTER(sz)]
     L.emb_cache_select.restype = C.c_int
     L.emb_cache_select.argtypes = [vp, i64, i64, i32, vp, sz, vp, vp, vp]
+    L.emb_cache_stage_misses.restype = C.c_int
+    L.emb_cache_stage_misses.argtypes = [vp, i64, i32, i32, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp]
+    L.emb_cache_stage_misses_hashed.restype = C.c_int
+    L.emb_cache_stage_misses_hashed.argtypes = [vp, i64, i32, i32, vp, i64, u64, vp, i64, vp, i64, vp, vp, vp, vp]
+    L.emb_bag_forward_staged.restype = C.c_int
+    L.emb_bag_forward_staged.argtypes = [vp, i64, i32, i32, vp, i64, vp, i64, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     L.emb_cache_select_static.restype = C.c_int
     L.emb_cache_select_static.argtypes = [vp, i64, i64, i32, vp, vp, vp]
     L.emb_cache_rebuild.restype = C.c_int
@@ -578,6 +585,42 @@ def emb_bag_forward_cached_hashed(table_ptr: int, num_rows: int, D: int, dtype: 
         int(table_ptr), int(num_rows), int(D), DTYPE[dtype], _ptr(cache_rows, _TABLE_TORCH[dtype], "cache_rows"),
         _ptr(cache_index, torch.uint8, "cache_index"), int(num_hot), C.c_uint64(int(salt) % (1 << 64)),
         _ptr(raw, _U64, "raw"), _ptr(offsets, torch.int64, "offsets"), int(B), raw.numel(), POOL[mode],
+        _ptr(out, torch.float32, "out"), _ptr(hit_miss, _U64, "hit_miss"), _ptr(status, torch.int32, "status"),
+        _stream()))
+
+
+def emb_cache_stage_misses(table_ptr: int, num_rows: int, D: int, dtype: str, cache_index: torch.Tensor, num_hot: int,
+                           ids: torch.Tensor, stage_rows: Optional[torch.Tensor], stage_capacity: int, loc: torch.Tensor,
+                           stage_count: torch.Tensor, status: Optional[torch.Tensor] = None,
+                           salt: Optional[int] = None) -> None:
+    """Resolve the lookups ``ids`` (row numbers, or raw IDs when ``salt`` is given) of one or several batches and
+    copy the rows they miss in the cache into ``stage_rows``; ``loc`` receives one location per lookup."""
+    if loc.numel() < ids.numel() or stage_count.numel() < 1:
+        raise TypeError("shape mismatch")
+    if stage_rows is not None and stage_rows.numel() * stage_rows.element_size() < stage_capacity * emb_row_bytes(D, dtype):
+        raise TypeError("stage_rows smaller than stage_capacity rows")
+    common = (int(table_ptr), int(num_rows), int(D), DTYPE[dtype], _ptr(cache_index, torch.uint8, "cache_index"), int(num_hot))
+    tail = (ids.numel(), _ptr(stage_rows, _TABLE_TORCH[dtype], "stage_rows"), int(stage_capacity),
+            _ptr(loc, torch.int64, "loc"), _ptr(stage_count, _U64, "stage_count"), _ptr(status, torch.int32, "status"),
+            _stream())
+    if salt is None:
+        _check("emb_cache_stage_misses", lib().emb_cache_stage_misses(*common, _ptr(ids, torch.int64, "rows"), *tail))
+    else:
+        _check("emb_cache_stage_misses_hashed", lib().emb_cache_stage_misses_hashed(
+            *common, C.c_uint64(int(salt) % (1 << 64)), _ptr(ids, _U64, "raw"), *tail))
+
+
+def emb_bag_forward_staged(table_ptr: int, num_rows: int, D: int, dtype: str, cache_rows: Optional[torch.Tensor],
+                           num_hot: int, stage_rows: Optional[torch.Tensor], stage_capacity: int, loc: torch.Tensor,
+                           offsets: torch.Tensor, B: int, mode: str, out: torch.Tensor,
+                           hit_miss: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None) -> None:
+    """The pooled lookup of one batch over the locations ``loc`` that ``emb_cache_stage_misses`` left."""
+    if offsets.numel() != B + 1 or out.numel() != B * D:
+        raise TypeError("shape mismatch")
+    _check("emb_bag_forward_staged", lib().emb_bag_forward_staged(
+        int(table_ptr), int(num_rows), int(D), DTYPE[dtype], _ptr(cache_rows, _TABLE_TORCH[dtype], "cache_rows"),
+        int(num_hot), _ptr(stage_rows, _TABLE_TORCH[dtype], "stage_rows"), int(stage_capacity),
+        _ptr(loc, torch.int64, "loc"), _ptr(offsets, torch.int64, "offsets"), int(B), loc.numel(), POOL[mode],
         _ptr(out, torch.float32, "out"), _ptr(hit_miss, _U64, "hit_miss"), _ptr(status, torch.int32, "status"),
         _stream()))
 

@@ -14,19 +14,13 @@
 // hosted tables are the ones the paper quantises): cache and table then hold
 // the same packed rows, a miss moves 48 instead of 256 bytes over the link
 // (D = 64, INT4), and rows are dequantised while they are gathered.
+#include "cache_index.h"
 #include "emb_internal.h"
 #include "gather.h"
 #include "gather_quant.h"
 #include "u64mod.h"
 
 namespace {
-
-struct CacheEntry {
-    uint64_t bits;    // bit i set: row 64*e + i is cached
-    uint32_t before;  // number of cached rows with a smaller row number
-    uint32_t pad;
-};
-static_assert(sizeof(CacheEntry) == 16, "cache index entry must be 16 bytes");
 
 constexpr int CB_BLOCK = 256;
 
@@ -127,15 +121,10 @@ struct CachedSource {
             emb_flag(status, EMB_STATUS_BAD_INDEX);
             return 0ull;
         }
-        const uint4 raw = *reinterpret_cast<const uint4 *>(index + (r >> 6));
-        const uint64_t bits = ((uint64_t)raw.y << 32) | raw.x;
-        const int bit = (int)(r & 63);
-        if ((bits >> bit) & 1ull) {
-            const uint64_t slot = (uint64_t)raw.z + (uint64_t)__popcll(bits & ((1ull << bit) - 1ull));
-            if (slot < num_hot) {  // always true for an index built from a valid hot set
-                ++hits;
-                return reinterpret_cast<uint64_t>(cache_rows + (int64_t)slot * row_bytes);
-            }
+        const int64_t slot = cache_probe(index, (uint64_t)r, num_hot);
+        if (slot >= 0) {
+            ++hits;
+            return reinterpret_cast<uint64_t>(cache_rows + slot * row_bytes);
         }
         ++misses;
         return reinterpret_cast<uint64_t>(table + r * row_bytes);
@@ -164,19 +153,7 @@ __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_kernel(const char
     constexpr int F = ChunkAcc<BF16>::FLOATS;
     gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, b, l, nnz, rows, offsets, chunks_per_row, mode,
                                             out + b * ((int64_t)chunks_per_row * F), status);
-    if (hit_miss) {
-        // every lane of the wavefront is still here: reduce, then one atomic per wavefront
-        uint32_t h = src.hits, m = src.misses;
-#pragma unroll
-        for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) {
-            h += __shfl_xor(h, d, EMB_WAVE);
-            m += __shfl_xor(m, d, EMB_WAVE);
-        }
-        if ((threadIdx.x & (EMB_WAVE - 1)) == 0) {
-            if (h) atomicAdd(&hit_miss[0], (unsigned long long)h);
-            if (m) atomicAdd(&hit_miss[1], (unsigned long long)m);
-        }
-    }
+    cache_add_hit_miss(src.hits, src.misses, hit_miss);
 }
 
 template <int LPR, int CPL, int UNROLL>
@@ -217,19 +194,7 @@ __global__ __launch_bounds__(Q_BLOCK) void bag_forward_cached_quant_kernel(const
     CachedSource src{table, cache_rows, index, (uint64_t)num_rows, (uint64_t)num_hot, row_bytes, status, 0u, 0u,
                      hashed, salt, magic};
     gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, b, l, nnz, rows, offsets, D, mode, out, status);
-    if (hit_miss) {
-        // every lane of the wavefront is still here: reduce, then one atomic per wavefront
-        uint32_t h = src.hits, m = src.misses;
-#pragma unroll
-        for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) {
-            h += __shfl_xor(h, d, EMB_WAVE);
-            m += __shfl_xor(m, d, EMB_WAVE);
-        }
-        if ((threadIdx.x & (EMB_WAVE - 1)) == 0) {
-            if (h) atomicAdd(&hit_miss[0], (unsigned long long)h);
-            if (m) atomicAdd(&hit_miss[1], (unsigned long long)m);
-        }
-    }
+    cache_add_hit_miss(src.hits, src.misses, hit_miss);
 }
 
 template <int BITS>
@@ -280,22 +245,6 @@ __device__ __forceinline__ CachedSource cached_source_of(const emb_cached_table 
                         tb.mod_magic};
 }
 
-__device__ __forceinline__ void add_hit_miss(const CachedSource &src, unsigned long long *hit_miss)
-{
-    if (!hit_miss) return;
-    // every lane of the wavefront is still here: reduce, then one atomic per wavefront
-    uint32_t h = src.hits, m = src.misses;
-#pragma unroll
-    for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) {
-        h += __shfl_xor(h, d, EMB_WAVE);
-        m += __shfl_xor(m, d, EMB_WAVE);
-    }
-    if ((threadIdx.x & (EMB_WAVE - 1)) == 0) {
-        if (h) atomicAdd(&hit_miss[0], (unsigned long long)h);
-        if (m) atomicAdd(&hit_miss[1], (unsigned long long)m);
-    }
-}
-
 template <int LPR, int CPL, int UNROLL, bool BF16>
 __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_tables_kernel(
     const emb_cached_table *__restrict__ tables, int64_t B, uint32_t blocks_per_table, int64_t nnz,
@@ -312,7 +261,7 @@ __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_tables_kernel(
     const int64_t bag = (int64_t)t * B + b;
     gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, bag, l, nnz, ids, offsets, chunks_per_row, mode,
                                             out + bag * ((int64_t)chunks_per_row * F), status);
-    add_hit_miss(src, hit_miss);
+    cache_add_hit_miss(src.hits, src.misses, hit_miss);
 }
 
 template <int LPR, int BITS, int UNROLL>
@@ -328,7 +277,7 @@ __global__ __launch_bounds__(Q_BLOCK) void bag_forward_cached_tables_quant_kerne
     const emb_cached_table tb = tables[t];
     CachedSource src = cached_source_of(tb, row_bytes, status, hashed);
     gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, (int64_t)t * B + b, l, nnz, ids, offsets, D, mode, out, status);
-    add_hit_miss(src, hit_miss);
+    cache_add_hit_miss(src.hits, src.misses, hit_miss);
 }
 
 struct CachedTablesArgs {

@@ -267,6 +267,28 @@ def test_cache_argument_errors(L):
     assert L.emb_table_fill(FAKE, 10, 6, 0, 1, None) == UNSUPPORTED
 
 
+def test_staging_argument_errors(L):
+    # emb_cache_stage_misses(table, R, D, dtype, index, num_hot, ids, nnz, stage_rows, capacity, loc, count, status, stream)
+    assert L.emb_cache_stage_misses(FAKE, 100, 64, 0, FAKE, 10, None, 0, None, 0, None, None, None, None) == OK   # no lookups
+    assert L.emb_cache_stage_misses(FAKE, 0, 64, 0, FAKE, 0, FAKE, 5, FAKE, 8, FAKE, FAKE, None, None) == INVALID
+    assert L.emb_cache_stage_misses(FAKE, 100, 64, 0, FAKE, 101, FAKE, 5, FAKE, 8, FAKE, FAKE, None, None) == INVALID
+    assert L.emb_cache_stage_misses(FAKE, 100, 6, 0, FAKE, 10, FAKE, 5, FAKE, 8, FAKE, FAKE, None, None) == UNSUPPORTED
+    assert L.emb_cache_stage_misses(FAKE, 100, 64, 0, FAKE, 10, FAKE, 5, None, 8, FAKE, FAKE, None, None) == INVALID
+    assert L.emb_cache_stage_misses(FAKE, 100, 64, 0, FAKE, 10, FAKE, 5, FAKE, 8, None, FAKE, None, None) == INVALID
+    assert L.emb_cache_stage_misses(FAKE, 100, 64, 0, FAKE, 10, FAKE, 5, FAKE, 8, FAKE, None, None, None) == INVALID
+    assert L.emb_cache_stage_misses(FAKE, 100, 64, 0, FAKE, 10, FAKE, 5, FAKE, -1, FAKE, FAKE, None, None) == INVALID
+    assert L.emb_cache_stage_misses(FAKE, 1 << 61, 64, 0, FAKE, 10, FAKE, 5, FAKE, 8, FAKE, FAKE, None, None) == UNSUPPORTED
+    assert L.emb_cache_stage_misses_hashed(FAKE, 100, 64, 0, None, 10, 7, FAKE, 5, FAKE, 8, FAKE, FAKE, None, None) == INVALID
+    # emb_bag_forward_staged(table, R, D, dtype, cache_rows, num_hot, stage_rows, capacity, loc, offsets, B, nnz, mode, out, ...)
+    assert L.emb_bag_forward_staged(FAKE, 100, 64, 0, FAKE, 10, FAKE, 8, FAKE, FAKE, 0, 0, 0, FAKE, None, None, None) == OK
+    assert L.emb_bag_forward_staged(FAKE, 100, 64, 0, FAKE, 10, FAKE, 8, FAKE, FAKE, 4, 8, 2, FAKE, None, None, None) == INVALID
+    assert L.emb_bag_forward_staged(FAKE, 100, 64, 0, None, 10, FAKE, 8, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID
+    assert L.emb_bag_forward_staged(FAKE, 100, 64, 0, FAKE, 10, None, 8, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID
+    assert L.emb_bag_forward_staged(FAKE, 100, 64, 0, FAKE, 10, FAKE, 8, None, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID
+    assert L.emb_bag_forward_staged(FAKE, 100, 64, 0, FAKE, 10, FAKE, 8, FAKE, FAKE, 4, 8, 0, FAKE + 4, None, None, None) == INVALID
+    assert L.emb_bag_forward_staged(FAKE, 100, 24, 2, FAKE, 10, FAKE, 8, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == UNSUPPORTED
+
+
 def test_cache_policy_argument_errors(L):
     n = C.c_size_t(0)
     assert L.emb_cache_select_workspace_bytes(250_000_000, C.byref(n)) == OK

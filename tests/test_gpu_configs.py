@@ -340,6 +340,36 @@ def _hybrid_parity(w, say_name):
     assert hm.cpu().tolist() == [hits, misses]                         # bit-exact hit/miss counts
     H.assert_pooled_close(out.cpu().numpy(), ref, absum, what=say_name)
     say("%s: %d hits, %d misses (%.1f %% hit rate)" % (say_name, hits, misses, 100.0 * hits / max(1, hits + misses)))
+
+    # the route with the misses fetched ahead: three batches staged by one launch (raw IDs), then one pooled lookup
+    # per batch over HBM only; every batch against the oracle's cached lookup of that batch
+    batches = [batch] + [wl.make_batch(w, i) for i in (1, 2)]
+    raws = torch.cat([torch.from_numpy(b["raw"].view(np.int64)) for b in batches]).to(H.DEV)
+    n_all = raws.numel()
+    cap = n_all // 8
+    stage = torch.empty((cap, w.D), dtype=torch.float32, device=H.DEV)
+    loc = torch.empty(n_all, dtype=torch.int64, device=H.DEV)
+    count = torch.zeros(1, dtype=torch.int64, device=H.DEV)
+    emb.emb_cache_stage_misses(ptr, w.R, w.D, "f32", index, K, raws, stage, cap, loc, count, status, salt=w.salt(0))
+    at = 0
+    total_misses = 0
+    for i, b in enumerate(batches):
+        off_b, rows_b = _oracle_index(w, b)
+        n = rows_b.size
+        hm.zero_()
+        emb.emb_bag_forward_staged(ptr, w.R, w.D, "f32", cache, K, stage, cap, loc[at:at + n], H.dev(off_b), w.B, w.pool,
+                                   out, hm, status)
+        torch.cuda.synchronize()
+        assert status.item() == 0
+        tb = wl.sparse_host_table(w.table_seed(0), w.R, w.D, "f32", rows_b)
+        ref_b, absum_b, (h_b, m_b), st = oracle.bag_forward_cached(tb, "f32", hot, rows_b, off_b, w.B, w.pool)
+        assert st == 0 and hm.cpu().tolist() == [h_b, m_b]
+        H.assert_pooled_close(out.cpu().numpy(), ref_b, absum_b, what="%s staged batch %d" % (say_name, i))
+        total_misses += m_b
+        at += n
+        del tb
+    assert int(count.item()) == total_misses and total_misses <= cap
+    say("%s: %d misses of 3 batches staged by one launch, lookups over HBM match the oracle" % (say_name, total_misses))
     return hits / max(1, hits + misses)
 
 

@@ -927,6 +927,107 @@ def test_cached_forward_reads_misses_from_pinned_host_memory():
     _cached_case(table_np, "f32", hot, rows, off, B, "sum", table_ptr=ptr)
 
 
+def _staged_case(table_np, packed_np, dtype, D, ptr, hot, batches, capacity, mode, salt=None):
+    """Several batches staged in one call, then one pooled lookup per batch, against the oracle's cached lookup of
+    each batch.  batches: list of (ids, off, B); ids are row numbers, or raw IDs when salt is given."""
+    R = packed_np.shape[0]
+    rb = emb.emb_row_bytes(D, dtype)
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}.get(dtype, torch.uint8)
+    row_shape = (rb,) if tdt == torch.uint8 else (D,)
+    index = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+    cache = torch.empty((max(hot.size, 1),) + row_shape, dtype=tdt, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_cache_build(ptr, R, D, dtype, H.dev(hot), cache, index, status)
+    ids_all = np.concatenate([b[0] for b in batches])
+    stage = torch.full((max(capacity, 1),) + row_shape, 0, dtype=tdt, device=H.DEV)
+    loc = torch.full((max(ids_all.size, 1),), -5, dtype=torch.int64, device=H.DEV)
+    count = torch.zeros(1, dtype=torch.int64, device=H.DEV)
+    emb.emb_cache_stage_misses(ptr, R, D, dtype, index, hot.size, H.dev(ids_all), stage, capacity, loc, count, status,
+                               salt=salt)
+    torch.cuda.synchronize()
+    want_status = 0
+    total_misses = 0
+    at = 0
+    for ids, off, B in batches:
+        rows = ids if salt is None else oracle.hash_ids(ids, salt, R)
+        out = torch.full((1, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+        hm = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+        emb.emb_bag_forward_staged(ptr, R, D, dtype, cache, hot.size, stage, capacity, loc[at:at + ids.size], H.dev(off), B,
+                                   mode, out, hm, status)
+        torch.cuda.synchronize()
+        kw = {} if dtype in ("f32", "bf16") else {"D": D}
+        ref, absum, (hits, misses), rst = oracle.bag_forward_cached(packed_np, dtype, hot, rows, off, B, mode, **kw)
+        want_status |= rst
+        total_misses += misses
+        assert hm.cpu().tolist() == [hits, misses]                 # bit-exact hit / miss counts, batch by batch
+        H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="staged lookup")
+        at += ids.size
+    assert int(status.item()) == want_status
+    assert int(count.item()) == total_misses                       # every missed lookup asked for a staging row
+    # what the staging buffer holds: a byte copy of a table row for every staged lookup
+    loc_np = loc[:ids_all.size].cpu().numpy()
+    staged = (loc_np >= 0) & ((loc_np >> 62) & 1).astype(bool)
+    slots = loc_np[staged] & ((1 << 61) - 1)
+    assert slots.size == min(total_misses, capacity) and np.unique(slots).size == slots.size
+    rows_all = ids_all if salt is None else oracle.hash_ids(ids_all, salt, R)
+    got = H.host_table(stage)[slots] if slots.size else None
+    if slots.size:
+        assert np.array_equal(got, packed_np[rows_all[staged]])
+
+
+@pytest.mark.parametrize("D,dtype", [(64, "f32"), (32, "bf16"), (320, "f32"), (64, "int4"), (48, "int8")])
+def test_staged_misses_of_several_batches_match_the_cached_lookup(D, dtype):
+    # the table lives in pinned host memory; three batches (one empty, one with out-of-range rows) are staged at once
+    rng = np.random.default_rng(2100 + D)
+    R = 40_000
+    x = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+    if dtype == "f32":
+        packed = x
+    elif dtype == "bf16":
+        packed = wl.f32_to_bf16_bits(x).reshape(R, D)
+    else:
+        packed = oracle.quantize_rows(x, dtype)
+    host = torch.from_numpy(packed.view(np.int16) if dtype == "bf16" else packed).pin_memory()
+    ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+    hot = np.sort(rng.choice(R, size=R // 10, replace=False)).astype(np.int64)
+    batches = []
+    for B, max_len in ((700, 40), (3, 0), (1500, 25)):
+        lengths = rng.integers(0, max_len + 1, size=B).astype(np.int32)
+        off, _ = oracle.lengths_to_offsets(lengths)
+        n = int(off[-1])
+        rows = np.where(rng.random(n) < 0.7, rng.choice(hot, size=n), rng.integers(0, R, size=n)).astype(np.int64)
+        batches.append((rows, off, B))
+    batches[2][0][[5, 77]] = [R + 3, -1]
+    n_miss = sum(int((~np.isin(b[0], hot) & (b[0] >= 0) & (b[0] < R)).sum()) for b in batches)
+    assert n_miss > 3000
+    for capacity in (n_miss + 10, n_miss // 3, 0):                 # room for all; the buffer runs full; no buffer
+        _staged_case(x, packed, dtype, D, ptr, hot, batches, capacity, "mean" if capacity else "sum")
+    # raw IDs, hashed while they are staged
+    raw_batches = [(rng.integers(0, 1 << 63, size=b[0].size, dtype=np.int64).view(np.uint64), b[1], b[2]) for b in batches]
+    _staged_case(x, packed, dtype, D, ptr, hot, raw_batches, n_miss * 2, "sum", salt=4242)
+    # no cache at all: every lookup is a miss and is staged
+    _staged_case(x, packed, dtype, D, ptr, np.zeros(0, np.int64), batches[:1], batches[0][0].size, "sum")
+
+
+def test_staged_lookup_rejects_locations_it_cannot_hold():
+    # a location array that was not written by the staging pass for these buffers: flagged and skipped, never read
+    R, D, B = 100, 16, 4
+    t = torch.ones((R, D), dtype=torch.float32, device=H.DEV)
+    cache = torch.ones((10, D), dtype=torch.float32, device=H.DEV)
+    stage = torch.ones((5, D), dtype=torch.float32, device=H.DEV)
+    loc = np.array([3, 10, (1 << 62) | 4, (1 << 62) | 5, (1 << 61) | 99, (1 << 61) | 100, -1, 9], dtype=np.int64)
+    off = np.array([0, 2, 4, 6, 8], dtype=np.int64)
+    out = torch.empty((1, B, D), dtype=torch.float32, device=H.DEV)
+    hm = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_staged(int(t.data_ptr()), R, D, "f32", cache, 10, stage, 5, H.dev(loc), H.dev(off), B, "sum", out,
+                               hm, status)
+    torch.cuda.synchronize()
+    assert status.item() == emb.STATUS_BAD_INDEX
+    assert out.cpu().numpy()[0, :, 0].tolist() == [1.0, 1.0, 1.0, 1.0]      # one valid location per bag
+    assert hm.cpu().tolist() == [2, 2]
+
+
 # ---------------------------------------------------------------------------
 # procedural table fill
 # ---------------------------------------------------------------------------
