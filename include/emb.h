@@ -598,6 +598,34 @@ int emb_bag_forward_latched_hashed(const void *latch_dev, int32_t T, int32_t D, 
                                    int64_t nnz, int32_t mode, float *out_dev,
                                    uint32_t *status_dev, void *stream);
 
+/* The same for hosted tables (Section 3.3: the versioned tables are the ones
+ * in CPU memory): records and latches of emb_cached_table descriptors.  A new
+ * model version, and likewise a refreshed cache of the same tables (new cache
+ * buffers, hence new descriptors), is made current by emb_version_publish of a
+ * hosted record: one switch, after which every lookup that latches reads table,
+ * cache rows and cache index of that record only.  Sizes, alignment, ownership
+ * and the behaviour with nothing published are as above; a latch of one kind
+ * refuses a record of the other (EMB_STATUS_NO_VERSION, version 0, zeros).
+ * emb_version_hosted_record_write validates the descriptors as
+ * emb_bag_forward_cached_tables does.  The lookups are
+ * emb_bag_forward_cached_tables / _hashed over the latched descriptors; the
+ * version the result belongs to is the u64 at latch_dev. */
+int emb_version_hosted_record_bytes(int32_t T, size_t *bytes);
+int emb_version_hosted_latch_bytes(int32_t T, size_t *bytes);
+int emb_version_hosted_record_write(void *record_dev, const emb_cached_table *tables_host,
+                                    const emb_cached_table *tables_dev, int32_t T, uint64_t version,
+                                    void *stream);
+int emb_version_hosted_latch(const uint64_t *handle_dev, int32_t T, void *latch_dev,
+                             uint32_t *status_dev, void *stream);
+int emb_bag_forward_cached_latched(const void *latch_dev, int32_t T, int32_t D, int32_t dtype,
+                                   const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B,
+                                   int64_t nnz, int32_t mode, float *out_dev, uint64_t *hit_miss_dev,
+                                   uint32_t *status_dev, void *stream);
+int emb_bag_forward_cached_latched_hashed(const void *latch_dev, int32_t T, int32_t D, int32_t dtype,
+                                          const uint64_t *raw_dev, const int64_t *offsets_dev,
+                                          int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                                          uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream);
+
 /* Device-visible address of page-locked host memory that is mapped into the
  * device address space (hipHostMalloc / a pinned torch tensor): the pointer to
  * pass as table_dev above.  EMB_ERR_HIP if the memory is not mapped; nothing is

@@ -51,6 +51,8 @@ EXPORTS = [
     "emb_cache_stage_misses", "emb_cache_stage_misses_hashed", "emb_bag_forward_staged",
     "emb_version_record_bytes", "emb_version_latch_bytes", "emb_version_record_write", "emb_version_publish",
     "emb_version_latch", "emb_bag_forward_latched", "emb_bag_forward_latched_hashed",
+    "emb_version_hosted_record_bytes", "emb_version_hosted_latch_bytes", "emb_version_hosted_record_write",
+    "emb_version_hosted_latch", "emb_bag_forward_cached_latched", "emb_bag_forward_cached_latched_hashed",
     "emb_cached_tables_init", "emb_bag_forward_cached_tables", "emb_bag_forward_cached_tables_hashed",
     "emb_cache_observe", "emb_cache_observe_hashed", "emb_cache_select_workspace_bytes", "emb_cache_select", "emb_cache_select_static",
     "emb_cache_rebuild",
@@ -150,6 +152,16 @@ def lib() -> C.CDLL:
     L.emb_cache_select_workspace_bytes.argtypes = [i64, C.POINTER(sz)]
     L.emb_cache_select.restype = C.c_int
     L.emb_cache_select.argtypes = [vp, i64, i64, i32, vp, sz, vp, vp, vp]
+    for fn in ("emb_version_hosted_record_bytes", "emb_version_hosted_latch_bytes"):
+        getattr(L, fn).restype = C.c_int
+        getattr(L, fn).argtypes = [i32, C.POINTER(sz)]
+    L.emb_version_hosted_record_write.restype = C.c_int
+    L.emb_version_hosted_record_write.argtypes = [vp, vp, vp, i32, u64, vp]
+    L.emb_version_hosted_latch.restype = C.c_int
+    L.emb_version_hosted_latch.argtypes = [vp, i32, vp, vp, vp]
+    for fn in ("emb_bag_forward_cached_latched", "emb_bag_forward_cached_latched_hashed"):
+        getattr(L, fn).restype = C.c_int
+        getattr(L, fn).argtypes = [vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     L.emb_cache_stage_misses.restype = C.c_int
     L.emb_cache_stage_misses.argtypes = [vp, i64, i32, i32, vp, i64, vp, i64, vp, i64, vp, vp, vp, vp]
     L.emb_cache_stage_misses_hashed.restype = C.c_int
@@ -814,3 +826,59 @@ def emb_table_fill(weights, num_rows: int, D: int, dtype: str, seed: int) -> Non
     ptr = weights if isinstance(weights, int) else _ptr(weights, _TABLE_TORCH[dtype], "weights")
     _check("emb_table_fill", lib().emb_table_fill(ptr, int(num_rows), int(D), DTYPE[dtype],
                                                   C.c_uint64(int(seed) % (1 << 64)), _stream()))
+
+
+# ---- version records of hosted tables ----------------------------------------------------------------
+def emb_version_hosted_record_bytes(T: int) -> int:
+    out = C.c_size_t(0)
+    _check("emb_version_hosted_record_bytes", lib().emb_version_hosted_record_bytes(int(T), C.byref(out)))
+    return int(out.value)
+
+
+def emb_version_hosted_latch_bytes(T: int) -> int:
+    out = C.c_size_t(0)
+    _check("emb_version_hosted_latch_bytes", lib().emb_version_hosted_latch_bytes(int(T), C.byref(out)))
+    return int(out.value)
+
+
+def emb_version_hosted_record_write(record: torch.Tensor, ct: CachedTables, version: int) -> None:
+    if record.numel() < emb_version_hosted_record_bytes(ct.T):
+        raise TypeError("record too small")
+    _check("emb_version_hosted_record_write", lib().emb_version_hosted_record_write(
+        _ptr(record, torch.uint8, "record"), int(ct.host.ctypes.data), int(ct.dev.data_ptr()), ct.T,
+        C.c_uint64(int(version)), _stream()))
+
+
+def emb_version_hosted_latch(handle: torch.Tensor, T: int, latch: torch.Tensor,
+                             status: Optional[torch.Tensor] = None) -> None:
+    if latch.numel() < emb_version_hosted_latch_bytes(T):
+        raise TypeError("latch too small")
+    _check("emb_version_hosted_latch", lib().emb_version_hosted_latch(
+        _ptr(handle, _U64, "handle"), int(T), _ptr(latch, torch.uint8, "latch"), _ptr(status, torch.int32, "status"),
+        _stream()))
+
+
+def _forward_cached_latched(fn: str, latch, T, D, dtype, ids, id_dtype, offsets, B, mode, out, hit_miss, status):
+    if latch.numel() < emb_version_hosted_latch_bytes(T):
+        raise TypeError("latch too small")
+    if offsets.numel() != T * B + 1 or out.numel() != T * B * D:
+        raise TypeError("shape mismatch")
+    _check(fn, getattr(lib(), fn)(
+        _ptr(latch, torch.uint8, "latch"), int(T), int(D), DTYPE[dtype], _ptr(ids, id_dtype, "ids"),
+        _ptr(offsets, torch.int64, "offsets"), int(B), ids.numel(), POOL[mode], _ptr(out, torch.float32, "out"),
+        _ptr(hit_miss, _U64, "hit_miss"), _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_bag_forward_cached_latched(latch: torch.Tensor, T: int, D: int, dtype: str, rows: torch.Tensor,
+                                   offsets: torch.Tensor, B: int, mode: str, out: torch.Tensor,
+                                   hit_miss: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None) -> None:
+    _forward_cached_latched("emb_bag_forward_cached_latched", latch, T, D, dtype, rows, torch.int64, offsets, B, mode, out,
+                            hit_miss, status)
+
+
+def emb_bag_forward_cached_latched_hashed(latch: torch.Tensor, T: int, D: int, dtype: str, raw: torch.Tensor,
+                                          offsets: torch.Tensor, B: int, mode: str, out: torch.Tensor,
+                                          hit_miss: Optional[torch.Tensor] = None,
+                                          status: Optional[torch.Tensor] = None) -> None:
+    _forward_cached_latched("emb_bag_forward_cached_latched_hashed", latch, T, D, dtype, raw, _U64, offsets, B, mode, out,
+                            hit_miss, status)

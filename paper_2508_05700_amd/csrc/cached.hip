@@ -532,15 +532,25 @@ static int cached_tables_entry(const emb_cached_table *th, const emb_cached_tabl
     int rc = cached_row_shape(D, dtype);
     if (rc != EMB_OK) return rc;
     if (T == 0 || B == 0) return EMB_OK;
-    if (!th || !td) return EMB_ERR_INVALID_ARG;
-    for (int32_t t = 0; t < T; ++t) {
-        const emb_cached_table &e = th[t];
-        if (e.num_rows <= 0 || e.num_hot < 0 || e.num_hot > e.num_rows) return EMB_ERR_INVALID_ARG;
-        if (!e.table || !e.cache_index || (e.num_hot > 0 && !e.cache_rows)) return EMB_ERR_INVALID_ARG;
-        if (!emb_aligned(e.table, 16) || !emb_aligned(e.cache_index, 16) || !emb_aligned(e.cache_rows, 16))
-            return EMB_ERR_INVALID_ARG;
-        if (e.mod_magic != emb_mod_magic((uint64_t)e.num_rows)) return EMB_ERR_INVALID_ARG;
-    }
+    rc = emb_check_cached_tables(th, td, T);
+    if (rc != EMB_OK) return rc;
+    return emb_forward_cached_unchecked_tables(td, T, D, dtype, ids_dev, offsets_dev, B, nnz, mode, out_dev, hit_miss_dev,
+                                               status_dev, stream, hashed);
+}
+
+// The launch of the multi-table cached lookup over descriptors that live in device memory only and
+// were validated when they were written (the latched copy of a hosted version record, versioned.hip).
+int emb_forward_cached_unchecked_tables(const emb_cached_table *td, int32_t T, int32_t D, int32_t dtype,
+                                        const int64_t *ids_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
+                                        int32_t mode, float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
+                                        void *stream, bool hashed)
+{
+    if (T < 0 || B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
+    if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
+    const int rc = cached_row_shape(D, dtype);
+    if (rc != EMB_OK) return rc;
+    if (T == 0 || B == 0) return EMB_OK;
+    if (!td) return EMB_ERR_INVALID_ARG;
     if (!offsets_dev || !out_dev || (nnz > 0 && !ids_dev)) return EMB_ERR_INVALID_ARG;
     if (!emb_aligned(out_dev, 16)) return EMB_ERR_INVALID_ARG;
     if (B > (int64_t)0x7FFFFFFF || T > 65535) return EMB_ERR_UNSUPPORTED;

@@ -50,6 +50,30 @@ int emb_forward_unchecked_tables(const emb_table *tables_dev, int32_t T, int32_t
                                  const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
                                  uint32_t *status_dev, void *stream, bool hashed);
 
+// The same for the descriptors of hosted tables with their caches.
+static inline int emb_check_cached_tables(const emb_cached_table *th, const emb_cached_table *td, int32_t T)
+{
+    if (T < 0) return EMB_ERR_INVALID_ARG;
+    if (T == 0) return EMB_OK;
+    if (!th || !td) return EMB_ERR_INVALID_ARG;
+    for (int32_t t = 0; t < T; ++t) {
+        const emb_cached_table &e = th[t];
+        if (e.num_rows <= 0 || e.num_hot < 0 || e.num_hot > e.num_rows) return EMB_ERR_INVALID_ARG;
+        if (!e.table || !e.cache_index || (e.num_hot > 0 && !e.cache_rows)) return EMB_ERR_INVALID_ARG;
+        if (!emb_aligned(e.table, 16) || !emb_aligned(e.cache_index, 16) || !emb_aligned(e.cache_rows, 16))
+            return EMB_ERR_INVALID_ARG;
+        if (e.mod_magic != ~UINT64_C(0) / (uint64_t)e.num_rows) return EMB_ERR_INVALID_ARG;
+    }
+    return EMB_OK;
+}
+
+// emb_bag_forward_cached_tables / _hashed over descriptors that exist in device memory only and were
+// validated earlier (the latched copy of a hosted version record; versioned.hip).
+int emb_forward_cached_unchecked_tables(const emb_cached_table *tables_dev, int32_t T, int32_t D, int32_t dtype,
+                                        const int64_t *ids_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
+                                        int32_t mode, float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
+                                        void *stream, bool hashed);
+
 // Row shape accepted by the gather kernels: whole 16-byte chunks, at most 1024 of them.
 // Quantised rows are read by the forward lookup only.
 static inline int emb_check_row_shape(int32_t D, int32_t dtype)

@@ -259,3 +259,28 @@ class HostedTableSet:
 
     def forward_hashed(self, raw: torch.Tensor, offsets: torch.Tensor, B: int, mode: str, out: torch.Tensor) -> None:
         emb.emb_bag_forward_cached_tables_hashed(self.tables, raw, offsets, B, mode, out, self.hit_miss, self.status)
+
+    # ---- the same set behind a version handle: a refresh becomes visible to lookups by one publish ----
+    def publish(self, version: int) -> None:
+        """Write a record of the descriptors as they are now (the active caches) and make it current.  Records
+        alternate between two buffers; the caller retires the older one's caches after the lookups that latched
+        it have finished (here: the next refresh but one overwrites them, in stream order)."""
+        T = len(self.caches)
+        if not hasattr(self, "handle"):
+            self.handle = torch.zeros(1, dtype=torch.int64, device=self.device)
+            self.records = [torch.empty(emb.emb_version_hosted_record_bytes(T), dtype=torch.uint8, device=self.device)
+                            for _ in range(2)]
+            self.latch = torch.empty(emb.emb_version_hosted_latch_bytes(T), dtype=torch.uint8, device=self.device)
+            self._rec = 0
+        self._rec = 1 - self._rec
+        emb.emb_version_hosted_record_write(self.records[self._rec], self.tables, version)
+        emb.emb_version_publish(self.handle, self.records[self._rec])
+
+    def forward_latched_hashed(self, raw: torch.Tensor, offsets: torch.Tensor, B: int, mode: str,
+                               out: torch.Tensor) -> torch.Tensor:
+        """Latch the current record, look up over it; returns the one-element view of the latched version."""
+        T = len(self.caches)
+        emb.emb_version_hosted_latch(self.handle, T, self.latch, self.status)
+        emb.emb_bag_forward_cached_latched_hashed(self.latch, T, self.D, self.dtype, raw, offsets, B, mode, out,
+                                                  self.hit_miss, self.status)
+        return emb.latched_version(self.latch)

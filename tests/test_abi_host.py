@@ -289,6 +289,32 @@ def test_staging_argument_errors(L):
     assert L.emb_bag_forward_staged(FAKE, 100, 24, 2, FAKE, 10, FAKE, 8, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == UNSUPPORTED
 
 
+def test_hosted_version_argument_errors(L):
+    n = C.c_size_t(0)
+    assert L.emb_version_hosted_record_bytes(4, C.byref(n)) == OK and n.value == 16 + 4 * 64
+    m = C.c_size_t(0)
+    assert L.emb_version_hosted_latch_bytes(4, C.byref(m)) == OK and m.value == n.value + 16384
+    assert L.emb_version_hosted_record_bytes(0, C.byref(n)) == INVALID
+    assert L.emb_version_hosted_latch_bytes(3, None) == INVALID
+    d = np.zeros(2, dtype=b.CACHED_DESC)
+    d["table"] = FAKE; d["cache_rows"] = FAKE; d["cache_index"] = FAKE
+    d["num_rows"] = [100, 7]; d["num_hot"] = [10, 7]
+    assert L.emb_cached_tables_init(d.ctypes.data, 2) == OK
+    assert L.emb_version_hosted_record_write(FAKE, d.ctypes.data, FAKE, 2, 0, None) == INVALID      # version 0 means none
+    assert L.emb_version_hosted_record_write(None, d.ctypes.data, FAKE, 2, 5, None) == INVALID
+    assert L.emb_version_hosted_record_write(FAKE, d.ctypes.data, None, 2, 5, None) == INVALID
+    bad = d.copy(); bad["num_hot"][1] = 8                                                            # more hot rows than rows
+    assert L.emb_version_hosted_record_write(FAKE, bad.ctypes.data, FAKE, 2, 5, None) == INVALID
+    bad = d.copy(); bad["mod_magic"][0] += 1                                                         # not initialised
+    assert L.emb_version_hosted_record_write(FAKE, bad.ctypes.data, FAKE, 2, 5, None) == INVALID
+    assert L.emb_version_hosted_latch(None, 2, FAKE, None, None) == INVALID
+    assert L.emb_version_hosted_latch(FAKE, 2, FAKE + 8, None, None) == INVALID
+    assert L.emb_bag_forward_cached_latched(None, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID
+    assert L.emb_bag_forward_cached_latched(FAKE, 2, 6, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == UNSUPPORTED
+    assert L.emb_bag_forward_cached_latched_hashed(FAKE, 2, 64, 0, FAKE, None, 4, 8, 0, FAKE, None, None, None) == INVALID
+    assert L.emb_bag_forward_cached_latched(FAKE, 2, 64, 0, FAKE, FAKE, 0, 0, 0, FAKE, None, None, None) == OK   # no bags
+
+
 def test_cache_policy_argument_errors(L):
     n = C.c_size_t(0)
     assert L.emb_cache_select_workspace_bytes(250_000_000, C.byref(n)) == OK

@@ -1346,6 +1346,121 @@ def test_versioned_lookup_by_row_number(dtype):
         assert np.array_equal(out.cpu().numpy(), plain)
 
 
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("int4", 64)])
+def test_versioned_lookup_over_hosted_tables_and_a_cache_refresh_as_one_switch(dtype, D):
+    # Two versions of a hosted table set (tables in pinned host memory, HBM caches), version 2 with other
+    # contents and row counts; and a third record that is version 2 again with REFRESHED caches (other hot
+    # sets, other cache buffers).  A lookup latches one record and returns (E, V) computed from that record's
+    # tables and caches only, whatever is published while it waits.
+    rng = np.random.default_rng(6200 + D)
+    T, B = 3, 150
+    quant = dtype == "int4"
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+
+    def make_version(rows_per_table, seed, hot_frac, salt0, tabs=None):
+        hosts, packed, hots, entries = [], [], [], []
+        for t, R in enumerate(rows_per_table):
+            if tabs is None:
+                x = (np.random.default_rng(seed + t).standard_normal((R, D)) * 0.01).astype(np.float32)
+                tab = oracle.quantize_rows(x, dtype) if quant else x
+            else:
+                tab = tabs[t]
+            host = torch.from_numpy(tab).pin_memory()
+            ptr = emb.emb_host_device_pointer(int(host.data_ptr()))
+            K = int(R * hot_frac)
+            hot = np.sort(np.random.default_rng(seed + 100 + t).choice(R, size=K, replace=False)).astype(np.int64)
+            cache = torch.zeros((max(K, 1), tab.shape[1]), dtype=torch.uint8 if quant else torch.float32, device=H.DEV)
+            index = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+            emb.emb_cache_build(ptr, R, D, dtype, H.dev(hot), cache, index, status)
+            hosts.append(host); packed.append(tab); hots.append(hot)
+            entries.append((ptr, R, cache, index, K, salt0 + t))
+        ct = emb.CachedTables(entries, D, dtype, device=torch.device(H.DEV))
+        return {"ct": ct, "np": packed, "hots": hots, "Rs": list(rows_per_table), "salts": [salt0 + t for t in range(T)],
+                "keep": hosts}
+
+    v1 = make_version([5000, 900, 12_000], 1, 0.1, 40)
+    v2 = make_version([7000, 2500, 3000], 2, 0.2, 50)
+    v2r = make_version(v2["Rs"], 3, 0.5, 50, tabs=v2["np"])             # version 2's tables, refreshed caches
+    recs = {}
+    for name, ver, number in (("v1", v1, 101), ("v2", v2, 102), ("v2r", v2r, 102)):
+        rec = torch.empty(emb.emb_version_hosted_record_bytes(T), dtype=torch.uint8, device=H.DEV)
+        emb.emb_version_hosted_record_write(rec, ver["ct"], number)
+        recs[name] = rec
+    lengths = rng.integers(0, 30, size=T * B).astype(np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    raw = rng.integers(0, 1 << 64, size=int(off[-1]), dtype=np.uint64)
+    raw_d, off_d = H.dev(raw), H.dev(off)
+    handle = torch.zeros(1, dtype=torch.int64, device=H.DEV)
+    latch = torch.empty(emb.emb_version_hosted_latch_bytes(T), dtype=torch.uint8, device=H.DEV)
+    out = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    hm = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+
+    def expect(ver):
+        outs, hits, misses = [], 0, 0
+        absums = []
+        for t in range(T):
+            s, e = int(off[t * B]), int(off[(t + 1) * B])
+            rows = oracle.hash_ids(raw[s:e], ver["salts"][t], ver["Rs"][t])
+            kw = {"D": D} if quant else {}
+            ref, absum, (h, m), st = oracle.bag_forward_cached(ver["np"][t], dtype, ver["hots"][t], rows,
+                                                               off[t * B:(t + 1) * B + 1] - s, B, "sum", **kw)
+            assert st == 0
+            outs.append(ref[0]); absums.append(absum[0]); hits += h; misses += m
+        return np.stack(outs), np.stack(absums), [hits, misses]
+
+    def lookup():
+        hm.zero_()
+        emb.emb_version_hosted_latch(handle, T, latch, status)
+        emb.emb_bag_forward_cached_latched_hashed(latch, T, D, dtype, raw_d, off_d, B, "sum", out, hm, status)
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), int(emb.latched_version(latch).item()), hm.cpu().tolist()
+
+    E, V, counts = lookup()                                            # nothing published
+    assert V == 0 and status.item() == emb.STATUS_NO_VERSION and not E.any()
+    status.zero_()
+    for name, ver, number in (("v1", v1, 101), ("v2", v2, 102), ("v2r", v2r, 102), ("v1", v1, 101)):
+        emb.emb_version_publish(handle, recs[name])
+        E, V, counts = lookup()
+        ref, absum, want = expect(ver)
+        assert V == number and status.item() == 0 and counts == want, name    # hit / miss counts of THAT record's caches
+        H.assert_pooled_close(E, ref, absum, what="hosted " + name)
+    # latched under version 1; version 2 with refreshed caches is published, on another stream, before the lookup runs
+    other = torch.cuda.Stream(device=H.DEV)
+    hm.zero_()
+    emb.emb_version_hosted_latch(handle, T, latch, status)
+    latched = torch.cuda.Event()
+    latched.record()
+    with torch.cuda.stream(other):
+        other.wait_event(latched)
+        emb.emb_version_publish(handle, recs["v2r"])
+        published = torch.cuda.Event()
+        published.record()
+    torch.cuda.current_stream().wait_event(published)
+    emb.emb_bag_forward_cached_latched_hashed(latch, T, D, dtype, raw_d, off_d, B, "sum", out, hm, status)
+    torch.cuda.synchronize()
+    ref1, absum1, want1 = expect(v1)
+    assert int(emb.latched_version(latch).item()) == 101 and hm.cpu().tolist() == want1
+    H.assert_pooled_close(out.cpu().numpy(), ref1, absum1, what="hosted, latched before the publish")
+    E, V, counts = lookup()
+    ref2, absum2, want2 = expect(v2r)
+    assert V == 102 and counts == want2
+    H.assert_pooled_close(E, ref2, absum2, what="hosted, after the publish")
+    # a latch for hosted tables refuses a record of HBM tables, and the other way round, harmlessly
+    w = [torch.zeros((10, D), dtype=torch.float32, device=H.DEV) for _ in range(T)]
+    ts = emb.TableSet(w, D, "f32", device=torch.device(H.DEV))
+    plain_rec = torch.empty(emb.emb_version_record_bytes(T), dtype=torch.uint8, device=H.DEV)
+    emb.emb_version_record_write(plain_rec, ts, 7)
+    emb.emb_version_publish(handle, plain_rec)
+    E, V, counts = lookup()
+    assert V == 0 and status.item() == emb.STATUS_NO_VERSION and not E.any()
+    status.zero_()
+    emb.emb_version_publish(handle, recs["v1"])
+    platch = torch.empty(emb.emb_version_latch_bytes(T), dtype=torch.uint8, device=H.DEV)
+    emb.emb_version_latch(handle, T, platch, status)
+    torch.cuda.synchronize()
+    assert int(emb.latched_version(platch).item()) == 0 and status.item() == emb.STATUS_NO_VERSION
+
+
 @pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 32), ("int4", 64), ("int8", 48)])
 def test_cached_forward_over_several_tables_in_one_launch(dtype, D):
     rng = np.random.default_rng(7000 + D)
@@ -1422,14 +1537,23 @@ def test_hosted_table_set_with_policy_refresh_matches_the_oracle():
     freq = [np.zeros(R, np.uint32) for R in Rs]
     hots = [np.zeros(0, np.int64) for _ in Rs]
     out = torch.empty((T, B, D), dtype=torch.float32, device=H.DEV)
+    out_v = torch.empty((T, B, D), dtype=torch.float32, device=H.DEV)
+    version = 1
+    hs.publish(version)                                               # the same set behind a version handle
     for step in range(6):
         lengths = rng.integers(0, 50, size=T * B).astype(np.int32)
         off, _ = oracle.lengths_to_offsets(lengths)
         raw = (np.minimum(rng.zipf(1.2, size=int(off[-1])), 1 << 20).astype(np.uint64)) * np.uint64(0x9E3779B97F4A7C15)
         hs.hit_miss.zero_()
+        got_version = hs.forward_latched_hashed(H.dev(raw), H.dev(off), B, "sum", out_v)
+        torch.cuda.synchronize()
+        counts_v = hs.hit_miss.cpu().tolist()
+        assert int(got_version.item()) == version
+        hs.hit_miss.zero_()
         hs.forward_hashed(H.dev(raw), H.dev(off), B, "sum", out)
         hs.observe(H.dev(raw), off, B)
         torch.cuda.synchronize()
+        assert torch.equal(out, out_v) and counts_v == hs.hit_miss.cpu().tolist()   # same caches, same bits
         got = out.cpu().numpy()
         hits = misses = 0
         for t in range(T):
@@ -1443,6 +1567,8 @@ def test_hosted_table_set_with_policy_refresh_matches_the_oracle():
         assert hs.hit_miss.cpu().tolist() == [hits, misses], step
         if step % 2 == 1:
             hs.refresh()
+            version += 1
+            hs.publish(version)                                       # refreshed caches become current in one switch
             torch.cuda.synchronize()
             for t in range(T):
                 hots[t] = oracle.cache_select(freq[t], Ks[t], 1)
