@@ -117,7 +117,7 @@ def _oracle_batch_inputs(w, b, seed):
         for t in range(w.T):
             seg = rows_np[off[t * w.B]:off[(t + 1) * w.B]]
             touched = np.unique(seg)
-            tables.append(oracle.quantize_rows(wl.table_values(w.table_seed(t, seed), touched, w.D), w.quant))
+            tables.append(oracle.quantize_rows(wl.table_values(w.table_seed(t, seed), touched, w.D), w.codes))
             parts.append(np.searchsorted(touched, seg))
         rows_np = np.concatenate(parts).astype(np.int64)
     else:
@@ -132,7 +132,7 @@ def _oracle_one_table(w, t, off, rows_np, tables, acc, dout):
 
     s, e = int(off[t * w.B]), int(off[(t + 1) * w.B])
     off_t = off[t * w.B:(t + 1) * w.B + 1] - s
-    store = w.quant if w.quant else w.dtype
+    store = w.codes if w.quant else w.dtype     # the oracle reads the codes; row padding is layout only
     kw = {"D": w.D} if w.quant else {}
     oracle.bag_forward([tables[t]], store, rows_np[s:e], off_t, w.B, w.pool, want_absum=False, **kw)
     if w.backward:
@@ -158,7 +158,7 @@ def cpu_baseline(w, batches_np, seed, min_seconds=10.0, max_batches=8):
     for b in batches_np[:max_batches]:
         off, rows_np, tables, ti = _oracle_batch_inputs(w, b, seed)
         t_index += ti
-        store = w.quant if w.quant else w.dtype
+        store = w.codes if w.quant else w.dtype
         kw = {"D": w.D} if w.quant else {}
         t0 = time.perf_counter()
         oracle.bag_forward(tables, store, rows_np, off, w.B, w.pool, want_absum=False, **kw)
@@ -1084,17 +1084,17 @@ def main() -> int:
                         stream_gbs))
 
     # ---- side measurements: the forward kernel alone on workloads 2 and 2u, and over INT4 copies
-    # of the same tables (2q4, 2uq4)
+    # of the same tables (2q4, 2uq4; 2uq4r: the INT4 rows padded to 64 bytes)
     extra = {}
     if not args.no_extra and args.workload == "3" and not args.scale_rows:
-        qkeep, qset = None, None
-        for name in ("2", "2un", "2u", "2q4", "2uq4"):
+        qsets = {}
+        for name in ("2", "2un", "2u", "2q4", "2uq4", "2uq4r"):
             wf = wl.WORKLOADS[name]
             tset = tabs.set
             if wf.quant:
-                if qset is None:
-                    qkeep, qset = pipeline.quantized_tableset(tabs, wf.quant)
-                tset = qset
+                if wf.quant not in qsets:
+                    qsets[wf.quant] = pipeline.quantized_tableset(tabs, wf.quant)
+                tset = qsets[wf.quant][1]
             fb = [pipeline.DeviceBatch(wf, wl.make_batch(wf, i, seed), dev) for i in range(args.batches)]
             fbuf = pipeline.StepBuffers(wf, max(d.nnz for d in fb), tabs.set.total_rows, dev)
             rows_v = []
@@ -1143,7 +1143,7 @@ def main() -> int:
                     name, ms, tot / n_it / (ms * 1e-3), gbs, 100 * gbs / HBM_PEAK_GBS))
             extra["forward_only_" + name] = ex
             del fb, fbuf, rows_v
-        del qkeep, qset
+        del qsets
 
     # ---- CPU baseline: the oracle, as it stands, on this host ----------------
     cpu = None

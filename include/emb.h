@@ -71,9 +71,12 @@ typedef enum { EMB_POOL_SUM = 0, EMB_POOL_MEAN = 1 } emb_pool;
  * served from cache.  Results are bit-identical with and without it; quantised
  * tables ignore it. */
 #define EMB_ROWS_STREAMING 0x100
-/* Storage type of table rows.  EMB_INT8 / EMB_INT4 are row-quantised tables
- * (see emb_quantize_rows); only the forward lookup reads those. */
-typedef enum { EMB_F32 = 0, EMB_BF16 = 1, EMB_INT8 = 2, EMB_INT4 = 3 } emb_dtype;
+/* Storage type of table rows.  EMB_INT8 / EMB_INT4 / EMB_INT4_ROW64 are
+ * row-quantised tables (see emb_quantize_rows); only the forward lookup reads
+ * those.  EMB_INT4_ROW64 holds the same scale, bias and codes as EMB_INT4 with
+ * every row padded to a multiple of 64 bytes: a choice for callers that prefer
+ * lookup speed to table size (rows then never straddle a 64-byte sector). */
+typedef enum { EMB_F32 = 0, EMB_BF16 = 1, EMB_INT8 = 2, EMB_INT4 = 3, EMB_INT4_ROW64 = 4 } emb_dtype;
 
 /* bits of the device status word */
 #define EMB_STATUS_BAD_INDEX 1u   /* a row index < 0 or >= num_rows of its table */
@@ -297,11 +300,14 @@ int emb_bag_forward_mixed(const emb_table *tables_host, const emb_table *tables_
 /* ---- row-quantised tables (Section 4.1.2: INT4 tables for serving) ------- */
 
 /* Bytes of one table row: D*4 (EMB_F32), D*2 (EMB_BF16), or for the quantised
- * types 8 + D (EMB_INT8) / 8 + D/2 (EMB_INT4) rounded up to a multiple of 16:
+ * types 8 + D (EMB_INT8) / 8 + D/2 (EMB_INT4) rounded up to a multiple of 16,
+ * 8 + D/2 rounded up to a multiple of 64 (EMB_INT4_ROW64):
  *   bytes 0..3 scale (fp32), bytes 4..7 bias (fp32), then the codes: one byte
  *   per element (INT8), or element 2k in the low and 2k+1 in the high nibble
- *   of byte k (INT4); zero padding.  Element value = scale * code + bias.
- * D = 64: 48 bytes for INT4, 37.5 % of an fp16 row.  0 on invalid arguments. */
+ *   of byte k (INT4, INT4_ROW64); zero padding.  Element value = scale * code
+ *   + bias.
+ * D = 64: 48 bytes for INT4, 37.5 % of an fp16 row; 64 bytes for INT4_ROW64,
+ * 50 %.  0 on invalid arguments. */
 int64_t emb_row_bytes(int32_t D, int32_t dtype);
 
 /* Post-training quantisation of an fp32 table [num_rows, D] (src_dev) into
@@ -309,8 +315,9 @@ int64_t emb_row_bytes(int32_t D, int32_t dtype);
  * asymmetric min/max, all in fp32 with IEEE division and round-half-even:
  *   bias = min_d x_d, scale = (max_d x_d - bias) / (2^b - 1), or 1 if the row
  *   is constant, code_d = clamp(rint((x_d - bias) / scale), 0, 2^b - 1).
- * dtype: EMB_INT8 or EMB_INT4.  Both pointers 16-byte aligned; dst_dev may be
- * mapped host memory (the rows are then written over the link).
+ * dtype: EMB_INT8, EMB_INT4 or EMB_INT4_ROW64 (the codes of EMB_INT4, wider
+ * padding).  Both pointers 16-byte aligned; dst_dev may be mapped host memory
+ * (the rows are then written over the link).
  * EMB_ERR_UNSUPPORTED if D is not a multiple of 16 or above 1024. */
 int emb_quantize_rows(const float *src_dev, int64_t num_rows, int32_t D, int32_t dtype,
                       void *dst_dev, void *stream);

@@ -18,7 +18,8 @@ import torch
 from . import build as _build
 
 POOL = {"sum": 0, "mean": 1}
-DTYPE = {"f32": 0, "bf16": 1, "int8": 2, "int4": 3}
+DTYPE = {"f32": 0, "bf16": 1, "int8": 2, "int4": 3, "int4r64": 4}
+QUANT_DTYPES = ("int8", "int4", "int4r64")   # row-quantised storage; "int4r64": INT4 rows padded to 64 bytes
 ROWS_STREAMING = 0x100   # hint bit for the forward lookups (EMB_ROWS_STREAMING)
 STATUS_BAD_INDEX = 1
 STATUS_BAD_OFFSETS = 2
@@ -227,7 +228,8 @@ def _check(fn: str, rc: int) -> None:
 
 
 _U64 = (torch.int64, torch.uint64)
-_TABLE_TORCH = {"f32": torch.float32, "bf16": torch.bfloat16, "int8": torch.uint8, "int4": torch.uint8}
+_TABLE_TORCH = {"f32": torch.float32, "bf16": torch.bfloat16, "int8": torch.uint8, "int4": torch.uint8,
+                "int4r64": torch.uint8}
 
 
 class TableSet:
@@ -251,7 +253,7 @@ class TableSet:
             if isinstance(w, tuple):
                 ptr, rows = int(w[0]), int(w[1])
             else:
-                width = emb_row_bytes(self.D, dtype) if dtype in ("int8", "int4") else self.D
+                width = emb_row_bytes(self.D, dtype) if dtype in QUANT_DTYPES else self.D
                 if w.dim() != 2 or w.shape[1] != width:
                     raise TypeError("weights[%d] must be [num_rows, %d]" % (t, width))
                 ptr, rows = _ptr(w, _TABLE_TORCH[dtype], "weights[%d]" % t), int(w.shape[0])

@@ -344,7 +344,7 @@ int dispatch_cached_tables_quant(int lpr, const CachedTablesArgs &a)
 // Row shapes the cached lookup accepts: those of the plain lookup, quantised ones included.
 int cached_row_shape(int32_t D, int32_t dtype)
 {
-    if (dtype == EMB_INT8 || dtype == EMB_INT4) return emb_check_quant_shape(D, dtype);
+    if (emb_is_quant(dtype)) return emb_check_quant_shape(D, dtype);
     return emb_check_row_shape(D, dtype);
 }
 
@@ -449,13 +449,13 @@ static int cached_entry(const void *table_dev, int64_t num_rows, int32_t D, int3
     if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
 
     hipStream_t s = emb_stream(stream);
-    if (dtype == EMB_INT8 || dtype == EMB_INT4) {
+    if (emb_is_quant(dtype)) {
         const int64_t rb = emb_row_bytes(D, dtype);
         const int ql = emb_quant_lanes(D);
         const char *tp = reinterpret_cast<const char *>(table_dev), *cp = reinterpret_cast<const char *>(cache_rows_dev);
         const CacheEntry *ip = reinterpret_cast<const CacheEntry *>(cache_index_dev);
         unsigned long long *hm = reinterpret_cast<unsigned long long *>(hit_miss_dev);
-        if (dtype == EMB_INT8)
+        if (emb_quant_bits(dtype) == 8)
             return dispatch_cached_quant<8>(ql, s, tp, cp, ip, num_rows, num_hot, B, nnz, rows_dev, offsets_dev, D, rb,
                                             mode, out_dev, hm, status_dev, hashed, salt, magic);
         return dispatch_cached_quant<4>(ql, s, tp, cp, ip, num_rows, num_hot, B, nnz, rows_dev, offsets_dev, D, rb, mode,
@@ -557,8 +557,9 @@ int emb_forward_cached_unchecked_tables(const emb_cached_table *td, int32_t T, i
 
     CachedTablesArgs a{td,      T,      B,         nnz,  ids_dev, offsets_dev, D, mode, emb_row_bytes(D, dtype),
                        out_dev, reinterpret_cast<unsigned long long *>(hit_miss_dev), status_dev, hashed, emb_stream(stream)};
-    if (dtype == EMB_INT8) return dispatch_cached_tables_quant<8>(emb_quant_lanes(D), a);
-    if (dtype == EMB_INT4) return dispatch_cached_tables_quant<4>(emb_quant_lanes(D), a);
+    if (emb_is_quant(dtype))
+        return emb_quant_bits(dtype) == 8 ? dispatch_cached_tables_quant<8>(emb_quant_lanes(D), a)
+                                          : dispatch_cached_tables_quant<4>(emb_quant_lanes(D), a);
     int lpr, cpl;
     emb_row_split((int)(a.row_bytes / 16), lpr, cpl);
     const bool bf16 = dtype == EMB_BF16;

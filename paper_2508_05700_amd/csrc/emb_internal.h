@@ -74,11 +74,19 @@ int emb_forward_cached_unchecked_tables(const emb_cached_table *tables_dev, int3
                                         int32_t mode, float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
                                         void *stream, bool hashed);
 
+// Row-quantised storage types and the bits of one of their codes (EMB_INT4_ROW64
+// differs from EMB_INT4 in the row stride only).
+static inline bool emb_is_quant(int32_t dtype)
+{
+    return dtype == EMB_INT8 || dtype == EMB_INT4 || dtype == EMB_INT4_ROW64;
+}
+static inline int emb_quant_bits(int32_t dtype) { return dtype == EMB_INT8 ? 8 : 4; }
+
 // Row shape accepted by the gather kernels: whole 16-byte chunks, at most 1024 of them.
 // Quantised rows are read by the forward lookup only.
 static inline int emb_check_row_shape(int32_t D, int32_t dtype)
 {
-    if (dtype == EMB_INT8 || dtype == EMB_INT4) return EMB_ERR_UNSUPPORTED;
+    if (emb_is_quant(dtype)) return EMB_ERR_UNSUPPORTED;
     int esz = emb_elem_size(dtype);
     if (esz == 0 || D <= 0) return EMB_ERR_INVALID_ARG;
     int64_t bytes = (int64_t)D * esz;

@@ -145,7 +145,7 @@ static int forward_entry(const emb_table *tables_host, const emb_table *tables_d
     const bool streaming = (mode & EMB_ROWS_STREAMING) != 0;
     mode &= ~EMB_ROWS_STREAMING;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
-    const bool quant = dtype == EMB_INT8 || dtype == EMB_INT4;
+    const bool quant = emb_is_quant(dtype);
     int rc = quant ? emb_check_quant_shape(D, dtype) : emb_check_row_shape(D, dtype);
     if (rc != EMB_OK) return rc;
     if (check_tables) {

@@ -5,8 +5,8 @@
 // Storage of one row of D elements, b = 8 or 4 bits per code:
 //   bytes 0..3 scale (fp32), bytes 4..7 bias (fp32), then the codes (INT8: one
 //   byte per element; INT4: element 2k in the low nibble of byte k, 2k+1 in the
-//   high nibble), zero-padded to a multiple of 16 bytes.  Element value =
-//   scale * code + bias.
+//   high nibble), zero-padded to a multiple of 16 bytes (EMB_INT4_ROW64: of 64
+//   bytes, otherwise the row of EMB_INT4).  Element value = scale * code + bias.
 //
 // Both kernels give a lane 16 consecutive elements of a row, i.e. 8 (INT4) or
 // 16 (INT8) code bytes, so a row of D elements takes LPR = D/16 lanes rounded up
@@ -88,8 +88,9 @@ __global__ __launch_bounds__(Q_BLOCK) void quantize_rows_kernel(const float *__r
     }
     if (l == 0) {
         *reinterpret_cast<uint2 *>(row) = make_uint2(__float_as_uint(scale), __float_as_uint(bias));
-        const int64_t used = 8 + (int64_t)D * BITS / 8;   // a multiple of 8: the padding is 0 or 8 bytes
-        if (used < row_bytes) *reinterpret_cast<uint2 *>(row + used) = make_uint2(0u, 0u);
+        // header and codes end on a multiple of 8 and so does the row: the padding is whole 8-byte words
+        for (int64_t at = 8 + (int64_t)D * BITS / 8; at < row_bytes; at += 8)
+            *reinterpret_cast<uint2 *>(row + at) = make_uint2(0u, 0u);
     }
 }
 
@@ -194,7 +195,7 @@ void dispatch_quantize(int lpr, hipStream_t s, const float *src, int64_t R, int3
 
 int emb_check_quant_shape(int32_t D, int32_t dtype)
 {
-    if (dtype != EMB_INT8 && dtype != EMB_INT4) return EMB_ERR_INVALID_ARG;
+    if (!emb_is_quant(dtype)) return EMB_ERR_INVALID_ARG;
     if (D <= 0) return EMB_ERR_INVALID_ARG;
     if (D % Q_ELEMS != 0 || D > Q_ELEMS * EMB_WAVE) return EMB_ERR_UNSUPPORTED;
     return EMB_OK;
@@ -208,6 +209,7 @@ extern "C" int64_t emb_row_bytes(int32_t D, int32_t dtype)
         case EMB_BF16: return (int64_t)D * 2;
         case EMB_INT8: return (8 + (int64_t)D + 15) / 16 * 16;
         case EMB_INT4: return D % 2 ? 0 : (8 + (int64_t)D / 2 + 15) / 16 * 16;
+        case EMB_INT4_ROW64: return D % 2 ? 0 : (8 + (int64_t)D / 2 + 63) / 64 * 64;
         default: return 0;
     }
 }
@@ -223,7 +225,7 @@ extern "C" int emb_quantize_rows(const float *src_dev, int64_t num_rows, int32_t
     if (num_rows > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
     const int64_t rb = emb_row_bytes(D, dtype);
     hipStream_t s = emb_stream(stream);
-    if (dtype == EMB_INT8) dispatch_quantize<8>(emb_quant_lanes(D), s, src_dev, num_rows, D, rb, static_cast<char *>(dst_dev));
+    if (emb_quant_bits(dtype) == 8) dispatch_quantize<8>(emb_quant_lanes(D), s, src_dev, num_rows, D, rb, static_cast<char *>(dst_dev));
     else dispatch_quantize<4>(emb_quant_lanes(D), s, src_dev, num_rows, D, rb, static_cast<char *>(dst_dev));
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
@@ -236,7 +238,7 @@ int emb_forward_quant(const emb_table *tables_dev, int32_t T, int32_t D, int32_t
 {
     const int64_t rb = emb_row_bytes(D, dtype);
     const int lpr = emb_quant_lanes(D);
-    if (dtype == EMB_INT8)
+    if (emb_quant_bits(dtype) == 8)
         return dispatch_quant_forward<8>(lpr, s, tables_dev, T, B, nnz, rows_dev, offsets_dev, D, rb, mode, out_dev,
                                          status_dev);
     return dispatch_quant_forward<4>(lpr, s, tables_dev, T, B, nnz, rows_dev, offsets_dev, D, rb, mode, out_dev,

@@ -242,7 +242,7 @@ int dispatch_staged_quant(int lpr, const StagedArgs &a)
 
 int staged_row_shape(int32_t D, int32_t dtype)
 {
-    if (dtype == EMB_INT8 || dtype == EMB_INT4) return emb_check_quant_shape(D, dtype);
+    if (emb_is_quant(dtype)) return emb_check_quant_shape(D, dtype);
     return emb_check_row_shape(D, dtype);
 }
 
@@ -333,8 +333,9 @@ extern "C" int emb_bag_forward_staged(const void *table_dev, int64_t num_rows, i
     a.hit_miss = reinterpret_cast<unsigned long long *>(hit_miss_dev);
     a.status = status_dev;
     a.s = emb_stream(stream);
-    if (dtype == EMB_INT8) return dispatch_staged_quant<8>(emb_quant_lanes(D), a);
-    if (dtype == EMB_INT4) return dispatch_staged_quant<4>(emb_quant_lanes(D), a);
+    if (emb_is_quant(dtype))
+        return emb_quant_bits(dtype) == 8 ? dispatch_staged_quant<8>(emb_quant_lanes(D), a)
+                                          : dispatch_staged_quant<4>(emb_quant_lanes(D), a);
     int lpr, cpl;
     emb_row_split((int)(a.src.row_bytes / 16), lpr, cpl);
     const bool bf16 = dtype == EMB_BF16;

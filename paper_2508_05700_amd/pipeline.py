@@ -190,8 +190,8 @@ class HotRowCache:
         self.table_ptr, self.R, self.D, self.dtype, self.salt = int(table_ptr), int(num_rows), int(D), dtype, int(salt)
         self.capacity, self.decay_shift = int(num_hot), int(decay_shift)
         rowb = emb.emb_row_bytes(D, dtype)
-        shape = (self.capacity, rowb) if dtype in ("int8", "int4") else (self.capacity, D)
-        tdt = torch.uint8 if dtype in ("int8", "int4") else (torch.float32 if dtype == "f32" else torch.bfloat16)
+        shape = (self.capacity, rowb) if dtype in emb.QUANT_DTYPES else (self.capacity, D)
+        tdt = torch.uint8 if dtype in emb.QUANT_DTYPES else (torch.float32 if dtype == "f32" else torch.bfloat16)
         self.rows = [torch.empty(shape, dtype=tdt, device=device) for _ in range(2)]
         self.index = [torch.empty(emb.emb_cache_index_bytes(num_rows), dtype=torch.uint8, device=device)
                       for _ in range(2)]

@@ -204,7 +204,9 @@ class Workload:
     hot_fraction: float = 0.0
     lr: float = 0.01
     eps: float = 1e-8
-    quant: Optional[str] = None   # "int8" | "int4": the fp32 tables are stored row-quantised (forward only)
+    # "int8" | "int4" | "int4r64" (INT4 rows padded to 64 bytes): the fp32 tables are stored row-quantised
+    # (forward only)
+    quant: Optional[str] = None
     streaming: bool = False       # the lookups pass the "rows are not reused" hint (IDs without popular heads)
 
     def scaled(self, rows: Optional[int] = None, bags: Optional[int] = None,
@@ -227,6 +229,11 @@ class Workload:
     def storage(self) -> str:
         """Storage type of the table rows the lookups read."""
         return self.quant or self.dtype
+
+    @property
+    def codes(self) -> Optional[str]:
+        """The quantised encoding without its row padding ("int4r64" holds the rows of "int4")."""
+        return "int4" if self.quant == "int4r64" else self.quant
 
     def table_seed(self, t: int, seed: int = DEFAULT_SEED) -> int:
         return int(seed) * 1000 + int(t)
@@ -264,6 +271,9 @@ WORKLOADS: Dict[str, Workload] = {
                     max_len=100, ids="zipf", alpha=1.05, n_keys=10 ** 9, pool="mean", quant="int8"),
     "2uq4": Workload("2uq4", T=16, R=10_000_000, D=64, dtype="f32", B=8192, length="poisson", mean_len=20,
                      max_len=100, ids="raw_uniform", pool="mean", quant="int4"),
+    # 2uq4r: 2uq4 with every INT4 row padded from 48 to 64 bytes (no row straddles a 64-byte sector)
+    "2uq4r": Workload("2uq4r", T=16, R=10_000_000, D=64, dtype="f32", B=8192, length="poisson", mean_len=20,
+                      max_len=100, ids="raw_uniform", pool="mean", quant="int4r64"),
     # 5: host-resident table plus an HBM cache of the hottest 5 % of rows
     "5": Workload("5", T=1, R=250_000_000, D=64, dtype="f32", B=16384, length="poisson", mean_len=30,
                   max_len=None, ids="zipf", alpha=1.1, n_keys=10 ** 9, pool="sum", hybrid=True,

@@ -132,11 +132,20 @@ def test_backward_argument_errors(L):
     assert f(*args(side=C.addressof(side))) == INVALID
 
 
+def fhq(L):
+    # padded INT4 rows, like the other quantised types, are not read by the hashing lookup or the backward
+    d0 = _tables()
+    assert L.emb_bag_backward_workspace_bytes(2, 4, 8, 1007, 64, 4) == 0
+    return L.emb_bag_forward_hashed(d0.ctypes.data, FAKE, 2, 64, 4, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None)
+
+
 def test_quantized_row_size_and_argument_errors(L):
     L.emb_row_bytes.restype = C.c_int64
     rb = L.emb_row_bytes
     assert rb(64, 0) == 256 and rb(64, 1) == 128 and rb(64, 2) == 80 and rb(64, 3) == 48
     assert rb(32, 3) == 32 and rb(16, 3) == 16 and rb(0, 3) == 0 and rb(63, 3) == 0 and rb(64, 9) == 0
+    # INT4 rows padded to whole 64-byte sectors
+    assert rb(64, 4) == 64 and rb(16, 4) == 64 and rb(112, 4) == 64 and rb(128, 4) == 128 and rb(63, 4) == 0
     q = L.emb_quantize_rows
     assert q(FAKE, 10, 24, 3, FAKE, None) == UNSUPPORTED        # D must be a multiple of 16
     assert q(FAKE, 10, 2048, 2, FAKE, None) == UNSUPPORTED
@@ -145,6 +154,8 @@ def test_quantized_row_size_and_argument_errors(L):
     assert q(FAKE, 10, 64, 3, FAKE + 8, None) == INVALID        # 16-byte alignment
     assert q(FAKE, -1, 64, 3, FAKE, None) == INVALID
     assert q(FAKE, 0, 64, 3, FAKE, None) == OK                  # nothing to do
+    assert q(FAKE, 0, 64, 4, FAKE, None) == OK and q(FAKE, 10, 24, 4, FAKE, None) == UNSUPPORTED
+    assert fhq(L) == UNSUPPORTED
     # the streaming hint is the only extra bit a mode may carry
     dm = _tables()
     assert L.emb_bag_forward(dm.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0x200, FAKE, None, None) == INVALID

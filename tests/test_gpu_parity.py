@@ -308,6 +308,70 @@ def test_forward_quantized_matches_oracle(D, dtype, mode):
     H.assert_pooled_close(out, ref, absum, what="quantised forward %s D=%d" % (dtype, D))
 
 
+@pytest.mark.parametrize("D", [16, 64, 112, 256])
+def test_int4_rows_padded_to_64_bytes_hold_the_int4_row_and_give_the_same_lookups(D):
+    # "int4r64" is a layout choice, not another encoding: the first bytes of every row are the oracle's INT4 row, the
+    # rest is zero, and every lookup route pools what the oracle pools from the unpadded INT4 table
+    rng = np.random.default_rng(990 + D)
+    R, B, K = 6007, 500, 700
+    x = _quant_source(rng, R, D)
+    packed = oracle.quantize_rows(x, "int4")
+    rb = (8 + D // 2 + 63) // 64 * 64
+    assert emb.emb_row_bytes(D, "int4r64") == rb
+    q = torch.full((R, rb), 0xAB, dtype=torch.uint8, device=H.DEV)
+    emb.emb_quantize_rows(H.dev(x), "int4r64", q)
+    torch.cuda.synchronize()
+    got = q.cpu().numpy()
+    assert np.array_equal(got[:, :packed.shape[1]], packed) and not got[:, packed.shape[1]:].any()
+    lengths = rng.integers(0, 40, size=B).astype(np.int32)
+    off, _ = oracle.lengths_to_offsets(lengths)
+    hot = np.sort(rng.choice(R, size=K, replace=False)).astype(np.int64)
+    n = int(off[-1])
+    rows = np.where(rng.random(n) < 0.6, rng.choice(hot, size=n), rng.integers(0, R, size=n)).astype(np.int64)
+    rows[[3, 11]] = [R, -2]
+    # plain lookup
+    ts = emb.TableSet([q], D, "int4r64", device=torch.device(H.DEV))
+    out, st = H.gpu_forward(ts, rows, off, B, "mean")
+    ref, absum, rst = oracle.bag_forward([packed], "int4", rows, off, B, "mean", D=D)
+    assert st == rst == emb.STATUS_BAD_INDEX
+    H.assert_pooled_close(out, ref, absum, what="padded INT4 forward D=%d" % D)
+    # cached lookup, and the staged one, over the same table
+    ptr = int(q.data_ptr())
+    index = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+    cache = torch.full((K, rb), 0xEE, dtype=torch.uint8, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_cache_build(ptr, R, D, "int4r64", H.dev(hot), cache, index, status)
+    o1 = torch.full((1, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    hm1 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    emb.emb_bag_forward_cached(ptr, R, D, "int4r64", cache, index, K, H.dev(rows), H.dev(off), B, "sum", o1, hm1, status)
+    cap = n
+    stage = torch.zeros((cap, rb), dtype=torch.uint8, device=H.DEV)
+    loc = torch.full((n,), -5, dtype=torch.int64, device=H.DEV)
+    count = torch.zeros(1, dtype=torch.int64, device=H.DEV)
+    emb.emb_cache_stage_misses(ptr, R, D, "int4r64", index, K, H.dev(rows), stage, cap, loc, count, status)
+    o2 = torch.full((1, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    hm2 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    emb.emb_bag_forward_staged(ptr, R, D, "int4r64", cache, K, stage, cap, loc, H.dev(off), B, "sum", o2, hm2, status)
+    torch.cuda.synchronize()
+    assert np.array_equal(cache.cpu().numpy(), got[hot])
+    ref, absum, (hits, misses), rst = oracle.bag_forward_cached(packed, "int4", hot, rows, off, B, "sum", D=D)
+    assert int(status.item()) == rst == emb.STATUS_BAD_INDEX
+    assert hm1.cpu().tolist() == hm2.cpu().tolist() == [hits, misses] and int(count.item()) == misses
+    H.assert_pooled_close(o1.cpu().numpy(), ref, absum, what="padded INT4 cached lookup")
+    H.assert_pooled_close(o2.cpu().numpy(), ref, absum, what="padded INT4 staged lookup")
+    # several hosted tables in one launch
+    ct = emb.CachedTables([(ptr, R, cache, index, K, 0)] * 2, D, "int4r64", device=torch.device(H.DEV))
+    off2 = np.concatenate([off, off[1:] + off[-1]])
+    rows2 = np.concatenate([rows, rows])
+    o3 = torch.full((2, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    hm3 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    emb.emb_bag_forward_cached_tables(ct, H.dev(rows2), H.dev(off2), B, "sum", o3, hm3, status)
+    torch.cuda.synchronize()
+    assert hm3.cpu().tolist() == [2 * hits, 2 * misses]
+    for t in range(2):
+        H.assert_pooled_close(o3[t].cpu().numpy(), ref, absum, what="padded INT4 hosted tables")
+
+
 def test_forward_quantized_grid_tables_are_bit_exact_and_empty_batch():
     # integer codes with scale 1 and integer bias: every partial sum is exact in fp32
     rng = np.random.default_rng(960)
