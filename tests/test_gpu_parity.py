@@ -56,7 +56,7 @@ def test_hash_ids_tables_bit_exact():
 # ---------------------------------------------------------------------------
 # offsets: bit-exact
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("n", [0, 1, 2, 4095, 4096, 4097, 131_072, 1_000_005, 4096 * 1025 + 3])
+@pytest.mark.parametrize("n", [0, 1, 2, 4095, 4096, 4097, 131_072, 200_003, 262_144, 262_145, 1_000_005, 4096 * 1025 + 3])
 def test_offsets_bit_exact(n):
     rng = np.random.default_rng(200 + n % 1000)
     L = rng.integers(0, 101, size=n).astype(np.int32)
@@ -77,6 +77,24 @@ def test_offsets_large_values_and_negative_lengths():
     torch.cuda.synchronize()
     ref, st = oracle.lengths_to_offsets(L)
     assert status.item() == st == emb.STATUS_BAD_OFFSETS and np.array_equal(out.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("n", [20_000, 300_000])
+def test_offsets_negative_lengths_in_earlier_tiles_and_unaligned_input(n):
+    # a negative length counts as 0 wherever it sits, also in tiles before the one that is being summed; the
+    # lengths need not start on a 16-byte boundary
+    rng = np.random.default_rng(210 + n)
+    L = rng.integers(0, 50, size=n + 1).astype(np.int32)
+    L[rng.choice(n, size=40, replace=False)] = -rng.integers(1, 1000, size=40).astype(np.int32)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    for skip in (0, 1):
+        src = H.dev(L)[skip:skip + n]
+        out = torch.full((n + 1,), -9, dtype=torch.int64, device=H.DEV)
+        status.zero_()
+        emb.emb_lengths_to_offsets(src, out, status)
+        torch.cuda.synchronize()
+        ref, st = oracle.lengths_to_offsets(L[skip:skip + n])
+        assert status.item() == st == emb.STATUS_BAD_OFFSETS and np.array_equal(out.cpu().numpy(), ref)
 
 
 # ---------------------------------------------------------------------------
