@@ -806,6 +806,9 @@ def main() -> int:
     ap.add_argument("--no-extra", action="store_true", help="skip the forward-only side measurements")
     ap.add_argument("--no-fused-forward", action="store_true",
                     help="hash the IDs in a kernel of their own instead of inside the forward lookup")
+    ap.add_argument("--separate-offsets", action="store_true",
+                    help="training step: bag offsets by emb_lengths_to_offsets (three launches) before the lookup, "
+                         "instead of inside emb_bag_forward_train_lengths")
     ap.add_argument("--overlap-sort", action="store_true",
                     help="enqueue the backward's sort on a second stream beside the forward (measured: no gain "
                          "here, the forward saturates HBM and the sort's small kernels only get slower)")
@@ -862,14 +865,18 @@ def main() -> int:
     K, W = args.steps, args.warmup
     fused = not args.no_fused_forward and not args.overlap_sort and not w.quant and dbs[0].raw is not None
 
+    train_route = fused and w.backward     # the lookup also writes the backward's records
+    offsets_inside = train_route and not args.separate_offsets   # ... and makes the bag offsets on the way
+
     def do_index(db):
         """Bag offsets, and the hashing unless it is fused into the forward.  Returns the rows (or None)."""
+        if offsets_inside:
+            return None
         if fused:
             emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
             return None
         return pipeline.run_index_stage(w, tabs.set, db, buf)
 
-    train_route = fused and w.backward     # the lookup also writes the backward's records
     versioned = args.versioned
     if versioned:
         if w.backward or not fused:
@@ -882,6 +889,10 @@ def main() -> int:
         emb.emb_version_publish(ver_handle, ver_record)
 
     def do_forward(db, rows):
+        if offsets_inside:
+            emb.emb_bag_forward_train_lengths(tabs.set, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets,
+                                              buf.workspace, None, buf.num_unique, buf.status)
+            return None
         if train_route:
             emb.emb_bag_forward_train(tabs.set, db.raw, buf.offsets, w.B, w.pool, buf.out, buf.workspace, None,
                                       buf.num_unique, buf.status)
@@ -1023,6 +1034,12 @@ def main() -> int:
             fwd_extra = nnz_i * 8 + bags * 4          # one 8-byte record per lookup, one scale per bag
         index_entry = entry("offsets_* (index stage, 3 launches; hashing is done inside the forward)", ms_index,
                             bags * 12, "12 B per bag (length in, offset out)")
+        if offsets_inside:
+            fwd_name = ("offsets_tile_scan + bwd_init + bag_forward_train_kernel (bag offsets + hash + gather-pool + "
+                        "the backward's records)")
+            fwd_extra += bags * 28                   # length in, sum within the tile out and in, offset out
+            index_entry = entry("(index stage: the bag offsets are made inside the training lookup)", ms_index, 1,
+                                "not priced: counted under the lookup")
     else:
         fwd_name = ("bag_forward_quant_kernel (gather-dequantise-pool, %s rows of %d B)" % (w.quant, rowb) if w.quant
                     else "bag_forward_kernel (gather-pool)")

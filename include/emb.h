@@ -345,6 +345,25 @@ int emb_bag_forward_train(const emb_table *tables_host, const emb_table *tables_
                           float *out_dev, int64_t *rows_out_dev, void *workspace_dev,
                           size_t workspace_bytes, int64_t *num_unique_out_dev,
                           uint32_t *status_dev, void *stream);
+/* emb_lengths_to_offsets and emb_bag_forward_train in one call (Section 3.1: a
+ * training step starts from the bag lengths and raw IDs of its batch): takes
+ * the T*B bag lengths instead of offsets and writes the offsets (i64[T*B+1])
+ * to offsets_out_dev for whoever needs them afterwards.  Pooled output,
+ * offsets, row numbers, status bits and the backward's records are
+ * bit-identical to the two calls; two launches fewer (the sums within tiles
+ * of 4096 lengths are one launch, the tiles' prefix sums are taken by the
+ * backward's set-up kernel, and the lookup adds the two).  A negative length
+ * counts as 0 and sets EMB_STATUS_BAD_OFFSETS; nnz must be the sum of the
+ * lengths (a different nnz sets EMB_STATUS_BAD_OFFSETS and aborts the backward
+ * as malformed offsets do).  offsets_out_dev must not overlap lengths_dev.
+ * Everything else as emb_bag_forward_train. */
+int emb_bag_forward_train_lengths(const emb_table *tables_host, const emb_table *tables_dev,
+                                  int32_t T, int32_t D, int32_t dtype, const uint64_t *raw_dev,
+                                  const int32_t *lengths_dev, int64_t B, int64_t nnz,
+                                  int32_t mode, float *out_dev, int64_t *offsets_out_dev,
+                                  int64_t *rows_out_dev, void *workspace_dev,
+                                  size_t workspace_bytes, int64_t *num_unique_out_dev,
+                                  uint32_t *status_dev, void *stream);
 int emb_bag_backward_sort_prepared(const emb_table *tables_host, const emb_table *tables_dev,
                                    int32_t T, int32_t D, int32_t dtype, int64_t B, int64_t nnz,
                                    void *workspace_dev, size_t workspace_bytes,

@@ -33,6 +33,7 @@ namespace {
 // ---------------------------------------------------------------------------
 struct BwdLayout {
     size_t ctrl, keys_a, keys_b, pay_a, pay_b, bag_scale, first_tile, tile_desc, hist, tile_heads, seg_start, seg_real,
+        local_offsets, tile_prefix,
         queue, queue_end, span_head, wave_heads, segs, multi_list, chunk_tasks, partials, total;
     int key_bytes;
     int lpr, cpl;       // lanes per row and chunks per lane of the update kernels
@@ -100,6 +101,10 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     L.multi_list = off;  off += align256((size_t)L.qslots * 4);
     L.chunk_tasks = off; off += align256((size_t)L.chunk_cap * sizeof(uint2));
     L.partials = off;    off += align256((size_t)L.chunk_cap * (size_t)D * 4);   // one chunk-sum slot per task
+    // emb_bag_forward_train_lengths: the offsets as sums within tiles, and the tiles' prefix sums
+    const size_t bags = (size_t)T * (size_t)B;
+    L.local_offsets = off; off += align256((bags + 1) * 8);
+    L.tile_prefix = off;   off += align256((bags / EMB_OFFSETS_TILE + 2) * 8);
     L.total = off;
     return L;
 }
@@ -112,22 +117,43 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
 // tiles of the sort (first_tile[t] = tiles of the tables before t; T + 1 entries)
 // and writes their descriptors.
 // T == 0 is passed when there are no records and the offsets are not to be read.
+// tile_prefix != NULL: `offsets` holds sums within tiles of EMB_OFFSETS_TILE lengths (emb_offsets_tile_sums);
+// the kernel first writes the exclusive prefix sums of the tile totals there (one entry per tile of the
+// T_all * B lengths, whatever T says) and reads every offset through emb_offset_at.
 __global__ __launch_bounds__(1024) void bwd_init_kernel(BwdCtrl *ctrl, const int64_t *__restrict__ offsets, int32_t T,
                                                          int64_t B, int64_t nnz, uint32_t *__restrict__ first_tile,
                                                          SortTile *__restrict__ desc, uint32_t tiles,
-                                                         int64_t *num_unique_out, uint32_t *status)
+                                                         int64_t *num_unique_out, uint32_t *status,
+                                                         int64_t *__restrict__ tile_prefix = nullptr,
+                                                         int64_t n_lengths = 0)
 {
     __shared__ uint32_t wave_sums[1024 / EMB_WAVE];
+    __shared__ int64_t wave_sums64[1024 / EMB_WAVE];
     __shared__ uint32_t bad;
     const int i = threadIdx.x;
     if (i == 0) bad = 0;
-    __syncthreads();
+    if (tile_prefix) {
+        const int64_t n_tiles = (n_lengths + EMB_OFFSETS_TILE - 1) / EMB_OFFSETS_TILE;
+        int64_t carry64 = 0;
+        for (int64_t k0 = 0; k0 < n_tiles; k0 += 1024) {
+            const int64_t k = k0 + i;
+            int64_t end = (k + 1) * EMB_OFFSETS_TILE;
+            if (end > n_lengths) end = n_lengths;
+            const int64_t v = k < n_tiles ? offsets[end] : 0;   // the tile's total stands at its end
+            int64_t total;
+            const int64_t inc = block_inclusive_scan<int64_t, 1024>(v, wave_sums64, total);
+            if (k < n_tiles) tile_prefix[k] = carry64 + inc - v;
+            carry64 += total;
+        }
+    }
+    __syncthreads();   // tile_prefix[] was written by this workgroup: visible to all of it now
     uint32_t carry = 0;
     for (int32_t t0 = 0; t0 < T; t0 += 1024) {
         const int32_t t = t0 + i;
         uint32_t c = 0;
         if (t < T) {
-            const int64_t s = offsets[(int64_t)t * B], e = offsets[(int64_t)(t + 1) * B];
+            const int64_t s = emb_offset_at(offsets, tile_prefix, (int64_t)t * B);
+            const int64_t e = emb_offset_at(offsets, tile_prefix, (int64_t)(t + 1) * B);
             const bool ok = s >= 0 && s <= e && e <= nnz && (t > 0 || s == 0) && (t < T - 1 || e == nnz);
             if (ok) c = (uint32_t)((e - s + SORT_TILE - 1) / SORT_TILE);
             else bad = 1;
@@ -158,7 +184,8 @@ __global__ __launch_bounds__(1024) void bwd_init_kernel(BwdCtrl *ctrl, const int
                 if (first_tile[mid] <= b) lo = mid;
                 else hi = mid;
             }
-            const int64_t s = offsets[(int64_t)lo * B], e = offsets[(int64_t)(lo + 1) * B];
+            const int64_t s = emb_offset_at(offsets, tile_prefix, (int64_t)lo * B);
+            const int64_t e = emb_offset_at(offsets, tile_prefix, (int64_t)(lo + 1) * B);
             const int64_t start = s + (int64_t)(b - first_tile[lo]) * SORT_TILE;
             const int64_t left = e - start;
             d.start = (uint32_t)start;
@@ -331,6 +358,9 @@ struct BwdArgs {
     const emb_table *tables_dev = nullptr;
     int32_t T = 0, D = 0, dtype = 0, mode = 0;
     const int64_t *rows = nullptr, *offsets = nullptr;
+    bool from_lengths = false;           // emb_bag_forward_train_lengths: the offsets are made on the way
+    const int32_t *lengths = nullptr;    // ... from these (NULL when there are no bags)
+    int64_t *offsets_out = nullptr;      // ... and written here
     int64_t B = 0, nnz = 0, total_rows = 0, max_rows = 0;
     int passes = 1;   // of the sort: enough for the bits of max_rows, the value that marks an invalid row
     const float *dout = nullptr;
@@ -599,8 +629,10 @@ __global__ __launch_bounds__(TRAIN_BLOCK) void bag_forward_train_kernel(
     const emb_table *__restrict__ tables, int32_t T, int64_t B, uint32_t blocks_per_table, int64_t nnz,
     const int64_t *__restrict__ raw, const int64_t *__restrict__ offsets, int32_t chunks_per_row, int32_t mode,
     float *__restrict__ out, int64_t *__restrict__ rows_out, KeyT *__restrict__ keys, uint32_t *__restrict__ pay,
-    float *__restrict__ bag_scale, BwdCtrl *ctrl, uint32_t *status)
+    float *__restrict__ bag_scale, BwdCtrl *ctrl, uint32_t *status, const int64_t *__restrict__ tile_prefix,
+    int64_t *__restrict__ offsets_out)
 {
+    // tile_prefix != NULL: `offsets` are sums within tiles (emb_offset_at) and the final offsets go to offsets_out
     constexpr int GROUPS = TRAIN_BLOCK / LPR;
     constexpr int F = ChunkAcc<BF16>::FLOATS;
     const uint32_t lb = emb_xcd_block(blockIdx.x, gridDim.x);
@@ -614,14 +646,18 @@ __global__ __launch_bounds__(TRAIN_BLOCK) void bag_forward_train_kernel(
     const emb_table tb = tables[t];
     if (live && l == 0) {
         // what bwd_keys_kernel does per bag: the scale of its gradient, or the abort of the backward
-        const int64_t s = offsets[bag], e = offsets[bag + 1];
+        const int64_t s = emb_offset_at(offsets, tile_prefix, bag), e = emb_offset_at(offsets, tile_prefix, bag + 1);
         if (s < 0 || e < s || e > nnz) atomicOr(&ctrl->abort, 1u);   // the lookup below flags the status word
         else bag_scale[bag] = (mode == EMB_POOL_MEAN && e > s) ? 1.0f / (float)(e - s) : 1.0f;
+        if (offsets_out) {
+            offsets_out[bag + 1] = e;
+            if (bag == 0) offsets_out[0] = 0;
+        }
     }
     TrainSource<KeyT> src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, tb.salt, tb.mod_magic,
                           (int64_t)chunks_per_row * 16, rows_out, keys, pay, (uint32_t)bag};
     gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, live, bag, l, nnz, raw, offsets, chunks_per_row, mode,
-                                            out + bag * ((int64_t)chunks_per_row * F), status);
+                                            out + bag * ((int64_t)chunks_per_row * F), status, tile_prefix);
 }
 
 template <typename KeyT, int LPR, int CPL, int UNROLL>
@@ -636,14 +672,19 @@ int launch_train(bool bf16, const BwdArgs &a, const BwdLayout &L, const int64_t 
     KeyT *keys = reinterpret_cast<KeyT *>(a.ws + L.keys_a);
     uint32_t *pay = reinterpret_cast<uint32_t *>(a.ws + L.pay_a);
     float *bag_scale = reinterpret_cast<float *>(a.ws + L.bag_scale);
+    // made from lengths: the offsets are the sums within tiles in the workspace plus the tiles' prefix sums
+    const int64_t *offsets = a.from_lengths ? reinterpret_cast<const int64_t *>(a.ws + L.local_offsets) : a.offsets;
+    const int64_t *tile_prefix = a.from_lengths ? reinterpret_cast<const int64_t *>(a.ws + L.tile_prefix) : nullptr;
     if (bf16)
         hipLaunchKernelGGL((bag_forward_train_kernel<LPR, CPL, UNROLL, true, KeyT>), dim3((unsigned)blocks),
                            dim3(TRAIN_BLOCK), 0, a.stream, a.tables_dev, a.T, a.B, (uint32_t)per_table, a.nnz, raw,
-                           a.offsets, chunks, a.mode, out, rows_out, keys, pay, bag_scale, ctrl, a.status);
+                           offsets, chunks, a.mode, out, rows_out, keys, pay, bag_scale, ctrl, a.status, tile_prefix,
+                           a.offsets_out);
     else
         hipLaunchKernelGGL((bag_forward_train_kernel<LPR, CPL, UNROLL, false, KeyT>), dim3((unsigned)blocks),
                            dim3(TRAIN_BLOCK), 0, a.stream, a.tables_dev, a.T, a.B, (uint32_t)per_table, a.nnz, raw,
-                           a.offsets, chunks, a.mode, out, rows_out, keys, pay, bag_scale, ctrl, a.status);
+                           offsets, chunks, a.mode, out, rows_out, keys, pay, bag_scale, ctrl, a.status, tile_prefix,
+                           a.offsets_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -654,8 +695,22 @@ int run_train_forward(const BwdArgs &a, const BwdLayout &L, const int64_t *raw, 
     BwdCtrl *ctrl = reinterpret_cast<BwdCtrl *>(a.ws + L.ctrl);
     uint32_t *first_tile = reinterpret_cast<uint32_t *>(a.ws + L.first_tile);
     SortTile *tile_desc = reinterpret_cast<SortTile *>(a.ws + L.tile_desc);
-    hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, a.stream, ctrl, a.offsets, a.nnz > 0 ? a.T : 0, a.B,
-                       a.nnz, first_tile, tile_desc, a.nnz > 0 ? (uint32_t)L.tiles : 0u, a.num_unique_out, a.status);
+    if (a.from_lengths) {
+        // bag offsets on the way: sums within tiles by one launch; the tiles' prefix sums by the
+        // single workgroup of bwd_init_kernel; the lookup adds the two (and writes the offsets out)
+        const int64_t n_lengths = (int64_t)a.T * a.B;
+        // (no bags: the offsets are the single entry 0, which the tile sums then write straight to the caller)
+        int64_t *local = n_lengths == 0 ? a.offsets_out : reinterpret_cast<int64_t *>(a.ws + L.local_offsets);
+        int64_t *tile_prefix = reinterpret_cast<int64_t *>(a.ws + L.tile_prefix);
+        const int rc = emb_offsets_tile_sums(a.lengths, n_lengths, local, a.status, a.stream);
+        if (rc != EMB_OK) return rc;
+        hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, a.stream, ctrl, local, a.nnz > 0 ? a.T : 0, a.B, a.nnz,
+                           first_tile, tile_desc, a.nnz > 0 ? (uint32_t)L.tiles : 0u, a.num_unique_out, a.status,
+                           tile_prefix, n_lengths);
+    } else {
+        hipLaunchKernelGGL(bwd_init_kernel, dim3(1), dim3(1024), 0, a.stream, ctrl, a.offsets, a.nnz > 0 ? a.T : 0, a.B,
+                           a.nnz, first_tile, tile_desc, a.nnz > 0 ? (uint32_t)L.tiles : 0u, a.num_unique_out, a.status);
+    }
     EMB_RETURN_IF_LAUNCH_FAILED();
     if (a.T == 0 || a.B == 0) return EMB_OK;
     const int chunks = a.D * emb_elem_size(a.dtype) / 16;
@@ -762,6 +817,34 @@ extern "C" int emb_bag_forward_train(const emb_table *tables_host, const emb_tab
     }
     a.mode = mode;
     a.offsets = offsets_dev;
+    a.num_unique_out = num_unique_out_dev;
+    a.status = status_dev;
+    const int64_t *raw = reinterpret_cast<const int64_t *>(raw_dev);
+    return L.key_bytes == 4 ? run_train_forward<uint32_t>(a, L, raw, out_dev, rows_out_dev)
+                            : run_train_forward<uint64_t>(a, L, raw, out_dev, rows_out_dev);
+}
+
+extern "C" int emb_bag_forward_train_lengths(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                                             int32_t D, int32_t dtype, const uint64_t *raw_dev,
+                                             const int32_t *lengths_dev, int64_t B, int64_t nnz, int32_t mode,
+                                             float *out_dev, int64_t *offsets_out_dev, int64_t *rows_out_dev,
+                                             void *workspace_dev, size_t workspace_bytes, int64_t *num_unique_out_dev,
+                                             uint32_t *status_dev, void *stream)
+{
+    if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
+    BwdArgs a;
+    BwdLayout L;
+    const int rc = bwd_plan(tables_host, tables_dev, T, D, dtype, B, nnz, workspace_dev, workspace_bytes, stream, a, L);
+    if (rc != EMB_OK) return rc;
+    if (!offsets_out_dev) return EMB_ERR_INVALID_ARG;
+    if (T > 0 && B > 0) {
+        if (!lengths_dev || !out_dev || (nnz > 0 && !raw_dev)) return EMB_ERR_INVALID_ARG;
+        if (!emb_aligned(out_dev, 16)) return EMB_ERR_INVALID_ARG;
+    }
+    a.mode = mode;
+    a.from_lengths = true;
+    a.lengths = lengths_dev;
+    a.offsets_out = offsets_out_dev;
     a.num_unique_out = num_unique_out_dev;
     a.status = status_dev;
     const int64_t *raw = reinterpret_cast<const int64_t *>(raw_dev);

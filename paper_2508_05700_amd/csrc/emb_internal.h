@@ -38,6 +38,22 @@ static inline int emb_check_tables(const emb_table *th, const emb_table *td, int
 
 static inline int emb_elem_size(int32_t dtype) { return dtype == EMB_F32 ? 4 : (dtype == EMB_BF16 ? 2 : 0); }
 
+// Bag offsets in two levels (offsets.hip): `local` holds, for entry i > 0, the sum of the lengths of
+// entry i's tile of EMB_OFFSETS_TILE lengths up to and including length i - 1 (entry 0 is 0), i.e. what
+// the first of emb_lengths_to_offsets' three launches leaves; the tile totals stand at the tile ends.
+// With the exclusive prefix sums of the tile totals, offsets[i] = local[i] + tile_prefix[(i - 1) / TILE].
+constexpr int EMB_OFFSETS_TILE = 4096;
+int emb_offsets_tile_sums(const int32_t *lengths_dev, int64_t n, int64_t *local_dev, uint32_t *status_dev,
+                          hipStream_t s);
+// offsets[i] from either form: tile_prefix == nullptr means `off` holds the final offsets.
+__device__ __forceinline__ int64_t emb_offset_at(const int64_t *__restrict__ off,
+                                                 const int64_t *__restrict__ tile_prefix, int64_t i)
+{
+    int64_t v = off[i];
+    if (tile_prefix && i > 0) v += tile_prefix[(i - 1) / EMB_OFFSETS_TILE];
+    return v;
+}
+
 // Quantised tables (quant.hip): shape check, and the pooled lookup emb_bag_forward hands over to.
 int emb_check_quant_shape(int32_t D, int32_t dtype);
 int emb_forward_quant(const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, const int64_t *rows_dev,

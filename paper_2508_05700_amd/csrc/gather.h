@@ -104,17 +104,19 @@ template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM = false, typename
 __device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t bag, int l, int64_t nnz,
                                                 const int64_t *__restrict__ rows,
                                                 const int64_t *__restrict__ offsets, int32_t chunks_per_row,
-                                                int32_t mode, float *__restrict__ out_row, uint32_t *status)
+                                                int32_t mode, float *__restrict__ out_row, uint32_t *status,
+                                                const int64_t *__restrict__ tile_prefix = nullptr)
 {
-    // `bag` indexes offsets; out_row is where the bag's pooled row goes (not touched unless live)
+    // `bag` indexes offsets; out_row is where the bag's pooled row goes (not touched unless live).
+    // tile_prefix: the offsets are sums within tiles and these are the tiles' prefix sums (emb_offset_at).
     constexpr int IPL = (UNROLL > LPR) ? UNROLL / LPR : 1;  // indices fetched per lane per batch
     constexpr int IB = IPL * LPR;                           // indices per batch
     static_assert(IB % UNROLL == 0, "index batch must be whole unroll groups");
 
     int64_t s = 0, e = 0;
     if (live) {
-        s = offsets[bag];
-        e = offsets[bag + 1];
+        s = emb_offset_at(offsets, tile_prefix, bag);
+        e = emb_offset_at(offsets, tile_prefix, bag + 1);
         if (s < 0 || e < s || e > nnz) {
             if (l == 0) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
             s = e = 0;

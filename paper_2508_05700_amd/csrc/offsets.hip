@@ -14,6 +14,7 @@ namespace {
 constexpr int SCAN_BLOCK = 1024;
 constexpr int SCAN_ITEMS = 4;
 constexpr int SCAN_TILE = SCAN_BLOCK * SCAN_ITEMS;
+static_assert(SCAN_TILE == EMB_OFFSETS_TILE, "callers of emb_offsets_tile_sums index the tile totals by this size");
 constexpr int SCAN_WAVES = SCAN_BLOCK / EMB_WAVE;
 
 __global__ __launch_bounds__(SCAN_BLOCK) void offsets_tile_scan_kernel(const int32_t *__restrict__ lengths, int64_t n,
@@ -84,6 +85,17 @@ __global__ __launch_bounds__(SCAN_BLOCK) void offsets_add_prefix_kernel(int64_t 
 }
 
 }  // namespace
+
+// The first launch alone: sums within tiles (for callers that add the tiles' prefix themselves).
+int emb_offsets_tile_sums(const int32_t *lengths_dev, int64_t n, int64_t *local_dev, uint32_t *status_dev, hipStream_t s)
+{
+    const int64_t tiles = n == 0 ? 1 : (n + SCAN_TILE - 1) / SCAN_TILE;
+    if (tiles > 0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(offsets_tile_scan_kernel, dim3((unsigned)tiles), dim3(SCAN_BLOCK), 0, s, lengths_dev, n, local_dev,
+                       status_dev);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    return EMB_OK;
+}
 
 extern "C" int emb_lengths_to_offsets(const int32_t *lengths_dev, int64_t n, int64_t *offsets_dev,
                                       uint32_t *status_dev, void *stream)

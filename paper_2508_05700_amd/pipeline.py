@@ -156,11 +156,10 @@ def run_step_overlapped(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf:
 
 
 def run_train_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers, stage_events=None) -> None:
-    """One pass of the whole path for a workload with a backward and raw IDs: bag offsets, the training
-    lookup (hashing, pooling and the backward's records in one kernel), sort, update."""
-    emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
-    emb.emb_bag_forward_train(tables, db.raw, buf.offsets, w.B, w.pool, buf.out, buf.workspace, None, buf.num_unique,
-                              buf.status)
+    """One pass of the whole path for a workload with a backward and raw IDs: the training lookup from
+    bag lengths and raw IDs (offsets, hashing, pooling and the backward's records), sort, update."""
+    emb.emb_bag_forward_train_lengths(tables, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets, buf.workspace, None,
+                                      buf.num_unique, buf.status)
     emb.emb_bag_backward_sort_prepared(tables, w.B, db.nnz, buf.workspace, buf.unique_keys, buf.unique_counts,
                                        buf.num_unique, buf.status, stage_events)
     emb.emb_bag_backward_update(tables, w.B, db.nnz, db.dout, w.lr, w.eps, buf.workspace, buf.num_unique,

@@ -211,6 +211,17 @@ def test_split_backward_and_helper_argument_errors(L):
     assert tr(*tr_args(dtype=3)) == UNSUPPORTED                       # quantised tables are not trained
     noacc = _tables(with_accum=False)
     assert tr(*tr_args(th=noacc.ctypes.data)) == UNSUPPORTED          # training needs accumulators
+    # the same lookup taking bag lengths: an array for the offsets it makes is required
+    trl = L.emb_bag_forward_train_lengths
+
+    def trl_args(**k):
+        return [d.ctypes.data, FAKE, 2, 64, 0, k.get("raw", FAKE), k.get("lengths", FAKE), 4, 8, k.get("mode", 1),
+                k.get("out", FAKE), k.get("offs", FAKE), None, k.get("ws", FAKE), k.get("wsb", need), None, None, None]
+    assert trl(*trl_args(offs=None)) == INVALID
+    assert trl(*trl_args(lengths=None)) == INVALID
+    assert trl(*trl_args(out=None)) == INVALID and trl(*trl_args(raw=None)) == INVALID
+    assert trl(*trl_args(mode=2)) == INVALID
+    assert trl(*trl_args(wsb=need - 256)) == WORKSPACE and trl(*trl_args(ws=None)) == WORKSPACE
     assert sp(d.ctypes.data, FAKE, 2, 64, 0, 4, 8, None, need, None, None, None, None, None, None) == WORKSPACE
     assert sp(d.ctypes.data, FAKE, 2, 3, 0, 4, 8, FAKE, need, None, None, None, None, None, None) == UNSUPPORTED
     # helpers: null arguments are refused before the runtime is touched

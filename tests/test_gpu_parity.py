@@ -791,6 +791,97 @@ def test_training_forward_equals_hashed_forward_plus_backward(D, dtype):
         assert np.array_equal(H.host_table(w3[t]), tables[t]) and float(a3[t].abs().sum()) == 0.0
 
 
+@pytest.mark.parametrize("T,B,D,dtype", [(3, 5000, 32, "f32"), (2, 4096, 16, "bf16"), (1, 1, 64, "f32"), (5, 1639, 8, "f32")])
+def test_training_forward_from_lengths_equals_offsets_then_training_forward(T, B, D, dtype):
+    # emb_bag_forward_train_lengths against emb_lengths_to_offsets + emb_bag_forward_train: offsets (also against the
+    # oracle), pooled output, row numbers, and after sort + update the tables, accumulators and row lists, bit for bit.
+    # The bags span several tiles of 4096 lengths and the tables do not start on tile boundaries.
+    rng = np.random.default_rng(4450 + T * B + D)
+    Rs = [int(r) for r in rng.integers(50, 30_000, size=T)]
+    salts = [int(x) for x in rng.integers(0, 1 << 62, size=T)]
+    tables, lengths, off, _ = H.random_case(rng, T, B, D, Rs, 12, dtype, scale=0.01)
+    lengths = lengths.copy()
+    lengths[0] = 5
+    if T * B > 4096:
+        lengths[4090:4100] = 0                                 # empty bags across a tile boundary
+        lengths[4096] = 77
+    off, _ = oracle.lengths_to_offsets(lengths)
+    nnz = int(off[-1])
+    raw = rng.integers(0, 1 << 64, size=max(nnz, 1), dtype=np.uint64)[:nnz]
+    raw[: nnz // 4] = raw[0]                                   # long runs
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+
+    def fresh():
+        w = [H.dev(t) for t in tables]
+        acc = [torch.zeros(R, dtype=torch.float32, device=H.DEV) for R in Rs]
+        return emb.TableSet(w, D, dtype, accum=acc, salts=salts, device=torch.device(H.DEV)), w, acc
+
+    def route(from_lengths, lengths_np, nnz_arg):
+        ts, w, a = fresh()
+        ws = torch.full((emb.emb_bag_backward_workspace_bytes(T, B, nnz_arg, ts.total_rows, D, dtype),), 0xA5,
+                        dtype=torch.uint8, device=H.DEV)
+        out = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+        rows = torch.full((max(nnz_arg, 1),), -1, dtype=torch.int64, device=H.DEV)[:nnz_arg]
+        offs = torch.full((T * B + 1,), -9, dtype=torch.int64, device=H.DEV)
+        uk = torch.full((max(nnz_arg, 1),), -7, dtype=torch.int64, device=H.DEV)
+        uc = torch.full((max(nnz_arg, 1),), -7, dtype=torch.int32, device=H.DEV)
+        nu = torch.full((1,), -7, dtype=torch.int64, device=H.DEV)
+        st = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+        raw_d = H.dev(raw[:nnz_arg]) if nnz_arg else torch.empty(0, dtype=torch.int64, device=H.DEV)
+        len_d = H.dev(lengths_np)
+        if from_lengths:
+            emb.emb_bag_forward_train_lengths(ts, raw_d, len_d, B, "mean", out, offs, ws, rows, nu, st)
+        else:
+            emb.emb_lengths_to_offsets(len_d, offs, st)
+            emb.emb_bag_forward_train(ts, raw_d, offs, B, "mean", out, ws, rows, nu, st)
+        emb.emb_bag_backward_sort_prepared(ts, B, nnz_arg, ws, uk, uc, nu, st)
+        emb.emb_bag_backward_update(ts, B, nnz_arg, H.dev(dout), 0.01, 1e-8, ws, nu, None, H.side_stream())
+        torch.cuda.synchronize()
+        return dict(out=out, rows=rows, offs=offs, uk=uk, uc=uc, U=int(nu.item()), st=int(st.item()), w=w, a=a)
+
+    a, b = route(True, lengths, nnz), route(False, lengths, nnz)
+    assert a["st"] == b["st"] == 0 and a["U"] == b["U"] > 0
+    assert np.array_equal(a["offs"].cpu().numpy(), off) and torch.equal(a["offs"], b["offs"])
+    assert torch.equal(a["out"], b["out"]) and torch.equal(a["rows"], b["rows"])
+    assert torch.equal(a["uk"][:a["U"]], b["uk"][:b["U"]]) and torch.equal(a["uc"][:a["U"]], b["uc"][:b["U"]])
+    for t in range(T):
+        assert torch.equal(a["w"][t], b["w"][t]) and torch.equal(a["a"][t], b["a"][t])
+    rows_ref = np.concatenate([oracle.hash_ids(raw[off[t * B]:off[(t + 1) * B]], salts[t], Rs[t]) for t in range(T)])
+    assert np.array_equal(a["rows"].cpu().numpy(), rows_ref)
+    ref, absum, _ = oracle.bag_forward(tables, dtype, rows_ref, off, B, "mean")
+    H.assert_pooled_close(a["out"].cpu().numpy(), ref, absum, what="training forward from lengths")
+    if T * B < 10:
+        return
+    # negative lengths count as 0 and are flagged, wherever they stand; both routes agree
+    neg = lengths.copy()
+    where = rng.choice(T * B, size=5, replace=False)
+    neg[where] = -3
+    off_n, st_n = oracle.lengths_to_offsets(neg)
+    a, b = route(True, neg, int(off_n[-1])), route(False, neg, int(off_n[-1]))
+    assert a["st"] == b["st"] == st_n == emb.STATUS_BAD_OFFSETS
+    assert np.array_equal(a["offs"].cpu().numpy(), off_n) and torch.equal(a["out"], b["out"]) and a["U"] == b["U"]
+    for t in range(T):
+        assert torch.equal(a["w"][t], b["w"][t]) and torch.equal(a["a"][t], b["a"][t])
+    # an nnz smaller than the sum of the lengths: flagged, the backward does nothing, as with offsets that end past nnz
+    a, b = route(True, lengths, nnz - 1), route(False, lengths, nnz - 1)
+    assert a["st"] & emb.STATUS_BAD_OFFSETS and b["st"] & emb.STATUS_BAD_OFFSETS and a["U"] == b["U"] == 0
+    for t in range(T):
+        assert np.array_equal(H.host_table(a["w"][t]), tables[t]) and float(a["a"][t].abs().sum()) == 0.0
+
+
+def test_training_forward_from_lengths_without_bags():
+    ts = emb.TableSet([torch.zeros((5, 16), dtype=torch.float32, device=H.DEV)], 16, "f32",
+                      accum=[torch.zeros(5, dtype=torch.float32, device=H.DEV)], device=torch.device(H.DEV))
+    ws = torch.empty(emb.emb_bag_backward_workspace_bytes(1, 0, 0, 5, 16, "f32"), dtype=torch.uint8, device=H.DEV)
+    offs = torch.full((1,), -9, dtype=torch.int64, device=H.DEV)
+    st = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_train_lengths(ts, torch.empty(0, dtype=torch.int64, device=H.DEV),
+                                      torch.empty(0, dtype=torch.int32, device=H.DEV), 0, "sum",
+                                      torch.empty((1, 0, 16), dtype=torch.float32, device=H.DEV), offs, ws, None, None, st)
+    torch.cuda.synchronize()
+    assert offs.item() == 0 and st.item() == 0
+
+
 def test_many_tables_take_the_paths_without_lds_staging():
     # more tables than the kernels stage in LDS (table boundaries in the hashing kernel, the table
     # directory in the update kernels): 1100 small tables, 3 bags each
