@@ -414,9 +414,9 @@ int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_rows, int32
                                   void *stream);
 
 /* The rows a hosted table's lookups miss in the cache, fetched ahead of the
- * lookups (Section 3.4: the fetch from CPU memory is started as early as
- * possible and runs beside the rest of the request; Section 3.3 for the hosted
- * table).  rows_dev (i64[nnz]) holds the lookups of one batch or of SEVERAL
+ * lookups (Section 3.4: the fetch from CPU memory starts at the first moment
+ * the ids are known and runs beside the rest of the request; Section 3.3 for
+ * the hosted table).  rows_dev (i64[nnz]) holds the lookups of one batch or of SEVERAL
  * batches one after the other: one launch then has the misses of all of them
  * in flight over the link together.  Every lookup is resolved (bounds check,
  * cache probe against cache_index_dev / num_hot as emb_cache_build left them);

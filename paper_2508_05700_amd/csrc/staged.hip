@@ -1,7 +1,7 @@
 // Host-resident table with an HBM hot-row cache (paper Section 3.3), the part of it
-// that Section 3.4 asks for: the rows that have to come from CPU memory are fetched as
-// early as possible, beside whatever else the request is doing, and the lookup itself
-// then reads HBM only.
+// that Section 3.4 is about: the rows that have to come from CPU memory are fetched
+// ahead of the lookup, while the request is still busy with other things, and the
+// lookup itself then reads HBM only.
 //
 //   emb_cache_stage_misses   takes the lookups of one or SEVERAL batches at once,
 //       resolves every lookup (hash, bounds, cache probe), copies every missed row
