@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "7bdf3eb9567c85ca",
+    "sources": "30d3e41e4b067810",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (178074.2, 67589.1), "update_kernel": (240632.1, 324000.5)},
-        "3b": {"bag_forward_train_kernel": (95254.2, 82186.6), "update_kernel": (170624.6, 224664.7)},
-        "2": {"bag_forward_hashed_kernel": (176745.1, 32768.0), "bag_forward_kernel": (177990.6, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338149.8, 32768.0), "bag_forward_kernel": (338143.6, 32768.0)},
-        "2un": {"bag_forward_kernel": (346112.5, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (124458.1, 32801.7)},
-        "2uq4": {"bag_forward_quant_kernel": (233562.2, 32880.6)},
-        "2uq4r": {"bag_forward_quant_kernel": (191613.4, 32845.8)},
-        "4": {"bag_forward_hashed_kernel": (52663.5, 8192.0)},
+        "3": {"bag_forward_train_kernel": (176782.0, 69135.9), "update_kernel": (240601.4, 323999.4)},
+        "3b": {"bag_forward_train_kernel": (94079.4, 81871.7), "update_kernel": (170524.9, 224747.6)},
+        "2": {"bag_forward_hashed_kernel": (176687.5, 32768.0), "bag_forward_kernel": (177962.3, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338148.3, 32768.0), "bag_forward_kernel": (338144.3, 32768.0)},
+        "2un": {"bag_forward_kernel": (346115.3, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (124427.8, 32801.8)},
+        "2uq4": {"bag_forward_quant_kernel": (233541.5, 32887.9)},
+        "2uq4r": {"bag_forward_quant_kernel": (191613.3, 32847.7)},
+        "4": {"bag_forward_hashed_kernel": (52640.8, 8192.0)},
     },
 }
 
