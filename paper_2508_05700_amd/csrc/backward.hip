@@ -646,7 +646,8 @@ __global__ __launch_bounds__(TRAIN_BLOCK) void bag_forward_train_kernel(
     const emb_table tb = tables[t];
     if (live && l == 0) {
         // what bwd_keys_kernel does per bag: the scale of its gradient, or the abort of the backward
-        const int64_t s = emb_offset_at(offsets, tile_prefix, bag), e = emb_offset_at(offsets, tile_prefix, bag + 1);
+        int64_t s, e;
+        emb_bag_bounds(offsets, tile_prefix, bag, s, e);
         if (s < 0 || e < s || e > nnz) atomicOr(&ctrl->abort, 1u);   // the lookup below flags the status word
         else bag_scale[bag] = (mode == EMB_POOL_MEAN && e > s) ? 1.0f / (float)(e - s) : 1.0f;
         if (offsets_out) {

@@ -53,6 +53,19 @@ __device__ __forceinline__ int64_t emb_offset_at(const int64_t *__restrict__ off
     if (tile_prefix && i > 0) v += tile_prefix[(i - 1) / EMB_OFFSETS_TILE];
     return v;
 }
+// Both bounds of bag `bag`, with the loads independent of each other (one memory round trip).
+__device__ __forceinline__ void emb_bag_bounds(const int64_t *__restrict__ off, const int64_t *__restrict__ tile_prefix,
+                                               int64_t bag, int64_t &s, int64_t &e)
+{
+    s = off[bag];
+    e = off[bag + 1];
+    if (tile_prefix) {   // uniform
+        const int64_t ps = tile_prefix[(bag > 0 ? bag - 1 : 0) / EMB_OFFSETS_TILE];
+        const int64_t pe = tile_prefix[bag / EMB_OFFSETS_TILE];
+        s += bag > 0 ? ps : 0;
+        e += pe;
+    }
+}
 
 // Quantised tables (quant.hip): shape check, and the pooled lookup emb_bag_forward hands over to.
 int emb_check_quant_shape(int32_t D, int32_t dtype);

@@ -115,8 +115,7 @@ __device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t 
 
     int64_t s = 0, e = 0;
     if (live) {
-        s = emb_offset_at(offsets, tile_prefix, bag);
-        e = emb_offset_at(offsets, tile_prefix, bag + 1);
+        emb_bag_bounds(offsets, tile_prefix, bag, s, e);
         if (s < 0 || e < s || e > nnz) {
             if (l == 0) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
             s = e = 0;
