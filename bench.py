@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "30d3e41e4b067810",
+    "sources": "b4172714e7b2c7f2",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (176782.0, 69135.9), "update_kernel": (240601.4, 323999.4)},
-        "3b": {"bag_forward_train_kernel": (94079.4, 81871.7), "update_kernel": (170524.9, 224747.6)},
-        "2": {"bag_forward_hashed_kernel": (176687.5, 32768.0), "bag_forward_kernel": (177962.3, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338148.3, 32768.0), "bag_forward_kernel": (338144.3, 32768.0)},
-        "2un": {"bag_forward_kernel": (346115.3, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (124427.8, 32801.8)},
-        "2uq4": {"bag_forward_quant_kernel": (233541.5, 32887.9)},
-        "2uq4r": {"bag_forward_quant_kernel": (191613.3, 32847.7)},
-        "4": {"bag_forward_hashed_kernel": (52640.8, 8192.0)},
+        "3": {"bag_forward_train_kernel": (177567.6, 69043.5), "update_kernel": (240569.9, 324000.4)},
+        "3b": {"bag_forward_train_kernel": (94813.2, 83125.0), "update_kernel": (170570.3, 224704.3)},
+        "2": {"bag_forward_hashed_kernel": (176140.9, 32768.0), "bag_forward_kernel": (177242.5, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338142.9, 32768.0), "bag_forward_kernel": (338144.9, 32768.0)},
+        "2un": {"bag_forward_kernel": (346031.1, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (124459.3, 32800.8)},
+        "2uq4": {"bag_forward_quant_kernel": (233543.3, 32889.6)},
+        "2uq4r": {"bag_forward_quant_kernel": (191622.9, 32846.5)},
+        "4": {"bag_forward_hashed_kernel": (52645.4, 8192.0)},
     },
 }
 
