@@ -1792,13 +1792,13 @@ def _graph_inputs(rng, T, B, max_len, Rs):
     return lengths, raw
 
 
-@pytest.mark.parametrize("side", [False, True])
-def test_a_captured_training_step_replays_like_eager_calls(side):
+@pytest.mark.parametrize("side,from_lengths", [(False, False), (True, False), (True, True)])
+def test_a_captured_training_step_replays_like_eager_calls(side, from_lengths):
     # offsets + training lookup + sort + update captured once into a graph, then replayed on new inputs
     # written into the same buffers (the number of lookups is part of the captured arguments, so every batch
     # here has the same total); each replay is compared with the oracle, with eager work and
     # synchronisations between the replays.
-    rng = np.random.default_rng(9000 + side)
+    rng = np.random.default_rng(9000 + side + 2 * from_lengths)
     T, B, D = 3, 400, 64
     Rs = [5000, 300, 20_000]
     tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
@@ -1826,8 +1826,11 @@ def test_a_captured_training_step_replays_like_eager_calls(side):
     sd = H.side_stream() if side else None
 
     def step():
-        emb.emb_lengths_to_offsets(lengths_d, offsets_d, status)
-        emb.emb_bag_forward_train(ts, raw_d, offsets_d, B, "mean", out_d, ws, None, nu, status)
+        if from_lengths:
+            emb.emb_bag_forward_train_lengths(ts, raw_d, lengths_d, B, "mean", out_d, offsets_d, ws, None, nu, status)
+        else:
+            emb.emb_lengths_to_offsets(lengths_d, offsets_d, status)
+            emb.emb_bag_forward_train(ts, raw_d, offsets_d, B, "mean", out_d, ws, None, nu, status)
         emb.emb_bag_backward_sort_prepared(ts, B, nnz, ws, None, None, nu, status, None)
         emb.emb_bag_backward_update(ts, B, nnz, dout_d, 0.01, 1e-8, ws, nu, None, sd)
 
@@ -1843,6 +1846,7 @@ def test_a_captured_training_step_replays_like_eager_calls(side):
         ref_out, absum, st = oracle.bag_forward(ref_tables, "f32", rows, off, B, "mean")
         r = oracle.bag_backward_rowwise_adagrad(ref_tables, ref_acc, "f32", rows, off, B, "mean", b[2], 0.01, 1e-8)
         assert st == 0 and r["status"] == 0 and status.item() == 0
+        assert np.array_equal(offsets_d.cpu().numpy(), off)
         H.assert_pooled_close(out_d.cpu().numpy(), ref_out, absum, what=what + " forward")
         assert int(nu.item()) == r["unique_keys"].size
         for t in range(T):
