@@ -869,6 +869,35 @@ def test_training_forward_from_lengths_equals_offsets_then_training_forward(T, B
         assert np.array_equal(H.host_table(a["w"][t]), tables[t]) and float(a["a"][t].abs().sum()) == 0.0
 
 
+def test_training_forward_from_lengths_with_more_than_a_thousand_tiles_of_bags():
+    # 4.2 M bags are more than 1024 tiles of 4096 lengths: the prefix sums over the tile totals take several rounds
+    rng = np.random.default_rng(4490)
+    T, B, D, R = 1, 4096 * 1030 + 17, 4, 5000
+    lengths = (rng.random(T * B) < 0.2).astype(np.int32)
+    lengths[[0, 4096 * 1024 - 1, 4096 * 1024, T * B - 1]] = [3, 2, 5, 4]
+    off, _ = oracle.lengths_to_offsets(lengths)
+    nnz = int(off[-1])
+    raw = rng.integers(0, 1 << 64, size=nnz, dtype=np.uint64)
+    table = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+    w = H.dev(table)
+    acc = torch.zeros(R, dtype=torch.float32, device=H.DEV)
+    ts = emb.TableSet([w], D, "f32", accum=[acc], salts=[9], device=torch.device(H.DEV))
+    ws = torch.empty(emb.emb_bag_backward_workspace_bytes(T, B, nnz, R, D, "f32"), dtype=torch.uint8, device=H.DEV)
+    out = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    offs = torch.full((T * B + 1,), -9, dtype=torch.int64, device=H.DEV)
+    nu = torch.zeros(1, dtype=torch.int64, device=H.DEV)
+    st = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_train_lengths(ts, H.dev(raw), H.dev(lengths), B, "sum", out, offs, ws, None, nu, st)
+    uk = torch.empty(nnz, dtype=torch.int64, device=H.DEV)
+    emb.emb_bag_backward_sort_prepared(ts, B, nnz, ws, uk, None, nu, st)
+    torch.cuda.synchronize()
+    assert st.item() == 0 and np.array_equal(offs.cpu().numpy(), off)
+    rows = oracle.hash_ids(raw, 9, R)
+    ref, absum, _ = oracle.bag_forward([table], "f32", rows, off, B, "sum")
+    H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="lookup over 4.2 M bags")
+    assert np.array_equal(uk[:int(nu.item())].cpu().numpy(), np.unique(rows))
+
+
 def test_training_forward_from_lengths_without_bags():
     ts = emb.TableSet([torch.zeros((5, 16), dtype=torch.float32, device=H.DEV)], 16, "f32",
                       accum=[torch.zeros(5, dtype=torch.float32, device=H.DEV)], device=torch.device(H.DEV))
