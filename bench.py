@@ -807,8 +807,8 @@ def main() -> int:
     ap.add_argument("--no-fused-forward", action="store_true",
                     help="hash the IDs in a kernel of their own instead of inside the forward lookup")
     ap.add_argument("--separate-offsets", action="store_true",
-                    help="training step: bag offsets by emb_lengths_to_offsets (three launches) before the lookup, "
-                         "instead of inside emb_bag_forward_train_lengths")
+                    help="bag offsets by emb_lengths_to_offsets (three launches) before the lookup, instead of inside "
+                         "emb_bag_forward_train_lengths / emb_bag_forward_hashed_lengths")
     ap.add_argument("--overlap-sort", action="store_true",
                     help="enqueue the backward's sort on a second stream beside the forward (measured: no gain "
                          "here, the forward saturates HBM and the sort's small kernels only get slower)")
@@ -867,10 +867,15 @@ def main() -> int:
 
     train_route = fused and w.backward     # the lookup also writes the backward's records
     offsets_inside = train_route and not args.separate_offsets   # ... and makes the bag offsets on the way
+    # forward-only with hashing inside the lookup: the lookup also takes the bag lengths (up to 2^20 bags)
+    lengths_route = (fused and not w.backward and not args.separate_offsets and not args.versioned
+                     and w.T * w.B <= (1 << 20))
+    off_scratch = (torch.empty(emb.emb_offsets_scratch_bytes(w.T * w.B), dtype=torch.uint8, device=dev)
+                   if lengths_route else None)
 
     def do_index(db):
         """Bag offsets, and the hashing unless it is fused into the forward.  Returns the rows (or None)."""
-        if offsets_inside:
+        if offsets_inside or lengths_route:
             return None
         if fused:
             emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
@@ -902,6 +907,10 @@ def main() -> int:
             emb.emb_version_latch(ver_handle, w.T, ver_latch, buf.status)
             emb.emb_bag_forward_latched_hashed(ver_latch, w.T, w.D, w.dtype, db.raw, buf.offsets, w.B, w.pool, buf.out,
                                                buf.status, streaming=w.streaming)
+            return None
+        if lengths_route:
+            emb.emb_bag_forward_hashed_lengths(tabs.set, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets,
+                                               off_scratch, None, buf.status, streaming=w.streaming)
             return None
         if fused:
             rows = buf.rows[:db.nnz]
@@ -1034,6 +1043,11 @@ def main() -> int:
             fwd_extra = nnz_i * 8 + bags * 4          # one 8-byte record per lookup, one scale per bag
         index_entry = entry("offsets_* (index stage, 3 launches; hashing is done inside the forward)", ms_index,
                             bags * 12, "12 B per bag (length in, offset out)")
+        if lengths_route:
+            fwd_name = "offsets_tile_scan + bag_forward_hashed_kernel (bag offsets + hash + gather-pool)"
+            fwd_extra += bags * 28                   # length in, sum within the tile out and in, offset out
+            index_entry = entry("(index stage: the bag offsets are made inside the lookup)", ms_index, 1,
+                                "not priced: counted under the lookup")
         if offsets_inside:
             fwd_name = ("offsets_tile_scan + bwd_init + bag_forward_train_kernel (bag offsets + hash + gather-pool + "
                         "the backward's records)")

@@ -267,6 +267,27 @@ int emb_bag_forward_hashed(const emb_table *tables_host, const emb_table *tables
                            float *out_dev, int64_t *rows_out_dev, uint32_t *status_dev,
                            void *stream);
 
+/* emb_lengths_to_offsets and emb_bag_forward_hashed in one call: the serving
+ * form of "bag lengths and raw IDs in, pooled embeddings out" (Sections 2.2,
+ * 3.4).  Takes the T*B bag lengths instead of offsets and writes the offsets
+ * (i64[T*B+1]) to offsets_out_dev.  Two launches instead of four: the sums of
+ * the lengths within tiles of 4096 go to scratch_dev (caller-owned,
+ * emb_offsets_scratch_bytes(T*B) bytes, 16-byte aligned, free again once the
+ * call's work has run), and every workgroup of the lookup adds the prefix sums
+ * of the tile totals itself.  Pooled output, offsets, row numbers and status
+ * bits are bit-identical to the two calls.  EMB_ERR_UNSUPPORTED for more than
+ * 1 048 576 bags (256 tiles: use the two calls) and for quantised tables.
+ * A negative length counts as 0 and sets EMB_STATUS_BAD_OFFSETS; nnz must be
+ * the sum of the lengths.  offsets_out_dev must not overlap lengths_dev or
+ * scratch_dev.  mode may carry EMB_ROWS_STREAMING. */
+size_t emb_offsets_scratch_bytes(int64_t num_bags_total);
+int emb_bag_forward_hashed_lengths(const emb_table *tables_host, const emb_table *tables_dev,
+                                   int32_t T, int32_t D, int32_t dtype, const uint64_t *raw_dev,
+                                   const int32_t *lengths_dev, int64_t B, int64_t nnz,
+                                   int32_t mode, float *out_dev, int64_t *offsets_out_dev,
+                                   int64_t *rows_out_dev, void *scratch_dev, size_t scratch_bytes,
+                                   uint32_t *status_dev, void *stream);
+
 /* Shape of one table for emb_bag_forward_mixed.  The caller fills D, dtype,
  * out_offset and out_stride; emb_table_shapes_init derives the rest for a batch
  * of B bags per table; like emb_table, the array is passed in host and in

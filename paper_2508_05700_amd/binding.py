@@ -45,7 +45,7 @@ assert SHAPE_DESC.itemsize == 32
 EXPORTS = [
     "emb_status_string", "emb_tables_init", "emb_hash_ids", "emb_hash_ids_tables", "emb_lengths_to_offsets",
     "emb_bag_forward", "emb_bag_forward_hashed", "emb_table_shapes_init", "emb_bag_forward_mixed", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
-    "emb_bag_backward_sort", "emb_bag_backward_update", "emb_bag_forward_train", "emb_bag_forward_train_lengths", "emb_bag_backward_sort_prepared", "emb_row_bytes", "emb_quantize_rows",
+    "emb_bag_backward_sort", "emb_bag_backward_update", "emb_bag_forward_train", "emb_bag_forward_train_lengths", "emb_offsets_scratch_bytes", "emb_bag_forward_hashed_lengths", "emb_bag_backward_sort_prepared", "emb_row_bytes", "emb_quantize_rows",
     "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_host_device_pointer",
@@ -116,6 +116,10 @@ def lib() -> C.CDLL:
     L.emb_bag_backward_sort.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, sz, vp, vp, vp, vp, vp, vp]
     L.emb_bag_forward_train.restype = C.c_int
     L.emb_bag_forward_train.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, sz, vp, vp, vp]
+    L.emb_offsets_scratch_bytes.restype = sz
+    L.emb_offsets_scratch_bytes.argtypes = [i64]
+    L.emb_bag_forward_hashed_lengths.restype = C.c_int
+    L.emb_bag_forward_hashed_lengths.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp, sz, vp, vp]
     L.emb_bag_forward_train_lengths.restype = C.c_int
     L.emb_bag_forward_train_lengths.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp, sz, vp, vp, vp]
     L.emb_bag_backward_sort_prepared.restype = C.c_int
@@ -339,6 +343,30 @@ def emb_bag_forward_hashed(tables: TableSet, raw: torch.Tensor, offsets: torch.T
         _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode] | (ROWS_STREAMING if streaming else 0),
         _ptr(out, torch.float32, "out"), _ptr(rows_out, torch.int64, "rows_out"), _ptr(status, torch.int32, "status"),
         _stream()))
+
+
+def emb_offsets_scratch_bytes(num_bags_total: int) -> int:
+    return int(lib().emb_offsets_scratch_bytes(int(num_bags_total)))
+
+
+def emb_bag_forward_hashed_lengths(tables: TableSet, raw: torch.Tensor, lengths: torch.Tensor, B: int, mode: str,
+                                   out: torch.Tensor, offsets_out: torch.Tensor, scratch: torch.Tensor,
+                                   rows_out: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None,
+                                   streaming: bool = False) -> None:
+    """``emb_lengths_to_offsets`` + ``emb_bag_forward_hashed`` in one call: takes the bag lengths, writes the
+    offsets; ``scratch`` holds ``emb_offsets_scratch_bytes(T * B)`` bytes."""
+    nnz = raw.numel()
+    n = tables.T * B
+    if lengths.numel() != n or offsets_out.numel() != n + 1 or out.numel() != n * tables.D:
+        raise TypeError("shape mismatch")
+    if rows_out is not None and rows_out.numel() != nnz:
+        raise TypeError("rows_out must have as many elements as raw")
+    _check("emb_bag_forward_hashed_lengths", lib().emb_bag_forward_hashed_lengths(
+        tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype], _ptr(raw, _U64, "raw"),
+        _ptr(lengths, torch.int32, "lengths") if n else None, int(B), nnz,
+        POOL[mode] | (ROWS_STREAMING if streaming else 0), _ptr(out, torch.float32, "out"),
+        _ptr(offsets_out, torch.int64, "offsets_out"), _ptr(rows_out, torch.int64, "rows_out"),
+        _ptr(scratch, torch.uint8, "scratch"), scratch.numel(), _ptr(status, torch.int32, "status"), _stream()))
 
 
 class MixedTables:

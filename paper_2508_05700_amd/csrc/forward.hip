@@ -9,6 +9,7 @@
 // cached lookup.
 #include "emb_internal.h"
 #include "gather.h"
+#include "scan.h"
 #include "u64mod.h"
 
 namespace {
@@ -47,15 +48,36 @@ struct HashedTableSource {
     }
 };
 
-template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM>
+// TWO_LEVEL (emb_bag_forward_hashed_lengths): `offsets` holds the sums of the bag lengths within tiles of
+// EMB_OFFSETS_TILE lengths (emb_offsets_tile_sums); every workgroup takes the exclusive prefix sums of the
+// tile totals itself (at most FWD_BLOCK tiles: one load per thread and a scan in LDS, beside the loads of
+// its bags' bounds) and the final offsets are written to offsets_out.
+template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM, bool TWO_LEVEL = false>
 __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb_table *__restrict__ tables, int32_t T,
                                                                        int64_t B, uint32_t blocks_per_table,
                                                                        int64_t nnz, const int64_t *__restrict__ raw,
                                                                        const int64_t *__restrict__ offsets,
                                                                        int32_t chunks_per_row, int32_t mode,
                                                                        float *__restrict__ out,
-                                                                       int64_t *__restrict__ rows_out, uint32_t *status)
+                                                                       int64_t *__restrict__ rows_out, uint32_t *status,
+                                                                       int64_t *__restrict__ offsets_out = nullptr)
 {
+    __shared__ int64_t tile_prefix[TWO_LEVEL ? FWD_BLOCK : 1];
+    __shared__ int64_t wave_sums[FWD_BLOCK / EMB_WAVE];
+    const int64_t n_bags = (int64_t)T * B;
+    const int64_t n_tiles = (n_bags + EMB_OFFSETS_TILE - 1) / EMB_OFFSETS_TILE;   // <= FWD_BLOCK (checked by the host)
+    const bool in_wave = TWO_LEVEL && n_tiles <= EMB_WAVE;   // uniform: a wavefront keeps the prefix sums in registers
+    if (TWO_LEVEL && !in_wave) {
+        const int64_t n = n_bags;
+        const int64_t k = threadIdx.x;
+        int64_t end = (k + 1) * EMB_OFFSETS_TILE;
+        if (end > n) end = n;
+        const int64_t v = k < n_tiles ? offsets[end] : 0;   // a tile's total stands at its end
+        int64_t total;
+        const int64_t inc = block_inclusive_scan<int64_t, FWD_BLOCK>(v, wave_sums, total);
+        tile_prefix[k] = inc - v;
+        __syncthreads();
+    }
     constexpr int GROUPS = FWD_BLOCK / LPR;
     const uint32_t lb = emb_xcd_block(blockIdx.x, gridDim.x);
     const uint32_t t_raw = lb / blocks_per_table;
@@ -68,8 +90,38 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb
                           (int64_t)chunks_per_row * 16, rows_out};
     constexpr int F = ChunkAcc<BF16>::FLOATS;
     const int64_t bag = (int64_t)t * B + b;
+    if (in_wave) {
+        // Up to 64 tiles of lengths: lane k of every wavefront loads tile k's total, a scan over the
+        // wavefront gives the tiles' prefix sums, and a bag fetches the two it needs by lane shuffles.
+        // The totals and the bag's own two sums are requested together; no LDS, no barrier.  All lanes
+        // take part in the shuffles (a bag that is not live stands in as bag 0).
+        const int lane = threadIdx.x & (EMB_WAVE - 1);
+        int64_t end = (int64_t)(lane + 1) * EMB_OFFSETS_TILE;
+        if (end > n_bags) end = n_bags;
+        const int64_t total = lane < n_tiles ? offsets[end] : 0;
+        const int64_t bc = b < B ? bag : 0;
+        const int64_t a0 = offsets[bc], a1 = offsets[bc + 1];
+        const int64_t prefix = wave_inclusive_scan(total) - total;
+        const int64_t ps = shfl_i64(prefix, (int)((bc > 0 ? bc - 1 : 0) / EMB_OFFSETS_TILE), EMB_WAVE);
+        const int64_t pe = shfl_i64(prefix, (int)(bc / EMB_OFFSETS_TILE), EMB_WAVE);
+        const int64_t s = a0 + (bc > 0 ? ps : 0), e = a1 + pe;
+        if (b < B && l == 0) {
+            offsets_out[bag + 1] = e;
+            if (bag == 0) offsets_out[0] = 0;
+        }
+        gather_pool_range<LPR, CPL, UNROLL, BF16, STREAM>(src, b < B, s, e, l, nnz, raw, chunks_per_row, mode,
+                                                          out + bag * ((int64_t)chunks_per_row * F), status);
+        return;
+    }
+    if (TWO_LEVEL && b < B && l == 0) {
+        int64_t s, e;
+        emb_bag_bounds(offsets, tile_prefix, bag, s, e);
+        offsets_out[bag + 1] = e;
+        if (bag == 0) offsets_out[0] = 0;
+    }
     gather_pool_bag<LPR, CPL, UNROLL, BF16, STREAM>(src, b < B, bag, l, nnz, raw, offsets, chunks_per_row, mode,
-                                            out + bag * ((int64_t)chunks_per_row * F), status);
+                                            out + bag * ((int64_t)chunks_per_row * F), status,
+                                            TWO_LEVEL ? tile_prefix : nullptr);
 }
 
 template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM>
@@ -99,9 +151,12 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_kernel(const emb_table 
 template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM>
 void launch_forward_variant(dim3 grid, hipStream_t s, const emb_table *tables, int32_t T, int64_t B, uint32_t per_table,
                             int64_t nnz, const int64_t *rows, const int64_t *offsets, int32_t chunks, int32_t mode,
-                            float *out, uint32_t *status, bool hashed, int64_t *rows_out)
+                            float *out, uint32_t *status, bool hashed, int64_t *rows_out, int64_t *offsets_out)
 {
-    if (hashed)
+    if (offsets_out)   // hashed, offsets in two levels
+        hipLaunchKernelGGL((bag_forward_hashed_kernel<LPR, CPL, UNROLL, BF16, STREAM, true>), grid, dim3(FWD_BLOCK), 0, s,
+                           tables, T, B, per_table, nnz, rows, offsets, chunks, mode, out, rows_out, status, offsets_out);
+    else if (hashed)
         hipLaunchKernelGGL((bag_forward_hashed_kernel<LPR, CPL, UNROLL, BF16, STREAM>), grid, dim3(FWD_BLOCK), 0, s,
                            tables, T, B, per_table, nnz, rows, offsets, chunks, mode, out, rows_out, status);
     else
@@ -113,7 +168,7 @@ void launch_forward_variant(dim3 grid, hipStream_t s, const emb_table *tables, i
 template <int LPR, int CPL, int UNROLL>
 int launch_forward(bool bf16, int32_t T, hipStream_t s, const emb_table *tables, int64_t B, int64_t nnz,
                    const int64_t *rows, const int64_t *offsets, int32_t chunks, int32_t mode, float *out,
-                   uint32_t *status, bool hashed, int64_t *rows_out, bool stream)
+                   uint32_t *status, bool hashed, int64_t *rows_out, bool stream, int64_t *offsets_out)
 {
     constexpr int GROUPS = FWD_BLOCK / LPR;
     const int64_t per_table = (B + GROUPS - 1) / GROUPS;
@@ -122,7 +177,7 @@ int launch_forward(bool bf16, int32_t T, hipStream_t s, const emb_table *tables,
     const dim3 grid((unsigned)blocks);
 #define EMB_FV(BF, ST)                                                                                              \
     launch_forward_variant<LPR, CPL, UNROLL, BF, ST>(grid, s, tables, T, B, (uint32_t)per_table, nnz, rows, offsets, \
-                                                     chunks, mode, out, status, hashed, rows_out)
+                                                     chunks, mode, out, status, hashed, rows_out, offsets_out)
     if (bf16) {
         if (stream) EMB_FV(true, true); else EMB_FV(true, false);
     } else {
@@ -139,7 +194,7 @@ int launch_forward(bool bf16, int32_t T, hipStream_t s, const emb_table *tables,
 static int forward_entry(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
                          int32_t dtype, const int64_t *rows_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
                          int32_t mode, float *out_dev, uint32_t *status_dev, void *stream, bool hashed,
-                         int64_t *rows_out_dev, bool check_tables = true)
+                         int64_t *rows_out_dev, bool check_tables = true, int64_t *offsets_out_dev = nullptr)
 {
     if (B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
     const bool streaming = (mode & EMB_ROWS_STREAMING) != 0;
@@ -172,7 +227,7 @@ static int forward_entry(const emb_table *tables_host, const emb_table *tables_d
     hipStream_t s = emb_stream(stream);
 #define EMB_FWD(L, C, U) \
     return launch_forward<L, C, U>(bf16, T, s, tables_dev, B, nnz, rows_dev, offsets_dev, chunks, mode, out_dev, \
-                                   status_dev, hashed, rows_out_dev, streaming)
+                                   status_dev, hashed, rows_out_dev, streaming, offsets_out_dev)
     if (cpl == 1) {
         switch (lpr) {
             case 1: EMB_FWD(1, 1, 8);
@@ -208,6 +263,39 @@ extern "C" int emb_bag_forward_hashed(const emb_table *tables_host, const emb_ta
 {
     return forward_entry(tables_host, tables_dev, T, D, dtype, reinterpret_cast<const int64_t *>(raw_dev), offsets_dev,
                          B, nnz, mode, out_dev, status_dev, stream, true, rows_out_dev);
+}
+
+extern "C" size_t emb_offsets_scratch_bytes(int64_t num_bags_total)
+{
+    return num_bags_total < 0 ? 0 : ((size_t)num_bags_total + 1) * 8;
+}
+
+extern "C" int emb_bag_forward_hashed_lengths(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                                              int32_t D, int32_t dtype, const uint64_t *raw_dev,
+                                              const int32_t *lengths_dev, int64_t B, int64_t nnz, int32_t mode,
+                                              float *out_dev, int64_t *offsets_out_dev, int64_t *rows_out_dev,
+                                              void *scratch_dev, size_t scratch_bytes, uint32_t *status_dev,
+                                              void *stream)
+{
+    if (B < 0 || nnz < 0 || T < 0) return EMB_ERR_INVALID_ARG;
+    if (!offsets_out_dev) return EMB_ERR_INVALID_ARG;
+    if (emb_is_quant(dtype)) return EMB_ERR_UNSUPPORTED;   // quantised tables take row numbers
+    const int64_t n = (int64_t)T * B;
+    if (B > 0 && T > (int64_t)FWD_BLOCK * EMB_OFFSETS_TILE / B) return EMB_ERR_UNSUPPORTED;   // more tiles than a workgroup scans
+    if (n > 0 && (!lengths_dev || !scratch_dev || !emb_aligned(scratch_dev, 16) ||
+                  scratch_bytes < emb_offsets_scratch_bytes(n)))
+        return EMB_ERR_INVALID_ARG;
+    // validate everything before the first launch: the sums within tiles go to the scratch array
+    // (or, with no bags at all, the single entry 0 straight to the caller's array)
+    int64_t *local = n == 0 ? offsets_out_dev : reinterpret_cast<int64_t *>(scratch_dev);
+    int rc = forward_entry(tables_host, tables_dev, T, D, dtype, nullptr, nullptr, 0, 0, mode, nullptr, nullptr, nullptr,
+                           true, nullptr);   // shapes, tables and mode only: B == 0 launches nothing
+    if (rc != EMB_OK) return rc;
+    if (n > 0 && (!out_dev || !emb_aligned(out_dev, 16) || (nnz > 0 && !raw_dev))) return EMB_ERR_INVALID_ARG;
+    rc = emb_offsets_tile_sums(lengths_dev, n, local, status_dev, emb_stream(stream));
+    if (rc != EMB_OK || n == 0) return rc;
+    return forward_entry(tables_host, tables_dev, T, D, dtype, reinterpret_cast<const int64_t *>(raw_dev), local, B, nnz,
+                         mode, out_dev, status_dev, stream, true, rows_out_dev, true, offsets_out_dev);
 }
 
 int emb_forward_unchecked_tables(const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, const int64_t *ids_dev,

@@ -100,26 +100,22 @@ static inline void emb_row_split(int chunks, int &lpr, int &cpl)
 //                                                       `rows` (value v) selects, 0 = skip it
 // ---------------------------------------------------------------------------
 // STREAM: the rows are read with non-temporal loads (see EMB_ROWS_STREAMING in the header).
+// The bag is given by its bounds: lookups [s, e) of `rows` (ignored unless live).
 template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM = false, typename Source>
-__device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t bag, int l, int64_t nnz,
-                                                const int64_t *__restrict__ rows,
-                                                const int64_t *__restrict__ offsets, int32_t chunks_per_row,
-                                                int32_t mode, float *__restrict__ out_row, uint32_t *status,
-                                                const int64_t *__restrict__ tile_prefix = nullptr)
+__device__ __forceinline__ void gather_pool_range(Source &src, bool live, int64_t s, int64_t e, int l, int64_t nnz,
+                                                  const int64_t *__restrict__ rows, int32_t chunks_per_row,
+                                                  int32_t mode, float *__restrict__ out_row, uint32_t *status)
 {
-    // `bag` indexes offsets; out_row is where the bag's pooled row goes (not touched unless live).
-    // tile_prefix: the offsets are sums within tiles and these are the tiles' prefix sums (emb_offset_at).
+    // out_row is where the bag's pooled row goes (not touched unless live)
     constexpr int IPL = (UNROLL > LPR) ? UNROLL / LPR : 1;  // indices fetched per lane per batch
     constexpr int IB = IPL * LPR;                           // indices per batch
     static_assert(IB % UNROLL == 0, "index batch must be whole unroll groups");
 
-    int64_t s = 0, e = 0;
-    if (live) {
-        emb_bag_bounds(offsets, tile_prefix, bag, s, e);
-        if (s < 0 || e < s || e > nnz) {
-            if (l == 0) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
-            s = e = 0;
-        }
+    if (!live) {
+        s = e = 0;
+    } else if (s < 0 || e < s || e > nnz) {
+        if (l == 0) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
+        s = e = 0;
     }
 
     ChunkAcc<BF16> acc[CPL];
@@ -175,4 +171,19 @@ __device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t 
             for (int i = 0; i < F / 4; ++i) o[i] = make_float4(r[4 * i], r[4 * i + 1], r[4 * i + 2], r[4 * i + 3]);
         }
     }
+}
+
+// The bag is number `bag` of `offsets`.  tile_prefix: the offsets are sums within tiles and these are the
+// tiles' prefix sums (emb_bag_bounds).
+template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM = false, typename Source>
+__device__ __forceinline__ void gather_pool_bag(Source &src, bool live, int64_t bag, int l, int64_t nnz,
+                                                const int64_t *__restrict__ rows,
+                                                const int64_t *__restrict__ offsets, int32_t chunks_per_row,
+                                                int32_t mode, float *__restrict__ out_row, uint32_t *status,
+                                                const int64_t *__restrict__ tile_prefix = nullptr)
+{
+    int64_t s = 0, e = 0;
+    if (live) emb_bag_bounds(offsets, tile_prefix, bag, s, e);
+    gather_pool_range<LPR, CPL, UNROLL, BF16, STREAM>(src, live, s, e, l, nnz, rows, chunks_per_row, mode, out_row,
+                                                      status);
 }

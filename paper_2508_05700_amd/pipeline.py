@@ -75,6 +75,8 @@ class StepBuffers:
                  side_stream: bool = True):
         n = max(int(max_nnz), 1)
         self.offsets = torch.empty(w.T * w.B + 1, dtype=torch.int64, device=device)
+        # scratch of the lookups that take bag lengths (sums within tiles)
+        self.offsets_scratch = torch.empty(emb.emb_offsets_scratch_bytes(w.T * w.B), dtype=torch.uint8, device=device)
         self.rows = torch.empty(n, dtype=torch.int64, device=device)
         self.out = torch.empty((w.T, w.B, w.D), dtype=torch.float32, device=device)
         self.status = torch.zeros(1, dtype=torch.int32, device=device)
@@ -105,16 +107,24 @@ def run_index_stage(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: Ste
     return rows
 
 
+LENGTHS_ROUTE_MAX_BAGS = 1 << 20    # what emb_bag_forward_hashed_lengths accepts (256 tiles of 4096 lengths)
+
+
 def run_index_and_forward_fused(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:
-    """Bag offsets, then hashing and pooled lookup in one kernel.  Returns the view of the row
+    """Bag offsets, hashing and pooled lookup (one call where the number of bags allows).  Returns the view of the row
     buffer the kernel filled (for the backward).  Workloads whose IDs are row numbers already, or
     whose tables are quantised, take the two-kernel route."""
     if db.raw is None or w.quant:
         rows = run_index_stage(w, tables, db, buf)
         run_forward(w, tables, rows, buf)
         return rows
-    emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
     rows = buf.rows[:db.nnz]
+    if w.T * w.B <= LENGTHS_ROUTE_MAX_BAGS:      # offsets made inside the lookup's call
+        emb.emb_bag_forward_hashed_lengths(tables, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets,
+                                           buf.offsets_scratch, rows if w.backward else None, buf.status,
+                                           streaming=w.streaming)
+        return rows
+    emb.emb_lengths_to_offsets(db.lengths, buf.offsets, buf.status)
     emb.emb_bag_forward_hashed(tables, db.raw, buf.offsets, w.B, w.pool, buf.out, rows if w.backward else None,
                                buf.status, streaming=w.streaming)
     return rows

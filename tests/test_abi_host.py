@@ -222,6 +222,20 @@ def test_split_backward_and_helper_argument_errors(L):
     assert trl(*trl_args(out=None)) == INVALID and trl(*trl_args(raw=None)) == INVALID
     assert trl(*trl_args(mode=2)) == INVALID
     assert trl(*trl_args(wsb=need - 256)) == WORKSPACE and trl(*trl_args(ws=None)) == WORKSPACE
+    # the forward-only lookup taking bag lengths
+    L.emb_offsets_scratch_bytes.restype = C.c_size_t
+    assert L.emb_offsets_scratch_bytes(C.c_int64(8)) == 72 and L.emb_offsets_scratch_bytes(C.c_int64(-1)) == 0
+    fhl = L.emb_bag_forward_hashed_lengths
+
+    def fhl_args(**k):
+        return [d.ctypes.data, FAKE, 2, 64, k.get("dtype", 0), k.get("raw", FAKE), k.get("lengths", FAKE), k.get("B", 4), 8,
+                k.get("mode", 1), k.get("out", FAKE), k.get("offs", FAKE), None, k.get("scratch", FAKE), k.get("sb", 72),
+                None, None]
+    assert fhl(*fhl_args(offs=None)) == INVALID and fhl(*fhl_args(lengths=None)) == INVALID
+    assert fhl(*fhl_args(scratch=None)) == INVALID and fhl(*fhl_args(sb=64)) == INVALID
+    assert fhl(*fhl_args(out=None)) == INVALID and fhl(*fhl_args(raw=None)) == INVALID
+    assert fhl(*fhl_args(mode=7)) == INVALID and fhl(*fhl_args(dtype=3)) == UNSUPPORTED
+    assert fhl(*fhl_args(B=600_000, sb=1 << 30)) == UNSUPPORTED       # 1.2 M bags: more than 256 tiles
     assert sp(d.ctypes.data, FAKE, 2, 64, 0, 4, 8, None, need, None, None, None, None, None, None) == WORKSPACE
     assert sp(d.ctypes.data, FAKE, 2, 3, 0, 4, 8, FAKE, need, None, None, None, None, None, None) == UNSUPPORTED
     # helpers: null arguments are refused before the runtime is touched

@@ -869,6 +869,86 @@ def test_training_forward_from_lengths_equals_offsets_then_training_forward(T, B
         assert np.array_equal(H.host_table(a["w"][t]), tables[t]) and float(a["a"][t].abs().sum()) == 0.0
 
 
+@pytest.mark.parametrize("T,B,D,dtype,streaming", [(3, 5000, 32, "f32", False), (2, 4096, 16, "bf16", True),
+                                                   (1, 1, 64, "f32", False), (7, 149_796, 4, "f32", False)])
+def test_hashed_forward_from_lengths_equals_offsets_then_hashed_forward(T, B, D, dtype, streaming):
+    # emb_bag_forward_hashed_lengths against emb_lengths_to_offsets + emb_bag_forward_hashed: offsets (also against
+    # the oracle), pooled output and row numbers bit for bit; the last case has 256 tiles of lengths, the most a
+    # workgroup scans
+    rng = np.random.default_rng(4470 + T * B + D)
+    Rs = [int(r) for r in rng.integers(50, 30_000, size=T)]
+    salts = [int(x) for x in rng.integers(0, 1 << 62, size=T)]
+    big = T * B > 100_000
+    tables, lengths, off, _ = H.random_case(rng, T, B, D, Rs, 2 if big else 12, dtype, scale=0.01, empty_frac=0.5 if big else 0.15)
+    lengths = lengths.copy()
+    lengths[0] = 5
+    if T * B > 4096:
+        lengths[4090:4100] = 0
+        lengths[4096] = 77
+    off, _ = oracle.lengths_to_offsets(lengths)
+    nnz = int(off[-1])
+    raw = rng.integers(0, 1 << 64, size=nnz, dtype=np.uint64)
+    ts = emb.TableSet([H.dev(t) for t in tables], D, dtype, salts=salts, device=torch.device(H.DEV))
+    scratch = torch.full((emb.emb_offsets_scratch_bytes(T * B),), 0xA5, dtype=torch.uint8, device=H.DEV)
+
+    def route(from_lengths, lengths_np, nnz_arg):
+        out = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+        rows = torch.full((nnz_arg,), -1, dtype=torch.int64, device=H.DEV)
+        offs = torch.full((T * B + 1,), -9, dtype=torch.int64, device=H.DEV)
+        st = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+        if from_lengths:
+            emb.emb_bag_forward_hashed_lengths(ts, H.dev(raw[:nnz_arg]), H.dev(lengths_np), B, "mean", out, offs, scratch,
+                                               rows, st, streaming=streaming)
+        else:
+            emb.emb_lengths_to_offsets(H.dev(lengths_np), offs, st)
+            emb.emb_bag_forward_hashed(ts, H.dev(raw[:nnz_arg]), offs, B, "mean", out, rows, st, streaming=streaming)
+        torch.cuda.synchronize()
+        return out, rows, offs, int(st.item())
+
+    a, b = route(True, lengths, nnz), route(False, lengths, nnz)
+    assert a[3] == b[3] == 0 and np.array_equal(a[2].cpu().numpy(), off) and torch.equal(a[2], b[2])
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    rows_ref = np.concatenate([oracle.hash_ids(raw[off[t * B]:off[(t + 1) * B]], salts[t], Rs[t]) for t in range(T)])
+    assert np.array_equal(a[1].cpu().numpy(), rows_ref)
+    ref, absum, _ = oracle.bag_forward(tables, dtype, rows_ref, off, B, "mean")
+    H.assert_pooled_close(a[0].cpu().numpy(), ref, absum, what="hashed forward from lengths")
+    if T * B < 10:
+        return
+    neg = lengths.copy()
+    neg[rng.choice(T * B, size=5, replace=False)] = -3
+    off_n, st_n = oracle.lengths_to_offsets(neg)
+    a, b = route(True, neg, int(off_n[-1])), route(False, neg, int(off_n[-1]))
+    assert a[3] == b[3] == st_n == emb.STATUS_BAD_OFFSETS and np.array_equal(a[2].cpu().numpy(), off_n)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    a, b = route(True, lengths, nnz - 1), route(False, lengths, nnz - 1)      # nnz below the sum of the lengths
+    assert a[3] & emb.STATUS_BAD_OFFSETS and b[3] & emb.STATUS_BAD_OFFSETS and torch.equal(a[0], b[0])
+
+
+def test_hashed_forward_from_lengths_argument_limits():
+    ts = emb.TableSet([torch.zeros((5, 16), dtype=torch.float32, device=H.DEV)], 16, "f32", device=torch.device(H.DEV))
+    offs = torch.full((1,), -9, dtype=torch.int64, device=H.DEV)
+    st = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    empty_i64, empty_i32 = torch.empty(0, dtype=torch.int64, device=H.DEV), torch.empty(0, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_hashed_lengths(ts, empty_i64, empty_i32, 0, "sum", torch.empty((1, 0, 16), dtype=torch.float32,
+                                       device=H.DEV), offs, torch.empty(8, dtype=torch.uint8, device=H.DEV), None, st)
+    torch.cuda.synchronize()
+    assert offs.item() == 0 and st.item() == 0
+    B = 256 * 4096 + 1                                                # one bag more than 256 tiles of lengths
+    with pytest.raises(emb.EmbError) as e:
+        emb.emb_bag_forward_hashed_lengths(ts, empty_i64, torch.zeros(B, dtype=torch.int32, device=H.DEV), B, "sum",
+                                           torch.empty((1, B, 16), dtype=torch.float32, device=H.DEV),
+                                           torch.empty(B + 1, dtype=torch.int64, device=H.DEV),
+                                           torch.empty(emb.emb_offsets_scratch_bytes(B), dtype=torch.uint8, device=H.DEV),
+                                           None, st)
+    assert e.value.code == -2
+    with pytest.raises(emb.EmbError) as e:                           # scratch too small
+        emb.emb_bag_forward_hashed_lengths(ts, empty_i64, torch.zeros(100, dtype=torch.int32, device=H.DEV), 100, "sum",
+                                           torch.empty((1, 100, 16), dtype=torch.float32, device=H.DEV),
+                                           torch.empty(101, dtype=torch.int64, device=H.DEV),
+                                           torch.empty(100 * 8, dtype=torch.uint8, device=H.DEV), None, st)
+    assert e.value.code == -1
+
+
 def test_training_forward_from_lengths_with_more_than_a_thousand_tiles_of_bags():
     # 4.2 M bags are more than 1024 tiles of 4096 lengths: the prefix sums over the tile totals take several rounds
     rng = np.random.default_rng(4490)
