@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "b4172714e7b2c7f2",
+    "sources": "bf6baaa13da5af89",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (177567.6, 69043.5), "update_kernel": (240569.9, 324000.4)},
-        "3b": {"bag_forward_train_kernel": (94813.2, 83125.0), "update_kernel": (170570.3, 224704.3)},
-        "2": {"bag_forward_hashed_kernel": (176140.9, 32768.0), "bag_forward_kernel": (177242.5, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338142.9, 32768.0), "bag_forward_kernel": (338144.9, 32768.0)},
-        "2un": {"bag_forward_kernel": (346031.1, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (124459.3, 32800.8)},
-        "2uq4": {"bag_forward_quant_kernel": (233543.3, 32889.6)},
-        "2uq4r": {"bag_forward_quant_kernel": (191622.9, 32846.5)},
-        "4": {"bag_forward_hashed_kernel": (52645.4, 8192.0)},
+        "3": {"bag_forward_train_kernel": (177594.2, 68981.0), "update_kernel": (240574.1, 323999.5)},
+        "3b": {"bag_forward_train_kernel": (94806.4, 83136.3), "update_kernel": (170582.7, 224710.5)},
+        "2": {"bag_forward_hashed_kernel": (176019.5, 33805.1), "bag_forward_kernel": (178015.1, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338189.3, 33793.5), "bag_forward_kernel": (338145.8, 32768.0)},
+        "2un": {"bag_forward_kernel": (346127.3, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (124402.2, 32801.3)},
+        "2uq4": {"bag_forward_quant_kernel": (233545.4, 32882.4)},
+        "2uq4r": {"bag_forward_quant_kernel": (191614.6, 32843.6)},
+        "4": {"bag_forward_hashed_kernel": (52684.9, 8704.5)},
     },
 }
 
