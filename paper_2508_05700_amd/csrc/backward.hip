@@ -419,9 +419,14 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
                        keys, n, sentinel, ctrl, queue, queue_end, span_head, wave_heads, (uint32_t)L.slots);
     EMB_RETURN_IF_LAUNCH_FAILED();
 
-    hipLaunchKernelGGL((update_kernel<KeyT, LPR, CPL, EU, BF16>), dim3((unsigned)L.upd_blocks), dim3(UPD_BLOCK), 0,
-                       a.stream, a.tables_dev, a.T, keys, pay, n, sentinel, bag_scale, a.dout, chunks, a.D, inv_D, a.lr,
-                       a.eps, bdiv, ctrl);
+    if (a.T <= UPD_LDS_TABLES)
+        hipLaunchKernelGGL((update_kernel<KeyT, LPR, CPL, EU, BF16, true>), dim3((unsigned)L.upd_blocks), dim3(UPD_BLOCK),
+                           0, a.stream, a.tables_dev, a.T, keys, pay, n, sentinel, bag_scale, a.dout, chunks, a.D, inv_D,
+                           a.lr, a.eps, bdiv, ctrl);
+    else
+        hipLaunchKernelGGL((update_kernel<KeyT, LPR, CPL, EU, BF16, false>), dim3((unsigned)L.upd_blocks), dim3(UPD_BLOCK),
+                           0, a.stream, a.tables_dev, a.T, keys, pay, n, sentinel, bag_scale, a.dout, chunks, a.D, inv_D,
+                           a.lr, a.eps, bdiv, ctrl);
     EMB_RETURN_IF_LAUNCH_FAILED();
     EMB_MARK(a, 4);
 

@@ -44,22 +44,33 @@ struct ChunkAcc<true> {
     }
 };
 
-__device__ __forceinline__ uint4 load_chunk(const char *p) { return *reinterpret_cast<const uint4 *>(p); }
+// Table rows, accumulators and gradients live in device (or mapped host) memory, never in LDS: the
+// accesses below say so (global address space), so that they are not generic ("flat") operations,
+// which count against both the memory and the LDS counters of a wavefront and make waits on one
+// wait for the other.
+#define EMB_GLOBAL __attribute__((address_space(1)))
+typedef uint32_t emb_u4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_chunk(const char *p)
+{
+    const emb_u4 v = *(const EMB_GLOBAL emb_u4 *)p;
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 // Streaming variants for data that is touched once (the rows and accumulators the update
 // rewrites): they are marked non-temporal so that they do not push reusable lines (hot
 // rows, gradient rows) out of L2 and the memory-side cache.
-typedef uint32_t emb_u4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_chunk_nt(const char *p)
 {
-    const emb_u4 v = __builtin_nontemporal_load(reinterpret_cast<const emb_u4 *>(p));
+    const emb_u4 v = __builtin_nontemporal_load((const EMB_GLOBAL emb_u4 *)p);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
+__device__ __forceinline__ float load_f32_nt(const float *p) { return __builtin_nontemporal_load((const EMB_GLOBAL float *)p); }
+__device__ __forceinline__ void store_f32_nt(float *p, float v) { __builtin_nontemporal_store(v, (EMB_GLOBAL float *)p); }
 __device__ __forceinline__ void store_chunk_nt(char *p, const uint4 &x)
 {
     emb_u4 v;
     v.x = x.x; v.y = x.y; v.z = x.z; v.w = x.w;
-    __builtin_nontemporal_store(v, reinterpret_cast<emb_u4 *>(p));
+    __builtin_nontemporal_store(v, (EMB_GLOBAL emb_u4 *)p);
 }
 
 

@@ -44,37 +44,51 @@
 // table directory: row bases, weight and accumulator pointers of the T tables,
 // staged in LDS when T is small enough
 // ---------------------------------------------------------------------------
-struct TableDir {
+// The staged copies are addressed as LDS (address space 3), the descriptors as device memory: a
+// generic pointer that may be either would turn every access into a flat operation, whose wait also
+// waits for the row stores of the run before.
+typedef char *emb_char_ptr;
+typedef float *emb_float_ptr;
+#define EMB_LDS __attribute__((address_space(3)))
+// ALWAYS_LDS: the caller knows at compile time that the directory is staged (T <= UPD_LDS_TABLES), so
+// the accessors are plain LDS reads with no device-memory arm beside them (whose presence makes the
+// compiler wait for every outstanding memory operation, the stores of the run before included, where
+// the two arms join).
+template <bool ALWAYS_LDS>
+struct TableDirT {
     const emb_table *tables;
-    const int64_t *s_base;
-    char *const *s_w;
-    float *const *s_a;
+    const EMB_LDS int64_t *s_base;
+    const EMB_LDS emb_char_ptr *s_w;
+    const EMB_LDS emb_float_ptr *s_a;
     bool staged;
     __device__ __forceinline__ int64_t base(int t) const
     {
         int64_t v;
-        if (staged) v = s_base[t]; else v = tables[t].row_base;
+        if (ALWAYS_LDS || staged) v = s_base[t]; else v = tables[t].row_base;
         return v;
     }
     __device__ __forceinline__ char *weights(int t) const
     {
         char *v;
-        if (staged) v = s_w[t]; else v = reinterpret_cast<char *>(tables[t].weights);
+        if (ALWAYS_LDS || staged) v = s_w[t]; else v = reinterpret_cast<char *>(tables[t].weights);
         return v;
     }
     __device__ __forceinline__ float *accum(int t) const
     {
         float *v;
-        if (staged) v = s_a[t]; else v = tables[t].accum;
+        if (ALWAYS_LDS || staged) v = s_a[t]; else v = tables[t].accum;
         return v;
     }
 };
+typedef TableDirT<false> TableDir;
 
-#define EMB_STAGE_TABLE_DIR(dir, tables, T, BLOCK)                              \
+#define EMB_STAGE_TABLE_DIR(dir, tables, T, BLOCK) EMB_STAGE_TABLE_DIR_T(dir, tables, T, BLOCK, false)
+#define EMB_STAGE_TABLE_DIR_T(dir, tables, T, BLOCK, ALWAYS)                    \
     __shared__ int64_t dir##_base[UPD_LDS_TABLES];                              \
     __shared__ char *dir##_w[UPD_LDS_TABLES];                                   \
     __shared__ float *dir##_a[UPD_LDS_TABLES];                                  \
-    TableDir dir{tables, dir##_base, dir##_w, dir##_a, (T) <= UPD_LDS_TABLES};  \
+    TableDirT<ALWAYS> dir{tables, (const EMB_LDS int64_t *)dir##_base, (const EMB_LDS emb_char_ptr *)dir##_w,       \
+                 (const EMB_LDS emb_float_ptr *)dir##_a, (T) <= UPD_LDS_TABLES};                            \
     if (dir.staged) {                                                           \
         for (int t_ = threadIdx.x; t_ < (T); t_ += (BLOCK)) {                   \
             dir##_base[t_] = tables[t_].row_base;                               \
@@ -215,7 +229,7 @@ __device__ __forceinline__ void adagrad_apply(const GradAcc<BF16> (&acc)[CPL], u
             store_chunk_nt(wrow + (int64_t)chunk * 16, x);
         }
     }
-    if (l == 0) __builtin_nontemporal_store(s_new, aptr);
+    if (l == 0) store_f32_nt(aptr, s_new);
 }
 
 // NB consecutive records starting at an address aligned to their total size.
@@ -240,7 +254,7 @@ __device__ __forceinline__ void load_records(const E *__restrict__ p, E (&out)[N
 // ---------------------------------------------------------------------------
 // short runs: one wavefront per span of UPD_SPAN sorted records
 // ---------------------------------------------------------------------------
-template <typename KeyT, int LPR, int CPL, int EU, bool BF16>
+template <typename KeyT, int LPR, int CPL, int EU, bool BF16, bool LDS_DIR>
 __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__restrict__ tables, int32_t T,
                                                            const KeyT *__restrict__ keys,
                                                            const uint32_t *__restrict__ pay, uint32_t n,
@@ -256,7 +270,7 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
     constexpr int F = GradAcc<BF16>::F;
     constexpr int V = GradAcc<BF16>::V;
     static_assert(UPD_SPAN == 4 * EMB_WAVE && UPD_LOOK == 32, "staging below assumes 4 records per lane + 32");
-    EMB_STAGE_TABLE_DIR(dir, tables, T, UPD_BLOCK)
+    EMB_STAGE_TABLE_DIR_T(dir, tables, T, UPD_BLOCK, LDS_DIR)
     // [0] = the record before the span, [1 + e] = record e of the window, [WIN + 1] = the record after it
     __shared__ KeyT lk[WAVES][WIN + 2];
     __shared__ uint32_t lp[WAVES][WIN];
@@ -356,20 +370,8 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
             const int64_t r = (int64_t)key - dir.base(t);
             char *wrow = dir.weights(t) + r * row_bytes;
             float *aptr = dir.accum(t) + r;
-            uint4 w[CPL];
-#pragma unroll
-            for (int c = 0; c < CPL; ++c) {
-                const int chunk = l + c * LPR;
-                w[c] = make_uint4(0, 0, 0, 0);
-                if (chunk < chunks_per_row) w[c] = load_chunk_nt(wrow + (int64_t)chunk * 16);
-            }
-            const float s_old = __builtin_nontemporal_load(aptr);
-            GradAcc<BF16> acc[CPL];
-#pragma unroll
-            for (int c = 0; c < CPL; ++c) acc[c].zero();
-            for (int e0 = pos; e0 < end; e0 += EU) {
-                float4 gr[EU][CPL][V];
-                float sc[EU];
+            // gradient rows of records e0 .. e0 + EU - 1 of the run (zeros past its end)
+            auto load_batch = [&](int e0, float4 (&gr)[EU][CPL][V], float (&sc)[EU]) {
 #pragma unroll
                 for (int u = 0; u < EU; ++u) {
                     const int e = e0 + u;
@@ -389,6 +391,29 @@ __global__ __launch_bounds__(UPD_BLOCK) void update_kernel(const emb_table *__re
                         }
                     }
                 }
+            };
+            GradAcc<BF16> acc[CPL];
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) acc[c].zero();
+            // The first gradient rows are requested before the table row and its accumulator: loads come
+            // back in the order they were asked for, so the sum can start while the row is still on its way.
+            float4 gr[EU][CPL][V];
+            float sc[EU];
+            load_batch(pos, gr, sc);
+            uint4 w[CPL];
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                const int chunk = l + c * LPR;
+                w[c] = make_uint4(0, 0, 0, 0);
+                if (chunk < chunks_per_row) w[c] = load_chunk_nt(wrow + (int64_t)chunk * 16);
+            }
+            const float s_old = load_f32_nt(aptr);
+#pragma unroll
+            for (int u = 0; u < EU; ++u)
+#pragma unroll
+                for (int c = 0; c < CPL; ++c) acc[c].fma(sc[u], gr[u][c]);
+            for (int e0 = pos + EU; e0 < end; e0 += EU) {
+                load_batch(e0, gr, sc);
 #pragma unroll
                 for (int u = 0; u < EU; ++u)
 #pragma unroll
