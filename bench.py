@@ -863,12 +863,12 @@ def main() -> int:
         del cal
 
     K, W = args.steps, args.warmup
-    fused = not args.no_fused_forward and not args.overlap_sort and not w.quant and dbs[0].raw is not None
+    fused = not args.no_fused_forward and not args.overlap_sort and dbs[0].raw is not None
 
     train_route = fused and w.backward     # the lookup also writes the backward's records
     offsets_inside = train_route and not args.separate_offsets   # ... and makes the bag offsets on the way
     # forward-only with hashing inside the lookup: the lookup also takes the bag lengths (up to 2^20 bags)
-    lengths_route = (fused and not w.backward and not args.separate_offsets and not args.versioned
+    lengths_route = (fused and not w.backward and not w.quant and not args.separate_offsets and not args.versioned
                      and w.T * w.B <= (1 << 20))
     off_scratch = (torch.empty(emb.emb_offsets_scratch_bytes(w.T * w.B), dtype=torch.uint8, device=dev)
                    if lengths_route else None)
@@ -1036,6 +1036,9 @@ def main() -> int:
 
     if fused:
         fwd_name, fwd_pmc = "bag_forward_hashed_kernel (hash + gather-pool)", "bag_forward_hashed_kernel"
+        if w.quant:
+            fwd_name = "bag_forward_quant_kernel (hash + gather-dequantise-pool, %s rows of %d B)" % (w.quant, rowb)
+            fwd_pmc = "bag_forward_quant_kernel"
         fwd_extra = 0
         if train_route:
             fwd_name = "bwd_init + bag_forward_train_kernel (hash + gather-pool + the backward's records)"

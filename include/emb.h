@@ -260,7 +260,7 @@ int emb_bag_backward_update(const emb_table *tables_host, const emb_table *table
  * bit-identical to emb_bag_forward over the hashed rows.  rows_out_dev
  * (nullable, i64[nnz]) receives the row numbers, for the backward; entries of
  * lookups that lie in no valid bag (EMB_STATUS_BAD_OFFSETS) are not written.
- * dtype: EMB_F32 or EMB_BF16 (EMB_ERR_UNSUPPORTED for quantised tables). */
+ * Any storage type of emb_bag_forward, the quantised ones included. */
 int emb_bag_forward_hashed(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
                            int32_t D, int32_t dtype, const uint64_t *raw_dev,
                            const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode,

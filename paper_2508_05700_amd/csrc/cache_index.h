@@ -5,6 +5,7 @@
 // or miss and yields the slot, with no collisions and no search.
 #pragma once
 #include "emb_internal.h"
+#include "gather.h"
 
 struct CacheEntry {
     uint64_t bits;    // bit i set: row 64*e + i is cached
@@ -16,7 +17,7 @@ static_assert(sizeof(CacheEntry) == 16, "cache index entry must be 16 bytes");
 // Slot of row r (0 <= r < num_rows) in the cache, or -1 if the row is not cached.
 __device__ __forceinline__ int64_t cache_probe(const CacheEntry *__restrict__ index, uint64_t r, uint64_t num_hot)
 {
-    const uint4 raw = *reinterpret_cast<const uint4 *>(index + (r >> 6));
+    const uint4 raw = load_chunk(reinterpret_cast<const char *>(index + (r >> 6)));   // device memory
     const uint64_t bits = ((uint64_t)raw.y << 32) | raw.x;
     const int bit = (int)(r & 63);
     if ((bits >> bit) & 1ull) {

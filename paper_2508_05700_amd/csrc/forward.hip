@@ -216,9 +216,9 @@ static int forward_entry(const emb_table *tables_host, const emb_table *tables_d
     if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
 
     if (quant) {
-        if (hashed) return EMB_ERR_UNSUPPORTED;   // quantised tables take row numbers
+        if (offsets_out_dev) return EMB_ERR_UNSUPPORTED;   // offsets in two levels: fp32 / bf16 rows only
         return emb_forward_quant(tables_dev, T, D, dtype, rows_dev, offsets_dev, B, nnz, mode, out_dev, status_dev,
-                                 emb_stream(stream));
+                                 emb_stream(stream), hashed, rows_out_dev);
     }
     const int chunks = D * emb_elem_size(dtype) / 16;
     int lpr, cpl;

@@ -7,7 +7,12 @@
 constexpr int Q_ELEMS = 16;   // elements per lane
 constexpr int Q_BLOCK = 256;
 
-__device__ __forceinline__ uint2 load_u2(const char *p) { return *reinterpret_cast<const uint2 *>(p); }
+typedef uint32_t emb_u2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 load_u2(const char *p)   // rows are in device (or mapped host) memory
+{
+    const emb_u2 v = *(const EMB_GLOBAL emb_u2 *)p;
+    return make_uint2(v.x, v.y);
+}
 
 // 16 codes of a lane -> fp32.  INT4: masking every other nibble leaves one code per
 // byte, which converts with the byte-to-float instructions.

@@ -13,6 +13,7 @@
 // to a power of two; D must be a multiple of 16 and at most 1024.
 #include "emb_internal.h"
 #include "gather_quant.h"
+#include "u64mod.h"
 
 namespace {
 
@@ -113,13 +114,29 @@ struct QuantTableSource {
     }
 };
 
-template <int LPR, int BITS, int UNROLL>
+// The entries are raw IDs: hashed by the lane that fetched them (Section 2.2), as in the lookup over
+// fp32 / bf16 rows; the row numbers can be written out.
+struct HashedQuantTableSource {
+    const char *weights;
+    uint64_t num_rows, salt, magic;
+    int64_t row_bytes;
+    int64_t *rows_out;   // nullable
+    __device__ __forceinline__ uint64_t resolve(int64_t raw, int64_t j) const
+    {
+        const uint64_t r = emb_fast_mod(emb_splitmix64((uint64_t)raw ^ salt), num_rows, magic);
+        if (rows_out) rows_out[j] = (int64_t)r;
+        return reinterpret_cast<uint64_t>(weights + (int64_t)r * row_bytes);
+    }
+};
+
+template <int LPR, int BITS, int UNROLL, bool HASHED>
 __global__ __launch_bounds__(Q_BLOCK) void bag_forward_quant_kernel(const emb_table *__restrict__ tables, int32_t T,
                                                                     int64_t B, uint32_t blocks_per_table, int64_t nnz,
                                                                     const int64_t *__restrict__ rows,
                                                                     const int64_t *__restrict__ offsets, int32_t D,
                                                                     int64_t row_bytes, int32_t mode,
-                                                                    float *__restrict__ out, uint32_t *status)
+                                                                    float *__restrict__ out, uint32_t *status,
+                                                                    int64_t *__restrict__ rows_out)
 {
     constexpr int GROUPS = Q_BLOCK / LPR;
     const uint32_t lb = emb_xcd_block(blockIdx.x, gridDim.x);
@@ -129,23 +146,36 @@ __global__ __launch_bounds__(Q_BLOCK) void bag_forward_quant_kernel(const emb_ta
     const int l = threadIdx.x % LPR;
     const int64_t b = tail ? B : (int64_t)(lb % blocks_per_table) * GROUPS + threadIdx.x / LPR;
     const emb_table tb = tables[t];
-    QuantTableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, row_bytes, status};
-    gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, (int64_t)t * B + b, l, nnz, rows, offsets, D, mode, out,
-                                               status);
+    if (HASHED) {
+        HashedQuantTableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, tb.salt,
+                                   tb.mod_magic, row_bytes, rows_out};
+        gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, (int64_t)t * B + b, l, nnz, rows, offsets, D, mode, out,
+                                                   status);
+    } else {
+        QuantTableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, row_bytes, status};
+        gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, (int64_t)t * B + b, l, nnz, rows, offsets, D, mode, out,
+                                                   status);
+    }
 }
 
 template <int LPR, int BITS>
 int launch_quant_forward(hipStream_t s, const emb_table *tables, int32_t T, int64_t B, int64_t nnz, const int64_t *rows,
                          const int64_t *offsets, int32_t D, int64_t row_bytes, int32_t mode, float *out,
-                         uint32_t *status)
+                         uint32_t *status, bool hashed, int64_t *rows_out)
 {
     constexpr int GROUPS = Q_BLOCK / LPR;
     constexpr int UNROLL = 8;
     const int64_t per_table = (B + GROUPS - 1) / GROUPS;
     const int64_t blocks = emb_round_up_xcds(per_table * T);
     if (blocks > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((bag_forward_quant_kernel<LPR, BITS, UNROLL>), dim3((unsigned)blocks), dim3(Q_BLOCK), 0, s,
-                       tables, T, B, (uint32_t)per_table, nnz, rows, offsets, D, row_bytes, mode, out, status);
+    if (hashed)
+        hipLaunchKernelGGL((bag_forward_quant_kernel<LPR, BITS, UNROLL, true>), dim3((unsigned)blocks), dim3(Q_BLOCK), 0,
+                           s, tables, T, B, (uint32_t)per_table, nnz, rows, offsets, D, row_bytes, mode, out, status,
+                           rows_out);
+    else
+        hipLaunchKernelGGL((bag_forward_quant_kernel<LPR, BITS, UNROLL, false>), dim3((unsigned)blocks), dim3(Q_BLOCK), 0,
+                           s, tables, T, B, (uint32_t)per_table, nnz, rows, offsets, D, row_bytes, mode, out, status,
+                           rows_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -153,10 +183,11 @@ int launch_quant_forward(hipStream_t s, const emb_table *tables, int32_t T, int6
 template <int BITS>
 int dispatch_quant_forward(int lpr, hipStream_t s, const emb_table *tables, int32_t T, int64_t B, int64_t nnz,
                            const int64_t *rows, const int64_t *offsets, int32_t D, int64_t row_bytes, int32_t mode,
-                           float *out, uint32_t *status)
+                           float *out, uint32_t *status, bool hashed, int64_t *rows_out)
 {
-#define EMB_QF(L) \
-    return launch_quant_forward<L, BITS>(s, tables, T, B, nnz, rows, offsets, D, row_bytes, mode, out, status)
+#define EMB_QF(L)                                                                                              \
+    return launch_quant_forward<L, BITS>(s, tables, T, B, nnz, rows, offsets, D, row_bytes, mode, out, status, \
+                                         hashed, rows_out)
     switch (lpr) {
         case 1: EMB_QF(1);
         case 2: EMB_QF(2);
@@ -232,15 +263,16 @@ extern "C" int emb_quantize_rows(const float *src_dev, int64_t num_rows, int32_t
 }
 
 // Called by emb_bag_forward (forward.hip) once the common arguments are checked.
+// hashed: rows_dev holds raw IDs; rows_out_dev (nullable) then receives the row numbers.
 int emb_forward_quant(const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, const int64_t *rows_dev,
                       const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
-                      uint32_t *status_dev, hipStream_t s)
+                      uint32_t *status_dev, hipStream_t s, bool hashed, int64_t *rows_out_dev)
 {
     const int64_t rb = emb_row_bytes(D, dtype);
     const int lpr = emb_quant_lanes(D);
     if (emb_quant_bits(dtype) == 8)
         return dispatch_quant_forward<8>(lpr, s, tables_dev, T, B, nnz, rows_dev, offsets_dev, D, rb, mode, out_dev,
-                                         status_dev);
+                                         status_dev, hashed, rows_out_dev);
     return dispatch_quant_forward<4>(lpr, s, tables_dev, T, B, nnz, rows_dev, offsets_dev, D, rb, mode, out_dev,
-                                     status_dev);
+                                     status_dev, hashed, rows_out_dev);
 }

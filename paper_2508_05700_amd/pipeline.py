@@ -112,14 +112,13 @@ LENGTHS_ROUTE_MAX_BAGS = 1 << 20    # what emb_bag_forward_hashed_lengths accept
 
 def run_index_and_forward_fused(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers) -> torch.Tensor:
     """Bag offsets, hashing and pooled lookup (one call where the number of bags allows).  Returns the view of the row
-    buffer the kernel filled (for the backward).  Workloads whose IDs are row numbers already, or
-    whose tables are quantised, take the two-kernel route."""
-    if db.raw is None or w.quant:
+    buffer the kernel filled (for the backward).  Workloads whose IDs are row numbers already take the two-kernel route."""
+    if db.raw is None:
         rows = run_index_stage(w, tables, db, buf)
         run_forward(w, tables, rows, buf)
         return rows
     rows = buf.rows[:db.nnz]
-    if w.T * w.B <= LENGTHS_ROUTE_MAX_BAGS:      # offsets made inside the lookup's call
+    if w.T * w.B <= LENGTHS_ROUTE_MAX_BAGS and not w.quant:      # offsets made inside the lookup's call
         emb.emb_bag_forward_hashed_lengths(tables, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets,
                                            buf.offsets_scratch, rows if w.backward else None, buf.status,
                                            streaming=w.streaming)

@@ -133,10 +133,11 @@ def test_backward_argument_errors(L):
 
 
 def fhq(L):
-    # padded INT4 rows, like the other quantised types, are not read by the hashing lookup or the backward
+    # padded INT4 rows, like the other quantised types, are not read by the backward; the hashing lookup
+    # applies the quantised shape rules to them (D a multiple of 16)
     d0 = _tables()
     assert L.emb_bag_backward_workspace_bytes(2, 4, 8, 1007, 64, 4) == 0
-    return L.emb_bag_forward_hashed(d0.ctypes.data, FAKE, 2, 64, 4, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None)
+    return L.emb_bag_forward_hashed(d0.ctypes.data, FAKE, 2, 24, 4, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None)
 
 
 def test_quantized_row_size_and_argument_errors(L):
@@ -161,10 +162,11 @@ def test_quantized_row_size_and_argument_errors(L):
     assert L.emb_bag_forward(dm.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0x200, FAKE, None, None) == INVALID
     assert L.emb_bag_forward(dm.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 0, 8, 0x100 | 1, FAKE, None, None) == OK
     # (no bags: the mode with the hint bit passes validation and nothing is launched)
-    # hashing fused into the forward: fp32 / bf16 tables only
+    # hashing fused into the forward (quantised tables included; their shape rules apply)
     d0 = _tables()
     fh = L.emb_bag_forward_hashed
-    assert fh(d0.ctypes.data, FAKE, 2, 64, 3, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == UNSUPPORTED
+    assert fh(d0.ctypes.data, FAKE, 2, 24, 3, FAKE, FAKE, 4, 8, 0, FAKE, None, None, None) == UNSUPPORTED
+    assert fh(d0.ctypes.data, FAKE, 2, 64, 3, FAKE, FAKE, 4, 8, 0, None, None, None, None) == INVALID
     assert fh(d0.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, None, None, None, None) == INVALID
     assert fh(d0.ctypes.data, FAKE, 2, 64, 0, None, FAKE, 4, 8, 0, FAKE, None, None, None) == INVALID
     # quantised tables are read by the forward only
@@ -420,7 +422,7 @@ def test_versioned_tables_argument_errors(L):
         assert fn(FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 7, FAKE, None, None) == INVALID   # pooling mode
         assert fn(FAKE, 2, 64, 0, FAKE, None, 4, 8, 0, FAKE, None, None) == INVALID
         assert fn(FAKE, 2, 64, 0, FAKE, FAKE, 0, 0, 0, FAKE, None, None) == OK        # no bags: nothing launched
-    assert L.emb_bag_forward_latched_hashed(FAKE, 2, 64, 3, FAKE, FAKE, 4, 8, 0, FAKE, None, None) == UNSUPPORTED
+    assert L.emb_bag_forward_latched_hashed(FAKE, 2, 24, 3, FAKE, FAKE, 4, 8, 0, FAKE, None, None) == UNSUPPORTED
 
 
 def test_cached_tables_descriptor_and_argument_errors(L):

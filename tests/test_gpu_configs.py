@@ -76,7 +76,7 @@ def _forward_parity(w, tabs, batch_index=0):
         else:
             buf.rows[:db.nnz].copy_(rows_two_step)
         rows_dev = buf.rows[:db.nnz]
-        if not w.quant:
+        if True:
             # and through a version handle (latch + lookup over the latched descriptors): same bits, version returned
             record = torch.empty(emb.emb_version_record_bytes(w.T), dtype=torch.uint8, device=dev)
             latch = torch.empty(emb.emb_version_latch_bytes(w.T), dtype=torch.uint8, device=dev)
@@ -85,7 +85,7 @@ def _forward_parity(w, tabs, batch_index=0):
             emb.emb_version_publish(handle, record)
             buf.out.fill_(float("nan"))
             emb.emb_version_latch(handle, w.T, latch, buf.status)
-            emb.emb_bag_forward_latched_hashed(latch, w.T, w.D, w.dtype, db.raw, buf.offsets, w.B, w.pool, buf.out,
+            emb.emb_bag_forward_latched_hashed(latch, w.T, w.D, w.storage, db.raw, buf.offsets, w.B, w.pool, buf.out,
                                                buf.status, streaming=w.streaming)
             torch.cuda.synchronize()
             assert int(buf.status.item()) == 0 and int(emb.latched_version(latch).item()) == 7

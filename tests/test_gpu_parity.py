@@ -390,6 +390,42 @@ def test_int4_rows_padded_to_64_bytes_hold_the_int4_row_and_give_the_same_lookup
         H.assert_pooled_close(o3[t].cpu().numpy(), ref, absum, what="padded INT4 hosted tables")
 
 
+@pytest.mark.parametrize("D,dtype", [(64, "int4"), (48, "int8"), (64, "int4r64"), (256, "int4")])
+def test_hashed_forward_over_quantized_tables_equals_hashing_first(D, dtype):
+    # hashing inside the quantised lookup: bit-identical to emb_hash_ids_tables + emb_bag_forward, row numbers
+    # written out, and the pooled values those of the oracle
+    rng = np.random.default_rng(970 + D + len(dtype))
+    T, B = 3, 500
+    Rs = [5000, 7, 20_000]
+    salts = [11, 0, M64]
+    codes = "int4" if dtype == "int4r64" else dtype
+    src = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
+    qt = [oracle.quantize_rows(x, codes) for x in src]
+    rb = emb.emb_row_bytes(D, dtype)
+    qdev = []
+    for q in qt:
+        pad = np.zeros((q.shape[0], rb), np.uint8)
+        pad[:, :q.shape[1]] = q
+        qdev.append(H.dev(pad))
+    lengths = rng.integers(0, 40, size=T * B).astype(np.int32)
+    lengths[rng.random(T * B) < 0.15] = 0
+    off, _ = oracle.lengths_to_offsets(lengths)
+    nnz = int(off[-1])
+    raw = rng.integers(0, 1 << 64, size=nnz, dtype=np.uint64)
+    rows = np.concatenate([oracle.hash_ids(raw[off[t * B]:off[(t + 1) * B]], salts[t], Rs[t]) for t in range(T)])
+    ts = emb.TableSet(qdev, D, dtype, salts=salts, device=torch.device(H.DEV))
+    out1 = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    out2 = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    rows_d = torch.full((nnz,), -1, dtype=torch.int64, device=H.DEV)
+    st = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_bag_forward_hashed(ts, H.dev(raw), H.dev(off), B, "mean", out1, rows_d, st)
+    emb.emb_bag_forward(ts, H.dev(rows), H.dev(off), B, "mean", out2, st)
+    torch.cuda.synchronize()
+    assert st.item() == 0 and np.array_equal(rows_d.cpu().numpy(), rows) and torch.equal(out1, out2)
+    ref, absum, _ = oracle.bag_forward(qt, codes, rows, off, B, "mean", D=D)
+    H.assert_pooled_close(out1.cpu().numpy(), ref, absum, what="hashed quantised forward %s D=%d" % (dtype, D))
+
+
 def test_forward_quantized_grid_tables_are_bit_exact_and_empty_batch():
     # integer codes with scale 1 and integer bias: every partial sum is exact in fp32
     rng = np.random.default_rng(960)
