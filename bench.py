@@ -868,7 +868,7 @@ def main() -> int:
     train_route = fused and w.backward     # the lookup also writes the backward's records
     offsets_inside = train_route and not args.separate_offsets   # ... and makes the bag offsets on the way
     # forward-only with hashing inside the lookup: the lookup also takes the bag lengths (up to 2^20 bags)
-    lengths_route = (fused and not w.backward and not w.quant and not args.separate_offsets and not args.versioned
+    lengths_route = (fused and not w.backward and not args.separate_offsets and not args.versioned
                      and w.T * w.B <= (1 << 20))
     off_scratch = (torch.empty(emb.emb_offsets_scratch_bytes(w.T * w.B), dtype=torch.uint8, device=dev)
                    if lengths_route else None)
@@ -1047,7 +1047,7 @@ def main() -> int:
         index_entry = entry("offsets_* (index stage, 3 launches; hashing is done inside the forward)", ms_index,
                             bags * 12, "12 B per bag (length in, offset out)")
         if lengths_route:
-            fwd_name = "offsets_tile_scan + bag_forward_hashed_kernel (bag offsets + hash + gather-pool)"
+            fwd_name = "offsets_tile_scan + " + fwd_name.replace("(hash", "(bag offsets + hash")
             fwd_extra += bags * 28                   # length in, sum within the tile out and in, offset out
             index_entry = entry("(index stage: the bag offsets are made inside the lookup)", ms_index, 1,
                                 "not priced: counted under the lookup")

@@ -276,7 +276,7 @@ int emb_bag_forward_hashed(const emb_table *tables_host, const emb_table *tables
  * call's work has run), and every workgroup of the lookup adds the prefix sums
  * of the tile totals itself.  Pooled output, offsets, row numbers and status
  * bits are bit-identical to the two calls.  EMB_ERR_UNSUPPORTED for more than
- * 1 048 576 bags (256 tiles: use the two calls) and for quantised tables.
+ * 1 048 576 bags (256 tiles: use the two calls).  Any storage type.
  * A negative length counts as 0 and sets EMB_STATUS_BAD_OFFSETS; nnz must be
  * the sum of the lengths.  offsets_out_dev must not overlap lengths_dev or
  * scratch_dev.  mode may carry EMB_ROWS_STREAMING. */

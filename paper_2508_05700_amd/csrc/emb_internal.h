@@ -71,7 +71,8 @@ __device__ __forceinline__ void emb_bag_bounds(const int64_t *__restrict__ off, 
 int emb_check_quant_shape(int32_t D, int32_t dtype);
 int emb_forward_quant(const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, const int64_t *rows_dev,
                       const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
-                      uint32_t *status_dev, hipStream_t s, bool hashed, int64_t *rows_out_dev);
+                      uint32_t *status_dev, hipStream_t s, bool hashed, int64_t *rows_out_dev,
+                      int64_t *offsets_out_dev);
 
 // emb_bag_forward / emb_bag_forward_hashed over descriptors that exist in device memory only and were
 // validated earlier (the latched copy of a version record; versioned.hip).

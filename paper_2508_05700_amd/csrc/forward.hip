@@ -9,6 +9,7 @@
 // cached lookup.
 #include "emb_internal.h"
 #include "gather.h"
+#include "gather_quant.h"
 #include "scan.h"
 #include "u64mod.h"
 
@@ -49,9 +50,8 @@ struct HashedTableSource {
 };
 
 // TWO_LEVEL (emb_bag_forward_hashed_lengths): `offsets` holds the sums of the bag lengths within tiles of
-// EMB_OFFSETS_TILE lengths (emb_offsets_tile_sums); every workgroup takes the exclusive prefix sums of the
-// tile totals itself (at most FWD_BLOCK tiles: one load per thread and a scan in LDS, beside the loads of
-// its bags' bounds) and the final offsets are written to offsets_out.
+// EMB_OFFSETS_TILE lengths (emb_offsets_tile_sums); the prefix sums of the tile totals are taken inside the
+// kernel (emb_two_level_bounds, at most FWD_BLOCK tiles) and the final offsets are written to offsets_out.
 template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM, bool TWO_LEVEL = false>
 __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb_table *__restrict__ tables, int32_t T,
                                                                        int64_t B, uint32_t blocks_per_table,
@@ -64,20 +64,6 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb
 {
     __shared__ int64_t tile_prefix[TWO_LEVEL ? FWD_BLOCK : 1];
     __shared__ int64_t wave_sums[FWD_BLOCK / EMB_WAVE];
-    const int64_t n_bags = (int64_t)T * B;
-    const int64_t n_tiles = (n_bags + EMB_OFFSETS_TILE - 1) / EMB_OFFSETS_TILE;   // <= FWD_BLOCK (checked by the host)
-    const bool in_wave = TWO_LEVEL && n_tiles <= EMB_WAVE;   // uniform: a wavefront keeps the prefix sums in registers
-    if (TWO_LEVEL && !in_wave) {
-        const int64_t n = n_bags;
-        const int64_t k = threadIdx.x;
-        int64_t end = (k + 1) * EMB_OFFSETS_TILE;
-        if (end > n) end = n;
-        const int64_t v = k < n_tiles ? offsets[end] : 0;   // a tile's total stands at its end
-        int64_t total;
-        const int64_t inc = block_inclusive_scan<int64_t, FWD_BLOCK>(v, wave_sums, total);
-        tile_prefix[k] = inc - v;
-        __syncthreads();
-    }
     constexpr int GROUPS = FWD_BLOCK / LPR;
     const uint32_t lb = emb_xcd_block(blockIdx.x, gridDim.x);
     const uint32_t t_raw = lb / blocks_per_table;
@@ -90,21 +76,9 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb
                           (int64_t)chunks_per_row * 16, rows_out};
     constexpr int F = ChunkAcc<BF16>::FLOATS;
     const int64_t bag = (int64_t)t * B + b;
-    if (in_wave) {
-        // Up to 64 tiles of lengths: lane k of every wavefront loads tile k's total, a scan over the
-        // wavefront gives the tiles' prefix sums, and a bag fetches the two it needs by lane shuffles.
-        // The totals and the bag's own two sums are requested together; no LDS, no barrier.  All lanes
-        // take part in the shuffles (a bag that is not live stands in as bag 0).
-        const int lane = threadIdx.x & (EMB_WAVE - 1);
-        int64_t end = (int64_t)(lane + 1) * EMB_OFFSETS_TILE;
-        if (end > n_bags) end = n_bags;
-        const int64_t total = lane < n_tiles ? offsets[end] : 0;
-        const int64_t bc = b < B ? bag : 0;
-        const int64_t a0 = offsets[bc], a1 = offsets[bc + 1];
-        const int64_t prefix = wave_inclusive_scan(total) - total;
-        const int64_t ps = shfl_i64(prefix, (int)((bc > 0 ? bc - 1 : 0) / EMB_OFFSETS_TILE), EMB_WAVE);
-        const int64_t pe = shfl_i64(prefix, (int)(bc / EMB_OFFSETS_TILE), EMB_WAVE);
-        const int64_t s = a0 + (bc > 0 ? ps : 0), e = a1 + pe;
+    if (TWO_LEVEL) {
+        int64_t s, e;
+        emb_two_level_bounds<FWD_BLOCK>(offsets, (int64_t)T * B, b < B, bag, tile_prefix, wave_sums, s, e);
         if (b < B && l == 0) {
             offsets_out[bag + 1] = e;
             if (bag == 0) offsets_out[0] = 0;
@@ -113,15 +87,8 @@ __global__ __launch_bounds__(FWD_BLOCK) void bag_forward_hashed_kernel(const emb
                                                           out + bag * ((int64_t)chunks_per_row * F), status);
         return;
     }
-    if (TWO_LEVEL && b < B && l == 0) {
-        int64_t s, e;
-        emb_bag_bounds(offsets, tile_prefix, bag, s, e);
-        offsets_out[bag + 1] = e;
-        if (bag == 0) offsets_out[0] = 0;
-    }
     gather_pool_bag<LPR, CPL, UNROLL, BF16, STREAM>(src, b < B, bag, l, nnz, raw, offsets, chunks_per_row, mode,
-                                            out + bag * ((int64_t)chunks_per_row * F), status,
-                                            TWO_LEVEL ? tile_prefix : nullptr);
+                                            out + bag * ((int64_t)chunks_per_row * F), status);
 }
 
 template <int LPR, int CPL, int UNROLL, bool BF16, bool STREAM>
@@ -216,9 +183,8 @@ static int forward_entry(const emb_table *tables_host, const emb_table *tables_d
     if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
 
     if (quant) {
-        if (offsets_out_dev) return EMB_ERR_UNSUPPORTED;   // offsets in two levels: fp32 / bf16 rows only
         return emb_forward_quant(tables_dev, T, D, dtype, rows_dev, offsets_dev, B, nnz, mode, out_dev, status_dev,
-                                 emb_stream(stream), hashed, rows_out_dev);
+                                 emb_stream(stream), hashed, rows_out_dev, offsets_out_dev);
     }
     const int chunks = D * emb_elem_size(dtype) / 16;
     int lpr, cpl;
@@ -279,8 +245,8 @@ extern "C" int emb_bag_forward_hashed_lengths(const emb_table *tables_host, cons
 {
     if (B < 0 || nnz < 0 || T < 0) return EMB_ERR_INVALID_ARG;
     if (!offsets_out_dev) return EMB_ERR_INVALID_ARG;
-    if (emb_is_quant(dtype)) return EMB_ERR_UNSUPPORTED;   // quantised tables take row numbers
     const int64_t n = (int64_t)T * B;
+    static_assert(FWD_BLOCK == Q_BLOCK, "the lookups over plain and quantised rows scan the same number of tiles");
     if (B > 0 && T > (int64_t)FWD_BLOCK * EMB_OFFSETS_TILE / B) return EMB_ERR_UNSUPPORTED;   // more tiles than a workgroup scans
     if (n > 0 && (!lengths_dev || !scratch_dev || !emb_aligned(scratch_dev, 16) ||
                   scratch_bytes < emb_offsets_scratch_bytes(n)))

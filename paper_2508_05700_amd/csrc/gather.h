@@ -2,6 +2,7 @@
 // or bf16 rows, accumulated in fp32.
 #pragma once
 #include "emb_internal.h"
+#include "scan.h"
 
 // Per-lane accumulator for one 16-byte chunk of a row.
 template <bool BF16>
@@ -79,6 +80,50 @@ __device__ __forceinline__ int64_t shfl_i64(int64_t v, int src, int width)
     int lo = __shfl((int)(uint32_t)(uint64_t)v, src, width);
     int hi = __shfl((int)(uint32_t)((uint64_t)v >> 32), src, width);
     return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+// Bounds of bag `bag` (clamped to bag 0 where the caller's lane group has no bag) from offsets kept in two
+// levels: `local` holds the sums of the bag lengths within tiles of EMB_OFFSETS_TILE lengths
+// (emb_offsets_tile_sums), the tile totals standing at the tile ends; the prefix sums of the totals are
+// taken here.  Up to 64 tiles every wavefront does that by itself: lane k loads tile k's total together
+// with the loads of its bag's own two sums, one scan over the wavefront, and the two prefixes a bag needs
+// come by lane shuffles (no LDS, no barrier).  Up to BLOCK tiles the workgroup scans the totals in LDS
+// (tile_prefix: BLOCK entries, wave_sums: BLOCK / 64).  Every thread of the workgroup calls this.
+template <int BLOCK>
+__device__ __forceinline__ void emb_two_level_bounds(const int64_t *__restrict__ local, int64_t n_bags, bool live,
+                                                     int64_t bag, int64_t *tile_prefix, int64_t *wave_sums,
+                                                     int64_t &s, int64_t &e)
+{
+    const int64_t n_tiles = (n_bags + EMB_OFFSETS_TILE - 1) / EMB_OFFSETS_TILE;   // <= BLOCK (checked by the host)
+    const int64_t bc = live ? bag : 0;
+    const int64_t ts = (bc > 0 ? bc - 1 : 0) / EMB_OFFSETS_TILE, te = bc / EMB_OFFSETS_TILE;
+    int64_t ps, pe;
+    if (n_tiles <= EMB_WAVE) {   // uniform
+        const int lane = threadIdx.x & (EMB_WAVE - 1);
+        int64_t end = (int64_t)(lane + 1) * EMB_OFFSETS_TILE;
+        if (end > n_bags) end = n_bags;
+        const int64_t total = lane < n_tiles ? local[end] : 0;
+        const int64_t a0 = local[bc], a1 = local[bc + 1];
+        const int64_t prefix = wave_inclusive_scan(total) - total;
+        ps = shfl_i64(prefix, (int)ts, EMB_WAVE);
+        pe = shfl_i64(prefix, (int)te, EMB_WAVE);
+        s = a0 + (bc > 0 ? ps : 0);
+        e = a1 + pe;
+        return;
+    }
+    const int64_t k = threadIdx.x;
+    int64_t end = (k + 1) * EMB_OFFSETS_TILE;
+    if (end > n_bags) end = n_bags;
+    const int64_t v = k < n_tiles ? local[end] : 0;
+    const int64_t a0 = local[bc], a1 = local[bc + 1];
+    int64_t total;
+    const int64_t inc = block_inclusive_scan<int64_t, BLOCK>(v, wave_sums, total);
+    tile_prefix[k] = inc - v;
+    __syncthreads();
+    ps = tile_prefix[ts];
+    pe = tile_prefix[te];
+    s = a0 + (bc > 0 ? ps : 0);
+    e = a1 + pe;
 }
 
 // Lanes per row (a power of two <= 64) and chunks per lane for a row of

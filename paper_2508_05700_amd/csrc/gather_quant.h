@@ -42,11 +42,11 @@ __device__ __forceinline__ void codes_to_float(const uint32_t (&w)[BITS == 8 ? 4
 // the 8-byte header (one request for the group) and its own 8 or 16 code bytes.
 // Each element is dequantised (one fused multiply-add) and then added, so the
 // rounding behaviour is that of summing fp32 rows.  `bag` indexes offsets and out.
+// The bag is given by its bounds: lookups [s, e) of `rows` (ignored unless live).
 template <int LPR, int BITS, int UNROLL, typename Source>
-__device__ __forceinline__ void gather_dequant_pool_bag(Source &src, bool live, int64_t bag, int l, int64_t nnz,
-                                                        const int64_t *__restrict__ rows,
-                                                        const int64_t *__restrict__ offsets, int32_t D, int32_t mode,
-                                                        float *__restrict__ out, uint32_t *status)
+__device__ __forceinline__ void gather_dequant_pool_range(Source &src, bool live, int64_t bag, int64_t s, int64_t e, int l,
+                                                          int64_t nnz, const int64_t *__restrict__ rows, int32_t D,
+                                                          int32_t mode, float *__restrict__ out, uint32_t *status)
 {
     constexpr int IPL = (UNROLL > LPR) ? UNROLL / LPR : 1;  // indices fetched per lane per batch
     constexpr int IB = IPL * LPR;                           // indices per batch
@@ -55,14 +55,11 @@ __device__ __forceinline__ void gather_dequant_pool_bag(Source &src, bool live, 
     const bool mine_elems = l * Q_ELEMS < D;         // lanes past the row (D/16 not a power of two) idle
     const int code_off = 8 + l * (BITS == 8 ? 16 : 8);
 
-    int64_t s = 0, e = 0;
-    if (live) {
-        s = offsets[bag];
-        e = offsets[bag + 1];
-        if (s < 0 || e < s || e > nnz) {
-            if (l == 0) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
-            s = e = 0;
-        }
+    if (!live) {
+        s = e = 0;
+    } else if (s < 0 || e < s || e > nnz) {
+        if (l == 0) emb_flag(status, EMB_STATUS_BAD_OFFSETS);
+        s = e = 0;
     }
     float acc[Q_ELEMS];
 #pragma unroll
@@ -123,6 +120,21 @@ __device__ __forceinline__ void gather_dequant_pool_bag(Source &src, bool live, 
         if (mean) v = make_float4(v.x / flen, v.y / flen, v.z / flen, v.w / flen);
         o[i] = v;
     }
+}
+
+// The bag is number `bag` of `offsets`.
+template <int LPR, int BITS, int UNROLL, typename Source>
+__device__ __forceinline__ void gather_dequant_pool_bag(Source &src, bool live, int64_t bag, int l, int64_t nnz,
+                                                        const int64_t *__restrict__ rows,
+                                                        const int64_t *__restrict__ offsets, int32_t D, int32_t mode,
+                                                        float *__restrict__ out, uint32_t *status)
+{
+    int64_t s = 0, e = 0;
+    if (live) {
+        s = offsets[bag];
+        e = offsets[bag + 1];
+    }
+    gather_dequant_pool_range<LPR, BITS, UNROLL>(src, live, bag, s, e, l, nnz, rows, D, mode, out, status);
 }
 
 // Lanes per row: D/16 rounded up to a power of two.

@@ -129,15 +129,20 @@ struct HashedQuantTableSource {
     }
 };
 
-template <int LPR, int BITS, int UNROLL, bool HASHED>
+// TWO_LEVEL (with HASHED): `offsets` holds the sums of the bag lengths within tiles (emb_two_level_bounds)
+// and the final offsets are written to offsets_out.
+template <int LPR, int BITS, int UNROLL, bool HASHED, bool TWO_LEVEL = false>
 __global__ __launch_bounds__(Q_BLOCK) void bag_forward_quant_kernel(const emb_table *__restrict__ tables, int32_t T,
                                                                     int64_t B, uint32_t blocks_per_table, int64_t nnz,
                                                                     const int64_t *__restrict__ rows,
                                                                     const int64_t *__restrict__ offsets, int32_t D,
                                                                     int64_t row_bytes, int32_t mode,
                                                                     float *__restrict__ out, uint32_t *status,
-                                                                    int64_t *__restrict__ rows_out)
+                                                                    int64_t *__restrict__ rows_out,
+                                                                    int64_t *__restrict__ offsets_out = nullptr)
 {
+    __shared__ int64_t tile_prefix[TWO_LEVEL ? Q_BLOCK : 1];
+    __shared__ int64_t wave_sums[Q_BLOCK / EMB_WAVE];
     constexpr int GROUPS = Q_BLOCK / LPR;
     const uint32_t lb = emb_xcd_block(blockIdx.x, gridDim.x);
     const uint32_t t_raw = lb / blocks_per_table;
@@ -149,8 +154,18 @@ __global__ __launch_bounds__(Q_BLOCK) void bag_forward_quant_kernel(const emb_ta
     if (HASHED) {
         HashedQuantTableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, tb.salt,
                                    tb.mod_magic, row_bytes, rows_out};
-        gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, (int64_t)t * B + b, l, nnz, rows, offsets, D, mode, out,
-                                                   status);
+        const int64_t bag = (int64_t)t * B + b;
+        if (TWO_LEVEL) {
+            int64_t s, e;
+            emb_two_level_bounds<Q_BLOCK>(offsets, (int64_t)T * B, b < B, bag, tile_prefix, wave_sums, s, e);
+            if (b < B && l == 0) {
+                offsets_out[bag + 1] = e;
+                if (bag == 0) offsets_out[0] = 0;
+            }
+            gather_dequant_pool_range<LPR, BITS, UNROLL>(src, b < B, bag, s, e, l, nnz, rows, D, mode, out, status);
+        } else {
+            gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, bag, l, nnz, rows, offsets, D, mode, out, status);
+        }
     } else {
         QuantTableSource src{reinterpret_cast<const char *>(tb.weights), (uint64_t)tb.num_rows, row_bytes, status};
         gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, (int64_t)t * B + b, l, nnz, rows, offsets, D, mode, out,
@@ -161,14 +176,18 @@ __global__ __launch_bounds__(Q_BLOCK) void bag_forward_quant_kernel(const emb_ta
 template <int LPR, int BITS>
 int launch_quant_forward(hipStream_t s, const emb_table *tables, int32_t T, int64_t B, int64_t nnz, const int64_t *rows,
                          const int64_t *offsets, int32_t D, int64_t row_bytes, int32_t mode, float *out,
-                         uint32_t *status, bool hashed, int64_t *rows_out)
+                         uint32_t *status, bool hashed, int64_t *rows_out, int64_t *offsets_out)
 {
     constexpr int GROUPS = Q_BLOCK / LPR;
     constexpr int UNROLL = 8;
     const int64_t per_table = (B + GROUPS - 1) / GROUPS;
     const int64_t blocks = emb_round_up_xcds(per_table * T);
     if (blocks > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
-    if (hashed)
+    if (offsets_out)   // hashed, offsets in two levels
+        hipLaunchKernelGGL((bag_forward_quant_kernel<LPR, BITS, UNROLL, true, true>), dim3((unsigned)blocks),
+                           dim3(Q_BLOCK), 0, s, tables, T, B, (uint32_t)per_table, nnz, rows, offsets, D, row_bytes, mode,
+                           out, status, rows_out, offsets_out);
+    else if (hashed)
         hipLaunchKernelGGL((bag_forward_quant_kernel<LPR, BITS, UNROLL, true>), dim3((unsigned)blocks), dim3(Q_BLOCK), 0,
                            s, tables, T, B, (uint32_t)per_table, nnz, rows, offsets, D, row_bytes, mode, out, status,
                            rows_out);
@@ -183,11 +202,11 @@ int launch_quant_forward(hipStream_t s, const emb_table *tables, int32_t T, int6
 template <int BITS>
 int dispatch_quant_forward(int lpr, hipStream_t s, const emb_table *tables, int32_t T, int64_t B, int64_t nnz,
                            const int64_t *rows, const int64_t *offsets, int32_t D, int64_t row_bytes, int32_t mode,
-                           float *out, uint32_t *status, bool hashed, int64_t *rows_out)
+                           float *out, uint32_t *status, bool hashed, int64_t *rows_out, int64_t *offsets_out)
 {
 #define EMB_QF(L)                                                                                              \
     return launch_quant_forward<L, BITS>(s, tables, T, B, nnz, rows, offsets, D, row_bytes, mode, out, status, \
-                                         hashed, rows_out)
+                                         hashed, rows_out, offsets_out)
     switch (lpr) {
         case 1: EMB_QF(1);
         case 2: EMB_QF(2);
@@ -264,15 +283,17 @@ extern "C" int emb_quantize_rows(const float *src_dev, int64_t num_rows, int32_t
 
 // Called by emb_bag_forward (forward.hip) once the common arguments are checked.
 // hashed: rows_dev holds raw IDs; rows_out_dev (nullable) then receives the row numbers.
+// offsets_out_dev != NULL (hashed only): offsets_dev holds sums within tiles, the offsets are written there.
 int emb_forward_quant(const emb_table *tables_dev, int32_t T, int32_t D, int32_t dtype, const int64_t *rows_dev,
                       const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
-                      uint32_t *status_dev, hipStream_t s, bool hashed, int64_t *rows_out_dev)
+                      uint32_t *status_dev, hipStream_t s, bool hashed, int64_t *rows_out_dev,
+                      int64_t *offsets_out_dev)
 {
     const int64_t rb = emb_row_bytes(D, dtype);
     const int lpr = emb_quant_lanes(D);
     if (emb_quant_bits(dtype) == 8)
         return dispatch_quant_forward<8>(lpr, s, tables_dev, T, B, nnz, rows_dev, offsets_dev, D, rb, mode, out_dev,
-                                         status_dev, hashed, rows_out_dev);
+                                         status_dev, hashed, rows_out_dev, offsets_out_dev);
     return dispatch_quant_forward<4>(lpr, s, tables_dev, T, B, nnz, rows_dev, offsets_dev, D, rb, mode, out_dev,
-                                     status_dev, hashed, rows_out_dev);
+                                     status_dev, hashed, rows_out_dev, offsets_out_dev);
 }

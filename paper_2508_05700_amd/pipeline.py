@@ -118,7 +118,7 @@ def run_index_and_forward_fused(w: Workload, tables: emb.TableSet, db: DeviceBat
         run_forward(w, tables, rows, buf)
         return rows
     rows = buf.rows[:db.nnz]
-    if w.T * w.B <= LENGTHS_ROUTE_MAX_BAGS and not w.quant:      # offsets made inside the lookup's call
+    if w.T * w.B <= LENGTHS_ROUTE_MAX_BAGS:      # offsets made inside the lookup's call
         emb.emb_bag_forward_hashed_lengths(tables, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets,
                                            buf.offsets_scratch, rows if w.backward else None, buf.status,
                                            streaming=w.streaming)

@@ -236,7 +236,7 @@ def test_split_backward_and_helper_argument_errors(L):
     assert fhl(*fhl_args(offs=None)) == INVALID and fhl(*fhl_args(lengths=None)) == INVALID
     assert fhl(*fhl_args(scratch=None)) == INVALID and fhl(*fhl_args(sb=64)) == INVALID
     assert fhl(*fhl_args(out=None)) == INVALID and fhl(*fhl_args(raw=None)) == INVALID
-    assert fhl(*fhl_args(mode=7)) == INVALID and fhl(*fhl_args(dtype=3)) == UNSUPPORTED
+    assert fhl(*fhl_args(mode=7)) == INVALID and fhl(*fhl_args(dtype=9)) == INVALID
     assert fhl(*fhl_args(B=600_000, sb=1 << 30)) == UNSUPPORTED       # 1.2 M bags: more than 256 tiles
     assert sp(d.ctypes.data, FAKE, 2, 64, 0, 4, 8, None, need, None, None, None, None, None, None) == WORKSPACE
     assert sp(d.ctypes.data, FAKE, 2, 3, 0, 4, 8, FAKE, need, None, None, None, None, None, None) == UNSUPPORTED

@@ -424,6 +424,15 @@ def test_hashed_forward_over_quantized_tables_equals_hashing_first(D, dtype):
     assert st.item() == 0 and np.array_equal(rows_d.cpu().numpy(), rows) and torch.equal(out1, out2)
     ref, absum, _ = oracle.bag_forward(qt, codes, rows, off, B, "mean", D=D)
     H.assert_pooled_close(out1.cpu().numpy(), ref, absum, what="hashed quantised forward %s D=%d" % (dtype, D))
+    # and from bag lengths, the offsets made on the way
+    out3 = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+    offs = torch.full((T * B + 1,), -9, dtype=torch.int64, device=H.DEV)
+    rows_d.fill_(-1)
+    scratch = torch.empty(emb.emb_offsets_scratch_bytes(T * B), dtype=torch.uint8, device=H.DEV)
+    emb.emb_bag_forward_hashed_lengths(ts, H.dev(raw), H.dev(lengths), B, "mean", out3, offs, scratch, rows_d, st)
+    torch.cuda.synchronize()
+    assert st.item() == 0 and torch.equal(out3, out1) and np.array_equal(offs.cpu().numpy(), off)
+    assert np.array_equal(rows_d.cpu().numpy(), rows)
 
 
 def test_forward_quantized_grid_tables_are_bit_exact_and_empty_batch():
