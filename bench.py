@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "bf6baaa13da5af89",
+    "sources": "91171d051dc23ef0",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (177594.2, 68981.0), "update_kernel": (240574.1, 323999.5)},
-        "3b": {"bag_forward_train_kernel": (94806.4, 83136.3), "update_kernel": (170582.7, 224710.5)},
-        "2": {"bag_forward_hashed_kernel": (176019.5, 33805.1), "bag_forward_kernel": (178015.1, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338189.3, 33793.5), "bag_forward_kernel": (338145.8, 32768.0)},
-        "2un": {"bag_forward_kernel": (346127.3, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (124402.2, 32801.3)},
-        "2uq4": {"bag_forward_quant_kernel": (233545.4, 32882.4)},
-        "2uq4r": {"bag_forward_quant_kernel": (191614.6, 32843.6)},
-        "4": {"bag_forward_hashed_kernel": (52684.9, 8704.5)},
+        "3": {"bag_forward_train_kernel": (177509.5, 69096.9), "update_kernel": (240558.4, 324004.6)},
+        "3b": {"bag_forward_train_kernel": (94672.5, 83116.3), "update_kernel": (170074.8, 220434.9)},
+        "2": {"bag_forward_hashed_kernel": (176294.7, 33801.9), "bag_forward_kernel": (177897.3, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338182.7, 33793.5), "bag_forward_kernel": (338144.1, 32768.0)},
+        "2un": {"bag_forward_kernel": (346126.4, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (122257.1, 33832.1)},
+        "2uq4": {"bag_forward_quant_kernel": (232562.3, 33925.5)},
+        "2uq4r": {"bag_forward_quant_kernel": (190414.4, 33872.6)},
+        "4": {"bag_forward_hashed_kernel": (52676.0, 8704.3)},
     },
 }
 
