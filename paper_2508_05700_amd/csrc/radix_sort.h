@@ -43,13 +43,17 @@ __device__ __forceinline__ void wave_rank_digits(const KeyT (&key)[SORT_ITEMS], 
         const uint64_t lv = __ballot(live);
         if (lv == 0) continue;            // uniform: the share ends before this step
         const uint32_t digit = (uint32_t)(key[k] >> shift) & (RADIX - 1);
-        uint64_t differ = 0;
+        // (kept as two 32-bit halves: a lane's own bit, spread over a word, serves both)
+        uint32_t differ_lo = 0, differ_hi = 0;
 #pragma unroll
         for (int bit = 0; bit < RADIX_BITS; ++bit) {
-            const uint64_t mine = 0ull - (uint64_t)((digit >> bit) & 1u);   // all ones if my bit is set
-            differ |= __ballot(mine != 0) ^ mine;
+            const uint32_t set = digit & (1u << bit);
+            const uint64_t with = __ballot(set != 0);
+            const uint32_t mine = set ? 0xFFFFFFFFu : 0u;   // all ones if my bit is set
+            differ_lo |= (uint32_t)with ^ mine;
+            differ_hi |= (uint32_t)(with >> 32) ^ mine;
         }
-        const uint64_t peers = lv & ~differ;   // dead lanes match nobody
+        const uint64_t peers = lv & ~(((uint64_t)differ_hi << 32) | differ_lo);   // dead lanes match nobody
         const uint32_t before = __popcll(peers & lt_mask);
         uint32_t prev = 0;
         if (live && before == 0) {  // lowest lane of each digit group updates the wavefront's counter
