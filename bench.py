@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "91171d051dc23ef0",
+    "sources": "0b291ff21997e378",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (177509.5, 69096.9), "update_kernel": (240558.4, 324004.6)},
-        "3b": {"bag_forward_train_kernel": (94672.5, 83116.3), "update_kernel": (170074.8, 220434.9)},
-        "2": {"bag_forward_hashed_kernel": (176294.7, 33801.9), "bag_forward_kernel": (177897.3, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338182.7, 33793.5), "bag_forward_kernel": (338144.1, 32768.0)},
-        "2un": {"bag_forward_kernel": (346126.4, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (122257.1, 33832.1)},
-        "2uq4": {"bag_forward_quant_kernel": (232562.3, 33925.5)},
-        "2uq4r": {"bag_forward_quant_kernel": (190414.4, 33872.6)},
-        "4": {"bag_forward_hashed_kernel": (52676.0, 8704.3)},
+        "3": {"bag_forward_train_kernel": (177526.4, 69043.2), "update_kernel": (240501.4, 324004.8)},
+        "3b": {"bag_forward_train_kernel": (94735.1, 83097.8), "update_kernel": (170137.9, 220407.0)},
+        "2": {"bag_forward_hashed_kernel": (176259.3, 33802.6), "bag_forward_kernel": (177947.4, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338181.5, 33793.5), "bag_forward_kernel": (338144.0, 32768.0)},
+        "2un": {"bag_forward_kernel": (346129.4, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (122280.5, 33830.7)},
+        "2uq4": {"bag_forward_quant_kernel": (232548.4, 33924.0)},
+        "2uq4r": {"bag_forward_quant_kernel": (190438.4, 33872.0)},
+        "4": {"bag_forward_hashed_kernel": (52664.8, 8704.2)},
     },
 }
 
