@@ -312,9 +312,21 @@ def bench_hybrid(args) -> int:
     log("setup: host table %d x %d %s (%.1f GB pinned), cache %d rows (%.2f GB), %.1f s" % (
         w.R, w.D, store, w.R * rowb / 1e9, n_hot, n_hot * rowb / 1e9, time.time() - t_setup))
 
+    from_lengths = (not args.no_fused_forward and not args.separate_offsets
+                    and w.B <= pipeline.LENGTHS_ROUTE_MAX_BAGS)
+    off_scratch = torch.empty(emb.emb_offsets_scratch_bytes(w.B), dtype=torch.uint8, device=dev)
+
     def step(db, e=None):
         if e:
             e[0].record()
+        if from_lengths:   # bag lengths in: the sums within tiles, then the lookup (index time counts with the lookup)
+            if e:
+                e[1].record()
+            emb.emb_bag_forward_cached_hashed_lengths(ptr, w.R, w.D, store, cache, index, n_hot, w.salt(0), db.raw,
+                                                      db.lengths, w.B, w.pool, out, offsets, off_scratch, hm, status)
+            if e:
+                e[2].record()
+            return
         emb.emb_lengths_to_offsets(db.lengths, offsets, status)
         if args.no_fused_forward:
             r = rows[:db.nnz]
@@ -446,7 +458,9 @@ def bench_hybrid(args) -> int:
                    "lookups_per_step": round(lookups / K, 1), "resident_batches": len(dbs), "seed": seed},
         "stages": {"index_ms": round(ms_index, 4), "forward_cached_ms": round(ms_fwd, 4),
                    "hit_rate": round(hits / max(1, hits + misses), 5), "misses_per_step": round(misses / K, 1)},
-        "roofline": {"kernel": "bag_forward_cached_quant_kernel" if w.quant else "bag_forward_cached_kernel",
+        "roofline": {"kernel": ("offsets_tile_scan_kernel + " if from_lengths else "") +
+                               ("bag_forward_cached_quant_kernel" if w.quant else "bag_forward_cached_kernel"),
+                     "bag_offsets": "made inside the lookup's call" if from_lengths else "separate launches",
                      "bound": "pcie", "achieved": round(pcie_gbs, 2),
                      "peak": PCIE_PEAK, "unit": "GB/s", "frac": round(pcie_gbs / PCIE_PEAK, 4), "traffic": None,
                      "avg_ms": round(ms_fwd, 4), "algorithmic_bytes": int(misses / K * rowb),
@@ -524,7 +538,18 @@ def bench_hybrid_tables(args) -> int:
     log("setup: %d host tables %d x %d %s (%.1f GB pinned in all), caches of %d rows each, %.1f s" % (
         w.T, w.R, w.D, store, w.T * w.R * rowb / 1e9, n_hot, time.time() - t_setup))
 
+    from_lengths = not args.separate_offsets and w.T * w.B <= pipeline.LENGTHS_ROUTE_MAX_BAGS
+    off_scratch = torch.empty(emb.emb_offsets_scratch_bytes(w.T * w.B), dtype=torch.uint8, device=dev)
+
     def step_one_launch(db, e=None):
+        if from_lengths:   # bag lengths in: the events bracket the sums within tiles and the lookup
+            if e:
+                e[0].record()
+            emb.emb_bag_forward_cached_tables_hashed_lengths(ct, db.raw, db.lengths, w.B, w.pool, out, offsets,
+                                                             off_scratch, hm, status)
+            if e:
+                e[1].record()
+            return
         emb.emb_lengths_to_offsets(db.lengths, offsets, status)
         if e:
             e[0].record()
@@ -580,7 +605,9 @@ def bench_hybrid_tables(args) -> int:
         "stages": {"forward_cached_tables_ms": round(ms_fwd, 4), "hit_rate": round(hits / max(1, hits + misses), 5),
                    "misses_per_step": round(misses / K, 1),
                    "one_lookup_per_table": {"ms_per_step": round(dt_pt / K * 1e3, 4), "lookups_ms": round(ms_pt, 4)}},
-        "roofline": {"kernel": "bag_forward_cached_tables_quant_kernel" if w.quant else "bag_forward_cached_tables_kernel",
+        "roofline": {"kernel": ("offsets_tile_scan_kernel + " if from_lengths else "") +
+                               ("bag_forward_cached_tables_quant_kernel" if w.quant else "bag_forward_cached_tables_kernel"),
+                     "bag_offsets": "made inside the lookup's call" if from_lengths else "separate launches",
                      "bound": "pcie", "achieved": round(pcie_gbs, 2), "peak": PCIE_PEAK, "unit": "GB/s",
                      "frac": round(pcie_gbs / PCIE_PEAK, 4), "traffic": None, "avg_ms": round(ms_fwd, 4),
                      "algorithmic_bytes": int(misses / K * rowb),

@@ -434,6 +434,26 @@ int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_rows, int32
                                   float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
                                   void *stream);
 
+/* emb_lengths_to_offsets and emb_bag_forward_cached_hashed in one call, for the
+ * hosted table what emb_bag_forward_hashed_lengths is for tables in HBM
+ * (Sections 2.2, 3.3, 3.4): the B bag lengths come in, the offsets (i64[B+1])
+ * go to offsets_out_dev, the sums within tiles go through scratch_dev
+ * (emb_offsets_scratch_bytes(B) bytes, 16-byte aligned, caller-owned) and the
+ * lookup adds the prefix sums of the tile totals itself.  Output, offsets,
+ * hit/miss counts and status bits equal those of the two calls.
+ * EMB_ERR_UNSUPPORTED for more than 1 048 576 bags.  nnz must be the sum of
+ * the lengths; a negative length counts as 0 and sets EMB_STATUS_BAD_OFFSETS;
+ * offsets_out_dev must not overlap lengths_dev or scratch_dev. */
+int emb_bag_forward_cached_hashed_lengths(const void *table_dev, int64_t num_rows, int32_t D,
+                                          int32_t dtype, const void *cache_rows_dev,
+                                          const void *cache_index_dev, int64_t num_hot,
+                                          uint64_t salt, const uint64_t *raw_dev,
+                                          const int32_t *lengths_dev, int64_t B, int64_t nnz,
+                                          int32_t mode, float *out_dev, int64_t *offsets_out_dev,
+                                          void *scratch_dev, size_t scratch_bytes,
+                                          uint64_t *hit_miss_dev, uint32_t *status_dev,
+                                          void *stream);
+
 /* The rows a hosted table's lookups miss in the cache, fetched ahead of the
  * lookups (Section 3.4: the fetch from CPU memory starts at the first moment
  * the ids are known and runs beside the rest of the request; Section 3.3 for
@@ -518,6 +538,16 @@ int emb_bag_forward_cached_tables_hashed(const emb_cached_table *tables_host,
                                          const int64_t *offsets_dev, int64_t B, int64_t nnz,
                                          int32_t mode, float *out_dev, uint64_t *hit_miss_dev,
                                          uint32_t *status_dev, void *stream);
+
+/* emb_bag_forward_cached_tables_hashed from the T*B bag lengths, in the manner
+ * of emb_bag_forward_cached_hashed_lengths: offsets_out_dev is i64[T*B+1],
+ * scratch_dev holds emb_offsets_scratch_bytes(T*B) bytes, at most 1 048 576
+ * bags over all tables (EMB_ERR_UNSUPPORTED beyond). */
+int emb_bag_forward_cached_tables_hashed_lengths(
+    const emb_cached_table *tables_host, const emb_cached_table *tables_dev, int32_t T, int32_t D,
+    int32_t dtype, const uint64_t *raw_dev, const int32_t *lengths_dev, int64_t B, int64_t nnz,
+    int32_t mode, float *out_dev, int64_t *offsets_out_dev, void *scratch_dev, size_t scratch_bytes,
+    uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream);
 
 /* ---- which rows the cache holds: frequency-based policy -------------------
  * Section 6 lists better caching strategies as open work and the paper names

@@ -48,13 +48,13 @@ EXPORTS = [
     "emb_bag_backward_sort", "emb_bag_backward_update", "emb_bag_forward_train", "emb_bag_forward_train_lengths", "emb_offsets_scratch_bytes", "emb_bag_forward_hashed_lengths", "emb_bag_backward_sort_prepared", "emb_row_bytes", "emb_quantize_rows",
     "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
-    "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_host_device_pointer",
+    "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_bag_forward_cached_hashed_lengths", "emb_host_device_pointer",
     "emb_cache_stage_misses", "emb_cache_stage_misses_hashed", "emb_bag_forward_staged",
     "emb_version_record_bytes", "emb_version_latch_bytes", "emb_version_record_write", "emb_version_publish",
     "emb_version_latch", "emb_bag_forward_latched", "emb_bag_forward_latched_hashed",
     "emb_version_hosted_record_bytes", "emb_version_hosted_latch_bytes", "emb_version_hosted_record_write",
     "emb_version_hosted_latch", "emb_bag_forward_cached_latched", "emb_bag_forward_cached_latched_hashed",
-    "emb_cached_tables_init", "emb_bag_forward_cached_tables", "emb_bag_forward_cached_tables_hashed",
+    "emb_cached_tables_init", "emb_bag_forward_cached_tables", "emb_bag_forward_cached_tables_hashed", "emb_bag_forward_cached_tables_hashed_lengths",
     "emb_cache_observe", "emb_cache_observe_hashed", "emb_cache_select_workspace_bytes", "emb_cache_select", "emb_cache_select_static",
     "emb_cache_rebuild",
     "emb_table_fill", "emb_checksum",
@@ -197,6 +197,12 @@ def lib() -> C.CDLL:
     L.emb_cached_tables_init.argtypes = [vp, i32]
     L.emb_bag_forward_cached_tables.restype = C.c_int
     L.emb_bag_forward_cached_tables.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
+    L.emb_bag_forward_cached_tables_hashed_lengths.restype = C.c_int
+    L.emb_bag_forward_cached_tables_hashed_lengths.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp,
+                                                               sz, vp, vp, vp]
+    L.emb_bag_forward_cached_hashed_lengths.restype = C.c_int
+    L.emb_bag_forward_cached_hashed_lengths.argtypes = [vp, i64, i32, i32, vp, vp, i64, u64, vp, vp, i64, i64, i32, vp,
+                                                        vp, vp, sz, vp, vp, vp]
     L.emb_bag_forward_cached_tables_hashed.restype = C.c_int
     L.emb_bag_forward_cached_tables_hashed.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     L.emb_checksum.restype = C.c_int
@@ -652,6 +658,25 @@ def emb_bag_forward_cached_hashed(table_ptr: int, num_rows: int, D: int, dtype: 
         _stream()))
 
 
+def emb_bag_forward_cached_hashed_lengths(table_ptr: int, num_rows: int, D: int, dtype: str, cache_rows: torch.Tensor,
+                                          cache_index: torch.Tensor, num_hot: int, salt: int, raw: torch.Tensor,
+                                          lengths: torch.Tensor, B: int, mode: str, out: torch.Tensor,
+                                          offsets_out: torch.Tensor, scratch: torch.Tensor,
+                                          hit_miss: Optional[torch.Tensor] = None,
+                                          status: Optional[torch.Tensor] = None) -> None:
+    """``emb_bag_forward_cached_hashed`` from the ``B`` bag lengths; writes the offsets to ``offsets_out``;
+    ``scratch`` holds ``emb_offsets_scratch_bytes(B)`` bytes."""
+    if lengths.numel() != B or offsets_out.numel() != B + 1 or out.numel() != B * D:
+        raise TypeError("shape mismatch")
+    _check("emb_bag_forward_cached_hashed_lengths", lib().emb_bag_forward_cached_hashed_lengths(
+        int(table_ptr), int(num_rows), int(D), DTYPE[dtype], _ptr(cache_rows, _TABLE_TORCH[dtype], "cache_rows"),
+        _ptr(cache_index, torch.uint8, "cache_index"), int(num_hot), C.c_uint64(int(salt) % (1 << 64)),
+        _ptr(raw, _U64, "raw"), _ptr(lengths, torch.int32, "lengths") if B else None, int(B), raw.numel(), POOL[mode],
+        _ptr(out, torch.float32, "out"), _ptr(offsets_out, torch.int64, "offsets_out"),
+        _ptr(scratch, torch.uint8, "scratch"), scratch.numel(), _ptr(hit_miss, _U64, "hit_miss"),
+        _ptr(status, torch.int32, "status"), _stream()))
+
+
 def emb_cache_stage_misses(table_ptr: int, num_rows: int, D: int, dtype: str, cache_index: torch.Tensor, num_hot: int,
                            ids: torch.Tensor, stage_rows: Optional[torch.Tensor], stage_capacity: int, loc: torch.Tensor,
                            stage_count: torch.Tensor, status: Optional[torch.Tensor] = None,
@@ -855,6 +880,23 @@ def emb_bag_forward_cached_tables_hashed(ct: CachedTables, raw: torch.Tensor, of
                                          status: Optional[torch.Tensor] = None) -> None:
     _forward_cached_tables("emb_bag_forward_cached_tables_hashed", ct, raw, _U64, offsets, B, mode, out, hit_miss,
                            status)
+
+
+def emb_bag_forward_cached_tables_hashed_lengths(ct: CachedTables, raw: torch.Tensor, lengths: torch.Tensor, B: int,
+                                                 mode: str, out: torch.Tensor, offsets_out: torch.Tensor,
+                                                 scratch: torch.Tensor, hit_miss: Optional[torch.Tensor] = None,
+                                                 status: Optional[torch.Tensor] = None) -> None:
+    """``emb_bag_forward_cached_tables_hashed`` from the ``T * B`` bag lengths; writes the offsets to
+    ``offsets_out``; ``scratch`` holds ``emb_offsets_scratch_bytes(T * B)`` bytes."""
+    n = ct.T * B
+    if lengths.numel() != n or offsets_out.numel() != n + 1 or out.numel() != n * ct.D:
+        raise TypeError("shape mismatch")
+    _check("emb_bag_forward_cached_tables_hashed_lengths", lib().emb_bag_forward_cached_tables_hashed_lengths(
+        int(ct.host.ctypes.data), int(ct.dev.data_ptr()), ct.T, ct.D, DTYPE[ct.dtype], _ptr(raw, _U64, "raw"),
+        _ptr(lengths, torch.int32, "lengths") if n else None, int(B), raw.numel(), POOL[mode],
+        _ptr(out, torch.float32, "out"), _ptr(offsets_out, torch.int64, "offsets_out"),
+        _ptr(scratch, torch.uint8, "scratch"), scratch.numel(), _ptr(hit_miss, _U64, "hit_miss"),
+        _ptr(status, torch.int32, "status"), _stream()))
 
 
 def emb_checksum(data, sum_out: torch.Tensor, nbytes: Optional[int] = None) -> None:

@@ -133,6 +133,28 @@ struct CachedSource {
 
 constexpr int CF_BLOCK = 256;
 
+// Bounds of bag `bag` for the cached lookups.  offsets_out == NULL: `offsets` are the final offsets.
+// Otherwise (the calls that take bag lengths) `offsets` holds the sums within tiles of lengths, the bounds
+// come from emb_two_level_bounds and the final offsets are written to offsets_out.  Every thread of the
+// workgroup calls this; the choice is uniform over the launch.
+template <int BLOCK>
+__device__ __forceinline__ void cached_bag_bounds(const int64_t *__restrict__ offsets, int64_t *__restrict__ offsets_out,
+                                                  int64_t n_bags, bool live, int64_t bag, int l, int64_t *tile_prefix,
+                                                  int64_t *wave_sums, int64_t &s, int64_t &e)
+{
+    s = e = 0;
+    if (offsets_out) {
+        emb_two_level_bounds<BLOCK>(offsets, n_bags, live, bag, tile_prefix, wave_sums, s, e);
+        if (live && l == 0) {
+            offsets_out[bag + 1] = e;
+            if (bag == 0) offsets_out[0] = 0;
+        }
+    } else if (live) {
+        s = offsets[bag];
+        e = offsets[bag + 1];
+    }
+}
+
 template <int LPR, int CPL, int UNROLL, bool BF16>
 __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_kernel(const char *__restrict__ table,
                                                                       const char *__restrict__ cache_rows,
@@ -143,16 +165,21 @@ __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_kernel(const char
                                                                       int32_t chunks_per_row, int32_t mode,
                                                                       float *__restrict__ out,
                                                                       unsigned long long *hit_miss, uint32_t *status,
-                                                                      bool hashed, uint64_t salt, uint64_t magic)
+                                                                      bool hashed, uint64_t salt, uint64_t magic,
+                                                                      int64_t *__restrict__ offsets_out)
 {
+    __shared__ int64_t tile_prefix[CF_BLOCK];
+    __shared__ int64_t wave_sums[CF_BLOCK / EMB_WAVE];
     constexpr int GROUPS = CF_BLOCK / LPR;
     const int l = threadIdx.x % LPR;
     const int64_t b = (int64_t)blockIdx.x * GROUPS + threadIdx.x / LPR;
     CachedSource src{table,  cache_rows, index, (uint64_t)num_rows, (uint64_t)num_hot, (int64_t)chunks_per_row * 16,
                      status, 0u,         0u,    hashed,             salt,              magic};
     constexpr int F = ChunkAcc<BF16>::FLOATS;
-    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, b, l, nnz, rows, offsets, chunks_per_row, mode,
-                                            out + b * ((int64_t)chunks_per_row * F), status);
+    int64_t s, e;
+    cached_bag_bounds<CF_BLOCK>(offsets, offsets_out, B, b < B, b, l, tile_prefix, wave_sums, s, e);
+    gather_pool_range<LPR, CPL, UNROLL, BF16>(src, b < B, s, e, l, nnz, rows, chunks_per_row, mode,
+                                              out + b * ((int64_t)chunks_per_row * F), status);
     cache_add_hit_miss(src.hits, src.misses, hit_miss);
 }
 
@@ -160,18 +187,18 @@ template <int LPR, int CPL, int UNROLL>
 int launch_cached(bool bf16, hipStream_t s, const char *table, const char *cache_rows, const CacheEntry *index,
                   int64_t num_rows, int64_t num_hot, int64_t B, int64_t nnz, const int64_t *rows,
                   const int64_t *offsets, int32_t chunks, int32_t mode, float *out, unsigned long long *hit_miss,
-                  uint32_t *status, bool hashed, uint64_t salt, uint64_t magic)
+                  uint32_t *status, bool hashed, uint64_t salt, uint64_t magic, int64_t *offsets_out)
 {
     constexpr int GROUPS = CF_BLOCK / LPR;
     dim3 grid((unsigned)((B + GROUPS - 1) / GROUPS));
     if (bf16)
         hipLaunchKernelGGL((bag_forward_cached_kernel<LPR, CPL, UNROLL, true>), grid, dim3(CF_BLOCK), 0, s, table,
                            cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, chunks, mode, out, hit_miss, status,
-                           hashed, salt, magic);
+                           hashed, salt, magic, offsets_out);
     else
         hipLaunchKernelGGL((bag_forward_cached_kernel<LPR, CPL, UNROLL, false>), grid, dim3(CF_BLOCK), 0, s, table,
                            cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, chunks, mode, out, hit_miss, status,
-                           hashed, salt, magic);
+                           hashed, salt, magic, offsets_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -186,14 +213,19 @@ __global__ __launch_bounds__(Q_BLOCK) void bag_forward_cached_quant_kernel(const
                                                                            int32_t D, int64_t row_bytes, int32_t mode,
                                                                            float *__restrict__ out,
                                                                            unsigned long long *hit_miss, uint32_t *status,
-                                                                           bool hashed, uint64_t salt, uint64_t magic)
+                                                                           bool hashed, uint64_t salt, uint64_t magic,
+                                                                           int64_t *__restrict__ offsets_out)
 {
+    __shared__ int64_t tile_prefix[Q_BLOCK];
+    __shared__ int64_t wave_sums[Q_BLOCK / EMB_WAVE];
     constexpr int GROUPS = Q_BLOCK / LPR;
     const int l = threadIdx.x % LPR;
     const int64_t b = (int64_t)blockIdx.x * GROUPS + threadIdx.x / LPR;
     CachedSource src{table, cache_rows, index, (uint64_t)num_rows, (uint64_t)num_hot, row_bytes, status, 0u, 0u,
                      hashed, salt, magic};
-    gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, b, l, nnz, rows, offsets, D, mode, out, status);
+    int64_t s, e;
+    cached_bag_bounds<Q_BLOCK>(offsets, offsets_out, B, b < B, b, l, tile_prefix, wave_sums, s, e);
+    gather_dequant_pool_range<LPR, BITS, UNROLL>(src, b < B, b, s, e, l, nnz, rows, D, mode, out, status);
     cache_add_hit_miss(src.hits, src.misses, hit_miss);
 }
 
@@ -201,14 +233,15 @@ template <int BITS>
 int dispatch_cached_quant(int lpr, hipStream_t s, const char *table, const char *cache_rows, const CacheEntry *index,
                           int64_t num_rows, int64_t num_hot, int64_t B, int64_t nnz, const int64_t *rows,
                           const int64_t *offsets, int32_t D, int64_t row_bytes, int32_t mode, float *out,
-                          unsigned long long *hit_miss, uint32_t *status, bool hashed, uint64_t salt, uint64_t magic)
+                          unsigned long long *hit_miss, uint32_t *status, bool hashed, uint64_t salt, uint64_t magic,
+                          int64_t *offsets_out)
 {
 #define EMB_CQ(L)                                                                                                   \
     do {                                                                                                            \
         constexpr int GROUPS = Q_BLOCK / L;                                                                         \
         hipLaunchKernelGGL((bag_forward_cached_quant_kernel<L, BITS, 8>), dim3((unsigned)((B + GROUPS - 1) / GROUPS)), \
                            dim3(Q_BLOCK), 0, s, table, cache_rows, index, num_rows, num_hot, B, nnz, rows, offsets, D, \
-                           row_bytes, mode, out, hit_miss, status, hashed, salt, magic);                            \
+                           row_bytes, mode, out, hit_miss, status, hashed, salt, magic, offsets_out);               \
         EMB_RETURN_IF_LAUNCH_FAILED();                                                                              \
         return EMB_OK;                                                                                              \
     } while (0)
@@ -249,8 +282,11 @@ template <int LPR, int CPL, int UNROLL, bool BF16>
 __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_tables_kernel(
     const emb_cached_table *__restrict__ tables, int64_t B, uint32_t blocks_per_table, int64_t nnz,
     const int64_t *__restrict__ ids, const int64_t *__restrict__ offsets, int32_t chunks_per_row, int32_t mode,
-    float *__restrict__ out, unsigned long long *hit_miss, uint32_t *status, bool hashed)
+    float *__restrict__ out, unsigned long long *hit_miss, uint32_t *status, bool hashed, int32_t T,
+    int64_t *__restrict__ offsets_out)
 {
+    __shared__ int64_t tile_prefix[CF_BLOCK];
+    __shared__ int64_t wave_sums[CF_BLOCK / EMB_WAVE];
     constexpr int GROUPS = CF_BLOCK / LPR;
     const uint32_t t = blockIdx.x / blocks_per_table;   // the grid is exactly T * blocks_per_table
     const int l = threadIdx.x % LPR;
@@ -259,8 +295,10 @@ __global__ __launch_bounds__(CF_BLOCK) void bag_forward_cached_tables_kernel(
     CachedSource src = cached_source_of(tb, (int64_t)chunks_per_row * 16, status, hashed);
     constexpr int F = ChunkAcc<BF16>::FLOATS;
     const int64_t bag = (int64_t)t * B + b;
-    gather_pool_bag<LPR, CPL, UNROLL, BF16>(src, b < B, bag, l, nnz, ids, offsets, chunks_per_row, mode,
-                                            out + bag * ((int64_t)chunks_per_row * F), status);
+    int64_t s, e;
+    cached_bag_bounds<CF_BLOCK>(offsets, offsets_out, (int64_t)T * B, b < B, bag, l, tile_prefix, wave_sums, s, e);
+    gather_pool_range<LPR, CPL, UNROLL, BF16>(src, b < B, s, e, l, nnz, ids, chunks_per_row, mode,
+                                              out + bag * ((int64_t)chunks_per_row * F), status);
     cache_add_hit_miss(src.hits, src.misses, hit_miss);
 }
 
@@ -268,15 +306,21 @@ template <int LPR, int BITS, int UNROLL>
 __global__ __launch_bounds__(Q_BLOCK) void bag_forward_cached_tables_quant_kernel(
     const emb_cached_table *__restrict__ tables, int64_t B, uint32_t blocks_per_table, int64_t nnz,
     const int64_t *__restrict__ ids, const int64_t *__restrict__ offsets, int32_t D, int64_t row_bytes, int32_t mode,
-    float *__restrict__ out, unsigned long long *hit_miss, uint32_t *status, bool hashed)
+    float *__restrict__ out, unsigned long long *hit_miss, uint32_t *status, bool hashed, int32_t T,
+    int64_t *__restrict__ offsets_out)
 {
+    __shared__ int64_t tile_prefix[Q_BLOCK];
+    __shared__ int64_t wave_sums[Q_BLOCK / EMB_WAVE];
     constexpr int GROUPS = Q_BLOCK / LPR;
     const uint32_t t = blockIdx.x / blocks_per_table;
     const int l = threadIdx.x % LPR;
     const int64_t b = (int64_t)(blockIdx.x % blocks_per_table) * GROUPS + threadIdx.x / LPR;
     const emb_cached_table tb = tables[t];
     CachedSource src = cached_source_of(tb, row_bytes, status, hashed);
-    gather_dequant_pool_bag<LPR, BITS, UNROLL>(src, b < B, (int64_t)t * B + b, l, nnz, ids, offsets, D, mode, out, status);
+    const int64_t bag = (int64_t)t * B + b;
+    int64_t s, e;
+    cached_bag_bounds<Q_BLOCK>(offsets, offsets_out, (int64_t)T * B, b < B, bag, l, tile_prefix, wave_sums, s, e);
+    gather_dequant_pool_range<LPR, BITS, UNROLL>(src, b < B, bag, s, e, l, nnz, ids, D, mode, out, status);
     cache_add_hit_miss(src.hits, src.misses, hit_miss);
 }
 
@@ -292,6 +336,7 @@ struct CachedTablesArgs {
     uint32_t *status;
     bool hashed;
     hipStream_t s;
+    int64_t *offsets_out;   // NULL: `offsets` are final; else they are sums within tiles and the offsets go here
 };
 
 template <int LPR, int CPL, int UNROLL>
@@ -305,11 +350,11 @@ int launch_cached_tables(const CachedTablesArgs &a, bool bf16)
     if (bf16)
         hipLaunchKernelGGL((bag_forward_cached_tables_kernel<LPR, CPL, UNROLL, true>), grid, dim3(CF_BLOCK), 0, a.s,
                            a.tables, a.B, (uint32_t)per_table, a.nnz, a.ids, a.offsets, chunks, a.mode, a.out, a.hit_miss,
-                           a.status, a.hashed);
+                           a.status, a.hashed, a.T, a.offsets_out);
     else
         hipLaunchKernelGGL((bag_forward_cached_tables_kernel<LPR, CPL, UNROLL, false>), grid, dim3(CF_BLOCK), 0, a.s,
                            a.tables, a.B, (uint32_t)per_table, a.nnz, a.ids, a.offsets, chunks, a.mode, a.out, a.hit_miss,
-                           a.status, a.hashed);
+                           a.status, a.hashed, a.T, a.offsets_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -322,7 +367,7 @@ int launch_cached_tables_quant(const CachedTablesArgs &a)
     if (per_table * a.T > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((bag_forward_cached_tables_quant_kernel<LPR, BITS, 8>), dim3((unsigned)(per_table * a.T)),
                        dim3(Q_BLOCK), 0, a.s, a.tables, a.B, (uint32_t)per_table, a.nnz, a.ids, a.offsets, a.D,
-                       a.row_bytes, a.mode, a.out, a.hit_miss, a.status, a.hashed);
+                       a.row_bytes, a.mode, a.out, a.hit_miss, a.status, a.hashed, a.T, a.offsets_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
     return EMB_OK;
 }
@@ -433,7 +478,8 @@ extern "C" int emb_cache_rebuild(const void *table_dev, int64_t num_rows, int32_
 static int cached_entry(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype, const void *cache_rows_dev,
                         const void *cache_index_dev, int64_t num_hot, const int64_t *rows_dev,
                         const int64_t *offsets_dev, int64_t B, int64_t nnz, int32_t mode, float *out_dev,
-                        uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream, bool hashed, uint64_t salt)
+                        uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream, bool hashed, uint64_t salt,
+                        int64_t *offsets_out_dev = nullptr)
 {
     const uint64_t magic = num_rows > 0 ? emb_mod_magic((uint64_t)num_rows) : 0;
     if (B < 0 || nnz < 0 || num_rows <= 0 || num_hot < 0) return EMB_ERR_INVALID_ARG;
@@ -457,9 +503,9 @@ static int cached_entry(const void *table_dev, int64_t num_rows, int32_t D, int3
         unsigned long long *hm = reinterpret_cast<unsigned long long *>(hit_miss_dev);
         if (emb_quant_bits(dtype) == 8)
             return dispatch_cached_quant<8>(ql, s, tp, cp, ip, num_rows, num_hot, B, nnz, rows_dev, offsets_dev, D, rb,
-                                            mode, out_dev, hm, status_dev, hashed, salt, magic);
+                                            mode, out_dev, hm, status_dev, hashed, salt, magic, offsets_out_dev);
         return dispatch_cached_quant<4>(ql, s, tp, cp, ip, num_rows, num_hot, B, nnz, rows_dev, offsets_dev, D, rb, mode,
-                                        out_dev, hm, status_dev, hashed, salt, magic);
+                                        out_dev, hm, status_dev, hashed, salt, magic, offsets_out_dev);
     }
     const int chunks = D * emb_elem_size(dtype) / 16;
     int lpr, cpl;
@@ -470,7 +516,8 @@ static int cached_entry(const void *table_dev, int64_t num_rows, int32_t D, int3
                                   reinterpret_cast<const char *>(cache_rows_dev),                               \
                                   reinterpret_cast<const CacheEntry *>(cache_index_dev), num_rows, num_hot, B, nnz, \
                                   rows_dev, offsets_dev, chunks, mode, out_dev,                                  \
-                                  reinterpret_cast<unsigned long long *>(hit_miss_dev), status_dev, hashed, salt, magic)
+                                  reinterpret_cast<unsigned long long *>(hit_miss_dev), status_dev, hashed, salt, magic, \
+                                  offsets_out_dev)
     if (cpl == 1) {
         switch (lpr) {
             case 1: EMB_CF(1, 1, 8);
@@ -512,6 +559,50 @@ extern "C" int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_
                         status_dev, stream, true, salt);
 }
 
+// The calls that take bag lengths: argument checks they share, then the sums within tiles into the scratch
+// array (with no bags at all, the single offset 0 straight to the caller).  Returns > 0 when nothing is left
+// to do.  `local` receives where the lookup finds the sums.
+static int lengths_front(const int32_t *lengths_dev, int64_t n, int64_t *offsets_out_dev, void *scratch_dev,
+                         size_t scratch_bytes, uint32_t *status_dev, void *stream, const int64_t **local)
+{
+    if (n < 0 || !offsets_out_dev) return EMB_ERR_INVALID_ARG;
+    if (n > (int64_t)CF_BLOCK * EMB_OFFSETS_TILE) return EMB_ERR_UNSUPPORTED;   // more tiles than a workgroup scans
+    if (n > 0 && (!lengths_dev || !scratch_dev || !emb_aligned(scratch_dev, 16) || scratch_bytes < ((size_t)n + 1) * 8))
+        return EMB_ERR_INVALID_ARG;
+    int64_t *dst = n == 0 ? offsets_out_dev : reinterpret_cast<int64_t *>(scratch_dev);
+    *local = dst;
+    const int rc = emb_offsets_tile_sums(lengths_dev, n, dst, status_dev, emb_stream(stream));
+    if (rc != EMB_OK) return rc;
+    return n == 0 ? 1 : EMB_OK;
+}
+static_assert(CF_BLOCK == Q_BLOCK, "the cached lookups over plain and quantised rows scan the same number of tiles");
+
+extern "C" int emb_bag_forward_cached_hashed_lengths(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
+                                                     const void *cache_rows_dev, const void *cache_index_dev,
+                                                     int64_t num_hot, uint64_t salt, const uint64_t *raw_dev,
+                                                     const int32_t *lengths_dev, int64_t B, int64_t nnz, int32_t mode,
+                                                     float *out_dev, int64_t *offsets_out_dev, void *scratch_dev,
+                                                     size_t scratch_bytes, uint64_t *hit_miss_dev,
+                                                     uint32_t *status_dev, void *stream)
+{
+    // everything the lookup itself would refuse is refused before the first launch: a dry call without bags
+    int rc = cached_entry(table_dev, num_rows, D, dtype, cache_rows_dev, cache_index_dev, num_hot, nullptr, nullptr, 0,
+                          nnz, mode, nullptr, nullptr, nullptr, nullptr, true, salt);
+    if (rc != EMB_OK) return rc;
+    if (B < 0) return EMB_ERR_INVALID_ARG;
+    if (B > 0 && (!table_dev || !cache_index_dev || (num_hot > 0 && !cache_rows_dev) || !out_dev ||
+                  !emb_aligned(table_dev, 16) || !emb_aligned(cache_index_dev, 16) || !emb_aligned(cache_rows_dev, 16) ||
+                  !emb_aligned(out_dev, 16) || (nnz > 0 && !raw_dev)))
+        return EMB_ERR_INVALID_ARG;
+    if (B > (int64_t)0x7FFFFFFF) return EMB_ERR_UNSUPPORTED;
+    const int64_t *local = nullptr;
+    rc = lengths_front(lengths_dev, B, offsets_out_dev, scratch_dev, scratch_bytes, status_dev, stream, &local);
+    if (rc != EMB_OK) return rc > 0 ? EMB_OK : rc;
+    return cached_entry(table_dev, num_rows, D, dtype, cache_rows_dev, cache_index_dev, num_hot,
+                        reinterpret_cast<const int64_t *>(raw_dev), local, B, nnz, mode, out_dev, hit_miss_dev,
+                        status_dev, stream, true, salt, offsets_out_dev);
+}
+
 extern "C" int emb_cached_tables_init(emb_cached_table *tables_host, int32_t T)
 {
     if (T < 0 || (T > 0 && !tables_host)) return EMB_ERR_INVALID_ARG;
@@ -538,12 +629,39 @@ static int cached_tables_entry(const emb_cached_table *th, const emb_cached_tabl
                                                status_dev, stream, hashed);
 }
 
+extern "C" int emb_bag_forward_cached_tables_hashed_lengths(const emb_cached_table *tables_host,
+                                                            const emb_cached_table *tables_dev, int32_t T, int32_t D,
+                                                            int32_t dtype, const uint64_t *raw_dev,
+                                                            const int32_t *lengths_dev, int64_t B, int64_t nnz,
+                                                            int32_t mode, float *out_dev, int64_t *offsets_out_dev,
+                                                            void *scratch_dev, size_t scratch_bytes,
+                                                            uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream)
+{
+    if (T < 0 || B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
+    if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
+    int rc = cached_row_shape(D, dtype);
+    if (rc != EMB_OK) return rc;
+    if (B > (int64_t)0x7FFFFFFF || T > 65535) return EMB_ERR_UNSUPPORTED;
+    const int64_t n = (int64_t)T * B;
+    if (n > 0) {
+        rc = emb_check_cached_tables(tables_host, tables_dev, T);
+        if (rc != EMB_OK) return rc;
+        if (!out_dev || !emb_aligned(out_dev, 16) || (nnz > 0 && !raw_dev)) return EMB_ERR_INVALID_ARG;
+    }
+    const int64_t *local = nullptr;
+    rc = lengths_front(lengths_dev, n, offsets_out_dev, scratch_dev, scratch_bytes, status_dev, stream, &local);
+    if (rc != EMB_OK) return rc > 0 ? EMB_OK : rc;
+    return emb_forward_cached_unchecked_tables(tables_dev, T, D, dtype, reinterpret_cast<const int64_t *>(raw_dev), local,
+                                               B, nnz, mode, out_dev, hit_miss_dev, status_dev, stream, true,
+                                               offsets_out_dev);
+}
+
 // The launch of the multi-table cached lookup over descriptors that live in device memory only and
 // were validated when they were written (the latched copy of a hosted version record, versioned.hip).
 int emb_forward_cached_unchecked_tables(const emb_cached_table *td, int32_t T, int32_t D, int32_t dtype,
                                         const int64_t *ids_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
                                         int32_t mode, float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
-                                        void *stream, bool hashed)
+                                        void *stream, bool hashed, int64_t *offsets_out_dev)
 {
     if (T < 0 || B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
@@ -556,7 +674,8 @@ int emb_forward_cached_unchecked_tables(const emb_cached_table *td, int32_t T, i
     if (B > (int64_t)0x7FFFFFFF || T > 65535) return EMB_ERR_UNSUPPORTED;
 
     CachedTablesArgs a{td,      T,      B,         nnz,  ids_dev, offsets_dev, D, mode, emb_row_bytes(D, dtype),
-                       out_dev, reinterpret_cast<unsigned long long *>(hit_miss_dev), status_dev, hashed, emb_stream(stream)};
+                       out_dev, reinterpret_cast<unsigned long long *>(hit_miss_dev), status_dev, hashed, emb_stream(stream),
+                       offsets_out_dev};
     if (emb_is_quant(dtype))
         return emb_quant_bits(dtype) == 8 ? dispatch_cached_tables_quant<8>(emb_quant_lanes(D), a)
                                           : dispatch_cached_tables_quant<4>(emb_quant_lanes(D), a);

@@ -98,11 +98,12 @@ static inline int emb_check_cached_tables(const emb_cached_table *th, const emb_
 }
 
 // emb_bag_forward_cached_tables / _hashed over descriptors that exist in device memory only and were
-// validated earlier (the latched copy of a hosted version record; versioned.hip).
+// validated earlier (the latched copy of a hosted version record; versioned.hip).  With offsets_out_dev,
+// offsets_dev holds sums within tiles (emb_offsets_tile_sums) and the lookup writes the offsets there.
 int emb_forward_cached_unchecked_tables(const emb_cached_table *tables_dev, int32_t T, int32_t D, int32_t dtype,
                                         const int64_t *ids_dev, const int64_t *offsets_dev, int64_t B, int64_t nnz,
                                         int32_t mode, float *out_dev, uint64_t *hit_miss_dev, uint32_t *status_dev,
-                                        void *stream, bool hashed);
+                                        void *stream, bool hashed, int64_t *offsets_out_dev = nullptr);
 
 // Row-quantised storage types and the bits of one of their codes (EMB_INT4_ROW64
 // differs from EMB_INT4 in the row stride only).

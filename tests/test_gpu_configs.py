@@ -340,6 +340,7 @@ def _hybrid_parity(w, say_name):
     assert hm.cpu().tolist() == [hits, misses]                         # bit-exact hit/miss counts
     H.assert_pooled_close(out.cpu().numpy(), ref, absum, what=say_name)
     say("%s: %d hits, %d misses (%.1f %% hit rate)" % (say_name, hits, misses, 100.0 * hits / max(1, hits + misses)))
+    _check_cached_from_lengths(w, "f32", ptr, cache, index, K, db, off, out, hm, say_name)
 
     # the route with the misses fetched ahead: three batches staged by one launch (raw IDs), then one pooled lookup
     # per batch over HBM only; every batch against the oracle's cached lookup of that batch
@@ -441,7 +442,23 @@ def test_workload_5q4_int4_host_table_with_hbm_cache():
     assert st == 0
     assert hm.cpu().tolist() == [hits, misses]
     H.assert_pooled_close(out.cpu().numpy(), ref, absum, what="workload 5q4")
+    _check_cached_from_lengths(w, w.quant, ptr, cache, index, K, db, off, out, hm, "5q4")
     assert 0.85 < hits / max(1, hits + misses) < 0.97
+
+
+def _check_cached_from_lengths(w, store, ptr, cache, index, K, db, off, out, hm, name):
+    """The call the bench times for a hosted table: raw IDs and bag lengths in.  Offsets against the oracle's,
+    pooled output and hit/miss counts bit for bit against the (oracle-checked) lookup over hashed rows."""
+    out2 = torch.full_like(out, float("nan"))
+    hm2 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    off2 = torch.full((w.B + 1,), -1, dtype=torch.int64, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    scratch = torch.empty(emb.emb_offsets_scratch_bytes(w.B), dtype=torch.uint8, device=H.DEV)
+    emb.emb_bag_forward_cached_hashed_lengths(ptr, w.R, w.D, store, cache, index, K, w.salt(0), db.raw, db.lengths, w.B,
+                                              w.pool, out2, off2, scratch, hm2, status)
+    torch.cuda.synchronize()
+    assert status.item() == 0 and np.array_equal(off2.cpu().numpy(), off), name
+    assert torch.equal(out2, out) and torch.equal(hm2, hm), name
 
 
 def test_workload_5q4_cache_policy_at_full_size():
@@ -575,6 +592,15 @@ def test_workload_5mq4_four_hosted_int4_tables_in_one_launch():
         hits, misses = hits + h, misses + m
     assert hm.cpu().tolist() == [hits, misses]
     say("5mq4: %d hits, %d misses" % (hits, misses))
+    # the call the bench times: the same lookup from the bag lengths (offsets made on the way), bit for bit
+    out2 = torch.full_like(out, float("nan"))
+    hm2 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+    off2 = torch.full_like(off_dev, -1)
+    scratch = torch.empty(emb.emb_offsets_scratch_bytes(w.T * w.B), dtype=torch.uint8, device=H.DEV)
+    emb.emb_bag_forward_cached_tables_hashed_lengths(ct, db.raw, db.lengths, w.B, w.pool, out2, off2, scratch, hm2, status)
+    torch.cuda.synchronize()
+    assert status.item() == 0 and np.array_equal(off2.cpu().numpy(), off)
+    assert torch.equal(out2, out) and torch.equal(hm2, hm)
     assert 0.8 < hits / max(1, hits + misses) < 0.97
 
 

@@ -1847,6 +1847,112 @@ def test_cached_forward_over_several_tables_in_one_launch(dtype, D):
             assert np.array_equal(one.cpu().numpy()[0], got[t])
         assert hm.cpu().tolist() == [hits, misses] and int(status.item()) == st_all
         assert st_all == (0 if hashed else emb.STATUS_BAD_INDEX)
+        if hashed:
+            # the same from the bag lengths: offsets written, same bits, same counts
+            o2 = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+            hm2 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+            off2 = torch.full((T * B + 1,), -1, dtype=torch.int64, device=H.DEV)
+            scratch = torch.empty(emb.emb_offsets_scratch_bytes(T * B), dtype=torch.uint8, device=H.DEV)
+            emb.emb_bag_forward_cached_tables_hashed_lengths(ct, H.dev(raw), H.dev(lengths), B, "mean", o2, off2, scratch,
+                                                             hm2, status)
+            torch.cuda.synchronize()
+            assert np.array_equal(off2.cpu().numpy(), off) and torch.equal(o2, out) and torch.equal(hm2, hm)
+            assert int(status.item()) == st_all
+
+
+@pytest.mark.parametrize("dtype,D,T,B", [("f32", 16, 3, 100_000), ("int4", 64, 1, 270_000), ("bf16", 32, 2, 2500)])
+def test_cached_forward_from_lengths_equals_offsets_then_cached_forward(dtype, D, T, B):
+    # 1, 66 and 74 tiles of lengths: the wavefront and the workgroup form of the prefix over tile totals;
+    # the single-table and the multi-table call; offsets against the oracle, pooled output against the
+    # (oracle-checked) calls that take offsets
+    rng = np.random.default_rng(7100 + D + T)
+    R, K = 5000, 700
+    quant = dtype in ("int8", "int4")
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    entries, keep = [], []
+    for t in range(T):
+        x = (rng.standard_normal((R, D)) * 0.01).astype(np.float32)
+        tab = oracle.quantize_rows(x, dtype) if quant else (wl.f32_to_bf16_bits(x).reshape(R, D) if dtype == "bf16" else x)
+        hot = np.sort(rng.choice(R, size=K, replace=False)).astype(np.int64)
+        tdev = H.dev(tab)
+        cache = torch.zeros((K, tab.shape[1]), dtype=tdev.dtype, device=H.DEV)
+        index = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+        emb.emb_cache_build(int(tdev.data_ptr()), R, D, dtype, H.dev(hot), cache, index, status)
+        keep.append(tdev)
+        entries.append((int(tdev.data_ptr()), R, cache, index, K, 900 + t))
+    n = T * B
+    lengths = (rng.random(n) < 0.3).astype(np.int32) * rng.integers(1, 6, size=n).astype(np.int32)
+    lengths[[0, n - 1]] = [0, 3]
+    off, _ = oracle.lengths_to_offsets(lengths)
+    raw = rng.integers(0, 1 << 64, size=int(off[-1]), dtype=np.uint64)
+    scratch = torch.empty(emb.emb_offsets_scratch_bytes(n), dtype=torch.uint8, device=H.DEV)
+    for mode in ("sum", "mean"):
+        want = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+        got = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+        hm1 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+        hm2 = torch.zeros(2, dtype=torch.int64, device=H.DEV)
+        off2 = torch.full((n + 1,), -1, dtype=torch.int64, device=H.DEV)
+        if T == 1:
+            ptr, _, cache, index, _, salt = entries[0]
+            emb.emb_bag_forward_cached_hashed(ptr, R, D, dtype, cache, index, K, salt, H.dev(raw), H.dev(off), B, mode,
+                                              want, hm1, status)
+            emb.emb_bag_forward_cached_hashed_lengths(ptr, R, D, dtype, cache, index, K, salt, H.dev(raw),
+                                                      H.dev(lengths), B, mode, got, off2, scratch, hm2, status)
+        else:
+            ct = emb.CachedTables(entries, D, dtype, device=torch.device(H.DEV))
+            emb.emb_bag_forward_cached_tables_hashed(ct, H.dev(raw), H.dev(off), B, mode, want, hm1, status)
+            emb.emb_bag_forward_cached_tables_hashed_lengths(ct, H.dev(raw), H.dev(lengths), B, mode, got, off2, scratch,
+                                                             hm2, status)
+        torch.cuda.synchronize()
+        assert status.item() == 0 and np.array_equal(off2.cpu().numpy(), off)
+        assert torch.equal(got, want) and torch.equal(hm1, hm2) and int(hm1.sum()) == raw.size
+
+
+def test_cached_forward_from_lengths_argument_limits():
+    D, R, K = 16, 100, 10
+    tab = torch.zeros((R, D), dtype=torch.float32, device=H.DEV)
+    cache = torch.zeros((K, D), dtype=torch.float32, device=H.DEV)
+    index = torch.empty(emb.emb_cache_index_bytes(R), dtype=torch.uint8, device=H.DEV)
+    status = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+    emb.emb_cache_build(int(tab.data_ptr()), R, D, "f32", H.dev(np.arange(K, dtype=np.int64)), cache, index, status)
+    ct = emb.CachedTables([(int(tab.data_ptr()), R, cache, index, K, 1)], D, "f32", device=torch.device(H.DEV))
+    raw = torch.zeros(0, dtype=torch.int64, device=H.DEV)
+    # no bags: the single offset is written, nothing else is touched
+    off = torch.full((1,), -1, dtype=torch.int64, device=H.DEV)
+    none = torch.zeros(0, dtype=torch.uint8, device=H.DEV)
+    emb.emb_bag_forward_cached_hashed_lengths(int(tab.data_ptr()), R, D, "f32", cache, index, K, 1, raw,
+                                              torch.zeros(0, dtype=torch.int32, device=H.DEV), 0, "sum",
+                                              torch.zeros(0, dtype=torch.float32, device=H.DEV), off, none, None, status)
+    torch.cuda.synchronize()
+    assert off.item() == 0
+    off.fill_(-1)
+    emb.emb_bag_forward_cached_tables_hashed_lengths(ct, raw, torch.zeros(0, dtype=torch.int32, device=H.DEV), 0, "sum",
+                                                     torch.zeros(0, dtype=torch.float32, device=H.DEV), off, none, None,
+                                                     status)
+    torch.cuda.synchronize()
+    assert off.item() == 0 and status.item() == 0
+    # scratch too small; too many bags
+    B = 5000
+    lengths = torch.zeros(B, dtype=torch.int32, device=H.DEV)
+    out = torch.zeros((B, D), dtype=torch.float32, device=H.DEV)
+    offs = torch.zeros(B + 1, dtype=torch.int64, device=H.DEV)
+    small = torch.empty(emb.emb_offsets_scratch_bytes(B) - 8, dtype=torch.uint8, device=H.DEV)
+    with pytest.raises(emb.EmbError) as ei:
+        emb.emb_bag_forward_cached_hashed_lengths(int(tab.data_ptr()), R, D, "f32", cache, index, K, 1, raw, lengths, B,
+                                                  "sum", out, offs, small, None, status)
+    assert ei.value.code == -1
+    with pytest.raises(emb.EmbError) as ei:
+        emb.emb_bag_forward_cached_tables_hashed_lengths(ct, raw, lengths, B, "sum", out, offs, small, None, status)
+    assert ei.value.code == -1
+    big = (1 << 20) + 1
+    lengths = torch.zeros(big, dtype=torch.int32, device=H.DEV)
+    out = torch.zeros((big, D), dtype=torch.float32, device=H.DEV)
+    offs = torch.zeros(big + 1, dtype=torch.int64, device=H.DEV)
+    scratch = torch.empty(emb.emb_offsets_scratch_bytes(big), dtype=torch.uint8, device=H.DEV)
+    with pytest.raises(emb.EmbError) as ei:
+        emb.emb_bag_forward_cached_hashed_lengths(int(tab.data_ptr()), R, D, "f32", cache, index, K, 1, raw, lengths, big,
+                                                  "sum", out, offs, scratch, None, status)
+    assert ei.value.code == -2
 
 
 def test_hosted_table_set_with_policy_refresh_matches_the_oracle():
