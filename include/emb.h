@@ -83,6 +83,8 @@ typedef enum { EMB_F32 = 0, EMB_BF16 = 1, EMB_INT8 = 2, EMB_INT4 = 3, EMB_INT4_R
 #define EMB_STATUS_BAD_OFFSETS 2u /* a negative length, or offsets not 0 <= s <= e <= nnz */
 #define EMB_STATUS_BAD_HOT_SET 4u /* hot rows not strictly ascending / out of range */
 #define EMB_STATUS_NO_VERSION 8u  /* a lookup latched a handle with no (matching) version published */
+#define EMB_STATUS_SORT_ABANDONED 16u /* the backward's sort gave up waiting for one of its own workgroups
+                                         (see emb_debug_sort_poll_limit); no row was updated */
 
 /* One embedding table.  The same array of T descriptors is passed twice to
  * the multi-table calls: in host memory (read for validation) and in device
@@ -391,6 +393,19 @@ int emb_bag_backward_sort_prepared(const emb_table *tables_host, const emb_table
                                    int64_t *unique_keys_out_dev, int32_t *unique_counts_out_dev,
                                    int64_t *num_unique_out_dev, uint32_t *status_dev,
                                    void *const *stage_events, void *stream);
+
+/* Diagnostics of the backward's sort (the radix sort named with the update in
+ * Section 3.1's fine-tuning step is this build's choice; the paper gives no
+ * algorithm).  From the second pass on, the workgroups of a sort pass tell
+ * each other their digit counts through words in the workspace; a workgroup
+ * waits for words of workgroups that were started before it, polling each at
+ * most `polls` times (default 2^20, some seconds).  When a wait runs out the
+ * sort is abandoned: EMB_STATUS_SORT_ABANDONED is set, every later kernel of
+ * the backward returns at once and no table row changes.  That is not
+ * expected to happen; this call exists to test the path: polls == 0 makes
+ * every wait fail at once, polls < 0 restores the default.  Host-only, takes
+ * effect for calls enqueued afterwards, process-wide. */
+void emb_debug_sort_poll_limit(int64_t polls);
 
 /* ---- host-resident table with an HBM hot-row cache (Section 3.3) --------- */
 

@@ -25,6 +25,7 @@ STATUS_BAD_INDEX = 1
 STATUS_BAD_OFFSETS = 2
 STATUS_BAD_HOT_SET = 4
 STATUS_NO_VERSION = 8
+STATUS_SORT_ABANDONED = 16
 BWD_STAGE_EVENTS = 6
 
 # numpy mirror of ``struct emb_table``
@@ -45,7 +46,7 @@ assert SHAPE_DESC.itemsize == 32
 EXPORTS = [
     "emb_status_string", "emb_tables_init", "emb_hash_ids", "emb_hash_ids_tables", "emb_lengths_to_offsets",
     "emb_bag_forward", "emb_bag_forward_hashed", "emb_table_shapes_init", "emb_bag_forward_mixed", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
-    "emb_bag_backward_sort", "emb_bag_backward_update", "emb_bag_forward_train", "emb_bag_forward_train_lengths", "emb_offsets_scratch_bytes", "emb_bag_forward_hashed_lengths", "emb_bag_backward_sort_prepared", "emb_row_bytes", "emb_quantize_rows",
+    "emb_bag_backward_sort", "emb_debug_sort_poll_limit", "emb_bag_backward_update", "emb_bag_forward_train", "emb_bag_forward_train_lengths", "emb_offsets_scratch_bytes", "emb_bag_forward_hashed_lengths", "emb_bag_backward_sort_prepared", "emb_row_bytes", "emb_quantize_rows",
     "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_bag_forward_cached_hashed_lengths", "emb_host_device_pointer",
@@ -116,6 +117,8 @@ def lib() -> C.CDLL:
     L.emb_bag_backward_sort.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, sz, vp, vp, vp, vp, vp, vp]
     L.emb_bag_forward_train.restype = C.c_int
     L.emb_bag_forward_train.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, sz, vp, vp, vp]
+    L.emb_debug_sort_poll_limit.restype = None
+    L.emb_debug_sort_poll_limit.argtypes = [i64]
     L.emb_offsets_scratch_bytes.restype = sz
     L.emb_offsets_scratch_bytes.argtypes = [i64]
     L.emb_bag_forward_hashed_lengths.restype = C.c_int
@@ -349,6 +352,12 @@ def emb_bag_forward_hashed(tables: TableSet, raw: torch.Tensor, offsets: torch.T
         _ptr(offsets, torch.int64, "offsets"), int(B), nnz, POOL[mode] | (ROWS_STREAMING if streaming else 0),
         _ptr(out, torch.float32, "out"), _ptr(rows_out, torch.int64, "rows_out"), _ptr(status, torch.int32, "status"),
         _stream()))
+
+
+def emb_debug_sort_poll_limit(polls: int) -> None:
+    """Test hook: how often a pass of the backward's sort polls another workgroup's word before it abandons the
+    sort (0: every wait fails at once; negative: the default)."""
+    lib().emb_debug_sort_poll_limit(int(polls))
 
 
 def emb_offsets_scratch_bytes(num_bags_total: int) -> int:

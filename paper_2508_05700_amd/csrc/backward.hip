@@ -32,7 +32,7 @@ namespace {
 // workspace
 // ---------------------------------------------------------------------------
 struct BwdLayout {
-    size_t ctrl, keys_a, keys_b, pay_a, pay_b, bag_scale, first_tile, tile_desc, hist, tile_heads, seg_start, seg_real,
+    size_t ctrl, keys_a, keys_b, pay_a, pay_b, bag_scale, first_tile, tile_desc, hist, sort_flags, tile_heads, seg_start, seg_real,
         local_offsets, tile_prefix,
         queue, queue_end, span_head, wave_heads, segs, multi_list, chunk_tasks, partials, total;
     int key_bytes;
@@ -89,7 +89,10 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     L.bag_scale = off;   off += align256((size_t)T * (size_t)B * 4 + 4);
     L.first_tile = off;  off += align256(((size_t)T + 1) * 4);
     L.tile_desc = off;   off += align256((size_t)L.tiles * sizeof(SortTile));
-    L.hist = off;        off += align256((size_t)(L.tiles + 1) * RADIX * 4);
+    // the digit counts of every pass, and the words the scatters of the passes after the first exchange
+    const int max_passes = L.key_bytes * 8 / RADIX_BITS;
+    L.hist = off;        off += align256((size_t)max_passes * (L.tiles + 1) * RADIX * 4);
+    L.sort_flags = off;  off += align256((size_t)(max_passes - 1) * L.tiles * RADIX * 8);
     L.tile_heads = off;  off += align256((size_t)L.flat_tiles * 8);
     L.seg_start = off;   off += align256((n + 1) * 4);
     L.seg_real = off;    off += align256(n * 4);
@@ -462,6 +465,16 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
     return EMB_OK;
 }
 
+// How often a scatter of the sort polls one word of another workgroup before it gives the sort up
+// (sort_lookback_walk, radix_sort.h); emb_debug_sort_poll_limit changes it.
+static constexpr uint32_t SORT_POLL_LIMIT_DEFAULT = 1u << 20;
+static uint32_t sort_poll_limit = SORT_POLL_LIMIT_DEFAULT;
+
+extern "C" void emb_debug_sort_poll_limit(int64_t polls)
+{
+    sort_poll_limit = polls < 0 ? SORT_POLL_LIMIT_DEFAULT : (polls > 0xFFFFFFFFll ? 0xFFFFFFFFu : (uint32_t)polls);
+}
+
 // Keys, sort and the optional list of distinct rows: everything that needs the indices only.
 // prepared: the control block, the tile descriptors and the records are in the workspace already
 // (emb_bag_forward_train put them there), so only the passes and the optional list run.
@@ -477,6 +490,7 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
     uint32_t *first_tile = reinterpret_cast<uint32_t *>(a.ws + L.first_tile);
     SortTile *tile_desc = reinterpret_cast<SortTile *>(a.ws + L.tile_desc);
     uint32_t *hist = reinterpret_cast<uint32_t *>(a.ws + L.hist);
+    unsigned long long *sort_flags = reinterpret_cast<unsigned long long *>(a.ws + L.sort_flags);
     unsigned long long *tile_heads = reinterpret_cast<unsigned long long *>(a.ws + L.tile_heads);
     uint32_t *seg_start = reinterpret_cast<uint32_t *>(a.ws + L.seg_start);
     uint32_t *seg_real = reinterpret_cast<uint32_t *>(a.ws + L.seg_real);
@@ -509,19 +523,42 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
 
     KeyT *kin = keys_a, *kout = keys_b;
     uint32_t *pin = pay_a, *pout = pay_b;
+    // the digit counts of all passes (four passes per launch), then one scan over all of them
+    for (int p0 = 0; p0 < a.passes; p0 += 4) {
+        unsigned long long *fl = p0 == 0 ? sort_flags : nullptr;   // the first launch clears the scatters' words
+        const int np = a.passes - p0 < 4 ? a.passes - p0 : 4;
+#define EMB_SORT_HIST(NP)                                                                                          \
+    hipLaunchKernelGGL((sort_hist_kernel<KeyT, NP>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, tile_desc, p0, hist, \
+                       tiles, fl, a.passes - 1, ctrl)
+        switch (np) {
+            case 1: EMB_SORT_HIST(1); break;
+            case 2: EMB_SORT_HIST(2); break;
+            case 3: EMB_SORT_HIST(3); break;
+            default: EMB_SORT_HIST(4); break;
+        }
+#undef EMB_SORT_HIST
+        EMB_RETURN_IF_LAUNCH_FAILED();
+    }
+    hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX * a.passes), dim3(1024), 0, s, hist, tiles, ctrl);
+    EMB_RETURN_IF_LAUNCH_FAILED();
+    const uint32_t poll_limit = sort_poll_limit;
     for (int p = 0; p < a.passes; ++p) {
         const int shift = p * RADIX_BITS;
-        hipLaunchKernelGGL(sort_hist_kernel<KeyT>, dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, tile_desc, shift, hist,
-                           tiles, ctrl);
-        EMB_RETURN_IF_LAUNCH_FAILED();
-        hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX), dim3(1024), 0, s, hist, tiles, ctrl);
-        EMB_RETURN_IF_LAUNCH_FAILED();
-        if (p == a.passes - 1)
-            hipLaunchKernelGGL((sort_scatter_kernel<KeyT, true>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, pin, kout,
-                               pout, tile_desc, shift, hist, tiles, a.tables_dev, local_sentinel, sentinel, ctrl);
-        else
-            hipLaunchKernelGGL((sort_scatter_kernel<KeyT, false>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, pin, kout,
-                               pout, tile_desc, shift, hist, tiles, a.tables_dev, local_sentinel, sentinel, ctrl);
+        const uint32_t *hp = hist + (size_t)p * RADIX * (tiles + 1);
+        unsigned long long *fl = p > 0 ? sort_flags + (size_t)(p - 1) * tiles * RADIX : nullptr;
+        const bool last = p == a.passes - 1;
+#define EMB_SORT_SCATTER(LAST, LOOKBACK)                                                                            \
+    hipLaunchKernelGGL((sort_scatter_kernel<KeyT, LAST, LOOKBACK>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, pin, \
+                       kout, pout, tile_desc, shift, hp, tiles, a.tables_dev, local_sentinel, sentinel, ctrl, fl,   \
+                       poll_limit, a.status)
+        if (p == 0) {
+            if (last) EMB_SORT_SCATTER(true, false);
+            else EMB_SORT_SCATTER(false, false);
+        } else {
+            if (last) EMB_SORT_SCATTER(true, true);
+            else EMB_SORT_SCATTER(false, true);
+        }
+#undef EMB_SORT_SCATTER
         EMB_RETURN_IF_LAUNCH_FAILED();
         KeyT *tk = kin; kin = kout; kout = tk;
         uint32_t *tp = pin; pin = pout; pout = tp;

@@ -1,5 +1,14 @@
-// Stable LSD radix sort of (key, payload) records, 8 bits per pass, as three
-// launches per pass: per-tile digit histogram, scan, stable scatter.
+// Stable LSD radix sort of (key, payload) records, 8 bits per pass.  One launch
+// counts the digits of every pass per tile (up to four passes per launch), one
+// scans all those counts, then every pass is one stable scatter.
+//
+// What a scatter needs besides the ranks inside its tile: how many records of its
+// table hold a smaller digit (the same whatever the order of the records, so the
+// counts taken before the first pass serve every pass) and how many records with
+// the same digit lie in earlier tiles of the table.  The latter depends on the
+// order the previous pass left: the first pass has it from the scanned counts,
+// the later passes exchange it between the workgroups of the scatter itself
+// (sort_lookback_walk).
 //
 // The sort is segmented: the records of one table are contiguous before the sort
 // (bags are table-major) and stay in the table's range, so the keys sorted are
@@ -68,26 +77,37 @@ __device__ __forceinline__ void wave_rank_digits(const KeyT (&key)[SORT_ITEMS], 
     }
 }
 
-// hist is [RADIX][tiles + 1]: row d holds digit d's count in every tile and, in
-// its last column (written by the scan), the digit's count over all tiles.
-template <typename KeyT>
+// hist is [passes][RADIX][tiles + 1]: row (p, d) holds the count of digit d of pass p in every
+// tile (the tiles as they are before the first pass) and, in its last column (written by the
+// scan), the count over all tiles.  One launch counts the digits of passes
+// [first_pass, first_pass + NP).  flags (optional): the scatters' exchange words (sort_lookback_walk) of the passes after the
+// first, [flag_passes][tiles][RADIX]; every tile in use clears its own.
+template <typename KeyT, int NP>
 __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__restrict__ keys,
-                                                               const SortTile *__restrict__ desc, int shift,
+                                                               const SortTile *__restrict__ desc, int first_pass,
                                                                uint32_t *__restrict__ hist, uint32_t tiles,
+                                                               unsigned long long *__restrict__ flags, int flag_passes,
                                                                const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
-    __shared__ uint32_t cnt[SORT_WAVES][RADIX];
+    __shared__ uint32_t cnt[SORT_WAVES][NP][RADIX];
     const SortTile tile = desc[blockIdx.x];
     const bool owner = threadIdx.x < RADIX;   // thread d < RADIX reports digit d
-    uint32_t *slot = hist + (size_t)(owner ? threadIdx.x : 0) * (tiles + 1) + blockIdx.x;
+    uint32_t *slot = hist + ((size_t)first_pass * RADIX + (owner ? threadIdx.x : 0)) * (tiles + 1) + blockIdx.x;
+    const size_t pass_stride = (size_t)RADIX * (tiles + 1);
     if (tile.count == 0) {   // uniform over the workgroup
-        if (owner) *slot = 0;
+        if (owner) {
+#pragma unroll
+            for (int q = 0; q < NP; ++q) slot[q * pass_stride] = 0;
+        }
         return;
+    }
+    if (flags && owner) {
+        for (int f = 0; f < flag_passes; ++f) flags[((size_t)f * tiles + blockIdx.x) * RADIX + threadIdx.x] = 0ull;
     }
     const int lane = threadIdx.x & (EMB_WAVE - 1);
     const int wave = threadIdx.x / EMB_WAVE;
-    for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_BLOCK) (&cnt[0][0])[i] = 0;
+    for (int i = threadIdx.x; i < SORT_WAVES * NP * RADIX; i += SORT_BLOCK) (&cnt[0][0][0])[i] = 0;
     __syncthreads();
     const uint32_t end = tile.start + tile.count;
     const uint32_t wbase = tile.start + wave * (SORT_TILE / SORT_WAVES);
@@ -97,36 +117,42 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__res
         const uint32_t i = wbase + k * EMB_WAVE + lane;
         key[k] = i < end ? keys[i] : (KeyT)0;
     }
-    // Counting needs no ranks: one LDS add per record into the wavefront's own counters.  Lanes
-    // that share a digit are serialised by the LDS, which is cheaper than matching them by ballots
-    // unless all 64 hold the same digit (the records of one hot row, once an earlier pass has made
-    // them adjacent): that case is one add by one lane.
+    // Counting needs no ranks: one LDS add per record and digit into the wavefront's own counters.
+    // Lanes that share a digit are serialised by the LDS, which is cheaper than matching them by
+    // ballots unless all 64 hold the same digit (the records of one hot row, which share every
+    // digit): that case is one add by one lane.
 #pragma unroll
     for (int k = 0; k < SORT_ITEMS; ++k) {
         const uint32_t i = wbase + k * EMB_WAVE + lane;
         const bool live = i < end;
-        const uint32_t digit = (uint32_t)(key[k] >> shift) & (RADIX - 1);
         const uint64_t lv = __ballot(live);
         if (lv == 0) continue;                                     // uniform
         const int first = __ffsll((unsigned long long)lv) - 1;
-        const uint32_t d0 = (uint32_t)__shfl((int)digit, first, EMB_WAVE);
-        if (__ballot(live && digit == d0) == lv) {                 // uniform
-            if (lane == first) cnt[wave][d0] += (uint32_t)__popcll(lv);
-        } else if (live) {
-            atomicAdd(&cnt[wave][digit], 1u);
+#pragma unroll
+        for (int q = 0; q < NP; ++q) {
+            const uint32_t digit = (uint32_t)(key[k] >> ((first_pass + q) * RADIX_BITS)) & (RADIX - 1);
+            const uint32_t d0 = (uint32_t)__shfl((int)digit, first, EMB_WAVE);
+            if (__ballot(live && digit == d0) == lv) {             // uniform
+                if (lane == first) cnt[wave][q][d0] += (uint32_t)__popcll(lv);
+            } else if (live) {
+                atomicAdd(&cnt[wave][q][digit], 1u);
+            }
         }
     }
     __syncthreads();
     if (owner) {
-        uint32_t c = 0;
 #pragma unroll
-        for (int w = 0; w < SORT_WAVES; ++w) c += cnt[w][threadIdx.x];
-        *slot = c;
+        for (int q = 0; q < NP; ++q) {
+            uint32_t c = 0;
+#pragma unroll
+            for (int w = 0; w < SORT_WAVES; ++w) c += cnt[w][q][threadIdx.x];
+            slot[q * pass_stride] = c;
+        }
     }
 }
 static_assert(SORT_BLOCK >= RADIX && SORT_BLOCK % RADIX == 0, "the first RADIX threads of a workgroup own one digit each");
 
-// One workgroup per digit: exclusive scan of that digit's per-tile counts in
+// One workgroup per pass and digit: exclusive scan of that digit's per-tile counts in
 // place; the digit's total goes to the row's last column.
 __global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ hist, uint32_t tiles,
                                                           const BwdCtrl *ctrl)
@@ -146,6 +172,90 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ 
     if (threadIdx.x == 0) row[tiles] = carry;
 }
 
+// How the workgroups of one scatter tell each other their digit counts.  Every tile owns one 64-bit
+// word per digit, cleared before the pass: the top two bits say what the low 32 hold: nothing yet,
+// the tile's own count (SORT_FLAG_COUNT), or the count of the table's tiles up to and including this
+// one (SORT_FLAG_PREFIX).  Count and state travel in one word, written and read with relaxed
+// device-scope atomics, so no fence is needed.  A tile publishes its count as soon as it has ranked
+// its records, then walks back over the earlier tiles of its table, adding counts until it meets a
+// prefix or the table's first tile, and publishes its own prefix.
+//
+// A tile only ever waits for tiles with a smaller number.  Workgroups are started in the order of
+// their numbers, so the unfinished tile with the smallest number is running and waits for nobody:
+// the waits end.  They are bounded all the same: after poll_limit polls of one word the tile gives
+// up and publishes SORT_FLAG_FAILED, every tile that meets that word does the same at once, and the
+// kernel sets the backward's abort flag: the sort is abandoned, no row is updated, and the caller
+// finds EMB_STATUS_SORT_ABANDONED in the status word.  poll_limit == 0 makes every wait fail at
+// once (used to test that path).
+constexpr unsigned long long SORT_FLAG_COUNT = 1ull << 62, SORT_FLAG_PREFIX = 2ull << 62, SORT_FLAG_FAILED = 3ull << 62;
+constexpr int SORT_LOOKBACK_BATCH = 4;   // words requested together (2, 4, 8 measure the same; 16 costs registers)
+
+__device__ __forceinline__ unsigned long long sort_flag_load(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void sort_flag_store(unsigned long long *p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// For the thread that owns digit `d` of tile `me`: the tile's own count goes out as soon as it is known ...
+__device__ __forceinline__ void sort_lookback_publish(unsigned long long *flags /*[tiles][RADIX]*/, uint32_t me, uint32_t d,
+                                                      uint32_t count)
+{
+    sort_flag_store(flags + (size_t)me * RADIX + d, SORT_FLAG_COUNT | count);
+}
+
+// ... and the walk follows once the scatter has done the work that does not depend on other tiles (by
+// then most of the words it needs have been published).  Returns in `before` the number of records with
+// this digit in tiles [first, me) and publishes the prefix; false if a wait ran out or met a failed tile.
+__device__ __forceinline__ bool sort_lookback_walk(unsigned long long *flags, uint32_t first, uint32_t me, uint32_t d,
+                                                   uint32_t count, uint32_t poll_limit, uint32_t &before)
+{
+    uint32_t sum = 0;
+    bool ok = true, done = false;
+    for (int64_t t = (int64_t)me - 1; t >= (int64_t)first && !done; t -= SORT_LOOKBACK_BATCH) {
+        unsigned long long v[SORT_LOOKBACK_BATCH];
+#pragma unroll
+        for (int i = 0; i < SORT_LOOKBACK_BATCH; ++i) {
+            const int64_t tt = t - i;
+            v[i] = tt >= (int64_t)first ? sort_flag_load(flags + (size_t)tt * RADIX + d) : SORT_FLAG_PREFIX;
+        }
+#pragma unroll
+        for (int i = 0; i < SORT_LOOKBACK_BATCH; ++i) {
+            if (done) break;
+            const int64_t tt = t - i;
+            if (tt < (int64_t)first) {
+                done = true;
+                break;
+            }
+            unsigned long long x = v[i];
+            uint32_t polls = 0;
+            while ((x >> 62) == 0) {            // not published yet
+                if (polls >= poll_limit) {
+                    x = SORT_FLAG_FAILED;
+                    break;
+                }
+                ++polls;
+                __builtin_amdgcn_s_sleep(2);
+                x = sort_flag_load(flags + (size_t)tt * RADIX + d);
+            }
+            if (poll_limit == 0) x = SORT_FLAG_FAILED;
+            const unsigned long long state = x & SORT_FLAG_FAILED;
+            if (state == SORT_FLAG_FAILED) {
+                ok = false;
+                done = true;
+                break;
+            }
+            sum += (uint32_t)x;
+            if (state == SORT_FLAG_PREFIX) done = true;
+        }
+    }
+    sort_flag_store(flags + (size_t)me * RADIX + d, ok ? (SORT_FLAG_PREFIX | (uint32_t)(sum + count)) : SORT_FLAG_FAILED);
+    before = sum;
+    return ok;
+}
+
 // Stable scatter of one tile.  After ranking, the tile's records are first put in
 // digit order in LDS; the copy-out then walks that order, so the lanes of a store
 // instruction write consecutive addresses within each digit's run (about
@@ -153,14 +263,17 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ 
 //
 // A record's destination is: start of its table's range + records of the table
 // with a smaller digit + records of the table with the same digit in earlier
-// tiles + its rank among the tile's records of that digit.  The scanned
-// histogram P (exclusive over all tiles, total in the last column) gives the two
-// middle terms as differences against the column of the table's first tile.
+// tiles + its rank among the tile's records of that digit.  The scanned counts P
+// of this pass's digit (exclusive over all tiles, total in the last column) give
+// the first middle term as a difference between the columns of the table's first
+// tile and of the next table's, whatever order the records are in.  The second:
+// LOOKBACK false (the first pass: the records are in the order they were counted
+// in) from P as well; LOOKBACK true from the other workgroups (sort_lookback_walk).
 //
 // LAST: the final pass writes the key's position in the concatenation of the
 // tables (row + row_base), and the marker of an invalid row (`local_sentinel`,
 // which sorts last inside its table) as `global_sentinel`.
-template <typename KeyT, bool LAST>
+template <typename KeyT, bool LAST, bool LOOKBACK>
 __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__restrict__ keys_in,
                                                                   const uint32_t *__restrict__ pay_in,
                                                                   KeyT *__restrict__ keys_out,
@@ -169,9 +282,14 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
                                                                   const uint32_t *__restrict__ hist /*scanned*/,
                                                                   uint32_t tiles, const emb_table *__restrict__ tables,
                                                                   KeyT local_sentinel, KeyT global_sentinel,
-                                                                  const BwdCtrl *ctrl)
+                                                                  BwdCtrl *ctrl, unsigned long long *flags,
+                                                                  uint32_t poll_limit, uint32_t *status)
 {
-    if (ctrl->abort) return;
+    if (ctrl->abort) {   // uniform; nobody is to wait for this tile
+        if (LOOKBACK && threadIdx.x < RADIX) sort_flag_store(flags + (size_t)blockIdx.x * RADIX + threadIdx.x, SORT_FLAG_FAILED);
+        return;
+    }
+    __shared__ uint32_t lookback_failed;
     __shared__ uint32_t cnt[SORT_WAVES][RADIX];  // per-wavefront digit counts, then offsets inside the tile
     __shared__ uint32_t delta[RADIX];            // global position minus tile position, per digit
     __shared__ unsigned long long wave_sums[SORT_WAVES];
@@ -185,8 +303,10 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
     // asked for together with them, not after the ranking
     const bool owner = threadIdx.x < RADIX;   // thread d < RADIX looks after digit d
     const uint32_t *hrow = hist + (size_t)(owner ? threadIdx.x : 0) * (tiles + 1);
-    const uint32_t p_first = hrow[tile.first], p_next = hrow[tile.next], p_mine = hrow[blockIdx.x];
+    const uint32_t p_first = hrow[tile.first], p_next = hrow[tile.next];
+    const uint32_t p_mine = LOOKBACK ? 0u : hrow[blockIdx.x];
     for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_BLOCK) (&cnt[0][0])[i] = 0;
+    if (threadIdx.x == 0) lookback_failed = 0;
     __syncthreads();
 
     const uint32_t end = tile.start + tile.count;
@@ -207,17 +327,18 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
     // table's records with a smaller digit (one scan over the digits of both, packed: the tile
     // counts add up to at most SORT_TILE, so the low half never carries), the wavefronts'
     // offsets within it, and the shift to global positions
+    const uint32_t d = owner ? threadIdx.x : 0;
+    const uint32_t digit_total = owner ? p_next - p_first : 0;   // in this table
+    uint32_t total = 0, dshift = 0;                              // dshift: delta[d] but for the earlier tiles' share
     {
-        const uint32_t d = owner ? threadIdx.x : 0;
-        const uint32_t digit_total = owner ? p_next - p_first : 0;   // in this table
-        const uint32_t before_in_digit = p_mine - p_first;           // in this table's earlier tiles
-        uint32_t c[SORT_WAVES], total = 0;
+        uint32_t c[SORT_WAVES];
         if (owner) {
 #pragma unroll
             for (int w = 0; w < SORT_WAVES; ++w) {
                 c[w] = cnt[w][d];
                 total += c[w];
             }
+            if (LOOKBACK) sort_lookback_publish(flags, blockIdx.x, d, total);
         }
         unsigned long long all;
         const unsigned long long inc = block_inclusive_scan<unsigned long long, SORT_BLOCK>(
@@ -231,7 +352,8 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
                 cnt[w][d] = run;
                 run += c[w];
             }
-            delta[d] = tile.seg_start + below + before_in_digit - start;
+            dshift = tile.seg_start + below - start;
+            if (!LOOKBACK) delta[d] = dshift + (p_mine - p_first);   // + the digit's records in the table's earlier tiles
         }
     }
     __syncthreads();
@@ -246,7 +368,20 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
             sp[at] = pay[k];
         }
     }
+    if (LOOKBACK && owner) {   // the other tiles have had the time of the step above to publish their counts
+        uint32_t before_in_digit = 0;
+        if (!sort_lookback_walk(flags, tile.first, blockIdx.x, d, total, poll_limit, before_in_digit))
+            lookback_failed = 1;
+        delta[d] = dshift + before_in_digit;
+    }
     __syncthreads();
+    if (LOOKBACK && lookback_failed) {   // uniform: positions unknown, nothing is written
+        if (threadIdx.x == 0) {
+            ctrl->abort = 1;
+            emb_flag(status, EMB_STATUS_SORT_ABANDONED);
+        }
+        return;
+    }
 
     KeyT row_base = 0;
     if (LAST) row_base = (KeyT)tables[tile.table].row_base;

@@ -1116,6 +1116,27 @@ def test_backward_bad_indices_skipped_and_bad_offsets_abort():
             assert np.all(acc_dev[t].cpu().numpy() == 0)
 
 
+def test_backward_sort_wait_that_runs_out_abandons_the_backward_and_changes_nothing():
+    # From the second pass on, the workgroups of a sort pass wait for each other's digit counts; the waits are
+    # bounded.  With the bound at zero every wait fails at once (forced from the host; every kernel still runs
+    # to its end): the status word says so, no row and no accumulator changes, and the same call with the
+    # default bound afterwards gives the oracle's result.
+    rng = np.random.default_rng(4471)
+    T, B, D, Rs = 2, 700, 16, [70_000, 300]          # 14 000 lookups per table: several sort tiles, three passes
+    tables, lengths, off, rows = H.random_case(rng, T, B, D, Rs, 20, scale=0.01)
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    ts, w_dev, acc_dev = H.make_tableset(tables, "f32", with_accum=True)
+    emb.emb_debug_sort_poll_limit(0)
+    try:
+        g = H.gpu_backward(ts, rows, off, B, "sum", dout, 0.01, 1e-8)
+    finally:
+        emb.emb_debug_sort_poll_limit(-1)
+    assert g["status"] == emb.STATUS_SORT_ABANDONED
+    for t in range(T):
+        assert np.array_equal(w_dev[t].cpu().numpy(), tables[t]) and np.all(acc_dev[t].cpu().numpy() == 0)
+    _check_backward_against_oracle(tables, Rs, rows, off, B, D, "sum", dout, "after an abandoned sort")
+
+
 def test_backward_empty_batch():
     tables = [np.ones((10, 16), dtype=np.float32)]
     ts, w_dev, acc_dev = H.make_tableset(tables, "f32", with_accum=True)
