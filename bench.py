@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "0b291ff21997e378",
+    "sources": "3609b0d737f48647",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (177526.4, 69043.2), "update_kernel": (240501.4, 324004.8)},
-        "3b": {"bag_forward_train_kernel": (94735.1, 83097.8), "update_kernel": (170137.9, 220407.0)},
-        "2": {"bag_forward_hashed_kernel": (176259.3, 33802.6), "bag_forward_kernel": (177947.4, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338181.5, 33793.5), "bag_forward_kernel": (338144.0, 32768.0)},
-        "2un": {"bag_forward_kernel": (346129.4, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (122280.5, 33830.7)},
-        "2uq4": {"bag_forward_quant_kernel": (232548.4, 33924.0)},
-        "2uq4r": {"bag_forward_quant_kernel": (190438.4, 33872.0)},
-        "4": {"bag_forward_hashed_kernel": (52664.8, 8704.2)},
+        "3": {"bag_forward_train_kernel": (177532.1, 69026.4), "update_kernel": (240530.4, 324005.0)},
+        "3b": {"bag_forward_train_kernel": (94784.5, 83112.4), "update_kernel": (170127.4, 220366.3)},
+        "2": {"bag_forward_hashed_kernel": (176259.9, 33801.9), "bag_forward_kernel": (177920.2, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338182.6, 33793.7), "bag_forward_kernel": (338143.7, 32768.0)},
+        "2un": {"bag_forward_kernel": (346128.2, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (122368.5, 33830.8)},
+        "2uq4": {"bag_forward_quant_kernel": (232574.6, 33921.5)},
+        "2uq4r": {"bag_forward_quant_kernel": (190425.6, 33871.9)},
+        "4": {"bag_forward_hashed_kernel": (52680.5, 8704.3)},
     },
 }
 
