@@ -468,6 +468,7 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
 // How often a scatter of the sort polls one word of another workgroup before it gives the sort up
 // (sort_lookback_walk, radix_sort.h); emb_debug_sort_poll_limit changes it.
 static constexpr uint32_t SORT_POLL_LIMIT_DEFAULT = 1u << 20;
+static constexpr int SORT_EXCHANGE_MAX_TILES = 64;   // per table, on average: above it every pass counts and scans
 static uint32_t sort_poll_limit = SORT_POLL_LIMIT_DEFAULT;
 
 extern "C" void emb_debug_sort_poll_limit(int64_t polls)
@@ -523,35 +524,51 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
 
     KeyT *kin = keys_a, *kout = keys_b;
     uint32_t *pin = pay_a, *pout = pay_b;
-    // the digit counts of all passes (four passes per launch), then one scan over all of them
-    for (int p0 = 0; p0 < a.passes; p0 += 4) {
-        unsigned long long *fl = p0 == 0 ? sort_flags : nullptr;   // the first launch clears the scatters' words
-        const int np = a.passes - p0 < 4 ? a.passes - p0 : 4;
+    // Two ways through the passes (radix_sort.h).  Tables of up to SORT_EXCHANGE_MAX_TILES tiles of records
+    // each (all the host can know is the average): the digits of all passes are counted by one launch
+    // and scanned by one, and the scatters of the later passes exchange their counts.  Larger tables: a
+    // counting launch and a scan per pass, because a scatter's walk back over its table's earlier tiles
+    // grows with their number (a table of 640 tiles sorts 12 % slower by exchange, one of 40 tiles 11 %
+    // faster).
+    const bool exchange = a.nnz <= (int64_t)SORT_EXCHANGE_MAX_TILES * SORT_TILE * (a.T > 0 ? a.T : 1);
+    const uint32_t poll_limit = sort_poll_limit;
+    if (exchange) {
+        for (int p0 = 0; p0 < a.passes; p0 += 4) {
+            unsigned long long *fl = p0 == 0 ? sort_flags : nullptr;   // the first launch clears the scatters' words
+            const int np = a.passes - p0 < 4 ? a.passes - p0 : 4;
 #define EMB_SORT_HIST(NP)                                                                                          \
     hipLaunchKernelGGL((sort_hist_kernel<KeyT, NP>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, tile_desc, p0, hist, \
                        tiles, fl, a.passes - 1, ctrl)
-        switch (np) {
-            case 1: EMB_SORT_HIST(1); break;
-            case 2: EMB_SORT_HIST(2); break;
-            case 3: EMB_SORT_HIST(3); break;
-            default: EMB_SORT_HIST(4); break;
-        }
+            switch (np) {
+                case 1: EMB_SORT_HIST(1); break;
+                case 2: EMB_SORT_HIST(2); break;
+                case 3: EMB_SORT_HIST(3); break;
+                default: EMB_SORT_HIST(4); break;
+            }
 #undef EMB_SORT_HIST
+            EMB_RETURN_IF_LAUNCH_FAILED();
+        }
+        hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX * a.passes), dim3(1024), 0, s, hist, tiles, ctrl);
         EMB_RETURN_IF_LAUNCH_FAILED();
     }
-    hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX * a.passes), dim3(1024), 0, s, hist, tiles, ctrl);
-    EMB_RETURN_IF_LAUNCH_FAILED();
-    const uint32_t poll_limit = sort_poll_limit;
     for (int p = 0; p < a.passes; ++p) {
         const int shift = p * RADIX_BITS;
-        const uint32_t *hp = hist + (size_t)p * RADIX * (tiles + 1);
-        unsigned long long *fl = p > 0 ? sort_flags + (size_t)(p - 1) * tiles * RADIX : nullptr;
+        uint32_t *hp = hist + (size_t)p * RADIX * (tiles + 1);
+        const bool lookback = exchange && p > 0;
+        unsigned long long *fl = lookback ? sort_flags + (size_t)(p - 1) * tiles * RADIX : nullptr;
         const bool last = p == a.passes - 1;
+        if (!exchange) {
+            hipLaunchKernelGGL((sort_hist_kernel<KeyT, 1>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, tile_desc, p, hist,
+                               tiles, (unsigned long long *)nullptr, 0, ctrl);
+            EMB_RETURN_IF_LAUNCH_FAILED();
+            hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX), dim3(1024), 0, s, hp, tiles, ctrl);
+            EMB_RETURN_IF_LAUNCH_FAILED();
+        }
 #define EMB_SORT_SCATTER(LAST, LOOKBACK)                                                                            \
     hipLaunchKernelGGL((sort_scatter_kernel<KeyT, LAST, LOOKBACK>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, pin, \
                        kout, pout, tile_desc, shift, hp, tiles, a.tables_dev, local_sentinel, sentinel, ctrl, fl,   \
                        poll_limit, a.status)
-        if (p == 0) {
+        if (!lookback) {
             if (last) EMB_SORT_SCATTER(true, false);
             else EMB_SORT_SCATTER(false, false);
         } else {

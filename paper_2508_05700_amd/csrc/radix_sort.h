@@ -1,14 +1,17 @@
-// Stable LSD radix sort of (key, payload) records, 8 bits per pass.  One launch
-// counts the digits of every pass per tile (up to four passes per launch), one
-// scans all those counts, then every pass is one stable scatter.
+// Stable LSD radix sort of (key, payload) records, 8 bits per pass, in one of two
+// forms the host chooses between (run_sort).  By exchange: one launch counts the
+// digits of every pass per tile (up to four passes per launch), one scans all
+// those counts, then every pass is one stable scatter.  Pass by pass: a counting
+// launch, a scan and a scatter for each pass.
 //
 // What a scatter needs besides the ranks inside its tile: how many records of its
-// table hold a smaller digit (the same whatever the order of the records, so the
+// table hold a smaller digit (the same whatever the order of the records, so
 // counts taken before the first pass serve every pass) and how many records with
 // the same digit lie in earlier tiles of the table.  The latter depends on the
-// order the previous pass left: the first pass has it from the scanned counts,
-// the later passes exchange it between the workgroups of the scatter itself
-// (sort_lookback_walk).
+// order the previous pass left: a pass that has just been counted has it from the
+// scanned counts (the first pass always, every pass in the pass-by-pass form); the
+// later passes of the exchange form pass it between the workgroups of the scatter
+// itself (sort_lookback_walk).
 //
 // The sort is segmented: the records of one table are contiguous before the sort
 // (bags are table-major) and stay in the table's range, so the keys sorted are

@@ -703,7 +703,8 @@ def test_backward_sort_tables_of_very_different_key_widths():
 
 def test_backward_sort_one_table_of_many_tiles():
     # 1.2 M lookups of one table: a sort segment of 293 tiles (the scan over a table's tiles runs over more
-    # than one workgroup's worth of them), with a row repeated 20 000 times among them.
+    # than one workgroup's worth of them), with a row repeated 20 000 times among them.  A table this large
+    # is sorted pass by pass (a counting launch and a scan for every pass).
     rng = np.random.default_rng(778)
     D, B, R = 4, 3000, 1_000_003
     lengths = np.full(B, 400, dtype=np.int64)
@@ -713,6 +714,26 @@ def test_backward_sort_one_table_of_many_tiles():
     tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32)]
     dout = rng.standard_normal((1, B, D)).astype(np.float32)
     _check_backward_against_oracle(tables, [R], rows, off, B, D, "mean", dout, "one table")
+
+
+def test_backward_sort_one_large_table_among_small_ones():
+    # Eight tables, 1.2 M of the 1.25 M lookups in one of them: the tables average few tiles, so the later
+    # passes exchange their per-tile counts between workgroups, and in the large table (293 tiles) a tile's
+    # walk back over the earlier tiles is long and meets tiles in every state.
+    rng = np.random.default_rng(779)
+    D, B, T = 4, 3000, 8
+    Rs = [5000, 300, 1_000_003, 70_000, 9, 2_000_000, 65_536, 1000]
+    lengths = np.zeros(T * B, dtype=np.int64)
+    lengths[2 * B:3 * B] = 400
+    for t in (0, 1, 3, 4, 5, 6, 7):
+        lengths[t * B:(t + 1) * B] = rng.integers(0, 5, size=B)
+    off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    rows = np.concatenate([rng.integers(0, Rs[t], size=int(off[(t + 1) * B] - off[t * B])) for t in range(T)]).astype(np.int64)
+    big = np.arange(int(off[2 * B]), int(off[3 * B]))
+    rows[rng.choice(big, size=20_000, replace=False)] = 500_000
+    tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    _check_backward_against_oracle(tables, Rs, rows, off, B, D, "sum", dout, "one large table among small ones")
 
 
 def test_backward_split_calls_on_two_streams_equal_the_single_call():
