@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "3609b0d737f48647",
+    "sources": "dad5122a2369350f",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (177532.1, 69026.4), "update_kernel": (240530.4, 324005.0)},
-        "3b": {"bag_forward_train_kernel": (94784.5, 83112.4), "update_kernel": (170127.4, 220366.3)},
-        "2": {"bag_forward_hashed_kernel": (176259.9, 33801.9), "bag_forward_kernel": (177920.2, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338182.6, 33793.7), "bag_forward_kernel": (338143.7, 32768.0)},
-        "2un": {"bag_forward_kernel": (346128.2, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (122368.5, 33830.8)},
-        "2uq4": {"bag_forward_quant_kernel": (232574.6, 33921.5)},
-        "2uq4r": {"bag_forward_quant_kernel": (190425.6, 33871.9)},
-        "4": {"bag_forward_hashed_kernel": (52680.5, 8704.3)},
+        "3": {"bag_forward_train_kernel": (177523.0, 69037.9), "update_kernel": (240524.4, 324005.7)},
+        "3b": {"bag_forward_train_kernel": (94777.2, 83094.2), "update_kernel": (170146.4, 220380.3)},
+        "2": {"bag_forward_hashed_kernel": (176254.4, 33801.7), "bag_forward_kernel": (177917.9, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338179.8, 33793.5), "bag_forward_kernel": (338146.4, 32768.0)},
+        "2un": {"bag_forward_kernel": (346128.8, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (122248.2, 33832.5)},
+        "2uq4": {"bag_forward_quant_kernel": (232541.8, 33928.7)},
+        "2uq4r": {"bag_forward_quant_kernel": (190396.7, 33870.7)},
+        "4": {"bag_forward_hashed_kernel": (52664.0, 8704.3)},
     },
 }
 
