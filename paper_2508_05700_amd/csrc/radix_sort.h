@@ -175,7 +175,8 @@ __global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ 
     if (threadIdx.x == 0) row[tiles] = carry;
 }
 
-// How the workgroups of one scatter tell each other their digit counts.  Every tile owns one 64-bit
+// How the workgroups of one scatter tell each other their digit counts (the scheme of a single-pass
+// scan with decoupled look-back, Merrill and Garland 2016, applied per digit).  Every tile owns one 64-bit
 // word per digit, cleared before the pass: the top two bits say what the low 32 hold: nothing yet,
 // the tile's own count (SORT_FLAG_COUNT), or the count of the table's tiles up to and including this
 // one (SORT_FLAG_PREFIX).  Count and state travel in one word, written and read with relaxed
