@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "dad5122a2369350f",
+    "sources": "63973a0096099254",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (177523.0, 69037.9), "update_kernel": (240524.4, 324005.7)},
-        "3b": {"bag_forward_train_kernel": (94777.2, 83094.2), "update_kernel": (170146.4, 220380.3)},
-        "2": {"bag_forward_hashed_kernel": (176254.4, 33801.7), "bag_forward_kernel": (177917.9, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338179.8, 33793.5), "bag_forward_kernel": (338146.4, 32768.0)},
-        "2un": {"bag_forward_kernel": (346128.8, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (122248.2, 33832.5)},
-        "2uq4": {"bag_forward_quant_kernel": (232541.8, 33928.7)},
-        "2uq4r": {"bag_forward_quant_kernel": (190396.7, 33870.7)},
-        "4": {"bag_forward_hashed_kernel": (52664.0, 8704.3)},
+        "3": {"bag_forward_train_kernel": (177537.2, 69053.4), "update_kernel": (240550.5, 324005.2)},
+        "3b": {"bag_forward_train_kernel": (94753.0, 83120.1), "update_kernel": (170118.7, 220415.8)},
+        "2": {"bag_forward_hashed_kernel": (176268.0, 33802.5), "bag_forward_kernel": (177930.8, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338180.8, 33793.6), "bag_forward_kernel": (338145.4, 32768.0)},
+        "2un": {"bag_forward_kernel": (346129.9, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (122263.2, 33832.5)},
+        "2uq4": {"bag_forward_quant_kernel": (232548.8, 33927.4)},
+        "2uq4r": {"bag_forward_quant_kernel": (190379.1, 33871.6)},
+        "4": {"bag_forward_hashed_kernel": (52661.9, 8704.3)},
     },
 }
 
