@@ -837,6 +837,9 @@ def main() -> int:
     ap.add_argument("--overlap-sort", action="store_true",
                     help="enqueue the backward's sort on a second stream beside the forward (measured: no gain "
                          "here, the forward saturates HBM and the sort's small kernels only get slower)")
+    ap.add_argument("--no-defer-join", action="store_true",
+                    help="the backward makes the step's stream wait for its side stream at its own end, not in "
+                         "the next step's lookup call")
     ap.add_argument("--no-side-stream", action="store_true",
                     help="run the backward's long-run path after the short-run update instead of beside it")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -898,6 +901,20 @@ def main() -> int:
     off_scratch = (torch.empty(emb.emb_offsets_scratch_bytes(w.T * w.B), dtype=torch.uint8, device=dev)
                    if lengths_route else None)
 
+    # The long-run half of a backward runs on a side stream.  The step's stream does not wait for it at the
+    # end of the backward but in the next step, between that step's set-up launches (which touch neither
+    # the tables nor the previous workspace) and its lookup: a wait met after the awaited work has ended
+    # costs the stream almost nothing, one met before costs some 10 us.  Steps then alternate between two
+    # workspaces.  All of it is work of the timed steps; the last join is waited for before the clock stops.
+    defer_join = (offsets_inside and buf.side is not None and not args.no_defer_join)
+    pair = [buf]
+    if defer_join:
+        second = pipeline.StepBuffers(w, max_nnz, tabs.set.total_rows, dev, side_stream=False)
+        second.side, second.status = buf.side, buf.status
+        buf.side.defer_join = True
+        pair.append(second)
+    steps_run = [0]
+
     def do_index(db):
         """Bag offsets, and the hashing unless it is fused into the forward.  Returns the rows (or None)."""
         if offsets_inside or lengths_route:
@@ -920,8 +937,9 @@ def main() -> int:
 
     def do_forward(db, rows):
         if offsets_inside:
-            emb.emb_bag_forward_train_lengths(tabs.set, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets,
-                                              buf.workspace, None, buf.num_unique, buf.status)
+            emb.emb_bag_forward_train_lengths_after(tabs.set, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets,
+                                                    buf.workspace, buf.side if defer_join else None, None,
+                                                    buf.num_unique, buf.status)
             return None
         if train_route:
             emb.emb_bag_forward_train(tabs.set, db.raw, buf.offsets, w.B, w.pool, buf.out, buf.workspace, None,
@@ -973,7 +991,13 @@ def main() -> int:
 
     dom = [new_events(2) for _ in range((K + EVENT_EVERY - 1) // EVENT_EVERY)]
 
+    def next_buffers():
+        nonlocal buf
+        buf = pair[steps_run[0] % len(pair)]
+        steps_run[0] += 1
+
     def timed_step(db, ev_k):
+        next_buffers()
         if w.backward:
             sev = [None, None, None, ev_k[0], ev_k[1], None] if ev_k else None
             if args.overlap_sort:
@@ -999,6 +1023,8 @@ def main() -> int:
     t0 = time.perf_counter()
     for k in range(K):
         timed_step(dbs[(W + k) % len(dbs)], dom[k // EVENT_EVERY] if k % EVENT_EVERY == 0 else None)
+    if defer_join:
+        buf.side.join()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
@@ -1013,6 +1039,7 @@ def main() -> int:
     torch.cuda.synchronize()
     for k in range(KI):
         db = dbs[(W + k) % len(dbs)]
+        next_buffers()
         ev[k][0].record()
         rows = do_index(db)
         ev[k][1].record()
@@ -1020,6 +1047,8 @@ def main() -> int:
         ev[k][2].record()
         if w.backward:
             do_backward(db, rows, bev[k])
+    if defer_join:
+        buf.side.join()
     torch.cuda.synchronize()
 
     lookups = sum(dbs[(W + k) % len(dbs)].nnz for k in range(K))
@@ -1120,6 +1149,9 @@ def main() -> int:
                        "bwd_unique_list_ms": round(st[2], 4), "bwd_update_ms": round(st[3], 4),
                        "bwd_long_runs_ms": round(st[4], 4), "unique_rows_last_batch": uniq,
                        "backward_algorithmic_bytes": backward_bytes(nnz_i, bags, uniq, w.D, w.esz, passes)})
+        stages["side_stream_join"] = ("in the next step's lookup call, after its set-up launches (two workspaces "
+                                      "alternate; bwd_long_runs_ms no longer contains the wait)" if defer_join
+                                      else ("at the end of the backward" if buf.side is not None else "no side stream"))
     log("step %.3f ms: index %.3f, forward %.3f, backward %.3f %s" % (
         elapsed / K * 1e3, ms_index, ms_fwd, ms_bwd,
         ("(keys %.3f, sort %.3f, update %.3f, long runs %.3f)" % (st[0], st[1], st[3], st[4])) if w.backward else ""))

@@ -156,13 +156,28 @@ size_t emb_bag_backward_workspace_bytes(int32_t T, int64_t B, int64_t nnz, int64
  * created and owned by the caller: stream is a hipStream_t other than the
  * call's `stream`, of default priority; fork_event and join_event are
  * hipEvent_t (timing may be disabled) that no other work uses while the call
- * is in flight.  The call's work is complete, in stream order, on `stream`
- * when it returns; nothing is left pending on the side stream that `stream`
- * does not wait for. */
+ * is in flight.  With defer_join == 0 the call's work is complete, in stream
+ * order, on `stream` when it returns; nothing is left pending on the side
+ * stream that `stream` does not wait for.
+ * defer_join != 0 (set by the caller; a struct filled by hand is zeroed
+ * first): emb_bag_backward_update / emb_bag_backward_rowwise_adagrad record
+ * join_event on the side stream but do not make `stream` wait for it.  A wait
+ * that a stream reaches before the awaited work has ended costs it some
+ * 10 us after that work's end; one that it reaches later costs almost
+ * nothing.  So a training loop defers the wait until work that does not
+ * depend on the update has been enqueued behind it: the next step's
+ * emb_bag_forward_train_lengths_after waits just before its lookup reads the
+ * tables, after its two set-up launches.  Until some stream has waited
+ * (that call, or emb_side_stream_join) and the work ordered after the wait,
+ * the caller must not read or write the tables and accumulators, nor reuse
+ * the backward's workspace and num_unique_out_dev: a loop that defers
+ * alternates between two workspaces. */
 typedef struct emb_side_stream {
     void *stream;
     void *fork_event;
     void *join_event;
+    int32_t defer_join;
+    int32_t reserved;   /* 0 */
 } emb_side_stream;
 
 /* Helpers for callers without a HIP binding of their own.  Events made here
@@ -178,6 +193,9 @@ typedef struct emb_side_stream {
  * if the runtime refuses. */
 int emb_side_stream_create(emb_side_stream *side);
 int emb_side_stream_destroy(emb_side_stream *side);
+/* Make `stream` wait for the work the last backward left on the side stream
+ * (see defer_join; harmless when nothing is pending). */
+int emb_side_stream_join(const emb_side_stream *side, void *stream);
 int emb_event_create(void **event_out, int32_t timing);
 int emb_event_destroy(void *event);
 int emb_event_record(void *event, void *stream);
@@ -387,6 +405,19 @@ int emb_bag_forward_train_lengths(const emb_table *tables_host, const emb_table 
                                   int64_t *rows_out_dev, void *workspace_dev,
                                   size_t workspace_bytes, int64_t *num_unique_out_dev,
                                   uint32_t *status_dev, void *stream);
+/* emb_bag_forward_train_lengths for a loop whose previous backward deferred
+ * its join (emb_side_stream, defer_join): `after` (nullable) is that
+ * backward's side stream; `stream` waits for its join_event after the two
+ * set-up launches and before the lookup.  workspace_dev and
+ * num_unique_out_dev must not be the ones that backward used. */
+int emb_bag_forward_train_lengths_after(const emb_table *tables_host, const emb_table *tables_dev,
+                                        int32_t T, int32_t D, int32_t dtype,
+                                        const uint64_t *raw_dev, const int32_t *lengths_dev,
+                                        int64_t B, int64_t nnz, int32_t mode, float *out_dev,
+                                        int64_t *offsets_out_dev, int64_t *rows_out_dev,
+                                        void *workspace_dev, size_t workspace_bytes,
+                                        int64_t *num_unique_out_dev, uint32_t *status_dev,
+                                        const emb_side_stream *after, void *stream);
 int emb_bag_backward_sort_prepared(const emb_table *tables_host, const emb_table *tables_dev,
                                    int32_t T, int32_t D, int32_t dtype, int64_t B, int64_t nnz,
                                    void *workspace_dev, size_t workspace_bytes,

@@ -47,7 +47,7 @@ EXPORTS = [
     "emb_status_string", "emb_tables_init", "emb_hash_ids", "emb_hash_ids_tables", "emb_lengths_to_offsets",
     "emb_bag_forward", "emb_bag_forward_hashed", "emb_table_shapes_init", "emb_bag_forward_mixed", "emb_bag_backward_workspace_bytes", "emb_bag_backward_rowwise_adagrad",
     "emb_bag_backward_sort", "emb_debug_sort_poll_limit", "emb_bag_backward_update", "emb_bag_forward_train", "emb_bag_forward_train_lengths", "emb_offsets_scratch_bytes", "emb_bag_forward_hashed_lengths", "emb_bag_backward_sort_prepared", "emb_row_bytes", "emb_quantize_rows",
-    "emb_side_stream_create", "emb_side_stream_destroy", "emb_event_create", "emb_event_destroy", "emb_event_record",
+    "emb_side_stream_create", "emb_side_stream_destroy", "emb_side_stream_join", "emb_bag_forward_train_lengths_after", "emb_event_create", "emb_event_destroy", "emb_event_record",
     "emb_event_elapsed_ms",
     "emb_cache_index_bytes", "emb_cache_build", "emb_bag_forward_cached", "emb_bag_forward_cached_hashed", "emb_bag_forward_cached_hashed_lengths", "emb_host_device_pointer",
     "emb_cache_stage_misses", "emb_cache_stage_misses_hashed", "emb_bag_forward_staged",
@@ -131,6 +131,11 @@ def lib() -> C.CDLL:
     L.emb_bag_backward_update.argtypes = [vp, vp, i32, i32, i32, i64, i64, vp, f32, f32, vp, sz, vp, vp, vp, vp]
     L.emb_side_stream_create.restype = C.c_int
     L.emb_side_stream_create.argtypes = [vp]
+    L.emb_side_stream_join.restype = C.c_int
+    L.emb_side_stream_join.argtypes = [vp, vp]
+    L.emb_bag_forward_train_lengths_after.restype = C.c_int
+    L.emb_bag_forward_train_lengths_after.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp, sz, vp,
+                                                      vp, vp, vp]
     L.emb_side_stream_destroy.restype = C.c_int
     L.emb_side_stream_destroy.argtypes = [vp]
     L.emb_event_create.restype = C.c_int
@@ -456,7 +461,8 @@ def emb_bag_backward_workspace_bytes(T: int, B: int, nnz: int, total_rows: int, 
 
 
 class _SideStreamC(C.Structure):
-    _fields_ = [("stream", C.c_void_p), ("fork_event", C.c_void_p), ("join_event", C.c_void_p)]
+    _fields_ = [("stream", C.c_void_p), ("fork_event", C.c_void_p), ("join_event", C.c_void_p),
+                ("defer_join", C.c_int32), ("reserved", C.c_int32)]
 
 
 class SideStream:
@@ -468,6 +474,20 @@ class SideStream:
         self.c = _SideStreamC()
         with torch.cuda.device(device if device is not None else torch.cuda.current_device()):
             _check("emb_side_stream_create", lib().emb_side_stream_create(C.addressof(self.c)))
+
+    @property
+    def defer_join(self) -> bool:
+        """True: a backward leaves its long-run work pending on this stream; the caller joins later
+        (``join``, or ``emb_bag_forward_train_lengths_after``) and alternates workspaces."""
+        return bool(self.c.defer_join)
+
+    @defer_join.setter
+    def defer_join(self, on: bool) -> None:
+        self.c.defer_join = 1 if on else 0
+
+    def join(self) -> None:
+        """Make the current stream wait for what the last backward left on this stream."""
+        _check("emb_side_stream_join", lib().emb_side_stream_join(C.addressof(self.c), _stream()))
 
     def __del__(self):
         try:
@@ -563,6 +583,27 @@ def emb_bag_forward_train_lengths(tables: TableSet, raw: torch.Tensor, lengths: 
         _ptr(offsets_out, torch.int64, "offsets_out"), _ptr(rows_out, torch.int64, "rows_out"),
         _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _ptr(num_unique, torch.int64, "num_unique"),
         _ptr(status, torch.int32, "status"), _stream()))
+
+
+def emb_bag_forward_train_lengths_after(tables: TableSet, raw: torch.Tensor, lengths: torch.Tensor, B: int, mode: str,
+                                        out: torch.Tensor, offsets_out: torch.Tensor, workspace: torch.Tensor,
+                                        after: Optional["SideStream"], rows_out: Optional[torch.Tensor] = None,
+                                        num_unique: Optional[torch.Tensor] = None,
+                                        status: Optional[torch.Tensor] = None) -> None:
+    """``emb_bag_forward_train_lengths`` that waits, just before its lookup, for the work a backward with a
+    deferred join left on ``after``; ``workspace`` and ``num_unique`` are not that backward's."""
+    nnz = raw.numel()
+    n = tables.T * B
+    if lengths.numel() != n or offsets_out.numel() != n + 1 or out.numel() != n * tables.D:
+        raise TypeError("shape mismatch")
+    if rows_out is not None and rows_out.numel() != nnz:
+        raise TypeError("rows_out must have as many elements as raw")
+    _check("emb_bag_forward_train_lengths_after", lib().emb_bag_forward_train_lengths_after(
+        tables.host_ptr, tables.dev_ptr, tables.T, tables.D, DTYPE[tables.dtype], _ptr(raw, _U64, "raw"),
+        _ptr(lengths, torch.int32, "lengths") if n else None, int(B), nnz, POOL[mode], _ptr(out, torch.float32, "out"),
+        _ptr(offsets_out, torch.int64, "offsets_out"), _ptr(rows_out, torch.int64, "rows_out"),
+        _ptr(workspace, torch.uint8, "workspace"), workspace.numel(), _ptr(num_unique, torch.int64, "num_unique"),
+        _ptr(status, torch.int32, "status"), C.addressof(after.c) if after is not None else None, _stream()))
 
 
 def emb_bag_backward_sort_prepared(tables: TableSet, B: int, nnz: int, workspace: torch.Tensor,

@@ -375,6 +375,7 @@ struct BwdArgs {
     uint32_t *status = nullptr;
     void *const *events = nullptr;
     const emb_side_stream *side = nullptr;   // NULL: everything on `stream`
+    const emb_side_stream *after = nullptr;  // emb_bag_forward_train_lengths_after: wait for its join event before the tables are read
     hipStream_t stream = nullptr;
     // record stage event i, if the caller asked for stage timing
     int mark(int i) const
@@ -457,9 +458,11 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
                        (uint32_t)L.qslots, partials, a.num_unique_out);
     EMB_RETURN_IF_LAUNCH_FAILED();
     if (a.side) {
+        // (with defer_join the caller makes its stream wait later: emb_side_stream_join, or the next
+        // step's emb_bag_forward_train_lengths_after)
         hipEvent_t join = reinterpret_cast<hipEvent_t>(a.side->join_event);
-        if (hipEventRecord(join, ls) != hipSuccess || hipStreamWaitEvent(a.stream, join, 0) != hipSuccess)
-            return EMB_ERR_HIP;
+        if (hipEventRecord(join, ls) != hipSuccess) return EMB_ERR_HIP;
+        if (!a.side->defer_join && hipStreamWaitEvent(a.stream, join, 0) != hipSuccess) return EMB_ERR_HIP;
     }
     EMB_MARK(a, 5);
     return EMB_OK;
@@ -772,6 +775,10 @@ int run_train_forward(const BwdArgs &a, const BwdLayout &L, const int64_t *raw, 
                            a.nnz, first_tile, tile_desc, a.nnz > 0 ? (uint32_t)L.tiles : 0u, a.num_unique_out, a.status);
     }
     EMB_RETURN_IF_LAUNCH_FAILED();
+    // Work of an earlier backward that still runs on its side stream changes table rows: the lookup
+    // waits for it; the two launches above read neither tables nor that backward's workspace.
+    if (a.after && hipStreamWaitEvent(a.stream, reinterpret_cast<hipEvent_t>(a.after->join_event), 0) != hipSuccess)
+        return EMB_ERR_HIP;
     if (a.T == 0 || a.B == 0) return EMB_OK;
     const int chunks = a.D * emb_elem_size(a.dtype) / 16;
     int lpr, cpl;
@@ -884,14 +891,15 @@ extern "C" int emb_bag_forward_train(const emb_table *tables_host, const emb_tab
                             : run_train_forward<uint64_t>(a, L, raw, out_dev, rows_out_dev);
 }
 
-extern "C" int emb_bag_forward_train_lengths(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
-                                             int32_t D, int32_t dtype, const uint64_t *raw_dev,
-                                             const int32_t *lengths_dev, int64_t B, int64_t nnz, int32_t mode,
-                                             float *out_dev, int64_t *offsets_out_dev, int64_t *rows_out_dev,
-                                             void *workspace_dev, size_t workspace_bytes, int64_t *num_unique_out_dev,
-                                             uint32_t *status_dev, void *stream)
+static int train_forward_from_lengths(const emb_table *tables_host, const emb_table *tables_dev, int32_t T, int32_t D,
+                                      int32_t dtype, const uint64_t *raw_dev, const int32_t *lengths_dev, int64_t B,
+                                      int64_t nnz, int32_t mode, float *out_dev, int64_t *offsets_out_dev,
+                                      int64_t *rows_out_dev, void *workspace_dev, size_t workspace_bytes,
+                                      int64_t *num_unique_out_dev, uint32_t *status_dev,
+                                      const emb_side_stream *after, void *stream)
 {
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
+    if (after && (!after->join_event || after->stream == stream)) return EMB_ERR_INVALID_ARG;
     BwdArgs a;
     BwdLayout L;
     const int rc = bwd_plan(tables_host, tables_dev, T, D, dtype, B, nnz, workspace_dev, workspace_bytes, stream, a, L);
@@ -902,6 +910,7 @@ extern "C" int emb_bag_forward_train_lengths(const emb_table *tables_host, const
         if (!emb_aligned(out_dev, 16)) return EMB_ERR_INVALID_ARG;
     }
     a.mode = mode;
+    a.after = after;
     a.from_lengths = true;
     a.lengths = lengths_dev;
     a.offsets_out = offsets_out_dev;
@@ -910,6 +919,31 @@ extern "C" int emb_bag_forward_train_lengths(const emb_table *tables_host, const
     const int64_t *raw = reinterpret_cast<const int64_t *>(raw_dev);
     return L.key_bytes == 4 ? run_train_forward<uint32_t>(a, L, raw, out_dev, rows_out_dev)
                             : run_train_forward<uint64_t>(a, L, raw, out_dev, rows_out_dev);
+}
+
+extern "C" int emb_bag_forward_train_lengths(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                                             int32_t D, int32_t dtype, const uint64_t *raw_dev,
+                                             const int32_t *lengths_dev, int64_t B, int64_t nnz, int32_t mode,
+                                             float *out_dev, int64_t *offsets_out_dev, int64_t *rows_out_dev,
+                                             void *workspace_dev, size_t workspace_bytes, int64_t *num_unique_out_dev,
+                                             uint32_t *status_dev, void *stream)
+{
+    return train_forward_from_lengths(tables_host, tables_dev, T, D, dtype, raw_dev, lengths_dev, B, nnz, mode, out_dev,
+                                      offsets_out_dev, rows_out_dev, workspace_dev, workspace_bytes, num_unique_out_dev,
+                                      status_dev, nullptr, stream);
+}
+
+extern "C" int emb_bag_forward_train_lengths_after(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,
+                                                   int32_t D, int32_t dtype, const uint64_t *raw_dev,
+                                                   const int32_t *lengths_dev, int64_t B, int64_t nnz, int32_t mode,
+                                                   float *out_dev, int64_t *offsets_out_dev, int64_t *rows_out_dev,
+                                                   void *workspace_dev, size_t workspace_bytes,
+                                                   int64_t *num_unique_out_dev, uint32_t *status_dev,
+                                                   const emb_side_stream *after, void *stream)
+{
+    return train_forward_from_lengths(tables_host, tables_dev, T, D, dtype, raw_dev, lengths_dev, B, nnz, mode, out_dev,
+                                      offsets_out_dev, rows_out_dev, workspace_dev, workspace_bytes, num_unique_out_dev,
+                                      status_dev, after, stream);
 }
 
 extern "C" int emb_bag_backward_sort_prepared(const emb_table *tables_host, const emb_table *tables_dev, int32_t T,

@@ -41,6 +41,7 @@ extern "C" int emb_side_stream_create(emb_side_stream *side)
 {
     if (!side) return EMB_ERR_INVALID_ARG;
     side->stream = side->fork_event = side->join_event = nullptr;
+    side->defer_join = side->reserved = 0;
     hipStream_t s = nullptr;
     if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) return EMB_ERR_HIP;   // default priority
     side->stream = s;
@@ -49,6 +50,14 @@ extern "C" int emb_side_stream_create(emb_side_stream *side)
         return EMB_ERR_HIP;
     }
     return EMB_OK;
+}
+
+extern "C" int emb_side_stream_join(const emb_side_stream *side, void *stream)
+{
+    if (!side || !side->join_event || side->stream == stream) return EMB_ERR_INVALID_ARG;
+    return hipStreamWaitEvent(emb_stream(stream), reinterpret_cast<hipEvent_t>(side->join_event), 0) == hipSuccess
+               ? EMB_OK
+               : EMB_ERR_HIP;
 }
 
 extern "C" int emb_side_stream_destroy(emb_side_stream *side)

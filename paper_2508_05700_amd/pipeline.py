@@ -164,11 +164,14 @@ def run_step_overlapped(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf:
     return rows
 
 
-def run_train_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers, stage_events=None) -> None:
+def run_train_step(w: Workload, tables: emb.TableSet, db: DeviceBatch, buf: StepBuffers, stage_events=None,
+                   after: Optional[emb.SideStream] = None) -> None:
     """One pass of the whole path for a workload with a backward and raw IDs: the training lookup from
-    bag lengths and raw IDs (offsets, hashing, pooling and the backward's records), sort, update."""
-    emb.emb_bag_forward_train_lengths(tables, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets, buf.workspace, None,
-                                      buf.num_unique, buf.status)
+    bag lengths and raw IDs (offsets, hashing, pooling and the backward's records), sort, update.
+    ``after``: the side stream of the previous step when its join was deferred (``defer_join``); the lookup
+    then waits for it, and ``buf`` must not be the previous step's."""
+    emb.emb_bag_forward_train_lengths_after(tables, db.raw, db.lengths, w.B, w.pool, buf.out, buf.offsets,
+                                            buf.workspace, after, None, buf.num_unique, buf.status)
     emb.emb_bag_backward_sort_prepared(tables, w.B, db.nnz, buf.workspace, buf.unique_keys, buf.unique_counts,
                                        buf.num_unique, buf.status, stage_events)
     emb.emb_bag_backward_update(tables, w.B, db.nnz, db.dout, w.lr, w.eps, buf.workspace, buf.num_unique,

@@ -126,9 +126,9 @@ def test_backward_argument_errors(L):
     noacc = _tables(with_accum=False)
     assert f(*args(th=noacc.ctypes.data)) == UNSUPPORTED
     # a side stream needs a stream of its own and both events
-    side = (C.c_void_p * 3)(FAKE, FAKE, None)
+    side = (C.c_void_p * 4)(FAKE, FAKE, None, None)
     assert f(*args(side=C.addressof(side))) == INVALID
-    side = (C.c_void_p * 3)(None, FAKE, FAKE)           # NULL is the call's own (default) stream here
+    side = (C.c_void_p * 4)(None, FAKE, FAKE, None)           # NULL is the call's own (default) stream here
     assert f(*args(side=C.addressof(side))) == INVALID
 
 
@@ -198,7 +198,7 @@ def test_split_backward_and_helper_argument_errors(L):
     assert upd(*upd_args(dout=FAKE + 4)) == INVALID           # gradient rows are read 16 bytes at a time
     assert upd(*upd_args(ws=None)) == WORKSPACE
     assert upd(*upd_args(nnz=1 << 31)) == UNSUPPORTED
-    side = (C.c_void_p * 3)(FAKE, None, FAKE)
+    side = (C.c_void_p * 4)(FAKE, None, FAKE, None)
     assert upd(*upd_args(side=C.addressof(side))) == INVALID
     # the training lookup and the sort that follows it
     tr, sp = L.emb_bag_forward_train, L.emb_bag_backward_sort_prepared
@@ -246,6 +246,17 @@ def test_split_backward_and_helper_argument_errors(L):
     assert L.emb_event_elapsed_ms(None, None, None) == INVALID
     assert L.emb_event_destroy(None) == OK
     assert L.emb_side_stream_create(None) == INVALID and L.emb_side_stream_destroy(None) == INVALID
+    # the struct as the header declares it and as the binding mirrors it
+    header = open(os.path.join(ROOT, "include", "emb.h")).read()
+    body = re.search(r"typedef struct emb_side_stream \{(.*?)\} emb_side_stream;", header, flags=re.S).group(1)
+    fields = re.findall(r"\b(\w+);", re.sub(r"/\*.*?\*/", "", body, flags=re.S))
+    assert fields == [f[0] for f in b._SideStreamC._fields_] and C.sizeof(b._SideStreamC) == 32
+    # joining: a side stream with its event, and not the stream that is to wait
+    assert L.emb_side_stream_join(None, None) == INVALID
+    side = (C.c_void_p * 4)(FAKE, FAKE, None, None)
+    assert L.emb_side_stream_join(C.addressof(side), None) == INVALID           # no join event
+    side = (C.c_void_p * 4)(None, FAKE, FAKE, None)
+    assert L.emb_side_stream_join(C.addressof(side), None) == INVALID           # its stream is the waiting one
 
 
 def test_mixed_forward_shapes_and_argument_errors(L):

@@ -203,6 +203,59 @@ def test_workload_3_forward_and_backward(tables16):
         assert int((tabs.accum[t] != 0).sum().item()) == int((acc[t] != 0).sum())
 
 
+def test_workload_3_steps_with_the_deferred_join_as_the_benchmark_runs_them(tables16):
+    # The benchmark's loop defers the wait for the backward's side stream into the next step's lookup call
+    # and alternates between two workspaces.  At full size: a step on batch 1 followed by the lookup of
+    # batch 2, once joining at the end of the backward (the route the test above checks against the
+    # oracle) and once deferred, from the same table state: pooled outputs of both lookups and every row and
+    # accumulator the two batches touch, bit for bit.
+    w = wl.WORKLOADS["3"]
+    tabs = tables16
+    dev = tabs.device
+    b1, b2 = wl.make_batch(w, 1), wl.make_batch(w, 2)
+    d1, d2 = pipeline.DeviceBatch(w, b1, dev), pipeline.DeviceBatch(w, b2, dev)
+    n = max(d1.nnz, d2.nnz)
+    buf_a = pipeline.StepBuffers(w, n, tabs.set.total_rows, dev)
+    buf_b = pipeline.StepBuffers(w, n, tabs.set.total_rows, dev, side_stream=False)
+    side = buf_a.side
+    (off1, rows1), (off2, rows2) = _oracle_index(w, b1), _oracle_index(w, b2)
+    touched = [torch.from_numpy(np.unique(np.concatenate([rows1[off1[t * w.B]:off1[(t + 1) * w.B]],
+                                                          rows2[off2[t * w.B]:off2[(t + 1) * w.B]]]))).to(dev)
+               for t in range(w.T)]
+    saved = [(tabs.weights[t][touched[t]].clone(), tabs.accum[t][touched[t]].clone()) for t in range(w.T)]
+
+    def route(defer):
+        side.defer_join = defer
+        pipeline.run_train_step(w, tabs.set, d1, buf_a)
+        # the next step's lookup alone (its backward would only repeat what the first step showed)
+        emb.emb_bag_forward_train_lengths_after(tabs.set, d2.raw, d2.lengths, w.B, w.pool, buf_b.out, buf_b.offsets,
+                                                buf_b.workspace, side if defer else None, None, buf_b.num_unique,
+                                                buf_a.status)
+        torch.cuda.synchronize()
+        assert int(buf_a.status.item()) == 0
+        state = [(tabs.weights[t][touched[t]].clone(), tabs.accum[t][touched[t]].clone()) for t in range(w.T)]
+        outs = (buf_a.out.clone(), buf_b.out.clone(), buf_b.offsets.clone())
+        for t in range(w.T):                      # back to the state both routes start from
+            tabs.weights[t][touched[t]] = saved[t][0]
+            tabs.accum[t][touched[t]] = saved[t][1]
+        torch.cuda.synchronize()
+        return outs, state
+
+    say("workload 3: step + next lookup, join at the end of the backward")
+    outs_a, state_a = route(False)
+    say("workload 3: the same with the join deferred into the next lookup")
+    outs_b, state_b = route(True)
+    side.defer_join = False
+    assert all(torch.equal(x, y) for x, y in zip(outs_a, outs_b))
+    changed = 0
+    for t in range(w.T):
+        assert torch.equal(state_a[t][0], state_b[t][0]) and torch.equal(state_a[t][1], state_b[t][1]), t
+        changed += int((state_a[t][0] != saved[t][0]).any(dim=1).sum().item())
+    assert changed > 500_000                      # the step did change rows, and the second lookup read some of them
+    del buf_a, buf_b, saved, state_a, state_b
+    torch.cuda.empty_cache()
+
+
 def test_workload_3b_bf16_tables_forward_and_backward():
     # Workload 3 with bf16 rows at full size, by the route the benchmark times.  Pooled values see no bf16
     # rounding (rows are widened exactly, sums are fp32): 1e-5.  Updated rows are written as bf16: 1e-2.

@@ -1137,6 +1137,73 @@ def test_backward_bad_indices_skipped_and_bad_offsets_abort():
             assert np.all(acc_dev[t].cpu().numpy() == 0)
 
 
+def test_training_steps_with_the_join_deferred_into_the_next_lookup_equal_steps_that_join_at_once():
+    # Five training steps over the same tables (hot IDs in every batch, so the long-run path on the side
+    # stream has work and its rows are read again by the next step's lookup).  Route A joins the side
+    # stream at the end of every backward; route B defers the join into the next step's lookup call and
+    # alternates between two workspaces.  Pooled outputs of every step, final tables and accumulators bit
+    # for bit; route A's final tables against the oracle run over the same five steps.
+    rng = np.random.default_rng(4477)
+    T, B, D = 3, 1200, 16
+    Rs = [30_000, 17, 50_001]
+    salts = [3, 9, 27]
+    tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for R in Rs]
+    steps = []
+    for k in range(5):
+        lengths = rng.integers(0, 30, size=T * B).astype(np.int32)
+        off, _ = oracle.lengths_to_offsets(lengths)
+        raw = rng.integers(0, 1 << 64, size=int(off[-1]), dtype=np.uint64)
+        raw[rng.random(raw.size) < 0.3] = 12345                        # a hot ID in every table
+        dout = rng.standard_normal((T, B, D)).astype(np.float32)
+        steps.append((lengths, off, raw, dout))
+
+    def run(defer):
+        w = [H.dev(t) for t in tables]
+        acc = [torch.zeros(R, dtype=torch.float32, device=H.DEV) for R in Rs]
+        ts = emb.TableSet(w, D, "f32", accum=acc, salts=salts, device=torch.device(H.DEV))
+        max_nnz = max(s[2].size for s in steps)
+        nbytes = emb.emb_bag_backward_workspace_bytes(T, B, max_nnz, ts.total_rows, D, "f32")
+        wss = [torch.empty(nbytes, dtype=torch.uint8, device=H.DEV) for _ in range(2 if defer else 1)]
+        nus = [torch.zeros(1, dtype=torch.int64, device=H.DEV) for _ in wss]
+        side = emb.SideStream(torch.device(H.DEV))
+        side.defer_join = defer
+        st = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+        outs, offs = [], []
+        for k, (lengths, off, raw, dout) in enumerate(steps):
+            ws, nu = wss[k % len(wss)], nus[k % len(wss)]
+            out = torch.full((T, B, D), float("nan"), dtype=torch.float32, device=H.DEV)
+            offs_out = torch.full((T * B + 1,), -1, dtype=torch.int64, device=H.DEV)
+            emb.emb_bag_forward_train_lengths_after(ts, H.dev(raw), H.dev(lengths), B, "sum", out, offs_out, ws,
+                                                    side if defer else None, None, nu, st)
+            emb.emb_bag_backward_sort_prepared(ts, B, raw.size, ws, None, None, nu, st)
+            emb.emb_bag_backward_update(ts, B, raw.size, H.dev(dout), 0.05, 1e-8, ws, nu, None, side)
+            outs.append(out)
+            offs.append(offs_out)
+        if defer:
+            side.join()
+        torch.cuda.synchronize()
+        assert st.item() == 0
+        return outs, offs, w, acc
+
+    outs_a, offs_a, w_a, acc_a = run(False)
+    outs_b, offs_b, w_b, acc_b = run(True)
+    for k in range(len(steps)):
+        assert torch.equal(outs_a[k], outs_b[k]) and torch.equal(offs_a[k], offs_b[k]), k
+        assert np.array_equal(offs_a[k].cpu().numpy(), steps[k][1])
+    for t in range(T):
+        assert torch.equal(w_a[t], w_b[t]) and torch.equal(acc_a[t], acc_b[t]), t
+    ref_t, ref_a = [t.copy() for t in tables], [np.zeros(R, np.float32) for R in Rs]
+    for lengths, off, raw, dout in steps:
+        rows = np.concatenate([oracle.hash_ids(raw[off[t * B]:off[(t + 1) * B]], salts[t], Rs[t]) for t in range(T)])
+        oracle.bag_backward_rowwise_adagrad(ref_t, ref_a, "f32", rows, off, B, "sum", dout, 0.05, 1e-8)
+    for t in range(T):
+        changed = np.flatnonzero((ref_t[t] != tables[t]).any(axis=1))
+        assert changed.size > 0
+        H.assert_rows_close(w_a[t].cpu().numpy()[changed], ref_t[t][changed], tables[t][changed], 0.05 * len(steps),
+                            what="five steps t=%d" % t)
+        assert np.array_equal(np.flatnonzero((w_a[t].cpu().numpy() != tables[t]).any(axis=1)), changed)
+
+
 def test_backward_sort_wait_that_runs_out_abandons_the_backward_and_changes_nothing():
     # From the second pass on, the workgroups of a sort pass wait for each other's digit counts; the waits are
     # bounded.  With the bound at zero every wait fails at once (forced from the host; every kernel still runs
