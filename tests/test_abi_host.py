@@ -224,6 +224,16 @@ def test_split_backward_and_helper_argument_errors(L):
     assert trl(*trl_args(out=None)) == INVALID and trl(*trl_args(raw=None)) == INVALID
     assert trl(*trl_args(mode=2)) == INVALID
     assert trl(*trl_args(wsb=need - 256)) == WORKSPACE and trl(*trl_args(ws=None)) == WORKSPACE
+    # ... and the form that waits for an earlier backward's side stream: the same refusals, and the side
+    # stream needs its join event and must not be the call's own stream (NULL here)
+    tra = L.emb_bag_forward_train_lengths_after
+    for kw in (dict(offs=None), dict(lengths=None), dict(out=None), dict(raw=None), dict(mode=2)):
+        assert tra(*(trl_args(**kw)[:-1] + [None, None])) == INVALID, kw
+    assert tra(*(trl_args(wsb=need - 256)[:-1] + [None, None])) == WORKSPACE
+    side = (C.c_void_p * 4)(FAKE, FAKE, None, None)
+    assert tra(*(trl_args()[:-1] + [C.addressof(side), None])) == INVALID
+    side = (C.c_void_p * 4)(None, FAKE, FAKE, None)
+    assert tra(*(trl_args()[:-1] + [C.addressof(side), None])) == INVALID
     # the forward-only lookup taking bag lengths
     L.emb_offsets_scratch_bytes.restype = C.c_size_t
     assert L.emb_offsets_scratch_bytes(C.c_int64(8)) == 72 and L.emb_offsets_scratch_bytes(C.c_int64(-1)) == 0
