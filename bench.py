@@ -319,13 +319,10 @@ def bench_hybrid(args) -> int:
     def step(db, e=None):
         if e:
             e[0].record()
-        if from_lengths:   # bag lengths in: the sums within tiles, then the lookup (index time counts with the lookup)
-            if e:
-                e[1].record()
+        if from_lengths:   # bag lengths in: the sums within tiles, then the lookup, which the library brackets itself
             emb.emb_bag_forward_cached_hashed_lengths(ptr, w.R, w.D, store, cache, index, n_hot, w.salt(0), db.raw,
-                                                      db.lengths, w.B, w.pool, out, offsets, off_scratch, hm, status)
-            if e:
-                e[2].record()
+                                                      db.lengths, w.B, w.pool, out, offsets, off_scratch, hm, status,
+                                                      lookup_events=(e[1], e[2]) if e else None)
             return
         emb.emb_lengths_to_offsets(db.lengths, offsets, status)
         if args.no_fused_forward:
@@ -457,9 +454,9 @@ def bench_hybrid(args) -> int:
                    "lookups_per_step": round(lookups / K, 1), "resident_batches": len(dbs), "seed": seed},
         "stages": {"index_ms": round(ms_index, 4), "forward_cached_ms": round(ms_fwd, 4),
                    "hit_rate": round(hits / max(1, hits + misses), 5), "misses_per_step": round(misses / K, 1)},
-        "roofline": {"kernel": ("offsets_tile_scan_kernel + " if from_lengths else "") +
-                               ("bag_forward_cached_quant_kernel" if w.quant else "bag_forward_cached_kernel"),
-                     "bag_offsets": "made inside the lookup's call" if from_lengths else "separate launches",
+        "roofline": {"kernel": "bag_forward_cached_quant_kernel" if w.quant else "bag_forward_cached_kernel",
+                     "bag_offsets": ("made inside the lookup's call (the kernel is bracketed by events the library "
+                                     "records)" if from_lengths else "separate launches"),
                      "bound": "pcie", "achieved": round(pcie_gbs, 2),
                      "peak": PCIE_PEAK, "unit": "GB/s", "frac": round(pcie_gbs / PCIE_PEAK, 4), "traffic": None,
                      "avg_ms": round(ms_fwd, 4), "algorithmic_bytes": int(misses / K * rowb),
@@ -541,13 +538,10 @@ def bench_hybrid_tables(args) -> int:
     off_scratch = torch.empty(emb.emb_offsets_scratch_bytes(w.T * w.B), dtype=torch.uint8, device=dev)
 
     def step_one_launch(db, e=None):
-        if from_lengths:   # bag lengths in: the events bracket the sums within tiles and the lookup
-            if e:
-                e[0].record()
+        if from_lengths:   # bag lengths in: the library brackets the lookup kernel itself
             emb.emb_bag_forward_cached_tables_hashed_lengths(ct, db.raw, db.lengths, w.B, w.pool, out, offsets,
-                                                             off_scratch, hm, status)
-            if e:
-                e[1].record()
+                                                             off_scratch, hm, status,
+                                                             lookup_events=(e[0], e[1]) if e else None)
             return
         emb.emb_lengths_to_offsets(db.lengths, offsets, status)
         if e:
@@ -603,9 +597,9 @@ def bench_hybrid_tables(args) -> int:
         "stages": {"forward_cached_tables_ms": round(ms_fwd, 4), "hit_rate": round(hits / max(1, hits + misses), 5),
                    "misses_per_step": round(misses / K, 1),
                    "one_lookup_per_table": {"ms_per_step": round(dt_pt / K * 1e3, 4), "lookups_ms": round(ms_pt, 4)}},
-        "roofline": {"kernel": ("offsets_tile_scan_kernel + " if from_lengths else "") +
-                               ("bag_forward_cached_tables_quant_kernel" if w.quant else "bag_forward_cached_tables_kernel"),
-                     "bag_offsets": "made inside the lookup's call" if from_lengths else "separate launches",
+        "roofline": {"kernel": "bag_forward_cached_tables_quant_kernel" if w.quant else "bag_forward_cached_tables_kernel",
+                     "bag_offsets": ("made inside the lookup's call (the kernel is bracketed by events the library "
+                                     "records)" if from_lengths else "separate launches"),
                      "bound": "pcie", "achieved": round(pcie_gbs, 2), "peak": PCIE_PEAK, "unit": "GB/s",
                      "frac": round(pcie_gbs / PCIE_PEAK, 4), "traffic": None, "avg_ms": round(ms_fwd, 4),
                      "algorithmic_bytes": int(misses / K * rowb),

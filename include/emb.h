@@ -489,7 +489,10 @@ int emb_bag_forward_cached_hashed(const void *table_dev, int64_t num_rows, int32
  * hit/miss counts and status bits equal those of the two calls.
  * EMB_ERR_UNSUPPORTED for more than 1 048 576 bags.  nnz must be the sum of
  * the lengths; a negative length counts as 0 and sets EMB_STATUS_BAD_OFFSETS;
- * offsets_out_dev must not overlap lengths_dev or scratch_dev. */
+ * offsets_out_dev must not overlap lengths_dev or scratch_dev.
+ * lookup_events (host, nullable): two hipEvent_t handles, each nullable,
+ * recorded on `stream` just before and just after the lookup kernel, for
+ * callers that time it apart from the launch that sums the lengths. */
 int emb_bag_forward_cached_hashed_lengths(const void *table_dev, int64_t num_rows, int32_t D,
                                           int32_t dtype, const void *cache_rows_dev,
                                           const void *cache_index_dev, int64_t num_hot,
@@ -498,7 +501,7 @@ int emb_bag_forward_cached_hashed_lengths(const void *table_dev, int64_t num_row
                                           int32_t mode, float *out_dev, int64_t *offsets_out_dev,
                                           void *scratch_dev, size_t scratch_bytes,
                                           uint64_t *hit_miss_dev, uint32_t *status_dev,
-                                          void *stream);
+                                          void *const *lookup_events, void *stream);
 
 /* The rows a hosted table's lookups miss in the cache, fetched ahead of the
  * lookups (Section 3.4: the fetch from CPU memory starts at the first moment
@@ -593,7 +596,7 @@ int emb_bag_forward_cached_tables_hashed_lengths(
     const emb_cached_table *tables_host, const emb_cached_table *tables_dev, int32_t T, int32_t D,
     int32_t dtype, const uint64_t *raw_dev, const int32_t *lengths_dev, int64_t B, int64_t nnz,
     int32_t mode, float *out_dev, int64_t *offsets_out_dev, void *scratch_dev, size_t scratch_bytes,
-    uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream);
+    uint64_t *hit_miss_dev, uint32_t *status_dev, void *const *lookup_events, void *stream);
 
 /* ---- which rows the cache holds: frequency-based policy -------------------
  * Section 6 lists better caching strategies as open work and the paper names

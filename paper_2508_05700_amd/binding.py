@@ -207,10 +207,10 @@ def lib() -> C.CDLL:
     L.emb_bag_forward_cached_tables.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     L.emb_bag_forward_cached_tables_hashed_lengths.restype = C.c_int
     L.emb_bag_forward_cached_tables_hashed_lengths.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp,
-                                                               sz, vp, vp, vp]
+                                                               sz, vp, vp, vp, vp]
     L.emb_bag_forward_cached_hashed_lengths.restype = C.c_int
     L.emb_bag_forward_cached_hashed_lengths.argtypes = [vp, i64, i32, i32, vp, vp, i64, u64, vp, vp, i64, i64, i32, vp,
-                                                        vp, vp, sz, vp, vp, vp]
+                                                        vp, vp, sz, vp, vp, vp, vp]
     L.emb_bag_forward_cached_tables_hashed.restype = C.c_int
     L.emb_bag_forward_cached_tables_hashed.argtypes = [vp, vp, i32, i32, i32, vp, vp, i64, i64, i32, vp, vp, vp, vp]
     L.emb_checksum.restype = C.c_int
@@ -521,6 +521,15 @@ class Event:
             pass
 
 
+def _lookup_events(events):
+    """Two events (each may be None) recorded around the lookup kernel of a call that launches two."""
+    if events is None:
+        return None
+    if len(events) != 2:
+        raise TypeError("lookup_events must hold 2 events")
+    return (C.c_void_p * 2)(*[None if e is None else int(e.cuda_event) for e in events])
+
+
 def _stage_events(stage_events):
     if stage_events is None:
         return None
@@ -713,7 +722,7 @@ def emb_bag_forward_cached_hashed_lengths(table_ptr: int, num_rows: int, D: int,
                                           lengths: torch.Tensor, B: int, mode: str, out: torch.Tensor,
                                           offsets_out: torch.Tensor, scratch: torch.Tensor,
                                           hit_miss: Optional[torch.Tensor] = None,
-                                          status: Optional[torch.Tensor] = None) -> None:
+                                          status: Optional[torch.Tensor] = None, lookup_events=None) -> None:
     """``emb_bag_forward_cached_hashed`` from the ``B`` bag lengths; writes the offsets to ``offsets_out``;
     ``scratch`` holds ``emb_offsets_scratch_bytes(B)`` bytes."""
     if lengths.numel() != B or offsets_out.numel() != B + 1 or out.numel() != B * D:
@@ -724,7 +733,7 @@ def emb_bag_forward_cached_hashed_lengths(table_ptr: int, num_rows: int, D: int,
         _ptr(raw, _U64, "raw"), _ptr(lengths, torch.int32, "lengths") if B else None, int(B), raw.numel(), POOL[mode],
         _ptr(out, torch.float32, "out"), _ptr(offsets_out, torch.int64, "offsets_out"),
         _ptr(scratch, torch.uint8, "scratch"), scratch.numel(), _ptr(hit_miss, _U64, "hit_miss"),
-        _ptr(status, torch.int32, "status"), _stream()))
+        _ptr(status, torch.int32, "status"), _lookup_events(lookup_events), _stream()))
 
 
 def emb_cache_stage_misses(table_ptr: int, num_rows: int, D: int, dtype: str, cache_index: torch.Tensor, num_hot: int,
@@ -935,7 +944,7 @@ def emb_bag_forward_cached_tables_hashed(ct: CachedTables, raw: torch.Tensor, of
 def emb_bag_forward_cached_tables_hashed_lengths(ct: CachedTables, raw: torch.Tensor, lengths: torch.Tensor, B: int,
                                                  mode: str, out: torch.Tensor, offsets_out: torch.Tensor,
                                                  scratch: torch.Tensor, hit_miss: Optional[torch.Tensor] = None,
-                                                 status: Optional[torch.Tensor] = None) -> None:
+                                                 status: Optional[torch.Tensor] = None, lookup_events=None) -> None:
     """``emb_bag_forward_cached_tables_hashed`` from the ``T * B`` bag lengths; writes the offsets to
     ``offsets_out``; ``scratch`` holds ``emb_offsets_scratch_bytes(T * B)`` bytes."""
     n = ct.T * B
@@ -946,7 +955,7 @@ def emb_bag_forward_cached_tables_hashed_lengths(ct: CachedTables, raw: torch.Te
         _ptr(lengths, torch.int32, "lengths") if n else None, int(B), raw.numel(), POOL[mode],
         _ptr(out, torch.float32, "out"), _ptr(offsets_out, torch.int64, "offsets_out"),
         _ptr(scratch, torch.uint8, "scratch"), scratch.numel(), _ptr(hit_miss, _U64, "hit_miss"),
-        _ptr(status, torch.int32, "status"), _stream()))
+        _ptr(status, torch.int32, "status"), _lookup_events(lookup_events), _stream()))
 
 
 def emb_checksum(data, sum_out: torch.Tensor, nbytes: Optional[int] = None) -> None:

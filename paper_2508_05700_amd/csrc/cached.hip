@@ -577,13 +577,21 @@ static int lengths_front(const int32_t *lengths_dev, int64_t n, int64_t *offsets
 }
 static_assert(CF_BLOCK == Q_BLOCK, "the cached lookups over plain and quantised rows scan the same number of tiles");
 
+// For callers that time the lookup kernel of a call that launches two: events[i] (hipEvent_t; the array and
+// each entry nullable) is recorded on the call's stream.
+static bool lookup_event(void *const *events, int i, void *stream)
+{
+    if (!events || !events[i]) return true;
+    return hipEventRecord(reinterpret_cast<hipEvent_t>(events[i]), emb_stream(stream)) == hipSuccess;
+}
+
 extern "C" int emb_bag_forward_cached_hashed_lengths(const void *table_dev, int64_t num_rows, int32_t D, int32_t dtype,
                                                      const void *cache_rows_dev, const void *cache_index_dev,
                                                      int64_t num_hot, uint64_t salt, const uint64_t *raw_dev,
                                                      const int32_t *lengths_dev, int64_t B, int64_t nnz, int32_t mode,
                                                      float *out_dev, int64_t *offsets_out_dev, void *scratch_dev,
                                                      size_t scratch_bytes, uint64_t *hit_miss_dev,
-                                                     uint32_t *status_dev, void *stream)
+                                                     uint32_t *status_dev, void *const *lookup_events, void *stream)
 {
     // everything the lookup itself would refuse is refused before the first launch: a dry call without bags
     int rc = cached_entry(table_dev, num_rows, D, dtype, cache_rows_dev, cache_index_dev, num_hot, nullptr, nullptr, 0,
@@ -598,9 +606,12 @@ extern "C" int emb_bag_forward_cached_hashed_lengths(const void *table_dev, int6
     const int64_t *local = nullptr;
     rc = lengths_front(lengths_dev, B, offsets_out_dev, scratch_dev, scratch_bytes, status_dev, stream, &local);
     if (rc != EMB_OK) return rc > 0 ? EMB_OK : rc;
-    return cached_entry(table_dev, num_rows, D, dtype, cache_rows_dev, cache_index_dev, num_hot,
-                        reinterpret_cast<const int64_t *>(raw_dev), local, B, nnz, mode, out_dev, hit_miss_dev,
-                        status_dev, stream, true, salt, offsets_out_dev);
+    if (!lookup_event(lookup_events, 0, stream)) return EMB_ERR_HIP;
+    rc = cached_entry(table_dev, num_rows, D, dtype, cache_rows_dev, cache_index_dev, num_hot,
+                      reinterpret_cast<const int64_t *>(raw_dev), local, B, nnz, mode, out_dev, hit_miss_dev, status_dev,
+                      stream, true, salt, offsets_out_dev);
+    if (rc != EMB_OK) return rc;
+    return lookup_event(lookup_events, 1, stream) ? EMB_OK : EMB_ERR_HIP;
 }
 
 extern "C" int emb_cached_tables_init(emb_cached_table *tables_host, int32_t T)
@@ -635,7 +646,8 @@ extern "C" int emb_bag_forward_cached_tables_hashed_lengths(const emb_cached_tab
                                                             const int32_t *lengths_dev, int64_t B, int64_t nnz,
                                                             int32_t mode, float *out_dev, int64_t *offsets_out_dev,
                                                             void *scratch_dev, size_t scratch_bytes,
-                                                            uint64_t *hit_miss_dev, uint32_t *status_dev, void *stream)
+                                                            uint64_t *hit_miss_dev, uint32_t *status_dev,
+                                                            void *const *lookup_events, void *stream)
 {
     if (T < 0 || B < 0 || nnz < 0) return EMB_ERR_INVALID_ARG;
     if (mode != EMB_POOL_SUM && mode != EMB_POOL_MEAN) return EMB_ERR_INVALID_ARG;
@@ -651,9 +663,11 @@ extern "C" int emb_bag_forward_cached_tables_hashed_lengths(const emb_cached_tab
     const int64_t *local = nullptr;
     rc = lengths_front(lengths_dev, n, offsets_out_dev, scratch_dev, scratch_bytes, status_dev, stream, &local);
     if (rc != EMB_OK) return rc > 0 ? EMB_OK : rc;
-    return emb_forward_cached_unchecked_tables(tables_dev, T, D, dtype, reinterpret_cast<const int64_t *>(raw_dev), local,
-                                               B, nnz, mode, out_dev, hit_miss_dev, status_dev, stream, true,
-                                               offsets_out_dev);
+    if (!lookup_event(lookup_events, 0, stream)) return EMB_ERR_HIP;
+    rc = emb_forward_cached_unchecked_tables(tables_dev, T, D, dtype, reinterpret_cast<const int64_t *>(raw_dev), local, B,
+                                             nnz, mode, out_dev, hit_miss_dev, status_dev, stream, true, offsets_out_dev);
+    if (rc != EMB_OK) return rc;
+    return lookup_event(lookup_events, 1, stream) ? EMB_OK : EMB_ERR_HIP;
 }
 
 // The launch of the multi-table cached lookup over descriptors that live in device memory only and

@@ -482,31 +482,32 @@ def test_cached_lookups_from_lengths_argument_errors(L):
     assert L.emb_cached_tables_init(d.ctypes.data, 2) == OK
     th = d.ctypes.data
     fn = L.emb_bag_forward_cached_tables_hashed_lengths
-    #  th, td, T, D, dtype, raw, lengths, B, nnz, mode, out, offsets_out, scratch, scratch_bytes, hit_miss, status, stream
-    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, FAKE, 72, None, None, None) == INVALID   # no offsets_out
-    assert fn(th, FAKE, 2, 64, 0, FAKE, None, 4, 8, 0, FAKE, FAKE, FAKE, 72, None, None, None) == INVALID   # no lengths
-    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, None, 72, None, None, None) == INVALID   # no scratch
-    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 64, None, None, None) == INVALID   # 9 sums need 72 bytes
-    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE + 8, 72, None, None, None) == INVALID
-    assert fn(None, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 72, None, None, None) == INVALID
-    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 7, FAKE, FAKE, FAKE, 72, None, None, None) == INVALID   # pooling mode
-    assert fn(th, FAKE, 2, 6, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 72, None, None, None) == UNSUPPORTED
-    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, (1 << 19) + 1, 8, 0, FAKE, FAKE, FAKE, 1 << 24, None, None, None) == UNSUPPORTED
+    #  th, td, T, D, dtype, raw, lengths, B, nnz, mode, out, offsets_out, scratch, scratch_bytes, hit_miss, status,
+    #  lookup_events, stream
+    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, None, FAKE, 72, None, None, None, None) == INVALID   # no offsets_out
+    assert fn(th, FAKE, 2, 64, 0, FAKE, None, 4, 8, 0, FAKE, FAKE, FAKE, 72, None, None, None, None) == INVALID   # no lengths
+    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, None, 72, None, None, None, None) == INVALID   # no scratch
+    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 64, None, None, None, None) == INVALID   # 9 sums need 72 bytes
+    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE + 8, 72, None, None, None, None) == INVALID
+    assert fn(None, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 72, None, None, None, None) == INVALID
+    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 7, FAKE, FAKE, FAKE, 72, None, None, None, None) == INVALID   # pooling mode
+    assert fn(th, FAKE, 2, 6, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 72, None, None, None, None) == UNSUPPORTED
+    assert fn(th, FAKE, 2, 64, 0, FAKE, FAKE, (1 << 19) + 1, 8, 0, FAKE, FAKE, FAKE, 1 << 24, None, None, None, None) == UNSUPPORTED
     bad = d.copy()
     bad["mod_magic"][1] = 1
-    assert fn(bad.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 72, None, None, None) == INVALID
+    assert fn(bad.ctypes.data, FAKE, 2, 64, 0, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 72, None, None, None, None) == INVALID
     one = L.emb_bag_forward_cached_hashed_lengths
     #  table, num_rows, D, dtype, cache_rows, cache_index, num_hot, salt, raw, lengths, B, nnz, mode, out, offsets_out,
-    #  scratch, scratch_bytes, hit_miss, status, stream
-    assert one(FAKE, 100, 64, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, None, FAKE, 40, None, None, None) == INVALID
-    assert one(FAKE, 100, 64, 0, FAKE, FAKE, 10, 1, FAKE, None, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None) == INVALID
-    assert one(FAKE, 100, 64, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 32, None, None, None) == INVALID
-    assert one(None, 100, 64, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None) == INVALID
-    assert one(FAKE, 0, 64, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None) == INVALID
-    assert one(FAKE, 100, 64, 0, FAKE, FAKE, 10, 1, None, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None) == INVALID
-    assert one(FAKE, 100, 6, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None) == UNSUPPORTED
+    #  scratch, scratch_bytes, hit_miss, status, lookup_events, stream
+    assert one(FAKE, 100, 64, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, None, FAKE, 40, None, None, None, None) == INVALID
+    assert one(FAKE, 100, 64, 0, FAKE, FAKE, 10, 1, FAKE, None, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None, None) == INVALID
+    assert one(FAKE, 100, 64, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 32, None, None, None, None) == INVALID
+    assert one(None, 100, 64, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None, None) == INVALID
+    assert one(FAKE, 0, 64, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None, None) == INVALID
+    assert one(FAKE, 100, 64, 0, FAKE, FAKE, 10, 1, None, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None, None) == INVALID
+    assert one(FAKE, 100, 6, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, 4, 8, 0, FAKE, FAKE, FAKE, 40, None, None, None, None) == UNSUPPORTED
     assert one(FAKE, 100, 64, 0, FAKE, FAKE, 10, 1, FAKE, FAKE, (1 << 20) + 1, 8, 0, FAKE, FAKE, FAKE, 1 << 24, None, None,
-               None) == UNSUPPORTED
+               None, None) == UNSUPPORTED
 
 
 def test_checksum_argument_errors(L):
