@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "66fe49c9c8ab8929",
+    "sources": "67f1ca655509d13b",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (177539.8, 69042.6), "update_kernel": (240469.5, 324007.4)},
-        "3b": {"bag_forward_train_kernel": (94875.8, 83257.9), "update_kernel": (169626.1, 220171.6)},
-        "2": {"bag_forward_hashed_kernel": (176249.8, 33802.6), "bag_forward_kernel": (177907.2, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338181.4, 33793.6), "bag_forward_kernel": (338141.9, 32768.0)},
-        "2un": {"bag_forward_kernel": (346128.7, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (122388.8, 33833.6)},
-        "2uq4": {"bag_forward_quant_kernel": (232560.8, 33931.5)},
-        "2uq4r": {"bag_forward_quant_kernel": (190427.2, 33874.7)},
-        "4": {"bag_forward_hashed_kernel": (52676.6, 8704.3)},
+        "3": {"bag_forward_train_kernel": (177517.3, 69002.2), "update_kernel": (240533.5, 324005.4)},
+        "3b": {"bag_forward_train_kernel": (94813.2, 83185.9), "update_kernel": (169945.0, 220257.2)},
+        "2": {"bag_forward_hashed_kernel": (176274.3, 33802.5), "bag_forward_kernel": (177931.5, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338181.8, 33793.2), "bag_forward_kernel": (338142.9, 32768.0)},
+        "2un": {"bag_forward_kernel": (346125.4, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (122286.1, 33831.4)},
+        "2uq4": {"bag_forward_quant_kernel": (232523.4, 33926.4)},
+        "2uq4r": {"bag_forward_quant_kernel": (190397.1, 33874.4)},
+        "4": {"bag_forward_hashed_kernel": (52668.9, 8704.3)},
     },
 }
 
