@@ -1172,6 +1172,29 @@ def main() -> int:
     # ---- side measurements: the forward kernel alone on workloads 2 and 2u, and over INT4 copies
     # of the same tables (2q4, 2uq4; 2uq4r: the INT4 rows padded to 64 bytes)
     extra = {}
+    if not args.no_extra and w.backward and not args.overlap_sort:
+        # the step when the trainer also wants the ordered list of distinct rows and their counts (optional
+        # outputs of the sort, not written in the timed steps)
+        for b_ in pair:
+            b_.unique_keys = torch.empty(max(max_nnz, 1), dtype=torch.int64, device=dev)
+            b_.unique_counts = torch.empty(max(max_nnz, 1), dtype=torch.int32, device=dev)
+        KU = min(K, 50)
+        for i in range(3):
+            timed_step(dbs[i % len(dbs)], None)
+        torch.cuda.synchronize()
+        tu = time.perf_counter()
+        for k in range(KU):
+            timed_step(dbs[(W + k) % len(dbs)], None)
+        if defer_join:
+            buf.side.join()
+        torch.cuda.synchronize()
+        ms_u = (time.perf_counter() - tu) / KU * 1e3
+        assert int(buf.status.item()) == 0
+        for b_ in pair:
+            b_.unique_keys = b_.unique_counts = None
+        extra["step_with_distinct_row_list"] = {"ms_per_step": round(ms_u, 4), "steps": KU,
+                                                "adds_ms": round(ms_u - elapsed / K * 1e3, 4)}
+        log("with the list of distinct rows written: step %.3f ms (+%.3f)" % (ms_u, ms_u - elapsed / K * 1e3))
     if not args.no_extra and args.workload == "3" and not args.scale_rows:
         qsets = {}
         for name in ("2", "2un", "2u", "2q4", "2uq4", "2uq4r"):

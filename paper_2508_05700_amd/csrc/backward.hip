@@ -93,7 +93,7 @@ inline BwdLayout bwd_layout(int32_t T, int64_t B, int64_t nnz, int64_t total_row
     const int max_passes = L.key_bytes * 8 / RADIX_BITS;
     L.hist = off;        off += align256((size_t)max_passes * (L.tiles + 1) * RADIX * 4);
     L.sort_flags = off;  off += align256((size_t)(max_passes - 1) * L.tiles * RADIX * 8);
-    L.tile_heads = off;  off += align256((size_t)L.flat_tiles * 8);
+    L.tile_heads = off;  off += align256((size_t)L.flat_tiles * 8);    // one exchange word per tile (runs_list_kernel)
     L.seg_start = off;   off += align256((n + 1) * 4);
     L.seg_real = off;    off += align256(n * 4);
     L.queue = off;       off += align256((size_t)L.qslots * 4);
@@ -250,89 +250,164 @@ __global__ __launch_bounds__(256) void bwd_keys_kernel(const emb_table *__restri
 // between the runs of two tables.  Every change of key starts a run; runs of the
 // sentinel are numbered with the others (their start ends the run before them)
 // but are not rows: seg_real maps a run to its place in the list of distinct rows.
-template <typename KeyT>
-__device__ __forceinline__ unsigned long long head_flags(const KeyT *keys, uint32_t i, uint32_t n, KeyT sentinel)
+// One launch numbers the runs.  A tile (SORT_TILE records of the sorted array, whatever table they belong
+// to) counts its run starts and row starts, and learns how many lie in the tiles before it from those tiles
+// themselves: the exchange of the sort's scatters (radix_sort.h: a count, then a prefix, in one flagged word;
+// bounded waits for tiles with smaller numbers only).  Here a tile has one word that holds both numbers
+// (31 bits each: there are fewer than 2^31 records), and the tile's first wavefront walks back
+// RUNS_WINDOWS * 64 tiles per round trip to memory: lane l requests the words of tiles t - l, t - 64 - l, ...
+// together, then the windows are added up nearest first until one holds a tile that knows its prefix.
+// flags: [tiles], cleared by the sort's first counting launch.
+constexpr int RUNS_WINDOWS = 4;
+__device__ __forceinline__ unsigned long long runs_pack(uint32_t runs, uint32_t rows)
 {
-    if (i >= n) return 0ull;
-    const KeyT k = keys[i];
-    if (i != 0 && keys[i - 1] == k) return 0ull;
-    return (1ull << 32) | (k != sentinel ? 1ull : 0ull);   // high half: runs, low half: rows
+    return ((unsigned long long)runs << 31) | rows;
 }
-
-template <typename KeyT>
-__global__ __launch_bounds__(SORT_BLOCK) void runs_count_kernel(const KeyT *__restrict__ keys, uint32_t n, KeyT sentinel,
-                                                                unsigned long long *__restrict__ tile_heads,
-                                                                const BwdCtrl *ctrl)
+__device__ __forceinline__ bool runs_lookback(unsigned long long *flags, uint32_t me, uint32_t count_runs,
+                                              uint32_t count_rows, uint32_t poll_limit, uint32_t &before_runs,
+                                              uint32_t &before_rows)
 {
-    if (ctrl->abort) return;
-    __shared__ unsigned long long wave_sums[SORT_WAVES];
-    const uint32_t base = blockIdx.x * SORT_TILE + threadIdx.x * SORT_ITEMS;
-    unsigned long long c = 0;
+    const int lane = threadIdx.x & (EMB_WAVE - 1);
+    if (lane == 0) sort_flag_store(flags + me, SORT_FLAG_COUNT | runs_pack(count_runs, count_rows));
+    uint32_t sum_runs = 0, sum_rows = 0;
+    bool done = false, ok = true;   // the same in all lanes
+    for (int64_t t = (int64_t)me - 1; !done; t -= RUNS_WINDOWS * EMB_WAVE) {
+        unsigned long long x[RUNS_WINDOWS];
 #pragma unroll
-    for (int k = 0; k < SORT_ITEMS; ++k) c += head_flags(keys, base + k, n, sentinel);
-    unsigned long long total;
-    block_inclusive_scan<unsigned long long, SORT_BLOCK>(c, wave_sums, total);
-    if (threadIdx.x == 0) tile_heads[blockIdx.x] = total;
-}
-
-__global__ __launch_bounds__(1024) void runs_scan_kernel(unsigned long long *__restrict__ tile_heads, uint32_t tiles,
-                                                          uint32_t n, uint32_t *__restrict__ seg_start, BwdCtrl *ctrl,
-                                                          int64_t *num_unique_out)
-{
-    if (ctrl->abort) return;
-    __shared__ unsigned long long wave_sums[1024 / EMB_WAVE];
-    unsigned long long carry = 0;
-    for (uint32_t b0 = 0; b0 < tiles; b0 += 1024) {
-        const uint32_t b = b0 + threadIdx.x;
-        const unsigned long long v = b < tiles ? tile_heads[b] : 0ull;
-        unsigned long long total;
-        const unsigned long long inc = block_inclusive_scan<unsigned long long, 1024>(v, wave_sums, total);
-        if (b < tiles) tile_heads[b] = carry + inc - v;
-        carry += total;
+        for (int w = 0; w < RUNS_WINDOWS; ++w) {
+            const int64_t tt = t - w * EMB_WAVE - lane;
+            x[w] = tt >= 0 ? sort_flag_load(flags + tt) : SORT_FLAG_PREFIX;   // before the first tile: a prefix of nothing
+        }
+#pragma unroll
+        for (int w = 0; w < RUNS_WINDOWS; ++w) {
+            if (done) break;   // uniform
+            const int64_t tt = t - w * EMB_WAVE - lane;
+            unsigned long long v = x[w];
+            uint32_t polls = 0;
+            while ((v >> 62) == 0) {            // not published yet
+                if (polls >= poll_limit) {
+                    v = SORT_FLAG_FAILED;
+                    break;
+                }
+                ++polls;
+                __builtin_amdgcn_s_sleep(2);
+                v = sort_flag_load(flags + tt);
+            }
+            if (poll_limit == 0 && tt >= 0) v = SORT_FLAG_FAILED;
+            const unsigned long long state = v & SORT_FLAG_FAILED;
+            const uint64_t prefix = __ballot(state == SORT_FLAG_PREFIX);
+            const int stop = prefix ? __ffsll((unsigned long long)prefix) - 1 : EMB_WAVE;   // the nearest tile that knows its prefix
+            if (__ballot(state == SORT_FLAG_FAILED && lane <= stop) != 0) {
+                ok = false;
+                done = true;
+                break;
+            }
+            uint32_t r = lane <= stop ? (uint32_t)((v >> 31) & 0x7FFFFFFFu) : 0u;
+            uint32_t q = lane <= stop ? (uint32_t)(v & 0x7FFFFFFFu) : 0u;
+#pragma unroll
+            for (int d = EMB_WAVE >> 1; d >= 1; d >>= 1) {
+                r += (uint32_t)__shfl_xor((int)r, d, EMB_WAVE);
+                q += (uint32_t)__shfl_xor((int)q, d, EMB_WAVE);
+            }
+            sum_runs += r;
+            sum_rows += q;
+            if (prefix) done = true;
+        }
     }
-    if (threadIdx.x == 0) {
-        const uint32_t runs = (uint32_t)(carry >> 32), rows = (uint32_t)carry;
-        ctrl->num_runs = runs;
-        ctrl->num_unique = rows;
-        seg_start[runs] = n;   // the last run ends with the records
-        if (num_unique_out) *num_unique_out = (int64_t)rows;
-    }
+    if (lane == 0)
+        sort_flag_store(flags + me, ok ? (SORT_FLAG_PREFIX | runs_pack(sum_runs + count_runs, sum_rows + count_rows))
+                                       : SORT_FLAG_FAILED);
+    before_runs = sum_runs;
+    before_rows = sum_rows;
+    return ok;
 }
 
 template <typename KeyT>
-__global__ __launch_bounds__(SORT_BLOCK) void runs_compact_kernel(const KeyT *__restrict__ keys, uint32_t n,
-                                                                  KeyT sentinel,
-                                                                  const unsigned long long *__restrict__ tile_heads,
-                                                                  uint32_t *__restrict__ seg_start,
-                                                                  uint32_t *__restrict__ seg_real,
-                                                                  int64_t *__restrict__ unique_keys_out,
-                                                                  const BwdCtrl *ctrl)
+__global__ __launch_bounds__(SORT_BLOCK) void runs_list_kernel(const KeyT *__restrict__ keys, uint32_t n, KeyT sentinel,
+                                                               unsigned long long *__restrict__ flags, uint32_t tiles,
+                                                               uint32_t *__restrict__ seg_start,
+                                                               uint32_t *__restrict__ seg_real,
+                                                               int64_t *__restrict__ unique_keys_out, BwdCtrl *ctrl,
+                                                               int64_t *num_unique_out, uint32_t poll_limit,
+                                                               uint32_t *status)
 {
-    if (ctrl->abort) return;
+    if (ctrl->abort) {   // uniform; nobody is to wait for this tile
+        if (threadIdx.x == 0) sort_flag_store(flags + blockIdx.x, SORT_FLAG_FAILED);
+        return;
+    }
     __shared__ unsigned long long wave_sums[SORT_WAVES];
+    __shared__ unsigned long long tile_before;   // runs in the high half, rows in the low half
+    __shared__ uint32_t lookback_failed;
+    // the tile's runs in order: where each starts, and its place among the rows (NO_ROW: the marker's run)
+    __shared__ uint32_t run_pos[SORT_TILE];
+    __shared__ uint32_t run_row[SORT_TILE];
+    constexpr uint32_t NO_ROW = 0xFFFFFFFFu;
+    // a thread looks at SORT_ITEMS consecutive records (the arrays carry SORT_PAD records of slack; what
+    // lies past n is not looked at) and at the record before them
     const uint32_t base = blockIdx.x * SORT_TILE + threadIdx.x * SORT_ITEMS;
+    KeyT k[SORT_ITEMS];
+    KeyT prev = sentinel;
+    if (base < n) {
+        load_records<KeyT, SORT_ITEMS>(keys + base, k);
+        if (base > 0) prev = keys[base - 1];
+    }
     unsigned long long f[SORT_ITEMS], c = 0;
 #pragma unroll
-    for (int k = 0; k < SORT_ITEMS; ++k) {
-        f[k] = head_flags(keys, base + k, n, sentinel);
-        c += f[k];
+    for (int e = 0; e < SORT_ITEMS; ++e) {
+        const uint32_t i = base + e;
+        f[e] = 0ull;
+        if (i < n && (i == 0 || k[e] != (e == 0 ? prev : k[e - 1])))
+            f[e] = (1ull << 32) | (k[e] != sentinel ? 1ull : 0ull);   // high half: runs, low half: rows
+        c += f[e];
     }
     unsigned long long total;
     const unsigned long long inc = block_inclusive_scan<unsigned long long, SORT_BLOCK>(c, wave_sums, total);
-    const unsigned long long before = tile_heads[blockIdx.x] + inc - c;
-    uint32_t v = (uint32_t)(before >> 32), u = (uint32_t)before;
+    // the tile's runs go to LDS in order while the first wavefront asks the earlier tiles
+    {
+        unsigned long long at = inc - c;
+        uint32_t v = (uint32_t)(at >> 32), u = (uint32_t)at;
 #pragma unroll
-    for (int k = 0; k < SORT_ITEMS; ++k) {
-        if (f[k]) {
-            const bool real = (f[k] & 1ull) != 0;
-            seg_start[v] = base + k;
-            seg_real[v] = real ? u : 0xFFFFFFFFu;
-            if (real) {
-                if (unique_keys_out) unique_keys_out[u] = (int64_t)keys[base + k];
-                ++u;
+        for (int e = 0; e < SORT_ITEMS; ++e) {
+            if (f[e]) {
+                const bool real = (f[e] & 1ull) != 0;
+                run_pos[v] = base + e;
+                run_row[v] = real ? u : NO_ROW;
+                u += real ? 1u : 0u;
+                ++v;
             }
-            ++v;
         }
+    }
+    if (threadIdx.x < EMB_WAVE) {
+        uint32_t runs_before = 0, rows_before = 0;
+        const bool ok = runs_lookback(flags, blockIdx.x, (uint32_t)(total >> 32), (uint32_t)total, poll_limit,
+                                      runs_before, rows_before);
+        if (threadIdx.x == 0) {
+            tile_before = ((unsigned long long)runs_before << 32) | rows_before;
+            lookback_failed = ok ? 0u : 1u;
+        }
+    }
+    __syncthreads();
+    if (lookback_failed) {   // uniform: the numbering is unknown, nothing is written
+        if (threadIdx.x == 0) {
+            ctrl->abort = 1;
+            emb_flag(status, EMB_STATUS_SORT_ABANDONED);
+        }
+        return;
+    }
+    const uint32_t v0 = (uint32_t)(tile_before >> 32), u0 = (uint32_t)tile_before;
+    const uint32_t tile_runs = (uint32_t)(total >> 32);
+    for (uint32_t i = threadIdx.x; i < tile_runs; i += SORT_BLOCK) {   // consecutive lanes, consecutive entries
+        const uint32_t pos = run_pos[i], row = run_row[i];
+        seg_start[v0 + i] = pos;
+        seg_real[v0 + i] = row == NO_ROW ? NO_ROW : u0 + row;
+        if (row != NO_ROW && unique_keys_out) unique_keys_out[u0 + row] = (int64_t)keys[pos];
+    }
+    if (blockIdx.x == tiles - 1 && threadIdx.x == 0) {   // the last tile knows the totals
+        const unsigned long long all = tile_before + total;
+        const uint32_t runs = (uint32_t)(all >> 32);
+        ctrl->num_runs = runs;
+        seg_start[runs] = n;   // the last run ends with the records
+        if (num_unique_out) *num_unique_out = (int64_t)(uint32_t)all;
     }
 }
 
@@ -347,11 +422,6 @@ __global__ __launch_bounds__(256) void runs_counts_kernel(const uint32_t *__rest
         const uint32_t u = seg_real[v];
         if (u != 0xFFFFFFFFu) unique_counts_out[u] = (int32_t)(seg_start[v + 1] - seg_start[v]);
     }
-}
-
-__global__ void runs_reset_kernel(BwdCtrl *ctrl)
-{
-    if (threadIdx.x == 0) ctrl->num_unique = 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -533,6 +603,10 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
     // counting launch and a scan per pass, because a scatter's walk back over its table's earlier tiles
     // grows with their number (a table of 640 tiles sorts 12 % slower by exchange, one of 40 tiles 11 %
     // faster).
+    // the optional list of distinct rows exchanges counts between tiles too; its words are cleared by the
+    // first counting launch
+    const bool want_list = a.unique_keys_out || a.unique_counts_out;
+    unsigned long long *list_flags = want_list ? tile_heads : nullptr;
     const bool exchange = a.nnz <= (int64_t)SORT_EXCHANGE_MAX_TILES * SORT_TILE * (a.T > 0 ? a.T : 1);
     const uint32_t poll_limit = sort_poll_limit;
     if (exchange) {
@@ -541,7 +615,7 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
             const int np = a.passes - p0 < 4 ? a.passes - p0 : 4;
 #define EMB_SORT_HIST(NP)                                                                                          \
     hipLaunchKernelGGL((sort_hist_kernel<KeyT, NP>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, tile_desc, p0, hist, \
-                       tiles, fl, a.passes - 1, ctrl)
+                       tiles, fl, a.passes - 1, p0 == 0 ? list_flags : nullptr, flat_tiles, ctrl)
             switch (np) {
                 case 1: EMB_SORT_HIST(1); break;
                 case 2: EMB_SORT_HIST(2); break;
@@ -562,7 +636,7 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
         const bool last = p == a.passes - 1;
         if (!exchange) {
             hipLaunchKernelGGL((sort_hist_kernel<KeyT, 1>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, tile_desc, p, hist,
-                               tiles, (unsigned long long *)nullptr, 0, ctrl);
+                               tiles, (unsigned long long *)nullptr, 0, p == 0 ? list_flags : nullptr, flat_tiles, ctrl);
             EMB_RETURN_IF_LAUNCH_FAILED();
             hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX), dim3(1024), 0, s, hp, tiles, ctrl);
             EMB_RETURN_IF_LAUNCH_FAILED();
@@ -586,15 +660,11 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
     // sorted records are now in (kin, pin)
     EMB_MARK(a, 2);
 
-    if (a.unique_keys_out || a.unique_counts_out) {
-        hipLaunchKernelGGL(runs_count_kernel<KeyT>, dim3(flat_tiles), dim3(SORT_BLOCK), 0, s, kin, n, sentinel,
-                           tile_heads, ctrl);
-        EMB_RETURN_IF_LAUNCH_FAILED();
-        hipLaunchKernelGGL(runs_scan_kernel, dim3(1), dim3(1024), 0, s, tile_heads, flat_tiles, n, seg_start, ctrl,
-                           a.num_unique_out);
-        EMB_RETURN_IF_LAUNCH_FAILED();
-        hipLaunchKernelGGL(runs_compact_kernel<KeyT>, dim3(flat_tiles), dim3(SORT_BLOCK), 0, s, kin, n, sentinel,
-                           tile_heads, seg_start, seg_real, a.unique_keys_out, ctrl);
+    if (want_list) {
+        // (the update counts the distinct rows again on its own: ctrl->num_unique is not touched here)
+        hipLaunchKernelGGL(runs_list_kernel<KeyT>, dim3(flat_tiles), dim3(SORT_BLOCK), 0, s, kin, n, sentinel, tile_heads,
+                           flat_tiles, seg_start, seg_real, a.unique_keys_out, ctrl, a.num_unique_out, poll_limit,
+                           a.status);
         EMB_RETURN_IF_LAUNCH_FAILED();
         if (a.unique_counts_out) {
             const unsigned cgrid = (unsigned)(flat_tiles < 1024 ? flat_tiles : 1024);
@@ -602,9 +672,6 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
                                a.unique_counts_out, ctrl);
             EMB_RETURN_IF_LAUNCH_FAILED();
         }
-        // the update recounts the runs itself: start it from zero again
-        hipLaunchKernelGGL(runs_reset_kernel, dim3(1), dim3(64), 0, s, ctrl);
-        EMB_RETURN_IF_LAUNCH_FAILED();
     }
 
     EMB_MARK(a, 3);

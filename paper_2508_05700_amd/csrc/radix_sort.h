@@ -84,15 +84,19 @@ __device__ __forceinline__ void wave_rank_digits(const KeyT (&key)[SORT_ITEMS], 
 // tile (the tiles as they are before the first pass) and, in its last column (written by the
 // scan), the count over all tiles.  One launch counts the digits of passes
 // [first_pass, first_pass + NP).  flags (optional): the scatters' exchange words (sort_lookback_walk) of the passes after the
-// first, [flag_passes][tiles][RADIX]; every tile in use clears its own.
+// first, [flag_passes][tiles][RADIX]; every tile in use clears its own.  list_flags (optional):
+// [list_tiles] words; workgroup b < list_tiles clears word b.
 template <typename KeyT, int NP>
 __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__restrict__ keys,
                                                                const SortTile *__restrict__ desc, int first_pass,
                                                                uint32_t *__restrict__ hist, uint32_t tiles,
                                                                unsigned long long *__restrict__ flags, int flag_passes,
-                                                               const BwdCtrl *ctrl)
+                                                               unsigned long long *__restrict__ list_flags,
+                                                               uint32_t list_tiles, const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
+    // (optional) the exchange word per tile of the kernel that lists the distinct rows after the sort
+    if (list_flags && blockIdx.x < list_tiles && threadIdx.x == 0) list_flags[blockIdx.x] = 0ull;
     __shared__ uint32_t cnt[SORT_WAVES][NP][RADIX];
     const SortTile tile = desc[blockIdx.x];
     const bool owner = threadIdx.x < RADIX;   // thread d < RADIX reports digit d
