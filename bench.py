@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "67f1ca655509d13b",
+    "sources": "f718b840e2ccf29c",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (177517.3, 69002.2), "update_kernel": (240533.5, 324005.4)},
-        "3b": {"bag_forward_train_kernel": (94813.2, 83185.9), "update_kernel": (169945.0, 220257.2)},
-        "2": {"bag_forward_hashed_kernel": (176274.3, 33802.5), "bag_forward_kernel": (177931.5, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338181.8, 33793.2), "bag_forward_kernel": (338142.9, 32768.0)},
-        "2un": {"bag_forward_kernel": (346125.4, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (122286.1, 33831.4)},
-        "2uq4": {"bag_forward_quant_kernel": (232523.4, 33926.4)},
-        "2uq4r": {"bag_forward_quant_kernel": (190397.1, 33874.4)},
-        "4": {"bag_forward_hashed_kernel": (52668.9, 8704.3)},
+        "3": {"bag_forward_train_kernel": (177530.7, 68993.5), "update_kernel": (240512.0, 324004.1)},
+        "3b": {"bag_forward_train_kernel": (94814.0, 83212.6), "update_kernel": (169966.5, 220185.4)},
+        "2": {"bag_forward_hashed_kernel": (176278.8, 33802.9), "bag_forward_kernel": (177925.1, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338179.3, 33793.4), "bag_forward_kernel": (338144.6, 32768.0)},
+        "2un": {"bag_forward_kernel": (346136.5, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (122245.9, 33832.4)},
+        "2uq4": {"bag_forward_quant_kernel": (232563.7, 33926.0)},
+        "2uq4r": {"bag_forward_quant_kernel": (190413.7, 33872.9)},
+        "4": {"bag_forward_hashed_kernel": (52660.5, 8704.3)},
     },
 }
 
