@@ -541,6 +541,7 @@ int launch_update(const BwdArgs &a, const BwdLayout &L, const KeyT *keys, const 
 // How often a scatter of the sort polls one word of another workgroup before it gives the sort up
 // (sort_lookback_walk, radix_sort.h); emb_debug_sort_poll_limit changes it.
 static constexpr uint32_t SORT_POLL_LIMIT_DEFAULT = 1u << 20;
+static constexpr int SORT_SCAN_BLOCKS = RADIX / SCAN_DIGITS / (SCAN_BLOCK_THREADS / EMB_WAVE);   // workgroups of the scan, per pass
 static constexpr int SORT_EXCHANGE_MAX_TILES = 64;   // per table, on average: above it every pass counts and scans
 static uint32_t sort_poll_limit = SORT_POLL_LIMIT_DEFAULT;
 
@@ -625,7 +626,8 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
 #undef EMB_SORT_HIST
             EMB_RETURN_IF_LAUNCH_FAILED();
         }
-        hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX * a.passes), dim3(1024), 0, s, hist, tiles, ctrl);
+        hipLaunchKernelGGL(sort_scan_kernel, dim3(SORT_SCAN_BLOCKS * a.passes), dim3(SCAN_BLOCK_THREADS), 0, s, hist, tiles,
+                           ctrl);
         EMB_RETURN_IF_LAUNCH_FAILED();
     }
     for (int p = 0; p < a.passes; ++p) {
@@ -638,7 +640,7 @@ int run_sort(const BwdArgs &a, const BwdLayout &L, bool prepared = false)
             hipLaunchKernelGGL((sort_hist_kernel<KeyT, 1>), dim3(tiles), dim3(SORT_BLOCK), 0, s, kin, tile_desc, p, hist,
                                tiles, (unsigned long long *)nullptr, 0, p == 0 ? list_flags : nullptr, flat_tiles, ctrl);
             EMB_RETURN_IF_LAUNCH_FAILED();
-            hipLaunchKernelGGL(sort_scan_kernel, dim3(RADIX), dim3(1024), 0, s, hp, tiles, ctrl);
+            hipLaunchKernelGGL(sort_scan_kernel, dim3(SORT_SCAN_BLOCKS), dim3(SCAN_BLOCK_THREADS), 0, s, hp, tiles, ctrl);
             EMB_RETURN_IF_LAUNCH_FAILED();
         }
 #define EMB_SORT_SCATTER(LAST, LOOKBACK)                                                                            \

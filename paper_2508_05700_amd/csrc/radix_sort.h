@@ -80,9 +80,11 @@ __device__ __forceinline__ void wave_rank_digits(const KeyT (&key)[SORT_ITEMS], 
     }
 }
 
-// hist is [passes][RADIX][tiles + 1]: row (p, d) holds the count of digit d of pass p in every
-// tile (the tiles as they are before the first pass) and, in its last column (written by the
-// scan), the count over all tiles.  One launch counts the digits of passes
+// hist is [passes][tiles + 1][RADIX]: entry (p, t, d) holds the count of digit d of pass p in
+// tile t (the tiles as they are before the first pass); the scan turns the counts of a digit
+// into their exclusive prefix sums over the tiles and writes the count over all tiles as entry
+// (p, tiles, d).  The RADIX counts of a tile lie together: the workgroup that counts a tile
+// writes them with consecutive lanes, and the scatter reads what it needs of them the same way.  One launch counts the digits of passes
 // [first_pass, first_pass + NP).  flags (optional): the scatters' exchange words (sort_lookback_walk) of the passes after the
 // first, [flag_passes][tiles][RADIX]; every tile in use clears its own.  list_flags (optional):
 // [list_tiles] words; workgroup b < list_tiles clears word b.
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__res
     __shared__ uint32_t cnt[SORT_WAVES][NP][RADIX];
     const SortTile tile = desc[blockIdx.x];
     const bool owner = threadIdx.x < RADIX;   // thread d < RADIX reports digit d
-    uint32_t *slot = hist + ((size_t)first_pass * RADIX + (owner ? threadIdx.x : 0)) * (tiles + 1) + blockIdx.x;
+    uint32_t *slot = hist + ((size_t)first_pass * (tiles + 1) + blockIdx.x) * RADIX + (owner ? threadIdx.x : 0);
     const size_t pass_stride = (size_t)RADIX * (tiles + 1);
     if (tile.count == 0) {   // uniform over the workgroup
         if (owner) {
@@ -159,24 +161,57 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_hist_kernel(const KeyT *__res
 }
 static_assert(SORT_BLOCK >= RADIX && SORT_BLOCK % RADIX == 0, "the first RADIX threads of a workgroup own one digit each");
 
-// One workgroup per pass and digit: exclusive scan of that digit's per-tile counts in
-// place; the digit's total goes to the row's last column.
-__global__ __launch_bounds__(1024) void sort_scan_kernel(uint32_t *__restrict__ hist, uint32_t tiles,
-                                                          const BwdCtrl *ctrl)
+// One wavefront per pass and group of SCAN_DIGITS digits: exclusive scan, over the tiles, of those
+// digits' counts, in place; the totals go to the entry after the last tile.  No LDS and no barrier: in
+// a round a lane takes SCAN_TILES_PER_LANE consecutive tiles (their SCAN_DIGITS counts are one 16-byte
+// load each, all requested together), sums them, and the lanes' sums are scanned by shuffles.
+constexpr int SCAN_DIGITS = 4;
+constexpr int SCAN_TILES_PER_LANE = 16;
+constexpr int SCAN_BLOCK_THREADS = 256;
+__global__ __launch_bounds__(SCAN_BLOCK_THREADS) void sort_scan_kernel(uint32_t *__restrict__ hist, uint32_t tiles,
+                                                                        const BwdCtrl *ctrl)
 {
     if (ctrl->abort) return;
-    __shared__ uint32_t wave_sums[1024 / EMB_WAVE];
-    uint32_t *row = hist + (size_t)blockIdx.x * (tiles + 1);
-    uint32_t carry = 0;
-    for (uint32_t b0 = 0; b0 < tiles; b0 += 1024) {
-        const uint32_t b = b0 + threadIdx.x;
-        const uint32_t v = b < tiles ? row[b] : 0u;
-        uint32_t total;
-        const uint32_t inc = block_inclusive_scan<uint32_t, 1024>(v, wave_sums, total);
-        if (b < tiles) row[b] = carry + inc - v;
-        carry += total;
+    static_assert(SCAN_DIGITS == 4 && RADIX % (SCAN_DIGITS * (SCAN_BLOCK_THREADS / EMB_WAVE)) == 0,
+                  "one uint4 per tile and digit group, whole workgroups per pass");
+    constexpr uint32_t GROUPS = RADIX / SCAN_DIGITS;   // digit groups (= wavefronts) per pass
+    const int lane = threadIdx.x & (EMB_WAVE - 1);
+    const uint32_t wave = blockIdx.x * (SCAN_BLOCK_THREADS / EMB_WAVE) + threadIdx.x / EMB_WAVE;
+    const uint32_t pass = wave / GROUPS, d0 = (wave % GROUPS) * SCAN_DIGITS;
+    uint32_t *base = hist + (size_t)pass * (tiles + 1) * RADIX + d0;
+    uint4 carry = make_uint4(0u, 0u, 0u, 0u);   // a count over all tiles is below 2^32
+    constexpr uint32_t ROUND = EMB_WAVE * SCAN_TILES_PER_LANE;
+    for (uint32_t b0 = 0; b0 < tiles; b0 += ROUND) {
+        const uint32_t first = b0 + lane * SCAN_TILES_PER_LANE;
+        uint4 v[SCAN_TILES_PER_LANE];
+#pragma unroll
+        for (int i = 0; i < SCAN_TILES_PER_LANE; ++i) {
+            v[i] = make_uint4(0u, 0u, 0u, 0u);
+            if (first + i < tiles) v[i] = *reinterpret_cast<const uint4 *>(base + (size_t)(first + i) * RADIX);
+        }
+        uint4 mine = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+        for (int i = 0; i < SCAN_TILES_PER_LANE; ++i) {
+            mine.x += v[i].x; mine.y += v[i].y; mine.z += v[i].z; mine.w += v[i].w;
+        }
+        uint4 inc;
+        inc.x = wave_inclusive_scan(mine.x);
+        inc.y = wave_inclusive_scan(mine.y);
+        inc.z = wave_inclusive_scan(mine.z);
+        inc.w = wave_inclusive_scan(mine.w);
+        uint4 run = make_uint4(carry.x + inc.x - mine.x, carry.y + inc.y - mine.y, carry.z + inc.z - mine.z,
+                               carry.w + inc.w - mine.w);
+#pragma unroll
+        for (int i = 0; i < SCAN_TILES_PER_LANE; ++i) {
+            if (first + i < tiles) *reinterpret_cast<uint4 *>(base + (size_t)(first + i) * RADIX) = run;
+            run.x += v[i].x; run.y += v[i].y; run.z += v[i].z; run.w += v[i].w;
+        }
+        carry.x += (uint32_t)__shfl((int)inc.x, EMB_WAVE - 1, EMB_WAVE);
+        carry.y += (uint32_t)__shfl((int)inc.y, EMB_WAVE - 1, EMB_WAVE);
+        carry.z += (uint32_t)__shfl((int)inc.z, EMB_WAVE - 1, EMB_WAVE);
+        carry.w += (uint32_t)__shfl((int)inc.w, EMB_WAVE - 1, EMB_WAVE);
     }
-    if (threadIdx.x == 0) row[tiles] = carry;
+    if (lane == 0) *reinterpret_cast<uint4 *>(base + (size_t)tiles * RADIX) = carry;
 }
 
 // How the workgroups of one scatter tell each other their digit counts (the scheme of a single-pass
@@ -310,9 +345,9 @@ __global__ __launch_bounds__(SORT_BLOCK) void sort_scatter_kernel(const KeyT *__
     // thread d's three entries of the scanned histogram do not depend on the records: they are
     // asked for together with them, not after the ranking
     const bool owner = threadIdx.x < RADIX;   // thread d < RADIX looks after digit d
-    const uint32_t *hrow = hist + (size_t)(owner ? threadIdx.x : 0) * (tiles + 1);
-    const uint32_t p_first = hrow[tile.first], p_next = hrow[tile.next];
-    const uint32_t p_mine = LOOKBACK ? 0u : hrow[blockIdx.x];
+    const uint32_t *hcol = hist + (owner ? threadIdx.x : 0);
+    const uint32_t p_first = hcol[(size_t)tile.first * RADIX], p_next = hcol[(size_t)tile.next * RADIX];
+    const uint32_t p_mine = LOOKBACK ? 0u : hcol[(size_t)blockIdx.x * RADIX];
     for (int i = threadIdx.x; i < SORT_WAVES * RADIX; i += SORT_BLOCK) (&cnt[0][0])[i] = 0;
     if (threadIdx.x == 0) lookback_failed = 0;
     __syncthreads();

@@ -736,6 +736,22 @@ def test_backward_sort_one_large_table_among_small_ones():
     _check_backward_against_oracle(tables, Rs, rows, off, B, D, "sum", dout, "one large table among small ones")
 
 
+@pytest.mark.parametrize("T", [3, 20])
+def test_backward_sort_more_than_a_thousand_tiles(T):
+    # 4.5 M lookups are 1 100 sort tiles: the scan over the per-tile digit counts takes more than one round.
+    # Three tables (366 tiles each) are sorted pass by pass, twenty tables (55 tiles each) by exchange.
+    rng = np.random.default_rng(780 + T)
+    D, R = 4, 100_003
+    B = 4_500_000 // (T * 250)
+    lengths = np.full(T * B, 250, dtype=np.int64)
+    off = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int64)
+    rows = rng.integers(0, R, size=int(off[-1])).astype(np.int64)
+    rows[rng.choice(rows.size, size=50_000, replace=False)] = 77       # a long run in whichever tables it falls
+    tables = [(rng.standard_normal((R, D)) * 0.01).astype(np.float32) for _ in range(T)]
+    dout = rng.standard_normal((T, B, D)).astype(np.float32)
+    _check_backward_against_oracle(tables, [R] * T, rows, off, B, D, "sum", dout, "more than a thousand tiles")
+
+
 def test_backward_split_calls_on_two_streams_equal_the_single_call():
     # emb_bag_backward_sort on a second stream (while other work runs on the first), then
     # emb_bag_backward_update: bit-identical tables, accumulators and row lists.
