@@ -40,19 +40,19 @@ def log(*a):
 # bytes or less are counted at their true size, so for kernels that issue those (4-byte accumulators,
 # 48-byte quantised rows) the scaled figure is an upper bound.
 PMC_TRAFFIC = {
-    "sources": "f718b840e2ccf29c",
+    "sources": "b73ec1126545090a",
     "fetch_scale": 2.0,
     "write_scale": 1.0,
     "kib_per_launch": {     # workload -> kernel -> (FETCH_SIZE, WRITE_SIZE)
-        "3": {"bag_forward_train_kernel": (177530.7, 68993.5), "update_kernel": (240512.0, 324004.1)},
-        "3b": {"bag_forward_train_kernel": (94814.0, 83212.6), "update_kernel": (169966.5, 220185.4)},
-        "2": {"bag_forward_hashed_kernel": (176278.8, 33802.9), "bag_forward_kernel": (177925.1, 32768.0)},
-        "2u": {"bag_forward_hashed_kernel": (338179.3, 33793.4), "bag_forward_kernel": (338144.6, 32768.0)},
-        "2un": {"bag_forward_kernel": (346136.5, 32768.0)},
-        "2q4": {"bag_forward_quant_kernel": (122245.9, 33832.4)},
-        "2uq4": {"bag_forward_quant_kernel": (232563.7, 33926.0)},
-        "2uq4r": {"bag_forward_quant_kernel": (190413.7, 33872.9)},
-        "4": {"bag_forward_hashed_kernel": (52660.5, 8704.3)},
+        "3": {"bag_forward_train_kernel": (177568.9, 68960.1), "update_kernel": (240525.8, 324005.4)},
+        "3b": {"bag_forward_train_kernel": (94766.7, 83182.2), "update_kernel": (169998.0, 220262.5)},
+        "2": {"bag_forward_hashed_kernel": (176278.2, 33800.9), "bag_forward_kernel": (177913.7, 32768.0)},
+        "2u": {"bag_forward_hashed_kernel": (338181.9, 33793.6), "bag_forward_kernel": (338144.8, 32768.0)},
+        "2un": {"bag_forward_kernel": (346124.6, 32768.0)},
+        "2q4": {"bag_forward_quant_kernel": (122247.6, 33832.7)},
+        "2uq4": {"bag_forward_quant_kernel": (232535.4, 33926.1)},
+        "2uq4r": {"bag_forward_quant_kernel": (190417.8, 33872.1)},
+        "4": {"bag_forward_hashed_kernel": (52665.0, 8704.2)},
     },
 }
 
